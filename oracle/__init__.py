@@ -1,0 +1,233 @@
+"""CPU oracle for the 2-bit lookup-table GEMM / convolution -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrappers over ``dg_oracle.c`` (the result, by explicit multiply of
+decoded levels) and ``dg_lut_reference.c`` (the table method's steps on packed
+bytes).  Only tests, the smoke check and the benchmark's CPU-baseline leg may
+import this package; the GPU library never does, and this package never imports
+the GPU library.
+
+Every function takes and returns numpy arrays.  Codes are ``uint8`` in
+``{0,1,2,3}``, one per element; levels are four integers per side.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "liboracle.so")
+_SOURCES = ("dg_oracle.c", "dg_lut_reference.c")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle's C files with gcc into ``oracle/liboracle.so``."""
+    srcs = [os.path.join(_HERE, s) for s in _SOURCES]
+    if not force and os.path.exists(_SO):
+        newest = max(os.path.getmtime(s) for s in srcs)
+        if os.path.getmtime(_SO) >= newest:
+            return _SO
+    cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-ffp-contract=off", "-fPIC",
+           "-shared", "-Wall", "-Wextra", "-o", _SO] + srcs
+    subprocess.run(cmd, check=True)
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_SO)
+        i64, p = ctypes.c_int64, ctypes.c_void_p
+        lib.dgo_max_threads.restype = ctypes.c_int
+        lib.dgo_set_threads.argtypes = [ctypes.c_int]
+        lib.dgo_gemm.argtypes = [p, p, p, p, i64, i64, i64, p]
+        lib.dgo_gemm_sampled.argtypes = [p, p, p, p, i64, i64, i64, p, p, i64, p]
+        lib.dgo_conv_out_dim.argtypes = [i64] * 4
+        lib.dgo_conv_out_dim.restype = i64
+        lib.dgo_conv2d.argtypes = [p, p, p, p] + [i64] * 11 + [p]
+        lib.dgo_conv2d_sampled.argtypes = [p, p, p, p] + [i64] * 11 + [p, i64, p]
+        lib.dgo_scale_epilogue_nhwc.argtypes = [p, p, i64, i64, p]
+        lib.dgo_scale_epilogue_nhwc.restype = None
+        lib.dgo_scale_epilogue_rows.argtypes = [p, p, i64, i64, p]
+        lib.dgo_scale_epilogue_rows.restype = None
+        lib.dgo_build_lut.argtypes = [p, p, p]
+        lib.dgo_build_lut.restype = None
+        lib.dgo_pack_codes.argtypes = [p, i64, p]
+        lib.dgo_unpack_codes.argtypes = [p, i64, p]
+        lib.dgo_unpack_codes.restype = None
+        lib.dgo_lut_gemm_packed.argtypes = [p, p, p, i64, i64, i64, p]
+        _lib = lib
+    return _lib
+
+
+class OracleError(ValueError):
+    """Raised when the oracle rejects its input (bad code, overflow, bad shape)."""
+
+
+_ERRORS = {1: "a code is greater than 3", 2: "a sum does not fit int32", 3: "bad shape or index"}
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise OracleError(_ERRORS.get(rc, f"error {rc}"))
+
+
+def _ptr(a: np.ndarray) -> ctypes.c_void_p:
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _codes(a, shape=None) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    if shape is not None and tuple(a.shape) != tuple(shape):
+        raise OracleError(f"expected shape {shape}, got {a.shape}")
+    return a
+
+
+def _levels(v) -> np.ndarray:
+    v = np.ascontiguousarray(v, dtype=np.int32)
+    if v.shape != (4,):
+        raise OracleError("a level table has exactly 4 entries")
+    return v
+
+
+def max_threads() -> int:
+    return int(_load().dgo_max_threads())
+
+
+def set_threads(n: int) -> None:
+    _load().dgo_set_threads(int(n))
+
+
+def gemm(Wc, Ac, levels_w, levels_a) -> np.ndarray:
+    """C[m][n] = sum_k lw[Wc[m][k]] * la[Ac[n][k]]  (int32, [M][N])."""
+    Wc, Ac = _codes(Wc), _codes(Ac)
+    M, K = Wc.shape
+    N, K2 = Ac.shape
+    if K != K2:
+        raise OracleError("reduction lengths differ")
+    C = np.zeros((M, N), dtype=np.int32)
+    lw, la = _levels(levels_w), _levels(levels_a)
+    _check(_load().dgo_gemm(_ptr(Wc), _ptr(Ac), _ptr(lw), _ptr(la), M, N, K, _ptr(C)))
+    return C
+
+
+def gemm_sampled(Wc, Ac, levels_w, levels_a, ms, ns) -> np.ndarray:
+    """The GEMM result at positions (ms[i], ns[i]) only."""
+    Wc, Ac = _codes(Wc), _codes(Ac)
+    M, K = Wc.shape
+    N, K2 = Ac.shape
+    if K != K2:
+        raise OracleError("reduction lengths differ")
+    ms = np.ascontiguousarray(ms, dtype=np.int64)
+    ns = np.ascontiguousarray(ns, dtype=np.int64)
+    out = np.zeros(ms.shape[0], dtype=np.int32)
+    lw, la = _levels(levels_w), _levels(levels_a)
+    _check(_load().dgo_gemm_sampled(_ptr(Wc), _ptr(Ac), _ptr(lw), _ptr(la), M, N, K,
+                                    _ptr(ms), _ptr(ns), ms.shape[0], _ptr(out)))
+    return out
+
+
+def conv_out_dim(size: int, k: int, stride: int, pad: int) -> int:
+    return int(_load().dgo_conv_out_dim(size, k, stride, pad))
+
+
+def conv2d(Wc, Xc, levels_w, levels_a, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    """Direct NHWC convolution.  Wc [Cout][KH][KW][Cin], Xc [B][H][W][Cin] -> int32 [B][OH][OW][Cout]."""
+    Wc, Xc = _codes(Wc), _codes(Xc)
+    Cout, KH, KW, Cin = Wc.shape
+    B, H, W, Cin2 = Xc.shape
+    if Cin != Cin2:
+        raise OracleError("channel counts differ")
+    sh, sw = stride
+    ph, pw = pad
+    OH, OW = conv_out_dim(H, KH, sh, ph), conv_out_dim(W, KW, sw, pw)
+    Y = np.zeros((B, max(OH, 0), max(OW, 0), Cout), dtype=np.int32)
+    lw, la = _levels(levels_w), _levels(levels_a)
+    _check(_load().dgo_conv2d(_ptr(Wc), _ptr(Xc), _ptr(lw), _ptr(la), B, H, W, Cin, Cout,
+                              KH, KW, sh, sw, ph, pw, _ptr(Y)))
+    return Y
+
+
+def conv2d_sampled(Wc, Xc, levels_w, levels_a, positions, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    """The convolution result at flat NHWC output indices ``positions`` only."""
+    Wc, Xc = _codes(Wc), _codes(Xc)
+    Cout, KH, KW, Cin = Wc.shape
+    B, H, W, Cin2 = Xc.shape
+    if Cin != Cin2:
+        raise OracleError("channel counts differ")
+    sh, sw = stride
+    ph, pw = pad
+    pos = np.ascontiguousarray(positions, dtype=np.int64)
+    out = np.zeros(pos.shape[0], dtype=np.int32)
+    lw, la = _levels(levels_w), _levels(levels_a)
+    _check(_load().dgo_conv2d_sampled(_ptr(Wc), _ptr(Xc), _ptr(lw), _ptr(la), B, H, W, Cin, Cout,
+                                      KH, KW, sh, sw, ph, pw, _ptr(pos), pos.shape[0], _ptr(out)))
+    return out
+
+
+def scale_epilogue_nhwc(acc, scale) -> np.ndarray:
+    """out[..., c] = float32(acc[..., c]) * scale[c]  (channels last)."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    scale = np.ascontiguousarray(scale, dtype=np.float32)
+    C = acc.shape[-1]
+    if scale.shape != (C,):
+        raise OracleError("one scale per channel")
+    out = np.zeros(acc.shape, dtype=np.float32)
+    _load().dgo_scale_epilogue_nhwc(_ptr(acc), _ptr(scale), acc.size // max(C, 1), C, _ptr(out))
+    return out
+
+
+def scale_epilogue_rows(acc, scale) -> np.ndarray:
+    """out[m][n] = float32(acc[m][n]) * scale[m]  (GEMM result stored [M][N])."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    scale = np.ascontiguousarray(scale, dtype=np.float32)
+    M, N = acc.shape
+    if scale.shape != (M,):
+        raise OracleError("one scale per row")
+    out = np.zeros(acc.shape, dtype=np.float32)
+    _load().dgo_scale_epilogue_rows(_ptr(acc), _ptr(scale), M, N, _ptr(out))
+    return out
+
+
+# ---- the table method's own steps (dg_lut_reference.c) -----------------------------------
+
+def build_lut(levels_w, levels_a) -> np.ndarray:
+    """table[4*w + a] = lw[w] * la[a]  (int32[16])."""
+    lw, la = _levels(levels_w), _levels(levels_a)
+    table = np.zeros(16, dtype=np.int32)
+    _load().dgo_build_lut(_ptr(lw), _ptr(la), _ptr(table))
+    return table
+
+
+def pack_codes(codes) -> np.ndarray:
+    """Pack along the last axis, four codes per byte, code k at bits 2*(k%4) of byte k//4."""
+    codes = _codes(codes)
+    if codes.shape[-1] % 4 != 0:
+        raise OracleError("the packed axis must be a multiple of 4")
+    packed = np.zeros(codes.shape[:-1] + (codes.shape[-1] // 4,), dtype=np.uint8)
+    _check(_load().dgo_pack_codes(_ptr(codes), codes.size, _ptr(packed)))
+    return packed
+
+
+def unpack_codes(packed) -> np.ndarray:
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    codes = np.zeros(packed.shape[:-1] + (packed.shape[-1] * 4,), dtype=np.uint8)
+    _load().dgo_unpack_codes(_ptr(packed), codes.size, _ptr(codes))
+    return codes
+
+
+def lut_gemm_packed(Wp, Ap, table, K: int) -> np.ndarray:
+    """GEMM by table lookup on packed operands (Algorithm 1, one byte at a time)."""
+    Wp = np.ascontiguousarray(Wp, dtype=np.uint8)
+    Ap = np.ascontiguousarray(Ap, dtype=np.uint8)
+    table = np.ascontiguousarray(table, dtype=np.int32)
+    M, N = Wp.shape[0], Ap.shape[0]
+    if Wp.shape[1] * 4 != K or Ap.shape[1] * 4 != K or table.shape != (16,):
+        raise OracleError("bad packed shapes")
+    C = np.zeros((M, N), dtype=np.int32)
+    _check(_load().dgo_lut_gemm_packed(_ptr(Wp), _ptr(Ap), _ptr(table), M, N, K, _ptr(C)))
+    return C

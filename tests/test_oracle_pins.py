@@ -1,0 +1,339 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+Hand-computed fixtures (tests/golden/), brute force over the 16 code pairs,
+closed forms, library routines on decoded levels (numpy int64 matmul, torch
+float64 conv2d), invariants of the sum, and statistical moments of the seeded
+workload.  A dropped term, a wrong sign, a transposed operand or a swapped
+kh/kw in the oracle fails at least one of these.  No GPU is used here.
+"""
+import itertools
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2304_09049_amd import workloads as wl
+
+LW = np.array(wl.LEVELS_W_SIGNED, dtype=np.int32)
+LA = np.array(wl.LEVELS_A_UNSIGNED, dtype=np.int32)
+LEVEL_SETS = [
+    (LW, LA),
+    (np.array([0, 1, -2, -1], dtype=np.int32), np.array([3, 1, 0, 2], dtype=np.int32)),   # two's-complement order
+    (np.array([-8, 7, 3, -5], dtype=np.int32), np.array([-7, 6, -8, 1], dtype=np.int32)),  # non-uniform
+    (np.array([127, -128, 5, 0], dtype=np.int32), np.array([-128, 127, 1, 0], dtype=np.int32)),
+]
+
+
+def _load(golden_dir, name):
+    with open(os.path.join(golden_dir, name)) as f:
+        return json.load(f)
+
+
+# ---- fixtures worked out by hand ---------------------------------------------------------
+
+def test_golden_tiny_gemm(golden_dir):
+    g = _load(golden_dir, "tiny_gemm.json")
+    C = oracle.gemm(g["Wc"], g["Ac"], g["levels_w"], g["levels_a"])
+    assert C.tolist() == g["C"]
+
+
+def test_golden_packed_bytes(golden_dir):
+    g = _load(golden_dir, "tiny_gemm.json")
+    assert oracle.pack_codes(np.array(g["Wc"], dtype=np.uint8)).tolist() == g["Wp"]
+    assert oracle.pack_codes(np.array(g["Ac"], dtype=np.uint8)).tolist() == g["Ap"]
+    assert oracle.unpack_codes(np.array(g["Wp"], dtype=np.uint8)).tolist() == g["Wc"]
+    table = oracle.build_lut(g["levels_w"], g["levels_a"])
+    C = oracle.lut_gemm_packed(g["Wp"], g["Ap"], table, 8)
+    assert C.tolist() == g["C"]
+
+
+def test_golden_lut16_table(golden_dir):
+    g = _load(golden_dir, "lut16_signed_unsigned.json")
+    table = oracle.build_lut(g["levels_w"], g["levels_a"])
+    assert table.tolist() == g["table"]
+    assert len(table) == g["entries"] == 2 ** g["index_bits"]
+
+
+def _tiny_conv_weights(g):
+    Wc = np.zeros((4, 3, 3, 4), dtype=np.uint8)
+    for co in range(4):
+        spec = g["W_taps"][str(co)]
+        Wc[co, :, :, :] = np.array(spec["default"], dtype=np.uint8)
+        for key, codes in spec.items():
+            if key == "default":
+                continue
+            kh, kw = (int(t) for t in key.split(","))
+            Wc[co, kh, kw, :] = np.array(codes, dtype=np.uint8)
+    return Wc
+
+
+@pytest.mark.parametrize("stride,key", [((1, 1), "Y_stride1"), ((2, 2), "Y_stride2")])
+def test_golden_tiny_conv(golden_dir, stride, key):
+    g = _load(golden_dir, "tiny_conv.json")
+    Wc = _tiny_conv_weights(g)
+    Xc = np.array(g["X"], dtype=np.uint8)
+    Y = oracle.conv2d(Wc, Xc, g["levels_w"], g["levels_a"], stride=stride, pad=(1, 1))
+    want = np.array(g[key], dtype=np.int32)              # [co][oh][ow]
+    assert Y.shape == (1,) + want.shape[1:] + (4,)
+    assert np.array_equal(Y[0].transpose(2, 0, 1), want)
+
+
+# ---- brute force over the 16 code pairs --------------------------------------------------
+
+@pytest.mark.parametrize("lw,la", LEVEL_SETS)
+def test_all_16_code_pairs(lw, la):
+    Wc = np.repeat(np.arange(4, dtype=np.uint8)[:, None], 4, axis=1)     # row m = code m, K = 4
+    Ac = np.repeat(np.arange(4, dtype=np.uint8)[:, None], 4, axis=1)
+    C = oracle.gemm(Wc, Ac, lw, la)
+    for m, n in itertools.product(range(4), range(4)):
+        assert C[m, n] == 4 * int(lw[m]) * int(la[n])
+
+
+@pytest.mark.parametrize("lw,la", LEVEL_SETS[:3])
+def test_each_slot_alone(lw, la):
+    # K = 4: one slot carries the code pair (c, d), the other three carry the filler pair (f, g)
+    for slot, c, d, f, g in itertools.product(range(4), range(4), range(4), (0, 3), (1, 2)):
+        w = np.full((1, 4), f, dtype=np.uint8)
+        a = np.full((1, 4), g, dtype=np.uint8)
+        w[0, slot], a[0, slot] = c, d
+        want = int(lw[c]) * int(la[d]) + 3 * int(lw[f]) * int(la[g])
+        assert oracle.gemm(w, a, lw, la)[0, 0] == want
+        table = oracle.build_lut(lw, la)
+        assert oracle.lut_gemm_packed(oracle.pack_codes(w), oracle.pack_codes(a), table, 4)[0, 0] == want
+
+
+def test_lut_index_is_weight_high_activation_low():
+    lw = np.array([1, 10, 100, 1000], dtype=np.int32)
+    la = np.array([1, 2, 3, 4], dtype=np.int32)
+    t = oracle.build_lut(lw, la)
+    for w, a in itertools.product(range(4), range(4)):
+        assert t[4 * w + a] == lw[w] * la[a]
+
+
+# ---- closed forms ------------------------------------------------------------------------
+
+@pytest.mark.parametrize("lw,la", LEVEL_SETS)
+def test_constant_codes_closed_form(lw, la):
+    K = 52
+    for c, d in itertools.product(range(4), range(4)):
+        C = oracle.gemm(np.full((3, K), c, np.uint8), np.full((5, K), d, np.uint8), lw, la)
+        assert np.all(C == K * int(lw[c]) * int(la[d]))
+
+
+def test_conv_constant_input_tap_counts():
+    # 3x3, pad 1 on a constant image: interior sees 9 taps, edges 6, corners 4
+    Cin, Cout, H, W = 8, 3, 5, 6
+    lw, la = LEVEL_SETS[2]
+    Wc = np.full((Cout, 3, 3, Cin), 1, np.uint8)
+    Xc = np.full((2, H, W, Cin), 3, np.uint8)
+    Y = oracle.conv2d(Wc, Xc, lw, la, pad=(1, 1))
+    unit = Cin * int(lw[1]) * int(la[3])
+    taps_h = np.array([2] + [3] * (H - 2) + [2])
+    taps_w = np.array([2] + [3] * (W - 2) + [2])
+    want = unit * np.outer(taps_h, taps_w)
+    for b in range(2):
+        for co in range(Cout):
+            assert np.array_equal(Y[b, :, :, co], want)
+
+
+def test_conv_out_dim_floor():
+    assert oracle.conv_out_dim(56, 3, 1, 1) == 56
+    assert oracle.conv_out_dim(56, 3, 2, 1) == 28
+    assert oracle.conv_out_dim(7, 3, 2, 0) == 3
+    assert oracle.conv_out_dim(8, 3, 2, 0) == 3      # floor, not ceil
+    assert oracle.conv_out_dim(224, 7, 2, 3) == 112
+    assert oracle.conv_out_dim(2, 3, 1, 0) == 0
+
+
+# ---- library routines on decoded levels --------------------------------------------------
+
+@pytest.mark.parametrize("lw,la", LEVEL_SETS)
+@pytest.mark.parametrize("M,N,K", [(7, 5, 12), (33, 17, 100), (64, 196, 576)])
+def test_gemm_equals_numpy_matmul(lw, la, M, N, K):
+    inp = wl.small_gemm(M, N, K, seed=M + N + K)
+    want = lw.astype(np.int64)[inp.Wc] @ la.astype(np.int64)[inp.Ac].T
+    assert np.array_equal(oracle.gemm(inp.Wc, inp.Ac, lw, la).astype(np.int64), want)
+
+
+CONV_CASES = [
+    # B, H, W, Cin, Cout, KH, KW, stride, pad
+    (2, 7, 9, 8, 5, 3, 3, (1, 1), (1, 1)),
+    (1, 8, 8, 4, 6, 3, 3, (2, 2), (1, 1)),
+    (2, 9, 6, 12, 4, 1, 1, (1, 1), (0, 0)),
+    (1, 10, 7, 4, 3, 5, 3, (2, 1), (2, 0)),
+    (1, 6, 11, 8, 2, 1, 7, (1, 3), (0, 3)),
+    (3, 5, 5, 16, 7, 3, 3, (1, 1), (0, 0)),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+@pytest.mark.parametrize("lw,la", LEVEL_SETS[:3])
+def test_conv_equals_torch_float64(case, lw, la):
+    B, H, W, Cin, Cout, KH, KW, stride, pad = case
+    inp = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H * W + Cin)
+    x = torch.from_numpy(la.astype(np.float64)[inp.Ac]).permute(0, 3, 1, 2)       # NCHW levels
+    w = torch.from_numpy(lw.astype(np.float64)[inp.Wc]).permute(0, 3, 1, 2)       # [Cout][Cin][KH][KW]
+    want = torch.nn.functional.conv2d(x, w, stride=stride, padding=pad).permute(0, 2, 3, 1).numpy()
+    got = oracle.conv2d(inp.Wc, inp.Ac, lw, la, stride=stride, pad=pad)
+    assert got.shape == want.shape
+    assert np.array_equal(got.astype(np.float64), want)       # exact: every value is a small integer
+
+
+# ---- invariants of the sum ---------------------------------------------------------------
+
+def test_table_path_equals_multiply_path():
+    for lw, la in LEVEL_SETS:
+        inp = wl.small_gemm(19, 23, 64, seed=5)
+        table = oracle.build_lut(lw, la)
+        via_table = oracle.lut_gemm_packed(oracle.pack_codes(inp.Wc), oracle.pack_codes(inp.Ac), table, 64)
+        assert np.array_equal(via_table, oracle.gemm(inp.Wc, inp.Ac, lw, la))
+
+
+def test_k_additivity_and_permutation():
+    lw, la = LEVEL_SETS[2]
+    inp = wl.small_gemm(9, 11, 40, seed=3)
+    full = oracle.gemm(inp.Wc, inp.Ac, lw, la)
+    left = oracle.gemm(inp.Wc[:, :16], inp.Ac[:, :16], lw, la)
+    right = oracle.gemm(inp.Wc[:, 16:], inp.Ac[:, 16:], lw, la)
+    assert np.array_equal(full, left + right)
+    perm = np.random.default_rng(0).permutation(40)
+    assert np.array_equal(full, oracle.gemm(inp.Wc[:, perm], inp.Ac[:, perm], lw, la))
+
+
+def test_relabelling_codes_with_levels():
+    lw, la = LEVEL_SETS[2]
+    inp = wl.small_gemm(6, 7, 24, seed=8)
+    base = oracle.gemm(inp.Wc, inp.Ac, lw, la)
+    pw, pa = np.array([2, 0, 3, 1]), np.array([1, 3, 0, 2])     # new code = p[old code]
+    lw2, la2 = np.empty_like(lw), np.empty_like(la)
+    lw2[pw], la2[pa] = lw, la
+    assert np.array_equal(base, oracle.gemm(pw[inp.Wc].astype(np.uint8), pa[inp.Ac].astype(np.uint8), lw2, la2))
+
+
+def test_scaling_weight_levels_scales_result():
+    lw, la = LEVEL_SETS[0]
+    inp = wl.small_gemm(5, 5, 32, seed=9)
+    assert np.array_equal(3 * oracle.gemm(inp.Wc, inp.Ac, lw, la), oracle.gemm(inp.Wc, inp.Ac, 3 * lw, la))
+    assert np.array_equal(-oracle.gemm(inp.Wc, inp.Ac, lw, la), oracle.gemm(inp.Wc, inp.Ac, lw, -la))
+
+
+def test_transposed_operands_are_not_interchangeable():
+    # guards the tests themselves: with these levels swapping the two sides must change the result
+    lw, la = LEVEL_SETS[0]
+    inp = wl.small_gemm(8, 8, 32, seed=1)
+    assert not np.array_equal(oracle.gemm(inp.Wc, inp.Ac, lw, la), oracle.gemm(inp.Wc, inp.Ac, la, lw))
+
+
+def test_conv1x1_is_gemm():
+    lw, la = LEVEL_SETS[2]
+    inp = wl.small_conv(2, 5, 4, 16, 6, 1, 1, seed=4)
+    Y = oracle.conv2d(inp.Wc, inp.Ac, lw, la)
+    C = oracle.gemm(inp.Wc.reshape(6, 16), inp.Ac.reshape(-1, 16), lw, la)        # [Cout][pixels]
+    assert np.array_equal(Y.reshape(-1, 6), C.T)
+
+
+def test_conv3x3_is_gemm_on_explicit_im2col():
+    # K index = (kh*KW + kw)*Cin + ci on both sides; a padded position uses a code whose level is 0
+    lw, la = LEVEL_SETS[0]                       # activation code 0 decodes to 0
+    inp = wl.small_conv(1, 6, 5, 4, 3, 3, 3, pad=(1, 1), seed=6)
+    Xpad = np.zeros((1, 8, 7, 4), np.uint8)
+    Xpad[:, 1:-1, 1:-1, :] = inp.Ac
+    cols = np.stack([Xpad[0, oh:oh + 3, ow:ow + 3, :].reshape(-1) for oh in range(6) for ow in range(5)])
+    C = oracle.gemm(inp.Wc.reshape(3, -1), cols, lw, la)
+    Y = oracle.conv2d(inp.Wc, inp.Ac, lw, la, pad=(1, 1))
+    assert np.array_equal(Y.reshape(-1, 3), C.T)
+
+
+def test_padding_contributes_zero_whatever_the_levels():
+    # out-of-image taps add nothing even when no activation code decodes to 0:
+    # compare with an un-padded convolution over an image padded with a code, minus that code's share
+    lw = np.array([-3, 2, 5, -1], dtype=np.int32)
+    la = np.array([4, -2, 7, 1], dtype=np.int32)                 # no zero level
+    inp = wl.small_conv(1, 5, 5, 4, 2, 3, 3, pad=(1, 1), seed=2)
+    Y = oracle.conv2d(inp.Wc, inp.Ac, lw, la, pad=(1, 1))
+    Xpad = np.zeros((1, 7, 7, 4), np.uint8)                      # padded with code 0 (level 4)
+    Xpad[:, 1:-1, 1:-1, :] = inp.Ac
+    ring = oracle.conv2d(inp.Wc, Xpad, lw, la) - Y               # what the ring of code-0 pixels added
+    # the same ring computed alone: image of code 0 everywhere minus the interior part
+    mask_levels = np.array([int(la[0]), 0, 0, 0], dtype=np.int32)
+    ring_codes = np.ones((1, 7, 7, 4), np.uint8)                 # code 1 -> level 0 under mask_levels
+    ring_codes[:, 0, :, :] = ring_codes[:, -1, :, :] = 0
+    ring_codes[:, :, 0, :] = ring_codes[:, :, -1, :] = 0
+    assert np.array_equal(ring, oracle.conv2d(inp.Wc, ring_codes, lw, mask_levels))
+
+
+def test_stride2_samples_stride1():
+    lw, la = LEVEL_SETS[2]
+    inp = wl.small_conv(1, 9, 9, 8, 3, 3, 3, pad=(1, 1), seed=12)
+    Y1 = oracle.conv2d(inp.Wc, inp.Ac, lw, la, stride=(1, 1), pad=(1, 1))
+    Y2 = oracle.conv2d(inp.Wc, inp.Ac, lw, la, stride=(2, 2), pad=(1, 1))
+    assert np.array_equal(Y2, Y1[:, ::2, ::2, :])
+
+
+def test_batch_items_are_independent():
+    lw, la = LEVEL_SETS[1]
+    inp = wl.small_conv(3, 6, 6, 8, 4, 3, 3, pad=(1, 1), seed=13)
+    Y = oracle.conv2d(inp.Wc, inp.Ac, lw, la, pad=(1, 1))
+    for b in range(3):
+        assert np.array_equal(Y[b:b + 1], oracle.conv2d(inp.Wc, inp.Ac[b:b + 1], lw, la, pad=(1, 1)))
+
+
+def test_sampled_variants_agree_with_full():
+    lw, la = LEVEL_SETS[2]
+    g = wl.small_gemm(13, 17, 48, seed=14)
+    full = oracle.gemm(g.Wc, g.Ac, lw, la)
+    ms, ns = np.array([0, 12, 5, 5]), np.array([16, 0, 3, 3])
+    assert np.array_equal(oracle.gemm_sampled(g.Wc, g.Ac, lw, la, ms, ns), full[ms, ns])
+    c = wl.small_conv(2, 6, 7, 8, 5, 3, 3, (2, 1), (1, 1), seed=15)
+    Y = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=(2, 1), pad=(1, 1))
+    pos = np.array([0, Y.size - 1, 17, 101])
+    assert np.array_equal(oracle.conv2d_sampled(c.Wc, c.Ac, lw, la, pos, stride=(2, 1), pad=(1, 1)),
+                          Y.reshape(-1)[pos])
+
+
+# ---- moments of the seeded workload (generator + decode sanity) --------------------------
+
+def test_moments_of_small_gemm_workload():
+    # uniform codes: E[lw] = -0.5, E[la] = 1.5, E[lw^2] = 1.5, E[la^2] = 3.5
+    # E[C] = 576 * (-0.75) = -432, Var[C] = 576 * (1.5*3.5 - 0.5625) = 2700
+    inp = wl.make_inputs(wl.CONFIGS["gemm_64x196x576"])
+    C = oracle.gemm(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a).astype(np.float64)
+    # C splits into a row part (64 samples, variance 1620), a column part (196 samples, 180) and an
+    # interaction part (900): the sample mean has sd ~5.1 and the pooled sample variance sd ~300
+    assert abs(C.mean() + 432.0) < 16.0
+    assert abs(C.var() / 2700.0 - 1.0) < 0.35
+    inter = C - C.mean(axis=0, keepdims=True) - C.mean(axis=1, keepdims=True) + C.mean()
+    assert abs(inter.var() / 900.0 - 1.0) < 0.1          # 576 * Var[lw] * Var[la] = 576 * 1.25 * 1.25
+
+
+def test_relu_skew_distribution():
+    codes = wl.draw_codes(np.random.default_rng(0), (200000,), "relu_skew")
+    freq = np.bincount(codes, minlength=4) / codes.size
+    assert abs(freq[0] - 0.5) < 0.01
+    assert np.all(np.abs(freq[1:] - 1.0 / 6.0) < 0.01)
+
+
+# ---- epilogue ------------------------------------------------------------------------------
+
+def test_scale_epilogue_is_one_float32_multiply():
+    acc = np.array([[1, -3, 16777217], [0, 2 ** 30 + 1, -(2 ** 24) - 3]], dtype=np.int32)
+    scale = np.array([0.1, 0.037, 0.5], dtype=np.float32)
+    want = acc.astype(np.float32) * scale            # numpy: int32 -> float32 (RNE), then float32 multiply
+    assert np.array_equal(oracle.scale_epilogue_nhwc(acc, scale), want)
+    # the conversion itself rounds to nearest even: 2^24 + 1 -> 2^24
+    assert oracle.scale_epilogue_nhwc(np.array([[16777217]], np.int32), np.array([1.0], np.float32))[0, 0] == 16777216.0
+    rows = oracle.scale_epilogue_rows(acc.T.copy(), scale)
+    assert np.array_equal(rows, want.T)
+
+
+# ---- error reporting ---------------------------------------------------------------------
+
+def test_oracle_rejects_bad_codes_and_overflow():
+    with pytest.raises(oracle.OracleError):
+        oracle.gemm(np.full((1, 4), 4, np.uint8), np.zeros((1, 4), np.uint8), LW, LA)
+    big = np.array([2 ** 15, 0, 0, 0], dtype=np.int32)
+    with pytest.raises(oracle.OracleError):
+        oracle.gemm(np.zeros((1, 8), np.uint8), np.zeros((1, 8), np.uint8), big, big)
