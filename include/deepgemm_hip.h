@@ -1,0 +1,165 @@
+/*
+ * deepgemm_hip.h -- C ABI of the MI355X (gfx950) 2-bit lookup-table GEMM / convolution library.
+ *
+ * The method (DeepGEMM, arXiv 2304.09049): weights and activations are quantised to 2-bit codes,
+ * every product of a weight level and an activation level is precomputed into a 16-entry table,
+ * and a dot product is formed by fetching table entries and adding them (Sec. 3.1; Sec. 3
+ * "LUT-16"; Algorithm 1).  Codes are packed four per byte (Sec. 3.1, Fig. 1).
+ *
+ * Notation: M = output channels / weight rows, N = output pixels x batch / activation rows,
+ * K = reduction length (KH*KW*Cin for a convolution).  Wc[m][k], Ac[n][k] are codes in {0..3};
+ * lw[4], la[4] are the level tables; LUT[4*w + a] = lw[w] * la[a].
+ *
+ * Conventions common to every call
+ *   - Every function returns a dg_status, never throws, never aborts, never synchronises the
+ *     device.  Arguments are validated on the host BEFORE anything is launched; on error nothing
+ *     has been launched and dg_last_error() holds a description (thread-local, static storage).
+ *   - Pointers named *_dev are DEVICE pointers owned by the caller; all other pointers are host
+ *     pointers.  Buffers must not alias.  The library allocates no device memory.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued asynchronously on it; results are valid once the caller has synchronised.
+ *   - The only library-owned object is dg_lut (a small host struct), freed by dg_lut_destroy.
+ */
+#ifndef DEEPGEMM_HIP_H
+#define DEEPGEMM_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DG_OK = 0,
+    DG_ERR_NULL = 1,        /* a required pointer is NULL */
+    DG_ERR_SHAPE = 2,       /* a dimension is <= 0, K or Cin is not a multiple of 4, empty output */
+    DG_ERR_RANGE = 3,       /* a table entry does not fit its type, or K*max|LUT| could overflow int32 */
+    DG_ERR_BUFFER = 4,      /* a buffer-size argument is too small */
+    DG_ERR_UNSUPPORTED = 5, /* the requested kernel variant cannot run this shape / table */
+    DG_ERR_HIP = 6          /* a HIP call failed; dg_last_error() carries hipGetErrorString */
+} dg_status;
+
+/* Name of a status code; static storage. */
+const char *dg_status_string(dg_status s);
+/* Detail of the calling thread's most recent failure ("" if none); thread-local static storage. */
+const char *dg_last_error(void);
+
+/* ---- the table (Sec. 3 "LUT-16": all 16 products w*a; Table 2: 2+2 index bits) ---------------- */
+
+/* Entry type.  The paper's tables hold 8-bit entries and assume no overflow, with wider entries
+ * "if required" (Sec. 3.2 "LUT Versions"); here the width is explicit and checked. */
+typedef enum { DG_LUT_I8 = 0, DG_LUT_I16 = 1 } dg_lut_dtype;
+
+typedef struct dg_lut dg_lut; /* opaque, immutable after build, usable from any thread */
+
+/*
+ * Build the table LUT[4*w + a] = levels_w[w] * levels_a[a] for codes w, a in {0..3}.
+ * levels_w / levels_a: host arrays of 4 signed levels in code order (signed or unsigned, uniform or
+ * not: Sec. 5.3).  Returns DG_ERR_RANGE if a product is not representable in `entry`
+ * (int8: [-128,127]; int16 always fits), DG_ERR_NULL for NULL arguments.  *out owns the result.
+ */
+dg_status dg_build_lut(const int8_t levels_w[4], const int8_t levels_a[4], dg_lut_dtype entry,
+                       dg_lut **out);
+/* Copy the 16 entries, widened to int16, to host array out16 (out16[4*w + a]). */
+dg_status dg_lut_entries(const dg_lut *lut, int16_t out16[16]);
+/* Free a table; NULL is allowed. */
+void dg_lut_destroy(dg_lut *lut);
+
+/* ---- packing (Sec. 3.1: several 2-bit values shift/OR-ed into a byte; weights offline, ------
+ *      activations at run time, Sec. 5.2) ------------------------------------------------------ */
+
+/*
+ * Bytes of a packed [rows][K] code matrix: rows*K/4.  0 if rows or K is negative or K % 4 != 0.
+ * Packed ACTIVATION layout (public): code k of a row is in byte k/4 of that row, bits
+ * [2*(k%4)+1 : 2*(k%4)]; rows are contiguous (K/4 bytes each).  For NHWC use rows = B*H*W, K = C.
+ * Packed WEIGHT layout: private to the library (Sec. 3 allows an offline re-arrangement); only
+ * its size, dg_packed_weight_bytes, is public.
+ */
+size_t dg_packed_activation_bytes(int64_t rows, int64_t K);
+size_t dg_packed_weight_bytes(int64_t M, int64_t K);
+
+/*
+ * Pack codes (one uint8 per code, values 0..3; higher bits are masked off) four per byte.
+ * codes_dev: device, [rows][K] row-major.  packed_dev: device, packed_bytes >= the size above
+ * (else DG_ERR_BUFFER).  K % 4 != 0 or rows/K <= 0 -> DG_ERR_SHAPE.  Asynchronous on hip_stream.
+ * A convolution's weights [Cout][KH][KW][Cin] are packed with M = Cout, K = KH*KW*Cin.
+ */
+dg_status dg_pack_weights(const uint8_t *codes_dev, int64_t M, int64_t K, void *packed_dev,
+                          size_t packed_bytes, void *hip_stream);
+dg_status dg_pack_activations(const uint8_t *codes_dev, int64_t N, int64_t K, void *packed_dev,
+                              size_t packed_bytes, void *hip_stream);
+
+/* ---- the kernels ------------------------------------------------------------------------------ */
+
+/*
+ * Which kernel runs.  AUTO picks the fastest table kernel for the shape.  The others exist for
+ * A/B measurement:
+ *   PERM     table rows held in registers, entries fetched with the byte-permute instruction
+ *   LDS      table held in LDS, one indexed read per product (any shape the library accepts)
+ *   MFMA_I8  NOT a table kernel: decodes codes to int8 levels and multiplies on the matrix cores;
+ *            kept only as the measured comparison
+ *   SMALLN   table kernel for few activation rows: K split across lanes + wavefront reduction
+ * A variant that cannot run the given shape or table returns DG_ERR_UNSUPPORTED.
+ */
+typedef enum {
+    DG_KERNEL_AUTO = 0,
+    DG_KERNEL_PERM = 1,
+    DG_KERNEL_LDS = 2,
+    DG_KERNEL_MFMA_I8 = 3,
+    DG_KERNEL_SMALLN = 4
+} dg_kernel;
+
+/*
+ * GEMM by table lookup (Algorithm 1 over all rows):
+ *     C[m][n] = sum_{k<K} LUT[4*Wc[m][k] + Ac[n][k]]          (exact, int32)
+ * Wp_dev: weights packed by dg_pack_weights(M, K).  Ap_dev: activations packed by
+ * dg_pack_activations(N, K) (or any buffer in the public activation layout).
+ * Output, one of:
+ *   scale_m_dev == NULL : C_dev[m*stride_cm + n*stride_cn] = sum (int32; strides in elements,
+ *                         both non-zero, the M*N addresses distinct)
+ *   scale_m_dev != NULL : Cf_dev[m*stride_cm + n*stride_cn] = (float)sum * scale_m_dev[m]
+ *                         (int32 -> binary32 round-to-nearest-even, then ONE binary32 multiply:
+ *                         the dequantisation stage of Sec. 5.4); C_dev is ignored and may be NULL.
+ * Errors: DG_ERR_NULL; DG_ERR_SHAPE (M, N, K <= 0 or K % 4 != 0); DG_ERR_RANGE if
+ * K * max|LUT| >= 2^31.
+ */
+dg_status dg_gemm_lut(const dg_lut *lut, const void *Wp_dev, const void *Ap_dev, int64_t M,
+                      int64_t N, int64_t K, int32_t *C_dev, int64_t stride_cm, int64_t stride_cn,
+                      const float *scale_m_dev, float *Cf_dev, dg_kernel variant,
+                      void *hip_stream);
+
+/* Convolution geometry; dilation 1, groups 1. */
+typedef struct {
+    int32_t B, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w;
+} dg_conv_desc;
+
+/* Output height/width: floor((in + 2*pad - k) / stride) + 1, or 0 if the kernel does not fit. */
+int64_t dg_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad);
+
+/*
+ * NHWC convolution by table lookup with implicit im2col (no expanded matrix is ever formed):
+ *     Y[b][oh][ow][co] = sum_{kh,kw,ci} LUT[4*Wc[co][kh][kw][ci] + Xc[b][ih][iw][ci]],
+ *     ih = oh*stride_h - pad_h + kh, iw = ow*stride_w - pad_w + kw;
+ *     taps outside the image add 0 to the sum whatever the level tables are.
+ * Wp_dev: dg_pack_weights(codes [Cout][KH][KW][Cin], M = Cout, K = KH*KW*Cin).
+ * Xp_dev: dg_pack_activations(codes [B][H][W][Cin], N = B*H*W, K = Cin).
+ * Output NHWC [B][OH][OW][Cout], contiguous: Y_dev (int32) when scale_cout_dev == NULL, else
+ * Yf_dev[...][co] = (float)sum * scale_cout_dev[co] (as in dg_gemm_lut) and Y_dev is ignored.
+ * Errors: DG_ERR_NULL; DG_ERR_SHAPE (a dimension <= 0, pad < 0, Cin % 4 != 0, OH or OW <= 0);
+ * DG_ERR_RANGE if KH*KW*Cin * max|LUT| >= 2^31.
+ */
+dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_dev,
+                        const dg_conv_desc *desc, int32_t *Y_dev, const float *scale_cout_dev,
+                        float *Yf_dev, dg_kernel variant, void *hip_stream);
+
+/* Name of the kernel that AUTO would pick (or that `variant` maps to) for this GEMM / convolution
+ * shape; static storage.  For reports only. */
+const char *dg_gemm_kernel_name(const dg_lut *lut, int64_t M, int64_t N, int64_t K,
+                                dg_kernel variant);
+const char *dg_conv_kernel_name(const dg_lut *lut, const dg_conv_desc *desc, dg_kernel variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEEPGEMM_HIP_H */

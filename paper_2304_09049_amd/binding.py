@@ -1,0 +1,208 @@
+"""ctypes binding over the C ABI of ``libdeepgemm_hip.so`` (declared in ``include/deepgemm_hip.h``).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.  torch is
+used for device memory and streams, nothing else.  There is no CPU fallback: if the library has
+not been built, loading fails with an explicit error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdeepgemm_hip.so")
+
+DG_OK = 0
+STATUS_NAMES = ("DG_OK", "DG_ERR_NULL", "DG_ERR_SHAPE", "DG_ERR_RANGE", "DG_ERR_BUFFER",
+                "DG_ERR_UNSUPPORTED", "DG_ERR_HIP")
+DG_LUT_I8, DG_LUT_I16 = 0, 1
+DG_KERNEL_AUTO, DG_KERNEL_PERM, DG_KERNEL_LDS, DG_KERNEL_MFMA_I8, DG_KERNEL_SMALLN = 0, 1, 2, 3, 4
+KERNELS = {"auto": DG_KERNEL_AUTO, "perm": DG_KERNEL_PERM, "lds": DG_KERNEL_LDS,
+           "mfma_i8": DG_KERNEL_MFMA_I8, "smalln": DG_KERNEL_SMALLN}
+
+# every symbol include/deepgemm_hip.h declares
+EXPORTS = (
+    "dg_status_string", "dg_last_error", "dg_build_lut", "dg_lut_entries", "dg_lut_destroy",
+    "dg_packed_activation_bytes", "dg_packed_weight_bytes", "dg_pack_weights", "dg_pack_activations",
+    "dg_gemm_lut", "dg_conv_out_dim", "dg_conv2d_lut", "dg_gemm_kernel_name", "dg_conv_kernel_name",
+)
+
+
+class ConvDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("B", "H", "W", "Cin", "Cout", "KH", "KW", "stride_h", "stride_w", "pad_h", "pad_w")]
+
+
+class DgError(RuntimeError):
+    def __init__(self, status: int, detail: str):
+        self.status = status
+        name = STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else f"status {status}"
+        super().__init__(f"{name}: {detail}")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the library (once).  Raises if it has not been built: there is no other path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2304_09049_amd.build` "
+                          "(hipcc, gfx950).  This package has no CPU fallback.")
+    L = ctypes.CDLL(LIB_PATH)
+    c_i64, c_vp, c_sz, c_int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    L.dg_status_string.argtypes, L.dg_status_string.restype = [c_int], ctypes.c_char_p
+    L.dg_last_error.argtypes, L.dg_last_error.restype = [], ctypes.c_char_p
+    L.dg_build_lut.argtypes, L.dg_build_lut.restype = [c_vp, c_vp, c_int, ctypes.POINTER(c_vp)], c_int
+    L.dg_lut_entries.argtypes, L.dg_lut_entries.restype = [c_vp, c_vp], c_int
+    L.dg_lut_destroy.argtypes, L.dg_lut_destroy.restype = [c_vp], None
+    L.dg_packed_activation_bytes.argtypes, L.dg_packed_activation_bytes.restype = [c_i64, c_i64], c_sz
+    L.dg_packed_weight_bytes.argtypes, L.dg_packed_weight_bytes.restype = [c_i64, c_i64], c_sz
+    for f in (L.dg_pack_weights, L.dg_pack_activations):
+        f.argtypes, f.restype = [c_vp, c_i64, c_i64, c_vp, c_sz, c_vp], c_int
+    L.dg_gemm_lut.argtypes = [c_vp, c_vp, c_vp, c_i64, c_i64, c_i64, c_vp, c_i64, c_i64, c_vp, c_vp, c_int, c_vp]
+    L.dg_gemm_lut.restype = c_int
+    L.dg_conv_out_dim.argtypes, L.dg_conv_out_dim.restype = [c_i64] * 4, c_i64
+    L.dg_conv2d_lut.argtypes = [c_vp, c_vp, c_vp, ctypes.POINTER(ConvDesc), c_vp, c_vp, c_vp, c_int, c_vp]
+    L.dg_conv2d_lut.restype = c_int
+    L.dg_gemm_kernel_name.argtypes, L.dg_gemm_kernel_name.restype = [c_vp, c_i64, c_i64, c_i64, c_int], ctypes.c_char_p
+    L.dg_conv_kernel_name.argtypes = [c_vp, ctypes.POINTER(ConvDesc), c_int]
+    L.dg_conv_kernel_name.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _check(status: int) -> None:
+    if status != DG_OK:
+        raise DgError(status, lib().dg_last_error().decode())
+
+
+def _kernel(variant) -> int:
+    return KERNELS[variant] if isinstance(variant, str) else int(variant)
+
+
+def _stream_ptr(stream) -> ctypes.c_void_p:
+    """hipStream_t of a torch stream (default: torch's current stream)."""
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev_ptr(t, dtype=None, name="tensor") -> ctypes.c_void_p:
+    if t is None:
+        return ctypes.c_void_p(0)
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class Lut:
+    """Owner of a ``dg_lut`` built by ``dg_build_lut``."""
+
+    def __init__(self, levels_w: Sequence[int], levels_a: Sequence[int], entry: int = DG_LUT_I8):
+        lw = (ctypes.c_int8 * 4)(*[int(v) for v in levels_w])
+        la = (ctypes.c_int8 * 4)(*[int(v) for v in levels_a])
+        handle = ctypes.c_void_p(0)
+        self._h = None
+        _check(lib().dg_build_lut(lw, la, int(entry), ctypes.byref(handle)))
+        self._h = handle
+
+    @property
+    def handle(self) -> ctypes.c_void_p:
+        return self._h
+
+    def entries(self):
+        out = (ctypes.c_int16 * 16)()
+        _check(lib().dg_lut_entries(self._h, out))
+        return list(out)
+
+    def __del__(self):
+        if getattr(self, "_h", None) is not None and _lib is not None:
+            _lib.dg_lut_destroy(self._h)
+            self._h = None
+
+
+def dg_build_lut(levels_w, levels_a, entry: int = DG_LUT_I8) -> Lut:
+    return Lut(levels_w, levels_a, entry)
+
+
+def dg_packed_activation_bytes(rows: int, K: int) -> int:
+    return int(lib().dg_packed_activation_bytes(rows, K))
+
+
+def dg_packed_weight_bytes(M: int, K: int) -> int:
+    return int(lib().dg_packed_weight_bytes(M, K))
+
+
+def dg_conv_out_dim(size: int, k: int, stride: int, pad: int) -> int:
+    return int(lib().dg_conv_out_dim(size, k, stride, pad))
+
+
+def _pack(fn, size_fn, codes, rows: int, K: int, out, stream):
+    import torch
+    if out is None:
+        out = torch.empty(size_fn(rows, K), dtype=torch.uint8, device=codes.device)
+    _check(fn(_dev_ptr(codes, torch.uint8, "codes"), rows, K, _dev_ptr(out, torch.uint8, "packed"),
+              out.numel(), _stream_ptr(stream)))
+    return out
+
+
+def dg_pack_weights(codes, M: int, K: int, out=None, stream=None):
+    """codes: uint8 device tensor with M*K elements ([M][K], or [Cout][KH][KW][Cin]) -> packed uint8 tensor."""
+    return _pack(lib().dg_pack_weights, dg_packed_weight_bytes, codes, M, K, out, stream)
+
+
+def dg_pack_activations(codes, N: int, K: int, out=None, stream=None):
+    """codes: uint8 device tensor with N*K elements ([N][K], or NHWC with N = B*H*W, K = C) -> packed uint8 tensor."""
+    return _pack(lib().dg_pack_activations, dg_packed_activation_bytes, codes, N, K, out, stream)
+
+
+def dg_gemm_lut(lut: Lut, Wp, Ap, M: int, N: int, K: int, out=None, scale=None, variant="auto",
+                stream=None, strides: Optional[Sequence[int]] = None):
+    """C[m][n] = sum_k LUT[4*Wc[m][k] + Ac[n][k]].  Returns int32 [M][N], or float32 when `scale` is given."""
+    import torch
+    dtype = torch.float32 if scale is not None else torch.int32
+    if out is None:
+        out = torch.empty((M, N), dtype=dtype, device=Wp.device)
+    scm, scn = (N, 1) if strides is None else strides
+    c_int = _dev_ptr(out, torch.int32, "out") if scale is None else ctypes.c_void_p(0)
+    c_f32 = _dev_ptr(out, torch.float32, "out") if scale is not None else ctypes.c_void_p(0)
+    _check(lib().dg_gemm_lut(lut.handle, _dev_ptr(Wp, torch.uint8, "Wp"), _dev_ptr(Ap, torch.uint8, "Ap"),
+                             M, N, K, c_int, scm, scn, _dev_ptr(scale, torch.float32, "scale"), c_f32,
+                             _kernel(variant), _stream_ptr(stream)))
+    return out
+
+
+def conv_desc(B, H, W, Cin, Cout, KH, KW, stride=(1, 1), pad=(0, 0)) -> ConvDesc:
+    return ConvDesc(B, H, W, Cin, Cout, KH, KW, stride[0], stride[1], pad[0], pad[1])
+
+
+def dg_conv2d_lut(lut: Lut, Wp, Xp, desc: ConvDesc, out=None, scale=None, variant="auto", stream=None):
+    """NHWC convolution by table lookup.  Returns [B][OH][OW][Cout], int32 or float32 (when `scale` is given)."""
+    import torch
+    OH = dg_conv_out_dim(desc.H, desc.KH, desc.stride_h, desc.pad_h)
+    OW = dg_conv_out_dim(desc.W, desc.KW, desc.stride_w, desc.pad_w)
+    dtype = torch.float32 if scale is not None else torch.int32
+    if out is None:
+        out = torch.empty((desc.B, max(OH, 0), max(OW, 0), desc.Cout), dtype=dtype, device=Wp.device)
+    y_int = _dev_ptr(out, torch.int32, "out") if scale is None else ctypes.c_void_p(0)
+    y_f32 = _dev_ptr(out, torch.float32, "out") if scale is not None else ctypes.c_void_p(0)
+    _check(lib().dg_conv2d_lut(lut.handle, _dev_ptr(Wp, torch.uint8, "Wp"), _dev_ptr(Xp, torch.uint8, "Xp"),
+                               ctypes.byref(desc), y_int, _dev_ptr(scale, torch.float32, "scale"), y_f32,
+                               _kernel(variant), _stream_ptr(stream)))
+    return out
+
+
+def dg_gemm_kernel_name(lut: Lut, M: int, N: int, K: int, variant="auto") -> str:
+    return lib().dg_gemm_kernel_name(lut.handle, M, N, K, _kernel(variant)).decode()
+
+
+def dg_conv_kernel_name(lut: Lut, desc: ConvDesc, variant="auto") -> str:
+    return lib().dg_conv_kernel_name(lut.handle, ctypes.byref(desc), _kernel(variant)).decode()

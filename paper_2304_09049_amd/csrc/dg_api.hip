@@ -1,0 +1,304 @@
+// Host side of the C ABI: argument validation, table construction, kernel selection.
+// Every entry point validates on the host before launching anything and never synchronises.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "dg_common.h"
+
+namespace {
+thread_local char g_error[512] = "";
+}
+
+dg_status dg_fail(dg_status s, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+dg_status dg_check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return dg_fail(DG_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return DG_OK;
+}
+
+extern "C" {
+
+const char *dg_status_string(dg_status s)
+{
+    switch (s) {
+    case DG_OK: return "DG_OK";
+    case DG_ERR_NULL: return "DG_ERR_NULL";
+    case DG_ERR_SHAPE: return "DG_ERR_SHAPE";
+    case DG_ERR_RANGE: return "DG_ERR_RANGE";
+    case DG_ERR_BUFFER: return "DG_ERR_BUFFER";
+    case DG_ERR_UNSUPPORTED: return "DG_ERR_UNSUPPORTED";
+    case DG_ERR_HIP: return "DG_ERR_HIP";
+    }
+    return "DG_ERR_UNKNOWN";
+}
+
+const char *dg_last_error(void) { return g_error; }
+
+// Sec. 3 "LUT-16": the table holds all possible results of w*a; index = weight code (high two
+// bits) concatenated with activation code (low two bits).
+dg_status dg_build_lut(const int8_t levels_w[4], const int8_t levels_a[4], dg_lut_dtype entry,
+                       dg_lut **out)
+{
+    if (!levels_w || !levels_a || !out) return dg_fail(DG_ERR_NULL, "dg_build_lut: NULL argument");
+    if (entry != DG_LUT_I8 && entry != DG_LUT_I16)
+        return dg_fail(DG_ERR_UNSUPPORTED, "dg_build_lut: unknown entry type %d", (int)entry);
+    dg_lut t;
+    memset(&t, 0, sizeof(t));
+    t.dtype = entry;
+    t.min_entry = INT32_MAX;
+    t.max_entry = INT32_MIN;
+    for (int w = 0; w < 4; ++w) {
+        t.levels_w[w] = levels_w[w];
+        t.levels_a[w] = levels_a[w];
+    }
+    for (int w = 0; w < 4; ++w)
+        for (int a = 0; a < 4; ++a) {
+            const int32_t prod = (int32_t)levels_w[w] * (int32_t)levels_a[a];
+            if (entry == DG_LUT_I8 && (prod < -128 || prod > 127))
+                return dg_fail(DG_ERR_RANGE,
+                               "dg_build_lut: product %d of levels_w[%d]=%d and levels_a[%d]=%d "
+                               "does not fit an int8 table entry",
+                               prod, w, (int)levels_w[w], a, (int)levels_a[a]);
+            t.entry[4 * w + a] = (int16_t)prod;   // |prod| <= 128*128 = 16384 always fits int16
+            if (prod < t.min_entry) t.min_entry = prod;
+            if (prod > t.max_entry) t.max_entry = prod;
+        }
+    t.max_abs = t.max_entry > -t.min_entry ? t.max_entry : -t.min_entry;
+    dg_lut *p = new (std::nothrow) dg_lut(t);
+    if (!p) return dg_fail(DG_ERR_BUFFER, "dg_build_lut: out of host memory");
+    *out = p;
+    return DG_OK;
+}
+
+dg_status dg_lut_entries(const dg_lut *lut, int16_t out16[16])
+{
+    if (!lut || !out16) return dg_fail(DG_ERR_NULL, "dg_lut_entries: NULL argument");
+    for (int i = 0; i < 16; ++i) out16[i] = lut->entry[i];
+    return DG_OK;
+}
+
+void dg_lut_destroy(dg_lut *lut) { delete lut; }
+
+size_t dg_packed_activation_bytes(int64_t rows, int64_t K)
+{
+    if (rows < 0 || K < 0 || K % 4 != 0) return 0;
+    return (size_t)rows * (size_t)(K / 4);
+}
+
+// The private weight layout currently coincides with the activation layout: with the table rows
+// and selectors expanded once per tile in LDS, no offline re-ordering of weights saves work here.
+size_t dg_packed_weight_bytes(int64_t M, int64_t K) { return dg_packed_activation_bytes(M, K); }
+
+static dg_status pack_common(const char *name, const uint8_t *codes_dev, int64_t rows, int64_t K,
+                             void *packed_dev, size_t packed_bytes, void *hip_stream)
+{
+    if (!codes_dev || !packed_dev) return dg_fail(DG_ERR_NULL, "%s: NULL buffer", name);
+    if (rows <= 0 || K <= 0 || K % 4 != 0)
+        return dg_fail(DG_ERR_SHAPE, "%s: rows=%lld K=%lld (need rows > 0, K > 0, K %% 4 == 0)", name,
+                       (long long)rows, (long long)K);
+    if (rows > INT32_MAX || K > INT32_MAX)
+        return dg_fail(DG_ERR_SHAPE, "%s: rows and K must each fit int32", name);
+    const size_t need = dg_packed_activation_bytes(rows, K);
+    if (packed_bytes < need)
+        return dg_fail(DG_ERR_BUFFER, "%s: packed buffer has %zu bytes, %zu needed", name,
+                       packed_bytes, need);
+    return dg_launch_pack(codes_dev, rows, K, (uint8_t *)packed_dev, (hipStream_t)hip_stream);
+}
+
+dg_status dg_pack_weights(const uint8_t *codes_dev, int64_t M, int64_t K, void *packed_dev,
+                          size_t packed_bytes, void *hip_stream)
+{
+    return pack_common("dg_pack_weights", codes_dev, M, K, packed_dev, packed_bytes, hip_stream);
+}
+
+dg_status dg_pack_activations(const uint8_t *codes_dev, int64_t N, int64_t K, void *packed_dev,
+                              size_t packed_bytes, void *hip_stream)
+{
+    return pack_common("dg_pack_activations", codes_dev, N, K, packed_dev, packed_bytes, hip_stream);
+}
+
+int64_t dg_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad)
+{
+    if (stride <= 0 || k <= 0 || in <= 0 || pad < 0) return 0;
+    const int64_t span = in + 2 * pad - k;
+    if (span < 0) return 0;
+    return span / stride + 1;
+}
+
+}   // extern "C"
+
+namespace {
+
+enum class Pick { Perm, Lds, Mfma, SmallN, Unsupported };
+
+Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
+{
+    switch (variant) {
+    case DG_KERNEL_PERM: return dg_perm_supports(lut, p) ? Pick::Perm : Pick::Unsupported;
+    case DG_KERNEL_LDS: return Pick::Lds;
+    case DG_KERNEL_MFMA_I8: return dg_mfma_supports(lut, p) ? Pick::Mfma : Pick::Unsupported;
+    case DG_KERNEL_SMALLN: return dg_smalln_supports(lut, p) ? Pick::SmallN : Pick::Unsupported;
+    case DG_KERNEL_AUTO:
+        // AUTO stays within the table kernels: the matrix-core kernel is a comparison only.
+        if (p.N <= 32 && dg_smalln_supports(lut, p)) return Pick::SmallN;
+        if (dg_perm_supports(lut, p)) return Pick::Perm;
+        return Pick::Lds;
+    }
+    return Pick::Unsupported;
+}
+
+dg_status run(const dg_lut *lut, const DgProblem &p, dg_kernel variant, hipStream_t stream)
+{
+    switch (pick_kernel(lut, p, variant)) {
+    case Pick::Perm: return dg_launch_perm(lut, p, stream);
+    case Pick::Lds: return dg_launch_lds(lut, p, stream);
+    case Pick::Mfma: return dg_launch_mfma(lut, p, stream);
+    case Pick::SmallN: return dg_launch_smalln(lut, p, stream);
+    case Pick::Unsupported: break;
+    }
+    return dg_fail(DG_ERR_UNSUPPORTED,
+                   "kernel variant %d cannot run M=%d N=%d K=%d (Cin=%d) with this table",
+                   (int)variant, p.M, p.N, p.K, p.Cin);
+}
+
+const char *pick_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
+{
+    switch (pick_kernel(lut, p, variant)) {
+    case Pick::Perm: return dg_perm_config_name(lut, p);
+    case Pick::Lds: return "lds";
+    case Pick::Mfma: return "mfma_i8";
+    case Pick::SmallN: return "smalln";
+    case Pick::Unsupported: break;
+    }
+    return "unsupported";
+}
+
+dg_status check_range(const char *name, const dg_lut *lut, int64_t K)
+{
+    // int32 accumulator: |sum| <= K * max|LUT| must stay below 2^31
+    if ((int64_t)lut->max_abs * K >= ((int64_t)1 << 31))
+        return dg_fail(DG_ERR_RANGE, "%s: K=%lld times max|LUT|=%d could overflow int32", name,
+                       (long long)K, lut->max_abs);
+    return DG_OK;
+}
+
+dg_status fill_gemm(const char *name, const dg_lut *lut, int64_t M, int64_t N, int64_t K,
+                    DgProblem *p)
+{
+    if (!lut) return dg_fail(DG_ERR_NULL, "%s: NULL table", name);
+    if (M <= 0 || N <= 0 || K <= 0 || K % 4 != 0)
+        return dg_fail(DG_ERR_SHAPE, "%s: M=%lld N=%lld K=%lld (need all > 0 and K %% 4 == 0)", name,
+                       (long long)M, (long long)N, (long long)K);
+    if (M > INT32_MAX / 2 || N > INT32_MAX / 2 || K > INT32_MAX / 2)
+        return dg_fail(DG_ERR_SHAPE, "%s: a dimension exceeds 2^30", name);
+    memset(p, 0, sizeof(*p));
+    p->M = (int32_t)M;
+    p->N = (int32_t)N;
+    p->K = (int32_t)K;
+    p->H = p->W = p->KH = p->KW = p->sh = p->sw = p->OH = p->OW = 1;
+    p->Cin = (int32_t)K;
+    return check_range(name, lut, K);
+}
+
+dg_status fill_conv(const char *name, const dg_lut *lut, const dg_conv_desc *d, DgProblem *p)
+{
+    if (!lut || !d) return dg_fail(DG_ERR_NULL, "%s: NULL table or descriptor", name);
+    if (d->B <= 0 || d->H <= 0 || d->W <= 0 || d->Cin <= 0 || d->Cout <= 0 || d->KH <= 0 ||
+        d->KW <= 0 || d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0)
+        return dg_fail(DG_ERR_SHAPE, "%s: every dimension and stride must be > 0 and pads >= 0", name);
+    if (d->Cin % 4 != 0) return dg_fail(DG_ERR_SHAPE, "%s: Cin=%d is not a multiple of 4", name, d->Cin);
+    const int64_t OH = dg_conv_out_dim(d->H, d->KH, d->stride_h, d->pad_h);
+    const int64_t OW = dg_conv_out_dim(d->W, d->KW, d->stride_w, d->pad_w);
+    if (OH <= 0 || OW <= 0) return dg_fail(DG_ERR_SHAPE, "%s: the filter does not fit the padded image", name);
+    const int64_t N = (int64_t)d->B * OH * OW;
+    const int64_t K = (int64_t)d->KH * d->KW * d->Cin;
+    const int64_t pixels = (int64_t)d->B * d->H * d->W;
+    if (N > INT32_MAX / 2 || K > INT32_MAX / 2 || pixels > INT32_MAX / 2 || d->Cout > INT32_MAX / 2)
+        return dg_fail(DG_ERR_SHAPE, "%s: a dimension exceeds 2^30", name);
+    memset(p, 0, sizeof(*p));
+    p->M = d->Cout;
+    p->N = (int32_t)N;
+    p->K = (int32_t)K;
+    p->H = d->H;
+    p->W = d->W;
+    p->Cin = d->Cin;
+    p->KH = d->KH;
+    p->KW = d->KW;
+    p->sh = d->stride_h;
+    p->sw = d->stride_w;
+    p->ph = d->pad_h;
+    p->pw = d->pad_w;
+    p->OH = (int32_t)OH;
+    p->OW = (int32_t)OW;
+    return check_range(name, lut, K);
+}
+
+}   // namespace
+
+extern "C" {
+
+dg_status dg_gemm_lut(const dg_lut *lut, const void *Wp_dev, const void *Ap_dev, int64_t M,
+                      int64_t N, int64_t K, int32_t *C_dev, int64_t stride_cm, int64_t stride_cn,
+                      const float *scale_m_dev, float *Cf_dev, dg_kernel variant, void *hip_stream)
+{
+    DgProblem p;
+    dg_status s = fill_gemm("dg_gemm_lut", lut, M, N, K, &p);
+    if (s != DG_OK) return s;
+    if (!Wp_dev || !Ap_dev) return dg_fail(DG_ERR_NULL, "dg_gemm_lut: NULL operand");
+    if (scale_m_dev ? !Cf_dev : !C_dev) return dg_fail(DG_ERR_NULL, "dg_gemm_lut: NULL output");
+    if (stride_cm == 0 || stride_cn == 0) return dg_fail(DG_ERR_SHAPE, "dg_gemm_lut: zero output stride");
+    p.Wp = (const uint8_t *)Wp_dev;
+    p.Xp = (const uint8_t *)Ap_dev;
+    p.C = C_dev;
+    p.Cf = Cf_dev;
+    p.scale = scale_m_dev;
+    p.stride_cm = stride_cm;
+    p.stride_cn = stride_cn;
+    return run(lut, p, variant, (hipStream_t)hip_stream);
+}
+
+dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_dev,
+                        const dg_conv_desc *desc, int32_t *Y_dev, const float *scale_cout_dev,
+                        float *Yf_dev, dg_kernel variant, void *hip_stream)
+{
+    DgProblem p;
+    dg_status s = fill_conv("dg_conv2d_lut", lut, desc, &p);
+    if (s != DG_OK) return s;
+    if (!Wp_dev || !Xp_dev) return dg_fail(DG_ERR_NULL, "dg_conv2d_lut: NULL operand");
+    if (scale_cout_dev ? !Yf_dev : !Y_dev) return dg_fail(DG_ERR_NULL, "dg_conv2d_lut: NULL output");
+    p.Wp = (const uint8_t *)Wp_dev;
+    p.Xp = (const uint8_t *)Xp_dev;
+    p.C = Y_dev;
+    p.Cf = Yf_dev;
+    p.scale = scale_cout_dev;
+    p.stride_cm = 1;          // NHWC: channel fastest
+    p.stride_cn = p.M;
+    return run(lut, p, variant, (hipStream_t)hip_stream);
+}
+
+const char *dg_gemm_kernel_name(const dg_lut *lut, int64_t M, int64_t N, int64_t K, dg_kernel variant)
+{
+    DgProblem p;
+    if (fill_gemm("dg_gemm_kernel_name", lut, M, N, K, &p) != DG_OK) return "invalid";
+    return pick_name(lut, p, variant);
+}
+
+const char *dg_conv_kernel_name(const dg_lut *lut, const dg_conv_desc *desc, dg_kernel variant)
+{
+    DgProblem p;
+    if (fill_conv("dg_conv_kernel_name", lut, desc, &p) != DG_OK) return "invalid";
+    return pick_name(lut, p, variant);
+}
+
+}   // extern "C"

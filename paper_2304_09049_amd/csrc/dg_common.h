@@ -1,0 +1,55 @@
+// Internal declarations shared by the host API and the gfx950 kernels of libdeepgemm_hip.
+// Nothing here is part of the public ABI (that is include/deepgemm_hip.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "deepgemm_hip.h"
+
+// The opaque table object: levels, the 16 products, and what the kernels need to know about them.
+struct dg_lut {
+    int8_t levels_w[4];
+    int8_t levels_a[4];
+    int16_t entry[16];   // entry[4*w + a] = levels_w[w] * levels_a[a]
+    dg_lut_dtype dtype;
+    int32_t min_entry;   // smallest product
+    int32_t max_entry;   // largest product
+    int32_t max_abs;     // max |product|
+};
+
+// 16 table entries passed to kernels by value (no device allocation is needed for a table).
+struct DgTable16 {
+    int16_t e[16];
+};
+
+// One implicit-GEMM problem.  A plain GEMM is the convolution with B = N, H = W = 1, a 1x1 filter
+// and Cin = K: "pixel" n is activation row n.
+//   M = Cout, N = B*OH*OW, K = KH*KW*Cin, reduction index k = (kh*KW + kw)*Cin + ci.
+struct DgProblem {
+    int32_t M, N, K;
+    int32_t H, W, Cin, KH, KW, sh, sw, ph, pw, OH, OW;
+    const uint8_t *Wp;    // packed weights, [M][K/4]
+    const uint8_t *Xp;    // packed activations, [B*H*W][Cin/4]
+    int32_t *C;           // int32 output (used when scale == nullptr)
+    float *Cf;            // fp32 output (used when scale != nullptr)
+    const float *scale;   // per-m scale or nullptr
+    int64_t stride_cm, stride_cn;   // element strides of the output
+};
+
+// Record the calling thread's error detail and return `s`.
+dg_status dg_fail(dg_status s, const char *fmt, ...);
+// Turn the launch status of the last kernel into a dg_status.
+dg_status dg_check_launch(const char *what);
+
+// Kernel launchers (each validates nothing: the API layer has done that).
+dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, uint8_t *packed,
+                         hipStream_t stream);
+dg_status dg_launch_lds(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+bool dg_perm_supports(const dg_lut *lut, const DgProblem &p);
+dg_status dg_launch_perm(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+const char *dg_perm_config_name(const dg_lut *lut, const DgProblem &p);
+bool dg_mfma_supports(const dg_lut *lut, const DgProblem &p);
+dg_status dg_launch_mfma(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+bool dg_smalln_supports(const dg_lut *lut, const DgProblem &p);
+dg_status dg_launch_smalln(const dg_lut *lut, const DgProblem &p, hipStream_t stream);

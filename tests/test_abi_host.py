@@ -1,0 +1,127 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared symbol,
+builds tables correctly and rejects bad arguments before anything is launched."""
+import ctypes
+import itertools
+import json
+import os
+import re
+
+import pytest
+
+from paper_2304_09049_amd import binding as dg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "deepgemm_hip.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = dg.lib()
+    names = declared_symbols()
+    assert set(names) == set(dg.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings():
+    L = dg.lib()
+    for i, name in enumerate(dg.STATUS_NAMES):
+        assert L.dg_status_string(i).decode() == name
+
+
+def test_build_lut_brute_force_all_pairs():
+    for lw, la in [((-2, -1, 0, 1), (0, 1, 2, 3)), ((0, 1, -2, -1), (3, 1, 0, 2)), ((-8, 7, 3, -5), (-7, 6, -8, 1))]:
+        t = dg.dg_build_lut(lw, la, dg.DG_LUT_I8).entries()
+        for w, a in itertools.product(range(4), range(4)):
+            assert t[4 * w + a] == lw[w] * la[a]
+
+
+def test_build_lut_matches_hand_written_table(golden_dir):
+    g = json.load(open(os.path.join(golden_dir, "lut16_signed_unsigned.json")))
+    assert dg.dg_build_lut(g["levels_w"], g["levels_a"]).entries() == g["table"]
+
+
+def test_build_lut_rejects_int8_overflow_and_accepts_int16():
+    with pytest.raises(dg.DgError) as e:
+        dg.dg_build_lut((127, 0, 0, 0), (2, 0, 0, 0), dg.DG_LUT_I8)
+    assert e.value.status == 3          # DG_ERR_RANGE: 254 does not fit int8
+    with pytest.raises(dg.DgError):
+        dg.dg_build_lut((-128, 0, 0, 0), (-1, 0, 0, 0), dg.DG_LUT_I8)   # +128
+    t = dg.dg_build_lut((127, -128, 0, 1), (-128, 127, 1, 0), dg.DG_LUT_I16).entries()
+    assert t[0] == 127 * -128 and t[5] == -128 * 127 and t[4] == 16384
+    dg.dg_build_lut((-128, 0, 0, 0), (1, 0, 0, 0), dg.DG_LUT_I8)        # -128 fits
+
+
+def test_build_lut_null_arguments():
+    L = dg.lib()
+    h = ctypes.c_void_p(0)
+    lw = (ctypes.c_int8 * 4)(1, 2, 3, 4)
+    assert L.dg_build_lut(None, lw, 0, ctypes.byref(h)) == 1
+    assert L.dg_build_lut(lw, lw, 0, None) == 1
+    assert L.dg_build_lut(lw, lw, 7, ctypes.byref(h)) == 5
+    assert b"NULL" in L.dg_last_error() or b"unknown" in L.dg_last_error()
+    L.dg_lut_destroy(None)
+
+
+def test_packed_sizes():
+    assert dg.dg_packed_activation_bytes(196, 576) == 196 * 144
+    assert dg.dg_packed_activation_bytes(3, 6) == 0           # K % 4 != 0
+    assert dg.dg_packed_activation_bytes(-1, 8) == 0
+    assert dg.dg_packed_weight_bytes(64, 576) >= 64 * 144
+
+
+def test_conv_out_dim():
+    assert dg.dg_conv_out_dim(56, 3, 1, 1) == 56
+    assert dg.dg_conv_out_dim(56, 3, 2, 1) == 28
+    assert dg.dg_conv_out_dim(8, 3, 2, 0) == 3
+    assert dg.dg_conv_out_dim(224, 7, 2, 3) == 112
+    assert dg.dg_conv_out_dim(2, 3, 1, 0) == 0
+
+
+def test_gemm_argument_errors_are_caught_before_any_launch():
+    L = dg.lib()
+    lut = dg.dg_build_lut((-2, -1, 0, 1), (0, 1, 2, 3))
+    fake = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
+    call = lambda *a: L.dg_gemm_lut(*a)
+    assert call(None, fake, fake, 4, 4, 4, fake, 4, 1, None, None, 0, None) == 1       # NULL table
+    assert call(lut.handle, None, fake, 4, 4, 4, fake, 4, 1, None, None, 0, None) == 1  # NULL operand
+    assert call(lut.handle, fake, fake, 4, 4, 4, None, 4, 1, None, None, 0, None) == 1  # NULL output
+    assert call(lut.handle, fake, fake, 4, 4, 4, fake, 4, 1, fake, None, 0, None) == 1  # scale but no fp32 out
+    assert call(lut.handle, fake, fake, 0, 4, 4, fake, 4, 1, None, None, 0, None) == 2  # M = 0
+    assert call(lut.handle, fake, fake, 4, 4, 6, fake, 4, 1, None, None, 0, None) == 2  # K % 4
+    assert call(lut.handle, fake, fake, 4, 4, 4, fake, 0, 1, None, None, 0, None) == 2  # zero stride
+    big = dg.dg_build_lut((127, -128, 0, 1), (-128, 127, 1, 0), dg.DG_LUT_I16)
+    assert call(big.handle, fake, fake, 4, 4, 1 << 18, fake, 4, 1, None, None, 0, None) == 3   # 2^18 * 16384 = 2^32
+    assert L.dg_last_error().decode() != ""
+
+
+def test_conv_argument_errors_are_caught_before_any_launch():
+    L = dg.lib()
+    lut = dg.dg_build_lut((-2, -1, 0, 1), (0, 1, 2, 3))
+    fake = ctypes.c_void_p(0x1000)
+
+    def call(desc, w=fake, x=fake, y=fake, scale=None, yf=None):
+        return L.dg_conv2d_lut(lut.handle, w, x, ctypes.byref(desc) if desc is not None else None, y, scale, yf, 0, None)
+
+    good = dg.conv_desc(1, 8, 8, 8, 4, 3, 3, (1, 1), (1, 1))
+    assert call(None) == 1
+    assert call(good, w=None) == 1
+    assert call(good, y=None) == 1
+    assert call(dg.conv_desc(1, 8, 8, 6, 4, 3, 3)) == 2                    # Cin % 4
+    assert call(dg.conv_desc(1, 2, 2, 8, 4, 3, 3)) == 2                    # filter larger than image
+    assert call(dg.conv_desc(1, 8, 8, 8, 4, 3, 3, (0, 1))) == 2            # stride 0
+    assert call(dg.conv_desc(1, 8, 8, 8, 4, 3, 3, (1, 1), (-1, 0))) == 2   # negative pad
+    assert call(dg.conv_desc(0, 8, 8, 8, 4, 3, 3)) == 2                    # empty batch
+
+
+def test_pack_argument_errors():
+    L = dg.lib()
+    fake = ctypes.c_void_p(0x1000)
+    assert L.dg_pack_activations(None, 4, 4, fake, 4, None) == 1
+    assert L.dg_pack_activations(fake, 4, 6, fake, 100, None) == 2
+    assert L.dg_pack_activations(fake, 0, 4, fake, 100, None) == 2
+    assert L.dg_pack_weights(fake, 4, 8, fake, 7, None) == 4               # needs 8 bytes

@@ -1,0 +1,81 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times (variant "auto"),
+plus every other variant that accepts the shape.  Where the oracle finishes in seconds the whole output
+is compared; otherwise a seeded sample of outputs (borders included) is computed one by one by the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2304_09049_amd import workloads as wl
+from gpu_helpers import GpuCase, run_or_unsupported
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = ["auto", "perm", "lds", "mfma_i8", "smalln"]
+FULL = ["gemm_64x196x576", "resnet18_conv3x3_b1", "resnet50_conv1x1_b32", "gemm_8192x1x8192_i16",
+        "gemm_8192x16x8192_i16"]
+SAMPLED = ["vgg16_conv3x3_b16", "gemm_8192x256x8192_i16", "gemm_8192x8192x8192_i16"]
+
+
+def _border_heavy_positions(w, rng, count):
+    """Flat NHWC output indices: a uniform sample plus every corner / some edge pixels of a few images."""
+    total = w.N * w.M
+    pos = [rng.integers(0, total, size=count)]
+    if w.kind == "conv":
+        OH = (w.H + 2 * w.pad[0] - w.KH) // w.stride[0] + 1
+        OW = (w.W + 2 * w.pad[1] - w.KW) // w.stride[1] + 1
+        for b in (0, w.B - 1):
+            for oh in (0, 1, OH - 2, OH - 1):
+                for ow in (0, 1, OW - 2, OW - 1):
+                    px = (b * OH + oh) * OW + ow
+                    pos.append(px * w.M + rng.integers(0, w.M, size=8))
+    return np.unique(np.concatenate(pos))
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_output(name):
+    w = wl.CONFIGS[name]
+    inp = wl.make_inputs(w)
+    case = GpuCase(inp)
+    if w.kind == "conv":
+        want = oracle.conv2d(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a, stride=w.stride, pad=w.pad)
+    else:
+        want = oracle.gemm(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a)
+    ran = []
+    for variant in VARIANTS:
+        got = run_or_unsupported(case, variant)
+        if got is None:
+            continue
+        ran.append(variant)
+        assert np.array_equal(got, want), f"{name} {variant}: {np.count_nonzero(got != want)} outputs differ"
+    assert "auto" in ran and "lds" in ran
+    if w.scale:
+        got = case.run("auto", scale=True).cpu().numpy()
+        ref = oracle.scale_epilogue_nhwc(want, inp.scale)
+        np.testing.assert_allclose(got, ref, rtol=1e-6, atol=0)
+
+
+@pytest.mark.parametrize("name", SAMPLED)
+def test_sampled_output(name):
+    w = wl.CONFIGS[name]
+    inp = wl.make_inputs(w)
+    case = GpuCase(inp)
+    rng = np.random.default_rng(123)
+    budget = 6e9                                  # multiply-adds the oracle is asked for
+    count = int(min(200000, budget // w.K))
+    pos = _border_heavy_positions(w, rng, count)
+    if w.kind == "conv":
+        want = oracle.conv2d_sampled(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a, pos, stride=w.stride, pad=w.pad)
+    else:
+        ms, ns = pos // w.N, pos % w.N            # GEMM output is [M][N]
+        want = oracle.gemm_sampled(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a, ms, ns)
+    ran = []
+    for variant in VARIANTS:
+        if variant == "lds" and w.ops > 2e11:
+            continue                               # the plain kernel would take too long at this size
+        got = run_or_unsupported(case, variant)
+        if got is None:
+            continue
+        ran.append(variant)
+        flat = got.reshape(-1)[pos]
+        assert np.array_equal(flat, want), f"{name} {variant}: {np.count_nonzero(flat != want)} sampled outputs differ"
+    assert "auto" in ran

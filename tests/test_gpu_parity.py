@@ -1,0 +1,191 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bar: bit-exact on int32 accumulators; fp32 epilogue within 1e-6 relative (it is one int->float
+conversion and one multiply, so equality is expected and also checked).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2304_09049_amd import binding as dg
+from paper_2304_09049_amd import workloads as wl
+from gpu_helpers import GpuCase, run_or_unsupported
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = ["auto", "lds", "perm", "mfma_i8", "smalln"]
+
+LEVELS = {
+    "signed_unsigned": ((-2, -1, 0, 1), (0, 1, 2, 3), dg.DG_LUT_I8),
+    "twos_complement": ((0, 1, -2, -1), (3, 1, 0, 2), dg.DG_LUT_I8),
+    "nonuniform_i8": ((-8, 7, 3, -5), (-7, 6, -8, 1), dg.DG_LUT_I8),
+    "nonuniform_i16": ((-8, 7, 3, -5), (-7, 6, -8, 1), dg.DG_LUT_I16),
+    "wide_i8": ((127, -128, 5, 0), (1, 0, 1, 1), dg.DG_LUT_I8),
+    "extreme_i16": ((127, -128, 5, 0), (-128, 127, 1, 0), dg.DG_LUT_I16),
+    "all_positive": ((1, 2, 3, 4), (4, 3, 2, 1), dg.DG_LUT_I8),
+}
+
+GEMM_SHAPES = [
+    (1, 1, 4), (3, 5, 8), (4, 4, 4), (17, 9, 20), (64, 196, 576), (70, 130, 192), (129, 257, 320),
+    (8, 1, 64), (1, 300, 128), (256, 512, 64), (33, 1000, 1024), (200, 3, 2048), (5, 16, 4096),
+]
+
+
+def _assert_same(got, want, what):
+    assert got.shape == want.shape, what
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        first = tuple(bad[0])
+        raise AssertionError(f"{what}: {len(bad)} of {got.size} differ; first at {first}: "
+                             f"got {got[first]} want {want[first]}")
+
+
+def test_pack_activations_matches_the_public_layout():
+    rng = np.random.default_rng(0)
+    for rows, K in [(1, 4), (3, 8), (7, 20), (196, 576), (5, 4096), (1000, 36)]:
+        codes = wl.draw_codes(rng, (rows, K))
+        got = dg.dg_pack_activations(torch.from_numpy(codes).cuda(), rows, K).cpu().numpy()
+        _assert_same(got.reshape(rows, K // 4), oracle.pack_codes(codes), f"pack {rows}x{K}")
+
+
+def test_pack_masks_high_bits_and_handles_unaligned_buffers():
+    rng = np.random.default_rng(1)
+    codes = wl.draw_codes(rng, (9, 52))
+    dirty = codes | (rng.integers(0, 64, size=codes.shape, dtype=np.uint8) << 2)   # garbage above bit 1
+    base = torch.zeros(9 * 52 + 3, dtype=torch.uint8, device="cuda")
+    view = base[3:]                                                                 # 3-byte offset
+    view.copy_(torch.from_numpy(dirty.reshape(-1)))
+    out = torch.zeros(9 * 13 + 1, dtype=torch.uint8, device="cuda")[1:]
+    dg.dg_pack_activations(view, 9, 52, out=out)
+    _assert_same(out.cpu().numpy().reshape(9, 13), oracle.pack_codes(codes), "unaligned pack")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("shape", GEMM_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_gemm_parity(shape, variant):
+    M, N, K = shape
+    inp = wl.small_gemm(M, N, K, seed=M * 7 + N * 3 + K)
+    case = GpuCase(inp)
+    got = run_or_unsupported(case, variant)
+    if got is None:
+        pytest.skip(f"{variant} declares {shape} unsupported")
+    _assert_same(got, oracle.gemm(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a), f"gemm {shape} {variant}")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("levels", sorted(LEVELS))
+def test_gemm_parity_level_tables(levels, variant):
+    lw, la, entry = LEVELS[levels]
+    for (M, N, K) in [(64, 196, 576), (37, 41, 4096), (130, 70, 64)]:
+        inp = wl.small_gemm(M, N, K, seed=11 + K)
+        case = GpuCase(inp, levels=(lw, la), entry=entry)
+        got = run_or_unsupported(case, variant)
+        if got is None:
+            pytest.skip(f"{variant} declares {levels} unsupported")
+        _assert_same(got, oracle.gemm(inp.Wc, inp.Ac, lw, la), f"gemm {levels} {(M, N, K)} {variant}")
+
+
+CONV_CASES = [
+    # B, H, W, Cin, Cout, KH, KW, stride, pad
+    (1, 3, 3, 4, 4, 3, 3, (1, 1), (1, 1)),
+    (2, 7, 9, 8, 5, 3, 3, (1, 1), (1, 1)),
+    (1, 8, 8, 16, 6, 3, 3, (2, 2), (1, 1)),
+    (2, 9, 6, 12, 4, 1, 1, (1, 1), (0, 0)),
+    (1, 10, 7, 4, 3, 5, 3, (2, 1), (2, 0)),
+    (1, 6, 11, 8, 2, 1, 7, (1, 3), (0, 3)),
+    (3, 5, 5, 16, 7, 3, 3, (1, 1), (0, 0)),
+    (1, 14, 14, 64, 64, 3, 3, (1, 1), (1, 1)),
+    (2, 13, 11, 64, 70, 3, 3, (1, 1), (1, 1)),
+    (1, 28, 28, 128, 33, 3, 3, (2, 2), (1, 1)),
+    (3, 9, 9, 256, 64, 1, 1, (1, 1), (0, 0)),
+    (1, 12, 12, 32, 40, 3, 3, (1, 1), (2, 2)),
+    (1, 17, 15, 48, 24, 5, 5, (1, 1), (2, 2)),
+    (2, 16, 16, 16, 130, 3, 3, (1, 1), (1, 1)),
+    (1, 9, 9, 64, 16, 7, 7, (2, 2), (3, 3)),
+]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("case_", CONV_CASES, ids=lambda c: "-".join(map(str, c[:7])))
+def test_conv_parity(case_, variant):
+    B, H, W, Cin, Cout, KH, KW, stride, pad = case_
+    for levels in ("signed_unsigned", "nonuniform_i8"):     # the second has no zero activation level
+        lw, la, entry = LEVELS[levels]
+        inp = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H * W + Cin + Cout)
+        case = GpuCase(inp, levels=(lw, la), entry=entry)
+        got = run_or_unsupported(case, variant)
+        if got is None:
+            pytest.skip(f"{variant} declares {case_} unsupported")
+        want = oracle.conv2d(inp.Wc, inp.Ac, lw, la, stride=stride, pad=pad)
+        _assert_same(got, want, f"conv {case_} {levels} {variant}")
+
+
+def test_golden_tiny_conv_on_gpu(golden_dir):
+    import json, os
+    from test_oracle_pins import _tiny_conv_weights
+    g = json.load(open(os.path.join(golden_dir, "tiny_conv.json")))
+    Wc, Xc = _tiny_conv_weights(g), np.array(g["X"], dtype=np.uint8)
+    for stride, key in (((1, 1), "Y_stride1"), ((2, 2), "Y_stride2")):
+        inp = wl.Inputs(workload=wl._conv("tiny", 1, 3, 3, 4, 4, 3, 3, stride, (1, 1)), levels_w=np.array(g["levels_w"]),
+                        levels_a=np.array(g["levels_a"]), Wc=Wc, Ac=Xc)
+        for variant in VARIANTS:
+            got = run_or_unsupported(GpuCase(inp), variant)
+            if got is not None:
+                _assert_same(got[0].transpose(2, 0, 1), np.array(g[key], dtype=np.int32), f"tiny conv {variant}")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_scale_epilogue(variant):
+    # convolution (NHWC, scale per channel) and GEMM (scale per row)
+    c = wl.small_conv(2, 13, 11, 64, 70, 3, 3, (1, 1), (1, 1), seed=5, scale=True)
+    case = GpuCase(c)
+    got = run_or_unsupported(case, variant, scale=True)
+    if got is None:
+        pytest.skip(f"{variant} unsupported")
+    acc = oracle.conv2d(c.Wc, c.Ac, c.levels_w, c.levels_a, stride=(1, 1), pad=(1, 1))
+    want = oracle.scale_epilogue_nhwc(acc, c.scale)
+    assert got.dtype == np.float32
+    np.testing.assert_allclose(got, want, rtol=1e-6, atol=0)
+    assert np.array_equal(got, want)          # one conversion and one multiply: expected to be identical
+
+    g = wl.make_inputs(wl.Workload(name="g", kind="gemm", M=70, N=130, K=192, scale=True, seed=3))
+    gc = GpuCase(g)
+    gg = run_or_unsupported(gc, variant, scale=True)
+    if gg is not None:
+        want = oracle.scale_epilogue_rows(oracle.gemm(g.Wc, g.Ac, g.levels_w, g.levels_a), g.scale)
+        np.testing.assert_allclose(gg, want, rtol=1e-6, atol=0)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_gemm_output_strides(variant):
+    # write C transposed ([N][M]) through the stride arguments
+    inp = wl.small_gemm(70, 130, 192, seed=21)
+    case = GpuCase(inp)
+    out = torch.full((130, 70), -7, dtype=torch.int32, device="cuda")
+    try:
+        dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, 70, 130, 192, out=out, variant=variant, strides=(1, 70))
+    except dg.DgError as e:
+        if e.status == 5:
+            pytest.skip(f"{variant} unsupported")
+        raise
+    torch.cuda.synchronize()
+    _assert_same(out.cpu().numpy(), oracle.gemm(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a).T.copy(), "strided")
+
+
+def test_results_do_not_depend_on_code_statistics():
+    # constant codes (every product the same table entry) and the skewed distribution
+    for c, d in ((0, 3), (3, 3), (2, 1)):
+        inp = wl.small_gemm(66, 140, 576, seed=1)
+        inp.Wc[:] = c
+        inp.Ac[:] = d
+        for variant in VARIANTS:
+            got = run_or_unsupported(GpuCase(inp), variant)
+            if got is not None:
+                assert np.all(got == 576 * int(inp.levels_w[c]) * int(inp.levels_a[d])), (c, d, variant)
+    inp = wl.small_gemm(64, 300, 256, seed=2, dist="relu_skew")
+    want = oracle.gemm(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a)
+    for variant in VARIANTS:
+        got = run_or_unsupported(GpuCase(inp), variant)
+        if got is not None:
+            _assert_same(got, want, f"skew {variant}")
