@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of the 2-bit lookup-table convolution on one MI355X.
+
+One "step" is one pass of the run-time hot path over one batch of synthetic codes already resident in
+HBM: pack the activation codes four per byte (dg_pack_activations), then the table convolution / GEMM with
+its epilogue (dg_conv2d_lut / dg_gemm_lut).  The table and the packed weights are built once, before the
+timed region (the paper packs weights offline, Sec. 5.2).  Steps are replayed from a HIP graph so that the
+host's launch cost does not cap a microsecond-scale kernel.
+
+Prints ONE JSON line.  `value` = 2*M*N*K / time per step, in GOPS, for the headline workload
+(ResNet18-style 3x3 convolution, batch 1, 56x56x64 -> 64, fp32 scale epilogue).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# published MI355X peaks used for the roofline fractions
+HBM_PEAK_GBS = 8000.0
+INT8_MFMA_PEAK_TOPS = 5000.0
+# VALU issue ceiling of the permute kernel: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions/s;
+# the inner loop spends one permute (4 products) and half a three-operand add per 4 products, so at most
+# 4 / 1.5 products per lane-instruction, 2 ops per product.
+VALU_LANE_INSTR_PER_S = 256 * 4 * 16 * 2.4e9
+PERM_ALU_PEAK_TOPS = VALU_LANE_INSTR_PER_S * (4 / 1.5) * 2 / 1e12
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default=None, help="name in workloads.CONFIGS (default: the headline conv)")
+    ap.add_argument("--variant", default="auto", help="auto | perm | lds | mfma_i8 | smalln")
+    ap.add_argument("--no-graph", action="store_true", help="launch every step from the host instead of a HIP graph")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the per-workload kernel sweep")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return ap.parse_args()
+
+
+class Runner:
+    """Device-resident operands of one workload and the calls that make up a step."""
+
+    def __init__(self, w, variant="auto"):
+        import torch
+        from paper_2304_09049_amd import binding as dg
+        from paper_2304_09049_amd import workloads as wl
+        self.torch, self.dg, self.w, self.variant = torch, dg, w, variant
+        self.inp = inp = wl.make_inputs(w)
+        dev = torch.device("cuda:0")
+        entry = dg.DG_LUT_I16 if w.lut_entry == "i16" else dg.DG_LUT_I8
+        self.lut = dg.dg_build_lut(inp.levels_w, inp.levels_a, entry)
+        self.Wp = dg.dg_pack_weights(torch.from_numpy(inp.Wc).to(dev), w.M, w.K)      # offline
+        self.codes = torch.from_numpy(inp.Ac).to(dev)                                  # resident input
+        self.scale = torch.from_numpy(inp.scale).to(dev) if inp.scale is not None else None
+        if w.kind == "conv":
+            self.rows, self.rowk = w.B * w.H * w.W, w.Cin
+            self.desc = dg.conv_desc(w.B, w.H, w.W, w.Cin, w.Cout, w.KH, w.KW, w.stride, w.pad)
+            OH = dg.dg_conv_out_dim(w.H, w.KH, w.stride[0], w.pad[0])
+            OW = dg.dg_conv_out_dim(w.W, w.KW, w.stride[1], w.pad[1])
+            shape = (w.B, OH, OW, w.Cout)
+        else:
+            self.rows, self.rowk = w.N, w.K
+            self.desc = None
+            shape = (w.M, w.N)
+        self.Ap = torch.empty(dg.dg_packed_activation_bytes(self.rows, self.rowk), dtype=torch.uint8, device=dev)
+        self.out = torch.empty(shape, dtype=torch.float32 if self.scale is not None else torch.int32, device=dev)
+        self.pack()
+        torch.cuda.synchronize()
+
+    def pack(self):
+        self.dg.dg_pack_activations(self.codes, self.rows, self.rowk, out=self.Ap)
+
+    def kernel(self, variant=None):
+        v = self.variant if variant is None else variant
+        if self.desc is not None:
+            self.dg.dg_conv2d_lut(self.lut, self.Wp, self.Ap, self.desc, out=self.out, scale=self.scale, variant=v)
+        else:
+            self.dg.dg_gemm_lut(self.lut, self.Wp, self.Ap, self.w.M, self.w.N, self.w.K, out=self.out,
+                                scale=self.scale, variant=v)
+
+    def step(self):
+        self.pack()
+        self.kernel()
+
+    def kernel_name(self, variant=None):
+        v = self.variant if variant is None else variant
+        if self.desc is not None:
+            return self.dg.dg_conv_kernel_name(self.lut, self.desc, v)
+        return self.dg.dg_gemm_kernel_name(self.lut, self.w.M, self.w.N, self.w.K, v)
+
+
+def time_calls(torch, fn, count, use_graph, chunk=500):
+    """Milliseconds per call of `fn` over exactly `count` calls, between two events on torch's current stream."""
+    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if use_graph:
+        per = min(chunk, count)
+        while count % per:
+            per -= 1
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            fn()                                   # make sure nothing lazy happens during capture
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(per):
+                    fn()
+        torch.cuda.synchronize()
+        graph.replay()                             # untimed: first replay uploads the graph
+        torch.cuda.synchronize()
+        start.record()
+        for _ in range(count // per):
+            graph.replay()
+        end.record()
+    else:
+        torch.cuda.synchronize()
+        start.record()
+        for _ in range(count):
+            fn()
+        end.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(end) / count
+
+
+def kernel_report(w, ms, name):
+    """Achieved rates of one kernel launch of duration `ms` against the three ceilings."""
+    gops = w.ops / (ms * 1e-3) / 1e9
+    gbs = w.algorithmic_bytes / (ms * 1e-3) / 1e9
+    return {
+        "kernel": name, "us": round(ms * 1e3, 3), "gops": round(gops, 1), "algorithmic_GBps": round(gbs, 1),
+        "frac_hbm": round(gbs / HBM_PEAK_GBS, 4),
+        "frac_int8_mfma_peak": round(gops / 1e3 / INT8_MFMA_PEAK_TOPS, 4),
+        "frac_perm_alu_peak": round(gops / 1e3 / PERM_ALU_PEAK_TOPS, 4),
+    }
+
+
+def roofline_object(w, ms, name):
+    """The roofline entry of the dominant kernel: HBM when the HBM time of the algorithmic bytes exceeds the
+    ALU time of the products at the permute kernel's issue ceiling, else ALU."""
+    t_hbm = w.algorithmic_bytes / (HBM_PEAK_GBS * 1e9)
+    t_alu = w.ops / (PERM_ALU_PEAK_TOPS * 1e12)
+    if name.startswith("mfma"):
+        ach = w.ops / (ms * 1e-3) / 1e12
+        return {"bound": "mfma", "achieved": round(ach, 3), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TFLOP/s",
+                "frac": round(ach / INT8_MFMA_PEAK_TOPS, 5), "traffic": None, "kernel": name}
+    if t_hbm >= t_alu:
+        ach = w.algorithmic_bytes / (ms * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBS, 5), "traffic": None, "kernel": name}
+    ach = w.ops / (ms * 1e-3) / 1e12
+    return {"bound": "alu", "achieved": round(ach, 3), "peak": round(PERM_ALU_PEAK_TOPS, 1), "unit": "TFLOP/s",
+            "frac": round(ach / PERM_ALU_PEAK_TOPS, 5), "traffic": None, "kernel": name,
+            "note": "integer table lookups+adds counted as 2 ops per product; peak = VALU issue ceiling of the permute loop"}
+
+
+def cpu_baseline(w):
+    """The CPU oracle, as it stands, on the host cores: the full headline workload, repeated."""
+    import oracle
+    from paper_2304_09049_amd import workloads as wl
+    inp = wl.make_inputs(w)
+
+    def once():
+        if w.kind == "conv":
+            return oracle.conv2d(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a, stride=w.stride, pad=w.pad)
+        return oracle.gemm(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a)
+
+    cores = oracle.max_threads()
+    once()
+    reps, t0 = 0, time.perf_counter()
+    while reps < 3 or time.perf_counter() - t0 < 5.0:
+        once()
+        reps += 1
+    dt_all = (time.perf_counter() - t0) / reps
+    oracle.set_threads(1)
+    t0 = time.perf_counter()
+    once()
+    dt_one = time.perf_counter() - t0
+    oracle.set_threads(cores)
+    return {"value": round(w.ops / dt_all / 1e9, 3), "unit": "GOPS", "cores": cores, "kind": "oracle",
+            "sample": f"the full {w.name} workload (M={w.M} N={w.N} K={w.K}), {reps} passes on {cores} threads",
+            "single_thread_gops": round(w.ops / dt_one / 1e9, 3)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this path has no multi-GPU leg (it would shard N with no "
+              "collective); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2304_09049_amd import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    use_graph = not args.no_graph
+    w = wl.CONFIGS[args.workload or wl.HEADLINE]
+    r = Runner(w, args.variant)
+
+    for _ in range(args.warmup):
+        r.step()
+    torch.cuda.synchronize()
+    ms_step = time_calls(torch, r.step, args.steps, use_graph)
+    ms_kernel = time_calls(torch, r.kernel, args.steps, use_graph)       # the dominant kernel alone
+    ms_pack = time_calls(torch, r.pack, args.steps, use_graph)
+    name = r.kernel_name()
+
+    line = {
+        "metric": "effective GOPS (2*M*N*K/s), 2-bit LUT conv",
+        "value": round(w.ops / (ms_step * 1e-3) / 1e9, 1),
+        "unit": "GOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32 accumulation of int8 table entries (2-bit codes); fp32 scale epilogue",
+        "data": "synthetic",
+        "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "variant": args.variant, "kernel": name,
+                   "step": "dg_pack_activations + " + ("dg_conv2d_lut" if w.kind == "conv" else "dg_gemm_lut"),
+                   "launch": "hip graph replay" if use_graph else "host launches"},
+        "kernel_only": kernel_report(w, ms_kernel, name),
+        "pack_activations_us": round(ms_pack * 1e3, 3),
+        "roofline": roofline_object(w, ms_kernel, name),
+        "paper_context": "up to 1.74x over QNNPACK INT8 on an Intel i7-9700K (speedup ratios only; no absolute figure)",
+    }
+
+    if not args.no_sweep:
+        sweep = []
+        for wname, ww in wl.CONFIGS.items():
+            rr = r if ww is w else Runner(ww, "auto")
+            for variant in ("auto", "mfma_i8", "lds"):
+                if variant == "lds" and ww.ops > 1e11:
+                    continue
+                try:
+                    kname = rr.kernel_name(variant)
+                    if kname == "unsupported":
+                        continue
+                    reps = 200 if ww.ops < 1e10 else (20 if ww.ops < 2e11 else 5)
+                    fn = lambda v=variant, q=rr: q.kernel(v)
+                    for _ in range(3):
+                        fn()
+                    ms = time_calls(torch, fn, reps, use_graph and reps >= 100, chunk=100)
+                    rep = kernel_report(ww, ms, kname)
+                    rep.update({"workload": wname, "variant": variant})
+                    sweep.append(rep)
+                except Exception as e:                      # report, never hide
+                    sweep.append({"workload": wname, "variant": variant, "error": str(e)})
+            del rr
+        line["sweep"] = sweep
+
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
