@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch every step from the host instead of a HIP graph")
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-workload kernel sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="also run one plain device-to-device copy of this many MiB (a known-size dispatch "
+                         "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled)")
     return ap.parse_args()
 
 
@@ -200,6 +203,13 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     use_graph = not args.no_graph
+    if args.calibrate_copy > 0:
+        src = torch.ones(args.calibrate_copy << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)             # an elementwise kernel: reads and writes exactly that many bytes
+        torch.cuda.synchronize()
+        del src, dst
     w = wl.CONFIGS[args.workload or wl.HEADLINE]
     r = Runner(w, args.variant)
 

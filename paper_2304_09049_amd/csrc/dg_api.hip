@@ -151,7 +151,7 @@ Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case DG_KERNEL_SMALLN: return dg_smalln_supports(lut, p) ? Pick::SmallN : Pick::Unsupported;
     case DG_KERNEL_AUTO:
         // AUTO stays within the table kernels: the matrix-core kernel is a comparison only.
-        if (p.N <= 32 && dg_smalln_supports(lut, p)) return Pick::SmallN;
+        if (p.N <= 32 && p.K >= 1024 && dg_smalln_supports(lut, p)) return Pick::SmallN;
         if (dg_perm_supports(lut, p)) return Pick::Perm;
         return Pick::Lds;
     }
