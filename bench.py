@@ -31,6 +31,21 @@ INT8_MFMA_PEAK_TOPS = 5000.0
 VALU_LANE_INSTR_PER_S = 256 * 4 * 16 * 2.4e9
 PERM_ALU_PEAK_TOPS = VALU_LANE_INSTR_PER_S * (4 / 1.5) * 2 / 1e12
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch),
+# each scaled by what the same counter reads for a 1 GiB elementwise copy (FETCH_SIZE reads 0.5 of the true
+# bytes -> x2.0; WRITE_SIZE reads them exactly -> x1.0).  Summaries with the commands are under profiles/.
+# Keyed by (workload, kernel name); a kernel or workload that was not profiled reports null.
+MEASURED_TRAFFIC_KIB = {
+    ("resnet18_conv3x3_b1", "perm_2x4_8x8_k96_s6_b1_m0"): (291.0 * 2.0, 784.0),
+    ("vgg16_conv3x3_b16", "perm_8x8_16x16_k48_s1_b2_m0"): (6661.0 * 2.0, 50176.6),
+    ("gemm_8192x1x8192_i16", "smalln"): (8279.5 * 2.0, 32.0),
+}
+
+
+def measured_traffic(w, name):
+    kib = MEASURED_TRAFFIC_KIB.get((w.name, name))
+    return None if kib is None else int(round((kib[0] + kib[1]) * 1024))
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -156,10 +171,12 @@ def roofline_object(w, ms, name):
     if t_hbm >= t_alu:
         ach = w.algorithmic_bytes / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBS, 5), "traffic": None, "kernel": name}
+                "frac": round(ach / HBM_PEAK_GBS, 5), "traffic": measured_traffic(w, name), "kernel": name,
+                "algorithmic_bytes": w.algorithmic_bytes}
     ach = w.ops / (ms * 1e-3) / 1e12
     return {"bound": "alu", "achieved": round(ach, 3), "peak": round(PERM_ALU_PEAK_TOPS, 1), "unit": "TFLOP/s",
-            "frac": round(ach / PERM_ALU_PEAK_TOPS, 5), "traffic": None, "kernel": name,
+            "frac": round(ach / PERM_ALU_PEAK_TOPS, 5), "traffic": measured_traffic(w, name), "kernel": name,
+            "algorithmic_bytes": w.algorithmic_bytes,
             "note": "integer table lookups+adds counted as 2 ops per product; peak = VALU issue ceiling of the permute loop"}
 
 

@@ -120,25 +120,41 @@ perm_lut_kernel(PermArgs a)
         for (int i = 0; i < TM * TN; ++i)
             if (g == 0) s_red[i * GT + t] = 0;
     }
+    __syncthreads();            // the pool table is visible; taken here, where every wave arrives at the same time
+
+    // the per-row scales of the epilogue are requested now so that their latency hides behind the K loop
+    const int m_first = m_base + ml * TM, n_first = n_base + nl * TN;
+    float sc[TM];
+    if (p.scale && g == 0) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) sc[i] = p.scale[min(m_first + i, p.M - 1)];
+    }
 
     // ---- loader tasks (fixed per lane for the whole K loop) ---------------------------------
     // weight side: (LDS slot, word) -> 8 pools;  activation side: (column pair, word) -> 8 selectors
     constexpr int WTASKS = BM * DW, WPER = (WTASKS + GT - 1) / GT;
     constexpr int ATASKS = NP * DW, APER = (ATASKS + GT - 1) / GT;
 
+    // When the group's lane count is a multiple of the tile's rows (column pairs), a lane keeps the same weight
+    // row (column pair) in all of its tasks and only the word index moves: the address set-up is done once.
+    constexpr bool W_FIXED = GT % BM == 0, A_FIXED = GT % NP == 0;
     const uint32_t *w_ptr[WPER];
     int w_slot[WPER], w_d[WPER];
 #pragma unroll
     for (int i = 0; i < WPER; ++i) {
         const int task = t + i * GT;
         // consecutive lanes own consecutive LDS slots; the weight row follows from the slot
-        w_slot[i] = task % BM;
-        w_d[i] = task / BM;
-        const int slot = w_slot[i];
-        const int row = ((slot >> 1) % LM) * TM + 2 * (slot / (2 * LM)) + (slot & 1);
-        int m = m_base + row;
-        if (m >= p.M) m = p.M - 1;                       // rows beyond M: read a valid row, never stored
-        w_ptr[i] = (const uint32_t *)(p.Wp + (int64_t)m * (p.K / 4)) + w_d[i] + g * DW;
+        w_slot[i] = W_FIXED ? t % BM : task % BM;
+        w_d[i] = W_FIXED ? t / BM + i * (GT / BM) : task / BM;
+        if (i == 0 || !W_FIXED) {
+            const int slot = w_slot[i];
+            const int row = ((slot >> 1) % LM) * TM + 2 * (slot / (2 * LM)) + (slot & 1);
+            int m = m_base + row;
+            if (m >= p.M) m = p.M - 1;                   // rows beyond M: read a valid row, never stored
+            w_ptr[i] = (const uint32_t *)(p.Wp + (int64_t)m * (p.K / 4)) + w_d[i] + g * DW;
+        } else {
+            w_ptr[i] = w_ptr[0] + i * (GT / BM);
+        }
     }
     int a_np[APER], a_k0[APER], a_ci[APER], a_kh[APER], a_kw[APER];
     int a_ih0[APER][2], a_iw0[APER][2];                   // top-left source pixel of the filter window
@@ -147,25 +163,43 @@ perm_lut_kernel(PermArgs a)
 #pragma unroll
     for (int i = 0; i < APER; ++i) {
         const int task = t + i * GT;
-        a_np[i] = task % NP;
-        const int d = task / NP;
+        a_np[i] = A_FIXED ? t % NP : task % NP;
+        const int d = A_FIXED ? t / NP + i * (GT / NP) : task / NP;
         a_k0[i] = g * KS + 16 * d;                        // first reduction position of this lane's word
         const uint32_t tap = fdiv((uint32_t)a_k0[i], a.div_cin);
         a_ci[i] = a_k0[i] - (int)tap * p.Cin;
         a_kh[i] = (int)fdiv(tap, a.div_kw);
         a_kw[i] = (int)tap - a_kh[i] * p.KW;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int n = n_base + 2 * a_np[i] + h;
-            a_ok[i][h] = (ATASKS % GT == 0 || task < ATASKS) && (n < p.N);
-            const uint32_t nn = a_ok[i][h] ? (uint32_t)n : 0u;
+        if (i == 0 || !A_FIXED) {
+            // the pair's first column by division, its second by stepping one pixel on
+            const int n0 = n_base + 2 * a_np[i];
+            const uint32_t nn = n0 < p.N ? (uint32_t)n0 : 0u;
             const uint32_t row = fdiv(nn, a.div_ow);              // b*OH + oh
-            const int ow = (int)(nn - row * (uint32_t)p.OW);
-            const uint32_t b = fdiv(row, a.div_oh);
-            const int oh = (int)(row - b * (uint32_t)p.OH);
-            a_ih0[i][h] = oh * p.sh - p.ph;
-            a_iw0[i][h] = ow * p.sw - p.pw;
-            a_off0[i][h] = (((int)b * p.H + a_ih0[i][h]) * p.W + a_iw0[i][h]) * cq;
+            int ow = (int)(nn - row * (uint32_t)p.OW);
+            int b = (int)fdiv(row, a.div_oh);
+            int oh = (int)row - b * p.OH;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                a_ok[i][h] = (ATASKS % GT == 0 || task < ATASKS) && (n0 + h < p.N);
+                a_ih0[i][h] = oh * p.sh - p.ph;
+                a_iw0[i][h] = ow * p.sw - p.pw;
+                a_off0[i][h] = ((b * p.H + a_ih0[i][h]) * p.W + a_iw0[i][h]) * cq;
+                if (++ow == p.OW) {
+                    ow = 0;
+                    if (++oh == p.OH) {
+                        oh = 0;
+                        ++b;
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                a_ok[i][h] = a_ok[0][h] && (ATASKS % GT == 0 || task < ATASKS);
+                a_ih0[i][h] = a_ih0[0][h];
+                a_iw0[i][h] = a_iw0[0][h];
+                a_off0[i][h] = a_off0[0][h];
+            }
         }
     }
 
@@ -281,7 +315,6 @@ perm_lut_kernel(PermArgs a)
     const int stages = (p.K + KS - 1) / KS;
     const int iters = (stages + SK - 1) / SK;       // stages per group (the last may be empty: all selectors 0x0C)
     fetch(0);
-    __syncthreads();            // s_table is ready
     expand(0);
     __syncthreads();
 
@@ -343,37 +376,62 @@ perm_lut_kernel(PermArgs a)
     }
 
     // ---- epilogue: remove the bias, optional per-channel scale, store ------------------------------
+    // This lane's outputs: rows m_first .. m_first+TM-1, columns n_first .. n_first+TN-1.  The contiguous output
+    // axis (channels when MFAST, columns otherwise) is written with 64/128-bit stores when alignment allows.
+    if (m_first >= p.M || n_first >= p.N) return;
+    const int64_t scm = MFAST ? 1 : p.stride_cm, scn = p.stride_cn;   // MFAST is launched only when stride_cm == 1
+    int32_t bias[TN];
+    {
+        const uint32_t row = fdiv((uint32_t)n_first, a.div_ow);
+        int ow = n_first - (int)row * p.OW;
+        int oh = (int)(row - fdiv(row, a.div_oh) * (uint32_t)p.OH);
+        const int full = a.min_entry * p.K;
 #pragma unroll
-    for (int c = 0; c < TN; ++c) {
-        const int n = n_base + nl * TN + c;
-        if (n >= p.N) continue;
-        int taps = p.KH * p.KW;
-        if (p.ph | p.pw) {                                 // count the filter taps inside the image
-            const uint32_t row = fdiv((uint32_t)n, a.div_ow);
-            const int ow = n - (int)row * p.OW;
-            const int oh = (int)(row - fdiv(row, a.div_oh) * (uint32_t)p.OH);
-            int th = 0, tw = 0;
-            for (int kh = 0; kh < p.KH; ++kh) {
-                const int ih = oh * p.sh - p.ph + kh;
-                th += (ih >= 0 && ih < p.H);
+        for (int c = 0; c < TN; ++c) {
+            bias[c] = full;
+            if (p.ph | p.pw) {
+                // filter taps inside the image: kh in [max(0, ph - oh*sh), min(KH, H + ph - oh*sh))
+                const int h0 = p.ph - oh * p.sh, w0 = p.pw - ow * p.sw;
+                const int th = min(p.KH, p.H + h0) - max(0, h0), tw = min(p.KW, p.W + w0) - max(0, w0);
+                bias[c] = a.min_entry * p.Cin * max(th, 0) * max(tw, 0);
             }
-            for (int kw = 0; kw < p.KW; ++kw) {
-                const int iw = ow * p.sw - p.pw + kw;
-                tw += (iw >= 0 && iw < p.W);
+            if (++ow == p.OW) {
+                ow = 0;
+                if (++oh == p.OH) oh = 0;
             }
-            taps = th * tw;
         }
-        const int32_t bias = a.min_entry * taps * p.Cin;
+    }
+    unsigned char *out = (unsigned char *)(p.scale ? (void *)p.Cf : (void *)p.C);   // both element types are 4 bytes
+    out += 4 * ((int64_t)m_first * scm + (int64_t)n_first * scn);
+    constexpr int VL = MFAST ? TM : TN;                      // elements along the contiguous axis
+    constexpr int VEC = VL % 4 == 0 ? 4 : 2;
+    const bool whole = MFAST ? (m_first + TM <= p.M) : (n_first + TN <= p.N);
+    const int64_t other = MFAST ? scn : scm;                 // stride of the axis the loop below walks
+    const int64_t contig = MFAST ? 1 : scn;                  // stride of the axis written within a line
+    const bool vec_ok = whole && contig == 1 && ((uintptr_t)out % (4 * VEC) == 0) && (other % VEC == 0);
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int m = m_base + ml * TM + i;
-            if (m >= p.M) continue;
-            const int32_t v = acc[i][c] + bias;
-            const int64_t o = (int64_t)m * p.stride_cm + (int64_t)n * p.stride_cn;
-            if (p.scale)
-                p.Cf[o] = (float)v * p.scale[m];
-            else
-                p.C[o] = v;
+    for (int o = 0; o < (MFAST ? TN : TM); ++o) {            // one line per column (MFAST) or per row
+        if (MFAST ? (n_first + o >= p.N) : (m_first + o >= p.M)) break;
+        uint32_t bits[VL];
+#pragma unroll
+        for (int e = 0; e < VL; ++e) {
+            const int i = MFAST ? e : o, c = MFAST ? o : e;
+            const int32_t v = acc[i][c] + bias[c];
+            bits[e] = p.scale ? __float_as_uint((float)v * sc[i]) : (uint32_t)v;
+        }
+        unsigned char *line = out + 4 * o * other;
+        if (vec_ok) {
+#pragma unroll
+            for (int e = 0; e < VL; e += VEC) {
+                if (VEC == 4)
+                    *(uint4 *)(line + 4 * e) = make_uint4(bits[e], bits[e + 1], bits[e + 2], bits[e + 3]);
+                else
+                    *(uint2 *)(line + 4 * e) = make_uint2(bits[e], bits[e + 1]);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < VL; ++e)
+                if (MFAST ? (m_first + e < p.M) : (n_first + e < p.N)) *(uint32_t *)(line + 4 * e * contig) = bits[e];
         }
     }
 }

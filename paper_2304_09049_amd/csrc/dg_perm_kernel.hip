@@ -58,7 +58,11 @@ const PermPlan *plan_for(const dg_lut *lut, const DgProblem &p)
     auto tiles = [&](const PermPlan *c) {
         return ((int64_t)(p.M + c->BM() - 1) / c->BM()) * (((int64_t)p.N + c->BN() - 1) / c->BN());
     };
-    const PermPlan *big = find(8, 8, 32, 1, mode), *mid = find(4, 8, 32, 1, mode);
+    // 48-code stages make one fold per stage for the benchmark table (range 9: a fold every 3 words); 64-code
+    // stages divide the 1x1 layers' K = 256
+    const PermPlan *big = find(8, 8, 48, 1, mode), *mid = find(4, 8, 64, 1, mode);
+    if (!big) big = find(8, 8, 32, 1, mode);
+    if (!mid) mid = find(4, 8, 32, 1, mode);
     const PermPlan *one_stage = find(2, 4, 96, 6, mode), *split = find(4, 4, 48, 4, mode);
     // 128 x 128 tiles when they fill the chip twice over, else 64 x 128, else split K inside the workgroup
     if (big && p.M > 64 && tiles(big) >= 2 * kComputeUnits) return big;

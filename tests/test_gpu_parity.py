@@ -189,3 +189,73 @@ def test_results_do_not_depend_on_code_statistics():
         got = run_or_unsupported(GpuCase(inp), variant)
         if got is not None:
             _assert_same(got, want, f"skew {variant}")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_gemm_general_output_strides(variant):
+    # neither stride is 1: every output lands in its own slot of a padded buffer, nothing else is touched
+    M, N, K = 70, 130, 192
+    inp = wl.small_gemm(M, N, K, seed=22)
+    case = GpuCase(inp)
+    scm, scn = 3 * N + 5, 3
+    out = torch.full((M * scm,), -7, dtype=torch.int32, device="cuda")
+    try:
+        dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant=variant, strides=(scm, scn))
+    except dg.DgError as e:
+        if e.status == 5:
+            pytest.skip(f"{variant} unsupported")
+        raise
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want = np.full(M * scm, -7, dtype=np.int32)
+    ref = oracle.gemm(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a)
+    idx = (np.arange(M)[:, None] * scm + np.arange(N)[None, :] * scn)
+    want[idx.reshape(-1)] = ref.reshape(-1)
+    _assert_same(got, want, f"general strides {variant}")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_degenerate_tables(variant):
+    # all-zero table (range 0), a table with a single non-zero entry, and a constant non-zero table
+    inp = wl.small_gemm(66, 140, 320, seed=31)
+    for lw, la in (((0, 0, 0, 0), (1, 2, 3, 4)), ((0, 0, 5, 0), (0, -7, 0, 0)), ((3, 3, 3, 3), (-2, -2, -2, -2))):
+        got = run_or_unsupported(GpuCase(inp, levels=(lw, la), entry=dg.DG_LUT_I8), variant)
+        if got is not None:
+            _assert_same(got, oracle.gemm(inp.Wc, inp.Ac, lw, la), f"degenerate {lw} {la} {variant}")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_long_reduction_near_the_int32_limit(variant):
+    # K = 131072 with |entries| up to 127*127: |sum| can reach 2^31 -> rejected; with entries up to 16129 / 2 it fits
+    K = 131072
+    inp = wl.small_gemm(6, 10, K, seed=32)
+    inp.Wc[0, :] = 0
+    inp.Ac[0, :] = 0                      # output (0,0) is K * lw[0] * la[0]: the largest magnitude the table allows
+    lw, la = (127, -128, 5, 0), (127, -128, 1, 0)
+    with pytest.raises(dg.DgError) as e:
+        GpuCase(inp, levels=(lw, la), entry=dg.DG_LUT_I16).run(variant)
+    assert e.value.status in (3, 5)       # DG_ERR_RANGE (or UNSUPPORTED for a variant that rejects the shape first)
+    lw, la = (63, -64, 5, 0), (127, -128, 1, 0)          # 131072 * 8192 = 2^30
+    case = GpuCase(inp, levels=(lw, la), entry=dg.DG_LUT_I16)
+    got = run_or_unsupported(case, variant)
+    if got is not None:
+        want = oracle.gemm(inp.Wc, inp.Ac, lw, la)
+        assert want[0, 0] == K * 63 * 127
+        _assert_same(got, want, f"long K {variant}")
+    # an int8 table of full range (255) over the same K exercises the 16-bit-lane fold period
+    lw, la = (127, -128, 5, 0), (1, 0, 1, 1)
+    got = run_or_unsupported(GpuCase(inp, levels=(lw, la), entry=dg.DG_LUT_I8), variant)
+    if got is not None:
+        _assert_same(got, oracle.gemm(inp.Wc, inp.Ac, lw, la), f"long K int8 {variant}")
+
+
+def test_empty_and_bad_shapes_launch_nothing():
+    lut = dg.dg_build_lut((-2, -1, 0, 1), (0, 1, 2, 3))
+    buf = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    out = torch.full((16,), 9, dtype=torch.int32, device="cuda")
+    for M, N, K in ((0, 4, 4), (4, 0, 4), (4, 4, 0), (4, 4, 6), (-1, 4, 4)):
+        with pytest.raises(dg.DgError) as e:
+            dg.dg_gemm_lut(lut, buf, buf, M, N, K, out=out)
+        assert e.value.status == 2
+    torch.cuda.synchronize()
+    assert bool((out == 9).all())
