@@ -78,7 +78,11 @@ struct PermShape {
     static constexpr int DW = KS / 16;         // 32-bit packed words per row per stage
     static constexpr int POOL_BYTES = NBUF * QS * BM * 8;   // per group, NBUF stages
     static constexpr int SELW = MODE == 1 ? 2 : 1;   // selector words per (pair q, column pair)
-    static constexpr int SEL_BYTES = NBUF * QS * NP * 4 * SELW;
+    // selector words one lane reads per pair q, padded to whole 128-bit reads (matters for TN = 14: 7 -> 8)
+    static constexpr int SPL = (TN / 2 * SELW + 3) / 4 * 4 > TN / 2 * SELW && TN / 2 * SELW > 4 ? (TN / 2 * SELW + 3) / 4 * 4
+                                                                                                : TN / 2 * SELW;
+    static constexpr int SROW = LN * SPL;            // selector words per pair q
+    static constexpr int SEL_BYTES = NBUF * QS * SROW * 4;
     static constexpr int RED_BYTES = SK > 1 ? TM * TN * GT * 4 : 0;
     static constexpr int LDS_BYTES = 128 + SK * (POOL_BYTES + SEL_BYTES) + RED_BYTES;
 };
@@ -92,6 +96,7 @@ perm_lut_kernel(PermArgs a)
 {
     using S = PermShape<TM, TN, LM, LN, KS, SK, NBUF, MODE>;
     constexpr int GT = S::GT, BM = S::BM, BN = S::BN, NP = S::NP, QS = S::QS, DW = S::DW, SELW = S::SELW;
+    constexpr int SPL = S::SPL, SROW = S::SROW;
     static_assert(TM % 2 == 0 && TN % 2 == 0 && KS % 16 == 0, "tile shape");
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -156,7 +161,7 @@ perm_lut_kernel(PermArgs a)
             w_ptr[i] = w_ptr[0] + i * (GT / BM);
         }
     }
-    int a_np[APER], a_k0[APER], a_ci[APER], a_kh[APER], a_kw[APER];
+    int a_np[APER], a_sidx[APER], a_k0[APER], a_ci[APER], a_kh[APER], a_kw[APER];
     int a_ih0[APER][2], a_iw0[APER][2];                   // top-left source pixel of the filter window
     int a_off0[APER][2];                                  // byte offset of that pixel (may be negative)
     bool a_ok[APER][2];
@@ -164,6 +169,7 @@ perm_lut_kernel(PermArgs a)
     for (int i = 0; i < APER; ++i) {
         const int task = t + i * GT;
         a_np[i] = A_FIXED ? t % NP : task % NP;
+        a_sidx[i] = (a_np[i] / (TN / 2)) * SPL + (a_np[i] % (TN / 2)) * SELW;   // word index of the pair in a selector row
         const int d = A_FIXED ? t / NP + i * (GT / NP) : task / NP;
         a_k0[i] = g * KS + 16 * d;                        // first reduction position of this lane's word
         const uint32_t tap = fdiv((uint32_t)a_k0[i], a.div_cin);
@@ -275,10 +281,10 @@ perm_lut_kernel(PermArgs a)
                     const uint32_t sel4 = (((e ? v[b] >> 4 : v[b])) & am) | om;      // four products per permute
                     const int q = 8 * d + 2 * b + e;
                     if (MODE == 0) {
-                        s_sel[(buf * QS + q) * NP + a_np[i]] = sel4;
+                        s_sel[(buf * QS + q) * SROW + a_sidx[i]] = sel4;
                     } else {
                         // two products per permute: [even position of n0, zero, even position of n1, zero], then odd
-                        uint2 *dst = (uint2 *)(s_sel + ((buf * QS + q) * NP + a_np[i]) * 2);
+                        uint2 *dst = (uint2 *)(s_sel + (buf * QS + q) * SROW + a_sidx[i]);
                         *dst = make_uint2((sel4 & 0x00FF00FFu) | 0x0C000C00u, ((sel4 >> 8) & 0x00FF00FFu) | 0x0C000C00u);
                     }
                 }
@@ -329,11 +335,11 @@ perm_lut_kernel(PermArgs a)
                 uint2 pool[TM];
                 uint32_t sel[TN / 2 * SELW];
                 const uint2 *pq = s_pool + (buf * QS + 8 * d + q) * BM;
-                const uint32_t *sq = s_sel + (buf * QS + 8 * d + q) * NP * SELW;
+                const uint32_t *sq = s_sel + (buf * QS + 8 * d + q) * SROW;
 #pragma unroll
                 for (int i = 0; i < TM; ++i) pool[i] = pq[(i >> 1) * 2 * LM + 2 * ml + (i & 1)];
 #pragma unroll
-                for (int j = 0; j < TN / 2 * SELW; ++j) sel[j] = sq[nl * (TN / 2) * SELW + j];
+                for (int j = 0; j < TN / 2 * SELW; ++j) sel[j] = sq[nl * SPL + j];
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll

@@ -8,7 +8,7 @@ namespace {
 using dgperm::PermArgs;
 
 struct PermPlan {
-    int TM, TN, LM, LN, KS, SK, NBUF, MODE;
+    int TM, TN, LM, LN, KS, SK, NBUF, MODE, OCC;   // OCC: workgroups of this shape that fit one compute unit
     const char *name;
     dg_status (*launch_mfast)(const PermArgs &, dim3, hipStream_t);   // output channel-fastest (NHWC)
     dg_status (*launch_nfast)(const PermArgs &, dim3, hipStream_t);   // output column-fastest ([M][N])
@@ -16,8 +16,8 @@ struct PermPlan {
     int BN() const { return LN * TN; }
 };
 
-#define DG_PLAN(TM, TN, LM, LN, KS, SK, NBUF, MODE)                                                       \
-    {TM, TN, LM, LN, KS, SK, NBUF, MODE,                                                                  \
+#define DG_PLAN(TM, TN, LM, LN, KS, SK, NBUF, MODE, OCC)                                                  \
+    {TM, TN, LM, LN, KS, SK, NBUF, MODE, OCC,                                                             \
      "perm_" #TM "x" #TN "_" #LM "x" #LN "_k" #KS "_s" #SK "_b" #NBUF "_m" #MODE,                         \
      dgperm::perm_launch<TM, TN, LM, LN, KS, SK, NBUF, MODE, true>,                                      \
      dgperm::perm_launch<TM, TN, LM, LN, KS, SK, NBUF, MODE, false>},
@@ -58,18 +58,32 @@ const PermPlan *plan_for(const dg_lut *lut, const DgProblem &p)
     auto tiles = [&](const PermPlan *c) {
         return ((int64_t)(p.M + c->BM() - 1) / c->BM()) * (((int64_t)p.N + c->BN() - 1) / c->BN());
     };
-    // 48-code stages make one fold per stage for the benchmark table (range 9: a fold every 3 words); 64-code
-    // stages divide the 1x1 layers' K = 256
-    const PermPlan *big = find(8, 8, 48, 1, mode), *mid = find(4, 8, 64, 1, mode);
-    if (!big) big = find(8, 8, 32, 1, mode);
-    if (!mid) mid = find(4, 8, 32, 1, mode);
+    // Whole-tile shapes: estimate the time of the busiest compute unit.  It holds ceil(tiles / CUs) workgroups,
+    // OCC at a time; n workgroups sharing a CU issue at rate[n] of its peak (one wave per SIMD cannot hide LDS
+    // latency), and a lane tile with fewer outputs spends more of its instructions outside the permute loop.
+    static const double rate[5] = {0.0, 0.55, 0.84, 0.92, 1.0};
+    const PermPlan *best = nullptr;
+    double best_time = 0.0;
+    for (int i = 0; i < kNumPlans; ++i) {
+        const PermPlan *c = &kPlans[i];
+        if (c->MODE != mode || c->SK != 1) continue;
+        if (c->BM() > 64 && p.M <= 64) continue;                       // half-empty tiles: never better
+        const int64_t per_cu = (tiles(c) + kComputeUnits - 1) / kComputeUnits;
+        const double shape_eff = c->TM * c->TN >= 64 ? 1.0 : (c->TM * c->TN >= 56 ? 0.95 : 0.82);
+        const double work = (double)c->BM() * c->BN() / shape_eff;
+        const int64_t full_rounds = per_cu / c->OCC, rest = per_cu % c->OCC;
+        double time = full_rounds * (c->OCC * work / rate[c->OCC > 4 ? 4 : c->OCC]);
+        if (rest) time += rest * work / rate[rest];
+        // prefer the stage length that divides K among otherwise equal shapes
+        if (p.K % c->KS != 0) time *= 1.0 + (double)(c->KS - p.K % c->KS) / p.K;
+        if (!best || time < best_time) best = c, best_time = time;
+    }
     const PermPlan *one_stage = find(2, 4, 96, 6, mode), *split = find(4, 4, 48, 4, mode);
-    // 128 x 128 tiles when they fill the chip twice over, else 64 x 128, else split K inside the workgroup
-    if (big && p.M > 64 && tiles(big) >= 2 * kComputeUnits) return big;
-    if (mid && tiles(mid) >= kComputeUnits) return mid;
+    // fewer tiles than compute units: split K inside the workgroup instead
+    if (best && tiles(best) >= kComputeUnits) return best;
     if (one_stage && p.K <= one_stage->KS * one_stage->SK) return one_stage;
     if (split) return split;
-    return mid ? mid : big;
+    return best;
 }
 
 // n / d == umulhi(n, mul) >> shift for every 0 <= n < 2^31 (d >= 2): with L = ceil(log2 d) and
