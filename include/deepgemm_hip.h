@@ -90,6 +90,18 @@ dg_status dg_pack_weights(const uint8_t *codes_dev, int64_t M, int64_t K, void *
 dg_status dg_pack_activations(const uint8_t *codes_dev, int64_t N, int64_t K, void *packed_dev,
                               size_t packed_bytes, void *hip_stream);
 
+/*
+ * Fused activation quantise + pack (the two stages that precede the table convolution in Sec. 5.4, with the
+ * quantiser of Sec. 2.1, Eq. 1):
+ *     q = clip(round(scale * x + zero_point), lo, lo + 3),   code = q - lo,   then packed as above.
+ * x_dev: device, fp32 [N][K] (NHWC: N = B*H*W, K = C).  The decision is taken in binary32 exactly as written:
+ * one multiply, one add (never fused), round-half-to-even, then the clip; NaN gives code 0.  lo = -2 for signed
+ * codes, 0 for unsigned ones (any lo is accepted).  Errors and buffer rules as dg_pack_activations.
+ */
+dg_status dg_quantize_pack_activations(const float *x_dev, int64_t N, int64_t K, float scale,
+                                       float zero_point, int32_t lo, void *packed_dev,
+                                       size_t packed_bytes, void *hip_stream);
+
 /* ---- the kernels ------------------------------------------------------------------------------ */
 
 /*

@@ -31,7 +31,7 @@ def build(force: bool = False) -> str:
         if os.path.getmtime(_SO) >= newest:
             return _SO
     cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-ffp-contract=off", "-fPIC",
-           "-shared", "-Wall", "-Wextra", "-o", _SO] + srcs
+           "-shared", "-Wall", "-Wextra", "-o", _SO] + srcs + ["-lm"]
     subprocess.run(cmd, check=True)
     return _SO
 
@@ -54,6 +54,7 @@ def _load():
         lib.dgo_scale_epilogue_nhwc.restype = None
         lib.dgo_scale_epilogue_rows.argtypes = [p, p, i64, i64, p]
         lib.dgo_scale_epilogue_rows.restype = None
+        lib.dgo_quantize_codes.argtypes = [p, i64, ctypes.c_float, ctypes.c_float, ctypes.c_int32, ctypes.c_int32, p]
         lib.dgo_build_lut.argtypes = [p, p, p]
         lib.dgo_build_lut.restype = None
         lib.dgo_pack_codes.argtypes = [p, i64, p]
@@ -191,6 +192,15 @@ def scale_epilogue_rows(acc, scale) -> np.ndarray:
     out = np.zeros(acc.shape, dtype=np.float32)
     _load().dgo_scale_epilogue_rows(_ptr(acc), _ptr(scale), M, N, _ptr(out))
     return out
+
+
+def quantize_codes(x, scale: float, zero_point: float, lo: int, hi: int) -> np.ndarray:
+    """code = clip(rint(float32(scale * x) + zero_point), lo, hi) - lo, decided in float32 (Eq. 1); hi - lo must be 3."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    codes = np.zeros(x.shape, dtype=np.uint8)
+    _check(_load().dgo_quantize_codes(_ptr(x), x.size, float(np.float32(scale)), float(np.float32(zero_point)),
+                                      int(lo), int(hi), _ptr(codes)))
+    return codes
 
 
 # ---- the table method's own steps (dg_lut_reference.c) -----------------------------------

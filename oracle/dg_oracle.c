@@ -263,3 +263,30 @@ void dgo_scale_epilogue_rows(const int32_t *acc, const float *scale,
             out[m * N + n] = f * scale[m];
         }
 }
+
+/*
+ * Uniform quantisation of activations to 2-bit codes (paper Sec. 2.1, Eq. 1):
+ *     x_q = clip(round(s * x + z), lo, hi),        code = x_q - lo   (so that code 0 is the lowest level)
+ * The printed equation has its closing parenthesis misplaced and its value set ends at 2^(b-1); it is read as
+ * clip(round(s*x + z), -2^(b-1), 2^(b-1) - 1) for signed data, and the range [lo, hi] = [lo, lo + 3] is an
+ * argument here so that unsigned (post-ReLU) activations use [0, 3].  The paper does not say how ties round;
+ * round-half-to-even is taken (the IEEE default, rintf).  The decision is taken in binary32, the precision of
+ * the input: t = s * x (one rounding), t + z (one rounding), rintf, compare.  NaN maps to code of `lo`
+ * (every comparison with NaN is false, so it falls through the clip as the lower bound).
+ * Returns 3 for a bad range.
+ */
+#include <math.h>
+int dgo_quantize_codes(const float *x, int64_t count, float s, float z, int32_t lo, int32_t hi,
+                       uint8_t *codes)
+{
+    if (count < 0 || hi - lo != 3) return 3;
+    for (int64_t i = 0; i < count; ++i) {
+        volatile float t = s * x[i];
+        volatile float u = t + z;
+        const float r = rintf(u);
+        int32_t q = lo;
+        if (r > (float)lo) q = r >= (float)hi ? hi : (int32_t)r;
+        codes[i] = (uint8_t)(q - lo);
+    }
+    return 0;
+}

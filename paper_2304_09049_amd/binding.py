@@ -25,6 +25,7 @@ KERNELS = {"auto": DG_KERNEL_AUTO, "perm": DG_KERNEL_PERM, "lds": DG_KERNEL_LDS,
 EXPORTS = (
     "dg_status_string", "dg_last_error", "dg_build_lut", "dg_lut_entries", "dg_lut_destroy",
     "dg_packed_activation_bytes", "dg_packed_weight_bytes", "dg_pack_weights", "dg_pack_activations",
+    "dg_quantize_pack_activations",
     "dg_gemm_lut", "dg_conv_out_dim", "dg_conv2d_lut", "dg_gemm_kernel_name", "dg_conv_kernel_name",
 )
 
@@ -63,6 +64,9 @@ def lib() -> ctypes.CDLL:
     L.dg_packed_weight_bytes.argtypes, L.dg_packed_weight_bytes.restype = [c_i64, c_i64], c_sz
     for f in (L.dg_pack_weights, L.dg_pack_activations):
         f.argtypes, f.restype = [c_vp, c_i64, c_i64, c_vp, c_sz, c_vp], c_int
+    L.dg_quantize_pack_activations.argtypes = [c_vp, c_i64, c_i64, ctypes.c_float, ctypes.c_float, ctypes.c_int32,
+                                               c_vp, c_sz, c_vp]
+    L.dg_quantize_pack_activations.restype = c_int
     L.dg_gemm_lut.argtypes = [c_vp, c_vp, c_vp, c_i64, c_i64, c_i64, c_vp, c_i64, c_i64, c_vp, c_vp, c_int, c_vp]
     L.dg_gemm_lut.restype = c_int
     L.dg_conv_out_dim.argtypes, L.dg_conv_out_dim.restype = [c_i64] * 4, c_i64
@@ -162,6 +166,16 @@ def dg_pack_weights(codes, M: int, K: int, out=None, stream=None):
 def dg_pack_activations(codes, N: int, K: int, out=None, stream=None):
     """codes: uint8 device tensor with N*K elements ([N][K], or NHWC with N = B*H*W, K = C) -> packed uint8 tensor."""
     return _pack(lib().dg_pack_activations, dg_packed_activation_bytes, codes, N, K, out, stream)
+
+
+def dg_quantize_pack_activations(x, N: int, K: int, scale: float, zero_point: float, lo: int, out=None, stream=None):
+    """x: float32 device tensor with N*K elements -> packed 2-bit codes of clip(rint(scale*x + zero_point), lo, lo+3) - lo."""
+    import torch
+    if out is None:
+        out = torch.empty(dg_packed_activation_bytes(N, K), dtype=torch.uint8, device=x.device)
+    _check(lib().dg_quantize_pack_activations(_dev_ptr(x, torch.float32, "x"), N, K, scale, zero_point, lo,
+                                              _dev_ptr(out, torch.uint8, "packed"), out.numel(), _stream_ptr(stream)))
+    return out
 
 
 def dg_gemm_lut(lut: Lut, Wp, Ap, M: int, N: int, K: int, out=None, scale=None, variant="auto",

@@ -128,6 +128,24 @@ dg_status dg_pack_activations(const uint8_t *codes_dev, int64_t N, int64_t K, vo
     return pack_common("dg_pack_activations", codes_dev, N, K, packed_dev, packed_bytes, hip_stream);
 }
 
+dg_status dg_quantize_pack_activations(const float *x_dev, int64_t N, int64_t K, float scale,
+                                       float zero_point, int32_t lo, void *packed_dev,
+                                       size_t packed_bytes, void *hip_stream)
+{
+    const char *name = "dg_quantize_pack_activations";
+    if (!x_dev || !packed_dev) return dg_fail(DG_ERR_NULL, "%s: NULL buffer", name);
+    if (N <= 0 || K <= 0 || K % 4 != 0)
+        return dg_fail(DG_ERR_SHAPE, "%s: N=%lld K=%lld (need N > 0, K > 0, K %% 4 == 0)", name, (long long)N,
+                       (long long)K);
+    if (N > INT32_MAX || K > INT32_MAX) return dg_fail(DG_ERR_SHAPE, "%s: N and K must each fit int32", name);
+    if (lo < -(1 << 24) || lo > (1 << 24)) return dg_fail(DG_ERR_RANGE, "%s: lo=%d is not exact in binary32", name, lo);
+    const size_t need = dg_packed_activation_bytes(N, K);
+    if (packed_bytes < need)
+        return dg_fail(DG_ERR_BUFFER, "%s: packed buffer has %zu bytes, %zu needed", name, packed_bytes, need);
+    return dg_launch_quantize_pack(x_dev, N, K, scale, zero_point, lo, (uint8_t *)packed_dev,
+                                   (hipStream_t)hip_stream);
+}
+
 int64_t dg_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad)
 {
     if (stride <= 0 || k <= 0 || in <= 0 || pad < 0) return 0;

@@ -45,6 +45,8 @@ dg_status dg_check_launch(const char *what);
 // Kernel launchers (each validates nothing: the API layer has done that).
 dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, uint8_t *packed,
                          hipStream_t stream);
+dg_status dg_launch_quantize_pack(const float *x, int64_t rows, int64_t K, float scale, float zero_point,
+                                  int32_t lo, uint8_t *packed, hipStream_t stream);
 dg_status dg_launch_lds(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 bool dg_perm_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_perm(const dg_lut *lut, const DgProblem &p, hipStream_t stream);

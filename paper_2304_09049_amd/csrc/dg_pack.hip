@@ -1,4 +1,5 @@
-// Packing kernel: 2-bit codes, one per byte, to four per byte (Sec. 3.1: packing by shift and OR).
+// Packing kernels: 2-bit codes, one per byte, to four per byte (Sec. 3.1: packing by shift and OR), and the fused
+// quantise + pack of fp32 activations (Sec. 2.1, Eq. 1, then the same packing).
 // Code k of a row lands in byte k/4, bits [2*(k%4)+1 : 2*(k%4)].  Rows are contiguous and K % 4 == 0,
 // so the whole matrix is one flat run of rows*K codes.  HBM-bound: 1 byte read and 1/4 byte written
 // per code; each lane moves 16 codes per 128-bit load and writes one 32-bit word.
@@ -36,7 +37,77 @@ pack_bytes_kernel(const uint8_t *__restrict__ codes, uint8_t *__restrict__ packe
     }
 }
 
+// Eq. 1 of the paper in binary32, operation by operation: multiply, add (not fused), round half to even, clip.
+// NaN fails every comparison and therefore yields code 0.
+__device__ __forceinline__ uint32_t quantize_code(float x, float s, float z, float lo_f, float hi_f, int lo)
+{
+    const float r = rintf(__fadd_rn(__fmul_rn(s, x), z));
+    int q = lo;
+    if (r > lo_f) q = r >= hi_f ? lo + 3 : (int)r;
+    return (uint32_t)(q - lo);
+}
+
+// 16 values per lane: four 128-bit loads, one 32-bit store (4.06 bytes of HBM traffic per code).
+__global__ void __launch_bounds__(256)
+quantize_pack_vec16_kernel(const float4 *__restrict__ x, uint32_t *__restrict__ packed, int64_t groups16, float s,
+                           float z, int lo)
+{
+    const float lo_f = (float)lo, hi_f = (float)(lo + 3);
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups16; g += stride) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float4 v = x[4 * g + j];
+            const uint32_t byte = quantize_code(v.x, s, z, lo_f, hi_f, lo) | (quantize_code(v.y, s, z, lo_f, hi_f, lo) << 2) |
+                                  (quantize_code(v.z, s, z, lo_f, hi_f, lo) << 4) |
+                                  (quantize_code(v.w, s, z, lo_f, hi_f, lo) << 6);
+            word |= byte << (8 * j);
+        }
+        packed[g] = word;
+    }
+}
+
+__global__ void __launch_bounds__(256)
+quantize_pack_bytes_kernel(const float *__restrict__ x, uint8_t *__restrict__ packed, int64_t first_group,
+                           int64_t groups4, float s, float z, int lo)
+{
+    const float lo_f = (float)lo, hi_f = (float)(lo + 3);
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t g = first_group + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups4; g += stride) {
+        const float *v = x + 4 * g;
+        packed[g] = (uint8_t)(quantize_code(v[0], s, z, lo_f, hi_f, lo) | (quantize_code(v[1], s, z, lo_f, hi_f, lo) << 2) |
+                              (quantize_code(v[2], s, z, lo_f, hi_f, lo) << 4) |
+                              (quantize_code(v[3], s, z, lo_f, hi_f, lo) << 6));
+    }
+}
+
 }   // namespace
+
+dg_status dg_launch_quantize_pack(const float *x, int64_t rows, int64_t K, float scale, float zero_point,
+                                  int32_t lo, uint8_t *packed, hipStream_t stream)
+{
+    const int64_t total = rows * K, groups4 = total / 4;
+    int64_t done4 = 0;
+    if ((uintptr_t)x % 16 == 0 && (uintptr_t)packed % 4 == 0 && total >= 16) {
+        const int64_t groups16 = total / 16;
+        int64_t blocks = (groups16 + 255) / 256;
+        if (blocks > 256 * 32) blocks = 256 * 32;
+        hipLaunchKernelGGL(quantize_pack_vec16_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           (const float4 *)x, (uint32_t *)packed, groups16, scale, zero_point, lo);
+        dg_status s = dg_check_launch("quantize_pack_vec16_kernel");
+        if (s != DG_OK) return s;
+        done4 = groups16 * 4;
+    }
+    if (done4 < groups4) {
+        int64_t blocks = (groups4 - done4 + 255) / 256;
+        if (blocks > 256 * 32) blocks = 256 * 32;
+        hipLaunchKernelGGL(quantize_pack_bytes_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, x, packed,
+                           done4, groups4, scale, zero_point, lo);
+        return dg_check_launch("quantize_pack_bytes_kernel");
+    }
+    return DG_OK;
+}
 
 dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, uint8_t *packed, hipStream_t stream)
 {

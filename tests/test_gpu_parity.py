@@ -259,3 +259,39 @@ def test_empty_and_bad_shapes_launch_nothing():
         assert e.value.status == 2
     torch.cuda.synchronize()
     assert bool((out == 9).all())
+
+
+def test_quantize_pack_matches_oracle_quantiser_and_packing():
+    rng = np.random.default_rng(40)
+    cases = [(7, 20, 1.7, 0.3, -2), (196, 576, 0.9, -0.2, 0), (33, 4096, 3.0, 0.5, -2), (1, 4, 1.0, 0.0, 0)]
+    for N, K, s, z, lo in cases:
+        x = rng.normal(0.3, 1.2, size=(N, K)).astype(np.float32)
+        # plant exact ties, huge values and non-finite values
+        flat = x.reshape(-1)
+        specials = np.array([0.5, -0.5, 1.5, 2.5, -1.5, 1e30, -1e30, np.inf, -np.inf, np.nan, 0.0, -0.0], np.float32)
+        flat[: min(flat.size, specials.size)] = specials[: flat.size]
+        got = dg.dg_quantize_pack_activations(torch.from_numpy(x).cuda(), N, K, s, z, lo).cpu().numpy()
+        want = oracle.pack_codes(oracle.quantize_codes(x, s, z, lo, lo + 3))
+        _assert_same(got.reshape(N, K // 4), want, f"quantize+pack {N}x{K}")
+    # an unaligned source pointer takes the byte path
+    x = rng.normal(0, 1, size=(9, 52)).astype(np.float32)
+    base = torch.zeros(9 * 52 + 1, dtype=torch.float32, device="cuda")
+    base[1:].copy_(torch.from_numpy(x.reshape(-1)))
+    got = dg.dg_quantize_pack_activations(base[1:], 9, 52, 2.0, 0.5, -2).cpu().numpy()
+    _assert_same(got.reshape(9, 13), oracle.pack_codes(oracle.quantize_codes(x, 2.0, 0.5, -2, 1)), "unaligned quantize")
+
+
+def test_quantize_pack_feeds_the_convolution():
+    # fp32 NHWC input -> quantise+pack -> table convolution, against oracle quantiser -> oracle convolution
+    rng = np.random.default_rng(41)
+    B, H, W, Cin, Cout = 2, 12, 12, 64, 32
+    x = np.abs(rng.normal(0, 1.0, size=(B, H, W, Cin))).astype(np.float32)
+    c = wl.small_conv(B, H, W, Cin, Cout, 3, 3, (1, 1), (1, 1), seed=42)
+    codes = oracle.quantize_codes(x, 1.5, 0.0, 0, 3)
+    want = oracle.conv2d(c.Wc, codes, c.levels_w, c.levels_a, pad=(1, 1))
+    lut = dg.dg_build_lut(c.levels_w, c.levels_a)
+    Wp = dg.dg_pack_weights(torch.from_numpy(c.Wc).cuda(), Cout, 9 * Cin)
+    Xp = dg.dg_quantize_pack_activations(torch.from_numpy(x).cuda(), B * H * W, Cin, 1.5, 0.0, 0)
+    y = dg.dg_conv2d_lut(lut, Wp, Xp, dg.conv_desc(B, H, W, Cin, Cout, 3, 3, (1, 1), (1, 1)))
+    torch.cuda.synchronize()
+    _assert_same(y.cpu().numpy(), want, "quantize -> conv")

@@ -337,3 +337,43 @@ def test_oracle_rejects_bad_codes_and_overflow():
     big = np.array([2 ** 15, 0, 0, 0], dtype=np.int32)
     with pytest.raises(oracle.OracleError):
         oracle.gemm(np.zeros((1, 8), np.uint8), np.zeros((1, 8), np.uint8), big, big)
+
+
+# ---- activation quantiser (Eq. 1) ------------------------------------------------------------
+
+def test_quantizer_hand_values():
+    # s = 2, z = 0.5, signed range [-2, 1]: t = 2x + 0.5, ties go to the even integer
+    x = np.array([-10.0, -1.3, -1.25, -1.0, -0.75, -0.5, -0.25, 0.0, 0.2, 0.25, 0.5, 0.75, 3.0], dtype=np.float32)
+    #   2x+.5 =   -19.5  -2.1  -2.0  -1.5  -1.0  -0.5   0.0  0.5  0.9   1.0  1.5   2.0  6.5
+    #   rint  =   -20    -2    -2    -2    -1    -0     0    0    1     1    2     2    6
+    #   clip  =   -2     -2    -2    -2    -1     0     0    0    1     1    1     1    1
+    want = np.array([0, 0, 0, 0, 1, 2, 2, 2, 3, 3, 3, 3, 3], dtype=np.uint8)
+    assert oracle.quantize_codes(x, 2.0, 0.5, -2, 1).tolist() == want.tolist()
+    # unsigned range [0, 3], s = 1, z = 0: rint(0.5) = 0, rint(1.5) = 2, rint(2.5) = 2
+    x = np.array([-1.0, 0.0, 0.49, 0.5, 0.51, 1.5, 2.5, 2.51, 3.4, 3.5, 100.0], dtype=np.float32)
+    want = np.array([0, 0, 0, 0, 1, 2, 2, 3, 3, 3, 3], dtype=np.uint8)
+    assert oracle.quantize_codes(x, 1.0, 0.0, 0, 3).tolist() == want.tolist()
+
+
+def test_quantizer_matches_numpy_float32_pipeline():
+    rng = np.random.default_rng(7)
+    x = rng.normal(0, 1.5, size=20000).astype(np.float32)
+    for s, z, lo in ((1.7, 0.3, -2), (0.9, -0.2, 0), (3.0, 0.5, -2)):
+        t = (np.float32(s) * x).astype(np.float32) + np.float32(z)          # two float32 roundings, no FMA
+        want = (np.clip(np.rint(t), lo, lo + 3) - lo).astype(np.uint8)
+        assert np.array_equal(oracle.quantize_codes(x, s, z, lo, lo + 3), want)
+
+
+def test_quantizer_special_values_and_range_check():
+    x = np.array([np.nan, np.inf, -np.inf, 1e30, -1e30], dtype=np.float32)
+    assert oracle.quantize_codes(x, 1.0, 0.0, -2, 1).tolist() == [0, 3, 0, 3, 0]
+    with pytest.raises(oracle.OracleError):
+        oracle.quantize_codes(x, 1.0, 0.0, 0, 4)
+
+
+def test_quantize_then_levels_recovers_a_uniform_grid():
+    # a value that already sits on the grid x = (q - z) / s quantises to q: the inverse of Eq. 1 on its range
+    s, z = 4.0, 1.0
+    q = np.arange(-2, 2)
+    x = ((q - z) / s).astype(np.float32)
+    assert oracle.quantize_codes(x, s, z, -2, 1).tolist() == [0, 1, 2, 3]
