@@ -69,6 +69,12 @@ __device__ __forceinline__ int32_t fold_bytes(uint32_t v, uint32_t ones, int32_t
     return (int32_t)__builtin_amdgcn_udot4(v, ones, (uint32_t)acc, false);
 }
 
+// Waves per SIMD the compiler is asked to leave room for (it sizes its register budget to this).  Measured: the
+// 16-bit-lane 8x8 tile gains from three waves per SIMD; every other shape is fastest with the compiler's own choice.
+#ifndef DG_PERM_MIN_WAVES
+#define DG_PERM_MIN_WAVES(TM, TN, SK, MODE) (((SK) == 1 && (MODE) == 1 && (TM) * (TN) == 64) ? 3 : 1)
+#endif
+
 template <int TM, int TN, int LM, int LN, int KS, int SK, int NBUF, int MODE>
 struct PermShape {
     static constexpr int GT = LM * LN;         // lanes of one K-split group
@@ -91,7 +97,7 @@ struct PermShape {
 // NBUF = 2 overlaps the expansion of the next stage with the permutes of the current one, NBUF = 1 halves the
 // LDS footprint (meant for shapes where every group has a single, long stage).
 template <int TM, int TN, int LM, int LN, int KS, int SK, int NBUF, int MODE, bool MFAST>
-__global__ void __launch_bounds__(LM *LN *SK)
+__global__ void __launch_bounds__(LM *LN *SK, DG_PERM_MIN_WAVES(TM, TN, SK, MODE))
 perm_lut_kernel(PermArgs a)
 {
     using S = PermShape<TM, TN, LM, LN, KS, SK, NBUF, MODE>;
