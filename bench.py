@@ -309,8 +309,8 @@ def main():
         sweep = []
         for wname, ww in wl.CONFIGS.items():
             rr = r if ww is w else Runner(ww, "auto")
-            for variant in ("auto", "mfma_i8", "lds"):
-                if variant == "lds" and ww.ops > 1e11:
+            for variant in ("auto", "mfma_i8", "lut65k", "lds"):
+                if variant in ("lds", "lut65k") and ww.ops > 1e11:
                     continue
                 try:
                     kname = rr.kernel_name(variant)

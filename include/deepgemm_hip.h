@@ -112,6 +112,8 @@ dg_status dg_quantize_pack_activations(const float *x_dev, int64_t N, int64_t K,
  *   MFMA_I8  NOT a table kernel: decodes codes to int8 levels and multiplies on the matrix cores;
  *            kept only as the measured comparison
  *   SMALLN   table kernel for few activation rows: K split across lanes + wavefront reduction
+ *   LUT65K   the paper's second table (Sec. 3 "LUT-65k"): one entry per (weight byte, activation byte) holding
+ *            the dot product of the four code pairs, kept in LDS; one fetch per four products
  * A variant that cannot run the given shape or table returns DG_ERR_UNSUPPORTED.
  */
 typedef enum {
@@ -119,7 +121,8 @@ typedef enum {
     DG_KERNEL_PERM = 1,
     DG_KERNEL_LDS = 2,
     DG_KERNEL_MFMA_I8 = 3,
-    DG_KERNEL_SMALLN = 4
+    DG_KERNEL_SMALLN = 4,
+    DG_KERNEL_LUT65K = 5
 } dg_kernel;
 
 /*

@@ -17,9 +17,9 @@ DG_OK = 0
 STATUS_NAMES = ("DG_OK", "DG_ERR_NULL", "DG_ERR_SHAPE", "DG_ERR_RANGE", "DG_ERR_BUFFER",
                 "DG_ERR_UNSUPPORTED", "DG_ERR_HIP")
 DG_LUT_I8, DG_LUT_I16 = 0, 1
-DG_KERNEL_AUTO, DG_KERNEL_PERM, DG_KERNEL_LDS, DG_KERNEL_MFMA_I8, DG_KERNEL_SMALLN = 0, 1, 2, 3, 4
+DG_KERNEL_AUTO, DG_KERNEL_PERM, DG_KERNEL_LDS, DG_KERNEL_MFMA_I8, DG_KERNEL_SMALLN, DG_KERNEL_LUT65K = 0, 1, 2, 3, 4, 5
 KERNELS = {"auto": DG_KERNEL_AUTO, "perm": DG_KERNEL_PERM, "lds": DG_KERNEL_LDS,
-           "mfma_i8": DG_KERNEL_MFMA_I8, "smalln": DG_KERNEL_SMALLN}
+           "mfma_i8": DG_KERNEL_MFMA_I8, "smalln": DG_KERNEL_SMALLN, "lut65k": DG_KERNEL_LUT65K}
 
 # every symbol include/deepgemm_hip.h declares
 EXPORTS = (

@@ -158,7 +158,7 @@ int64_t dg_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad)
 
 namespace {
 
-enum class Pick { Perm, Lds, Mfma, SmallN, Unsupported };
+enum class Pick { Perm, Lds, Mfma, SmallN, Lut65k, Unsupported };
 
 Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
 {
@@ -167,6 +167,7 @@ Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case DG_KERNEL_LDS: return Pick::Lds;
     case DG_KERNEL_MFMA_I8: return dg_mfma_supports(lut, p) ? Pick::Mfma : Pick::Unsupported;
     case DG_KERNEL_SMALLN: return dg_smalln_supports(lut, p) ? Pick::SmallN : Pick::Unsupported;
+    case DG_KERNEL_LUT65K: return dg_lut65k_supports(lut, p) ? Pick::Lut65k : Pick::Unsupported;
     case DG_KERNEL_AUTO:
         // AUTO stays within the table kernels: the matrix-core kernel is a comparison only.
         if (p.N <= 32 && p.K >= 1024 && dg_smalln_supports(lut, p)) return Pick::SmallN;
@@ -183,6 +184,7 @@ dg_status run(const dg_lut *lut, const DgProblem &p, dg_kernel variant, hipStrea
     case Pick::Lds: return dg_launch_lds(lut, p, stream);
     case Pick::Mfma: return dg_launch_mfma(lut, p, stream);
     case Pick::SmallN: return dg_launch_smalln(lut, p, stream);
+    case Pick::Lut65k: return dg_launch_lut65k(lut, p, stream);
     case Pick::Unsupported: break;
     }
     return dg_fail(DG_ERR_UNSUPPORTED,
@@ -197,6 +199,7 @@ const char *pick_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case Pick::Lds: return "lds";
     case Pick::Mfma: return "mfma_i8";
     case Pick::SmallN: return "smalln";
+    case Pick::Lut65k: return "lut65k";
     case Pick::Unsupported: break;
     }
     return "unsupported";

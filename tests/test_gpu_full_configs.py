@@ -10,7 +10,7 @@ from gpu_helpers import GpuCase, run_or_unsupported
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = ["auto", "perm", "lds", "mfma_i8", "smalln"]
+VARIANTS = ["auto", "perm", "lds", "mfma_i8", "smalln", "lut65k"]
 FULL = ["gemm_64x196x576", "resnet18_conv3x3_b1", "resnet50_conv1x1_b32", "gemm_8192x1x8192_i16",
         "gemm_8192x16x8192_i16"]
 SAMPLED = ["vgg16_conv3x3_b16", "gemm_8192x256x8192_i16", "gemm_8192x8192x8192_i16"]
@@ -70,8 +70,8 @@ def test_sampled_output(name):
         want = oracle.gemm_sampled(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a, ms, ns)
     ran = []
     for variant in VARIANTS:
-        if variant == "lds" and w.ops > 2e11:
-            continue                               # the plain kernel would take too long at this size
+        if variant in ("lds", "lut65k") and w.ops > 2e11:
+            continue                               # the plain kernels would take too long at this size
         got = run_or_unsupported(case, variant)
         if got is None:
             continue
