@@ -6,8 +6,9 @@ bytes).  Only tests, the smoke check and the benchmark's CPU-baseline leg may
 import this package; the GPU library never does, and this package never imports
 the GPU library.
 
-Every function takes and returns numpy arrays.  Codes are ``uint8`` in
-``{0,1,2,3}``, one per element; levels are four integers per side.
+Every function takes and returns numpy arrays.  Codes are ``uint8``, one per
+element; levels are 4 integers per side (2-bit codes, the paper's kernels) or 8 /
+16 (the 3- and 4-bit extension of Sec. 3.3).
 """
 from __future__ import annotations
 
@@ -44,23 +45,23 @@ def _load():
         i64, p = ctypes.c_int64, ctypes.c_void_p
         lib.dgo_max_threads.restype = ctypes.c_int
         lib.dgo_set_threads.argtypes = [ctypes.c_int]
-        lib.dgo_gemm.argtypes = [p, p, p, p, i64, i64, i64, p]
-        lib.dgo_gemm_sampled.argtypes = [p, p, p, p, i64, i64, i64, p, p, i64, p]
+        lib.dgo_gemm.argtypes = [p, p, p, p, ctypes.c_int, i64, i64, i64, p]
+        lib.dgo_gemm_sampled.argtypes = [p, p, p, p, ctypes.c_int, i64, i64, i64, p, p, i64, p]
         lib.dgo_conv_out_dim.argtypes = [i64] * 4
         lib.dgo_conv_out_dim.restype = i64
-        lib.dgo_conv2d.argtypes = [p, p, p, p] + [i64] * 11 + [p]
-        lib.dgo_conv2d_sampled.argtypes = [p, p, p, p] + [i64] * 11 + [p, i64, p]
+        lib.dgo_conv2d.argtypes = [p, p, p, p, ctypes.c_int] + [i64] * 11 + [p]
+        lib.dgo_conv2d_sampled.argtypes = [p, p, p, p, ctypes.c_int] + [i64] * 11 + [p, i64, p]
         lib.dgo_scale_epilogue_nhwc.argtypes = [p, p, i64, i64, p]
         lib.dgo_scale_epilogue_nhwc.restype = None
         lib.dgo_scale_epilogue_rows.argtypes = [p, p, i64, i64, p]
         lib.dgo_scale_epilogue_rows.restype = None
         lib.dgo_quantize_codes.argtypes = [p, i64, ctypes.c_float, ctypes.c_float, ctypes.c_int32, ctypes.c_int32, p]
-        lib.dgo_build_lut.argtypes = [p, p, p]
+        lib.dgo_build_lut.argtypes = [p, p, ctypes.c_int, p]
         lib.dgo_build_lut.restype = None
-        lib.dgo_pack_codes.argtypes = [p, i64, p]
-        lib.dgo_unpack_codes.argtypes = [p, i64, p]
+        lib.dgo_pack_codes.argtypes = [p, i64, ctypes.c_int, p]
+        lib.dgo_unpack_codes.argtypes = [p, i64, ctypes.c_int, p]
         lib.dgo_unpack_codes.restype = None
-        lib.dgo_lut_gemm_packed.argtypes = [p, p, p, i64, i64, i64, p]
+        lib.dgo_lut_gemm_packed.argtypes = [p, p, p, ctypes.c_int, i64, i64, i64, p]
         _lib = lib
     return _lib
 
@@ -90,9 +91,16 @@ def _codes(a, shape=None) -> np.ndarray:
 
 def _levels(v) -> np.ndarray:
     v = np.ascontiguousarray(v, dtype=np.int32)
-    if v.shape != (4,):
-        raise OracleError("a level table has exactly 4 entries")
+    if v.ndim != 1 or v.shape[0] not in (4, 8, 16):
+        raise OracleError("a level table has 4, 8 or 16 entries (2-, 3- or 4-bit codes)")
     return v
+
+
+def _both(levels_w, levels_a):
+    lw, la = _levels(levels_w), _levels(levels_a)
+    if lw.shape != la.shape:
+        raise OracleError("both sides use the same code width")
+    return lw, la, int(lw.shape[0])
 
 
 def max_threads() -> int:
@@ -111,8 +119,8 @@ def gemm(Wc, Ac, levels_w, levels_a) -> np.ndarray:
     if K != K2:
         raise OracleError("reduction lengths differ")
     C = np.zeros((M, N), dtype=np.int32)
-    lw, la = _levels(levels_w), _levels(levels_a)
-    _check(_load().dgo_gemm(_ptr(Wc), _ptr(Ac), _ptr(lw), _ptr(la), M, N, K, _ptr(C)))
+    lw, la, nlev = _both(levels_w, levels_a)
+    _check(_load().dgo_gemm(_ptr(Wc), _ptr(Ac), _ptr(lw), _ptr(la), nlev, M, N, K, _ptr(C)))
     return C
 
 
@@ -126,8 +134,8 @@ def gemm_sampled(Wc, Ac, levels_w, levels_a, ms, ns) -> np.ndarray:
     ms = np.ascontiguousarray(ms, dtype=np.int64)
     ns = np.ascontiguousarray(ns, dtype=np.int64)
     out = np.zeros(ms.shape[0], dtype=np.int32)
-    lw, la = _levels(levels_w), _levels(levels_a)
-    _check(_load().dgo_gemm_sampled(_ptr(Wc), _ptr(Ac), _ptr(lw), _ptr(la), M, N, K,
+    lw, la, nlev = _both(levels_w, levels_a)
+    _check(_load().dgo_gemm_sampled(_ptr(Wc), _ptr(Ac), _ptr(lw), _ptr(la), nlev, M, N, K,
                                     _ptr(ms), _ptr(ns), ms.shape[0], _ptr(out)))
     return out
 
@@ -147,8 +155,8 @@ def conv2d(Wc, Xc, levels_w, levels_a, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
     ph, pw = pad
     OH, OW = conv_out_dim(H, KH, sh, ph), conv_out_dim(W, KW, sw, pw)
     Y = np.zeros((B, max(OH, 0), max(OW, 0), Cout), dtype=np.int32)
-    lw, la = _levels(levels_w), _levels(levels_a)
-    _check(_load().dgo_conv2d(_ptr(Wc), _ptr(Xc), _ptr(lw), _ptr(la), B, H, W, Cin, Cout,
+    lw, la, nlev = _both(levels_w, levels_a)
+    _check(_load().dgo_conv2d(_ptr(Wc), _ptr(Xc), _ptr(lw), _ptr(la), nlev, B, H, W, Cin, Cout,
                               KH, KW, sh, sw, ph, pw, _ptr(Y)))
     return Y
 
@@ -164,8 +172,8 @@ def conv2d_sampled(Wc, Xc, levels_w, levels_a, positions, stride=(1, 1), pad=(0,
     ph, pw = pad
     pos = np.ascontiguousarray(positions, dtype=np.int64)
     out = np.zeros(pos.shape[0], dtype=np.int32)
-    lw, la = _levels(levels_w), _levels(levels_a)
-    _check(_load().dgo_conv2d_sampled(_ptr(Wc), _ptr(Xc), _ptr(lw), _ptr(la), B, H, W, Cin, Cout,
+    lw, la, nlev = _both(levels_w, levels_a)
+    _check(_load().dgo_conv2d_sampled(_ptr(Wc), _ptr(Xc), _ptr(lw), _ptr(la), nlev, B, H, W, Cin, Cout,
                                       KH, KW, sh, sw, ph, pw, _ptr(pos), pos.shape[0], _ptr(out)))
     return out
 
@@ -206,38 +214,45 @@ def quantize_codes(x, scale: float, zero_point: float, lo: int, hi: int) -> np.n
 # ---- the table method's own steps (dg_lut_reference.c) -----------------------------------
 
 def build_lut(levels_w, levels_a) -> np.ndarray:
-    """table[4*w + a] = lw[w] * la[a]  (int32[16])."""
-    lw, la = _levels(levels_w), _levels(levels_a)
-    table = np.zeros(16, dtype=np.int32)
-    _load().dgo_build_lut(_ptr(lw), _ptr(la), _ptr(table))
+    """table[nlev*w + a] = lw[w] * la[a]  (int32, nlev*nlev entries: 16 for 2-bit codes, 64, 256)."""
+    lw, la, nlev = _both(levels_w, levels_a)
+    table = np.zeros(nlev * nlev, dtype=np.int32)
+    _load().dgo_build_lut(_ptr(lw), _ptr(la), nlev, _ptr(table))
     return table
 
 
-def pack_codes(codes) -> np.ndarray:
-    """Pack along the last axis, four codes per byte, code k at bits 2*(k%4) of byte k//4."""
+def codes_per_byte(bits: int) -> int:
+    return 4 if bits == 2 else 2
+
+
+def pack_codes(codes, bits: int = 2) -> np.ndarray:
+    """Pack along the last axis: 2-bit codes four per byte (code k at bits 2*(k%4) of byte k//4); 3- and 4-bit
+    codes two per byte in 4-bit slots (code k at bits 4*(k%2) of byte k//2)."""
     codes = _codes(codes)
-    if codes.shape[-1] % 4 != 0:
-        raise OracleError("the packed axis must be a multiple of 4")
-    packed = np.zeros(codes.shape[:-1] + (codes.shape[-1] // 4,), dtype=np.uint8)
-    _check(_load().dgo_pack_codes(_ptr(codes), codes.size, _ptr(packed)))
+    per = codes_per_byte(bits)
+    if codes.shape[-1] % per != 0:
+        raise OracleError(f"the packed axis must be a multiple of {per}")
+    packed = np.zeros(codes.shape[:-1] + (codes.shape[-1] // per,), dtype=np.uint8)
+    _check(_load().dgo_pack_codes(_ptr(codes), codes.size, bits, _ptr(packed)))
     return packed
 
 
-def unpack_codes(packed) -> np.ndarray:
+def unpack_codes(packed, bits: int = 2) -> np.ndarray:
     packed = np.ascontiguousarray(packed, dtype=np.uint8)
-    codes = np.zeros(packed.shape[:-1] + (packed.shape[-1] * 4,), dtype=np.uint8)
-    _load().dgo_unpack_codes(_ptr(packed), codes.size, _ptr(codes))
+    codes = np.zeros(packed.shape[:-1] + (packed.shape[-1] * codes_per_byte(bits),), dtype=np.uint8)
+    _load().dgo_unpack_codes(_ptr(packed), codes.size, bits, _ptr(codes))
     return codes
 
 
-def lut_gemm_packed(Wp, Ap, table, K: int) -> np.ndarray:
+def lut_gemm_packed(Wp, Ap, table, K: int, bits: int = 2) -> np.ndarray:
     """GEMM by table lookup on packed operands (Algorithm 1, one byte at a time)."""
     Wp = np.ascontiguousarray(Wp, dtype=np.uint8)
     Ap = np.ascontiguousarray(Ap, dtype=np.uint8)
     table = np.ascontiguousarray(table, dtype=np.int32)
     M, N = Wp.shape[0], Ap.shape[0]
-    if Wp.shape[1] * 4 != K or Ap.shape[1] * 4 != K or table.shape != (16,):
+    per = codes_per_byte(bits)
+    if Wp.shape[1] * per != K or Ap.shape[1] * per != K or table.shape != (1 << (2 * bits),):
         raise OracleError("bad packed shapes")
     C = np.zeros((M, N), dtype=np.int32)
-    _check(_load().dgo_lut_gemm_packed(_ptr(Wp), _ptr(Ap), _ptr(table), M, N, K, _ptr(C)))
+    _check(_load().dgo_lut_gemm_packed(_ptr(Wp), _ptr(Ap), _ptr(table), bits, M, N, K, _ptr(C)))
     return C

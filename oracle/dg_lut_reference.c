@@ -19,40 +19,51 @@
  *
  * Packed layout used here: code k of a row sits in byte k/4, bits
  * [2*(k%4)+1 : 2*(k%4)].  Nothing here is shared with the HIP library.
+ *
+ * Sec. 3.3 / Table 2 describe (without implementing) the same scheme for 3- and
+ * 4-bit codes: index = b + b bits, 2^(2b) entries.  For those widths the functions
+ * below take `bits`; a byte then holds TWO codes, each in a 4-bit slot (code k in
+ * byte k/2, bits [4*(k%2)+bits-1 : 4*(k%2)]) -- the paper does not give a layout for
+ * them, this is this build's reading.  The index is w * 2^bits + a.
  */
 #include <stdint.h>
 
-/* table[4*w + a] = lw[w] * la[a] */
-void dgo_build_lut(const int32_t lw[4], const int32_t la[4], int32_t table[16])
+/* table[nlev*w + a] = lw[w] * la[a], nlev = 2^bits levels per side (16 entries for 2 bits, 64, 256) */
+void dgo_build_lut(const int32_t *lw, const int32_t *la, int nlev, int32_t *table)
 {
-    for (int w = 0; w < 4; ++w)
-        for (int a = 0; a < 4; ++a)
-            table[4 * w + a] = lw[w] * la[a];
+    for (int w = 0; w < nlev; ++w)
+        for (int a = 0; a < nlev; ++a)
+            table[nlev * w + a] = lw[w] * la[a];
 }
 
-/* Pack `count` codes (count % 4 == 0), four per byte, by shift and OR. */
-int dgo_pack_codes(const uint8_t *codes, int64_t count, uint8_t *packed)
+static int slot_bits(int bits) { return bits == 2 ? 2 : 4; }
+
+/* Pack `count` codes of `bits` bits, 8/slot_bits per byte, by shift and OR. */
+int dgo_pack_codes(const uint8_t *codes, int64_t count, int bits, uint8_t *packed)
 {
-    if (count < 0 || count % 4 != 0) return 3;
-    for (int64_t j = 0; j < count / 4; ++j) {
+    if (bits < 2 || bits > 4) return 3;
+    const int sb = slot_bits(bits), per = 8 / sb;
+    if (count < 0 || count % per != 0) return 3;
+    for (int64_t j = 0; j < count / per; ++j) {
         uint8_t byte = 0;
-        for (int i = 0; i < 4; ++i) {
-            uint8_t c = codes[4 * j + i];
-            if (c > 3) return 1;
-            byte = (uint8_t)(byte | (c << (2 * i)));
+        for (int i = 0; i < per; ++i) {
+            uint8_t c = codes[per * j + i];
+            if (c >= (1 << bits)) return 1;
+            byte = (uint8_t)(byte | (c << (sb * i)));
         }
         packed[j] = byte;
     }
     return 0;
 }
 
-/* Inverse of dgo_pack_codes: mask each 2-bit field out again. */
-void dgo_unpack_codes(const uint8_t *packed, int64_t count, uint8_t *codes)
+/* Inverse of dgo_pack_codes: mask each field out again. */
+void dgo_unpack_codes(const uint8_t *packed, int64_t count, int bits, uint8_t *codes)
 {
-    const uint8_t mask = 3;
-    for (int64_t j = 0; j < count / 4; ++j)
-        for (int i = 0; i < 4; ++i)
-            codes[4 * j + i] = (uint8_t)((packed[j] >> (2 * i)) & mask);
+    const int sb = slot_bits(bits), per = 8 / sb;
+    const uint8_t mask = (uint8_t)((1 << bits) - 1);
+    for (int64_t j = 0; j < count / per; ++j)
+        for (int i = 0; i < per; ++i)
+            codes[per * j + i] = (uint8_t)((packed[j] >> (sb * i)) & mask);
 }
 
 /*
@@ -60,21 +71,23 @@ void dgo_unpack_codes(const uint8_t *packed, int64_t count, uint8_t *codes)
  * C is [M][N].  The inner loop is Algorithm 1 on one byte at a time.
  */
 int dgo_lut_gemm_packed(const uint8_t *Wp, const uint8_t *Ap,
-                        const int32_t table[16],
+                        const int32_t *table, int bits,
                         int64_t M, int64_t N, int64_t K, int32_t *C)
 {
-    if (M < 0 || N < 0 || K < 0 || K % 4 != 0) return 3;
-    const int64_t KB = K / 4;
-    const uint8_t mask = 3;
+    if (bits < 2 || bits > 4) return 3;
+    const int sb = slot_bits(bits), per = 8 / sb;
+    if (M < 0 || N < 0 || K < 0 || K % per != 0) return 3;
+    const int64_t KB = K / per;
+    const uint8_t mask = (uint8_t)((1 << bits) - 1);
     for (int64_t m = 0; m < M; ++m)
         for (int64_t n = 0; n < N; ++n) {
             int64_t sum = 0;
             for (int64_t j = 0; j < KB; ++j) {
                 const uint8_t vec_w = Wp[m * KB + j];
                 const uint8_t vec_a = Ap[n * KB + j];
-                for (int i = 0; i < 4; ++i) {
-                    const int shift = i * 2;
-                    const int indx = (((vec_w >> shift) & mask) << 2) |
+                for (int i = 0; i < per; ++i) {
+                    const int shift = i * sb;
+                    const int indx = (((vec_w >> shift) & mask) << bits) |
                                      ((vec_a >> shift) & mask);
                     sum += table[indx];
                 }

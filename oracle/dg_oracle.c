@@ -23,10 +23,12 @@
  *   EPI  : Yf = (float)Y * scale[co]   (Sec. 5.4: dequantisation is a separate,
  *          cheap stage; one binary32 multiply, no fused multiply-add).
  *
- * Inputs are UNPACKED codes, one uint8 in {0,1,2,3} per code, plus the two
- * 4-entry level tables.  Sums are taken in int64 and narrowed with a check.
+ * Inputs are UNPACKED codes, one uint8 per code, plus the two level tables of
+ * `nlev` entries each: nlev = 4 for the paper's 2-bit kernels, 8 or 16 for the
+ * 3- and 4-bit extension it describes (Sec. 3.3, Table 2).  Sums are taken in
+ * int64 and narrowed with a check.
  *
- * Return codes: 0 ok, 1 a code was > 3, 2 a sum does not fit int32,
+ * Return codes: 0 ok, 1 a code was >= nlev, 2 a sum does not fit int32,
  *               3 bad shape.
  *
  * OpenMP is used on the outermost output loop only; it changes no sum.
@@ -57,11 +59,11 @@ void dgo_set_threads(int n)
 
 /* One dot product over K codes on decoded levels.  Returns 1 on a bad code. */
 static int dot_levels(const uint8_t *w, const uint8_t *a, int64_t K,
-                      const int32_t lw[4], const int32_t la[4], int64_t *out)
+                      const int32_t *lw, const int32_t *la, int nlev, int64_t *out)
 {
     int64_t s = 0;
     for (int64_t k = 0; k < K; ++k) {
-        if (w[k] > 3 || a[k] > 3) return 1;
+        if (w[k] >= nlev || a[k] >= nlev) return 1;
         s += (int64_t)lw[w[k]] * (int64_t)la[a[k]];
     }
     *out = s;
@@ -70,16 +72,16 @@ static int dot_levels(const uint8_t *w, const uint8_t *a, int64_t K,
 
 /* GEMM.  Wc is [M][K], Ac is [N][K], C is [M][N] row-major. */
 int dgo_gemm(const uint8_t *Wc, const uint8_t *Ac,
-             const int32_t lw[4], const int32_t la[4],
+             const int32_t *lw, const int32_t *la, int nlev,
              int64_t M, int64_t N, int64_t K, int32_t *C)
 {
-    if (M < 0 || N < 0 || K < 0) return 3;
+    if (M < 0 || N < 0 || K < 0 || nlev < 1 || nlev > 16) return 3;
     int err = 0;
 #pragma omp parallel for schedule(static) reduction(max : err)
     for (int64_t m = 0; m < M; ++m) {
         for (int64_t n = 0; n < N; ++n) {
             int64_t s;
-            if (dot_levels(Wc + m * K, Ac + n * K, K, lw, la, &s)) {
+            if (dot_levels(Wc + m * K, Ac + n * K, K, lw, la, nlev, &s)) {
                 if (err < 1) err = 1;
                 continue;
             }
@@ -95,12 +97,12 @@ int dgo_gemm(const uint8_t *Wc, const uint8_t *Ac,
 
 /* GEMM at a list of sampled output positions: out[i] = C[ms[i]][ns[i]]. */
 int dgo_gemm_sampled(const uint8_t *Wc, const uint8_t *Ac,
-                     const int32_t lw[4], const int32_t la[4],
+                     const int32_t *lw, const int32_t *la, int nlev,
                      int64_t M, int64_t N, int64_t K,
                      const int64_t *ms, const int64_t *ns, int64_t count,
                      int32_t *out)
 {
-    if (M < 0 || N < 0 || K < 0 || count < 0) return 3;
+    if (M < 0 || N < 0 || K < 0 || count < 0 || nlev < 1 || nlev > 16) return 3;
     int err = 0;
 #pragma omp parallel for schedule(static) reduction(max : err)
     for (int64_t i = 0; i < count; ++i) {
@@ -109,7 +111,7 @@ int dgo_gemm_sampled(const uint8_t *Wc, const uint8_t *Ac,
             if (err < 3) err = 3;
             continue;
         }
-        if (dot_levels(Wc + m * K, Ac + n * K, K, lw, la, &s)) {
+        if (dot_levels(Wc + m * K, Ac + n * K, K, lw, la, nlev, &s)) {
             if (err < 1) err = 1;
             continue;
         }
@@ -133,7 +135,7 @@ int64_t dgo_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad)
 
 /* One output element of the direct convolution. */
 static int conv_point(const uint8_t *Wc, const uint8_t *Xc,
-                      const int32_t lw[4], const int32_t la[4],
+                      const int32_t *lw, const int32_t *la, int nlev,
                       int64_t H, int64_t W, int64_t Cin,
                       int64_t KH, int64_t KW,
                       int64_t sh, int64_t sw, int64_t ph, int64_t pw,
@@ -150,7 +152,7 @@ static int conv_point(const uint8_t *Wc, const uint8_t *Xc,
             const uint8_t *x = Xc + ((b * H + ih) * W + iw) * Cin;
             const uint8_t *w = Wc + ((co * KH + kh) * KW + kw) * Cin;
             for (int64_t ci = 0; ci < Cin; ++ci) {
-                if (w[ci] > 3 || x[ci] > 3) return 1;
+                if (w[ci] >= nlev || x[ci] >= nlev) return 1;
                 s += (int64_t)lw[w[ci]] * (int64_t)la[x[ci]];
             }
         }
@@ -164,13 +166,13 @@ static int conv_point(const uint8_t *Wc, const uint8_t *Xc,
  * Y is [B][OH][OW][Cout].  Dilation 1, groups 1.
  */
 int dgo_conv2d(const uint8_t *Wc, const uint8_t *Xc,
-               const int32_t lw[4], const int32_t la[4],
+               const int32_t *lw, const int32_t *la, int nlev,
                int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
                int64_t KH, int64_t KW, int64_t sh, int64_t sw,
                int64_t ph, int64_t pw, int32_t *Y)
 {
     if (B < 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 ||
-        KW <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0)
+        KW <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0 || nlev < 1 || nlev > 16)
         return 3;
     const int64_t OH = dgo_conv_out_dim(H, KH, sh, ph);
     const int64_t OW = dgo_conv_out_dim(W, KW, sw, pw);
@@ -181,7 +183,7 @@ int dgo_conv2d(const uint8_t *Wc, const uint8_t *Xc,
         for (int64_t ow = 0; ow < OW; ++ow) {
             for (int64_t co = 0; co < Cout; ++co) {
                 int64_t s;
-                if (conv_point(Wc, Xc, lw, la, H, W, Cin, KH, KW, sh, sw, ph,
+                if (conv_point(Wc, Xc, lw, la, nlev, H, W, Cin, KH, KW, sh, sw, ph,
                                pw, b, oh, ow, co, &s)) {
                     if (err < 1) err = 1;
                     continue;
@@ -199,14 +201,14 @@ int dgo_conv2d(const uint8_t *Wc, const uint8_t *Xc,
 
 /* Convolution at sampled output positions; pos[i] is a flat NHWC output index. */
 int dgo_conv2d_sampled(const uint8_t *Wc, const uint8_t *Xc,
-                       const int32_t lw[4], const int32_t la[4],
+                       const int32_t *lw, const int32_t *la, int nlev,
                        int64_t B, int64_t H, int64_t W, int64_t Cin,
                        int64_t Cout, int64_t KH, int64_t KW, int64_t sh,
                        int64_t sw, int64_t ph, int64_t pw,
                        const int64_t *pos, int64_t count, int32_t *out)
 {
     if (B < 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 ||
-        KW <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0 || count < 0)
+        KW <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0 || count < 0 || nlev < 1 || nlev > 16)
         return 3;
     const int64_t OH = dgo_conv_out_dim(H, KH, sh, ph);
     const int64_t OW = dgo_conv_out_dim(W, KW, sw, pw);
@@ -223,7 +225,7 @@ int dgo_conv2d_sampled(const uint8_t *Wc, const uint8_t *Xc,
         const int64_t ow = (p / Cout) % OW;
         const int64_t oh = (p / (Cout * OW)) % OH;
         const int64_t b = p / (Cout * OW * OH);
-        if (conv_point(Wc, Xc, lw, la, H, W, Cin, KH, KW, sh, sw, ph, pw, b,
+        if (conv_point(Wc, Xc, lw, la, nlev, H, W, Cin, KH, KW, sh, sw, ph, pw, b,
                        oh, ow, co, &s)) {
             if (err < 1) err = 1;
             continue;

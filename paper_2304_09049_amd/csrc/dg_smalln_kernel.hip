@@ -16,7 +16,6 @@
 
 namespace {
 
-constexpr int RB = 16;            // weight rows per block (8 row pairs, all loaded before they are used)
 constexpr int KT = 32;            // codes of K per lane per chunk
 constexpr int KC = 256 * KT;      // codes of K per chunk
 
@@ -62,7 +61,8 @@ __device__ __forceinline__ void selectors(uint32_t x0, uint32_t x1, uint32_t am,
     }
 }
 
-template <int NC>
+// NC activation rows per pass; RB weight rows per block (all of a block's words are loaded before any is used).
+template <int NC, int RB>
 __global__ void __launch_bounds__(256)
 smalln_kernel(SmallNArgs a)
 {
@@ -88,7 +88,7 @@ smalln_kernel(SmallNArgs a)
                 const uint32_t am = live ? 0x03030303u : 0u, om = live ? 0x04000400u : 0x0C0C0C0Cu;
                 const int koff = live ? kt / 4 : 0;
 
-                // all weight words of the row block first: 16 independent 8-byte loads in flight per lane
+                // all weight words of the row block first: RB independent 8-byte loads in flight per lane
                 uint2 w[RB];
 #pragma unroll
                 for (int r = 0; r < RB; ++r) {
@@ -176,17 +176,20 @@ dg_status dg_launch_smalln(const dg_lut *lut, const DgProblem &p, hipStream_t st
         for (int w = 0; w < 4; ++w) col |= (uint32_t)(lut->entry[4 * w + c] - lut->min_entry) << (8 * w);
         a.cols[c] = col;
     }
-    const int total_blocks = (p.M + RB - 1) / RB;
+    // one activation row: 8-row blocks (more workgroups in flight while the weights stream in); more rows: 16-row
+    // blocks (the activation pools are rebuilt per block, so longer blocks amortise them)
+    const int rb = p.N >= 2 ? 16 : 8;
+    const int total_blocks = (p.M + rb - 1) / rb;
     // about four workgroups per compute unit; longer runs of row blocks per workgroup beyond that
     int per_wg = (total_blocks + 1023) / 1024;
     if (per_wg < 1) per_wg = 1;
     a.blocks_per_wg = per_wg;
     const dim3 grid((unsigned)((total_blocks + per_wg - 1) / per_wg));
     if (p.N >= 4)
-        hipLaunchKernelGGL(smalln_kernel<4>, grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((smalln_kernel<4, 16>), grid, dim3(256), 0, stream, a);
     else if (p.N >= 2)
-        hipLaunchKernelGGL(smalln_kernel<2>, grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((smalln_kernel<2, 16>), grid, dim3(256), 0, stream, a);
     else
-        hipLaunchKernelGGL(smalln_kernel<1>, grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((smalln_kernel<1, 8>), grid, dim3(256), 0, stream, a);
     return dg_check_launch("smalln_kernel");
 }

@@ -101,11 +101,11 @@ class Inputs:
     scale: Optional[np.ndarray] = field(default=None)   # float32[M] or None
 
 
-def draw_codes(rng: np.random.Generator, shape, dist: str = "uniform") -> np.ndarray:
-    """2-bit codes.  "uniform": each of 0..3 with probability 1/4.
-    "relu_skew": code 0 with probability 1/2, codes 1..3 with 1/6 each."""
+def draw_codes(rng: np.random.Generator, shape, dist: str = "uniform", nlev: int = 4) -> np.ndarray:
+    """Codes in 0..nlev-1 (nlev = 4: the paper's 2-bit codes; 8, 16: its 3- and 4-bit extension).
+    "uniform": every code equally likely.  "relu_skew" (2-bit only): code 0 with probability 1/2, codes 1..3 with 1/6 each."""
     if dist == "uniform":
-        return rng.integers(0, 4, size=shape, dtype=np.uint8)
+        return rng.integers(0, nlev, size=shape, dtype=np.uint8)
     if dist == "relu_skew":
         r = rng.integers(0, 6, size=shape, dtype=np.uint8)   # 0,1,2 -> code 0; 3,4,5 -> codes 1,2,3
         return np.where(r < 3, 0, r - 2).astype(np.uint8)

@@ -377,3 +377,61 @@ def test_quantize_then_levels_recovers_a_uniform_grid():
     q = np.arange(-2, 2)
     x = ((q - z) / s).astype(np.float32)
     assert oracle.quantize_codes(x, s, z, -2, 1).tolist() == [0, 1, 2, 3]
+
+
+# ---- 3- and 4-bit codes (Sec. 3.3, Table 2: index 3+3 / 4+4 bits, 64 / 256 entries) ---------------------
+
+WIDE_LEVELS = {
+    3: (np.array([-4, -3, -2, -1, 0, 1, 2, 3], dtype=np.int32), np.array([0, 1, 2, 3, 4, 5, 6, 7], dtype=np.int32)),
+    4: (np.arange(-8, 8, dtype=np.int32), np.array([0, 3, 1, 7, 2, 9, 4, 15, 5, 6, 8, 10, 11, 12, 13, 14], dtype=np.int32)),
+}
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_table_sizes_follow_table2(bits):
+    lw, la = WIDE_LEVELS[bits]
+    table = oracle.build_lut(lw, la)
+    assert len(table) == 2 ** (2 * bits) == {3: 64, 4: 256}[bits]        # Table 2: 2^6 = 64, 2^8 = 256 entries
+    for w, a in itertools.product(range(2 ** bits), repeat=2):
+        assert table[(w << bits) | a] == lw[w] * la[a]
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_wide_codes_all_pairs_and_matmul(bits):
+    lw, la = WIDE_LEVELS[bits]
+    nlev = 2 ** bits
+    Wc = np.repeat(np.arange(nlev, dtype=np.uint8)[:, None], 2, axis=1)
+    C = oracle.gemm(Wc, Wc, lw, la)
+    for m, n in itertools.product(range(nlev), repeat=2):
+        assert C[m, n] == 2 * int(lw[m]) * int(la[n])
+    rng = np.random.default_rng(bits)
+    Wc, Ac = wl.draw_codes(rng, (13, 40), nlev=nlev), wl.draw_codes(rng, (9, 40), nlev=nlev)
+    want = lw.astype(np.int64)[Wc] @ la.astype(np.int64)[Ac].T
+    assert np.array_equal(oracle.gemm(Wc, Ac, lw, la).astype(np.int64), want)
+    via_table = oracle.lut_gemm_packed(oracle.pack_codes(Wc, bits), oracle.pack_codes(Ac, bits),
+                                       oracle.build_lut(lw, la), 40, bits)
+    assert np.array_equal(via_table.astype(np.int64), want)
+    with pytest.raises(oracle.OracleError):
+        oracle.gemm(np.full((1, 2), nlev, np.uint8), np.zeros((1, 2), np.uint8), lw, la)    # code out of range
+
+
+def test_wide_codes_packing_hand_values():
+    # two codes per byte in 4-bit slots: [5, 10] -> 5 + 10*16 = 165; [7, 1] -> 7 + 16 = 23; [0, 15] -> 240
+    assert oracle.pack_codes(np.array([[5, 10, 0, 15]], np.uint8), 4).tolist() == [[165, 240]]
+    assert oracle.pack_codes(np.array([[7, 1, 3, 0]], np.uint8), 3).tolist() == [[23, 3]]
+    assert oracle.unpack_codes(np.array([[165, 240]], np.uint8), 4).tolist() == [[5, 10, 0, 15]]
+    with pytest.raises(oracle.OracleError):
+        oracle.pack_codes(np.array([[8, 0]], np.uint8), 3)                 # 8 is not a 3-bit code
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_wide_codes_conv_equals_torch(bits):
+    lw, la = WIDE_LEVELS[bits]
+    rng = np.random.default_rng(10 + bits)
+    Wc = wl.draw_codes(rng, (5, 3, 3, 6), nlev=2 ** bits)
+    Xc = wl.draw_codes(rng, (2, 7, 8, 6), nlev=2 ** bits)
+    x = torch.from_numpy(la.astype(np.float64)[Xc]).permute(0, 3, 1, 2)
+    w = torch.from_numpy(lw.astype(np.float64)[Wc]).permute(0, 3, 1, 2)
+    want = torch.nn.functional.conv2d(x, w, stride=(2, 1), padding=(1, 1)).permute(0, 2, 3, 1).numpy()
+    got = oracle.conv2d(Wc, Xc, lw, la, stride=(2, 1), pad=(1, 1))
+    assert np.array_equal(got.astype(np.float64), want)
