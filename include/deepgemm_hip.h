@@ -61,7 +61,19 @@ typedef struct dg_lut dg_lut; /* opaque, immutable after build, usable from any 
  */
 dg_status dg_build_lut(const int8_t levels_w[4], const int8_t levels_a[4], dg_lut_dtype entry,
                        dg_lut **out);
-/* Copy the 16 entries, widened to int16, to host array out16 (out16[4*w + a]). */
+/*
+ * The same table for b-bit codes, b = 2, 3 or 4 (Sec. 3.3 and Table 2: index b + b bits, 2^(2b) = 16 / 64 / 256
+ * entries; the paper describes this scaling without implementing it).  levels_w / levels_a hold 2^b levels each;
+ * entry index = (w << b) | a.  Tables with b > 2 run on the LDS kernel only.  bits outside 2..4 ->
+ * DG_ERR_UNSUPPORTED.  dg_build_lut is the b = 2 case.
+ */
+dg_status dg_build_lut_bits(int32_t bits, const int8_t *levels_w, const int8_t *levels_a,
+                            dg_lut_dtype entry, dg_lut **out);
+/* Code width of a table (0 for NULL). */
+int32_t dg_lut_bits(const dg_lut *lut);
+/* Copy all 2^(2b) entries, widened to int16; count must equal that number (else DG_ERR_BUFFER). */
+dg_status dg_lut_entries_all(const dg_lut *lut, int16_t *out, int32_t count);
+/* Copy the 16 entries of a 2-bit table, widened to int16, to host array out16 (out16[4*w + a]). */
 dg_status dg_lut_entries(const dg_lut *lut, int16_t out16[16]);
 /* Free a table; NULL is allowed. */
 void dg_lut_destroy(dg_lut *lut);
@@ -78,6 +90,9 @@ void dg_lut_destroy(dg_lut *lut);
  */
 size_t dg_packed_activation_bytes(int64_t rows, int64_t K);
 size_t dg_packed_weight_bytes(int64_t M, int64_t K);
+/* Bytes of a packed [rows][K] matrix of b-bit codes: 3- and 4-bit codes sit two per byte, each in a 4-bit slot
+ * (code k in byte k/2, bits [4*(k%2)+b-1 : 4*(k%2)]), for weights and activations alike.  0 on bad arguments. */
+size_t dg_packed_bytes_bits(int64_t rows, int64_t K, int32_t bits);
 
 /*
  * Pack codes (one uint8 per code, values 0..3; higher bits are masked off) four per byte.
@@ -89,6 +104,10 @@ dg_status dg_pack_weights(const uint8_t *codes_dev, int64_t M, int64_t K, void *
                           size_t packed_bytes, void *hip_stream);
 dg_status dg_pack_activations(const uint8_t *codes_dev, int64_t N, int64_t K, void *packed_dev,
                               size_t packed_bytes, void *hip_stream);
+/* Pack b-bit codes (weights or activations); b = 2 is dg_pack_activations.  K must be a multiple of the codes per
+ * byte (4 for b = 2, else 2). */
+dg_status dg_pack_codes_bits(const uint8_t *codes_dev, int64_t rows, int64_t K, int32_t bits, void *packed_dev,
+                             size_t packed_bytes, void *hip_stream);
 
 /*
  * Fused activation quantise + pack (the two stages that precede the table convolution in Sec. 5.4, with the

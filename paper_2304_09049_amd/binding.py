@@ -23,9 +23,10 @@ KERNELS = {"auto": DG_KERNEL_AUTO, "perm": DG_KERNEL_PERM, "lds": DG_KERNEL_LDS,
 
 # every symbol include/deepgemm_hip.h declares
 EXPORTS = (
-    "dg_status_string", "dg_last_error", "dg_build_lut", "dg_lut_entries", "dg_lut_destroy",
-    "dg_packed_activation_bytes", "dg_packed_weight_bytes", "dg_pack_weights", "dg_pack_activations",
-    "dg_quantize_pack_activations",
+    "dg_status_string", "dg_last_error", "dg_build_lut", "dg_build_lut_bits", "dg_lut_bits", "dg_lut_entries",
+    "dg_lut_entries_all", "dg_lut_destroy",
+    "dg_packed_activation_bytes", "dg_packed_weight_bytes", "dg_packed_bytes_bits", "dg_pack_weights",
+    "dg_pack_activations", "dg_pack_codes_bits", "dg_quantize_pack_activations",
     "dg_gemm_lut", "dg_conv_out_dim", "dg_conv2d_lut", "dg_gemm_kernel_name", "dg_conv_kernel_name",
 )
 
@@ -59,6 +60,13 @@ def lib() -> ctypes.CDLL:
     L.dg_last_error.argtypes, L.dg_last_error.restype = [], ctypes.c_char_p
     L.dg_build_lut.argtypes, L.dg_build_lut.restype = [c_vp, c_vp, c_int, ctypes.POINTER(c_vp)], c_int
     L.dg_lut_entries.argtypes, L.dg_lut_entries.restype = [c_vp, c_vp], c_int
+    L.dg_build_lut_bits.argtypes = [ctypes.c_int32, c_vp, c_vp, c_int, ctypes.POINTER(c_vp)]
+    L.dg_build_lut_bits.restype = c_int
+    L.dg_lut_bits.argtypes, L.dg_lut_bits.restype = [c_vp], ctypes.c_int32
+    L.dg_lut_entries_all.argtypes, L.dg_lut_entries_all.restype = [c_vp, c_vp, ctypes.c_int32], c_int
+    L.dg_packed_bytes_bits.argtypes, L.dg_packed_bytes_bits.restype = [c_i64, c_i64, ctypes.c_int32], c_sz
+    L.dg_pack_codes_bits.argtypes = [c_vp, c_i64, c_i64, ctypes.c_int32, c_vp, c_sz, c_vp]
+    L.dg_pack_codes_bits.restype = c_int
     L.dg_lut_destroy.argtypes, L.dg_lut_destroy.restype = [c_vp], None
     L.dg_packed_activation_bytes.argtypes, L.dg_packed_activation_bytes.restype = [c_i64, c_i64], c_sz
     L.dg_packed_weight_bytes.argtypes, L.dg_packed_weight_bytes.restype = [c_i64, c_i64], c_sz
@@ -110,12 +118,19 @@ def _dev_ptr(t, dtype=None, name="tensor") -> ctypes.c_void_p:
 class Lut:
     """Owner of a ``dg_lut`` built by ``dg_build_lut``."""
 
-    def __init__(self, levels_w: Sequence[int], levels_a: Sequence[int], entry: int = DG_LUT_I8):
-        lw = (ctypes.c_int8 * 4)(*[int(v) for v in levels_w])
-        la = (ctypes.c_int8 * 4)(*[int(v) for v in levels_a])
+    def __init__(self, levels_w: Sequence[int], levels_a: Sequence[int], entry: int = DG_LUT_I8, bits: int = 2):
+        nlev = 1 << bits
+        if len(levels_w) != nlev or len(levels_a) != nlev:
+            raise ValueError(f"{bits}-bit codes need {nlev} levels per side")
+        lw = (ctypes.c_int8 * nlev)(*[int(v) for v in levels_w])
+        la = (ctypes.c_int8 * nlev)(*[int(v) for v in levels_a])
         handle = ctypes.c_void_p(0)
         self._h = None
-        _check(lib().dg_build_lut(lw, la, int(entry), ctypes.byref(handle)))
+        self.bits = bits
+        if bits == 2:
+            _check(lib().dg_build_lut(lw, la, int(entry), ctypes.byref(handle)))
+        else:
+            _check(lib().dg_build_lut_bits(bits, lw, la, int(entry), ctypes.byref(handle)))
         self._h = handle
 
     @property
@@ -123,8 +138,12 @@ class Lut:
         return self._h
 
     def entries(self):
-        out = (ctypes.c_int16 * 16)()
-        _check(lib().dg_lut_entries(self._h, out))
+        count = 1 << (2 * self.bits)
+        out = (ctypes.c_int16 * count)()
+        if self.bits == 2:
+            _check(lib().dg_lut_entries(self._h, out))
+        else:
+            _check(lib().dg_lut_entries_all(self._h, out, count))
         return list(out)
 
     def __del__(self):
@@ -135,6 +154,24 @@ class Lut:
 
 def dg_build_lut(levels_w, levels_a, entry: int = DG_LUT_I8) -> Lut:
     return Lut(levels_w, levels_a, entry)
+
+
+def dg_build_lut_bits(bits: int, levels_w, levels_a, entry: int = DG_LUT_I8) -> Lut:
+    return Lut(levels_w, levels_a, entry, bits=bits)
+
+
+def dg_packed_bytes_bits(rows: int, K: int, bits: int) -> int:
+    return int(lib().dg_packed_bytes_bits(rows, K, bits))
+
+
+def dg_pack_codes_bits(codes, rows: int, K: int, bits: int, out=None, stream=None):
+    """codes: uint8 device tensor with rows*K elements of `bits`-bit codes -> packed uint8 tensor (weights or activations)."""
+    import torch
+    if out is None:
+        out = torch.empty(dg_packed_bytes_bits(rows, K, bits), dtype=torch.uint8, device=codes.device)
+    _check(lib().dg_pack_codes_bits(_dev_ptr(codes, torch.uint8, "codes"), rows, K, bits,
+                                    _dev_ptr(out, torch.uint8, "packed"), out.numel(), _stream_ptr(stream)))
+    return out
 
 
 def dg_packed_activation_bytes(rows: int, K: int) -> int:

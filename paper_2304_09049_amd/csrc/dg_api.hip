@@ -50,27 +50,37 @@ const char *dg_last_error(void) { return g_error; }
 dg_status dg_build_lut(const int8_t levels_w[4], const int8_t levels_a[4], dg_lut_dtype entry,
                        dg_lut **out)
 {
+    return dg_build_lut_bits(2, levels_w, levels_a, entry, out);
+}
+
+// Table 2: b + b index bits, 2^(2b) entries (16, 64, 256 for b = 2, 3, 4).
+dg_status dg_build_lut_bits(int32_t bits, const int8_t *levels_w, const int8_t *levels_a,
+                            dg_lut_dtype entry, dg_lut **out)
+{
     if (!levels_w || !levels_a || !out) return dg_fail(DG_ERR_NULL, "dg_build_lut: NULL argument");
+    if (bits < 2 || bits > 4) return dg_fail(DG_ERR_UNSUPPORTED, "dg_build_lut: %d-bit codes (2, 3 or 4)", bits);
     if (entry != DG_LUT_I8 && entry != DG_LUT_I16)
         return dg_fail(DG_ERR_UNSUPPORTED, "dg_build_lut: unknown entry type %d", (int)entry);
+    const int nlev = 1 << bits;
     dg_lut t;
     memset(&t, 0, sizeof(t));
+    t.bits = bits;
     t.dtype = entry;
     t.min_entry = INT32_MAX;
     t.max_entry = INT32_MIN;
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < nlev; ++w) {
         t.levels_w[w] = levels_w[w];
         t.levels_a[w] = levels_a[w];
     }
-    for (int w = 0; w < 4; ++w)
-        for (int a = 0; a < 4; ++a) {
+    for (int w = 0; w < nlev; ++w)
+        for (int a = 0; a < nlev; ++a) {
             const int32_t prod = (int32_t)levels_w[w] * (int32_t)levels_a[a];
             if (entry == DG_LUT_I8 && (prod < -128 || prod > 127))
                 return dg_fail(DG_ERR_RANGE,
                                "dg_build_lut: product %d of levels_w[%d]=%d and levels_a[%d]=%d "
                                "does not fit an int8 table entry",
                                prod, w, (int)levels_w[w], a, (int)levels_a[a]);
-            t.entry[4 * w + a] = (int16_t)prod;   // |prod| <= 128*128 = 16384 always fits int16
+            t.entry[(w << bits) | a] = (int16_t)prod;   // |prod| <= 128*128 = 16384 always fits int16
             if (prod < t.min_entry) t.min_entry = prod;
             if (prod > t.max_entry) t.max_entry = prod;
         }
@@ -84,48 +94,72 @@ dg_status dg_build_lut(const int8_t levels_w[4], const int8_t levels_a[4], dg_lu
 dg_status dg_lut_entries(const dg_lut *lut, int16_t out16[16])
 {
     if (!lut || !out16) return dg_fail(DG_ERR_NULL, "dg_lut_entries: NULL argument");
+    if (lut->bits != 2) return dg_fail(DG_ERR_UNSUPPORTED, "dg_lut_entries: a %d-bit table has more than 16 entries", lut->bits);
     for (int i = 0; i < 16; ++i) out16[i] = lut->entry[i];
+    return DG_OK;
+}
+
+int32_t dg_lut_bits(const dg_lut *lut) { return lut ? lut->bits : 0; }
+
+dg_status dg_lut_entries_all(const dg_lut *lut, int16_t *out, int32_t count)
+{
+    if (!lut || !out) return dg_fail(DG_ERR_NULL, "dg_lut_entries_all: NULL argument");
+    if (count != 1 << (2 * lut->bits))
+        return dg_fail(DG_ERR_BUFFER, "dg_lut_entries_all: the table has %d entries, not %d", 1 << (2 * lut->bits), count);
+    for (int i = 0; i < count; ++i) out[i] = lut->entry[i];
     return DG_OK;
 }
 
 void dg_lut_destroy(dg_lut *lut) { delete lut; }
 
-size_t dg_packed_activation_bytes(int64_t rows, int64_t K)
+size_t dg_packed_activation_bytes(int64_t rows, int64_t K) { return dg_packed_bytes_bits(rows, K, 2); }
+
+size_t dg_packed_bytes_bits(int64_t rows, int64_t K, int32_t bits)
 {
-    if (rows < 0 || K < 0 || K % 4 != 0) return 0;
-    return (size_t)rows * (size_t)(K / 4);
+    if (bits < 2 || bits > 4) return 0;
+    const int per_byte = bits == 2 ? 4 : 2;
+    if (rows < 0 || K < 0 || K % per_byte != 0) return 0;
+    return (size_t)rows * (size_t)(K / per_byte);
 }
 
 // The private weight layout currently coincides with the activation layout: with the table rows
 // and selectors expanded once per tile in LDS, no offline re-ordering of weights saves work here.
 size_t dg_packed_weight_bytes(int64_t M, int64_t K) { return dg_packed_activation_bytes(M, K); }
 
-static dg_status pack_common(const char *name, const uint8_t *codes_dev, int64_t rows, int64_t K,
+static dg_status pack_common(const char *name, const uint8_t *codes_dev, int64_t rows, int64_t K, int32_t bits,
                              void *packed_dev, size_t packed_bytes, void *hip_stream)
 {
     if (!codes_dev || !packed_dev) return dg_fail(DG_ERR_NULL, "%s: NULL buffer", name);
-    if (rows <= 0 || K <= 0 || K % 4 != 0)
-        return dg_fail(DG_ERR_SHAPE, "%s: rows=%lld K=%lld (need rows > 0, K > 0, K %% 4 == 0)", name,
-                       (long long)rows, (long long)K);
+    if (bits < 2 || bits > 4) return dg_fail(DG_ERR_UNSUPPORTED, "%s: %d-bit codes (2, 3 or 4)", name, bits);
+    const int per_byte = bits == 2 ? 4 : 2;
+    if (rows <= 0 || K <= 0 || K % per_byte != 0)
+        return dg_fail(DG_ERR_SHAPE, "%s: rows=%lld K=%lld (need rows > 0, K > 0, K %% %d == 0)", name,
+                       (long long)rows, (long long)K, per_byte);
     if (rows > INT32_MAX || K > INT32_MAX)
         return dg_fail(DG_ERR_SHAPE, "%s: rows and K must each fit int32", name);
-    const size_t need = dg_packed_activation_bytes(rows, K);
+    const size_t need = dg_packed_bytes_bits(rows, K, bits);
     if (packed_bytes < need)
         return dg_fail(DG_ERR_BUFFER, "%s: packed buffer has %zu bytes, %zu needed", name,
                        packed_bytes, need);
-    return dg_launch_pack(codes_dev, rows, K, (uint8_t *)packed_dev, (hipStream_t)hip_stream);
+    return dg_launch_pack(codes_dev, rows, K, bits, (uint8_t *)packed_dev, (hipStream_t)hip_stream);
+}
+
+dg_status dg_pack_codes_bits(const uint8_t *codes_dev, int64_t rows, int64_t K, int32_t bits, void *packed_dev,
+                             size_t packed_bytes, void *hip_stream)
+{
+    return pack_common("dg_pack_codes_bits", codes_dev, rows, K, bits, packed_dev, packed_bytes, hip_stream);
 }
 
 dg_status dg_pack_weights(const uint8_t *codes_dev, int64_t M, int64_t K, void *packed_dev,
                           size_t packed_bytes, void *hip_stream)
 {
-    return pack_common("dg_pack_weights", codes_dev, M, K, packed_dev, packed_bytes, hip_stream);
+    return pack_common("dg_pack_weights", codes_dev, M, K, 2, packed_dev, packed_bytes, hip_stream);
 }
 
 dg_status dg_pack_activations(const uint8_t *codes_dev, int64_t N, int64_t K, void *packed_dev,
                               size_t packed_bytes, void *hip_stream)
 {
-    return pack_common("dg_pack_activations", codes_dev, N, K, packed_dev, packed_bytes, hip_stream);
+    return pack_common("dg_pack_activations", codes_dev, N, K, 2, packed_dev, packed_bytes, hip_stream);
 }
 
 dg_status dg_quantize_pack_activations(const float *x_dev, int64_t N, int64_t K, float scale,
@@ -162,6 +196,8 @@ enum class Pick { Perm, Lds, Mfma, SmallN, Lut65k, Unsupported };
 
 Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
 {
+    // 3- and 4-bit tables (64 / 256 entries) run on the plain LDS kernel only
+    if (lut->bits != 2) return (variant == DG_KERNEL_AUTO || variant == DG_KERNEL_LDS) ? Pick::Lds : Pick::Unsupported;
     switch (variant) {
     case DG_KERNEL_PERM: return dg_perm_supports(lut, p) ? Pick::Perm : Pick::Unsupported;
     case DG_KERNEL_LDS: return Pick::Lds;
@@ -218,9 +254,10 @@ dg_status fill_gemm(const char *name, const dg_lut *lut, int64_t M, int64_t N, i
                     DgProblem *p)
 {
     if (!lut) return dg_fail(DG_ERR_NULL, "%s: NULL table", name);
-    if (M <= 0 || N <= 0 || K <= 0 || K % 4 != 0)
-        return dg_fail(DG_ERR_SHAPE, "%s: M=%lld N=%lld K=%lld (need all > 0 and K %% 4 == 0)", name,
-                       (long long)M, (long long)N, (long long)K);
+    const int per_byte = lut->bits == 2 ? 4 : 2;
+    if (M <= 0 || N <= 0 || K <= 0 || K % per_byte != 0)
+        return dg_fail(DG_ERR_SHAPE, "%s: M=%lld N=%lld K=%lld (need all > 0 and K %% %d == 0)", name,
+                       (long long)M, (long long)N, (long long)K, per_byte);
     if (M > INT32_MAX / 2 || N > INT32_MAX / 2 || K > INT32_MAX / 2)
         return dg_fail(DG_ERR_SHAPE, "%s: a dimension exceeds 2^30", name);
     memset(p, 0, sizeof(*p));
@@ -238,7 +275,9 @@ dg_status fill_conv(const char *name, const dg_lut *lut, const dg_conv_desc *d, 
     if (d->B <= 0 || d->H <= 0 || d->W <= 0 || d->Cin <= 0 || d->Cout <= 0 || d->KH <= 0 ||
         d->KW <= 0 || d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0)
         return dg_fail(DG_ERR_SHAPE, "%s: every dimension and stride must be > 0 and pads >= 0", name);
-    if (d->Cin % 4 != 0) return dg_fail(DG_ERR_SHAPE, "%s: Cin=%d is not a multiple of 4", name, d->Cin);
+    const int per_byte = lut->bits == 2 ? 4 : 2;
+    if (d->Cin % per_byte != 0)
+        return dg_fail(DG_ERR_SHAPE, "%s: Cin=%d is not a multiple of %d", name, d->Cin, per_byte);
     const int64_t OH = dg_conv_out_dim(d->H, d->KH, d->stride_h, d->pad_h);
     const int64_t OW = dg_conv_out_dim(d->W, d->KW, d->stride_w, d->pad_w);
     if (OH <= 0 || OW <= 0) return dg_fail(DG_ERR_SHAPE, "%s: the filter does not fit the padded image", name);

@@ -9,9 +9,10 @@
 
 // The opaque table object: levels, the 16 products, and what the kernels need to know about them.
 struct dg_lut {
-    int8_t levels_w[4];
-    int8_t levels_a[4];
-    int16_t entry[16];   // entry[4*w + a] = levels_w[w] * levels_a[a]
+    int32_t bits;        // code width: 2 (the paper's kernels), 3 or 4 (Sec. 3.3); 2^bits levels per side
+    int8_t levels_w[16];
+    int8_t levels_a[16];
+    int16_t entry[256];  // entry[(w << bits) | a] = levels_w[w] * levels_a[a]; 2^(2*bits) entries are used
     dg_lut_dtype dtype;
     int32_t min_entry;   // smallest product
     int32_t max_entry;   // largest product
@@ -43,7 +44,7 @@ dg_status dg_fail(dg_status s, const char *fmt, ...);
 dg_status dg_check_launch(const char *what);
 
 // Kernel launchers (each validates nothing: the API layer has done that).
-dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, uint8_t *packed,
+dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits, uint8_t *packed,
                          hipStream_t stream);
 dg_status dg_launch_quantize_pack(const float *x, int64_t rows, int64_t K, float scale, float zero_point,
                                   int32_t lo, uint8_t *packed, hipStream_t stream);

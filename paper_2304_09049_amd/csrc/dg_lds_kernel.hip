@@ -1,39 +1,51 @@
-// The plain table kernel: the 16-entry table sits in LDS and every product is one indexed LDS read.
-// This is Algorithm 1 of the paper mapped one output per lane: for each packed byte pair, for the
-// four 2-bit slots, index = (weight code << 2) | activation code, fetch, add (int32).
-// It accepts every shape the library accepts (any K % 4 == 0, any stride / pad, any table) and is
-// the fallback for shapes the tuned kernels do not cover, and the "table in LDS" side of the
-// register-vs-LDS comparison.
+// The plain table kernel: the table sits in LDS and every product is one indexed LDS read.
+// This is Algorithm 1 of the paper mapped one output per lane: for each packed byte pair, for each code slot,
+// index = (weight code << bits) | activation code, fetch, add (int32).
+// It accepts every shape the library accepts (any K, any stride / pad, any table) and every code width: the
+// paper's 2-bit codes (16 entries) and the 3- and 4-bit extension it describes in Sec. 3.3 / Table 2 (64 and 256
+// entries; two codes per byte in 4-bit slots).  It is the fallback for shapes the tuned kernels do not cover, and
+// the "16-entry table in LDS" side of the register-versus-LDS comparison.
+#include <cstring>
+
 #include "dg_common.h"
 
 namespace {
 
-template <typename WordT>
+// The table travels in the kernel arguments (512 bytes at most): no device allocation is needed for it.
+struct Table256 {
+    int16_t e[256];
+};
+
+template <int BITS, typename WordT>
 __device__ __forceinline__ int32_t lookup_run(const int32_t *lut, const uint8_t *w, const uint8_t *x, int bytes)
 {
     // `bytes` packed bytes of one filter tap: both runs are contiguous (channel-fastest layouts)
-    int32_t acc = 0;
+    constexpr int SLOT = BITS == 2 ? 2 : 4;                  // bits per code slot
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
     constexpr int WB = sizeof(WordT);
+    int32_t acc = 0;
     const WordT *w4 = (const WordT *)w;
     const WordT *x4 = (const WordT *)x;
     for (int j = 0; j < bytes / WB; ++j) {
         const uint32_t vw = w4[j], va = x4[j];
 #pragma unroll
-        for (int i = 0; i < 4 * WB; ++i) {
-            const int shift = 2 * i;
-            const uint32_t indx = (((vw >> shift) & 3u) << 2) | ((va >> shift) & 3u);
+        for (int i = 0; i < 8 * WB / SLOT; ++i) {
+            const int shift = SLOT * i;
+            const uint32_t indx = (((vw >> shift) & MASK) << BITS) | ((va >> shift) & MASK);
             acc += lut[indx];
         }
     }
     return acc;
 }
 
-template <typename WordT>
+template <int BITS, typename WordT>
 __global__ void __launch_bounds__(256)
-lds_lut_kernel(DgProblem p, DgTable16 table)
+lds_lut_kernel(DgProblem p, Table256 table)
 {
-    __shared__ int32_t lut[16];
-    if (threadIdx.x < 16) lut[threadIdx.x] = table.e[threadIdx.x];
+    constexpr int ENTRIES = 1 << (2 * BITS);
+    constexpr int PER_BYTE = BITS == 2 ? 4 : 2;
+    __shared__ int32_t lut[ENTRIES];
+    for (int i = threadIdx.x; i < ENTRIES; i += blockDim.x) lut[i] = table.e[i];
     __syncthreads();
 
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -44,8 +56,8 @@ lds_lut_kernel(DgProblem p, DgTable16 table)
     const int oh = (n / p.OW) % p.OH;
     const int b = n / (p.OW * p.OH);
 
-    const int tap_bytes = p.Cin / 4;
-    const uint8_t *wrow = p.Wp + (int64_t)m * (p.K / 4);
+    const int tap_bytes = p.Cin / PER_BYTE;
+    const uint8_t *wrow = p.Wp + (int64_t)m * (p.K / PER_BYTE);
     int32_t acc = 0;
     for (int kh = 0; kh < p.KH; ++kh) {
         const int ih = oh * p.sh - p.ph + kh;
@@ -55,7 +67,7 @@ lds_lut_kernel(DgProblem p, DgTable16 table)
             if (iw < 0 || iw >= p.W) continue;
             const uint8_t *x = p.Xp + (((int64_t)b * p.H + ih) * p.W + iw) * tap_bytes;
             const uint8_t *w = wrow + (int64_t)(kh * p.KW + kw) * tap_bytes;
-            acc += lookup_run<WordT>(lut, w, x, tap_bytes);
+            acc += lookup_run<BITS, WordT>(lut, w, x, tap_bytes);
         }
     }
     const int64_t o = (int64_t)m * p.stride_cm + (int64_t)n * p.stride_cn;
@@ -65,20 +77,33 @@ lds_lut_kernel(DgProblem p, DgTable16 table)
         p.C[o] = acc;
 }
 
+template <int BITS>
+void launch_bits(const DgProblem &p, const Table256 &t, bool words, unsigned blocks, hipStream_t stream)
+{
+    if (words)
+        hipLaunchKernelGGL((lds_lut_kernel<BITS, uint32_t>), dim3(blocks), dim3(256), 0, stream, p, t);
+    else
+        hipLaunchKernelGGL((lds_lut_kernel<BITS, uint8_t>), dim3(blocks), dim3(256), 0, stream, p, t);
+}
+
 }   // namespace
 
 dg_status dg_launch_lds(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
 {
-    DgTable16 t;
-    for (int i = 0; i < 16; ++i) t.e[i] = lut->entry[i];
+    Table256 t;
+    memset(&t, 0, sizeof(t));
+    const int entries = 1 << (2 * lut->bits);
+    for (int i = 0; i < entries; ++i) t.e[i] = lut->entry[i];
     const int64_t total = (int64_t)p.M * p.N;
     const int64_t blocks = (total + 255) / 256;
     if (blocks > INT32_MAX) return dg_fail(DG_ERR_UNSUPPORTED, "lds kernel: M*N too large for one grid");
     // 32-bit reads need every tap run to start on a 4-byte boundary
-    const bool words = (p.Cin % 16 == 0) && ((uintptr_t)p.Wp % 4 == 0) && ((uintptr_t)p.Xp % 4 == 0);
-    if (words)
-        hipLaunchKernelGGL(lds_lut_kernel<uint32_t>, dim3((unsigned)blocks), dim3(256), 0, stream, p, t);
-    else
-        hipLaunchKernelGGL(lds_lut_kernel<uint8_t>, dim3((unsigned)blocks), dim3(256), 0, stream, p, t);
+    const int per_byte = lut->bits == 2 ? 4 : 2;
+    const bool words = (p.Cin % (4 * per_byte) == 0) && ((uintptr_t)p.Wp % 4 == 0) && ((uintptr_t)p.Xp % 4 == 0);
+    switch (lut->bits) {
+    case 2: launch_bits<2>(p, t, words, (unsigned)blocks, stream); break;
+    case 3: launch_bits<3>(p, t, words, (unsigned)blocks, stream); break;
+    default: launch_bits<4>(p, t, words, (unsigned)blocks, stream); break;
+    }
     return dg_check_launch("lds_lut_kernel");
 }

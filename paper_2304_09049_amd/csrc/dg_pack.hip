@@ -109,8 +109,27 @@ dg_status dg_launch_quantize_pack(const float *x, int64_t rows, int64_t K, float
     return DG_OK;
 }
 
-dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, uint8_t *packed, hipStream_t stream)
+namespace {
+// 3- and 4-bit codes: two per byte, each in a 4-bit slot (the layout the paper leaves open for Sec. 3.3).
+__global__ void __launch_bounds__(256)
+pack_slots4_kernel(const uint8_t *__restrict__ codes, uint8_t *__restrict__ packed, int64_t pairs, uint32_t mask)
 {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < pairs; g += stride)
+        packed[g] = (uint8_t)((codes[2 * g] & mask) | ((codes[2 * g + 1] & mask) << 4));
+}
+}   // namespace
+
+dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits, uint8_t *packed, hipStream_t stream)
+{
+    if (bits != 2) {
+        const int64_t pairs = rows * K / 2;
+        int64_t blocks = (pairs + 255) / 256;
+        if (blocks > 256 * 32) blocks = 256 * 32;
+        hipLaunchKernelGGL(pack_slots4_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, codes, packed, pairs,
+                           (1u << bits) - 1u);
+        return dg_check_launch("pack_slots4_kernel");
+    }
     const int64_t total = rows * K;           // multiple of 4
     const int64_t groups4 = total / 4;
     int64_t done4 = 0;

@@ -125,3 +125,22 @@ def test_pack_argument_errors():
     assert L.dg_pack_activations(fake, 4, 6, fake, 100, None) == 2
     assert L.dg_pack_activations(fake, 0, 4, fake, 100, None) == 2
     assert L.dg_pack_weights(fake, 4, 8, fake, 7, None) == 4               # needs 8 bytes
+
+
+def test_wide_tables_follow_table2():
+    # Table 2 of the paper: b + b index bits, 2^(2b) entries
+    for bits, n in ((3, 64), (4, 256)):
+        lw = list(range(-(1 << (bits - 1)), 1 << (bits - 1)))
+        la = list(range(1 << bits))
+        t = dg.dg_build_lut_bits(bits, lw, la, dg.DG_LUT_I8)
+        e = t.entries()
+        assert len(e) == n and dg.lib().dg_lut_bits(t.handle) == bits
+        for w, a in itertools.product(range(1 << bits), repeat=2):
+            assert e[(w << bits) | a] == lw[w] * la[a]
+    L = dg.lib()
+    h = ctypes.c_void_p(0)
+    lw = (ctypes.c_int8 * 32)(*range(32))
+    assert L.dg_build_lut_bits(5, lw, lw, 0, ctypes.byref(h)) == 5
+    assert L.dg_build_lut_bits(1, lw, lw, 0, ctypes.byref(h)) == 5
+    assert dg.dg_packed_bytes_bits(10, 8, 4) == 40 and dg.dg_packed_bytes_bits(10, 8, 3) == 40
+    assert dg.dg_packed_bytes_bits(10, 8, 2) == 20 and dg.dg_packed_bytes_bits(10, 7, 4) == 0

@@ -295,3 +295,38 @@ def test_quantize_pack_feeds_the_convolution():
     y = dg.dg_conv2d_lut(lut, Wp, Xp, dg.conv_desc(B, H, W, Cin, Cout, 3, 3, (1, 1), (1, 1)))
     torch.cuda.synchronize()
     _assert_same(y.cpu().numpy(), want, "quantize -> conv")
+
+
+WIDE = {
+    3: ([-4, -3, -2, -1, 0, 1, 2, 3], [0, 1, 2, 3, 4, 5, 6, 7]),
+    4: (list(range(-8, 8)), [0, 3, 1, 7, 2, 9, 4, 15, 5, 6, 8, 10, 11, 12, 13, 14]),
+}
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_wide_codes_gemm_and_conv(bits):
+    # Sec. 3.3 / Table 2: 64- and 256-entry tables; they run on the LDS kernel (AUTO picks it, the others decline)
+    lw, la = WIDE[bits]
+    nlev = 1 << bits
+    rng = np.random.default_rng(50 + bits)
+    lut = dg.dg_build_lut_bits(bits, lw, la, dg.DG_LUT_I8)
+    for M, N, K in ((5, 7, 6), (64, 196, 576), (33, 130, 40)):
+        Wc, Ac = wl.draw_codes(rng, (M, K), nlev=nlev), wl.draw_codes(rng, (N, K), nlev=nlev)
+        Wp = dg.dg_pack_codes_bits(torch.from_numpy(Wc).cuda(), M, K, bits)
+        Ap = dg.dg_pack_codes_bits(torch.from_numpy(Ac).cuda(), N, K, bits)
+        _assert_same(Ap.cpu().numpy().reshape(N, K // 2), oracle.pack_codes(Ac, bits), f"{bits}-bit pack")
+        got = dg.dg_gemm_lut(lut, Wp, Ap, M, N, K)
+        torch.cuda.synchronize()
+        _assert_same(got.cpu().numpy(), oracle.gemm(Wc, Ac, lw, la), f"{bits}-bit gemm {(M, N, K)}")
+        assert dg.dg_gemm_kernel_name(lut, M, N, K) == "lds"
+        with pytest.raises(dg.DgError) as e:
+            dg.dg_gemm_lut(lut, Wp, Ap, M, N, K, variant="perm")
+        assert e.value.status == 5
+    B, H, W, Cin, Cout = 2, 9, 7, 16, 12
+    Wc = wl.draw_codes(rng, (Cout, 3, 3, Cin), nlev=nlev)
+    Xc = wl.draw_codes(rng, (B, H, W, Cin), nlev=nlev)
+    Wp = dg.dg_pack_codes_bits(torch.from_numpy(Wc).cuda(), Cout, 9 * Cin, bits)
+    Xp = dg.dg_pack_codes_bits(torch.from_numpy(Xc).cuda(), B * H * W, Cin, bits)
+    y = dg.dg_conv2d_lut(lut, Wp, Xp, dg.conv_desc(B, H, W, Cin, Cout, 3, 3, (2, 1), (1, 1)))
+    torch.cuda.synchronize()
+    _assert_same(y.cpu().numpy(), oracle.conv2d(Wc, Xc, lw, la, stride=(2, 1), pad=(1, 1)), f"{bits}-bit conv")
