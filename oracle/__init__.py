@@ -56,6 +56,12 @@ def _load():
         lib.dgo_scale_epilogue_rows.argtypes = [p, p, i64, i64, p]
         lib.dgo_scale_epilogue_rows.restype = None
         lib.dgo_quantize_codes.argtypes = [p, i64, ctypes.c_float, ctypes.c_float, ctypes.c_int32, ctypes.c_int32, p]
+        lib.dgo_gemm_table.argtypes = [p, p, p, ctypes.c_int, i64, i64, i64, p]
+        lib.dgo_conv2d_table.argtypes = [p, p, p, ctypes.c_int] + [i64] * 11 + [p]
+        lib.dgo_build_lut_f32.argtypes = [p, p, p]
+        lib.dgo_build_lut_f32.restype = None
+        lib.dgo_gemm_table_f32.argtypes = [p, p, p, i64, i64, i64, p]
+        lib.dgo_conv2d_table_f32.argtypes = [p, p, p] + [i64] * 11 + [p]
         lib.dgo_build_lut.argtypes = [p, p, ctypes.c_int, p]
         lib.dgo_build_lut.restype = None
         lib.dgo_pack_codes.argtypes = [p, i64, ctypes.c_int, p]
@@ -209,6 +215,70 @@ def quantize_codes(x, scale: float, zero_point: float, lo: int, hi: int) -> np.n
     _check(_load().dgo_quantize_codes(_ptr(x), x.size, float(np.float32(scale)), float(np.float32(zero_point)),
                                       int(lo), int(hi), _ptr(codes)))
     return codes
+
+
+# ---- tables that are given as such: arbitrary integer entries, binary32 entries --------------------------------
+
+def _nlev_of_table(table) -> int:
+    n = {16: 4, 64: 8, 256: 16}.get(int(np.asarray(table).size))
+    if n is None:
+        raise OracleError("a table has 16, 64 or 256 entries")
+    return n
+
+
+def gemm_table(Wc, Ac, table) -> np.ndarray:
+    """C[m][n] = sum_k table[nlev*Wc[m][k] + Ac[n][k]] for an arbitrary integer table (it need not be a product of levels)."""
+    Wc, Ac = _codes(Wc), _codes(Ac)
+    table = np.ascontiguousarray(table, dtype=np.int32).reshape(-1)
+    (M, K), N = Wc.shape, Ac.shape[0]
+    C = np.zeros((M, N), dtype=np.int32)
+    _check(_load().dgo_gemm_table(_ptr(Wc), _ptr(Ac), _ptr(table), _nlev_of_table(table), M, N, K, _ptr(C)))
+    return C
+
+
+def conv2d_table(Wc, Xc, table, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    Wc, Xc = _codes(Wc), _codes(Xc)
+    table = np.ascontiguousarray(table, dtype=np.int32).reshape(-1)
+    Cout, KH, KW, Cin = Wc.shape
+    B, H, W, _ = Xc.shape
+    OH, OW = conv_out_dim(H, KH, stride[0], pad[0]), conv_out_dim(W, KW, stride[1], pad[1])
+    Y = np.zeros((B, max(OH, 0), max(OW, 0), Cout), dtype=np.int32)
+    _check(_load().dgo_conv2d_table(_ptr(Wc), _ptr(Xc), _ptr(table), _nlev_of_table(table), B, H, W, Cin, Cout,
+                                    KH, KW, stride[0], stride[1], pad[0], pad[1], _ptr(Y)))
+    return Y
+
+
+def build_lut_f32(levels_w, levels_a) -> np.ndarray:
+    """table[4*w + a] = float32(lw[w]) * float32(la[a]), one binary32 multiply each."""
+    lw = np.ascontiguousarray(levels_w, dtype=np.float32)
+    la = np.ascontiguousarray(levels_a, dtype=np.float32)
+    if lw.shape != (4,) or la.shape != (4,):
+        raise OracleError("binary32 tables are defined for 2-bit codes: 4 levels per side")
+    table = np.zeros(16, dtype=np.float32)
+    _load().dgo_build_lut_f32(_ptr(lw), _ptr(la), _ptr(table))
+    return table
+
+
+def gemm_table_f32(Wc, Ac, table) -> np.ndarray:
+    """binary32 sum of table entries, one addition per k in ascending order, starting from +0."""
+    Wc, Ac = _codes(Wc), _codes(Ac)
+    table = np.ascontiguousarray(table, dtype=np.float32)
+    (M, K), N = Wc.shape, Ac.shape[0]
+    C = np.zeros((M, N), dtype=np.float32)
+    _check(_load().dgo_gemm_table_f32(_ptr(Wc), _ptr(Ac), _ptr(table), M, N, K, _ptr(C)))
+    return C
+
+
+def conv2d_table_f32(Wc, Xc, table, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
+    Wc, Xc = _codes(Wc), _codes(Xc)
+    table = np.ascontiguousarray(table, dtype=np.float32)
+    Cout, KH, KW, Cin = Wc.shape
+    B, H, W, _ = Xc.shape
+    OH, OW = conv_out_dim(H, KH, stride[0], pad[0]), conv_out_dim(W, KW, stride[1], pad[1])
+    Y = np.zeros((B, max(OH, 0), max(OW, 0), Cout), dtype=np.float32)
+    _check(_load().dgo_conv2d_table_f32(_ptr(Wc), _ptr(Xc), _ptr(table), B, H, W, Cin, Cout, KH, KW,
+                                        stride[0], stride[1], pad[0], pad[1], _ptr(Y)))
+    return Y
 
 
 # ---- the table method's own steps (dg_lut_reference.c) -----------------------------------

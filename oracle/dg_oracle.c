@@ -292,3 +292,123 @@ int dgo_quantize_codes(const float *x, int64_t count, float s, float z, int32_t 
     }
     return 0;
 }
+
+/*
+ * Table-defined variants.  Sec. 5.3 stresses that the table stores RESULTS, so it may hold anything: products of
+ * non-uniform levels, signed or unsigned, integer or floating point.  A table need not even factor into level
+ * vectors.  For such tables the result has this plain definition:
+ *     C[m][n] = sum_k  T[ nlev * Wc[m][k] + Ac[n][k] ]
+ * Integer tables: exact (int64 sum, checked).  binary32 tables: the sum is taken in binary32, one addition per
+ * reduction position in ascending order of k (for a convolution: kh, then kw, then ci, taps outside the image
+ * skipped), starting from +0.0f -- the order is part of the definition because float addition does not commute
+ * with rounding.  The paper gives no order; this one is this build's reading.
+ */
+int dgo_gemm_table(const uint8_t *Wc, const uint8_t *Ac, const int32_t *table, int nlev,
+                   int64_t M, int64_t N, int64_t K, int32_t *C)
+{
+    if (M < 0 || N < 0 || K < 0 || nlev < 1 || nlev > 16) return 3;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t s = 0;
+            for (int64_t k = 0; k < K; ++k) {
+                const uint8_t w = Wc[m * K + k], a = Ac[n * K + k];
+                if (w >= nlev || a >= nlev) return 1;
+                s += table[nlev * w + a];
+            }
+            if (s > INT32_MAX || s < INT32_MIN) return 2;
+            C[m * N + n] = (int32_t)s;
+        }
+    return 0;
+}
+
+int dgo_conv2d_table(const uint8_t *Wc, const uint8_t *Xc, const int32_t *table, int nlev,
+                     int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                     int64_t KH, int64_t KW, int64_t sh, int64_t sw, int64_t ph, int64_t pw, int32_t *Y)
+{
+    if (B < 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || sh <= 0 || sw <= 0 ||
+        ph < 0 || pw < 0 || nlev < 1 || nlev > 16)
+        return 3;
+    const int64_t OH = dgo_conv_out_dim(H, KH, sh, ph), OW = dgo_conv_out_dim(W, KW, sw, pw);
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t oh = 0; oh < OH; ++oh)
+            for (int64_t ow = 0; ow < OW; ++ow)
+                for (int64_t co = 0; co < Cout; ++co) {
+                    int64_t s = 0;
+                    for (int64_t kh = 0; kh < KH; ++kh) {
+                        const int64_t ih = oh * sh - ph + kh;
+                        if (ih < 0 || ih >= H) continue;
+                        for (int64_t kw = 0; kw < KW; ++kw) {
+                            const int64_t iw = ow * sw - pw + kw;
+                            if (iw < 0 || iw >= W) continue;
+                            for (int64_t ci = 0; ci < Cin; ++ci) {
+                                const uint8_t w = Wc[((co * KH + kh) * KW + kw) * Cin + ci];
+                                const uint8_t a = Xc[((b * H + ih) * W + iw) * Cin + ci];
+                                if (w >= nlev || a >= nlev) return 1;
+                                s += table[nlev * w + a];
+                            }
+                        }
+                    }
+                    if (s > INT32_MAX || s < INT32_MIN) return 2;
+                    Y[((b * OH + oh) * OW + ow) * Cout + co] = (int32_t)s;
+                }
+    return 0;
+}
+
+/* table[4*w + a] = lw[w] * la[a], one binary32 multiply each */
+void dgo_build_lut_f32(const float lw[4], const float la[4], float table[16])
+{
+    for (int w = 0; w < 4; ++w)
+        for (int a = 0; a < 4; ++a) {
+            volatile float p = lw[w] * la[a];
+            table[4 * w + a] = p;
+        }
+}
+
+int dgo_gemm_table_f32(const uint8_t *Wc, const uint8_t *Ac, const float table[16],
+                       int64_t M, int64_t N, int64_t K, float *C)
+{
+    if (M < 0 || N < 0 || K < 0) return 3;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            volatile float s = 0.0f;
+            for (int64_t k = 0; k < K; ++k) {
+                const uint8_t w = Wc[m * K + k], a = Ac[n * K + k];
+                if (w > 3 || a > 3) return 1;
+                s = s + table[4 * w + a];
+            }
+            C[m * N + n] = s;
+        }
+    return 0;
+}
+
+int dgo_conv2d_table_f32(const uint8_t *Wc, const uint8_t *Xc, const float table[16],
+                         int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                         int64_t KH, int64_t KW, int64_t sh, int64_t sw, int64_t ph, int64_t pw, float *Y)
+{
+    if (B < 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || sh <= 0 || sw <= 0 ||
+        ph < 0 || pw < 0)
+        return 3;
+    const int64_t OH = dgo_conv_out_dim(H, KH, sh, ph), OW = dgo_conv_out_dim(W, KW, sw, pw);
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t oh = 0; oh < OH; ++oh)
+            for (int64_t ow = 0; ow < OW; ++ow)
+                for (int64_t co = 0; co < Cout; ++co) {
+                    volatile float s = 0.0f;
+                    for (int64_t kh = 0; kh < KH; ++kh) {
+                        const int64_t ih = oh * sh - ph + kh;
+                        if (ih < 0 || ih >= H) continue;
+                        for (int64_t kw = 0; kw < KW; ++kw) {
+                            const int64_t iw = ow * sw - pw + kw;
+                            if (iw < 0 || iw >= W) continue;
+                            for (int64_t ci = 0; ci < Cin; ++ci) {
+                                const uint8_t w = Wc[((co * KH + kh) * KW + kw) * Cin + ci];
+                                const uint8_t a = Xc[((b * H + ih) * W + iw) * Cin + ci];
+                                if (w > 3 || a > 3) return 1;
+                                s = s + table[4 * w + a];
+                            }
+                        }
+                    }
+                    Y[((b * OH + oh) * OW + ow) * Cout + co] = s;
+                }
+    return 0;
+}

@@ -435,3 +435,62 @@ def test_wide_codes_conv_equals_torch(bits):
     want = torch.nn.functional.conv2d(x, w, stride=(2, 1), padding=(1, 1)).permute(0, 2, 3, 1).numpy()
     got = oracle.conv2d(Wc, Xc, lw, la, stride=(2, 1), pad=(1, 1))
     assert np.array_equal(got.astype(np.float64), want)
+
+
+# ---- tables given as such: non-separable integer tables, binary32 tables (Sec. 5.3) -----------------------
+
+def test_table_oracle_equals_level_oracle_for_product_tables():
+    for lw, la in LEVEL_SETS:
+        g = wl.small_gemm(11, 13, 36, seed=21)
+        assert np.array_equal(oracle.gemm_table(g.Wc, g.Ac, oracle.build_lut(lw, la)), oracle.gemm(g.Wc, g.Ac, lw, la))
+        c = wl.small_conv(2, 6, 5, 8, 3, 3, 3, (2, 1), (1, 1), seed=22)
+        assert np.array_equal(oracle.conv2d_table(c.Wc, c.Ac, oracle.build_lut(lw, la), stride=(2, 1), pad=(1, 1)),
+                              oracle.conv2d(c.Wc, c.Ac, lw, la, stride=(2, 1), pad=(1, 1)))
+
+
+def test_table_oracle_on_a_non_separable_table_by_one_hot_matmul():
+    rng = np.random.default_rng(23)
+    table = rng.integers(-100, 100, size=16).astype(np.int32)           # rank 4 with overwhelming probability
+    assert np.linalg.matrix_rank(table.reshape(4, 4)) > 1
+    g = wl.small_gemm(9, 12, 28, seed=24)
+    # C = sum_v  T[Wc][:, :, v] @ onehot(Ac == v)^T : an independent formulation in numpy int64
+    want = sum(table.reshape(4, 4).astype(np.int64)[g.Wc][:, :, v] @ (g.Ac == v).astype(np.int64).T for v in range(4))
+    assert np.array_equal(oracle.gemm_table(g.Wc, g.Ac, table).astype(np.int64), want)
+    assert np.array_equal(oracle.lut_gemm_packed(oracle.pack_codes(g.Wc), oracle.pack_codes(g.Ac), table, 28), want)
+    # single-pair brute force: K = 1 picks exactly one entry
+    for w, a in itertools.product(range(4), range(4)):
+        assert oracle.gemm_table(np.array([[w]], np.uint8), np.array([[a]], np.uint8), table)[0, 0] == table[4 * w + a]
+
+
+def test_f32_table_is_one_multiply_per_entry():
+    lw = np.array([0.1, -0.37, 1.5, 3.0e-3], np.float32)
+    la = np.array([0.0, 0.7, 1.9, 2.25], np.float32)
+    want = (lw[:, None] * la[None, :]).astype(np.float32).reshape(-1)       # numpy float32 multiply
+    assert np.array_equal(oracle.build_lut_f32(lw, la), want)
+
+
+def test_f32_sum_is_sequential_in_k():
+    table = oracle.build_lut_f32(np.array([1.0e8, -1.0e8, 1.0, 0.5], np.float32), np.array([1.0, 1.0, 1.0, 1.0], np.float32))
+    # weights: big, small, small, -big.  Sequential float32: ((1e8 + 1) + 0.5) - 1e8 = 0 (both small terms are absorbed);
+    # any other order gives 1.5 or 1 or 0.5
+    Wc = np.array([[0, 2, 3, 1]], np.uint8)
+    Ac = np.zeros((1, 4), np.uint8)
+    assert oracle.gemm_table_f32(Wc, Ac, table)[0, 0] == 0.0
+    Wc = np.array([[2, 3, 0, 1]], np.uint8)                               # small terms first: (1 + 0.5 + 1e8) - 1e8 = 0 too,
+    assert oracle.gemm_table_f32(Wc, Ac, table)[0, 0] == np.float32(np.float32(np.float32(1.5) + np.float32(1e8)) - np.float32(1e8))
+    # against numpy's sequential float32 accumulate on random data
+    rng = np.random.default_rng(25)
+    t = rng.normal(0, 1, 16).astype(np.float32)
+    g = wl.small_gemm(5, 6, 200, seed=26)
+    got = oracle.gemm_table_f32(g.Wc, g.Ac, t)
+    for m, n in itertools.product(range(5), range(6)):
+        terms = t[4 * g.Wc[m].astype(np.int64) + g.Ac[n]]
+        assert got[m, n] == np.add.accumulate(terms, dtype=np.float32)[-1]
+
+
+def test_f32_table_with_integer_levels_equals_integer_oracle():
+    lw, la = LEVEL_SETS[0]
+    c = wl.small_conv(1, 6, 6, 8, 4, 3, 3, pad=(1, 1), seed=27)
+    t = oracle.build_lut_f32(lw.astype(np.float32), la.astype(np.float32))
+    got = oracle.conv2d_table_f32(c.Wc, c.Ac, t, pad=(1, 1))
+    assert np.array_equal(got, oracle.conv2d(c.Wc, c.Ac, lw, la, pad=(1, 1)).astype(np.float32))
