@@ -49,7 +49,7 @@ const char *dg_last_error(void);
 
 /* Entry type.  The paper's tables hold 8-bit entries and assume no overflow, with wider entries
  * "if required" (Sec. 3.2 "LUT Versions"); here the width is explicit and checked. */
-typedef enum { DG_LUT_I8 = 0, DG_LUT_I16 = 1 } dg_lut_dtype;
+typedef enum { DG_LUT_I8 = 0, DG_LUT_I16 = 1, DG_LUT_F32 = 2 } dg_lut_dtype;
 
 typedef struct dg_lut dg_lut; /* opaque, immutable after build, usable from any thread */
 
@@ -69,6 +69,24 @@ dg_status dg_build_lut(const int8_t levels_w[4], const int8_t levels_a[4], dg_lu
  */
 dg_status dg_build_lut_bits(int32_t bits, const int8_t *levels_w, const int8_t *levels_a,
                             dg_lut_dtype entry, dg_lut **out);
+/*
+ * A 2-bit table given as such: entries[4*w + a] may be ANY 16 integers, not only products of two level vectors
+ * (the table stores results, Sec. 5.3).  entry = DG_LUT_I8 checks every value against [-128, 127]
+ * (DG_ERR_RANGE); DG_LUT_I16 accepts all.  The table kernels run such tables unchanged; the matrix-core
+ * comparison kernel needs the level vectors and returns DG_ERR_UNSUPPORTED for them.
+ */
+dg_status dg_build_lut_entries(const int16_t entries[16], dg_lut_dtype entry, dg_lut **out);
+/*
+ * A 2-bit table of binary32 products of floating-point levels (non-uniform quantisation, Sec. 5.3):
+ * entry[4*w + a] = levels_w[w] * levels_a[a], one binary32 multiply each.  With such a table dg_gemm_lut /
+ * dg_conv2d_lut write binary32 to Cf_dev / Yf_dev (required; the int32 pointer is ignored): the sum of the
+ * fetched entries taken in binary32, one addition per reduction position in ascending k (for a convolution kh,
+ * then kw, then ci; taps outside the image skipped), starting from +0; then, if a scale is given, one multiply by
+ * scale[m].  Only the LDS kernel runs binary32 tables (AUTO selects it).
+ */
+dg_status dg_build_lut_f32(const float levels_w[4], const float levels_a[4], dg_lut **out);
+/* Copy the 16 binary32 entries of a DG_LUT_F32 table (DG_ERR_UNSUPPORTED for integer tables). */
+dg_status dg_lut_entries_f32(const dg_lut *lut, float out[16]);
 /* Code width of a table (0 for NULL). */
 int32_t dg_lut_bits(const dg_lut *lut);
 /* Copy all 2^(2b) entries, widened to int16; count must equal that number (else DG_ERR_BUFFER). */

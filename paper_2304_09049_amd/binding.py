@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libdeepgemm_hip.so")
 DG_OK = 0
 STATUS_NAMES = ("DG_OK", "DG_ERR_NULL", "DG_ERR_SHAPE", "DG_ERR_RANGE", "DG_ERR_BUFFER",
                 "DG_ERR_UNSUPPORTED", "DG_ERR_HIP")
-DG_LUT_I8, DG_LUT_I16 = 0, 1
+DG_LUT_I8, DG_LUT_I16, DG_LUT_F32 = 0, 1, 2
 DG_KERNEL_AUTO, DG_KERNEL_PERM, DG_KERNEL_LDS, DG_KERNEL_MFMA_I8, DG_KERNEL_SMALLN, DG_KERNEL_LUT65K = 0, 1, 2, 3, 4, 5
 KERNELS = {"auto": DG_KERNEL_AUTO, "perm": DG_KERNEL_PERM, "lds": DG_KERNEL_LDS,
            "mfma_i8": DG_KERNEL_MFMA_I8, "smalln": DG_KERNEL_SMALLN, "lut65k": DG_KERNEL_LUT65K}
@@ -24,7 +24,7 @@ KERNELS = {"auto": DG_KERNEL_AUTO, "perm": DG_KERNEL_PERM, "lds": DG_KERNEL_LDS,
 # every symbol include/deepgemm_hip.h declares
 EXPORTS = (
     "dg_status_string", "dg_last_error", "dg_build_lut", "dg_build_lut_bits", "dg_lut_bits", "dg_lut_entries",
-    "dg_lut_entries_all", "dg_lut_destroy",
+    "dg_lut_entries_all", "dg_lut_destroy", "dg_build_lut_entries", "dg_build_lut_f32", "dg_lut_entries_f32",
     "dg_packed_activation_bytes", "dg_packed_weight_bytes", "dg_packed_bytes_bits", "dg_pack_weights",
     "dg_pack_activations", "dg_pack_codes_bits", "dg_quantize_pack_activations",
     "dg_gemm_lut", "dg_conv_out_dim", "dg_conv2d_lut", "dg_gemm_kernel_name", "dg_conv_kernel_name",
@@ -60,6 +60,9 @@ def lib() -> ctypes.CDLL:
     L.dg_last_error.argtypes, L.dg_last_error.restype = [], ctypes.c_char_p
     L.dg_build_lut.argtypes, L.dg_build_lut.restype = [c_vp, c_vp, c_int, ctypes.POINTER(c_vp)], c_int
     L.dg_lut_entries.argtypes, L.dg_lut_entries.restype = [c_vp, c_vp], c_int
+    L.dg_build_lut_entries.argtypes, L.dg_build_lut_entries.restype = [c_vp, c_int, ctypes.POINTER(c_vp)], c_int
+    L.dg_build_lut_f32.argtypes, L.dg_build_lut_f32.restype = [c_vp, c_vp, ctypes.POINTER(c_vp)], c_int
+    L.dg_lut_entries_f32.argtypes, L.dg_lut_entries_f32.restype = [c_vp, c_vp], c_int
     L.dg_build_lut_bits.argtypes = [ctypes.c_int32, c_vp, c_vp, c_int, ctypes.POINTER(c_vp)]
     L.dg_build_lut_bits.restype = c_int
     L.dg_lut_bits.argtypes, L.dg_lut_bits.restype = [c_vp], ctypes.c_int32
@@ -118,15 +121,28 @@ def _dev_ptr(t, dtype=None, name="tensor") -> ctypes.c_void_p:
 class Lut:
     """Owner of a ``dg_lut`` built by ``dg_build_lut``."""
 
-    def __init__(self, levels_w: Sequence[int], levels_a: Sequence[int], entry: int = DG_LUT_I8, bits: int = 2):
+    def __init__(self, levels_w: Sequence[int], levels_a: Sequence[int], entry: int = DG_LUT_I8, bits: int = 2,
+                 entries: Optional[Sequence[int]] = None):
+        self._h = None
+        self.bits = bits
+        self.is_f32 = entry == DG_LUT_F32
+        handle = ctypes.c_void_p(0)
+        if entries is not None:                       # a table given as such (any 16 integers)
+            arr = (ctypes.c_int16 * 16)(*[int(v) for v in entries])
+            _check(lib().dg_build_lut_entries(arr, int(entry), ctypes.byref(handle)))
+            self._h = handle
+            return
+        if self.is_f32:                               # binary32 products of floating-point levels
+            lwf = (ctypes.c_float * 4)(*[float(v) for v in levels_w])
+            laf = (ctypes.c_float * 4)(*[float(v) for v in levels_a])
+            _check(lib().dg_build_lut_f32(lwf, laf, ctypes.byref(handle)))
+            self._h = handle
+            return
         nlev = 1 << bits
         if len(levels_w) != nlev or len(levels_a) != nlev:
             raise ValueError(f"{bits}-bit codes need {nlev} levels per side")
         lw = (ctypes.c_int8 * nlev)(*[int(v) for v in levels_w])
         la = (ctypes.c_int8 * nlev)(*[int(v) for v in levels_a])
-        handle = ctypes.c_void_p(0)
-        self._h = None
-        self.bits = bits
         if bits == 2:
             _check(lib().dg_build_lut(lw, la, int(entry), ctypes.byref(handle)))
         else:
@@ -138,6 +154,10 @@ class Lut:
         return self._h
 
     def entries(self):
+        if self.is_f32:
+            outf = (ctypes.c_float * 16)()
+            _check(lib().dg_lut_entries_f32(self._h, outf))
+            return list(outf)
         count = 1 << (2 * self.bits)
         out = (ctypes.c_int16 * count)()
         if self.bits == 2:
@@ -154,6 +174,14 @@ class Lut:
 
 def dg_build_lut(levels_w, levels_a, entry: int = DG_LUT_I8) -> Lut:
     return Lut(levels_w, levels_a, entry)
+
+
+def dg_build_lut_entries(entries, entry: int = DG_LUT_I16) -> Lut:
+    return Lut((), (), entry, entries=entries)
+
+
+def dg_build_lut_f32(levels_w, levels_a) -> Lut:
+    return Lut(levels_w, levels_a, DG_LUT_F32)
 
 
 def dg_build_lut_bits(bits: int, levels_w, levels_a, entry: int = DG_LUT_I8) -> Lut:
@@ -219,12 +247,13 @@ def dg_gemm_lut(lut: Lut, Wp, Ap, M: int, N: int, K: int, out=None, scale=None, 
                 stream=None, strides: Optional[Sequence[int]] = None):
     """C[m][n] = sum_k LUT[4*Wc[m][k] + Ac[n][k]].  Returns int32 [M][N], or float32 when `scale` is given."""
     import torch
-    dtype = torch.float32 if scale is not None else torch.int32
+    as_float = scale is not None or lut.is_f32
+    dtype = torch.float32 if as_float else torch.int32
     if out is None:
         out = torch.empty((M, N), dtype=dtype, device=Wp.device)
     scm, scn = (N, 1) if strides is None else strides
-    c_int = _dev_ptr(out, torch.int32, "out") if scale is None else ctypes.c_void_p(0)
-    c_f32 = _dev_ptr(out, torch.float32, "out") if scale is not None else ctypes.c_void_p(0)
+    c_int = _dev_ptr(out, torch.int32, "out") if not as_float else ctypes.c_void_p(0)
+    c_f32 = _dev_ptr(out, torch.float32, "out") if as_float else ctypes.c_void_p(0)
     _check(lib().dg_gemm_lut(lut.handle, _dev_ptr(Wp, torch.uint8, "Wp"), _dev_ptr(Ap, torch.uint8, "Ap"),
                              M, N, K, c_int, scm, scn, _dev_ptr(scale, torch.float32, "scale"), c_f32,
                              _kernel(variant), _stream_ptr(stream)))
@@ -240,11 +269,12 @@ def dg_conv2d_lut(lut: Lut, Wp, Xp, desc: ConvDesc, out=None, scale=None, varian
     import torch
     OH = dg_conv_out_dim(desc.H, desc.KH, desc.stride_h, desc.pad_h)
     OW = dg_conv_out_dim(desc.W, desc.KW, desc.stride_w, desc.pad_w)
-    dtype = torch.float32 if scale is not None else torch.int32
+    as_float = scale is not None or lut.is_f32
+    dtype = torch.float32 if as_float else torch.int32
     if out is None:
         out = torch.empty((desc.B, max(OH, 0), max(OW, 0), desc.Cout), dtype=dtype, device=Wp.device)
-    y_int = _dev_ptr(out, torch.int32, "out") if scale is None else ctypes.c_void_p(0)
-    y_f32 = _dev_ptr(out, torch.float32, "out") if scale is not None else ctypes.c_void_p(0)
+    y_int = _dev_ptr(out, torch.int32, "out") if not as_float else ctypes.c_void_p(0)
+    y_f32 = _dev_ptr(out, torch.float32, "out") if as_float else ctypes.c_void_p(0)
     _check(lib().dg_conv2d_lut(lut.handle, _dev_ptr(Wp, torch.uint8, "Wp"), _dev_ptr(Xp, torch.uint8, "Xp"),
                                ctypes.byref(desc), y_int, _dev_ptr(scale, torch.float32, "scale"), y_f32,
                                _kernel(variant), _stream_ptr(stream)))

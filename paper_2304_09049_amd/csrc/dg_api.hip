@@ -66,6 +66,7 @@ dg_status dg_build_lut_bits(int32_t bits, const int8_t *levels_w, const int8_t *
     memset(&t, 0, sizeof(t));
     t.bits = bits;
     t.dtype = entry;
+    t.separable = true;
     t.min_entry = INT32_MAX;
     t.max_entry = INT32_MIN;
     for (int w = 0; w < nlev; ++w) {
@@ -95,11 +96,66 @@ dg_status dg_lut_entries(const dg_lut *lut, int16_t out16[16])
 {
     if (!lut || !out16) return dg_fail(DG_ERR_NULL, "dg_lut_entries: NULL argument");
     if (lut->bits != 2) return dg_fail(DG_ERR_UNSUPPORTED, "dg_lut_entries: a %d-bit table has more than 16 entries", lut->bits);
+    if (lut->dtype == DG_LUT_F32) return dg_fail(DG_ERR_UNSUPPORTED, "dg_lut_entries: a binary32 table (use dg_lut_entries_f32)");
     for (int i = 0; i < 16; ++i) out16[i] = lut->entry[i];
     return DG_OK;
 }
 
 int32_t dg_lut_bits(const dg_lut *lut) { return lut ? lut->bits : 0; }
+
+dg_status dg_build_lut_entries(const int16_t entries[16], dg_lut_dtype entry, dg_lut **out)
+{
+    if (!entries || !out) return dg_fail(DG_ERR_NULL, "dg_build_lut_entries: NULL argument");
+    if (entry != DG_LUT_I8 && entry != DG_LUT_I16)
+        return dg_fail(DG_ERR_UNSUPPORTED, "dg_build_lut_entries: entry type %d is not an integer type", (int)entry);
+    dg_lut t;
+    memset(&t, 0, sizeof(t));
+    t.bits = 2;
+    t.dtype = entry;
+    t.separable = false;
+    t.min_entry = INT32_MAX;
+    t.max_entry = INT32_MIN;
+    for (int i = 0; i < 16; ++i) {
+        const int32_t v = entries[i];
+        if (entry == DG_LUT_I8 && (v < -128 || v > 127))
+            return dg_fail(DG_ERR_RANGE, "dg_build_lut_entries: entry %d = %d does not fit int8", i, v);
+        t.entry[i] = (int16_t)v;
+        if (v < t.min_entry) t.min_entry = v;
+        if (v > t.max_entry) t.max_entry = v;
+    }
+    t.max_abs = t.max_entry > -t.min_entry ? t.max_entry : -t.min_entry;
+    dg_lut *p = new (std::nothrow) dg_lut(t);
+    if (!p) return dg_fail(DG_ERR_BUFFER, "dg_build_lut_entries: out of host memory");
+    *out = p;
+    return DG_OK;
+}
+
+dg_status dg_build_lut_f32(const float levels_w[4], const float levels_a[4], dg_lut **out)
+{
+    if (!levels_w || !levels_a || !out) return dg_fail(DG_ERR_NULL, "dg_build_lut_f32: NULL argument");
+    dg_lut t;
+    memset(&t, 0, sizeof(t));
+    t.bits = 2;
+    t.dtype = DG_LUT_F32;
+    t.separable = true;
+    for (int w = 0; w < 4; ++w)
+        for (int a = 0; a < 4; ++a) {
+            volatile float prod = levels_w[w] * levels_a[a];     // one binary32 multiply, kept out of wider registers
+            t.fentry[4 * w + a] = prod;
+        }
+    dg_lut *p = new (std::nothrow) dg_lut(t);
+    if (!p) return dg_fail(DG_ERR_BUFFER, "dg_build_lut_f32: out of host memory");
+    *out = p;
+    return DG_OK;
+}
+
+dg_status dg_lut_entries_f32(const dg_lut *lut, float out[16])
+{
+    if (!lut || !out) return dg_fail(DG_ERR_NULL, "dg_lut_entries_f32: NULL argument");
+    if (lut->dtype != DG_LUT_F32) return dg_fail(DG_ERR_UNSUPPORTED, "dg_lut_entries_f32: an integer table");
+    for (int i = 0; i < 16; ++i) out[i] = lut->fentry[i];
+    return DG_OK;
+}
 
 dg_status dg_lut_entries_all(const dg_lut *lut, int16_t *out, int32_t count)
 {
@@ -192,16 +248,18 @@ int64_t dg_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad)
 
 namespace {
 
-enum class Pick { Perm, Lds, Mfma, SmallN, Lut65k, Unsupported };
+enum class Pick { Perm, Lds, LdsF32, Mfma, SmallN, Lut65k, Unsupported };
 
 Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
 {
     // 3- and 4-bit tables (64 / 256 entries) run on the plain LDS kernel only
+    if (lut->dtype == DG_LUT_F32)
+        return (variant == DG_KERNEL_AUTO || variant == DG_KERNEL_LDS) ? Pick::LdsF32 : Pick::Unsupported;
     if (lut->bits != 2) return (variant == DG_KERNEL_AUTO || variant == DG_KERNEL_LDS) ? Pick::Lds : Pick::Unsupported;
     switch (variant) {
     case DG_KERNEL_PERM: return dg_perm_supports(lut, p) ? Pick::Perm : Pick::Unsupported;
     case DG_KERNEL_LDS: return Pick::Lds;
-    case DG_KERNEL_MFMA_I8: return dg_mfma_supports(lut, p) ? Pick::Mfma : Pick::Unsupported;
+    case DG_KERNEL_MFMA_I8: return lut->separable && dg_mfma_supports(lut, p) ? Pick::Mfma : Pick::Unsupported;
     case DG_KERNEL_SMALLN: return dg_smalln_supports(lut, p) ? Pick::SmallN : Pick::Unsupported;
     case DG_KERNEL_LUT65K: return dg_lut65k_supports(lut, p) ? Pick::Lut65k : Pick::Unsupported;
     case DG_KERNEL_AUTO:
@@ -218,6 +276,7 @@ dg_status run(const dg_lut *lut, const DgProblem &p, dg_kernel variant, hipStrea
     switch (pick_kernel(lut, p, variant)) {
     case Pick::Perm: return dg_launch_perm(lut, p, stream);
     case Pick::Lds: return dg_launch_lds(lut, p, stream);
+    case Pick::LdsF32: return dg_launch_lds_f32(lut, p, stream);
     case Pick::Mfma: return dg_launch_mfma(lut, p, stream);
     case Pick::SmallN: return dg_launch_smalln(lut, p, stream);
     case Pick::Lut65k: return dg_launch_lut65k(lut, p, stream);
@@ -233,6 +292,7 @@ const char *pick_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     switch (pick_kernel(lut, p, variant)) {
     case Pick::Perm: return dg_perm_config_name(lut, p);
     case Pick::Lds: return "lds";
+    case Pick::LdsF32: return "lds_f32";
     case Pick::Mfma: return "mfma_i8";
     case Pick::SmallN: return "smalln";
     case Pick::Lut65k: return "lut65k";
@@ -243,8 +303,8 @@ const char *pick_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
 
 dg_status check_range(const char *name, const dg_lut *lut, int64_t K)
 {
-    // int32 accumulator: |sum| <= K * max|LUT| must stay below 2^31
-    if ((int64_t)lut->max_abs * K >= ((int64_t)1 << 31))
+    // int32 accumulator: |sum| <= K * max|LUT| must stay below 2^31 (binary32 tables have no such bound)
+    if (lut->dtype != DG_LUT_F32 && (int64_t)lut->max_abs * K >= ((int64_t)1 << 31))
         return dg_fail(DG_ERR_RANGE, "%s: K=%lld times max|LUT|=%d could overflow int32", name,
                        (long long)K, lut->max_abs);
     return DG_OK;
@@ -316,7 +376,8 @@ dg_status dg_gemm_lut(const dg_lut *lut, const void *Wp_dev, const void *Ap_dev,
     dg_status s = fill_gemm("dg_gemm_lut", lut, M, N, K, &p);
     if (s != DG_OK) return s;
     if (!Wp_dev || !Ap_dev) return dg_fail(DG_ERR_NULL, "dg_gemm_lut: NULL operand");
-    if (scale_m_dev ? !Cf_dev : !C_dev) return dg_fail(DG_ERR_NULL, "dg_gemm_lut: NULL output");
+    if ((scale_m_dev || lut->dtype == DG_LUT_F32) ? !Cf_dev : !C_dev)
+        return dg_fail(DG_ERR_NULL, "dg_gemm_lut: NULL output");
     if (stride_cm == 0 || stride_cn == 0) return dg_fail(DG_ERR_SHAPE, "dg_gemm_lut: zero output stride");
     p.Wp = (const uint8_t *)Wp_dev;
     p.Xp = (const uint8_t *)Ap_dev;
@@ -336,7 +397,8 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
     dg_status s = fill_conv("dg_conv2d_lut", lut, desc, &p);
     if (s != DG_OK) return s;
     if (!Wp_dev || !Xp_dev) return dg_fail(DG_ERR_NULL, "dg_conv2d_lut: NULL operand");
-    if (scale_cout_dev ? !Yf_dev : !Y_dev) return dg_fail(DG_ERR_NULL, "dg_conv2d_lut: NULL output");
+    if ((scale_cout_dev || lut->dtype == DG_LUT_F32) ? !Yf_dev : !Y_dev)
+        return dg_fail(DG_ERR_NULL, "dg_conv2d_lut: NULL output");
     p.Wp = (const uint8_t *)Wp_dev;
     p.Xp = (const uint8_t *)Xp_dev;
     p.C = Y_dev;

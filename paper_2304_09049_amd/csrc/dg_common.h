@@ -14,6 +14,8 @@ struct dg_lut {
     int8_t levels_a[16];
     int16_t entry[256];  // entry[(w << bits) | a] = levels_w[w] * levels_a[a]; 2^(2*bits) entries are used
     dg_lut_dtype dtype;
+    bool separable;      // built from level vectors (the matrix-core comparison kernel needs them)
+    float fentry[16];    // DG_LUT_F32 tables only: binary32 products of floating-point levels
     int32_t min_entry;   // smallest product
     int32_t max_entry;   // largest product
     int32_t max_abs;     // max |product|
@@ -49,6 +51,7 @@ dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits
 dg_status dg_launch_quantize_pack(const float *x, int64_t rows, int64_t K, float scale, float zero_point,
                                   int32_t lo, uint8_t *packed, hipStream_t stream);
 dg_status dg_launch_lds(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+dg_status dg_launch_lds_f32(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 bool dg_perm_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_perm(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 const char *dg_perm_config_name(const dg_lut *lut, const DgProblem &p);

@@ -77,6 +77,54 @@ lds_lut_kernel(DgProblem p, Table256 table)
         p.C[o] = acc;
 }
 
+// binary32 table: the sum is one binary32 addition per reduction position, in ascending k, starting from +0
+// (the compiler does not re-associate floating-point additions, so the source order is the arithmetic order).
+struct TableF32 {
+    float e[16];
+};
+
+template <typename WordT>
+__global__ void __launch_bounds__(256)
+lds_lut_f32_kernel(DgProblem p, TableF32 table)
+{
+    __shared__ float lut[16];
+    if (threadIdx.x < 16) lut[threadIdx.x] = table.e[threadIdx.x];
+    __syncthreads();
+
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)p.M * p.N) return;
+    const int m = (int)(t % p.M);
+    const int n = (int)(t / p.M);
+    const int ow = n % p.OW;
+    const int oh = (n / p.OW) % p.OH;
+    const int b = n / (p.OW * p.OH);
+
+    constexpr int WB = sizeof(WordT);
+    const int tap_bytes = p.Cin / 4;
+    const uint8_t *wrow = p.Wp + (int64_t)m * (p.K / 4);
+    float acc = 0.0f;
+    for (int kh = 0; kh < p.KH; ++kh) {
+        const int ih = oh * p.sh - p.ph + kh;
+        if (ih < 0 || ih >= p.H) continue;
+        for (int kw = 0; kw < p.KW; ++kw) {
+            const int iw = ow * p.sw - p.pw + kw;
+            if (iw < 0 || iw >= p.W) continue;
+            const WordT *x = (const WordT *)(p.Xp + (((int64_t)b * p.H + ih) * p.W + iw) * tap_bytes);
+            const WordT *w = (const WordT *)(wrow + (int64_t)(kh * p.KW + kw) * tap_bytes);
+            for (int j = 0; j < tap_bytes / WB; ++j) {
+                const uint32_t vw = w[j], va = x[j];
+#pragma unroll
+                for (int i = 0; i < 4 * WB; ++i) {
+                    const int shift = 2 * i;
+                    acc = __fadd_rn(acc, lut[(((vw >> shift) & 3u) << 2) | ((va >> shift) & 3u)]);
+                }
+            }
+        }
+    }
+    const int64_t o = (int64_t)m * p.stride_cm + (int64_t)n * p.stride_cn;
+    p.Cf[o] = p.scale ? __fmul_rn(acc, p.scale[m]) : acc;
+}
+
 template <int BITS>
 void launch_bits(const DgProblem &p, const Table256 &t, bool words, unsigned blocks, hipStream_t stream)
 {
@@ -106,4 +154,18 @@ dg_status dg_launch_lds(const dg_lut *lut, const DgProblem &p, hipStream_t strea
     default: launch_bits<4>(p, t, words, (unsigned)blocks, stream); break;
     }
     return dg_check_launch("lds_lut_kernel");
+}
+
+dg_status dg_launch_lds_f32(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
+{
+    TableF32 t;
+    for (int i = 0; i < 16; ++i) t.e[i] = lut->fentry[i];
+    const int64_t blocks = ((int64_t)p.M * p.N + 255) / 256;
+    if (blocks > INT32_MAX) return dg_fail(DG_ERR_UNSUPPORTED, "lds kernel: M*N too large for one grid");
+    const bool words = (p.Cin % 16 == 0) && ((uintptr_t)p.Wp % 4 == 0) && ((uintptr_t)p.Xp % 4 == 0);
+    if (words)
+        hipLaunchKernelGGL(lds_lut_f32_kernel<uint32_t>, dim3((unsigned)blocks), dim3(256), 0, stream, p, t);
+    else
+        hipLaunchKernelGGL(lds_lut_f32_kernel<uint8_t>, dim3((unsigned)blocks), dim3(256), 0, stream, p, t);
+    return dg_check_launch("lds_lut_f32_kernel");
 }

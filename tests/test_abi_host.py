@@ -144,3 +144,16 @@ def test_wide_tables_follow_table2():
     assert L.dg_build_lut_bits(1, lw, lw, 0, ctypes.byref(h)) == 5
     assert dg.dg_packed_bytes_bits(10, 8, 4) == 40 and dg.dg_packed_bytes_bits(10, 8, 3) == 40
     assert dg.dg_packed_bytes_bits(10, 8, 2) == 20 and dg.dg_packed_bytes_bits(10, 7, 4) == 0
+
+
+def test_tables_given_as_such():
+    entries = [3, -7, 100, 0, 5, 5, -128, 127, 1, 2, 3, 4, -1, -2, -3, -4]
+    assert dg.dg_build_lut_entries(entries, dg.DG_LUT_I8).entries() == entries
+    with pytest.raises(dg.DgError) as e:
+        dg.dg_build_lut_entries([200] + [0] * 15, dg.DG_LUT_I8)
+    assert e.value.status == 3
+    assert dg.dg_build_lut_entries([200] + [0] * 15, dg.DG_LUT_I16).entries()[0] == 200
+    import numpy as np
+    lw, la = np.array([0.1, -0.37, 1.5, 3.0e-3], np.float32), np.array([0.0, 0.7, 1.9, 2.25], np.float32)
+    got = np.array(dg.dg_build_lut_f32(lw, la).entries(), dtype=np.float32)
+    assert np.array_equal(got, (lw[:, None] * la[None, :]).astype(np.float32).reshape(-1))   # one float32 multiply each

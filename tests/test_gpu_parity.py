@@ -330,3 +330,64 @@ def test_wide_codes_gemm_and_conv(bits):
     y = dg.dg_conv2d_lut(lut, Wp, Xp, dg.conv_desc(B, H, W, Cin, Cout, 3, 3, (2, 1), (1, 1)))
     torch.cuda.synchronize()
     _assert_same(y.cpu().numpy(), oracle.conv2d(Wc, Xc, lw, la, stride=(2, 1), pad=(1, 1)), f"{bits}-bit conv")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_non_separable_table(variant):
+    # any 16 integers are a valid table (the table stores results, Sec. 5.3); the matrix-core comparison declines
+    rng = np.random.default_rng(60)
+    for lo, hi, entry in ((-3, 4, dg.DG_LUT_I8), (-100, 100, dg.DG_LUT_I8), (-3000, 3000, dg.DG_LUT_I16)):
+        table = rng.integers(lo, hi, size=16)
+        lut = dg.dg_build_lut_entries(table, entry)
+        g = wl.small_gemm(70, 130, 192, seed=61)
+        Wp = dg.dg_pack_weights(torch.from_numpy(g.Wc).cuda(), 70, 192)
+        Ap = dg.dg_pack_activations(torch.from_numpy(g.Ac).cuda(), 130, 192)
+        try:
+            got = dg.dg_gemm_lut(lut, Wp, Ap, 70, 130, 192, variant=variant)
+        except dg.DgError as e:
+            assert e.status == 5 and variant not in ("auto", "lds")
+            continue
+        assert variant != "mfma_i8"
+        torch.cuda.synchronize()
+        _assert_same(got.cpu().numpy(), oracle.gemm_table(g.Wc, g.Ac, table), f"table {lo}..{hi} {variant}")
+        c = wl.small_conv(2, 13, 11, 64, 24, 3, 3, (1, 1), (1, 1), seed=62)
+        Wp = dg.dg_pack_weights(torch.from_numpy(c.Wc).cuda(), 24, 576)
+        Xp = dg.dg_pack_activations(torch.from_numpy(c.Ac).cuda(), 2 * 13 * 11, 64)
+        try:
+            y = dg.dg_conv2d_lut(lut, Wp, Xp, dg.conv_desc(2, 13, 11, 64, 24, 3, 3, (1, 1), (1, 1)), variant=variant)
+        except dg.DgError as e:
+            assert e.status == 5 and variant not in ("auto", "lds")     # e.g. the small-N kernel takes no 3x3 filter
+            continue
+        torch.cuda.synchronize()
+        _assert_same(y.cpu().numpy(), oracle.conv2d_table(c.Wc, c.Ac, table, pad=(1, 1)), f"table conv {variant}")
+
+
+def test_f32_table():
+    # binary32 products of floating-point levels, summed in binary32 in ascending k: expected to match bit for bit
+    lw = np.array([-0.731, -0.204, 0.118, 0.655], np.float32)
+    la = np.array([0.0, 0.391, 0.874, 1.62], np.float32)
+    lut = dg.dg_build_lut_f32(lw, la)
+    table = oracle.build_lut_f32(lw, la)
+    assert np.array_equal(np.array(lut.entries(), np.float32), table)
+    g = wl.small_gemm(33, 57, 320, seed=63)
+    Wp = dg.dg_pack_weights(torch.from_numpy(g.Wc).cuda(), 33, 320)
+    Ap = dg.dg_pack_activations(torch.from_numpy(g.Ac).cuda(), 57, 320)
+    got = dg.dg_gemm_lut(lut, Wp, Ap, 33, 57, 320)
+    torch.cuda.synchronize()
+    want = oracle.gemm_table_f32(g.Wc, g.Ac, table)
+    assert got.dtype == torch.float32 and dg.dg_gemm_kernel_name(lut, 33, 57, 320) == "lds_f32"
+    np.testing.assert_allclose(got.cpu().numpy(), want, rtol=1e-6, atol=0)
+    assert np.array_equal(got.cpu().numpy(), want)
+    c = wl.small_conv(2, 9, 8, 16, 10, 3, 3, (1, 2), (1, 1), seed=64, scale=True)
+    Wp = dg.dg_pack_weights(torch.from_numpy(c.Wc).cuda(), 10, 144)
+    Xp = dg.dg_pack_activations(torch.from_numpy(c.Ac).cuda(), 2 * 9 * 8, 16)
+    desc = dg.conv_desc(2, 9, 8, 16, 10, 3, 3, (1, 2), (1, 1))
+    y = dg.dg_conv2d_lut(lut, Wp, Xp, desc)
+    ys = dg.dg_conv2d_lut(lut, Wp, Xp, desc, scale=torch.from_numpy(c.scale).cuda())
+    torch.cuda.synchronize()
+    want = oracle.conv2d_table_f32(c.Wc, c.Ac, table, stride=(1, 2), pad=(1, 1))
+    assert np.array_equal(y.cpu().numpy(), want)
+    assert np.array_equal(ys.cpu().numpy(), want * c.scale[None, None, None, :])
+    with pytest.raises(dg.DgError) as e:
+        dg.dg_conv2d_lut(lut, Wp, Xp, desc, variant="perm")
+    assert e.value.status == 5
