@@ -309,7 +309,7 @@ def main():
         sweep = []
         for wname, ww in wl.CONFIGS.items():
             rr = r if ww is w else Runner(ww, "auto")
-            for variant in ("auto", "mfma_i8", "lut65k", "lds"):
+            for variant in ("auto", "onehot_mfma", "mfma_i8", "lut65k", "lds"):
                 if variant in ("lds", "lut65k") and ww.ops > 1e11:
                     continue
                 try:

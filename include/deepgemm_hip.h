@@ -151,6 +151,8 @@ dg_status dg_quantize_pack_activations(const float *x_dev, int64_t N, int64_t K,
  *   SMALLN   table kernel for few activation rows: K split across lanes + wavefront reduction
  *   LUT65K   the paper's second table (Sec. 3 "LUT-65k"): one entry per (weight byte, activation byte) holding
  *            the dot product of the four code pairs, kept in LDS; one fetch per four products
+ *   ONEHOT_MFMA  table kernel on the matrix cores: each int8 MFMA multiply is by a one-hot byte of the activation
+ *            code, i.e. it selects one entry of the weight code's table row; any 16 int8 entries, 4x the MFMA work
  * A variant that cannot run the given shape or table returns DG_ERR_UNSUPPORTED.
  */
 typedef enum {
@@ -159,7 +161,8 @@ typedef enum {
     DG_KERNEL_LDS = 2,
     DG_KERNEL_MFMA_I8 = 3,
     DG_KERNEL_SMALLN = 4,
-    DG_KERNEL_LUT65K = 5
+    DG_KERNEL_LUT65K = 5,
+    DG_KERNEL_ONEHOT_MFMA = 6
 } dg_kernel;
 
 /*

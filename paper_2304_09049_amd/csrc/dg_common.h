@@ -59,5 +59,7 @@ bool dg_mfma_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_mfma(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 bool dg_lut65k_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_lut65k(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+bool dg_onehot_supports(const dg_lut *lut, const DgProblem &p);
+dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 bool dg_smalln_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_smalln(const dg_lut *lut, const DgProblem &p, hipStream_t stream);

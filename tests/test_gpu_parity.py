@@ -14,7 +14,7 @@ from gpu_helpers import GpuCase, run_or_unsupported
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = ["auto", "lds", "perm", "mfma_i8", "smalln", "lut65k"]
+VARIANTS = ["auto", "lds", "perm", "mfma_i8", "smalln", "lut65k", "onehot_mfma"]
 
 LEVELS = {
     "signed_unsigned": ((-2, -1, 0, 1), (0, 1, 2, 3), dg.DG_LUT_I8),
