@@ -53,7 +53,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default=None, help="name in workloads.CONFIGS (default: the headline conv)")
-    ap.add_argument("--variant", default="auto", help="auto | perm | lds | mfma_i8 | smalln")
+    ap.add_argument("--variant", default="auto", help="auto | perm | lds | mfma_i8 | smalln | lut65k | onehot_mfma")
     ap.add_argument("--no-graph", action="store_true", help="launch every step from the host instead of a HIP graph")
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-workload kernel sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
