@@ -265,10 +265,12 @@ Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case DG_KERNEL_ONEHOT_MFMA: return dg_onehot_supports(lut, p) ? Pick::OneHot : Pick::Unsupported;
     case DG_KERNEL_AUTO:
         // AUTO stays within the table kernels: the decode-and-multiply matrix-core kernel is a comparison only.
+        // one or two columns: K across the lanes of a wavefront streams the weights once at full width
+        if (p.N <= 2 && p.K >= 1024 && dg_smalln_supports(lut, p)) return Pick::SmallN;
+        // int8 tables: selecting entries with one-hot operands on the matrix cores outruns the permute loop at every
+        // size measured (1.5x on a 0.2 GOP layer, 5x - 10x from 3 GOP upwards)
+        if (dg_onehot_supports(lut, p)) return Pick::OneHot;
         if (p.N <= 32 && p.K >= 1024 && dg_smalln_supports(lut, p)) return Pick::SmallN;
-        // large layers: selecting table entries with one-hot operands on the matrix cores outruns the permute
-        // loop (measured 1.5x - 7x from 3 GOP upwards); small ones are latency-bound and stay on the permute kernel
-        if (p.N >= 256 && 2.0 * p.M * p.N * p.K >= 2e9 && dg_onehot_supports(lut, p)) return Pick::OneHot;
         if (dg_perm_supports(lut, p)) return Pick::Perm;
         return Pick::Lds;
     }

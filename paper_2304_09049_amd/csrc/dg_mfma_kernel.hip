@@ -12,12 +12,12 @@
 // pixel, prefetched one chunk ahead), there is no LDS staging and no barrier.  Integer sums do not
 // depend on the order of the reduction, so the kernel assigns reduction positions to MFMA operand
 // bytes in whatever order makes the loads contiguous; both operands use the same assignment.
-#include "dg_common.h"
+#include "dg_mfma_tile.h"
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
+typedef dg_v4i v4i;
+typedef dg_v16i v16i;
 
 struct MfmaArgs {
     DgProblem p;
@@ -59,7 +59,7 @@ __device__ __forceinline__ v4i decode(uint32_t word, uint32_t levels, uint32_t a
     return r;
 }
 
-template <int WM, int WN, int CH>
+template <int WM, int WN, int CH, bool TR>
 __global__ void __launch_bounds__(256)
 mfma_i8_kernel(MfmaArgs a)
 {
@@ -113,8 +113,10 @@ mfma_i8_kernel(MfmaArgs a)
 #pragma unroll
         for (int bn = 0; bn < WN; ++bn) {
             const int ih = x_ih0[bn] + kh, iw = x_iw0[bn] + kw;
-            vb[bn] = x_ok[bn] && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-            wb[bn] = load_words<CH>(p.Xp + x_off0[bn] + tap_off, vb[bn]);
+            vb[bn] = x_ok[bn] & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
+            // always load (a tap outside the image reads the first pixel instead and is masked later): a load under
+            // a branch would make the compiler wait for it at once, and the prefetch would hide nothing
+            wb[bn] = load_words<CH>(vb[bn] ? p.Xp + x_off0[bn] + tap_off : p.Xp + h * (4 * CH), true);
         }
         ci += CHUNK;
         if (ci == p.Cin) {
@@ -139,7 +141,7 @@ mfma_i8_kernel(MfmaArgs a)
             am[bn] = vb[bn] ? 0x03030303u : 0u;
             om[bn] = vb[bn] ? 0u : 0x0C0C0C0Cu;
         }
-        if (c + 1 < chunks) fetch(c + 1);
+        fetch(c + 1 < chunks ? c + 1 : c);                  // unconditional (the last one re-reads in bounds and is unused)
 #pragma unroll
         for (int s = 0; s < CH; ++s) {
             v4i fa[WM], fb[WN];
@@ -151,39 +153,33 @@ mfma_i8_kernel(MfmaArgs a)
             for (int bm = 0; bm < WM; ++bm)
 #pragma unroll
                 for (int bn = 0; bn < WN; ++bn)
-                    acc[bm][bn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[bm], fb[bn], acc[bm][bn], 0, 0, 0);
+                    acc[bm][bn] = dg_mfma_step<TR>(fa[bm], fb[bn], acc[bm][bn]);
         }
     }
 
-    // 32x32 accumulator layout: lane holds column (lane % 32) and rows 8*(e/4) + 4*(lane/32) + e%4, e = 0..15
-#pragma unroll
-    for (int bn = 0; bn < WN; ++bn) {
-        const int n = n0 + bn * 32 + r;
-        if (n >= p.N) continue;
-#pragma unroll
-        for (int bm = 0; bm < WM; ++bm)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m0 + bm * 32 + 8 * (e / 4) + 4 * h + (e % 4);
-                if (m >= p.M) continue;
-                const int64_t o = (int64_t)m * p.stride_cm + (int64_t)n * p.stride_cn;
-                if (p.scale)
-                    p.Cf[o] = (float)acc[bm][bn][e] * p.scale[m];
-                else
-                    p.C[o] = acc[bm][bn][e];
-            }
-    }
+    dg_mfma_store_tile<WM, WN, TR>(p, acc, m0, n0, lane);
 }
 
-template <int WM, int WN>
+template <int WM, int WN, bool TR>
 void launch_ch(const MfmaArgs &a, int ch, dim3 grid, hipStream_t stream)
 {
     if (ch == 4)
-        hipLaunchKernelGGL((mfma_i8_kernel<WM, WN, 4>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((mfma_i8_kernel<WM, WN, 4, TR>), grid, dim3(256), 0, stream, a);
     else if (ch == 2)
-        hipLaunchKernelGGL((mfma_i8_kernel<WM, WN, 2>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((mfma_i8_kernel<WM, WN, 2, TR>), grid, dim3(256), 0, stream, a);
     else
-        hipLaunchKernelGGL((mfma_i8_kernel<WM, WN, 1>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((mfma_i8_kernel<WM, WN, 1, TR>), grid, dim3(256), 0, stream, a);
+}
+
+template <bool TR>
+void launch_tile(const MfmaArgs &a, int wm, int wn, int ch, dim3 grid, hipStream_t stream)
+{
+    if (wm == 4)
+        launch_ch<4, 4, TR>(a, ch, grid, stream);
+    else if (wn == 4)
+        launch_ch<2, 4, TR>(a, ch, grid, stream);
+    else
+        launch_ch<2, 1, TR>(a, ch, grid, stream);
 }
 
 }   // namespace
@@ -218,11 +214,10 @@ dg_status dg_launch_mfma(const dg_lut *lut, const DgProblem &p, hipStream_t stre
     const int64_t blocks = (a.wave_tiles + 3) / 4;
     if (blocks > INT32_MAX) return dg_fail(DG_ERR_UNSUPPORTED, "mfma kernel: too many tiles for one grid");
     const dim3 grid((unsigned)blocks);
-    if (wm == 4)
-        launch_ch<4, 4>(a, ch, grid, stream);
-    else if (wn == 4)
-        launch_ch<2, 4>(a, ch, grid, stream);
+    // the output axis with stride 1 goes on the MFMA columns (see dg_mfma_tile.h)
+    if (p.stride_cm == 1 && p.stride_cn != 1)
+        launch_tile<true>(a, wm, wn, ch, grid, stream);
     else
-        launch_ch<2, 1>(a, ch, grid, stream);
+        launch_tile<false>(a, wm, wn, ch, grid, stream);
     return dg_check_launch("mfma_i8_kernel");
 }

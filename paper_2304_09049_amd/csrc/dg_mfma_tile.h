@@ -1,0 +1,48 @@
+// Accumulator tiles of v_mfma_i32_32x32x32_i8 and their way to memory, shared by the two matrix-core kernels.
+//
+// A 32x32 accumulator block lives in 16 registers per lane: the lane holds MFMA column (lane % 32) and MFMA rows
+// 8*(e/4) + 4*(lane/32) + e%4, e = 0..15.  Which problem axis sits on the MFMA columns is the kernel's choice (the two
+// operands have the same lane layout, so swapping them transposes the block): the axis whose output stride is 1
+// goes on the columns, so that the 32 lanes of a half wavefront store 128 contiguous bytes.
+//   TR == false: MFMA rows = m, columns = n  (acc = mfma(weights, activations)) -- row-major GEMM output, n contiguous
+//   TR == true : MFMA rows = n, columns = m  (acc = mfma(activations, weights)) -- NHWC convolution output, m contiguous
+#pragma once
+
+#include "dg_common.h"
+
+typedef int dg_v4i __attribute__((ext_vector_type(4)));
+typedef int dg_v16i __attribute__((ext_vector_type(16)));
+
+template <bool TR>
+__device__ __forceinline__ dg_v16i dg_mfma_step(dg_v4i w, dg_v4i x, dg_v16i acc)
+{
+    return TR ? __builtin_amdgcn_mfma_i32_32x32x32_i8(x, w, acc, 0, 0, 0)
+              : __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, acc, 0, 0, 0);
+}
+
+// Store the (WM*32) x (WN*32) tile at (m0, n0): int32 as it is, or float(acc) * scale[m] (one conversion, one multiply).
+template <int WM, int WN, bool TR>
+__device__ __forceinline__ void dg_mfma_store_tile(const DgProblem &p, const dg_v16i (&acc)[WM][WN], int m0, int n0,
+                                                   int lane)
+{
+    const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int bm = 0; bm < WM; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < WN; ++bn) {
+            const int col = TR ? m0 + bm * 32 + r : n0 + bn * 32 + r;
+            if (col >= (TR ? p.M : p.N)) continue;
+            const float sc = (TR && p.scale) ? p.scale[col] : 0.0f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = (TR ? n0 + bn * 32 : m0 + bm * 32) + 8 * (e / 4) + 4 * h + (e % 4);
+                if (row >= (TR ? p.N : p.M)) continue;
+                const int m = TR ? col : row, n = TR ? row : col;
+                const int64_t o = (int64_t)m * p.stride_cm + (int64_t)n * p.stride_cn;
+                if (p.scale)
+                    p.Cf[o] = (float)acc[bm][bn][e] * (TR ? sc : p.scale[m]);
+                else
+                    p.C[o] = acc[bm][bn][e];
+            }
+        }
+}

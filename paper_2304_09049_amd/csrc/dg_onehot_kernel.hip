@@ -8,21 +8,26 @@
 // MFMA unit SELECTS one table entry per reduction position and adds it.  Four times the MFMA work of the
 // rank-1 decode kernel, but every table is accepted and the VALU only expands codes.
 //
-// Expansion: a packed byte holds two nibbles = two code pairs; an LDS table maps a weight nibble to its two rows
-// (8 bytes) and an activation nibble to its two one-hot quadruples (8 bytes), so a lane builds a 16-byte MFMA
-// operand (4 reduction positions) from one packed byte with two 64-bit LDS reads.  A second, all-zero table
-// stands in for filter taps outside the image.  Wave tiles, global loads and the epilogue follow the
-// comparison kernel: each wave owns (WM*32) x (WN*32) outputs, no barrier after the tables are written.
-#include "dg_common.h"
+// Expansion, without LDS: the order of the 4K axis is free as long as both operands use the same one, so the 16 operand
+// bytes of a lane are laid out value-major: dword v holds, for 4 reduction positions, T[w(k)][v] (weights) or
+// [a(k) == v] (activations).  With the four 2-bit codes spread into the bytes of a selector word
+// ((word >> 2j) & 0x03030303 takes code j of each of a word's four bytes), each operand dword is ONE byte permute:
+// of the table's column v for the weights, of the constant 1 << 8v for the activations.  A filter tap outside the
+// image gets selector bytes 4 (the permute's upper, all-zero source), so it selects nothing.
+// Wave tiles, global loads and the epilogue follow the comparison kernel: each wave owns (WM*32) x (WN*32) outputs,
+// operands come straight from global memory, and there is no LDS and no barrier.
+#include <cstdlib>
+
+#include "dg_mfma_tile.h"
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
+typedef dg_v4i v4i;
+typedef dg_v16i v16i;
 
 struct OneHotArgs {
     DgProblem p;
-    uint32_t rows[4];        // rows[w] = bytes T[w][0..3] (signed int8, as stored)
+    uint32_t cols[4];        // cols[v] = bytes T[0..3][v] (signed int8, as stored): the permute pool of value v
     int32_t tiles_m;
     int64_t wave_tiles;
 };
@@ -48,30 +53,21 @@ __device__ __forceinline__ Words<CH> load_words(const uint8_t *ptr, bool ok)
     return w;
 }
 
-// one packed byte (4 codes) -> 16 operand bytes: two table reads of 8 bytes each
-__device__ __forceinline__ v4i expand_byte(const uint2 *table, uint32_t byte)
+// selector word of 4 reduction positions -> the 4 operand dwords (one per activation value v)
+__device__ __forceinline__ v4i select4(uint32_t p0, uint32_t p1, uint32_t p2, uint32_t p3, uint32_t sel)
 {
-    const uint2 lo = table[byte & 15u], hi = table[byte >> 4];
     v4i r;
-    r[0] = (int)lo.x, r[1] = (int)lo.y, r[2] = (int)hi.x, r[3] = (int)hi.y;
+    r[0] = (int)__builtin_amdgcn_perm(0u, p0, sel);
+    r[1] = (int)__builtin_amdgcn_perm(0u, p1, sel);
+    r[2] = (int)__builtin_amdgcn_perm(0u, p2, sel);
+    r[3] = (int)__builtin_amdgcn_perm(0u, p3, sel);
     return r;
 }
 
-template <int WM, int WN, int CH>
-__global__ void __launch_bounds__(256)
+template <int WM, int WN, int CH, bool TR>
+__global__ void __launch_bounds__(256, 2)
 onehot_mfma_kernel(OneHotArgs a)
 {
-    // [0..15] weight nibble -> {row[w even], row[w odd]}; [16..31] activation nibble -> one-hot quadruples;
-    // [32..47] zeros (a tap outside the image selects nothing)
-    __shared__ uint2 s_table[48];
-    if (threadIdx.x < 16) {
-        const int t = threadIdx.x;
-        s_table[t] = make_uint2(a.rows[t & 3], a.rows[t >> 2]);
-        s_table[16 + t] = make_uint2(1u << (8 * (t & 3)), 1u << (8 * (t >> 2)));
-        s_table[32 + t] = make_uint2(0u, 0u);
-    }
-    __syncthreads();
-
     const DgProblem &p = a.p;
     const int lane = threadIdx.x & 63;
     const int64_t wave_tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -121,8 +117,10 @@ onehot_mfma_kernel(OneHotArgs a)
 #pragma unroll
         for (int bn = 0; bn < WN; ++bn) {
             const int ih = x_ih0[bn] + kh, iw = x_iw0[bn] + kw;
-            vb[bn] = x_ok[bn] && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-            wb[bn] = load_words<CH>(p.Xp + x_off0[bn] + tap_off, vb[bn]);
+            vb[bn] = x_ok[bn] & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
+            // always load (a tap outside the image reads the first pixel instead and is masked later): a load under
+            // a branch would make the compiler wait for it at once, and the prefetch would hide nothing
+            wb[bn] = load_words<CH>(vb[bn] ? p.Xp + x_off0[bn] + tap_off : p.Xp + h * (4 * CH), true);
         }
         ci += CHUNK;
         if (ci == p.Cin) {
@@ -138,61 +136,184 @@ onehot_mfma_kernel(OneHotArgs a)
     fetch(0);
     for (int c = 0; c < chunks; ++c) {
         Words<CH> ca[WM], cb[WN];
-        const uint2 *tb[WN];
+        uint32_t pad[WN];
 #pragma unroll
         for (int bm = 0; bm < WM; ++bm) ca[bm] = wa[bm];
 #pragma unroll
         for (int bn = 0; bn < WN; ++bn) {
             cb[bn] = wb[bn];
-            tb[bn] = s_table + (vb[bn] ? 16 : 32);
+            pad[bn] = vb[bn] ? 0u : 0x04040404u;
         }
-        if (c + 1 < chunks) fetch(c + 1);
+        fetch(c + 1 < chunks ? c + 1 : c);                  // unconditional (the last one re-reads in bounds and is unused)
+        // Step t (word t/4, code t%4 of its four bytes) is one MFMA step.  The operands of step t+1 are built between
+        // the MFMAs of step t so that the matrix unit and the VALU of a single
+        // wavefront overlap; the scheduling groups pin that interleaving.
+        constexpr int T = 4 * CH;
+        v4i fa[2][WM], fb[2][WN];
+        auto expand = [&](int t, int u, int buf) {           // operand u of step t: u < WM weights, else activations
+            const int sw = t / 4, sh = 2 * (t % 4);
+            if (u < WM)
+                fa[buf][u] = select4(a.cols[0], a.cols[1], a.cols[2], a.cols[3], (ca[u].v[sw] >> sh) & 0x03030303u);
+            else
+                fb[buf][u - WM] = select4(0x00000001u, 0x00000100u, 0x00010000u, 0x01000000u,
+                                          ((cb[u - WM].v[sw] >> sh) & 0x03030303u) | pad[u - WM]);
+        };
 #pragma unroll
-        for (int s = 0; s < CH; ++s) {
+        for (int u = 0; u < WM + WN; ++u) expand(0, u, 0);
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {                    // one packed byte = 4 reduction positions = one MFMA step
-                v4i fa[WM], fb[WN];
+        for (int t = 0; t < T; ++t) {
+            const int cur = t & 1;
 #pragma unroll
-                for (int bm = 0; bm < WM; ++bm) fa[bm] = expand_byte(s_table, (ca[bm].v[s] >> (8 * b)) & 0xFFu);
+            for (int i = 0; i < WM * WN; ++i) {
+                const int bm = i / WN, bn = i % WN;
+                acc[bm][bn] = dg_mfma_step<TR>(fa[cur][bm], fb[cur][bn], acc[bm][bn]);
+                // the WM + WN operands of the next step are spread evenly over the WM * WN MFMAs of this one
+                constexpr int U = WM + WN, MN = WM * WN;
+                const int u0 = i * U / MN, u1 = (i + 1) * U / MN;
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                         // one MFMA ...
+                if (t + 1 < T) {
 #pragma unroll
-                for (int bn = 0; bn < WN; ++bn) fb[bn] = expand_byte(tb[bn], (cb[bn].v[s] >> (8 * b)) & 0xFFu);
-#pragma unroll
-                for (int bm = 0; bm < WM; ++bm)
-#pragma unroll
-                    for (int bn = 0; bn < WN; ++bn)
-                        acc[bm][bn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[bm], fb[bn], acc[bm][bn], 0, 0, 0);
+                    for (int u = u0; u < u1; ++u) expand(t + 1, u, cur ^ 1);
+                    if (u1 - u0 == 1) __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);   // ... then that VALU work
+                    if (u1 - u0 == 2) __builtin_amdgcn_sched_group_barrier(0x002, 12, 0);
+                }
             }
         }
     }
 
-#pragma unroll
-    for (int bn = 0; bn < WN; ++bn) {
-        const int n = n0 + bn * 32 + r;
-        if (n >= p.N) continue;
-#pragma unroll
-        for (int bm = 0; bm < WM; ++bm)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m0 + bm * 32 + 8 * (e / 4) + 4 * h + (e % 4);
-                if (m >= p.M) continue;
-                const int64_t o = (int64_t)m * p.stride_cm + (int64_t)n * p.stride_cn;
-                if (p.scale)
-                    p.Cf[o] = (float)acc[bm][bn][e] * p.scale[m];
-                else
-                    p.C[o] = acc[bm][bn][e];
-            }
-    }
+    dg_mfma_store_tile<WM, WN, TR>(p, acc, m0, n0, lane);
 }
 
-template <int WM, int WN>
+template <int WM, int WN, bool TR>
 void launch_ch(const OneHotArgs &a, int ch, dim3 grid, hipStream_t stream)
 {
     if (ch == 4)
-        hipLaunchKernelGGL((onehot_mfma_kernel<WM, WN, 4>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((onehot_mfma_kernel<WM, WN, 4, TR>), grid, dim3(256), 0, stream, a);
     else if (ch == 2)
-        hipLaunchKernelGGL((onehot_mfma_kernel<WM, WN, 2>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((onehot_mfma_kernel<WM, WN, 2, TR>), grid, dim3(256), 0, stream, a);
     else
-        hipLaunchKernelGGL((onehot_mfma_kernel<WM, WN, 1>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((onehot_mfma_kernel<WM, WN, 1, TR>), grid, dim3(256), 0, stream, a);
+}
+
+template <bool TR>
+void launch_wn(const OneHotArgs &a, int wn, int ch, dim3 grid, hipStream_t stream)
+{
+    if (wn == 4)
+        launch_ch<2, 4, TR>(a, ch, grid, stream);
+    else if (wn == 2)
+        launch_ch<2, 2, TR>(a, ch, grid, stream);
+    else
+        launch_ch<2, 1, TR>(a, ch, grid, stream);
+}
+
+// Small layers: too few 64 x 32 tiles to occupy the chip, and a wavefront that walks all of K alone pays the memory
+// latency once per chunk.  Here a workgroup owns ONE 32 x 32 output block and its S wavefronts split K between them
+// (whole chunks of 32*CH reduction positions each), so a layer with T blocks puts T*S wavefronts in flight and each
+// of them waits for memory once or twice.  Partial blocks meet in LDS: every wavefront writes its 16 accumulator
+// registers, one barrier, then the threads add the S partials of each output element (integer, so exact in any order)
+// and store it -- 128 contiguous bytes per half wavefront, as in the large-layer kernel.
+struct OneHotSplitArgs {
+    DgProblem p;
+    uint32_t cols[4];
+    int32_t tiles_m;
+    int32_t chunks;          // K / (32*CH)
+    int32_t cpw;             // chunks per wavefront
+};
+
+template <int CH, bool TR>
+__global__ void __launch_bounds__(1024)
+onehot_splitk_kernel(OneHotSplitArgs a)
+{
+    extern __shared__ int32_t s_part[];                     // [S][16][64]
+    const DgProblem &p = a.p;
+    const int lane = threadIdx.x & 63, ws = threadIdx.x >> 6, S = blockDim.x >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int m0 = ((int)blockIdx.x % a.tiles_m) * 32;
+    const int n0 = ((int)blockIdx.x / a.tiles_m) * 32;
+    const int cq = p.Cin / 4;
+    constexpr int CHUNK = 32 * CH;
+    const int c0 = ws * a.cpw, c1 = min(c0 + a.cpw, a.chunks);
+
+    v16i acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0;
+
+    if (c0 < c1) {
+        const int m = min(m0 + r, p.M - 1);
+        const uint8_t *w_ptr = p.Wp + (int64_t)m * (p.K / 4) + h * (4 * CH);
+        const int n = n0 + r;
+        const bool x_ok = n < p.N;
+        const int nn = x_ok ? n : 0;
+        const int ow = nn % p.OW, oh = (nn / p.OW) % p.OH, b = nn / (p.OW * p.OH);
+        const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+        const int64_t x_off0 = (((int64_t)b * p.H + ih0) * p.W + iw0) * cq + h * (4 * CH);
+        // filter tap of this wavefront's first chunk
+        const int pos = c0 * CHUNK, tap = pos / p.Cin;
+        int ci = pos - tap * p.Cin, kh = tap / p.KW, kw = tap - (tap / p.KW) * p.KW;
+
+        Words<CH> wa, wb;
+        bool vb;
+        auto fetch = [&](int chunk) {
+            wa = load_words<CH>(w_ptr + (int64_t)chunk * (CHUNK / 4), true);
+            const int ih = ih0 + kh, iw = iw0 + kw;
+            vb = x_ok & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
+            const int64_t tap_off = ((int64_t)kh * p.W + kw) * cq + ci / 4;
+            wb = load_words<CH>(vb ? p.Xp + x_off0 + tap_off : p.Xp + h * (4 * CH), true);
+            ci += CHUNK;
+            if (ci == p.Cin) {
+                ci = 0;
+                if (++kw == p.KW) {
+                    kw = 0;
+                    ++kh;
+                }
+            }
+        };
+        fetch(c0);
+        for (int c = c0; c < c1; ++c) {
+            const Words<CH> ca = wa, cb = wb;
+            const uint32_t pad = vb ? 0u : 0x04040404u;
+            fetch(c + 1 < c1 ? c + 1 : c);                  // unconditional (the last one re-reads in bounds and is unused)
+#pragma unroll
+            for (int t = 0; t < 4 * CH; ++t) {
+                const int sw = t / 4, sh = 2 * (t % 4);
+                const v4i fa = select4(a.cols[0], a.cols[1], a.cols[2], a.cols[3], (ca.v[sw] >> sh) & 0x03030303u);
+                const v4i fb = select4(0x00000001u, 0x00000100u, 0x00010000u, 0x01000000u,
+                                       ((cb.v[sw] >> sh) & 0x03030303u) | pad);
+                acc = dg_mfma_step<TR>(fa, fb, acc);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s_part[(ws * 16 + e) * 64 + lane] = acc[e];
+    __syncthreads();
+
+    for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
+        const int e = idx >> 6, l = idx & 63;
+        int32_t sum = 0;
+        for (int w = 0; w < S; ++w) sum += s_part[(w * 16 + e) * 64 + l];
+        const int row = 8 * (e / 4) + 4 * (l >> 5) + (e % 4), col = l & 31;     // MFMA block coordinates
+        const int m = m0 + (TR ? col : row), n = n0 + (TR ? row : col);
+        if (m >= p.M || n >= p.N) continue;
+        const int64_t o = (int64_t)m * p.stride_cm + (int64_t)n * p.stride_cn;
+        if (p.scale)
+            p.Cf[o] = (float)sum * p.scale[m];
+        else
+            p.C[o] = sum;
+    }
+}
+
+template <bool TR>
+void launch_splitk(const OneHotSplitArgs &a, int ch, dim3 grid, int S, hipStream_t stream)
+{
+    const dim3 block(64 * S);
+    const size_t lds = (size_t)S * 16 * 64 * sizeof(int32_t);
+    if (ch == 4)
+        hipLaunchKernelGGL((onehot_splitk_kernel<4, TR>), grid, block, lds, stream, a);
+    else if (ch == 2)
+        hipLaunchKernelGGL((onehot_splitk_kernel<2, TR>), grid, block, lds, stream, a);
+    else
+        hipLaunchKernelGGL((onehot_splitk_kernel<1, TR>), grid, block, lds, stream, a);
 }
 
 }   // namespace
@@ -212,26 +333,52 @@ dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t st
     a.p = p;
     for (int w = 0; w < 4; ++w) {
         uint32_t r = 0;
-        for (int c = 0; c < 4; ++c) r |= (uint32_t)(uint8_t)(int8_t)lut->entry[4 * w + c] << (8 * c);
-        a.rows[w] = r;
+        for (int c = 0; c < 4; ++c) r |= (uint32_t)(uint8_t)(int8_t)lut->entry[4 * c + w] << (8 * c);
+        a.cols[w] = r;
     }
     const int ch = p.Cin % 128 == 0 ? 4 : (p.Cin % 64 == 0 ? 2 : 1);
     auto tiles = [&](int wm, int wn) {
         return ((int64_t)(p.M + wm * 32 - 1) / (wm * 32)) * (((int64_t)p.N + wn * 32 - 1) / (wn * 32));
     };
+    const bool tr = p.stride_cm == 1 && p.stride_cn != 1;   // the output axis with stride 1 goes on the MFMA columns
+    const int chunks = p.K / (32 * ch);
+    const bool force_split = getenv("DG_ONEHOT_SPLITK") != nullptr;      // tuning override
+    const bool few_tiles = tiles(2, 1) < 512 || (tiles(2, 1) < 1024 && chunks >= 32);
+    if ((few_tiles && chunks > 1) || force_split) {
+        // small layer: one 32 x 32 block per workgroup, K split over up to 16 wavefronts, about 2048 wavefronts in all
+        OneHotSplitArgs b;
+        b.p = p;
+        for (int v = 0; v < 4; ++v) b.cols[v] = a.cols[v];
+        const int64_t blocks = tiles(1, 1);
+        int S = (int)((2048 + blocks - 1) / blocks);
+        S = S < 1 ? 1 : (S > 16 ? 16 : S);
+        if (S > chunks) S = chunks;
+        b.chunks = chunks;
+        b.cpw = (chunks + S - 1) / S;
+        S = (chunks + b.cpw - 1) / b.cpw;
+        b.tiles_m = (p.M + 31) / 32;
+        if (tr)
+            launch_splitk<true>(b, ch, dim3((unsigned)blocks), S, stream);
+        else
+            launch_splitk<false>(b, ch, dim3((unsigned)blocks), S, stream);
+        return dg_check_launch("onehot_splitk_kernel");
+    }
+    // the widest tile that still gives every SIMD a wavefront
     int wm = 2, wn = 1;
     if (tiles(2, 4) >= 1024) wm = 2, wn = 4;
-    else if (tiles(2, 2) >= 512) wm = 2, wn = 2;
+    else if (tiles(2, 2) >= 1024) wm = 2, wn = 2;
+    if (const char *e = getenv("DG_ONEHOT_WN")) {            // tuning override: 1, 2 or 4
+        const int v = atoi(e);
+        if (v == 1 || v == 2 || v == 4) wn = v;
+    }
     a.tiles_m = (p.M + wm * 32 - 1) / (wm * 32);
     a.wave_tiles = tiles(wm, wn);
     const int64_t blocks = (a.wave_tiles + 3) / 4;
     if (blocks > INT32_MAX) return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel: too many tiles for one grid");
     const dim3 grid((unsigned)blocks);
-    if (wn == 4)
-        launch_ch<2, 4>(a, ch, grid, stream);
-    else if (wn == 2)
-        launch_ch<2, 2>(a, ch, grid, stream);
+    if (tr)
+        launch_wn<true>(a, wn, ch, grid, stream);
     else
-        launch_ch<2, 1>(a, ch, grid, stream);
+        launch_wn<false>(a, wn, ch, grid, stream);
     return dg_check_launch("onehot_mfma_kernel");
 }

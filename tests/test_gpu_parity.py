@@ -29,6 +29,8 @@ LEVELS = {
 GEMM_SHAPES = [
     (1, 1, 4), (3, 5, 8), (4, 4, 4), (17, 9, 20), (64, 196, 576), (70, 130, 192), (129, 257, 320),
     (8, 1, 64), (1, 300, 128), (256, 512, 64), (33, 1000, 1024), (200, 3, 2048), (5, 16, 4096),
+    # enough 64 x 32 / 64 x 64 / 64 x 128 tiles for the large-layer matrix-core kernels, with ragged edges
+    (70, 8200, 96), (70, 32800, 64), (70, 65600, 128),
 ]
 
 
@@ -103,6 +105,10 @@ CONV_CASES = [
     (1, 17, 15, 48, 24, 5, 5, (1, 1), (2, 2)),
     (2, 16, 16, 16, 130, 3, 3, (1, 1), (1, 1)),
     (1, 9, 9, 64, 16, 7, 7, (2, 2), (3, 3)),
+    # large-layer tile shapes of the matrix-core kernels (64 x 32, 64 x 64, 64 x 128), NHWC output
+    (4, 48, 48, 32, 70, 3, 3, (1, 1), (1, 1)),
+    (9, 64, 64, 64, 70, 1, 1, (1, 1), (0, 0)),
+    (17, 64, 64, 128, 70, 3, 3, (1, 1), (1, 1)),
 ]
 
 
