@@ -36,9 +36,9 @@ PERM_ALU_PEAK_TOPS = VALU_LANE_INSTR_PER_S * (4 / 1.5) * 2 / 1e12
 # bytes -> x2.0; WRITE_SIZE reads them exactly -> x1.0).  Summaries with the commands are under profiles/.
 # Keyed by (workload, kernel name); a kernel or workload that was not profiled reports null.
 MEASURED_TRAFFIC_KIB = {
-    ("resnet18_conv3x3_b1", "perm_2x4_8x8_k96_s6_b1_m0"): (291.0 * 2.0, 784.0),
-    ("vgg16_conv3x3_b16", "perm_8x8_16x16_k48_s1_b2_m0"): (6661.0 * 2.0, 50176.6),
-    ("gemm_8192x1x8192_i16", "smalln"): (8279.5 * 2.0, 32.0),
+    ("resnet18_conv3x3_b1", "onehot_mfma_splitk_s9"): (227.7 * 2.0, 784.0),
+    ("vgg16_conv3x3_b16", "onehot_mfma_64x128"): (4643.4 * 2.0, 50176.0),
+    ("gemm_8192x1x8192_i16", "smalln"): (8252.0 * 2.0, 32.0),
 }
 
 
@@ -162,27 +162,43 @@ def time_calls(torch, fn, count, use_graph, chunk=500):
     return start.elapsed_time(end) / count
 
 
+def mfma_ops_factor(name):
+    """int8 MFMA operations issued per effective operation: the one-hot kernel contracts over 4K (one operand byte per
+    table column), the decode-and-multiply comparison kernel over K; table kernels on the VALU issue none."""
+    if name.startswith("onehot_mfma"):
+        return 4
+    if name.startswith("mfma_i8"):
+        return 1
+    return None
+
+
 def kernel_report(w, ms, name):
     """Achieved rates of one kernel launch of duration `ms` against the three ceilings."""
     gops = w.ops / (ms * 1e-3) / 1e9
     gbs = w.algorithmic_bytes / (ms * 1e-3) / 1e9
+    f = mfma_ops_factor(name)
     return {
         "kernel": name, "us": round(ms * 1e3, 3), "gops": round(gops, 1), "algorithmic_GBps": round(gbs, 1),
         "frac_hbm": round(gbs / HBM_PEAK_GBS, 4),
-        "frac_int8_mfma_peak": round(gops / 1e3 / INT8_MFMA_PEAK_TOPS, 4),
-        "frac_perm_alu_peak": round(gops / 1e3 / PERM_ALU_PEAK_TOPS, 4),
+        "frac_int8_mfma_peak": None if f is None else round(f * gops / 1e3 / INT8_MFMA_PEAK_TOPS, 4),
+        "frac_perm_alu_peak": round(gops / 1e3 / PERM_ALU_PEAK_TOPS, 4) if name.startswith("perm") else None,
     }
 
 
 def roofline_object(w, ms, name):
-    """The roofline entry of the dominant kernel: HBM when the HBM time of the algorithmic bytes exceeds the
-    ALU time of the products at the permute kernel's issue ceiling, else ALU."""
+    """The roofline entry of the dominant kernel.  Matrix-core kernels: int8 MFMA operations issued (4 per effective
+    operation for the one-hot table kernel) against the dense int8 peak.  VALU table kernels: HBM when the HBM time
+    of the algorithmic bytes exceeds the ALU time of the products at the permute kernel's issue ceiling, else ALU."""
     t_hbm = w.algorithmic_bytes / (HBM_PEAK_GBS * 1e9)
     t_alu = w.ops / (PERM_ALU_PEAK_TOPS * 1e12)
-    if name.startswith("mfma"):
-        ach = w.ops / (ms * 1e-3) / 1e12
+    f = mfma_ops_factor(name)
+    if f is not None:
+        ach = f * w.ops / (ms * 1e-3) / 1e12
         return {"bound": "mfma", "achieved": round(ach, 3), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TFLOP/s",
-                "frac": round(ach / INT8_MFMA_PEAK_TOPS, 5), "traffic": None, "kernel": name}
+                "frac": round(ach / INT8_MFMA_PEAK_TOPS, 5), "traffic": measured_traffic(w, name), "kernel": name,
+                "algorithmic_bytes": w.algorithmic_bytes, "effective_tops": round(w.ops / (ms * 1e-3) / 1e12, 3),
+                "note": f"int8 MFMA operations issued = {f} x 2MNK (one-hot selection contracts over 4K); "
+                        "integer TOP/s against the dense int8 peak"}
     if t_hbm >= t_alu:
         ach = w.algorithmic_bytes / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -193,6 +209,20 @@ def roofline_object(w, ms, name):
             "frac": round(ach / PERM_ALU_PEAK_TOPS, 5), "traffic": measured_traffic(w, name), "kernel": name,
             "algorithmic_bytes": w.algorithmic_bytes,
             "note": "integer table lookups+adds counted as 2 ops per product; peak = VALU issue ceiling of the permute loop"}
+
+
+def launch_floor_us(torch, w, name, use_graph):
+    """Duration of an empty kernel with the grid of the split-K one-hot kernel (the shape is in its name): what the
+    launch alone costs.  None for other kernels."""
+    from paper_2304_09049_amd import binding as dg
+    prefix = "onehot_mfma_splitk_s"
+    if not name.startswith(prefix):
+        return None
+    blocks, threads = -(-w.M // 32) * -(-w.N // 32), 64 * int(name[len(prefix):])
+    fn = lambda: dg.dg_launch_empty(blocks, threads)
+    for _ in range(3):
+        fn()
+    return round(time_calls(torch, fn, 2000, use_graph) * 1e3, 3)
 
 
 def stage_kernels(torch, w):
@@ -302,6 +332,7 @@ def main():
         "kernel_only": kernel_report(w, ms_kernel, name),
         "pack_activations_us": round(ms_pack * 1e3, 3),
         "roofline": roofline_object(w, ms_kernel, name),
+        "empty_launch_same_grid_us": launch_floor_us(torch, w, name, use_graph),
         "paper_context": "up to 1.74x over QNNPACK INT8 on an Intel i7-9700K (speedup ratios only; no absolute figure)",
     }
 
@@ -309,7 +340,7 @@ def main():
         sweep = []
         for wname, ww in wl.CONFIGS.items():
             rr = r if ww is w else Runner(ww, "auto")
-            for variant in ("auto", "onehot_mfma", "mfma_i8", "lut65k", "lds"):
+            for variant in ("auto", "perm", "mfma_i8", "lut65k", "lds"):
                 if variant in ("lds", "lut65k") and ww.ops > 1e11:
                     continue
                 try:

@@ -208,6 +208,11 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
                         const dg_conv_desc *desc, int32_t *Y_dev, const float *scale_cout_dev,
                         float *Yf_dev, dg_kernel variant, void *hip_stream);
 
+/* Measurement aid: launch a kernel that does nothing, `blocks` workgroups of `threads` threads (a multiple of 64,
+ * at most 1024), on `hip_stream`.  Its duration is what a launch of that shape costs before any work is done, the
+ * floor under the duration of a small layer's kernel.  Errors: DG_ERR_SHAPE. */
+dg_status dg_launch_empty(int64_t blocks, int32_t threads, void *hip_stream);
+
 /* Name of the kernel that AUTO would pick (or that `variant` maps to) for this GEMM / convolution
  * shape; static storage.  For reports only. */
 const char *dg_gemm_kernel_name(const dg_lut *lut, int64_t M, int64_t N, int64_t K,

@@ -30,6 +30,7 @@ EXPORTS = (
     "dg_packed_activation_bytes", "dg_packed_weight_bytes", "dg_packed_bytes_bits", "dg_pack_weights",
     "dg_pack_activations", "dg_pack_codes_bits", "dg_quantize_pack_activations",
     "dg_gemm_lut", "dg_conv_out_dim", "dg_conv2d_lut", "dg_gemm_kernel_name", "dg_conv_kernel_name",
+    "dg_launch_empty",
 )
 
 
@@ -88,6 +89,7 @@ def lib() -> ctypes.CDLL:
     L.dg_gemm_kernel_name.argtypes, L.dg_gemm_kernel_name.restype = [c_vp, c_i64, c_i64, c_i64, c_int], ctypes.c_char_p
     L.dg_conv_kernel_name.argtypes = [c_vp, ctypes.POINTER(ConvDesc), c_int]
     L.dg_conv_kernel_name.restype = ctypes.c_char_p
+    L.dg_launch_empty.argtypes, L.dg_launch_empty.restype = [c_i64, c_int, c_vp], c_int
     _lib = L
     return L
 
@@ -289,3 +291,8 @@ def dg_gemm_kernel_name(lut: Lut, M: int, N: int, K: int, variant="auto") -> str
 
 def dg_conv_kernel_name(lut: Lut, desc: ConvDesc, variant="auto") -> str:
     return lib().dg_conv_kernel_name(lut.handle, ctypes.byref(desc), _kernel(variant)).decode()
+
+
+def dg_launch_empty(blocks: int, threads: int, stream=None) -> None:
+    """A launch that does nothing: the cost of a grid of that shape (measurement aid)."""
+    _check(lib().dg_launch_empty(blocks, threads, _stream_ptr(stream)))

@@ -9,6 +9,8 @@
 
 namespace {
 thread_local char g_error[512] = "";
+
+__global__ void empty_kernel() {}
 }
 
 dg_status dg_fail(dg_status s, const char *fmt, ...)
@@ -303,7 +305,7 @@ const char *pick_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case Pick::Mfma: return "mfma_i8";
     case Pick::SmallN: return "smalln";
     case Pick::Lut65k: return "lut65k";
-    case Pick::OneHot: return "onehot_mfma";
+    case Pick::OneHot: return dg_onehot_config_name(lut, p);
     case Pick::Unsupported: break;
     }
     return "unsupported";
@@ -415,6 +417,14 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
     p.stride_cm = 1;          // NHWC: channel fastest
     p.stride_cn = p.M;
     return run(lut, p, variant, (hipStream_t)hip_stream);
+}
+
+dg_status dg_launch_empty(int64_t blocks, int32_t threads, void *hip_stream)
+{
+    if (blocks <= 0 || blocks > INT32_MAX || threads <= 0 || threads > 1024 || threads % 64 != 0)
+        return dg_fail(DG_ERR_SHAPE, "dg_launch_empty: blocks=%lld threads=%d", (long long)blocks, threads);
+    hipLaunchKernelGGL(empty_kernel, dim3((unsigned)blocks), dim3((unsigned)threads), 0, (hipStream_t)hip_stream);
+    return dg_check_launch("empty_kernel");
 }
 
 const char *dg_gemm_kernel_name(const dg_lut *lut, int64_t M, int64_t N, int64_t K, dg_kernel variant)

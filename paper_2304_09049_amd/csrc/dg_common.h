@@ -61,5 +61,6 @@ bool dg_lut65k_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_lut65k(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 bool dg_onehot_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+const char *dg_onehot_config_name(const dg_lut *lut, const DgProblem &p);
 bool dg_smalln_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_smalln(const dg_lut *lut, const DgProblem &p, hipStream_t stream);

@@ -327,6 +327,65 @@ bool dg_onehot_supports(const dg_lut *lut, const DgProblem &p)
     return true;
 }
 
+namespace {
+
+// Which of the two kernels runs a problem, and its shape.
+struct OneHotPlan {
+    int ch;          // 32-bit words of packed codes per lane half and chunk
+    bool split;      // small layer: 32 x 32 block per workgroup, K split over S wavefronts
+    int wn;          // large layer: the wave tile is 64 x (32*wn)
+    int S, cpw, chunks;
+};
+
+int64_t tile_count(const DgProblem &p, int wm, int wn)
+{
+    return ((int64_t)(p.M + wm * 32 - 1) / (wm * 32)) * (((int64_t)p.N + wn * 32 - 1) / (wn * 32));
+}
+
+OneHotPlan plan_for(const DgProblem &p)
+{
+    OneHotPlan q;
+    q.ch = p.Cin % 128 == 0 ? 4 : (p.Cin % 64 == 0 ? 2 : 1);
+    q.chunks = p.K / (32 * q.ch);
+    q.wn = 1, q.S = 1, q.cpw = q.chunks;
+    // too few 64 x 32 tiles to give every SIMD a wavefront (or barely enough, and a long K to walk): split K
+    const int64_t t21 = tile_count(p, 2, 1);
+    const bool few_tiles = t21 < 512 || (t21 < 1024 && q.chunks >= 32);
+    q.split = (few_tiles && q.chunks > 1) || getenv("DG_ONEHOT_SPLITK") != nullptr;   // (tuning override)
+    if (q.split) {
+        // about 2048 wavefronts in all, at most 16 per workgroup, whole chunks each
+        const int64_t blocks = tile_count(p, 1, 1);
+        int S = (int)((2048 + blocks - 1) / blocks);
+        S = S < 1 ? 1 : (S > 16 ? 16 : S);
+        if (S > q.chunks) S = q.chunks;
+        q.cpw = (q.chunks + S - 1) / S;
+        q.S = (q.chunks + q.cpw - 1) / q.cpw;
+        return q;
+    }
+    // the widest tile that still gives every SIMD a wavefront
+    if (tile_count(p, 2, 4) >= 1024) q.wn = 4;
+    else if (tile_count(p, 2, 2) >= 1024) q.wn = 2;
+    if (const char *e = getenv("DG_ONEHOT_WN")) {            // tuning override: 1, 2 or 4
+        const int v = atoi(e);
+        if (v == 1 || v == 2 || v == 4) q.wn = v;
+    }
+    return q;
+}
+
+}   // namespace
+
+const char *dg_onehot_config_name(const dg_lut *, const DgProblem &p)
+{
+    static const char *const split_names[17] = {
+        "", "onehot_mfma_splitk_s1", "onehot_mfma_splitk_s2", "onehot_mfma_splitk_s3", "onehot_mfma_splitk_s4",
+        "onehot_mfma_splitk_s5", "onehot_mfma_splitk_s6", "onehot_mfma_splitk_s7", "onehot_mfma_splitk_s8",
+        "onehot_mfma_splitk_s9", "onehot_mfma_splitk_s10", "onehot_mfma_splitk_s11", "onehot_mfma_splitk_s12",
+        "onehot_mfma_splitk_s13", "onehot_mfma_splitk_s14", "onehot_mfma_splitk_s15", "onehot_mfma_splitk_s16"};
+    const OneHotPlan q = plan_for(p);
+    if (q.split) return split_names[q.S];
+    return q.wn == 4 ? "onehot_mfma_64x128" : (q.wn == 2 ? "onehot_mfma_64x64" : "onehot_mfma_64x32");
+}
+
 dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
 {
     OneHotArgs a;
@@ -336,49 +395,31 @@ dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t st
         for (int c = 0; c < 4; ++c) r |= (uint32_t)(uint8_t)(int8_t)lut->entry[4 * c + w] << (8 * c);
         a.cols[w] = r;
     }
-    const int ch = p.Cin % 128 == 0 ? 4 : (p.Cin % 64 == 0 ? 2 : 1);
-    auto tiles = [&](int wm, int wn) {
-        return ((int64_t)(p.M + wm * 32 - 1) / (wm * 32)) * (((int64_t)p.N + wn * 32 - 1) / (wn * 32));
-    };
+    const OneHotPlan q = plan_for(p);
     const bool tr = p.stride_cm == 1 && p.stride_cn != 1;   // the output axis with stride 1 goes on the MFMA columns
-    const int chunks = p.K / (32 * ch);
-    const bool force_split = getenv("DG_ONEHOT_SPLITK") != nullptr;      // tuning override
-    const bool few_tiles = tiles(2, 1) < 512 || (tiles(2, 1) < 1024 && chunks >= 32);
-    if ((few_tiles && chunks > 1) || force_split) {
-        // small layer: one 32 x 32 block per workgroup, K split over up to 16 wavefronts, about 2048 wavefronts in all
+    if (q.split) {
         OneHotSplitArgs b;
         b.p = p;
         for (int v = 0; v < 4; ++v) b.cols[v] = a.cols[v];
-        const int64_t blocks = tiles(1, 1);
-        int S = (int)((2048 + blocks - 1) / blocks);
-        S = S < 1 ? 1 : (S > 16 ? 16 : S);
-        if (S > chunks) S = chunks;
-        b.chunks = chunks;
-        b.cpw = (chunks + S - 1) / S;
-        S = (chunks + b.cpw - 1) / b.cpw;
+        b.chunks = q.chunks;
+        b.cpw = q.cpw;
         b.tiles_m = (p.M + 31) / 32;
+        const int64_t blocks = tile_count(p, 1, 1);
+        if (blocks > INT32_MAX) return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel: too many tiles for one grid");
         if (tr)
-            launch_splitk<true>(b, ch, dim3((unsigned)blocks), S, stream);
+            launch_splitk<true>(b, q.ch, dim3((unsigned)blocks), q.S, stream);
         else
-            launch_splitk<false>(b, ch, dim3((unsigned)blocks), S, stream);
+            launch_splitk<false>(b, q.ch, dim3((unsigned)blocks), q.S, stream);
         return dg_check_launch("onehot_splitk_kernel");
     }
-    // the widest tile that still gives every SIMD a wavefront
-    int wm = 2, wn = 1;
-    if (tiles(2, 4) >= 1024) wm = 2, wn = 4;
-    else if (tiles(2, 2) >= 1024) wm = 2, wn = 2;
-    if (const char *e = getenv("DG_ONEHOT_WN")) {            // tuning override: 1, 2 or 4
-        const int v = atoi(e);
-        if (v == 1 || v == 2 || v == 4) wn = v;
-    }
-    a.tiles_m = (p.M + wm * 32 - 1) / (wm * 32);
-    a.wave_tiles = tiles(wm, wn);
+    a.tiles_m = (p.M + 63) / 64;
+    a.wave_tiles = tile_count(p, 2, q.wn);
     const int64_t blocks = (a.wave_tiles + 3) / 4;
     if (blocks > INT32_MAX) return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel: too many tiles for one grid");
     const dim3 grid((unsigned)blocks);
     if (tr)
-        launch_wn<true>(a, wn, ch, grid, stream);
+        launch_wn<true>(a, q.wn, q.ch, grid, stream);
     else
-        launch_wn<false>(a, wn, ch, grid, stream);
+        launch_wn<false>(a, q.wn, q.ch, grid, stream);
     return dg_check_launch("onehot_mfma_kernel");
 }
