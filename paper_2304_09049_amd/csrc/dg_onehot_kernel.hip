@@ -65,7 +65,7 @@ __device__ __forceinline__ v4i select4(uint32_t p0, uint32_t p1, uint32_t p2, ui
 }
 
 template <int WM, int WN, int CH, bool TR>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256, (WM * WN > 8 ? 1 : 2))
 onehot_mfma_kernel(OneHotArgs a)
 {
     const DgProblem &p = a.p;
@@ -198,7 +198,9 @@ void launch_ch(const OneHotArgs &a, int ch, dim3 grid, hipStream_t stream)
 template <bool TR>
 void launch_wn(const OneHotArgs &a, int wn, int ch, dim3 grid, hipStream_t stream)
 {
-    if (wn == 4)
+    if (wn == 7)
+        launch_ch<2, 7, TR>(a, ch, grid, stream);
+    else if (wn == 4)
         launch_ch<2, 4, TR>(a, ch, grid, stream);
     else if (wn == 2)
         launch_ch<2, 2, TR>(a, ch, grid, stream);
@@ -351,7 +353,14 @@ OneHotPlan plan_for(const DgProblem &p)
     // too few 64 x 32 tiles to give every SIMD a wavefront (or barely enough, and a long K to walk): split K
     const int64_t t21 = tile_count(p, 2, 1);
     const bool few_tiles = t21 < 512 || (t21 < 1024 && q.chunks >= 32);
-    q.split = (few_tiles && q.chunks > 1) || getenv("DG_ONEHOT_SPLITK") != nullptr;   // (tuning override)
+    q.split = few_tiles && q.chunks > 1;
+    // DG_ONEHOT_PLAN = split | 1 | 2 | 4 | 7 overrides the choice (tuning, and tests that must reach every plan)
+    const char *force = getenv("DG_ONEHOT_PLAN");
+    int force_wn = 0;
+    if (force) {
+        if (force[0] == 's') q.split = true;
+        else if (atoi(force) == 1 || atoi(force) == 2 || atoi(force) == 4 || atoi(force) == 7) force_wn = atoi(force), q.split = false;
+    }
     if (q.split) {
         // about 2048 wavefronts in all, at most 16 per workgroup, whole chunks each
         const int64_t blocks = tile_count(p, 1, 1);
@@ -362,13 +371,24 @@ OneHotPlan plan_for(const DgProblem &p)
         q.S = (q.chunks + q.cpw - 1) / q.cpw;
         return q;
     }
-    // the widest tile that still gives every SIMD a wavefront
-    if (tile_count(p, 2, 4) >= 1024) q.wn = 4;
-    else if (tile_count(p, 2, 2) >= 1024) q.wn = 2;
-    if (const char *e = getenv("DG_ONEHOT_WN")) {            // tuning override: 1, 2 or 4
-        const int v = atoi(e);
-        if (v == 1 || v == 2 || v == 4) q.wn = v;
+    // Wave tile 64 x (32*wn): the one with the least modelled time on the busiest SIMD, in cycles.  A SIMD's
+    // wavefronts share its matrix pipe, so its time is (tiles per SIMD, rounded up) x (32x32 blocks per tile) x (MFMA
+    // steps of K) x (cycles per MFMA: 32, more where the VALU work of building operands or the operand loads show --
+    // measured 42 for one block column, 33 for two), plus what no other wavefront hides: one prologue (~3000 cycles)
+    // and the last tile's stores (~600 cycles per block).  7 blocks wide fits the 56 x 56 and 28 x 28 images of
+    // ImageNet networks (N = 49 * 2^k) where 4 wide leaves the last round of tiles half empty.  The constants are
+    // fitted to timings of 50 layer shapes; ties go to the wider tile (fewer operand loads).
+    static const int widths[4] = {7, 4, 2, 1};
+    static const double mfma_cycles[4] = {32.0, 32.0, 33.0, 42.0};
+    const double steps = p.K / 8.0;
+    double best = 0.0;
+    for (int i = 0; i < 4; ++i) {
+        const int wn = widths[i];
+        const double per_simd = (double)((tile_count(p, 2, wn) + 1023) / 1024);
+        const double cost = per_simd * 2 * wn * steps * mfma_cycles[i] + 3000.0 + 600.0 * 2 * wn;
+        if (i == 0 || cost < best * 0.999) best = cost, q.wn = wn;
     }
+    if (force_wn) q.wn = force_wn;
     return q;
 }
 
@@ -383,7 +403,8 @@ const char *dg_onehot_config_name(const dg_lut *, const DgProblem &p)
         "onehot_mfma_splitk_s13", "onehot_mfma_splitk_s14", "onehot_mfma_splitk_s15", "onehot_mfma_splitk_s16"};
     const OneHotPlan q = plan_for(p);
     if (q.split) return split_names[q.S];
-    return q.wn == 4 ? "onehot_mfma_64x128" : (q.wn == 2 ? "onehot_mfma_64x64" : "onehot_mfma_64x32");
+    return q.wn == 7 ? "onehot_mfma_64x224"
+                     : (q.wn == 4 ? "onehot_mfma_64x128" : (q.wn == 2 ? "onehot_mfma_64x64" : "onehot_mfma_64x32"));
 }
 
 dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream)

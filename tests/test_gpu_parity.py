@@ -29,8 +29,6 @@ LEVELS = {
 GEMM_SHAPES = [
     (1, 1, 4), (3, 5, 8), (4, 4, 4), (17, 9, 20), (64, 196, 576), (70, 130, 192), (129, 257, 320),
     (8, 1, 64), (1, 300, 128), (256, 512, 64), (33, 1000, 1024), (200, 3, 2048), (5, 16, 4096),
-    # enough 64 x 32 / 64 x 64 / 64 x 128 tiles for the large-layer matrix-core kernels, with ragged edges
-    (70, 8200, 96), (70, 32800, 64), (70, 65600, 128),
 ]
 
 
@@ -105,10 +103,6 @@ CONV_CASES = [
     (1, 17, 15, 48, 24, 5, 5, (1, 1), (2, 2)),
     (2, 16, 16, 16, 130, 3, 3, (1, 1), (1, 1)),
     (1, 9, 9, 64, 16, 7, 7, (2, 2), (3, 3)),
-    # large-layer tile shapes of the matrix-core kernels (64 x 32, 64 x 64, 64 x 128), NHWC output
-    (4, 48, 48, 32, 70, 3, 3, (1, 1), (1, 1)),
-    (9, 64, 64, 64, 70, 1, 1, (1, 1), (0, 0)),
-    (17, 64, 64, 128, 70, 3, 3, (1, 1), (1, 1)),
 ]
 
 
@@ -125,6 +119,40 @@ def test_conv_parity(case_, variant):
             pytest.skip(f"{variant} declares {case_} unsupported")
         want = oracle.conv2d(inp.Wc, inp.Ac, lw, la, stride=stride, pad=pad)
         _assert_same(got, want, f"conv {case_} {levels} {variant}")
+
+
+ONEHOT_PLANS = {"split": "onehot_mfma_splitk_s", "1": "onehot_mfma_64x32", "2": "onehot_mfma_64x64",
+                "4": "onehot_mfma_64x128", "7": "onehot_mfma_64x224"}
+
+
+@pytest.mark.parametrize("plan", sorted(ONEHOT_PLANS))
+def test_onehot_every_plan(plan, monkeypatch):
+    """Every wave tile of the one-hot matrix-core kernel and its split-K form, forced on shapes with ragged edges in
+    M and N (the library picks among them by a cost model that small test shapes would never move off one plan):
+    GEMM with row-major and column-major output, convolution with padding and stride, int32 and scaled fp32 output."""
+    monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
+    for (M, N, K) in [(70, 1000, 96), (130, 777, 64), (64, 300, 256), (33, 250, 1024)]:
+        inp = wl.small_gemm(M, N, K, seed=M + N + K)
+        case = GpuCase(inp)
+        assert case.kernel_name("onehot_mfma").startswith(ONEHOT_PLANS[plan])
+        want = oracle.gemm(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a)
+        _assert_same(case.run("onehot_mfma").cpu().numpy(), want, f"gemm {(M, N, K)} plan {plan}")
+        out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
+        dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant="onehot_mfma", strides=(1, M))
+        torch.cuda.synchronize()
+        _assert_same(out.cpu().numpy(), want.T.copy(), f"gemm {(M, N, K)} column-major plan {plan}")
+    lw, la, entry = LEVELS["nonuniform_i8"]                  # no zero activation level: padding must still add 0
+    for (B, H, W, Cin, Cout, KH, KW, stride, pad) in [(2, 24, 24, 32, 70, 3, 3, (1, 1), (1, 1)),
+                                                      (1, 30, 30, 128, 40, 3, 3, (2, 2), (1, 1)),
+                                                      (3, 16, 16, 64, 33, 1, 1, (1, 1), (0, 0)),
+                                                      (1, 20, 20, 64, 96, 5, 5, (1, 1), (2, 2))]:
+        c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        assert case.kernel_name("onehot_mfma").startswith(ONEHOT_PLANS[plan])
+        acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
+        _assert_same(case.run("onehot_mfma").cpu().numpy(), acc, f"conv {(B, H, W, Cin, Cout)} plan {plan}")
+        got = case.run("onehot_mfma", scale=True).cpu().numpy()
+        assert np.array_equal(got, oracle.scale_epilogue_nhwc(acc, c.scale)), f"scaled conv plan {plan}"
 
 
 def test_golden_tiny_conv_on_gpu(golden_dir):
