@@ -162,6 +162,20 @@ def time_calls(torch, fn, count, use_graph, chunk=500):
     return start.elapsed_time(end) / count
 
 
+def time_steady(torch, fn, use_graph):
+    """Milliseconds per call once the clocks have settled: size the run to about 30 ms of GPU work from a first rough
+    timing, run it once untimed, then time it (the first passes after an idle spell run up to 15 % slower)."""
+    for _ in range(3):
+        fn()
+    rough = max(time_calls(torch, fn, 5, False), 1e-3)
+    reps = int(min(2000, max(10, 30.0 / rough)))
+    graph = use_graph and reps >= 100
+    if graph:
+        reps -= reps % 100
+    time_calls(torch, fn, reps, graph, chunk=100)
+    return time_calls(torch, fn, reps, graph, chunk=100)
+
+
 def mfma_ops_factor(name):
     """int8 MFMA operations issued per effective operation: the one-hot kernel contracts over 4K (one operand byte per
     table column), the decode-and-multiply comparison kernel over K; table kernels on the VALU issue none."""
@@ -248,7 +262,7 @@ def stage_kernels(torch, w):
         dg.dg_quantize_pack_activations(xs[turn[0] % n_x], rows, k, 1.0, 0.0, 0, out=out)
 
     report = []
-    for name, fn, nbytes in (("pack_vec16_kernel", pack, count + count // 4),
+    for name, fn, nbytes in (("pack_vec16_unrolled_kernel", pack, count + count // 4),
                              ("quantize_pack_vec16_kernel", quantize_pack, 4 * count + count // 4)):
         for _ in range(3):
             fn()
@@ -347,20 +361,15 @@ def main():
                     kname = rr.kernel_name(variant)
                     if kname == "unsupported":
                         continue
-                    reps = 200 if ww.ops < 1e10 else (20 if ww.ops < 2e11 else 5)
                     fn = lambda v=variant, q=rr: q.kernel(v)
-                    for _ in range(3):
-                        fn()
-                    ms = time_calls(torch, fn, reps, use_graph and reps >= 100, chunk=100)
+                    ms = time_steady(torch, fn, use_graph)
                     rep = kernel_report(ww, ms, kname)
                     rep.update({"workload": wname, "variant": variant})
                     if variant == "auto" and ww.kind == "gemm" and ww.N <= 16 and ww.M * ww.K // 4 >= (8 << 20):
                         # weight-streaming shapes: also with the weights NOT resident in the last-level cache
                         rr.make_cold_weights()
                         cold = lambda q=rr: q.kernel_cold("auto")
-                        for _ in range(3):
-                            cold()
-                        ms_cold = time_calls(torch, cold, 200, use_graph, chunk=100)
+                        ms_cold = time_steady(torch, cold, use_graph)
                         rep["us_weights_from_hbm"] = round(ms_cold * 1e3, 3)
                         rep["frac_hbm_weights_from_hbm"] = round(ww.algorithmic_bytes / (ms_cold * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
                         rr.cold = None

@@ -25,6 +25,23 @@ pack_vec16_kernel(const uint4 *__restrict__ codes, uint32_t *__restrict__ packed
     }
 }
 
+// Large inputs: U independent 128-bit loads per lane are issued before the first is used (more bytes in flight per
+// wavefront), each still coalesced across the workgroup.  `groups16` is a multiple of 256*U here.
+template <int U>
+__global__ void __launch_bounds__(256)
+pack_vec16_unrolled_kernel(const uint4 *__restrict__ codes, uint32_t *__restrict__ packed, int64_t groups16)
+{
+    const int64_t stride = (int64_t)gridDim.x * (256 * U);
+    for (int64_t base = (int64_t)blockIdx.x * (256 * U) + threadIdx.x; base < groups16; base += stride) {
+        uint4 v[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j) v[j] = codes[base + 256 * j];
+#pragma unroll
+        for (int j = 0; j < U; ++j)
+            packed[base + 256 * j] = pack4(v[j].x) | (pack4(v[j].y) << 8) | (pack4(v[j].z) << 16) | (pack4(v[j].w) << 24);
+    }
+}
+
 // Any alignment, any count that is a multiple of 4: one packed byte per lane per step.
 __global__ void __launch_bounds__(256)
 pack_bytes_kernel(const uint8_t *__restrict__ codes, uint8_t *__restrict__ packed, int64_t first_group,
@@ -136,12 +153,24 @@ dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits
     const bool aligned = ((uintptr_t)codes % 16 == 0) && ((uintptr_t)packed % 4 == 0);
     if (aligned && total >= 16) {
         const int64_t groups16 = total / 16;
-        int64_t blocks = (groups16 + 255) / 256;
-        if (blocks > 256 * 32) blocks = 256 * 32;   // grid-stride beyond 32 workgroups per CU
-        hipLaunchKernelGGL(pack_vec16_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
-                           (const uint4 *)codes, (uint32_t *)packed, groups16);
-        dg_status s = dg_check_launch("pack_vec16_kernel");
-        if (s != DG_OK) return s;
+        constexpr int U = 4;
+        const int64_t big = groups16 >= 256 * 1024 ? groups16 / (256 * U) * (256 * U) : 0;   // from 4 Mi codes up
+        if (big > 0) {
+            int64_t blocks = big / (256 * U);
+            if (blocks > 256 * 32) blocks = 256 * 32;
+            hipLaunchKernelGGL(pack_vec16_unrolled_kernel<U>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                               (const uint4 *)codes, (uint32_t *)packed, big);
+            dg_status s = dg_check_launch("pack_vec16_unrolled_kernel");
+            if (s != DG_OK) return s;
+        }
+        if (big < groups16) {
+            int64_t blocks = (groups16 - big + 255) / 256;
+            if (blocks > 256 * 32) blocks = 256 * 32;   // grid-stride beyond 32 workgroups per CU
+            hipLaunchKernelGGL(pack_vec16_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                               (const uint4 *)codes + big, (uint32_t *)packed + big, groups16 - big);
+            dg_status s = dg_check_launch("pack_vec16_kernel");
+            if (s != DG_OK) return s;
+        }
         done4 = groups16 * 4;
     }
     if (done4 < groups4) {

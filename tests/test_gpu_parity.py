@@ -43,7 +43,8 @@ def _assert_same(got, want, what):
 
 def test_pack_activations_matches_the_public_layout():
     rng = np.random.default_rng(0)
-    for rows, K in [(1, 4), (3, 8), (7, 20), (196, 576), (5, 4096), (1000, 36)]:
+    # the last case is large enough for the unrolled kernel, with a remainder for each of the other two
+    for rows, K in [(1, 4), (3, 8), (7, 20), (196, 576), (5, 4096), (1000, 36), (4101, 1028)]:
         codes = wl.draw_codes(rng, (rows, K))
         got = dg.dg_pack_activations(torch.from_numpy(codes).cuda(), rows, K).cpu().numpy()
         _assert_same(got.reshape(rows, K // 4), oracle.pack_codes(codes), f"pack {rows}x{K}")
