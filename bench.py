@@ -273,6 +273,37 @@ def stage_kernels(torch, w):
     return report
 
 
+def wide_code_kernels(torch, w, use_graph):
+    """The 3- and 4-bit tables of Sec. 3.3 / Table 2 on the shape of workload `w` (a convolution): the one-hot
+    matrix-core kernel AUTO picks and the plain LDS kernel.  The MFMA fraction counts the operations issued:
+    2^bits per effective operation."""
+    from paper_2304_09049_amd import binding as dg
+    dev = torch.device("cuda:0")
+    report = []
+    for bits in (3, 4):
+        nlev = 1 << bits
+        lw = list(range(-(nlev // 2), nlev // 2))
+        la = list(range(nlev))
+        lut = dg.dg_build_lut_bits(bits, lw, la, dg.DG_LUT_I8)
+        gen = torch.Generator(device=dev).manual_seed(bits)
+        Wc = torch.randint(0, nlev, (w.Cout, w.KH, w.KW, w.Cin), dtype=torch.uint8, device=dev, generator=gen)
+        Xc = torch.randint(0, nlev, (w.B, w.H, w.W, w.Cin), dtype=torch.uint8, device=dev, generator=gen)
+        Wp = dg.dg_pack_codes_bits(Wc, w.Cout, w.KH * w.KW * w.Cin, bits)
+        Xp = dg.dg_pack_codes_bits(Xc, w.B * w.H * w.W, w.Cin, bits)
+        desc = dg.conv_desc(w.B, w.H, w.W, w.Cin, w.Cout, w.KH, w.KW, w.stride, w.pad)
+        out = dg.dg_conv2d_lut(lut, Wp, Xp, desc)
+        for variant in ("auto", "lds"):
+            fn = lambda v=variant: dg.dg_conv2d_lut(lut, Wp, Xp, desc, out=out, variant=v)
+            ms = time_steady(torch, fn, use_graph)
+            name = dg.dg_conv_kernel_name(lut, desc, variant)
+            tops = w.ops / (ms * 1e-3) / 1e12
+            report.append({"bits": bits, "workload_shape": w.name, "variant": variant, "kernel": name,
+                           "us": round(ms * 1e3, 3), "gops": round(tops * 1e3, 1),
+                           "frac_int8_mfma_peak": round(nlev * tops / INT8_MFMA_PEAK_TOPS, 4)
+                           if name.startswith("onehot_mfma") else None})
+    return report
+
+
 def cpu_baseline(w):
     """The CPU oracle, as it stands, on the host cores: the full headline workload, repeated."""
     import oracle
@@ -379,6 +410,7 @@ def main():
             del rr
         line["sweep"] = sweep
         line["stage_kernels"] = stage_kernels(torch, wl.CONFIGS["resnet50_conv1x1_b32"])
+        line["wide_codes"] = wide_code_kernels(torch, wl.CONFIGS["vgg16_conv3x3_b16"], use_graph)
 
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(w)

@@ -152,7 +152,8 @@ dg_status dg_quantize_pack_activations(const float *x_dev, int64_t N, int64_t K,
  *   LUT65K   the paper's second table (Sec. 3 "LUT-65k"): one entry per (weight byte, activation byte) holding
  *            the dot product of the four code pairs, kept in LDS; one fetch per four products
  *   ONEHOT_MFMA  table kernel on the matrix cores: each int8 MFMA multiply is by a one-hot byte of the activation
- *            code, i.e. it selects one entry of the weight code's table row; any 16 int8 entries, 4x the MFMA work
+ *            code, i.e. it selects one entry of the weight code's table row; any int8 entries, 2-, 3- or 4-bit
+ *            codes (2^bits times the MFMA work of a plain int8 product); needs Cin % 32 == 0 (2-bit) or % 16 (3-, 4-bit)
  * A variant that cannot run the given shape or table returns DG_ERR_UNSUPPORTED.
  */
 typedef enum {

@@ -254,10 +254,15 @@ enum class Pick { Perm, Lds, LdsF32, Mfma, SmallN, Lut65k, OneHot, Unsupported }
 
 Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
 {
-    // 3- and 4-bit tables (64 / 256 entries) run on the plain LDS kernel only
+    // binary32 tables run on the plain LDS kernel only; 3- and 4-bit tables on the one-hot matrix-core kernel or the LDS kernel
     if (lut->dtype == DG_LUT_F32)
         return (variant == DG_KERNEL_AUTO || variant == DG_KERNEL_LDS) ? Pick::LdsF32 : Pick::Unsupported;
-    if (lut->bits != 2) return (variant == DG_KERNEL_AUTO || variant == DG_KERNEL_LDS) ? Pick::Lds : Pick::Unsupported;
+    if (lut->bits != 2) {
+        if (variant == DG_KERNEL_LDS) return Pick::Lds;
+        if (variant == DG_KERNEL_AUTO) return dg_onehot_supports(lut, p) ? Pick::OneHot : Pick::Lds;
+        if (variant == DG_KERNEL_ONEHOT_MFMA && dg_onehot_supports(lut, p)) return Pick::OneHot;
+        return Pick::Unsupported;
+    }
     switch (variant) {
     case DG_KERNEL_PERM: return dg_perm_supports(lut, p) ? Pick::Perm : Pick::Unsupported;
     case DG_KERNEL_LDS: return Pick::Lds;

@@ -1,0 +1,452 @@
+// Table lookup on the matrix cores by one-hot selection -- TABLE kernels (they work for any int8 entries, whether or
+// not they factor into level vectors), unlike the decode-and-multiply comparison kernel.
+//
+//   C[m][n] = sum_k T[w(m,k)][a(n,k)] = sum_k sum_{v<L} T[w(m,k)][v] * [a(n,k) == v],      L = 2^BITS levels
+//
+// so with A'[m][(k,v)] = T[w(m,k)][v] (the table ROW of the weight code, L int8) and B'[n][(k,v)] = [a(n,k) == v]
+// (a one-hot run of L bytes) the layer is an int8 contraction of length L*K: each multiply is by 0 or 1, i.e. the
+// MFMA unit SELECTS one table entry per reduction position and adds it.  L times the MFMA work of the rank-1 decode
+// kernel, but every table is accepted and the VALU only expands codes.  BITS = 2 is the paper's LUT-16 (Sec. 3);
+// BITS = 3 and 4 are the 64- and 256-entry tables of its Sec. 3.3 / Table 2 (codes two per byte in 4-bit slots).
+//
+// Expansion, without LDS: the order of the (k,v) axis is free as long as both operands use the same one, so the 16
+// operand bytes of a lane are laid out value-major: each dword holds, for ONE value v and 4 reduction positions,
+// T[w(k)][v] (weights) or [a(k) == v] (activations); a lane's operand of one MFMA step is the 4 dwords of a group of
+// 4 values, and a selector of 4 positions feeds L/4 steps.  With the codes of a packed word's four bytes spread into
+// the bytes of a selector ((word >> slot) & mask), a dword is a byte permute (v_perm_b32 picks 4 bytes out of 8):
+//   weights      BITS 2: of the 4 bytes T[0..3][v];  BITS 3: of the 8 bytes T[0..7][v];
+//                BITS 4: of T[0..7][v] with the selector of the codes below 8, OR'd with that of T[8..15][v] with
+//                the selector of the codes from 8 up (each selector reads 0x0C = "constant 0" where it does not apply)
+//   activations  of a constant holding a single 1 at byte v % 4, in the lower or upper permute source as v / 4 says
+// A filter tap outside the image, or a column beyond N, gets selector bytes 0x0C: it selects nothing.
+#pragma once
+
+#include "dg_mfma_tile.h"
+
+namespace dgoh {
+
+typedef dg_v4i v4i;
+typedef dg_v16i v16i;
+
+// pool[v * (L/4) + q] = bytes T[4q .. 4q+3][v] (signed int8, as stored): column v of the table, 4 weight codes per word
+struct Pools {
+    uint32_t w[64];
+};
+
+struct Args {
+    DgProblem p;
+    Pools pools;
+    int32_t tiles_m;
+    int64_t wave_tiles;
+};
+
+struct SplitArgs {
+    DgProblem p;
+    Pools pools;
+    int32_t tiles_m;
+    int32_t chunks;          // K / (codes per chunk)
+    int32_t cpw;             // chunks per wavefront
+};
+
+template <int BITS>
+struct Fmt {
+    static constexpr int SLOT = BITS == 2 ? 2 : 4;             // bits per code slot in a packed byte
+    static constexpr int PER_BYTE = 8 / SLOT;                  // codes per packed byte
+    static constexpr int SELS = 8 / SLOT;                      // selectors (of 4 positions) per 32-bit word
+    static constexpr int GROUPS = (1 << BITS) / 4;             // MFMA steps per selector: groups of 4 values
+    static constexpr int STEPS = SELS * GROUPS;                // MFMA steps per 32-bit word
+    static constexpr uint32_t MASK = ((1u << BITS) - 1u) * 0x01010101u;
+    static constexpr int QW = (1 << BITS) / 4;                 // pool words per value
+    // rough VALU instruction counts of building one operand of one step (for the scheduling groups)
+    static constexpr int VALU_W = BITS == 4 ? 14 : 6;
+    static constexpr int VALU_A = BITS == 4 ? 7 : 6;
+};
+
+template <int CH>
+struct Words {
+    uint32_t v[CH];
+};
+
+template <int CH>
+__device__ __forceinline__ Words<CH> load_words(const uint8_t *ptr)
+{
+    Words<CH> w;
+    if (CH == 4) {
+        const uint4 t = *(const uint4 *)ptr;
+        w.v[0] = t.x, w.v[1 % CH] = t.y, w.v[2 % CH] = t.z, w.v[3 % CH] = t.w;
+    } else if (CH == 2) {
+        const uint2 t = *(const uint2 *)ptr;
+        w.v[0] = t.x, w.v[1 % CH] = t.y;
+    } else {
+        w.v[0] = *(const uint32_t *)ptr;
+    }
+    return w;
+}
+
+// Selector of 4 reduction positions.  BITS < 4: `lo` holds the codes.  BITS 4: `lo` the codes below 8 (0x0C
+// elsewhere), `hi` the codes from 8 up, minus 8 (0x0C elsewhere).
+struct Sel {
+    uint32_t lo, hi;
+};
+
+constexpr uint32_t NOTHING = 0x0C0C0C0Cu;                      // permute selector bytes that read as 0
+
+template <int BITS>
+__device__ __forceinline__ Sel make_sel(uint32_t word, int j, bool valid)
+{
+    typedef Fmt<BITS> F;
+    const uint32_t raw = (word >> (F::SLOT * j)) & F::MASK;
+    Sel s;
+    if (BITS == 4) {
+        const uint32_t flag = (raw & 0x08080808u) >> 3;          // 1 in the bytes whose code is 8 or more
+        const uint32_t up = (flag << 8) - flag;                  // 0xFF in those bytes
+        s.lo = (up & NOTHING) | (~up & raw);
+        s.hi = (up & (raw & 0x07070707u)) | (~up & NOTHING);
+        if (!valid) s.lo = NOTHING, s.hi = NOTHING;
+    } else {
+        s.lo = valid ? raw : NOTHING;
+        s.hi = 0;
+    }
+    return s;
+}
+
+// the weight operand of value group g: T[w(k)][4g + i] for the selector's 4 positions, i = 0..3
+template <int BITS>
+__device__ __forceinline__ v4i weight_operand(const Pools &pl, Sel s, int g)
+{
+    typedef Fmt<BITS> F;
+    v4i r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t *c = pl.w + (4 * g + i) * F::QW;
+        uint32_t d;
+        if (BITS == 2)
+            d = __builtin_amdgcn_perm(0u, c[0], s.lo);
+        else if (BITS == 3)
+            d = __builtin_amdgcn_perm(c[1 % F::QW], c[0], s.lo);
+        else
+            d = __builtin_amdgcn_perm(c[1 % F::QW], c[0], s.lo) | __builtin_amdgcn_perm(c[3 % F::QW], c[2 % F::QW], s.hi);
+        r[i] = (int)d;
+    }
+    return r;
+}
+
+// the activation operand of value group g: [a(k) == 4g + i]
+template <int BITS>
+__device__ __forceinline__ v4i onehot_operand(Sel s, int g)
+{
+    v4i r;
+    const uint32_t sel = (BITS == 4 && g >= 2) ? s.hi : s.lo;   // values 8..15 of 4-bit codes use the upper selector
+    const bool upper = (g & 1) != 0;                            // values 4..7 (12..15): the permute's upper source
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t one = 1u << (8 * i);
+        r[i] = (int)(upper ? __builtin_amdgcn_perm(one, 0u, sel) : __builtin_amdgcn_perm(0u, one, sel));
+    }
+    return r;
+}
+
+template <int N>
+__device__ __forceinline__ void sched_valu()
+{
+    __builtin_amdgcn_sched_group_barrier(0x002, N, 0);
+}
+
+// Position bookkeeping shared by the two kernels: output column n -> image coordinates, and the filter tap of a chunk.
+struct Column {
+    bool ok;
+    int ih0, iw0;
+    int64_t off0;
+};
+
+__device__ __forceinline__ Column make_column(const DgProblem &p, int n, int bytes_per_pixel, int lane_byte)
+{
+    Column c;
+    c.ok = n < p.N;
+    const int nn = c.ok ? n : 0;
+    const int ow = nn % p.OW, oh = (nn / p.OW) % p.OH, b = nn / (p.OW * p.OH);
+    c.ih0 = oh * p.sh - p.ph;
+    c.iw0 = ow * p.sw - p.pw;
+    c.off0 = (((int64_t)b * p.H + c.ih0) * p.W + c.iw0) * bytes_per_pixel + lane_byte;
+    return c;
+}
+
+// Large layers: each wavefront owns a (WM*32) x (WN*32) tile; operands come straight from global memory (L2), one
+// chunk ahead; no LDS, no barrier.
+template <int BITS, int WM, int WN, int CH, bool TR>
+__global__ void __launch_bounds__(256, (WM * WN > 8 ? 1 : 2))
+onehot_mfma_kernel(Args a)
+{
+    typedef Fmt<BITS> F;
+    const DgProblem &p = a.p;
+    const int lane = threadIdx.x & 63;
+    const int64_t wave_tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (wave_tile >= a.wave_tiles) return;                 // whole waves leave; there is no barrier below
+    const int r = lane & 31, h = lane >> 5;
+    const int m0 = (int)(wave_tile % a.tiles_m) * (WM * 32);
+    const int n0 = (int)(wave_tile / a.tiles_m) * (WN * 32);
+    const int cq = p.Cin / F::PER_BYTE;                     // packed bytes per pixel
+    constexpr int CHUNK = 8 * CH * F::PER_BYTE;             // codes of K per chunk: 4*CH packed bytes per lane half
+
+    const uint8_t *w_ptr[WM];
+#pragma unroll
+    for (int bm = 0; bm < WM; ++bm) {
+        int m = m0 + bm * 32 + r;
+        if (m >= p.M) m = p.M - 1;
+        w_ptr[bm] = p.Wp + (int64_t)m * (p.K / F::PER_BYTE) + h * (4 * CH);
+    }
+    Column col[WN];
+#pragma unroll
+    for (int bn = 0; bn < WN; ++bn) col[bn] = make_column(p, n0 + bn * 32 + r, cq, h * (4 * CH));
+
+    v16i acc[WM][WN];
+#pragma unroll
+    for (int bm = 0; bm < WM; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < WN; ++bn)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[bm][bn][e] = 0;
+
+    int kh = 0, kw = 0, ci = 0;
+    Words<CH> wa[WM], wb[WN];
+    bool vb[WN];
+    auto fetch = [&](int chunk) {
+#pragma unroll
+        for (int bm = 0; bm < WM; ++bm) wa[bm] = load_words<CH>(w_ptr[bm] + (int64_t)chunk * (8 * CH));
+        const int64_t tap_off = ((int64_t)kh * p.W + kw) * cq + ci / F::PER_BYTE;
+#pragma unroll
+        for (int bn = 0; bn < WN; ++bn) {
+            const int ih = col[bn].ih0 + kh, iw = col[bn].iw0 + kw;
+            vb[bn] = col[bn].ok & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
+            // always load (a tap outside the image reads the first pixel instead and is masked by its selector): a
+            // load under a branch would make the compiler wait for it at once, and the prefetch would hide nothing
+            wb[bn] = load_words<CH>(vb[bn] ? p.Xp + col[bn].off0 + tap_off : p.Xp + h * (4 * CH));
+        }
+        ci += CHUNK;
+        if (ci == p.Cin) {
+            ci = 0;
+            if (++kw == p.KW) {
+                kw = 0;
+                ++kh;
+            }
+        }
+    };
+
+    const int chunks = p.K / CHUNK;
+    fetch(0);
+    for (int c = 0; c < chunks; ++c) {
+        Words<CH> ca[WM], cb[WN];
+        bool valid[WN];
+#pragma unroll
+        for (int bm = 0; bm < WM; ++bm) ca[bm] = wa[bm];
+#pragma unroll
+        for (int bn = 0; bn < WN; ++bn) {
+            cb[bn] = wb[bn];
+            valid[bn] = vb[bn];
+        }
+        fetch(c + 1 < chunks ? c + 1 : c);                  // unconditional (the last one re-reads in bounds and is unused)
+        // Step t = one MFMA per block of the tile: word t / STEPS, selector j of it, value group g.  The operands of
+        // step t+1 are built between the MFMAs of step t so that the matrix unit and the VALU of a single wavefront
+        // overlap; the scheduling groups pin that interleaving.
+        constexpr int T = F::STEPS * CH;
+        v4i fa[2][WM], fb[2][WN];
+        Sel sa[WM], sb[WN];
+        auto expand = [&](int t, int u, int buf) {           // operand u of step t: u < WM weights, else activations
+            const int word = t / F::STEPS, j = (t % F::STEPS) / F::GROUPS, g = t % F::GROUPS;
+            if (u < WM) {
+                if (g == 0) sa[u] = make_sel<BITS>(ca[u].v[word], j, true);
+                fa[buf][u] = weight_operand<BITS>(a.pools, sa[u], g);
+            } else {
+                if (g == 0) sb[u - WM] = make_sel<BITS>(cb[u - WM].v[word], j, valid[u - WM]);
+                fb[buf][u - WM] = onehot_operand<BITS>(sb[u - WM], g);
+            }
+        };
+#pragma unroll
+        for (int u = 0; u < WM + WN; ++u) expand(0, u, 0);
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int cur = t & 1;
+#pragma unroll
+            for (int i = 0; i < WM * WN; ++i) {
+                const int bm = i / WN, bn = i % WN;
+                acc[bm][bn] = dg_mfma_step<TR>(fa[cur][bm], fb[cur][bn], acc[bm][bn]);
+                // the WM + WN operands of the next step are spread evenly over the WM * WN MFMAs of this one
+                constexpr int U = WM + WN, MN = WM * WN;
+                const int u0 = i * U / MN, u1 = (i + 1) * U / MN;
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                         // one MFMA ...
+                if (t + 1 < T) {
+#pragma unroll
+                    for (int u = u0; u < u1; ++u) {
+                        expand(t + 1, u, cur ^ 1);
+                        if (u < WM)
+                            sched_valu<F::VALU_W>();                                       // ... then that VALU work
+                        else
+                            sched_valu<F::VALU_A>();
+                    }
+                }
+            }
+        }
+    }
+
+    dg_mfma_store_tile<WM, WN, TR>(p, acc, m0, n0, lane);
+}
+
+// Small layers: too few 64 x 32 tiles to occupy the chip, and a wavefront that walks all of K alone pays the memory
+// latency once per chunk.  Here a workgroup owns ONE 32 x 32 output block and its S wavefronts split K between them
+// (whole chunks each), so a layer with T blocks puts T*S wavefronts in flight and each of them waits for memory once
+// or twice.  Partial blocks meet in LDS: every wavefront writes its 16 accumulator registers, one barrier, then the
+// threads add the S partials of each output element (integer, so exact in any order) and store it -- 128 contiguous
+// bytes per half wavefront, as in the large-layer kernel.
+template <int BITS, int CH, bool TR>
+__global__ void __launch_bounds__(1024)
+onehot_splitk_kernel(SplitArgs a)
+{
+    typedef Fmt<BITS> F;
+    extern __shared__ int32_t s_part[];                     // [S][16][64]
+    const DgProblem &p = a.p;
+    const int lane = threadIdx.x & 63, ws = threadIdx.x >> 6, S = blockDim.x >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int m0 = ((int)blockIdx.x % a.tiles_m) * 32;
+    const int n0 = ((int)blockIdx.x / a.tiles_m) * 32;
+    const int cq = p.Cin / F::PER_BYTE;
+    constexpr int CHUNK = 8 * CH * F::PER_BYTE;
+    const int c0 = ws * a.cpw, c1 = min(c0 + a.cpw, a.chunks);
+
+    v16i acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0;
+
+    if (c0 < c1) {
+        const int m = min(m0 + r, p.M - 1);
+        const uint8_t *w_ptr = p.Wp + (int64_t)m * (p.K / F::PER_BYTE) + h * (4 * CH);
+        const Column col = make_column(p, n0 + r, cq, h * (4 * CH));
+        // filter tap of this wavefront's first chunk
+        const int pos = c0 * CHUNK, tap = pos / p.Cin;
+        int ci = pos - tap * p.Cin, kh = tap / p.KW, kw = tap - (tap / p.KW) * p.KW;
+
+        Words<CH> wa, wb;
+        bool vb;
+        auto fetch = [&](int chunk) {
+            wa = load_words<CH>(w_ptr + (int64_t)chunk * (8 * CH));
+            const int ih = col.ih0 + kh, iw = col.iw0 + kw;
+            vb = col.ok & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
+            const int64_t tap_off = ((int64_t)kh * p.W + kw) * cq + ci / F::PER_BYTE;
+            wb = load_words<CH>(vb ? p.Xp + col.off0 + tap_off : p.Xp + h * (4 * CH));
+            ci += CHUNK;
+            if (ci == p.Cin) {
+                ci = 0;
+                if (++kw == p.KW) {
+                    kw = 0;
+                    ++kh;
+                }
+            }
+        };
+        fetch(c0);
+        for (int c = c0; c < c1; ++c) {
+            const Words<CH> ca = wa, cb = wb;
+            const bool valid = vb;
+            fetch(c + 1 < c1 ? c + 1 : c);                  // unconditional (the last one re-reads in bounds and is unused)
+#pragma unroll
+            for (int word = 0; word < CH; ++word)
+#pragma unroll
+                for (int j = 0; j < F::SELS; ++j) {
+                    const Sel sa = make_sel<BITS>(ca.v[word], j, true), sb = make_sel<BITS>(cb.v[word], j, valid);
+#pragma unroll
+                    for (int g = 0; g < F::GROUPS; ++g)
+                        acc = dg_mfma_step<TR>(weight_operand<BITS>(a.pools, sa, g), onehot_operand<BITS>(sb, g), acc);
+                }
+        }
+    }
+
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s_part[(ws * 16 + e) * 64 + lane] = acc[e];
+    __syncthreads();
+
+    for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
+        const int e = idx >> 6, l = idx & 63;
+        int32_t sum = 0;
+        for (int w = 0; w < S; ++w) sum += s_part[(w * 16 + e) * 64 + l];
+        const int row = 8 * (e / 4) + 4 * (l >> 5) + (e % 4), c = l & 31;       // MFMA block coordinates
+        const int m = m0 + (TR ? c : row), n = n0 + (TR ? row : c);
+        if (m >= p.M || n >= p.N) continue;
+        const int64_t o = (int64_t)m * p.stride_cm + (int64_t)n * p.stride_cn;
+        if (p.scale)
+            p.Cf[o] = (float)sum * p.scale[m];
+        else
+            p.C[o] = sum;
+    }
+}
+
+// What runs a problem: the split-K kernel with S wavefronts per block, or the large-layer kernel with a 64 x (32*wn) tile.
+struct Plan {
+    int ch;          // 32-bit words of packed codes per lane half and chunk
+    bool split;
+    int wn;
+    int S, cpw, chunks;
+};
+
+template <int BITS, int WM, int WN, bool TR>
+void launch_ch(const Args &a, int ch, dim3 grid, hipStream_t stream)
+{
+    // (4-bit codes: the host never plans 4-word chunks -- 32 MFMA steps -- so they are not instantiated)
+    if constexpr (BITS != 4) {
+        if (ch == 4) {
+            hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 4, TR>), grid, dim3(256), 0, stream, a);
+            return;
+        }
+    }
+    if (ch == 2)
+        hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 2, TR>), grid, dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 1, TR>), grid, dim3(256), 0, stream, a);
+}
+
+template <int BITS, bool TR>
+void launch_tr(const DgProblem &p, const Pools &pools, const Plan &q, int64_t blocks11, int64_t wave_tiles,
+               hipStream_t stream)
+{
+    if (q.split) {
+        SplitArgs b;
+        b.p = p;
+        b.pools = pools;
+        b.chunks = q.chunks;
+        b.cpw = q.cpw;
+        b.tiles_m = (p.M + 31) / 32;
+        const dim3 grid((unsigned)blocks11), block(64 * q.S);
+        const size_t lds = (size_t)q.S * 16 * 64 * sizeof(int32_t);
+        if constexpr (BITS != 4) {
+            if (q.ch == 4) {
+                hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 4, TR>), grid, block, lds, stream, b);
+                return;
+            }
+        }
+        if (q.ch == 2)
+            hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 2, TR>), grid, block, lds, stream, b);
+        else
+            hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 1, TR>), grid, block, lds, stream, b);
+        return;
+    }
+    Args a;
+    a.p = p;
+    a.pools = pools;
+    a.tiles_m = (p.M + 63) / 64;
+    a.wave_tiles = wave_tiles;
+    const dim3 grid((unsigned)((wave_tiles + 3) / 4));
+    if (q.wn == 7)
+        launch_ch<BITS, 2, 7, TR>(a, q.ch, grid, stream);
+    else if (q.wn == 4)
+        launch_ch<BITS, 2, 4, TR>(a, q.ch, grid, stream);
+    else if (q.wn == 2)
+        launch_ch<BITS, 2, 2, TR>(a, q.ch, grid, stream);
+    else
+        launch_ch<BITS, 2, 1, TR>(a, q.ch, grid, stream);
+}
+
+// One translation unit per code width and output layout instantiates launch_tr (the kernels are many: 4 tiles x
+// 3 chunk sizes each).  TR: the output axis with stride 1 goes on the MFMA columns (see dg_mfma_tile.h).
+#define DGOH_DECLARE(B, T) \
+    void launch_bits##B##_tr##T(const DgProblem &, const Pools &, const Plan &, int64_t, int64_t, hipStream_t);
+DGOH_DECLARE(2, 0) DGOH_DECLARE(2, 1) DGOH_DECLARE(3, 0) DGOH_DECLARE(3, 1) DGOH_DECLARE(4, 0) DGOH_DECLARE(4, 1)
+#undef DGOH_DECLARE
+
+}   // namespace dgoh

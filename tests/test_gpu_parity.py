@@ -333,38 +333,58 @@ def test_quantize_pack_feeds_the_convolution():
 
 
 WIDE = {
-    3: ([-4, -3, -2, -1, 0, 1, 2, 3], [0, 1, 2, 3, 4, 5, 6, 7]),
+    3: ([-4, -3, -2, -1, 0, 1, 2, 3], [5, 1, 2, 3, 4, 7, 6, 9]),        # no zero activation level: padding must still add 0
     4: (list(range(-8, 8)), [0, 3, 1, 7, 2, 9, 4, 15, 5, 6, 8, 10, 11, 12, 13, 14]),
 }
 
 
+@pytest.mark.parametrize("plan", ["auto", "lds", "split", "1", "2", "4", "7"])
 @pytest.mark.parametrize("bits", [3, 4])
-def test_wide_codes_gemm_and_conv(bits):
-    # Sec. 3.3 / Table 2: 64- and 256-entry tables; they run on the LDS kernel (AUTO picks it, the others decline)
+def test_wide_codes_gemm_and_conv(bits, plan, monkeypatch):
+    """Sec. 3.3 / Table 2: 64- and 256-entry tables.  They run on the LDS kernel (every shape) and on the one-hot
+    matrix-core kernels (Cin % 16 == 0), whose every plan is forced in turn; the 2-bit-only kernels decline."""
     lw, la = WIDE[bits]
     nlev = 1 << bits
     rng = np.random.default_rng(50 + bits)
     lut = dg.dg_build_lut_bits(bits, lw, la, dg.DG_LUT_I8)
-    for M, N, K in ((5, 7, 6), (64, 196, 576), (33, 130, 40)):
+    variant = plan if plan in ("auto", "lds") else "onehot_mfma"
+    if variant == "onehot_mfma":
+        monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
+    for M, N, K in ((5, 7, 6), (64, 196, 576), (33, 130, 40), (70, 300, 64), (40, 1000, 96), (130, 257, 1024)):
         Wc, Ac = wl.draw_codes(rng, (M, K), nlev=nlev), wl.draw_codes(rng, (N, K), nlev=nlev)
         Wp = dg.dg_pack_codes_bits(torch.from_numpy(Wc).cuda(), M, K, bits)
         Ap = dg.dg_pack_codes_bits(torch.from_numpy(Ac).cuda(), N, K, bits)
         _assert_same(Ap.cpu().numpy().reshape(N, K // 2), oracle.pack_codes(Ac, bits), f"{bits}-bit pack")
-        got = dg.dg_gemm_lut(lut, Wp, Ap, M, N, K)
+        name = dg.dg_gemm_kernel_name(lut, M, N, K, variant)
+        if K % 16 != 0:
+            assert name == ("lds" if variant != "onehot_mfma" else "unsupported")
+        else:
+            assert name.startswith("lds" if variant == "lds" else "onehot_mfma")
+        if name == "unsupported":
+            continue
+        got = dg.dg_gemm_lut(lut, Wp, Ap, M, N, K, variant=variant)
         torch.cuda.synchronize()
-        _assert_same(got.cpu().numpy(), oracle.gemm(Wc, Ac, lw, la), f"{bits}-bit gemm {(M, N, K)}")
-        assert dg.dg_gemm_kernel_name(lut, M, N, K) == "lds"
+        want = oracle.gemm(Wc, Ac, lw, la)
+        _assert_same(got.cpu().numpy(), want, f"{bits}-bit gemm {(M, N, K)} {plan}")
+        out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")         # column-major output
+        dg.dg_gemm_lut(lut, Wp, Ap, M, N, K, out=out, variant=variant, strides=(1, M))
+        torch.cuda.synchronize()
+        _assert_same(out.cpu().numpy(), want.T.copy(), f"{bits}-bit gemm {(M, N, K)} {plan} column-major")
         with pytest.raises(dg.DgError) as e:
             dg.dg_gemm_lut(lut, Wp, Ap, M, N, K, variant="perm")
         assert e.value.status == 5
-    B, H, W, Cin, Cout = 2, 9, 7, 16, 12
-    Wc = wl.draw_codes(rng, (Cout, 3, 3, Cin), nlev=nlev)
-    Xc = wl.draw_codes(rng, (B, H, W, Cin), nlev=nlev)
-    Wp = dg.dg_pack_codes_bits(torch.from_numpy(Wc).cuda(), Cout, 9 * Cin, bits)
-    Xp = dg.dg_pack_codes_bits(torch.from_numpy(Xc).cuda(), B * H * W, Cin, bits)
-    y = dg.dg_conv2d_lut(lut, Wp, Xp, dg.conv_desc(B, H, W, Cin, Cout, 3, 3, (2, 1), (1, 1)))
-    torch.cuda.synchronize()
-    _assert_same(y.cpu().numpy(), oracle.conv2d(Wc, Xc, lw, la, stride=(2, 1), pad=(1, 1)), f"{bits}-bit conv")
+    for (B, H, W, Cin, Cout, KH, KW, stride, pad) in [(2, 9, 7, 16, 12, 3, 3, (2, 1), (1, 1)),
+                                                      (2, 20, 20, 32, 70, 3, 3, (1, 1), (1, 1)),
+                                                      (1, 17, 15, 64, 40, 5, 5, (1, 1), (2, 2)),
+                                                      (3, 12, 12, 128, 33, 1, 1, (1, 1), (0, 0))]:
+        Wc = wl.draw_codes(rng, (Cout, KH, KW, Cin), nlev=nlev)
+        Xc = wl.draw_codes(rng, (B, H, W, Cin), nlev=nlev)
+        Wp = dg.dg_pack_codes_bits(torch.from_numpy(Wc).cuda(), Cout, KH * KW * Cin, bits)
+        Xp = dg.dg_pack_codes_bits(torch.from_numpy(Xc).cuda(), B * H * W, Cin, bits)
+        y = dg.dg_conv2d_lut(lut, Wp, Xp, dg.conv_desc(B, H, W, Cin, Cout, KH, KW, stride, pad), variant=variant)
+        torch.cuda.synchronize()
+        _assert_same(y.cpu().numpy(), oracle.conv2d(Wc, Xc, lw, la, stride=stride, pad=pad),
+                     f"{bits}-bit conv {(B, H, W, Cin, Cout)} {plan}")
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
