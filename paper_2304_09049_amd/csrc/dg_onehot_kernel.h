@@ -33,9 +33,32 @@ struct Pools {
     uint32_t w[64];
 };
 
+// n / d for 0 <= n < 2^31 by multiply-high and shift (d fixed per launch, prepared on the host: with
+// L = ceil(log2 d), mul = ceil(2^(31+L) / d) and shift = L - 1; d = 1 is passed through)
+struct FastDiv {
+    uint32_t mul, shift, d;
+};
+
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f)
+{
+    return f.d == 1 ? n : __umulhi(n, f.mul) >> f.shift;
+}
+
+inline FastDiv make_div(uint32_t d)
+{
+    FastDiv f = {0u, 0u, d};
+    if (d < 2) return f;
+    uint32_t L = 0;
+    while ((1ull << L) < d) ++L;
+    f.mul = (uint32_t)(((1ull << (31 + L)) + d - 1) / d);
+    f.shift = L - 1;
+    return f;
+}
+
 struct Args {
     DgProblem p;
     Pools pools;
+    FastDiv div_ow, div_oh;
     int32_t tiles_m;
     int64_t wave_tiles;
 };
@@ -43,6 +66,7 @@ struct Args {
 struct SplitArgs {
     DgProblem p;
     Pools pools;
+    FastDiv div_ow, div_oh, div_cin, div_kw;
     int32_t tiles_m;
     int32_t chunks;          // K / (codes per chunk)
     int32_t cpw;             // chunks per wavefront
@@ -159,12 +183,14 @@ struct Column {
     int64_t off0;
 };
 
-__device__ __forceinline__ Column make_column(const DgProblem &p, int n, int bytes_per_pixel, int lane_byte)
+__device__ __forceinline__ Column make_column(const DgProblem &p, const FastDiv &div_ow, const FastDiv &div_oh, int n,
+                                              int bytes_per_pixel, int lane_byte)
 {
     Column c;
     c.ok = n < p.N;
     const int nn = c.ok ? n : 0;
-    const int ow = nn % p.OW, oh = (nn / p.OW) % p.OH, b = nn / (p.OW * p.OH);
+    const int t = (int)fdiv((uint32_t)nn, div_ow), ow = nn - t * p.OW;
+    const int b = (int)fdiv((uint32_t)t, div_oh), oh = t - b * p.OH;
     c.ih0 = oh * p.sh - p.ph;
     c.iw0 = ow * p.sw - p.pw;
     c.off0 = (((int64_t)b * p.H + c.ih0) * p.W + c.iw0) * bytes_per_pixel + lane_byte;
@@ -197,7 +223,7 @@ onehot_mfma_kernel(Args a)
     }
     Column col[WN];
 #pragma unroll
-    for (int bn = 0; bn < WN; ++bn) col[bn] = make_column(p, n0 + bn * 32 + r, cq, h * (4 * CH));
+    for (int bn = 0; bn < WN; ++bn) col[bn] = make_column(p, a.div_ow, a.div_oh, n0 + bn * 32 + r, cq, h * (4 * CH));
 
     v16i acc[WM][WN];
 #pragma unroll
@@ -310,24 +336,28 @@ onehot_splitk_kernel(SplitArgs a)
     const int n0 = ((int)blockIdx.x / a.tiles_m) * 32;
     const int cq = p.Cin / F::PER_BYTE;
     constexpr int CHUNK = 8 * CH * F::PER_BYTE;
-    const int c0 = ws * a.cpw, c1 = min(c0 + a.cpw, a.chunks);
+    // every wavefront has at least one chunk (the host sizes S that way); the max only keeps an odd launch harmless
+    const int c0 = ws * a.cpw, c1 = max(c0, min(c0 + a.cpw, a.chunks));
 
     v16i acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0;
 
-    if (c0 < c1) {
-        const int m = min(m0 + r, p.M - 1);
-        const uint8_t *w_ptr = p.Wp + (int64_t)m * (p.K / F::PER_BYTE) + h * (4 * CH);
-        const Column col = make_column(p, n0 + r, cq, h * (4 * CH));
+    // The prologue is most of this kernel's life, so it is ordered for latency: the weight load needs no division and
+    // goes first; the scale of the epilogue (NHWC: one channel per thread whatever element it sums) is fetched now.
+    const int mw = min(m0 + r, p.M - 1);
+    const uint8_t *w_ptr = p.Wp + (int64_t)mw * (p.K / F::PER_BYTE) + h * (4 * CH);
+    Words<CH> wa = load_words<CH>(w_ptr + (int64_t)min(c0, a.chunks - 1) * (8 * CH)), wb;
+    float sc = 0.0f;
+    if (TR && p.scale) sc = p.scale[mw];
+    {
+        const Column col = make_column(p, a.div_ow, a.div_oh, n0 + r, cq, h * (4 * CH));
         // filter tap of this wavefront's first chunk
-        const int pos = c0 * CHUNK, tap = pos / p.Cin;
-        int ci = pos - tap * p.Cin, kh = tap / p.KW, kw = tap - (tap / p.KW) * p.KW;
+        const int pos = c0 * CHUNK, tap = (int)fdiv((uint32_t)pos, a.div_cin), tkh = (int)fdiv((uint32_t)tap, a.div_kw);
+        int ci = pos - tap * p.Cin, kh = tkh, kw = tap - tkh * p.KW;
 
-        Words<CH> wa, wb;
         bool vb;
-        auto fetch = [&](int chunk) {
-            wa = load_words<CH>(w_ptr + (int64_t)chunk * (8 * CH));
+        auto fetch_x = [&]() {
             const int ih = col.ih0 + kh, iw = col.iw0 + kw;
             vb = col.ok & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
             const int64_t tap_off = ((int64_t)kh * p.W + kw) * cq + ci / F::PER_BYTE;
@@ -341,11 +371,13 @@ onehot_splitk_kernel(SplitArgs a)
                 }
             }
         };
-        fetch(c0);
+        fetch_x();
         for (int c = c0; c < c1; ++c) {
             const Words<CH> ca = wa, cb = wb;
             const bool valid = vb;
-            fetch(c + 1 < c1 ? c + 1 : c);                  // unconditional (the last one re-reads in bounds and is unused)
+            // unconditional prefetch (the last one re-reads in bounds and is unused)
+            wa = load_words<CH>(w_ptr + (int64_t)(c + 1 < c1 ? c + 1 : c) * (8 * CH));
+            fetch_x();
 #pragma unroll
             for (int word = 0; word < CH; ++word)
 #pragma unroll
@@ -371,7 +403,7 @@ onehot_splitk_kernel(SplitArgs a)
         if (m >= p.M || n >= p.N) continue;
         const int64_t o = (int64_t)m * p.stride_cm + (int64_t)n * p.stride_cn;
         if (p.scale)
-            p.Cf[o] = (float)sum * p.scale[m];
+            p.Cf[o] = (float)sum * (TR ? sc : p.scale[m]);      // TR: m = m0 + thread % 32, the channel fetched above
         else
             p.C[o] = sum;
     }
@@ -412,6 +444,8 @@ void launch_tr(const DgProblem &p, const Pools &pools, const Plan &q, int64_t bl
         b.chunks = q.chunks;
         b.cpw = q.cpw;
         b.tiles_m = (p.M + 31) / 32;
+        b.div_ow = make_div((uint32_t)p.OW), b.div_oh = make_div((uint32_t)p.OH);
+        b.div_cin = make_div((uint32_t)p.Cin), b.div_kw = make_div((uint32_t)p.KW);
         const dim3 grid((unsigned)blocks11), block(64 * q.S);
         const size_t lds = (size_t)q.S * 16 * 64 * sizeof(int32_t);
         if constexpr (BITS != 4) {
@@ -431,6 +465,7 @@ void launch_tr(const DgProblem &p, const Pools &pools, const Plan &q, int64_t bl
     a.pools = pools;
     a.tiles_m = (p.M + 63) / 64;
     a.wave_tiles = wave_tiles;
+    a.div_ow = make_div((uint32_t)p.OW), a.div_oh = make_div((uint32_t)p.OH);
     const dim3 grid((unsigned)((wave_tiles + 3) / 4));
     if (q.wn == 7)
         launch_ch<BITS, 2, 7, TR>(a, q.ch, grid, stream);
