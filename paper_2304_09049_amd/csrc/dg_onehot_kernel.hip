@@ -39,7 +39,9 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p)
     if (q.split) {
         // about 2048 wavefronts in all, at most 16 per workgroup, whole chunks each
         const int64_t blocks = tile_count(p, 1, 1);
-        int S = (int)((2048 + blocks - 1) / blocks);
+        int64_t target = 2048;
+        if (const char *e = getenv("DG_ONEHOT_WAVES")) target = atoi(e) > 0 ? atoi(e) : target;   // tuning override
+        int S = (int)((target + blocks - 1) / blocks);
         S = S < 1 ? 1 : (S > 16 ? 16 : S);
         if (S > q.chunks) S = q.chunks;
         q.cpw = (q.chunks + S - 1) / S;
