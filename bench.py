@@ -274,17 +274,20 @@ def stage_kernels(torch, w):
 
 
 def wide_code_kernels(torch, w, use_graph):
-    """The 3- and 4-bit tables of Sec. 3.3 / Table 2 on the shape of workload `w` (a convolution): the one-hot
-    matrix-core kernel AUTO picks and the plain LDS kernel.  The MFMA fraction counts the operations issued:
-    2^bits per effective operation."""
+    """Tables beyond the 16 int8 entries of the headline path, on the shape of workload `w` (a convolution): 2-bit codes
+    with int16 entries (two int8 planes), and the 3- and 4-bit tables of Sec. 3.3 / Table 2; each on the one-hot
+    matrix-core kernel AUTO picks and on the plain LDS kernel.  The MFMA fraction counts the operations issued:
+    2^bits per effective operation (8 for the two planes of 2-bit codes)."""
     from paper_2304_09049_amd import binding as dg
     dev = torch.device("cuda:0")
     report = []
-    for bits in (3, 4):
+    for bits in (2, 3, 4):
         nlev = 1 << bits
-        lw = list(range(-(nlev // 2), nlev // 2))
-        la = list(range(nlev))
-        lut = dg.dg_build_lut_bits(bits, lw, la, dg.DG_LUT_I8)
+        if bits == 2:
+            # 2-bit codes with entries up to 16384: beyond int8, so the one-hot kernel selects from two int8 planes
+            lut = dg.dg_build_lut_bits(2, [127, -128, 5, 3], [-128, 127, 1, 2], dg.DG_LUT_I16)
+        else:
+            lut = dg.dg_build_lut_bits(bits, list(range(-(nlev // 2), nlev // 2)), list(range(nlev)), dg.DG_LUT_I8)
         gen = torch.Generator(device=dev).manual_seed(bits)
         Wc = torch.randint(0, nlev, (w.Cout, w.KH, w.KW, w.Cin), dtype=torch.uint8, device=dev, generator=gen)
         Xc = torch.randint(0, nlev, (w.B, w.H, w.W, w.Cin), dtype=torch.uint8, device=dev, generator=gen)
@@ -299,7 +302,7 @@ def wide_code_kernels(torch, w, use_graph):
             tops = w.ops / (ms * 1e-3) / 1e12
             report.append({"bits": bits, "workload_shape": w.name, "variant": variant, "kernel": name,
                            "us": round(ms * 1e3, 3), "gops": round(tops * 1e3, 1),
-                           "frac_int8_mfma_peak": round(nlev * tops / INT8_MFMA_PEAK_TOPS, 4)
+                           "frac_int8_mfma_peak": round((8 if bits == 2 else nlev) * tops / INT8_MFMA_PEAK_TOPS, 4)
                            if name.startswith("onehot_mfma") else None})
     return report
 

@@ -153,7 +153,8 @@ dg_status dg_quantize_pack_activations(const float *x_dev, int64_t N, int64_t K,
  *            the dot product of the four code pairs, kept in LDS; one fetch per four products
  *   ONEHOT_MFMA  table kernel on the matrix cores: each int8 MFMA multiply is by a one-hot byte of the activation
  *            code, i.e. it selects one entry of the weight code's table row; any int8 entries, 2-, 3- or 4-bit
- *            codes (2^bits times the MFMA work of a plain int8 product); needs Cin % 32 == 0 (2-bit) or % 16 (3-, 4-bit)
+ *            codes (2^bits times the MFMA work of a plain int8 product); 2-bit tables with wider entries (up to
+ *            32639) are selected from two int8 planes; needs Cin % 32 == 0 (2-bit) or % 16 (3-, 4-bit)
  * A variant that cannot run the given shape or table returns DG_ERR_UNSUPPORTED.
  */
 typedef enum {

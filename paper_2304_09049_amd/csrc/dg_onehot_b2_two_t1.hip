@@ -1,0 +1,11 @@
+// The one-hot matrix-core kernels for 2-bit codes with entries beyond int8 (two int8 planes), output stride-1 axis =
+// m (NHWC convolution) (one translation unit per variant keeps build times even).
+#include "dg_onehot_kernel.h"
+
+namespace dgoh {
+void launch_bits2_two_tr1(const DgProblem &p, const Pools &pools, const Plan &q, int64_t blocks11, int64_t wave_tiles,
+                          hipStream_t stream)
+{
+    launch_tr<2, true, true>(p, pools, q, blocks11, wave_tiles, stream);
+}
+}   // namespace dgoh

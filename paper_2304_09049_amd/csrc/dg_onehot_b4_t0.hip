@@ -6,6 +6,6 @@ namespace dgoh {
 void launch_bits4_tr0(const DgProblem &p, const Pools &pools, const Plan &q, int64_t blocks11, int64_t wave_tiles,
                         hipStream_t stream)
 {
-    launch_tr<4, false>(p, pools, q, blocks11, wave_tiles, stream);
+    launch_tr<4, false, false>(p, pools, q, blocks11, wave_tiles, stream);
 }
 }   // namespace dgoh

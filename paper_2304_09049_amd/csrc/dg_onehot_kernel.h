@@ -19,6 +19,10 @@
 //                the selector of the codes from 8 up (each selector reads 0x0C = "constant 0" where it does not apply)
 //   activations  of a constant holding a single 1 at byte v % 4, in the lower or upper permute source as v / 4 says
 // A filter tap outside the image, or a column beyond N, gets selector bytes 0x0C: it selects nothing.
+//
+// Entries beyond int8 (2-bit codes only): the table is split into two int8 planes, T = 256 * hi + lo with
+// lo = ((T + 128) mod 256) - 128, each selected into an accumulator of its own (the two planes take the places of the
+// tile's two weight row blocks, so a tile covers 32 rows instead of 64), and the result is 256 * acc_hi + acc_lo.
 #pragma once
 
 #include "dg_mfma_tile.h"
@@ -28,7 +32,8 @@ namespace dgoh {
 typedef dg_v4i v4i;
 typedef dg_v16i v16i;
 
-// pool[v * (L/4) + q] = bytes T[4q .. 4q+3][v] (signed int8, as stored): column v of the table, 4 weight codes per word
+// pool[v * (L/4) + q] = bytes T[4q .. 4q+3][v] (signed int8, as stored): column v of the table, 4 weight codes per word.
+// A second plane (two-plane tables, 2-bit codes) sits at word 32.
 struct Pools {
     uint32_t w[64];
 };
@@ -136,13 +141,13 @@ __device__ __forceinline__ Sel make_sel(uint32_t word, int j, bool valid)
 
 // the weight operand of value group g: T[w(k)][4g + i] for the selector's 4 positions, i = 0..3
 template <int BITS>
-__device__ __forceinline__ v4i weight_operand(const Pools &pl, Sel s, int g)
+__device__ __forceinline__ v4i weight_operand(const Pools &pl, Sel s, int g, int plane = 0)
 {
     typedef Fmt<BITS> F;
     v4i r;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const uint32_t *c = pl.w + (4 * g + i) * F::QW;
+        const uint32_t *c = pl.w + 32 * plane + (4 * g + i) * F::QW;
         uint32_t d;
         if (BITS == 2)
             d = __builtin_amdgcn_perm(0u, c[0], s.lo);
@@ -199,24 +204,26 @@ __device__ __forceinline__ Column make_column(const DgProblem &p, const FastDiv 
 
 // Large layers: each wavefront owns a (WM*32) x (WN*32) tile; operands come straight from global memory (L2), one
 // chunk ahead; no LDS, no barrier.
-template <int BITS, int WM, int WN, int CH, bool TR>
+template <int BITS, int WM, int WN, int CH, bool TR, bool TWO>
 __global__ void __launch_bounds__(256, (WM * WN > 8 ? 1 : 2))
 onehot_mfma_kernel(Args a)
 {
     typedef Fmt<BITS> F;
+    static_assert(!TWO || (WM == 2 && BITS == 2), "two planes stand in for the two weight row blocks of 2-bit tiles");
+    constexpr int RB = TWO ? 1 : WM;                       // weight row blocks of 32 rows
     const DgProblem &p = a.p;
     const int lane = threadIdx.x & 63;
     const int64_t wave_tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (wave_tile >= a.wave_tiles) return;                 // whole waves leave; there is no barrier below
     const int r = lane & 31, h = lane >> 5;
-    const int m0 = (int)(wave_tile % a.tiles_m) * (WM * 32);
+    const int m0 = (int)(wave_tile % a.tiles_m) * (RB * 32);
     const int n0 = (int)(wave_tile / a.tiles_m) * (WN * 32);
     const int cq = p.Cin / F::PER_BYTE;                     // packed bytes per pixel
     constexpr int CHUNK = 8 * CH * F::PER_BYTE;             // codes of K per chunk: 4*CH packed bytes per lane half
 
-    const uint8_t *w_ptr[WM];
+    const uint8_t *w_ptr[RB];
 #pragma unroll
-    for (int bm = 0; bm < WM; ++bm) {
+    for (int bm = 0; bm < RB; ++bm) {
         int m = m0 + bm * 32 + r;
         if (m >= p.M) m = p.M - 1;
         w_ptr[bm] = p.Wp + (int64_t)m * (p.K / F::PER_BYTE) + h * (4 * CH);
@@ -234,11 +241,11 @@ onehot_mfma_kernel(Args a)
             for (int e = 0; e < 16; ++e) acc[bm][bn][e] = 0;
 
     int kh = 0, kw = 0, ci = 0;
-    Words<CH> wa[WM], wb[WN];
+    Words<CH> wa[RB], wb[WN];
     bool vb[WN];
     auto fetch = [&](int chunk) {
 #pragma unroll
-        for (int bm = 0; bm < WM; ++bm) wa[bm] = load_words<CH>(w_ptr[bm] + (int64_t)chunk * (8 * CH));
+        for (int bm = 0; bm < RB; ++bm) wa[bm] = load_words<CH>(w_ptr[bm] + (int64_t)chunk * (8 * CH));
         const int64_t tap_off = ((int64_t)kh * p.W + kw) * cq + ci / F::PER_BYTE;
 #pragma unroll
         for (int bn = 0; bn < WN; ++bn) {
@@ -261,10 +268,10 @@ onehot_mfma_kernel(Args a)
     const int chunks = p.K / CHUNK;
     fetch(0);
     for (int c = 0; c < chunks; ++c) {
-        Words<CH> ca[WM], cb[WN];
+        Words<CH> ca[RB], cb[WN];
         bool valid[WN];
 #pragma unroll
-        for (int bm = 0; bm < WM; ++bm) ca[bm] = wa[bm];
+        for (int bm = 0; bm < RB; ++bm) ca[bm] = wa[bm];
 #pragma unroll
         for (int bn = 0; bn < WN; ++bn) {
             cb[bn] = wb[bn];
@@ -276,12 +283,13 @@ onehot_mfma_kernel(Args a)
         // overlap; the scheduling groups pin that interleaving.
         constexpr int T = F::STEPS * CH;
         v4i fa[2][WM], fb[2][WN];
-        Sel sa[WM], sb[WN];
+        Sel sa[RB], sb[WN];
         auto expand = [&](int t, int u, int buf) {           // operand u of step t: u < WM weights, else activations
             const int word = t / F::STEPS, j = (t % F::STEPS) / F::GROUPS, g = t % F::GROUPS;
             if (u < WM) {
-                if (g == 0) sa[u] = make_sel<BITS>(ca[u].v[word], j, true);
-                fa[buf][u] = weight_operand<BITS>(a.pools, sa[u], g);
+                const int rb = TWO ? 0 : u, plane = TWO ? u : 0;    // two planes: one row block, selector made once
+                if (g == 0 && plane == 0) sa[rb] = make_sel<BITS>(ca[rb].v[word], j, true);
+                fa[buf][u] = weight_operand<BITS>(a.pools, sa[rb], g, plane);
             } else {
                 if (g == 0) sb[u - WM] = make_sel<BITS>(cb[u - WM].v[word], j, valid[u - WM]);
                 fb[buf][u - WM] = onehot_operand<BITS>(sb[u - WM], g);
@@ -314,7 +322,17 @@ onehot_mfma_kernel(Args a)
         }
     }
 
-    dg_mfma_store_tile<WM, WN, TR>(p, acc, m0, n0, lane);
+    if (TWO) {
+        v16i both[1][WN];
+#pragma unroll
+        for (int bn = 0; bn < WN; ++bn)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                both[0][bn][e] = (int)((uint32_t)acc[0][bn][e] + ((uint32_t)acc[1][bn][e] << 8));   // 256 * hi + lo
+        dg_mfma_store_tile<1, WN, TR>(p, both, m0, n0, lane);
+    } else {
+        dg_mfma_store_tile<WM, WN, TR>(p, acc, m0, n0, lane);
+    }
 }
 
 // Small layers: too few 64 x 32 tiles to occupy the chip, and a wavefront that walks all of K alone pays the memory
@@ -323,7 +341,7 @@ onehot_mfma_kernel(Args a)
 // or twice.  Partial blocks meet in LDS: every wavefront writes its 16 accumulator registers, one barrier, then the
 // threads add the S partials of each output element (integer, so exact in any order) and store it -- 128 contiguous
 // bytes per half wavefront, as in the large-layer kernel.
-template <int BITS, int CH, bool TR>
+template <int BITS, int CH, bool TR, bool TWO>
 __global__ void __launch_bounds__(1024)
 onehot_splitk_kernel(SplitArgs a)
 {
@@ -339,9 +357,9 @@ onehot_splitk_kernel(SplitArgs a)
     // every wavefront has at least one chunk (the host sizes S that way); the max only keeps an odd launch harmless
     const int c0 = ws * a.cpw, c1 = max(c0, min(c0 + a.cpw, a.chunks));
 
-    v16i acc;
+    v16i acc, acc_hi;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] = 0;
+    for (int e = 0; e < 16; ++e) acc[e] = 0, acc_hi[e] = 0;
 
     // The prologue is most of this kernel's life, so it is ordered for latency: the weight load needs no division and
     // goes first; the scale of the epilogue (NHWC: one channel per thread whatever element it sums) is fetched now.
@@ -384,10 +402,17 @@ onehot_splitk_kernel(SplitArgs a)
                 for (int j = 0; j < F::SELS; ++j) {
                     const Sel sa = make_sel<BITS>(ca.v[word], j, true), sb = make_sel<BITS>(cb.v[word], j, valid);
 #pragma unroll
-                    for (int g = 0; g < F::GROUPS; ++g)
-                        acc = dg_mfma_step<TR>(weight_operand<BITS>(a.pools, sa, g), onehot_operand<BITS>(sb, g), acc);
+                    for (int g = 0; g < F::GROUPS; ++g) {
+                        const v4i fb = onehot_operand<BITS>(sb, g);
+                        acc = dg_mfma_step<TR>(weight_operand<BITS>(a.pools, sa, g, 0), fb, acc);
+                        if (TWO) acc_hi = dg_mfma_step<TR>(weight_operand<BITS>(a.pools, sa, g, 1), fb, acc_hi);
+                    }
                 }
         }
+    }
+    if (TWO) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] = (int)((uint32_t)acc[e] + ((uint32_t)acc_hi[e] << 8));       // 256 * hi + lo
     }
 
 #pragma unroll
@@ -412,28 +437,31 @@ onehot_splitk_kernel(SplitArgs a)
 // What runs a problem: the split-K kernel with S wavefronts per block, or the large-layer kernel with a 64 x (32*wn) tile.
 struct Plan {
     int ch;          // 32-bit words of packed codes per lane half and chunk
+    bool two;        // entries beyond int8: two int8 planes
     bool split;
     int wn;
     int S, cpw, chunks;
 };
 
-template <int BITS, int WM, int WN, bool TR>
+template <int BITS, int WM, int WN, bool TR, bool TWO>
 void launch_ch(const Args &a, int ch, dim3 grid, hipStream_t stream)
 {
     // (4-bit codes: the host never plans 4-word chunks -- 32 MFMA steps -- so they are not instantiated)
     if constexpr (BITS != 4) {
         if (ch == 4) {
-            hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 4, TR>), grid, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 4, TR, TWO>), grid, dim3(256), 0, stream, a);
             return;
         }
     }
     if (ch == 2)
-        hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 2, TR>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 2, TR, TWO>), grid, dim3(256), 0, stream, a);
     else
-        hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 1, TR>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 1, TR, TWO>), grid, dim3(256), 0, stream, a);
 }
 
-template <int BITS, bool TR>
+// `blocks11`: 32 x 32 blocks of the output (the split-K grid); `wave_tiles`: tiles of the planned width, 64 rows high
+// (32 with two planes), 4 per workgroup.
+template <int BITS, bool TR, bool TWO>
 void launch_tr(const DgProblem &p, const Pools &pools, const Plan &q, int64_t blocks11, int64_t wave_tiles,
                hipStream_t stream)
 {
@@ -450,31 +478,31 @@ void launch_tr(const DgProblem &p, const Pools &pools, const Plan &q, int64_t bl
         const size_t lds = (size_t)q.S * 16 * 64 * sizeof(int32_t);
         if constexpr (BITS != 4) {
             if (q.ch == 4) {
-                hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 4, TR>), grid, block, lds, stream, b);
+                hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 4, TR, TWO>), grid, block, lds, stream, b);
                 return;
             }
         }
         if (q.ch == 2)
-            hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 2, TR>), grid, block, lds, stream, b);
+            hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 2, TR, TWO>), grid, block, lds, stream, b);
         else
-            hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 1, TR>), grid, block, lds, stream, b);
+            hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 1, TR, TWO>), grid, block, lds, stream, b);
         return;
     }
     Args a;
     a.p = p;
     a.pools = pools;
-    a.tiles_m = (p.M + 63) / 64;
+    a.tiles_m = TWO ? (p.M + 31) / 32 : (p.M + 63) / 64;
     a.wave_tiles = wave_tiles;
     a.div_ow = make_div((uint32_t)p.OW), a.div_oh = make_div((uint32_t)p.OH);
     const dim3 grid((unsigned)((wave_tiles + 3) / 4));
     if (q.wn == 7)
-        launch_ch<BITS, 2, 7, TR>(a, q.ch, grid, stream);
+        launch_ch<BITS, 2, 7, TR, TWO>(a, q.ch, grid, stream);
     else if (q.wn == 4)
-        launch_ch<BITS, 2, 4, TR>(a, q.ch, grid, stream);
+        launch_ch<BITS, 2, 4, TR, TWO>(a, q.ch, grid, stream);
     else if (q.wn == 2)
-        launch_ch<BITS, 2, 2, TR>(a, q.ch, grid, stream);
+        launch_ch<BITS, 2, 2, TR, TWO>(a, q.ch, grid, stream);
     else
-        launch_ch<BITS, 2, 1, TR>(a, q.ch, grid, stream);
+        launch_ch<BITS, 2, 1, TR, TWO>(a, q.ch, grid, stream);
 }
 
 // One translation unit per code width and output layout instantiates launch_tr (the kernels are many: 4 tiles x
@@ -483,5 +511,8 @@ void launch_tr(const DgProblem &p, const Pools &pools, const Plan &q, int64_t bl
     void launch_bits##B##_tr##T(const DgProblem &, const Pools &, const Plan &, int64_t, int64_t, hipStream_t);
 DGOH_DECLARE(2, 0) DGOH_DECLARE(2, 1) DGOH_DECLARE(3, 0) DGOH_DECLARE(3, 1) DGOH_DECLARE(4, 0) DGOH_DECLARE(4, 1)
 #undef DGOH_DECLARE
+// the two-plane kernels (2-bit codes, entries beyond int8)
+void launch_bits2_two_tr0(const DgProblem &, const Pools &, const Plan &, int64_t, int64_t, hipStream_t);
+void launch_bits2_two_tr1(const DgProblem &, const Pools &, const Plan &, int64_t, int64_t, hipStream_t);
 
 }   // namespace dgoh

@@ -15,9 +15,13 @@ int64_t tile_count(const DgProblem &p, int wm, int wn)
     return ((int64_t)(p.M + wm * 32 - 1) / (wm * 32)) * (((int64_t)p.N + wn * 32 - 1) / (wn * 32));
 }
 
+bool fits_int8(const dg_lut *lut) { return lut->min_entry >= -128 && lut->max_entry <= 127; }
+
 Plan plan_for(const dg_lut *lut, const DgProblem &p)
 {
     Plan q;
+    q.two = !fits_int8(lut);                               // two int8 planes; a tile is then 32 rows high, not 64
+    const int wm = q.two ? 1 : 2;
     // a lane half reads 4*ch packed bytes of one filter tap per chunk
     const int tap_bytes = p.Cin / per_byte(lut);
     q.ch = tap_bytes % 32 == 0 ? 4 : (tap_bytes % 16 == 0 ? 2 : 1);
@@ -25,7 +29,7 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p)
     q.chunks = (p.K / per_byte(lut)) / (8 * q.ch);
     q.wn = 1, q.S = 1, q.cpw = q.chunks;
     // too few 64 x 32 tiles to give every SIMD a wavefront (or barely enough, and a long K to walk): split K
-    const int64_t t21 = tile_count(p, 2, 1);
+    const int64_t t21 = tile_count(p, wm, 1);
     const bool few_tiles = t21 < 512 || (t21 < 1024 && q.chunks >= 32);
     q.split = few_tiles && q.chunks > 1;
     // DG_ONEHOT_PLAN = split | 1 | 2 | 4 | 7 overrides the choice (tuning, and tests that must reach every plan)
@@ -61,7 +65,7 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p)
     double best = 0.0;
     for (int i = 0; i < 4; ++i) {
         const int wn = widths[i];
-        const double per_simd = (double)((tile_count(p, 2, wn) + 1023) / 1024);
+        const double per_simd = (double)((tile_count(p, wm, wn) + 1023) / 1024);
         const double cost = per_simd * 2 * wn * steps * mfma_cycles[i] + 3000.0 + 600.0 * 2 * wn;
         if (i == 0 || cost < best * 0.999) best = cost, q.wn = wn;
     }
@@ -74,7 +78,8 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p)
 bool dg_onehot_supports(const dg_lut *lut, const DgProblem &p)
 {
     if (lut->dtype == DG_LUT_F32) return false;
-    if (lut->min_entry < -128 || lut->max_entry > 127) return false;   // entries are MFMA int8 operands
+    // MFMA operands are int8: wider entries take two planes, T = 256 * hi + lo (2-bit codes only, hi within int8)
+    if (!fits_int8(lut) && (lut->bits != 2 || lut->max_entry > 127 * 256 + 127)) return false;
     if (p.Cin % (8 * per_byte(lut)) != 0) return false;                // a lane half reads whole words of one tap
     const Plan q = plan_for(lut, p);
     if ((uintptr_t)p.Wp % (4 * q.ch) != 0 || (uintptr_t)p.Xp % (4 * q.ch) != 0) return false;
@@ -83,31 +88,46 @@ bool dg_onehot_supports(const dg_lut *lut, const DgProblem &p)
 
 const char *dg_onehot_config_name(const dg_lut *lut, const DgProblem &p)
 {
-    static const char *const split_names[17] = {
-        "", "onehot_mfma_splitk_s1", "onehot_mfma_splitk_s2", "onehot_mfma_splitk_s3", "onehot_mfma_splitk_s4",
-        "onehot_mfma_splitk_s5", "onehot_mfma_splitk_s6", "onehot_mfma_splitk_s7", "onehot_mfma_splitk_s8",
-        "onehot_mfma_splitk_s9", "onehot_mfma_splitk_s10", "onehot_mfma_splitk_s11", "onehot_mfma_splitk_s12",
-        "onehot_mfma_splitk_s13", "onehot_mfma_splitk_s14", "onehot_mfma_splitk_s15", "onehot_mfma_splitk_s16"};
+    static const char *const split_names[2][17] = {
+        {"", "onehot_mfma_splitk_s1", "onehot_mfma_splitk_s2", "onehot_mfma_splitk_s3", "onehot_mfma_splitk_s4",
+         "onehot_mfma_splitk_s5", "onehot_mfma_splitk_s6", "onehot_mfma_splitk_s7", "onehot_mfma_splitk_s8",
+         "onehot_mfma_splitk_s9", "onehot_mfma_splitk_s10", "onehot_mfma_splitk_s11", "onehot_mfma_splitk_s12",
+         "onehot_mfma_splitk_s13", "onehot_mfma_splitk_s14", "onehot_mfma_splitk_s15", "onehot_mfma_splitk_s16"},
+        {"", "onehot_mfma_2p_splitk_s1", "onehot_mfma_2p_splitk_s2", "onehot_mfma_2p_splitk_s3", "onehot_mfma_2p_splitk_s4",
+         "onehot_mfma_2p_splitk_s5", "onehot_mfma_2p_splitk_s6", "onehot_mfma_2p_splitk_s7", "onehot_mfma_2p_splitk_s8",
+         "onehot_mfma_2p_splitk_s9", "onehot_mfma_2p_splitk_s10", "onehot_mfma_2p_splitk_s11", "onehot_mfma_2p_splitk_s12",
+         "onehot_mfma_2p_splitk_s13", "onehot_mfma_2p_splitk_s14", "onehot_mfma_2p_splitk_s15", "onehot_mfma_2p_splitk_s16"}};
+    static const char *const tile_names[2][4] = {
+        {"onehot_mfma_64x224", "onehot_mfma_64x128", "onehot_mfma_64x64", "onehot_mfma_64x32"},
+        {"onehot_mfma_2p_32x224", "onehot_mfma_2p_32x128", "onehot_mfma_2p_32x64", "onehot_mfma_2p_32x32"}};
     const Plan q = plan_for(lut, p);
-    if (q.split) return split_names[q.S];
-    return q.wn == 7 ? "onehot_mfma_64x224"
-                     : (q.wn == 4 ? "onehot_mfma_64x128" : (q.wn == 2 ? "onehot_mfma_64x64" : "onehot_mfma_64x32"));
+    if (q.split) return split_names[q.two][q.S];
+    return tile_names[q.two][q.wn == 7 ? 0 : (q.wn == 4 ? 1 : (q.wn == 2 ? 2 : 3))];
 }
 
 dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
 {
-    // column v of the table, 4 weight codes per word: the permute pools
+    // column v of the table, 4 weight codes per word: the permute pools.  Entries beyond int8 go in two planes,
+    // T = 256 * hi + lo with lo in [-128, 127] (so hi is within [-128, 128) for every int16 T).
+    const Plan q = plan_for(lut, p);
     dgoh::Pools pools;
     const int L = 1 << lut->bits, qw = L / 4;
     for (int i = 0; i < 64; ++i) pools.w[i] = 0;
     for (int v = 0; v < L; ++v)
-        for (int w = 0; w < L; ++w)
-            pools.w[v * qw + w / 4] |= (uint32_t)(uint8_t)(int8_t)lut->entry[(w << lut->bits) | v] << (8 * (w % 4));
-    const Plan q = plan_for(lut, p);
-    const int64_t blocks11 = tile_count(p, 1, 1), wave_tiles = tile_count(p, 2, q.wn);
+        for (int w = 0; w < L; ++w) {
+            const int T = lut->entry[(w << lut->bits) | v];
+            const int lo = q.two ? ((T + 128) & 255) - 128 : T, hi = (T - lo) / 256;
+            pools.w[v * qw + w / 4] |= (uint32_t)(uint8_t)(int8_t)lo << (8 * (w % 4));
+            if (q.two) pools.w[32 + v * qw + w / 4] |= (uint32_t)(uint8_t)(int8_t)hi << (8 * (w % 4));
+        }
+    const int64_t blocks11 = tile_count(p, 1, 1), wave_tiles = tile_count(p, q.two ? 1 : 2, q.wn);
     if ((q.split ? blocks11 : (wave_tiles + 3) / 4) > INT32_MAX)
         return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel: too many tiles for one grid");
     const bool tr = p.stride_cm == 1 && p.stride_cn != 1;   // the output axis with stride 1 goes on the MFMA columns
+    if (q.two) {
+        (tr ? dgoh::launch_bits2_two_tr1 : dgoh::launch_bits2_two_tr0)(p, pools, q, blocks11, wave_tiles, stream);
+        return dg_check_launch(q.split ? "onehot_splitk_kernel" : "onehot_mfma_kernel");
+    }
     switch (lut->bits) {
     case 2: (tr ? dgoh::launch_bits2_tr1 : dgoh::launch_bits2_tr0)(p, pools, q, blocks11, wave_tiles, stream); break;
     case 3: (tr ? dgoh::launch_bits3_tr1 : dgoh::launch_bits3_tr0)(p, pools, q, blocks11, wave_tiles, stream); break;

@@ -126,30 +126,35 @@ ONEHOT_PLANS = {"split": "onehot_mfma_splitk_s", "1": "onehot_mfma_64x32", "2": 
                 "4": "onehot_mfma_64x128", "7": "onehot_mfma_64x224"}
 
 
+@pytest.mark.parametrize("table", ["signed_unsigned", "extreme_i16"])
 @pytest.mark.parametrize("plan", sorted(ONEHOT_PLANS))
-def test_onehot_every_plan(plan, monkeypatch):
+def test_onehot_every_plan(plan, table, monkeypatch):
     """Every wave tile of the one-hot matrix-core kernel and its split-K form, forced on shapes with ragged edges in
     M and N (the library picks among them by a cost model that small test shapes would never move off one plan):
-    GEMM with row-major and column-major output, convolution with padding and stride, int32 and scaled fp32 output."""
+    GEMM with row-major and column-major output, convolution with padding and stride, int32 and scaled fp32 output.
+    Once with an int8 table (one plane) and once with entries up to 16384 (two int8 planes)."""
     monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
+    glw, gla, gentry = LEVELS[table]
+    prefix = ONEHOT_PLANS[plan] if table == "signed_unsigned" else ONEHOT_PLANS[plan].replace("onehot_mfma_", "onehot_mfma_2p_").replace("_64x", "_32x")
     for (M, N, K) in [(70, 1000, 96), (130, 777, 64), (64, 300, 256), (33, 250, 1024)]:
         inp = wl.small_gemm(M, N, K, seed=M + N + K)
-        case = GpuCase(inp)
-        assert case.kernel_name("onehot_mfma").startswith(ONEHOT_PLANS[plan])
-        want = oracle.gemm(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a)
+        case = GpuCase(inp, levels=(glw, gla), entry=gentry)
+        assert case.kernel_name("onehot_mfma").startswith(prefix)
+        want = oracle.gemm(inp.Wc, inp.Ac, glw, gla)
         _assert_same(case.run("onehot_mfma").cpu().numpy(), want, f"gemm {(M, N, K)} plan {plan}")
         out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
         dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant="onehot_mfma", strides=(1, M))
         torch.cuda.synchronize()
         _assert_same(out.cpu().numpy(), want.T.copy(), f"gemm {(M, N, K)} column-major plan {plan}")
-    lw, la, entry = LEVELS["nonuniform_i8"]                  # no zero activation level: padding must still add 0
+    # no zero activation level: padding must still add 0
+    lw, la, entry = LEVELS["nonuniform_i8"] if table == "signed_unsigned" else ((127, -128, 5, 3), (-128, 127, 1, 2), dg.DG_LUT_I16)
     for (B, H, W, Cin, Cout, KH, KW, stride, pad) in [(2, 24, 24, 32, 70, 3, 3, (1, 1), (1, 1)),
                                                       (1, 30, 30, 128, 40, 3, 3, (2, 2), (1, 1)),
                                                       (3, 16, 16, 64, 33, 1, 1, (1, 1), (0, 0)),
                                                       (1, 20, 20, 64, 96, 5, 5, (1, 1), (2, 2))]:
         c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
         case = GpuCase(c, levels=(lw, la), entry=entry)
-        assert case.kernel_name("onehot_mfma").startswith(ONEHOT_PLANS[plan])
+        assert case.kernel_name("onehot_mfma").startswith(prefix)
         acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
         _assert_same(case.run("onehot_mfma").cpu().numpy(), acc, f"conv {(B, H, W, Cin, Cout)} plan {plan}")
         got = case.run("onehot_mfma", scale=True).cpu().numpy()
