@@ -453,10 +453,14 @@ void launch_ch(const Args &a, int ch, dim3 grid, hipStream_t stream)
             return;
         }
     }
-    if (ch == 2)
-        hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 2, TR, TWO>), grid, dim3(256), 0, stream, a);
-    else
-        hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 1, TR, TWO>), grid, dim3(256), 0, stream, a);
+    // (nor 2-word chunks on their widest tile: 16 steps of 14 MFMAs take the compiler minutes; the host plans 1 word)
+    if constexpr (!(BITS == 4 && WN == 7)) {
+        if (ch == 2) {
+            hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 2, TR, TWO>), grid, dim3(256), 0, stream, a);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 1, TR, TWO>), grid, dim3(256), 0, stream, a);
 }
 
 // `blocks11`: 32 x 32 blocks of the output (the split-K grid); `wave_tiles`: tiles of the planned width, 64 rows high

@@ -70,6 +70,7 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p)
         if (i == 0 || cost < best * 0.999) best = cost, q.wn = wn;
     }
     if (force_wn) q.wn = force_wn;
+    if (lut->bits == 4 && q.wn == 7) q.ch = 1;             // (the 2-word kernel of this tile is not built: see launch_ch)
     return q;
 }
 
