@@ -338,17 +338,18 @@ onehot_mfma_kernel(Args a)
 // Small layers: too few 64 x 32 tiles to occupy the chip, and a wavefront that walks all of K alone pays the memory
 // latency once per chunk.  Here a workgroup owns ONE 32 x 32 output block and its S wavefronts split K between them
 // (whole chunks each), so a layer with T blocks puts T*S wavefronts in flight and each of them waits for memory once
-// or twice.  Partial blocks meet in LDS: every wavefront writes its 16 accumulator registers, one barrier, then the
-// threads add the S partials of each output element (integer, so exact in any order) and store it -- 128 contiguous
+// or twice.  Partial blocks meet in LDS: every wavefront adds its 16 accumulator registers to the block's sums with
+// LDS integer atomics (exact in any order), one barrier, then the threads scale and store the sums -- 128 contiguous
 // bytes per half wavefront, as in the large-layer kernel.
 template <int BITS, int CH, bool TR, bool TWO>
 __global__ void __launch_bounds__(1024)
 onehot_splitk_kernel(SplitArgs a)
 {
     typedef Fmt<BITS> F;
-    extern __shared__ int32_t s_part[];                     // [S][16][64]
+    __shared__ int32_t s_sum[16 * 64];                      // the block's sums, [accumulator register][lane]
     const DgProblem &p = a.p;
-    const int lane = threadIdx.x & 63, ws = threadIdx.x >> 6, S = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, ws = threadIdx.x >> 6;
+    for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) s_sum[idx] = 0;
     const int r = lane & 31, h = lane >> 5;
     const int m0 = ((int)blockIdx.x % a.tiles_m) * 32;
     const int n0 = ((int)blockIdx.x / a.tiles_m) * 32;
@@ -390,6 +391,9 @@ onehot_splitk_kernel(SplitArgs a)
             }
         };
         fetch_x();
+        // every wavefront's zeroes are in LDS before any wavefront adds to them; the global loads issued above stay in
+        // flight across this barrier (it waits for LDS only), so the wavefronts' staggered starts cost nothing here
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         for (int c = c0; c < c1; ++c) {
             const Words<CH> ca = wa, cb = wb;
             const bool valid = vb;
@@ -415,14 +419,15 @@ onehot_splitk_kernel(SplitArgs a)
         for (int e = 0; e < 16; ++e) acc[e] = (int)((uint32_t)acc[e] + ((uint32_t)acc_hi[e] << 8));       // 256 * hi + lo
     }
 
+    // the wavefronts' partial blocks meet by LDS integer atomics (exact in any order)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) s_part[(ws * 16 + e) * 64 + lane] = acc[e];
+    for (int e = 0; e < 16; ++e)
+        __hip_atomic_fetch_add(&s_sum[e * 64 + lane], acc[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     __syncthreads();
 
     for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
         const int e = idx >> 6, l = idx & 63;
-        int32_t sum = 0;
-        for (int w = 0; w < S; ++w) sum += s_part[(w * 16 + e) * 64 + l];
+        const int32_t sum = s_sum[idx];
         const int row = 8 * (e / 4) + 4 * (l >> 5) + (e % 4), c = l & 31;       // MFMA block coordinates
         const int m = m0 + (TR ? c : row), n = n0 + (TR ? row : c);
         if (m >= p.M || n >= p.N) continue;
@@ -479,7 +484,7 @@ void launch_tr(const DgProblem &p, const Pools &pools, const Plan &q, int64_t bl
         b.div_ow = make_div((uint32_t)p.OW), b.div_oh = make_div((uint32_t)p.OH);
         b.div_cin = make_div((uint32_t)p.Cin), b.div_kw = make_div((uint32_t)p.KW);
         const dim3 grid((unsigned)blocks11), block(64 * q.S);
-        const size_t lds = (size_t)q.S * 16 * 64 * sizeof(int32_t);
+        const size_t lds = 0;
         if constexpr (BITS != 4) {
             if (q.ch == 4) {
                 hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 4, TR, TWO>), grid, block, lds, stream, b);
