@@ -157,3 +157,28 @@ def test_tables_given_as_such():
     lw, la = np.array([0.1, -0.37, 1.5, 3.0e-3], np.float32), np.array([0.0, 0.7, 1.9, 2.25], np.float32)
     got = np.array(dg.dg_build_lut_f32(lw, la).entries(), dtype=np.float32)
     assert np.array_equal(got, (lw[:, None] * la[None, :]).astype(np.float32).reshape(-1))   # one float32 multiply each
+
+
+def test_empty_launch_rejects_bad_grids_before_launching():
+    L = dg.lib()
+    assert L.dg_launch_empty(0, 64, None) == 2
+    assert L.dg_launch_empty(10, 0, None) == 2
+    assert L.dg_launch_empty(10, 100, None) == 2          # not a multiple of 64
+    assert L.dg_launch_empty(10, 2048, None) == 2         # more than 1024 threads
+    assert L.dg_launch_empty(1 << 40, 64, None) == 2
+
+
+def test_kernel_names_need_no_gpu():
+    # the plan functions are host code: small layers split K, large ones get a wave tile, wide entries two planes
+    lut = dg.dg_build_lut((-2, -1, 0, 1), (0, 1, 2, 3))
+    assert dg.dg_gemm_kernel_name(lut, 64, 196, 576).startswith("onehot_mfma_splitk_s")
+    assert dg.dg_gemm_kernel_name(lut, 8192, 8192, 8192) == "onehot_mfma_64x128"
+    assert dg.dg_gemm_kernel_name(lut, 8192, 1, 8192) == "smalln"
+    assert dg.dg_gemm_kernel_name(lut, 64, 196, 48).startswith("perm")        # Cin % 32 != 0, % 16 == 0
+    assert dg.dg_gemm_kernel_name(lut, 5, 7, 12) == "lds"                      # Cin % 16 != 0
+    assert dg.dg_gemm_kernel_name(lut, 64, 196, 576, "mfma_i8") == "mfma_i8"
+    wide = dg.dg_build_lut((127, -128, 5, 0), (-128, 127, 1, 0), dg.DG_LUT_I16)
+    assert dg.dg_gemm_kernel_name(wide, 8192, 8192, 8192) == "onehot_mfma_2p_32x128"
+    t4 = dg.dg_build_lut_bits(4, list(range(-8, 8)), list(range(16)), dg.DG_LUT_I8)
+    assert dg.dg_gemm_kernel_name(t4, 256, 50176, 2304) == "onehot_mfma_64x224"
+    assert dg.dg_gemm_kernel_name(t4, 256, 50176, 2304, "perm") == "unsupported"
