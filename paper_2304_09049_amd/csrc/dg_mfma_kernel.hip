@@ -101,6 +101,8 @@ mfma_i8_kernel(MfmaArgs a)
         for (int bn = 0; bn < WN; ++bn)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[bm][bn][e] = 0;
+    float sc_cols[WM];                                      // the epilogue's scales, fetched now
+    dg_mfma_column_scales<WM, TR>(p, m0, lane, sc_cols);
 
     // the chunk's filter tap (same for every lane: a chunk never straddles taps since Cin % CHUNK == 0)
     int kh = 0, kw = 0, ci = 0;
@@ -157,7 +159,7 @@ mfma_i8_kernel(MfmaArgs a)
         }
     }
 
-    dg_mfma_store_tile<WM, WN, TR>(p, acc, m0, n0, lane);
+    dg_mfma_store_tile<WM, WN, TR>(p, acc, m0, n0, lane, sc_cols);
 }
 
 template <int WM, int WN, bool TR>

@@ -20,10 +20,22 @@ __device__ __forceinline__ dg_v16i dg_mfma_step(dg_v4i w, dg_v4i x, dg_v16i acc)
               : __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, acc, 0, 0, 0);
 }
 
+// With TR a lane stores one channel m per row block whatever the element, so its scales can be fetched long before the
+// stores: dg_mfma_column_scales at the start of the kernel, handed to dg_mfma_store_tile at the end.
+template <int WM, bool TR>
+__device__ __forceinline__ void dg_mfma_column_scales(const DgProblem &p, int m0, int lane, float (&sc)[WM])
+{
+#pragma unroll
+    for (int bm = 0; bm < WM; ++bm) {
+        const int m = min(m0 + bm * 32 + (lane & 31), p.M - 1);
+        sc[bm] = (TR && p.scale) ? p.scale[m] : 0.0f;
+    }
+}
+
 // Store the (WM*32) x (WN*32) tile at (m0, n0): int32 as it is, or float(acc) * scale[m] (one conversion, one multiply).
 template <int WM, int WN, bool TR>
 __device__ __forceinline__ void dg_mfma_store_tile(const DgProblem &p, const dg_v16i (&acc)[WM][WN], int m0, int n0,
-                                                   int lane)
+                                                   int lane, const float (&sc_cols)[WM])
 {
     const int r = lane & 31, h = lane >> 5;
 #pragma unroll
@@ -32,7 +44,7 @@ __device__ __forceinline__ void dg_mfma_store_tile(const DgProblem &p, const dg_
         for (int bn = 0; bn < WN; ++bn) {
             const int col = TR ? m0 + bm * 32 + r : n0 + bn * 32 + r;
             if (col >= (TR ? p.M : p.N)) continue;
-            const float sc = (TR && p.scale) ? p.scale[col] : 0.0f;
+            const float sc = sc_cols[bm];
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int row = (TR ? n0 + bn * 32 : m0 + bm * 32) + 8 * (e / 4) + 4 * h + (e % 4);

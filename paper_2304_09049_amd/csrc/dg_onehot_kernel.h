@@ -239,6 +239,8 @@ onehot_mfma_kernel(Args a)
         for (int bn = 0; bn < WN; ++bn)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[bm][bn][e] = 0;
+    float sc_cols[RB];                                      // the epilogue's scales, fetched now
+    dg_mfma_column_scales<RB, TR>(p, m0, lane, sc_cols);
 
     int kh = 0, kw = 0, ci = 0;
     Words<CH> wa[RB], wb[WN];
@@ -329,9 +331,9 @@ onehot_mfma_kernel(Args a)
 #pragma unroll
             for (int e = 0; e < 16; ++e)
                 both[0][bn][e] = (int)((uint32_t)acc[0][bn][e] + ((uint32_t)acc[1][bn][e] << 8));   // 256 * hi + lo
-        dg_mfma_store_tile<1, WN, TR>(p, both, m0, n0, lane);
+        dg_mfma_store_tile<1, WN, TR>(p, both, m0, n0, lane, (const float (&)[1])sc_cols);
     } else {
-        dg_mfma_store_tile<WM, WN, TR>(p, acc, m0, n0, lane);
+        dg_mfma_store_tile<WM, WN, TR>(p, acc, m0, n0, lane, (const float (&)[WM])sc_cols);
     }
 }
 
