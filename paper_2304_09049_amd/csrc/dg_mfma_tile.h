@@ -32,29 +32,36 @@ __device__ __forceinline__ void dg_mfma_column_scales(const DgProblem &p, int m0
     }
 }
 
-// Store the (WM*32) x (WN*32) tile at (m0, n0): int32 as it is, or float(acc) * scale[m] (one conversion, one multiply).
+// Store one 32x32 block whose first row / column sit at (mb, nb): int32 as it is, or float(acc) * scale[m] (one
+// conversion, one multiply); `sc` is the lane's prefetched scale (TR only).
+template <bool TR>
+__device__ __forceinline__ void dg_mfma_store_block(const DgProblem &p, const dg_v16i &acc, int mb, int nb, int lane,
+                                                    float sc)
+{
+    const int r = lane & 31, h = lane >> 5;
+    const int col = (TR ? mb : nb) + r;
+    if (col >= (TR ? p.M : p.N)) return;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int row = (TR ? nb : mb) + 8 * (e / 4) + 4 * h + (e % 4);
+        if (row >= (TR ? p.N : p.M)) continue;
+        const int m = TR ? col : row, n = TR ? row : col;
+        const int64_t o = (int64_t)m * p.stride_cm + (int64_t)n * p.stride_cn;
+        if (p.scale)
+            p.Cf[o] = (float)acc[e] * (TR ? sc : p.scale[m]);
+        else
+            p.C[o] = acc[e];
+    }
+}
+
+// Store the (WM*32) x (WN*32) tile at (m0, n0).
 template <int WM, int WN, bool TR>
 __device__ __forceinline__ void dg_mfma_store_tile(const DgProblem &p, const dg_v16i (&acc)[WM][WN], int m0, int n0,
                                                    int lane, const float (&sc_cols)[WM])
 {
-    const int r = lane & 31, h = lane >> 5;
 #pragma unroll
     for (int bm = 0; bm < WM; ++bm)
 #pragma unroll
-        for (int bn = 0; bn < WN; ++bn) {
-            const int col = TR ? m0 + bm * 32 + r : n0 + bn * 32 + r;
-            if (col >= (TR ? p.M : p.N)) continue;
-            const float sc = sc_cols[bm];
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = (TR ? n0 + bn * 32 : m0 + bm * 32) + 8 * (e / 4) + 4 * h + (e % 4);
-                if (row >= (TR ? p.N : p.M)) continue;
-                const int m = TR ? col : row, n = TR ? row : col;
-                const int64_t o = (int64_t)m * p.stride_cm + (int64_t)n * p.stride_cn;
-                if (p.scale)
-                    p.Cf[o] = (float)acc[bm][bn][e] * (TR ? sc : p.scale[m]);
-                else
-                    p.C[o] = acc[bm][bn][e];
-            }
-        }
+        for (int bn = 0; bn < WN; ++bn)
+            dg_mfma_store_block<TR>(p, acc[bm][bn], m0 + bm * 32, n0 + bn * 32, lane, sc_cols[bm]);
 }

@@ -63,7 +63,7 @@ inline FastDiv make_div(uint32_t d)
 struct Args {
     DgProblem p;
     Pools pools;
-    FastDiv div_ow, div_oh;
+    FastDiv div_ow, div_oh, div_cin, div_kw;
     int32_t tiles_m;
     int64_t wave_tiles;
 };
@@ -203,23 +203,37 @@ __device__ __forceinline__ Column make_column(const DgProblem &p, const FastDiv 
 }
 
 // Large layers: each wavefront owns a (WM*32) x (WN*32) tile; operands come straight from global memory (L2), one
-// chunk ahead; no LDS, no barrier.
-template <int BITS, int WM, int WN, int CH, bool TR, bool TWO>
+// chunk ahead.  SKW = 1: a wavefront walks all of K, there is no LDS and no barrier.  SKW = 2 or 4 (layers whose tiles
+// alone would leave SIMDs idle or with a single wavefront): SKW wavefronts of the workgroup share a tile and split K
+// between them in contiguous runs of chunks; their accumulators meet in LDS by integer atomics (exact in any order)
+// and each of them stores a share of the tile's blocks.
+template <int BITS, int WM, int WN, int CH, bool TR, bool TWO, int SKW>
 __global__ void __launch_bounds__(256, (WM * WN > 8 ? 1 : 2))
 onehot_mfma_kernel(Args a)
 {
     typedef Fmt<BITS> F;
     static_assert(!TWO || (WM == 2 && BITS == 2), "two planes stand in for the two weight row blocks of 2-bit tiles");
     constexpr int RB = TWO ? 1 : WM;                       // weight row blocks of 32 rows
+    constexpr int TPW = 4 / SKW;                           // tiles per workgroup
+    constexpr int NB = RB * WN;                            // 32x32 output blocks per tile
+    extern __shared__ int32_t s_acc[];                      // SKW > 1: [TPW][NB][16][64] sums
     const DgProblem &p = a.p;
-    const int lane = threadIdx.x & 63;
-    const int64_t wave_tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (wave_tile >= a.wave_tiles) return;                 // whole waves leave; there is no barrier below
+    const int lane = threadIdx.x & 63, w4 = threadIdx.x >> 6;
+    const int ks = w4 % SKW, tw = w4 / SKW;                 // this wavefront's share of K, and its tile within the workgroup
+    const int64_t my_tile = (int64_t)blockIdx.x * TPW + tw;
+    const bool active = my_tile < a.wave_tiles;
+    if (SKW == 1 && !active) return;                       // whole waves leave; there is no barrier on this path
+    const int64_t wave_tile = active ? my_tile : 0;        // (an idle wavefront of a shared workgroup adds zeros)
+    if (SKW > 1)
+        for (int i = threadIdx.x; i < TPW * NB * 1024; i += 256) s_acc[i] = 0;
     const int r = lane & 31, h = lane >> 5;
     const int m0 = (int)(wave_tile % a.tiles_m) * (RB * 32);
     const int n0 = (int)(wave_tile / a.tiles_m) * (WN * 32);
     const int cq = p.Cin / F::PER_BYTE;                     // packed bytes per pixel
     constexpr int CHUNK = 8 * CH * F::PER_BYTE;             // codes of K per chunk: 4*CH packed bytes per lane half
+    const int chunks = p.K / CHUNK;
+    const int cps = (chunks + SKW - 1) / SKW;               // chunks per share of K
+    const int c0 = min(ks * cps, chunks), c1 = active ? min(c0 + cps, chunks) : c0;
 
     const uint8_t *w_ptr[RB];
 #pragma unroll
@@ -242,12 +256,20 @@ onehot_mfma_kernel(Args a)
     float sc_cols[RB];                                      // the epilogue's scales, fetched now
     dg_mfma_column_scales<RB, TR>(p, m0, lane, sc_cols);
 
+    // filter tap of this wavefront's first chunk
     int kh = 0, kw = 0, ci = 0;
+    if (SKW > 1) {
+        const int pos = c0 * CHUNK, tap = (int)fdiv((uint32_t)pos, a.div_cin);
+        kh = (int)fdiv((uint32_t)tap, a.div_kw);
+        kw = tap - kh * p.KW;
+        ci = pos - tap * p.Cin;
+    }
     Words<CH> wa[RB], wb[WN];
     bool vb[WN];
-    auto fetch = [&](int chunk) {
+    auto fetch = [&](int chunk) {                            // `chunk` is clamped: a fetch past the share is unused
+        const int cw = min(chunk, chunks - 1);
 #pragma unroll
-        for (int bm = 0; bm < RB; ++bm) wa[bm] = load_words<CH>(w_ptr[bm] + (int64_t)chunk * (8 * CH));
+        for (int bm = 0; bm < RB; ++bm) wa[bm] = load_words<CH>(w_ptr[bm] + (int64_t)cw * (8 * CH));
         const int64_t tap_off = ((int64_t)kh * p.W + kw) * cq + ci / F::PER_BYTE;
 #pragma unroll
         for (int bn = 0; bn < WN; ++bn) {
@@ -267,9 +289,11 @@ onehot_mfma_kernel(Args a)
         }
     };
 
-    const int chunks = p.K / CHUNK;
-    fetch(0);
-    for (int c = 0; c < chunks; ++c) {
+    fetch(c0);
+    // every wavefront's zeroes are in LDS before any wavefront adds to them; the loads above stay in flight across
+    // this barrier (it waits for LDS only)
+    if (SKW > 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    for (int c = c0; c < c1; ++c) {
         Words<CH> ca[RB], cb[WN];
         bool valid[WN];
 #pragma unroll
@@ -279,7 +303,7 @@ onehot_mfma_kernel(Args a)
             cb[bn] = wb[bn];
             valid[bn] = vb[bn];
         }
-        fetch(c + 1 < chunks ? c + 1 : c);                  // unconditional (the last one re-reads in bounds and is unused)
+        fetch(c + 1 < c1 ? c + 1 : c);                      // unconditional (the last one re-reads in bounds and is unused)
         // Step t = one MFMA per block of the tile: word t / STEPS, selector j of it, value group g.  The operands of
         // step t+1 are built between the MFMAs of step t so that the matrix unit and the VALU of a single wavefront
         // overlap; the scheduling groups pin that interleaving.
@@ -324,16 +348,35 @@ onehot_mfma_kernel(Args a)
         }
     }
 
-    if (TWO) {
-        v16i both[1][WN];
+    // the tile's blocks as they go to memory: two planes merge into one block row, 256 * hi + lo
+    v16i out[RB][WN];
+#pragma unroll
+    for (int bm = 0; bm < RB; ++bm)
 #pragma unroll
         for (int bn = 0; bn < WN; ++bn)
 #pragma unroll
             for (int e = 0; e < 16; ++e)
-                both[0][bn][e] = (int)((uint32_t)acc[0][bn][e] + ((uint32_t)acc[1][bn][e] << 8));   // 256 * hi + lo
-        dg_mfma_store_tile<1, WN, TR>(p, both, m0, n0, lane, (const float (&)[1])sc_cols);
-    } else {
-        dg_mfma_store_tile<WM, WN, TR>(p, acc, m0, n0, lane, (const float (&)[WM])sc_cols);
+                out[bm][bn][e] = TWO ? (int)((uint32_t)acc[0][bn][e] + ((uint32_t)acc[WM - 1][bn][e] << 8)) : acc[bm][bn][e];
+    if (SKW == 1) {
+        dg_mfma_store_tile<RB, WN, TR>(p, out, m0, n0, lane, sc_cols);
+        return;
+    }
+    int32_t *sums = s_acc + tw * (NB * 1024);
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            __hip_atomic_fetch_add(&sums[(i * 16 + e) * 64 + lane], out[i / WN][i % WN][e], __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+    __syncthreads();
+    if (!active) return;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        if (i % SKW != ks) continue;                        // each wavefront of the tile stores a share of its blocks
+        v16i blk;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) blk[e] = sums[(i * 16 + e) * 64 + lane];
+        dg_mfma_store_block<TR>(p, blk, m0 + (i / WN) * 32, n0 + (i % WN) * 32, lane, sc_cols[i / WN]);
     }
 }
 
@@ -447,83 +490,102 @@ struct Plan {
     bool two;        // entries beyond int8: two int8 planes
     bool split;
     int wn;
+    int skw;         // large-layer kernel: wavefronts sharing a tile (1, 2 or 4)
     int S, cpw, chunks;
 };
 
-template <int BITS, int WM, int WN, bool TR, bool TWO>
+// dynamic LDS of the large-layer kernel: the shared tiles' sums
+template <int WM, int WN, bool TWO, int SKW>
+constexpr size_t main_lds_bytes()
+{
+    return SKW == 1 ? 0 : (size_t)(4 / SKW) * (TWO ? 1 : WM) * WN * 1024 * sizeof(int32_t);
+}
+
+template <int BITS, int WM, int WN, bool TR, bool TWO, int SKW>
 void launch_ch(const Args &a, int ch, dim3 grid, hipStream_t stream)
 {
+    constexpr size_t lds = main_lds_bytes<WM, WN, TWO, SKW>();
+    static_assert(lds <= 64 * 1024, "the host plans only shapes whose sums fit 64 KB of LDS");
     // (4-bit codes: the host never plans 4-word chunks -- 32 MFMA steps -- so they are not instantiated)
     if constexpr (BITS != 4) {
         if (ch == 4) {
-            hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 4, TR, TWO>), grid, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 4, TR, TWO, SKW>), grid, dim3(256), lds, stream, a);
             return;
         }
     }
     // (nor 2-word chunks on their widest tile: 16 steps of 14 MFMAs take the compiler minutes; the host plans 1 word)
     if constexpr (!(BITS == 4 && WN == 7)) {
         if (ch == 2) {
-            hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 2, TR, TWO>), grid, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 2, TR, TWO, SKW>), grid, dim3(256), lds, stream, a);
             return;
         }
     }
-    hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 1, TR, TWO>), grid, dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 1, TR, TWO, SKW>), grid, dim3(256), lds, stream, a);
 }
 
-// `blocks11`: 32 x 32 blocks of the output (the split-K grid); `wave_tiles`: tiles of the planned width, 64 rows high
-// (32 with two planes), 4 per workgroup.
-template <int BITS, bool TR, bool TWO>
-void launch_tr(const DgProblem &p, const Pools &pools, const Plan &q, int64_t blocks11, int64_t wave_tiles,
-               hipStream_t stream)
+// The large-layer kernel on `wave_tiles` tiles of the planned width, 64 rows high (32 with two planes); a workgroup
+// holds 4 / SKW of them.  The widest tile shares only among 4 wavefronts (two tiles of sums would not fit 64 KB).
+template <int BITS, bool TR, bool TWO, int SKW>
+void launch_main(const DgProblem &p, const Pools &pools, const Plan &q, int64_t wave_tiles, hipStream_t stream)
 {
-    if (q.split) {
-        SplitArgs b;
-        b.p = p;
-        b.pools = pools;
-        b.chunks = q.chunks;
-        b.cpw = q.cpw;
-        b.tiles_m = (p.M + 31) / 32;
-        b.div_ow = make_div((uint32_t)p.OW), b.div_oh = make_div((uint32_t)p.OH);
-        b.div_cin = make_div((uint32_t)p.Cin), b.div_kw = make_div((uint32_t)p.KW);
-        const dim3 grid((unsigned)blocks11), block(64 * q.S);
-        const size_t lds = 0;
-        if constexpr (BITS != 4) {
-            if (q.ch == 4) {
-                hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 4, TR, TWO>), grid, block, lds, stream, b);
-                return;
-            }
-        }
-        if (q.ch == 2)
-            hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 2, TR, TWO>), grid, block, lds, stream, b);
-        else
-            hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 1, TR, TWO>), grid, block, lds, stream, b);
-        return;
-    }
     Args a;
     a.p = p;
     a.pools = pools;
     a.tiles_m = TWO ? (p.M + 31) / 32 : (p.M + 63) / 64;
     a.wave_tiles = wave_tiles;
     a.div_ow = make_div((uint32_t)p.OW), a.div_oh = make_div((uint32_t)p.OH);
-    const dim3 grid((unsigned)((wave_tiles + 3) / 4));
-    if (q.wn == 7)
-        launch_ch<BITS, 2, 7, TR, TWO>(a, q.ch, grid, stream);
-    else if (q.wn == 4)
-        launch_ch<BITS, 2, 4, TR, TWO>(a, q.ch, grid, stream);
-    else if (q.wn == 2)
-        launch_ch<BITS, 2, 2, TR, TWO>(a, q.ch, grid, stream);
-    else
-        launch_ch<BITS, 2, 1, TR, TWO>(a, q.ch, grid, stream);
+    a.div_cin = make_div((uint32_t)p.Cin), a.div_kw = make_div((uint32_t)p.KW);
+    constexpr int TPW = 4 / SKW;
+    const dim3 grid((unsigned)((wave_tiles + TPW - 1) / TPW));
+    if (q.wn == 7) {
+        if constexpr (SKW != 2) launch_ch<BITS, 2, 7, TR, TWO, SKW>(a, q.ch, grid, stream);
+    } else if (q.wn == 4) {
+        launch_ch<BITS, 2, 4, TR, TWO, SKW>(a, q.ch, grid, stream);
+    } else if (q.wn == 2) {
+        launch_ch<BITS, 2, 2, TR, TWO, SKW>(a, q.ch, grid, stream);
+    } else {
+        launch_ch<BITS, 2, 1, TR, TWO, SKW>(a, q.ch, grid, stream);
+    }
 }
 
-// One translation unit per code width and output layout instantiates launch_tr (the kernels are many: 4 tiles x
+// The split-K kernel on `blocks11` 32 x 32 blocks of the output.
+template <int BITS, bool TR, bool TWO>
+void launch_split(const DgProblem &p, const Pools &pools, const Plan &q, int64_t blocks11, hipStream_t stream)
+{
+    SplitArgs b;
+    b.p = p;
+    b.pools = pools;
+    b.chunks = q.chunks;
+    b.cpw = q.cpw;
+    b.tiles_m = (p.M + 31) / 32;
+    b.div_ow = make_div((uint32_t)p.OW), b.div_oh = make_div((uint32_t)p.OH);
+    b.div_cin = make_div((uint32_t)p.Cin), b.div_kw = make_div((uint32_t)p.KW);
+    const dim3 grid((unsigned)blocks11), block(64 * q.S);
+    if constexpr (BITS != 4) {
+        if (q.ch == 4) {
+            hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 4, TR, TWO>), grid, block, 0, stream, b);
+            return;
+        }
+    }
+    if (q.ch == 2)
+        hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 2, TR, TWO>), grid, block, 0, stream, b);
+    else
+        hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 1, TR, TWO>), grid, block, 0, stream, b);
+}
+
+// One translation unit per (code width, output layout, K share) instantiates these (the kernels are many: 4 tiles x
 // 3 chunk sizes each).  TR: the output axis with stride 1 goes on the MFMA columns (see dg_mfma_tile.h).
-#define DGOH_DECLARE(B, T) \
-    void launch_bits##B##_tr##T(const DgProblem &, const Pools &, const Plan &, int64_t, int64_t, hipStream_t);
-DGOH_DECLARE(2, 0) DGOH_DECLARE(2, 1) DGOH_DECLARE(3, 0) DGOH_DECLARE(3, 1) DGOH_DECLARE(4, 0) DGOH_DECLARE(4, 1)
-#undef DGOH_DECLARE
-// the two-plane kernels (2-bit codes, entries beyond int8)
-void launch_bits2_two_tr0(const DgProblem &, const Pools &, const Plan &, int64_t, int64_t, hipStream_t);
-void launch_bits2_two_tr1(const DgProblem &, const Pools &, const Plan &, int64_t, int64_t, hipStream_t);
+// Unit "bBtTkK" defines unit_main_bB_tT_kK, and for K = 1 also unit_split_bB_tT; B = 22 stands for 2-bit codes in two planes.
+typedef void (*MainFn)(const DgProblem &, const Pools &, const Plan &, int64_t, hipStream_t);
+#define DGOH_UNIT(B, T, K) \
+    void unit_main_b##B##_t##T##_k##K(const DgProblem &, const Pools &, const Plan &, int64_t, hipStream_t);
+#define DGOH_UNIT_SPLIT(B, T) \
+    void unit_split_b##B##_t##T(const DgProblem &, const Pools &, const Plan &, int64_t, hipStream_t);
+DGOH_UNIT(2, 0, 1) DGOH_UNIT(2, 0, 2) DGOH_UNIT(2, 0, 4) DGOH_UNIT(2, 1, 1) DGOH_UNIT(2, 1, 2) DGOH_UNIT(2, 1, 4)
+DGOH_UNIT(3, 0, 1) DGOH_UNIT(3, 1, 1) DGOH_UNIT(4, 0, 1) DGOH_UNIT(4, 1, 1) DGOH_UNIT(22, 0, 1) DGOH_UNIT(22, 1, 1)
+DGOH_UNIT_SPLIT(2, 0) DGOH_UNIT_SPLIT(2, 1) DGOH_UNIT_SPLIT(3, 0) DGOH_UNIT_SPLIT(3, 1) DGOH_UNIT_SPLIT(4, 0)
+DGOH_UNIT_SPLIT(4, 1) DGOH_UNIT_SPLIT(22, 0) DGOH_UNIT_SPLIT(22, 1)
+#undef DGOH_UNIT
+#undef DGOH_UNIT_SPLIT
 
 }   // namespace dgoh

@@ -1,6 +1,7 @@
 // Host side of the one-hot matrix-core kernels (dg_onehot_kernel.h): which problems they take, which of their
 // shapes runs a given problem, and the launch.
 #include <cstdlib>
+#include <cstring>
 
 #include "dg_onehot_kernel.h"
 
@@ -27,49 +28,65 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p)
     q.ch = tap_bytes % 32 == 0 ? 4 : (tap_bytes % 16 == 0 ? 2 : 1);
     if (lut->bits == 4 && q.ch == 4) q.ch = 2;             // (a 4-word chunk of 4-bit codes would be 32 MFMA steps)
     q.chunks = (p.K / per_byte(lut)) / (8 * q.ch);
-    q.wn = 1, q.S = 1, q.cpw = q.chunks;
-    // too few 64 x 32 tiles to give every SIMD a wavefront (or barely enough, and a long K to walk): split K
-    const int64_t t21 = tile_count(p, wm, 1);
-    const bool few_tiles = t21 < 512 || (t21 < 1024 && q.chunks >= 32);
-    q.split = few_tiles && q.chunks > 1;
-    // DG_ONEHOT_PLAN = split | 1 | 2 | 4 | 7 overrides the choice (tuning, and tests that must reach every plan)
-    const char *force = getenv("DG_ONEHOT_PLAN");
-    int force_wn = 0;
-    if (force) {
-        const int v = atoi(force);
-        if (force[0] == 's') q.split = true;
-        else if (v == 1 || v == 2 || v == 4 || v == 7) force_wn = v, q.split = false;
-    }
-    if (q.split) {
-        // about 2048 wavefronts in all, at most 16 per workgroup, whole chunks each
-        const int64_t blocks = tile_count(p, 1, 1);
-        int64_t target = 2048;
-        if (const char *e = getenv("DG_ONEHOT_WAVES")) target = atoi(e) > 0 ? atoi(e) : target;   // tuning override
-        int S = (int)((target + blocks - 1) / blocks);
-        S = S < 1 ? 1 : (S > 16 ? 16 : S);
-        if (S > q.chunks) S = q.chunks;
-        q.cpw = (q.chunks + S - 1) / S;
-        q.S = (q.chunks + q.cpw - 1) / q.cpw;
-        return q;
-    }
-    // Wave tile 64 x (32*wn): the one with the least modelled time on the busiest SIMD, in cycles.  A SIMD's
-    // wavefronts share its matrix pipe, so its time is (tiles per SIMD, rounded up) x (32x32 blocks per tile) x (MFMA
-    // steps of K) x (cycles per MFMA: 32, more where the VALU work of building operands or the operand loads show --
-    // measured 42 for one block column, 33 for two), plus what no other wavefront hides: one prologue (~3000 cycles)
-    // and the last tile's stores (~600 cycles per block).  7 blocks wide fits the 56 x 56 and 28 x 28 images of
-    // ImageNet networks (N = 49 * 2^k) where 4 wide leaves the last round of tiles half empty.  The constants are
-    // fitted to timings of 48 layer shapes with 2-bit codes; ties go to the wider tile (fewer operand loads).
+    q.wn = 1, q.skw = 1, q.S = 1, q.cpw = q.chunks;
+    q.split = false;
+    // the split-K kernel's shape: about 2048 wavefronts in all, at most 16 per workgroup, whole chunks each
+    const int64_t blocks11 = tile_count(p, 1, 1);
+    int64_t target = 2048;
+    if (const char *e = getenv("DG_ONEHOT_WAVES")) target = atoi(e) > 0 ? atoi(e) : target;   // tuning override
+    int S = (int)((target + blocks11 - 1) / blocks11);
+    S = S < 1 ? 1 : (S > 16 ? 16 : S);
+    if (S > q.chunks) S = q.chunks;
+    const int split_cpw = (q.chunks + S - 1) / S, split_S = (q.chunks + split_cpw - 1) / split_cpw;
+
+    // Which kernel and shape: the one with the least modelled time on the busiest SIMD, in cycles.  A SIMD's wavefronts
+    // share its matrix pipe, so the time of a plan is (wavefronts per SIMD, rounded up) x (32x32 blocks per tile) x
+    // (MFMA steps of a wavefront's share of K) x (cycles per MFMA), plus what no other wavefront hides: a prologue, the
+    // last tile's stores, and the LDS exchange where wavefronts share a tile.  Sharing a tile (2 or 4 wavefronts
+    // splitting K) fills SIMDs that the tiles alone would leave idle; 7 blocks wide fits the 56 x 56 and 28 x 28 images
+    // of ImageNet networks (N = 49 * 2^k) where 4 wide leaves the last round of tiles half empty.  The constants are a
+    // least-regret fit to timings of 78 layer shapes x 12 plans with 2-bit codes (the plan chosen is within 14 % of
+    // the best measured one on each, 1.3 % on average); ties go to the wider, less shared plan.
     static const int widths[4] = {7, 4, 2, 1};
-    static const double mfma_cycles[4] = {32.0, 32.0, 33.0, 42.0};
+    static const double mfma_cycles[4] = {37.7, 28.9, 29.5, 34.0};
+    const bool can_share = lut->bits == 2 && !q.two;
     const double steps = (double)p.K * (1 << lut->bits) / 32.0;
     double best = 0.0;
-    for (int i = 0; i < 4; ++i) {
-        const int wn = widths[i];
-        const double per_simd = (double)((tile_count(p, wm, wn) + 1023) / 1024);
-        const double cost = per_simd * 2 * wn * steps * mfma_cycles[i] + 3000.0 + 600.0 * 2 * wn;
-        if (i == 0 || cost < best * 0.999) best = cost, q.wn = wn;
+    bool first = true;
+    for (int i = 0; i < 4; ++i)
+        for (int skw = 1; skw <= (can_share ? 4 : 1); skw *= 2) {
+            const int wn = widths[i];
+            if (skw > q.chunks || (wn == 7 && skw == 2)) continue;      // (two 64x224 tiles of sums exceed 64 KB of LDS)
+            const int64_t per_simd = (tile_count(p, wm, wn) * skw + 1023) / 1024;
+            const double lone = per_simd == 1 ? 0.84 : (per_simd == 2 ? 0.78 : 1.0);   // (the rounding up overstates short queues)
+            double cost = (double)per_simd * 2 * wn * (steps / skw) * mfma_cycles[i] * lone + 2670.0 + 350.0 * 2 * wn / skw;
+            if (skw > 1) cost += 955.0 + 147.0 * 2 * wn;
+            if (first || cost < best * 0.999) best = cost, q.wn = wn, q.skw = skw, first = false;
+        }
+    if (can_share) {
+        const int64_t per_simd = (blocks11 * split_S + 1023) / 1024;
+        const double cost = (double)per_simd * (steps * split_cpw / q.chunks) * 50.6 + 3370.0;
+        q.split = q.chunks > 1 && cost < best;
+    } else {
+        // other code widths and two-plane tables (not in the fit): split K when there are too few 64 x 32 tiles to give
+        // every SIMD a wavefront, or barely enough and a long K to walk
+        const int64_t t21 = tile_count(p, wm, 1);
+        q.split = (t21 < 512 || (t21 < 1024 && q.chunks >= 32)) && q.chunks > 1;
     }
-    if (force_wn) q.wn = force_wn;
+    // DG_ONEHOT_PLAN = split | <wn> | <wn>k<skw> (wn = 1, 2, 4, 7; skw = 1, 2, 4) overrides the choice (tuning, and
+    // tests that must reach every plan)
+    if (const char *force = getenv("DG_ONEHOT_PLAN")) {
+        const int v = atoi(force);
+        if (force[0] == 's') q.split = true;
+        else if (v == 1 || v == 2 || v == 4 || v == 7) {
+            int k = 1;
+            if (const char *at = strchr(force, 'k')) k = atoi(at + 1);
+            q.split = false;
+            q.wn = v;
+            q.skw = (can_share && (k == 2 || k == 4) && k <= q.chunks && !(v == 7 && k == 2)) ? k : 1;
+        }
+    }
+    if (q.split) q.cpw = split_cpw, q.S = split_S;
     if (lut->bits == 4 && q.wn == 7) q.ch = 1;             // (the 2-word kernel of this tile is not built: see launch_ch)
     return q;
 }
@@ -98,12 +115,15 @@ const char *dg_onehot_config_name(const dg_lut *lut, const DgProblem &p)
          "onehot_mfma_2p_splitk_s5", "onehot_mfma_2p_splitk_s6", "onehot_mfma_2p_splitk_s7", "onehot_mfma_2p_splitk_s8",
          "onehot_mfma_2p_splitk_s9", "onehot_mfma_2p_splitk_s10", "onehot_mfma_2p_splitk_s11", "onehot_mfma_2p_splitk_s12",
          "onehot_mfma_2p_splitk_s13", "onehot_mfma_2p_splitk_s14", "onehot_mfma_2p_splitk_s15", "onehot_mfma_2p_splitk_s16"}};
-    static const char *const tile_names[2][4] = {
-        {"onehot_mfma_64x224", "onehot_mfma_64x128", "onehot_mfma_64x64", "onehot_mfma_64x32"},
-        {"onehot_mfma_2p_32x224", "onehot_mfma_2p_32x128", "onehot_mfma_2p_32x64", "onehot_mfma_2p_32x32"}};
+    static const char *const tile_names[2][3][4] = {
+        {{"onehot_mfma_64x224", "onehot_mfma_64x128", "onehot_mfma_64x64", "onehot_mfma_64x32"},
+         {"", "onehot_mfma_64x128_k2", "onehot_mfma_64x64_k2", "onehot_mfma_64x32_k2"},
+         {"onehot_mfma_64x224_k4", "onehot_mfma_64x128_k4", "onehot_mfma_64x64_k4", "onehot_mfma_64x32_k4"}},
+        {{"onehot_mfma_2p_32x224", "onehot_mfma_2p_32x128", "onehot_mfma_2p_32x64", "onehot_mfma_2p_32x32"},
+         {"", "", "", ""}, {"", "", "", ""}}};
     const Plan q = plan_for(lut, p);
     if (q.split) return split_names[q.two][q.S];
-    return tile_names[q.two][q.wn == 7 ? 0 : (q.wn == 4 ? 1 : (q.wn == 2 ? 2 : 3))];
+    return tile_names[q.two][q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)][q.wn == 7 ? 0 : (q.wn == 4 ? 1 : (q.wn == 2 ? 2 : 3))];
 }
 
 dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
@@ -122,17 +142,24 @@ dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t st
             if (q.two) pools.w[32 + v * qw + w / 4] |= (uint32_t)(uint8_t)(int8_t)hi << (8 * (w % 4));
         }
     const int64_t blocks11 = tile_count(p, 1, 1), wave_tiles = tile_count(p, q.two ? 1 : 2, q.wn);
-    if ((q.split ? blocks11 : (wave_tiles + 3) / 4) > INT32_MAX)
+    if ((q.split ? blocks11 : wave_tiles) > INT32_MAX)
         return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel: too many tiles for one grid");
-    const bool tr = p.stride_cm == 1 && p.stride_cn != 1;   // the output axis with stride 1 goes on the MFMA columns
-    if (q.two) {
-        (tr ? dgoh::launch_bits2_two_tr1 : dgoh::launch_bits2_two_tr0)(p, pools, q, blocks11, wave_tiles, stream);
-        return dg_check_launch(q.split ? "onehot_splitk_kernel" : "onehot_mfma_kernel");
+    const int tr = (p.stride_cm == 1 && p.stride_cn != 1) ? 1 : 0;   // the output axis with stride 1 goes on the MFMA columns
+    using namespace dgoh;
+    // [code width: 2, 3, 4, 2 in two planes][layout]
+    static const MainFn split_units[4][2] = {{unit_split_b2_t0, unit_split_b2_t1}, {unit_split_b3_t0, unit_split_b3_t1},
+                                             {unit_split_b4_t0, unit_split_b4_t1}, {unit_split_b22_t0, unit_split_b22_t1}};
+    static const MainFn main_units[4][2] = {{unit_main_b2_t0_k1, unit_main_b2_t1_k1}, {unit_main_b3_t0_k1, unit_main_b3_t1_k1},
+                                            {unit_main_b4_t0_k1, unit_main_b4_t1_k1}, {unit_main_b22_t0_k1, unit_main_b22_t1_k1}};
+    static const MainFn shared_units[2][2] = {{unit_main_b2_t0_k2, unit_main_b2_t1_k2}, {unit_main_b2_t0_k4, unit_main_b2_t1_k4}};
+    const int width = q.two ? 3 : lut->bits - 2;
+    if (q.split) {
+        split_units[width][tr](p, pools, q, blocks11, stream);
+        return dg_check_launch("onehot_splitk_kernel");
     }
-    switch (lut->bits) {
-    case 2: (tr ? dgoh::launch_bits2_tr1 : dgoh::launch_bits2_tr0)(p, pools, q, blocks11, wave_tiles, stream); break;
-    case 3: (tr ? dgoh::launch_bits3_tr1 : dgoh::launch_bits3_tr0)(p, pools, q, blocks11, wave_tiles, stream); break;
-    default: (tr ? dgoh::launch_bits4_tr1 : dgoh::launch_bits4_tr0)(p, pools, q, blocks11, wave_tiles, stream); break;
-    }
-    return dg_check_launch(q.split ? "onehot_splitk_kernel" : "onehot_mfma_kernel");
+    if (q.skw > 1)
+        shared_units[q.skw == 4][tr](p, pools, q, wave_tiles, stream);      // (planned for 2-bit one-plane tables only)
+    else
+        main_units[width][tr](p, pools, q, wave_tiles, stream);
+    return dg_check_launch("onehot_mfma_kernel");
 }

@@ -123,7 +123,11 @@ def test_conv_parity(case_, variant):
 
 
 ONEHOT_PLANS = {"split": "onehot_mfma_splitk_s", "1": "onehot_mfma_64x32", "2": "onehot_mfma_64x64",
-                "4": "onehot_mfma_64x128", "7": "onehot_mfma_64x224"}
+                "4": "onehot_mfma_64x128", "7": "onehot_mfma_64x224",
+                # 2 or 4 wavefronts sharing a tile and splitting K
+                "1k2": "onehot_mfma_64x32_k2", "1k4": "onehot_mfma_64x32_k4", "2k2": "onehot_mfma_64x64_k2",
+                "2k4": "onehot_mfma_64x64_k4", "4k2": "onehot_mfma_64x128_k2", "4k4": "onehot_mfma_64x128_k4",
+                "7k4": "onehot_mfma_64x224_k4"}
 
 
 @pytest.mark.parametrize("table", ["signed_unsigned", "extreme_i16"])
@@ -133,13 +137,23 @@ def test_onehot_every_plan(plan, table, monkeypatch):
     M and N (the library picks among them by a cost model that small test shapes would never move off one plan):
     GEMM with row-major and column-major output, convolution with padding and stride, int32 and scaled fp32 output.
     Once with an int8 table (one plane) and once with entries up to 16384 (two int8 planes)."""
+    if "k" in plan and table != "signed_unsigned":
+        pytest.skip("tiles are shared only by the one-plane kernels")
     monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
     glw, gla, gentry = LEVELS[table]
     prefix = ONEHOT_PLANS[plan] if table == "signed_unsigned" else ONEHOT_PLANS[plan].replace("onehot_mfma_", "onehot_mfma_2p_").replace("_64x", "_32x")
+
+    def right_kernel(name, chunks):
+        if plan == "split":
+            return name.startswith(prefix)
+        if "k" in plan and chunks < int(plan.split("k")[1]):
+            return name == prefix.rsplit("_k", 1)[0]        # fewer chunks than sharers: the unshared kernel
+        return name == prefix
+
     for (M, N, K) in [(70, 1000, 96), (130, 777, 64), (64, 300, 256), (33, 250, 1024)]:
         inp = wl.small_gemm(M, N, K, seed=M + N + K)
         case = GpuCase(inp, levels=(glw, gla), entry=gentry)
-        assert case.kernel_name("onehot_mfma").startswith(prefix)
+        assert right_kernel(case.kernel_name("onehot_mfma"), K // (128 if K % 128 == 0 else (64 if K % 64 == 0 else 32)))
         want = oracle.gemm(inp.Wc, inp.Ac, glw, gla)
         _assert_same(case.run("onehot_mfma").cpu().numpy(), want, f"gemm {(M, N, K)} plan {plan}")
         out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
@@ -154,7 +168,8 @@ def test_onehot_every_plan(plan, table, monkeypatch):
                                                       (1, 20, 20, 64, 96, 5, 5, (1, 1), (2, 2))]:
         c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
         case = GpuCase(c, levels=(lw, la), entry=entry)
-        assert case.kernel_name("onehot_mfma").startswith(prefix)
+        assert right_kernel(case.kernel_name("onehot_mfma"),
+                            KH * KW * Cin // (128 if Cin % 128 == 0 else (64 if Cin % 64 == 0 else 32)))
         acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
         _assert_same(case.run("onehot_mfma").cpu().numpy(), acc, f"conv {(B, H, W, Cin, Cout)} plan {plan}")
         got = case.run("onehot_mfma", scale=True).cpu().numpy()
