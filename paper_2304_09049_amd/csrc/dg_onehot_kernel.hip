@@ -48,8 +48,12 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p)
     // least-regret fit to timings of 78 layer shapes x 12 plans with 2-bit codes (the plan chosen is within 14 % of
     // the best measured one on each, 1.3 % on average); ties go to the wider, less shared plan.
     static const int widths[4] = {7, 4, 2, 1};
-    static const double mfma_cycles[4] = {37.7, 28.9, 29.5, 34.0};
     const bool can_share = lut->bits == 2 && !q.two;
+    // (the wider codes and two-plane tables, with 2 to 4 times the MFMA work per load, keep the constants of an earlier
+    // fit without sharing, under which their measured times are better: 32 cycles per MFMA, 33 and 42 for the two
+    // narrowest tiles, 3000 + 600 per block for prologue and stores)
+    static const double fitted_cycles[4] = {37.7, 28.9, 29.5, 34.0}, plain_cycles[4] = {32.0, 32.0, 33.0, 42.0};
+    const double *mfma_cycles = can_share ? fitted_cycles : plain_cycles;
     const double steps = (double)p.K * (1 << lut->bits) / 32.0;
     double best = 0.0;
     bool first = true;
@@ -58,8 +62,9 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p)
             const int wn = widths[i];
             if (skw > q.chunks || (wn == 7 && skw == 2)) continue;      // (two 64x224 tiles of sums exceed 64 KB of LDS)
             const int64_t per_simd = (tile_count(p, wm, wn) * skw + 1023) / 1024;
-            const double lone = per_simd == 1 ? 0.84 : (per_simd == 2 ? 0.78 : 1.0);   // (the rounding up overstates short queues)
-            double cost = (double)per_simd * 2 * wn * (steps / skw) * mfma_cycles[i] * lone + 2670.0 + 350.0 * 2 * wn / skw;
+            const double lone = !can_share ? 1.0 : (per_simd == 1 ? 0.84 : (per_simd == 2 ? 0.78 : 1.0));   // (rounding up overstates short queues)
+            double cost = (double)per_simd * 2 * wn * (steps / skw) * mfma_cycles[i] * lone;
+            cost += can_share ? 2670.0 + 350.0 * 2 * wn / skw : 3000.0 + 600.0 * 2 * wn;
             if (skw > 1) cost += 955.0 + 147.0 * 2 * wn;
             if (first || cost < best * 0.999) best = cost, q.wn = wn, q.skw = skw, first = false;
         }
