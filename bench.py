@@ -36,9 +36,9 @@ PERM_ALU_PEAK_TOPS = VALU_LANE_INSTR_PER_S * (4 / 1.5) * 2 / 1e12
 # bytes -> x2.0; WRITE_SIZE reads them exactly -> x1.0).  Summaries with the commands are under profiles/.
 # Keyed by (workload, kernel name); a kernel or workload that was not profiled reports null.
 MEASURED_TRAFFIC_KIB = {
-    ("resnet18_conv3x3_b1", "onehot_mfma_splitk_s9"): (231.2 * 2.0, 784.0),
-    ("vgg16_conv3x3_b16", "onehot_mfma_64x224"): (3601.5 * 2.0, 50176.0),
-    ("gemm_8192x1x8192_i16", "smalln"): (8252.0 * 2.0, 32.0),
+    ("resnet18_conv3x3_b1", "onehot_mfma_splitk_s9"): (230.7 * 2.0, 784.0),
+    ("vgg16_conv3x3_b16", "onehot_mfma_64x128"): (4607.8 * 2.0, 50176.0),
+    ("gemm_8192x1x8192_i16", "smalln"): (8251.9 * 2.0, 32.0),
 }
 
 
