@@ -176,6 +176,31 @@ def test_onehot_every_plan(plan, table, monkeypatch):
         assert np.array_equal(got, oracle.scale_epilogue_nhwc(acc, c.scale)), f"scaled conv plan {plan}"
 
 
+def test_random_convolution_shapes():
+    """Seeded random convolution geometries (image, filter, stride, padding, channel counts, batch) through AUTO and
+    every variant that accepts them: the oracle is the plain nested loop, so any disagreement is a kernel indexing bug."""
+    rng = np.random.default_rng(2024)
+    lw, la, entry = LEVELS["nonuniform_i8"]              # no zero activation level
+    ran = {v: 0 for v in VARIANTS}
+    for _ in range(40):
+        KH, KW = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        sh, sw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        ph, pw = int(rng.integers(0, KH)), int(rng.integers(0, KW))
+        H, W = int(rng.integers(KH, 24)), int(rng.integers(KW, 24))
+        Cin = int(rng.choice([4, 8, 16, 32, 48, 64, 96, 128, 256]))
+        Cout = int(rng.integers(1, 140))
+        B = int(rng.integers(1, 5))
+        c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, (sh, sw), (ph, pw), seed=int(rng.integers(1 << 30)))
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        want = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=(sh, sw), pad=(ph, pw))
+        for variant in VARIANTS:
+            got = run_or_unsupported(case, variant)
+            if got is not None:
+                ran[variant] += 1
+                _assert_same(got, want, f"conv B={B} {H}x{W} Cin={Cin} Cout={Cout} {KH}x{KW} s=({sh},{sw}) p=({ph},{pw}) {variant}")
+    assert ran["auto"] == 40 and ran["lds"] == 40 and ran["onehot_mfma"] >= 10 and ran["perm"] >= 10
+
+
 def test_golden_tiny_conv_on_gpu(golden_dir):
     import json, os
     from test_oracle_pins import _tiny_conv_weights
