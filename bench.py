@@ -173,7 +173,23 @@ def time_steady(torch, fn, use_graph):
     if graph:
         reps -= reps % 100
     time_calls(torch, fn, reps, graph, chunk=100)
-    return time_calls(torch, fn, reps, graph, chunk=100)
+    runs = sorted(time_calls(torch, fn, reps, graph, chunk=100) for _ in range(5))
+    return runs[2]                                 # median of 5
+
+
+def single_launch_us(torch, fn):
+    """Median over 21 single launches of the time between two events around one launch from the host (what one call
+    costs in isolation: launch latency included, nothing overlapped)."""
+    torch.cuda.synchronize()
+    out = []
+    for _ in range(21):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        torch.cuda.synchronize()
+        out.append(a.elapsed_time(b) * 1e3)
+    return round(sorted(out)[10], 2)
 
 
 def mfma_ops_factor(name):
@@ -193,9 +209,12 @@ def kernel_report(w, ms, name):
     f = mfma_ops_factor(name)
     return {
         "kernel": name, "us": round(ms * 1e3, 3), "gops": round(gops, 1), "algorithmic_GBps": round(gbs, 1),
+        # the three ceilings side by side, all in effective operations (2MNK) or algorithmic bytes
         "frac_hbm": round(gbs / HBM_PEAK_GBS, 4),
+        "frac_int8_mfma_peak_effective": round(gops / 1e3 / INT8_MFMA_PEAK_TOPS, 4),
+        "frac_valu_lookup_ceiling": round(gops / 1e3 / PERM_ALU_PEAK_TOPS, 4),
+        # matrix-core kernels: int8 MFMA operations actually issued (4 per effective operation for one-hot selection)
         "frac_int8_mfma_peak": None if f is None else round(f * gops / 1e3 / INT8_MFMA_PEAK_TOPS, 4),
-        "frac_perm_alu_peak": round(gops / 1e3 / PERM_ALU_PEAK_TOPS, 4) if name.startswith("perm") else None,
     }
 
 
@@ -399,6 +418,9 @@ def main():
                     ms = time_steady(torch, fn, use_graph)
                     rep = kernel_report(ww, ms, kname)
                     rep.update({"workload": wname, "variant": variant})
+                    if ww.ops < 1e9:
+                        # roofline time far below the launch overhead: also what one isolated launch costs
+                        rep["single_launch_us"] = single_launch_us(torch, fn)
                     if variant == "auto" and ww.kind == "gemm" and ww.N <= 16 and ww.M * ww.K // 4 >= (8 << 20):
                         # weight-streaming shapes: also with the weights NOT resident in the last-level cache
                         rr.make_cold_weights()
