@@ -259,8 +259,9 @@ def launch_floor_us(torch, w, name, use_graph):
 
 
 def stage_kernels(torch, w):
-    """The HBM-bound stages either side of the table kernel, on one large activation tensor: packing of codes and the
-    fused fp32 quantise + pack.  Bytes are algorithmic (input read once + packed output written once)."""
+    """The HBM-bound stages either side of the table kernel, on one large activation tensor: packing of codes, the
+    fused fp32 quantise + pack, and the dequantise of int32 sums.  Bytes are algorithmic (input read once + output
+    written once)."""
     from paper_2304_09049_amd import binding as dg
     rows, k = w.B * w.H * w.W, w.Cin
     count = rows * k
@@ -280,9 +281,18 @@ def stage_kernels(torch, w):
         turn[0] += 1
         dg.dg_quantize_pack_activations(xs[turn[0] % n_x], rows, k, 1.0, 0.0, 0, out=out)
 
+    accs = [torch.randint(-1000, 1000, (count,), dtype=torch.int32, device=dev) for _ in range(n_x)]
+    scale_c = torch.rand(k, dtype=torch.float32, device=dev)
+    deq = torch.empty(count, dtype=torch.float32, device=dev)
+
+    def dequantize():
+        turn[0] += 1
+        dg.dg_dequantize(accs[turn[0] % n_x], rows, k, scale_c, out=deq)
+
     report = []
     for name, fn, nbytes in (("pack_vec16_unrolled_kernel", pack, count + count // 4),
-                             ("quantize_pack_vec16_kernel", quantize_pack, 4 * count + count // 4)):
+                             ("quantize_pack_vec16_kernel", quantize_pack, 4 * count + count // 4),
+                             ("dequantize_kernel", dequantize, 8 * count)):
         for _ in range(3):
             fn()
         ms = time_calls(torch, fn, 200, True, chunk=100)

@@ -139,6 +139,17 @@ dg_status dg_quantize_pack_activations(const float *x_dev, int64_t N, int64_t K,
                                        float zero_point, int32_t lo, void *packed_dev,
                                        size_t packed_bytes, void *hip_stream);
 
+/*
+ * The matching dequantise stage (Sec. 5.4 names it as the operator after the table convolution), for callers that
+ * keep the int32 sums: out[r][c] = (float)acc[r][c] * scale_c[c] -- one int32 -> binary32 conversion (round to
+ * nearest even) and one binary32 multiply, exactly what the scale epilogue of dg_gemm_lut / dg_conv2d_lut does.
+ * acc_dev: device, int32 [rows][C] contiguous (NHWC: rows = B*OH*OW, C = Cout); scale_c_dev: device, fp32 [C];
+ * out_dev: device, fp32 [rows][C] (may be acc_dev itself: element by element in place).
+ * Errors: DG_ERR_NULL; DG_ERR_SHAPE if rows <= 0 or C <= 0.
+ */
+dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const float *scale_c_dev,
+                        float *out_dev, void *hip_stream);
+
 /* ---- the kernels ------------------------------------------------------------------------------ */
 
 /*

@@ -30,7 +30,7 @@ EXPORTS = (
     "dg_packed_activation_bytes", "dg_packed_weight_bytes", "dg_packed_bytes_bits", "dg_pack_weights",
     "dg_pack_activations", "dg_pack_codes_bits", "dg_quantize_pack_activations",
     "dg_gemm_lut", "dg_conv_out_dim", "dg_conv2d_lut", "dg_gemm_kernel_name", "dg_conv_kernel_name",
-    "dg_launch_empty",
+    "dg_launch_empty", "dg_dequantize",
 )
 
 
@@ -90,6 +90,7 @@ def lib() -> ctypes.CDLL:
     L.dg_conv_kernel_name.argtypes = [c_vp, ctypes.POINTER(ConvDesc), c_int]
     L.dg_conv_kernel_name.restype = ctypes.c_char_p
     L.dg_launch_empty.argtypes, L.dg_launch_empty.restype = [c_i64, c_int, c_vp], c_int
+    L.dg_dequantize.argtypes, L.dg_dequantize.restype = [c_vp, c_i64, c_i64, c_vp, c_vp, c_vp], c_int
     _lib = L
     return L
 
@@ -296,3 +297,13 @@ def dg_conv_kernel_name(lut: Lut, desc: ConvDesc, variant="auto") -> str:
 def dg_launch_empty(blocks: int, threads: int, stream=None) -> None:
     """A launch that does nothing: the cost of a grid of that shape (measurement aid)."""
     _check(lib().dg_launch_empty(blocks, threads, _stream_ptr(stream)))
+
+
+def dg_dequantize(acc, rows: int, C: int, scale, out=None, stream=None):
+    """acc: int32 device tensor [rows][C]; scale: float32 [C] -> float32 [rows][C] = float(acc) * scale[c]."""
+    import torch
+    if out is None:
+        out = torch.empty(acc.shape, dtype=torch.float32, device=acc.device)
+    _check(lib().dg_dequantize(_dev_ptr(acc, torch.int32, "acc"), rows, C, _dev_ptr(scale, torch.float32, "scale"),
+                               _dev_ptr(out, torch.float32, "out"), _stream_ptr(stream)))
+    return out

@@ -238,6 +238,16 @@ dg_status dg_quantize_pack_activations(const float *x_dev, int64_t N, int64_t K,
                                    (hipStream_t)hip_stream);
 }
 
+dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const float *scale_c_dev, float *out_dev,
+                        void *hip_stream)
+{
+    const char *name = "dg_dequantize";
+    if (!acc_dev || !scale_c_dev || !out_dev) return dg_fail(DG_ERR_NULL, "%s: NULL buffer", name);
+    if (rows <= 0 || C <= 0 || C > INT32_MAX || rows > INT64_MAX / C)
+        return dg_fail(DG_ERR_SHAPE, "%s: rows=%lld C=%lld", name, (long long)rows, (long long)C);
+    return dg_launch_dequantize(acc_dev, rows, C, scale_c_dev, out_dev, (hipStream_t)hip_stream);
+}
+
 int64_t dg_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad)
 {
     if (stride <= 0 || k <= 0 || in <= 0 || pad < 0) return 0;

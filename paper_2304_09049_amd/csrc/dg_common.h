@@ -50,6 +50,8 @@ dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits
                          hipStream_t stream);
 dg_status dg_launch_quantize_pack(const float *x, int64_t rows, int64_t K, float scale, float zero_point,
                                   int32_t lo, uint8_t *packed, hipStream_t stream);
+dg_status dg_launch_dequantize(const int32_t *acc, int64_t rows, int64_t C, const float *scale, float *out,
+                               hipStream_t stream);
 dg_status dg_launch_lds(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 dg_status dg_launch_lds_f32(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 bool dg_perm_supports(const dg_lut *lut, const DgProblem &p);

@@ -182,3 +182,45 @@ dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits
     }
     return DG_OK;
 }
+
+namespace {
+// Dequantise: out = float(acc) * scale[channel].  HBM-bound: 4 bytes read and 4 written per element; 128-bit accesses
+// when the row length and the pointers allow (then a lane's four elements are four consecutive channels of one row).
+template <bool VEC>
+__global__ void __launch_bounds__(256)
+dequantize_kernel(const int32_t *acc, const float *__restrict__ scale, float *out, int64_t total, int32_t C)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    if (VEC) {
+        const int64_t groups = total / 4;
+        for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups; g += stride) {
+            const int4 v = ((const int4 *)acc)[g];
+            const int c = (int)((4 * g) % C);
+            const float4 s = *(const float4 *)(scale + c);
+            float4 o;
+            o.x = __fmul_rn((float)v.x, s.x), o.y = __fmul_rn((float)v.y, s.y);
+            o.z = __fmul_rn((float)v.z, s.z), o.w = __fmul_rn((float)v.w, s.w);
+            ((float4 *)out)[g] = o;
+        }
+    } else {
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride)
+            out[i] = __fmul_rn((float)acc[i], scale[i % C]);
+    }
+}
+}   // namespace
+
+dg_status dg_launch_dequantize(const int32_t *acc, int64_t rows, int64_t C, const float *scale, float *out,
+                               hipStream_t stream)
+{
+    const int64_t total = rows * C;
+    const bool vec = C % 4 == 0 && (uintptr_t)acc % 16 == 0 && (uintptr_t)out % 16 == 0 && (uintptr_t)scale % 16 == 0;
+    int64_t blocks = ((vec ? total / 4 : total) + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (vec)
+        hipLaunchKernelGGL(dequantize_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, acc, scale, out, total,
+                           (int32_t)C);
+    else
+        hipLaunchKernelGGL(dequantize_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, acc, scale, out, total,
+                           (int32_t)C);
+    return dg_check_launch("dequantize_kernel");
+}

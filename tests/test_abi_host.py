@@ -183,3 +183,12 @@ def test_kernel_names_need_no_gpu():
     t4 = dg.dg_build_lut_bits(4, list(range(-8, 8)), list(range(16)), dg.DG_LUT_I8)
     assert dg.dg_gemm_kernel_name(t4, 256, 50176, 2304).startswith("onehot_mfma_64x")
     assert dg.dg_gemm_kernel_name(t4, 256, 50176, 2304, "perm") == "unsupported"
+
+
+def test_dequantize_argument_errors():
+    L = dg.lib()
+    fake = ctypes.c_void_p(0x1000)
+    assert L.dg_dequantize(None, 4, 4, fake, fake, None) == 1
+    assert L.dg_dequantize(fake, 4, 4, None, fake, None) == 1
+    assert L.dg_dequantize(fake, 0, 4, fake, fake, None) == 2
+    assert L.dg_dequantize(fake, 4, -1, fake, fake, None) == 2

@@ -361,6 +361,27 @@ def test_quantize_pack_matches_oracle_quantiser_and_packing():
     _assert_same(got.reshape(9, 13), oracle.pack_codes(oracle.quantize_codes(x, 2.0, 0.5, -2, 1)), "unaligned quantize")
 
 
+def test_dequantize_equals_the_scale_epilogue():
+    # int32 sums -> separate dequantise stage == oracle epilogue == the kernels' fused epilogue, bit for bit
+    rng = np.random.default_rng(77)
+    for rows, C in ((7, 5), (196, 64), (33, 130), (1000, 256)):
+        acc = rng.integers(-(1 << 30), 1 << 30, size=(rows, C)).astype(np.int32)     # beyond 2^24: conversion rounds
+        acc[0, : min(C, 4)] = [0, -1, (1 << 24) + 1, -(1 << 24) - 3][: min(C, 4)]
+        scale = rng.uniform(0.01, 0.1, size=C).astype(np.float32)
+        got = dg.dg_dequantize(torch.from_numpy(acc).cuda(), rows, C, torch.from_numpy(scale).cuda()).cpu().numpy()
+        assert np.array_equal(got, oracle.scale_epilogue_nhwc(acc.reshape(1, 1, rows, C), scale).reshape(rows, C))
+    c = wl.small_conv(2, 13, 11, 64, 70, 3, 3, (1, 1), (1, 1), seed=5, scale=True)
+    case = GpuCase(c)
+    y = case.run("auto")
+    fused = case.run("auto", scale=True)
+    sep = dg.dg_dequantize(y, 2 * 13 * 11, 70, case.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(sep.reshape(fused.shape), fused)
+    with pytest.raises(dg.DgError) as e:
+        dg.dg_dequantize(y, 0, 70, case.scale)
+    assert e.value.status == 2
+
+
 def test_quantize_pack_feeds_the_convolution():
     # fp32 NHWC input -> quantise+pack -> table convolution, against oracle quantiser -> oracle convolution
     rng = np.random.default_rng(41)
