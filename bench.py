@@ -336,6 +336,33 @@ def wide_code_kernels(torch, w, use_graph):
     return report
 
 
+def fused_layers(torch, names, use_graph):
+    """A whole layer -- table convolution, scale, re-quantise, pack -- as one kernel (dg_conv2d_lut_requant) against
+    the same work as two calls (dg_conv2d_lut with the scale epilogue, then dg_quantize_pack_activations)."""
+    from paper_2304_09049_amd import binding as dg
+    from paper_2304_09049_amd import workloads as wl
+    report = []
+    for name in names:
+        w = wl.CONFIGS[name]
+        r = Runner(w, "auto")
+        dev = r.Wp.device
+        scale = r.scale if r.scale is not None else torch.rand(w.Cout, dtype=torch.float32, device=dev) * 0.09 + 0.01
+        yf = torch.empty(r.out.shape, dtype=torch.float32, device=dev)
+        packed = torch.empty(dg.dg_packed_activation_bytes(w.N, w.Cout), dtype=torch.uint8, device=dev)
+
+        def two_calls():
+            dg.dg_conv2d_lut(r.lut, r.Wp, r.Ap, r.desc, out=yf, scale=scale)
+            dg.dg_quantize_pack_activations(yf, w.N, w.Cout, 0.05, 0.5, 0, out=packed)
+
+        def fused():
+            dg.dg_conv2d_lut_requant(r.lut, r.Wp, r.Ap, r.desc, scale, 0.05, 0.5, 0, out=packed)
+
+        t2, t1 = time_steady(torch, two_calls, use_graph), time_steady(torch, fused, use_graph)
+        report.append({"workload": name, "kernel": r.kernel_name(), "conv_then_quantize_pack_us": round(t2 * 1e3, 3),
+                       "fused_layer_us": round(t1 * 1e3, 3), "fused_gops": round(w.ops / (t1 * 1e-3) / 1e9, 1)})
+    return report
+
+
 def cpu_baseline(w):
     """The CPU oracle, as it stands, on the host cores: the full headline workload, repeated."""
     import oracle
@@ -446,6 +473,8 @@ def main():
         line["sweep"] = sweep
         line["stage_kernels"] = stage_kernels(torch, wl.CONFIGS["resnet50_conv1x1_b32"])
         line["wide_codes"] = wide_code_kernels(torch, wl.CONFIGS["vgg16_conv3x3_b16"], use_graph)
+        line["fused_layers"] = fused_layers(torch, ["resnet18_conv3x3_b1", "resnet50_conv1x1_b32", "vgg16_conv3x3_b16"],
+                                            use_graph)
 
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(w)

@@ -221,6 +221,22 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
                         const dg_conv_desc *desc, int32_t *Y_dev, const float *scale_cout_dev,
                         float *Yf_dev, dg_kernel variant, void *hip_stream);
 
+/*
+ * A whole layer in one kernel: table convolution, dequantise, re-quantise (Sec. 2.1, Eq. 1) and pack -- the stages
+ * Sec. 5.4 lists after one another -- so that the output is the packed activation tensor of the next layer:
+ *     y    = (float)sum * scale_cout_dev[co]                               (as in dg_conv2d_lut)
+ *     code = clip(round(q_scale * y + q_zero), lo, lo + 3) - lo            (as in dg_quantize_pack_activations)
+ * packed_out_dev: device, dg_packed_activation_bytes(B*OH*OW, Cout) bytes, the public layout ([pixel][Cout/4]).
+ * Every decision is taken in binary32, operation by operation, so the result equals dg_conv2d_lut followed by
+ * dg_quantize_pack_activations bit for bit.  Needs Cout % 4 == 0 and a table and shape the one-hot matrix-core
+ * kernel accepts (variant AUTO or ONEHOT_MFMA; otherwise DG_ERR_UNSUPPORTED -- run the two calls instead).
+ * Errors: as dg_conv2d_lut; DG_ERR_SHAPE if Cout % 4 != 0; DG_ERR_BUFFER if packed_bytes is too small.
+ */
+dg_status dg_conv2d_lut_requant(const dg_lut *lut, const void *Wp_dev, const void *Xp_dev,
+                                const dg_conv_desc *desc, const float *scale_cout_dev, float q_scale,
+                                float q_zero, int32_t lo, void *packed_out_dev, size_t packed_bytes,
+                                dg_kernel variant, void *hip_stream);
+
 /* Measurement aid: launch a kernel that does nothing, `blocks` workgroups of `threads` threads (a multiple of 64,
  * at most 1024), on `hip_stream`.  Its duration is what a launch of that shape costs before any work is done, the
  * floor under the duration of a small layer's kernel.  Errors: DG_ERR_SHAPE. */

@@ -30,7 +30,7 @@ EXPORTS = (
     "dg_packed_activation_bytes", "dg_packed_weight_bytes", "dg_packed_bytes_bits", "dg_pack_weights",
     "dg_pack_activations", "dg_pack_codes_bits", "dg_quantize_pack_activations",
     "dg_gemm_lut", "dg_conv_out_dim", "dg_conv2d_lut", "dg_gemm_kernel_name", "dg_conv_kernel_name",
-    "dg_launch_empty", "dg_dequantize",
+    "dg_launch_empty", "dg_dequantize", "dg_conv2d_lut_requant",
 )
 
 
@@ -91,6 +91,9 @@ def lib() -> ctypes.CDLL:
     L.dg_conv_kernel_name.restype = ctypes.c_char_p
     L.dg_launch_empty.argtypes, L.dg_launch_empty.restype = [c_i64, c_int, c_vp], c_int
     L.dg_dequantize.argtypes, L.dg_dequantize.restype = [c_vp, c_i64, c_i64, c_vp, c_vp, c_vp], c_int
+    L.dg_conv2d_lut_requant.argtypes = [c_vp, c_vp, c_vp, ctypes.POINTER(ConvDesc), c_vp, ctypes.c_float, ctypes.c_float,
+                                        ctypes.c_int32, c_vp, ctypes.c_size_t, c_int, c_vp]
+    L.dg_conv2d_lut_requant.restype = c_int
     _lib = L
     return L
 
@@ -306,4 +309,19 @@ def dg_dequantize(acc, rows: int, C: int, scale, out=None, stream=None):
         out = torch.empty(acc.shape, dtype=torch.float32, device=acc.device)
     _check(lib().dg_dequantize(_dev_ptr(acc, torch.int32, "acc"), rows, C, _dev_ptr(scale, torch.float32, "scale"),
                                _dev_ptr(out, torch.float32, "out"), _stream_ptr(stream)))
+    return out
+
+
+def dg_conv2d_lut_requant(lut: Lut, Wp, Xp, desc: ConvDesc, scale, q_scale: float, q_zero: float, lo: int, out=None,
+                          variant="auto", stream=None):
+    """One fused layer: table convolution, per-channel scale, re-quantisation and packing -> packed uint8 [B*OH*OW][Cout/4]."""
+    import torch
+    OH = dg_conv_out_dim(desc.H, desc.KH, desc.stride_h, desc.pad_h)
+    OW = dg_conv_out_dim(desc.W, desc.KW, desc.stride_w, desc.pad_w)
+    if out is None:
+        out = torch.empty(dg_packed_activation_bytes(desc.B * OH * OW, desc.Cout), dtype=torch.uint8, device=Wp.device)
+    _check(lib().dg_conv2d_lut_requant(lut.handle, _dev_ptr(Wp, torch.uint8, "Wp"), _dev_ptr(Xp, torch.uint8, "Xp"),
+                                       ctypes.byref(desc), _dev_ptr(scale, torch.float32, "scale"), q_scale, q_zero, lo,
+                                       _dev_ptr(out, torch.uint8, "packed"), out.numel(), _kernel(variant),
+                                       _stream_ptr(stream)))
     return out

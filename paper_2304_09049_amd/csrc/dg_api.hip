@@ -434,6 +434,37 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
     return run(lut, p, variant, (hipStream_t)hip_stream);
 }
 
+dg_status dg_conv2d_lut_requant(const dg_lut *lut, const void *Wp_dev, const void *Xp_dev, const dg_conv_desc *desc,
+                                const float *scale_cout_dev, float q_scale, float q_zero, int32_t lo,
+                                void *packed_out_dev, size_t packed_bytes, dg_kernel variant, void *hip_stream)
+{
+    const char *name = "dg_conv2d_lut_requant";
+    DgProblem p;
+    dg_status s = fill_conv(name, lut, desc, &p);
+    if (s != DG_OK) return s;
+    if (p.M % 4 != 0) return dg_fail(DG_ERR_SHAPE, "%s: Cout=%d is not a multiple of 4", name, p.M);
+    if (!Wp_dev || !Xp_dev || !scale_cout_dev || !packed_out_dev) return dg_fail(DG_ERR_NULL, "%s: NULL buffer", name);
+    if (lo < -(1 << 24) || lo > (1 << 24)) return dg_fail(DG_ERR_RANGE, "%s: lo=%d is not exact in binary32", name, lo);
+    const size_t need = dg_packed_activation_bytes(p.N, p.M);
+    if (packed_bytes < need)
+        return dg_fail(DG_ERR_BUFFER, "%s: packed buffer has %zu bytes, %zu needed", name, packed_bytes, need);
+    p.Wp = (const uint8_t *)Wp_dev;
+    p.Xp = (const uint8_t *)Xp_dev;
+    p.scale = scale_cout_dev;
+    p.stride_cm = 1;
+    p.stride_cn = p.M;
+    p.Qp = (uint8_t *)packed_out_dev;
+    p.q_scale = q_scale;
+    p.q_zero = q_zero;
+    p.q_lo = lo;
+    // the re-quantising epilogue lives in the one-hot matrix-core kernels
+    if ((variant != DG_KERNEL_AUTO && variant != DG_KERNEL_ONEHOT_MFMA) || lut->dtype == DG_LUT_F32 ||
+        !dg_onehot_supports(lut, p))
+        return dg_fail(DG_ERR_UNSUPPORTED, "%s: needs the one-hot matrix-core kernel (variant %d, Cin=%d, table range %d..%d)",
+                       name, (int)variant, p.Cin, lut->min_entry, lut->max_entry);
+    return dg_launch_onehot(lut, p, (hipStream_t)hip_stream);
+}
+
 dg_status dg_launch_empty(int64_t blocks, int32_t threads, void *hip_stream)
 {
     if (blocks <= 0 || blocks > INT32_MAX || threads <= 0 || threads > 1024 || threads % 64 != 0)

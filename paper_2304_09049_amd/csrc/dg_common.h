@@ -38,6 +38,11 @@ struct DgProblem {
     float *Cf;            // fp32 output (used when scale != nullptr)
     const float *scale;   // per-m scale or nullptr
     int64_t stride_cm, stride_cn;   // element strides of the output
+    // Re-quantising epilogue (the packed activations of the next layer instead of C / Cf), used when Qp != nullptr:
+    // code = clip(rint(q_scale * (float(sum) * scale[m]) + q_zero), q_lo, q_lo + 3) - q_lo, four channels per byte.
+    uint8_t *Qp;          // [N][M/4]; requires scale, M % 4 == 0 and the NHWC output order (stride_cm == 1)
+    float q_scale, q_zero;
+    int32_t q_lo;
 };
 
 // Record the calling thread's error detail and return `s`.

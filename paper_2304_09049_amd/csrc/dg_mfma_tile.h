@@ -9,6 +9,7 @@
 #pragma once
 
 #include "dg_common.h"
+#include "dg_quant.h"
 
 typedef int dg_v4i __attribute__((ext_vector_type(4)));
 typedef int dg_v16i __attribute__((ext_vector_type(16)));
@@ -34,10 +35,48 @@ __device__ __forceinline__ void dg_mfma_column_scales(const DgProblem &p, int m0
 
 // Store one 32x32 block whose first row / column sit at (mb, nb): int32 as it is, or float(acc) * scale[m] (one
 // conversion, one multiply); `sc` is the lane's prefetched scale (TR only).
+// OR of `v` over the four lanes of a quad (two DPP quad permutes); every lane gets the result.
+__device__ __forceinline__ uint32_t dg_quad_or(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+    return v;
+}
+
+// Re-quantising store of one block (TR layout only: the lanes of a quad hold four consecutive channels of one output
+// pixel).  Each lane turns its 16 sums into 2-bit codes; the codes of a quad's four channels are OR'd into the packed
+// byte across the quad; of every four consecutive pixels (accumulator registers 4q .. 4q+3) lane i of the quad keeps
+// and stores the byte of pixel i, so all lanes store.  Call with all 64 lanes active.
+__device__ __forceinline__ void dg_mfma_requant_block(const DgProblem &p, const dg_v16i &acc, int mb, int nb, int lane,
+                                                      float sc)
+{
+    const int r = lane & 31, h = lane >> 5, q = r & 3;
+    const bool live = mb + r < p.M;                       // (M % 4 == 0: a quad is inside M or outside as a whole)
+    const float lo_f = (float)p.q_lo, hi_f = (float)(p.q_lo + 3);
+    const int64_t row_bytes = p.M / 4;
+#pragma unroll
+    for (int e4 = 0; e4 < 4; ++e4) {
+        uint32_t mine = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float y = __fmul_rn((float)acc[4 * e4 + i], sc);
+            const uint32_t code = live ? dg_quantize_code(y, p.q_scale, p.q_zero, lo_f, hi_f, p.q_lo) : 0u;
+            const uint32_t byte = dg_quad_or(code << (2 * q));
+            if (q == i) mine = byte;
+        }
+        const int n = nb + 8 * e4 + 4 * h + q;            // the pixel whose byte this lane kept
+        if (live && n < p.N) p.Qp[(int64_t)n * row_bytes + (mb + r) / 4] = (uint8_t)mine;
+    }
+}
+
 template <bool TR>
 __device__ __forceinline__ void dg_mfma_store_block(const DgProblem &p, const dg_v16i &acc, int mb, int nb, int lane,
                                                     float sc)
 {
+    if (TR && p.Qp) {
+        dg_mfma_requant_block(p, acc, mb, nb, lane, sc);
+        return;
+    }
     const int r = lane & 31, h = lane >> 5;
     const int col = (TR ? mb : nb) + r;
     if (col >= (TR ? p.M : p.N)) return;

@@ -470,6 +470,21 @@ onehot_splitk_kernel(SplitArgs a)
         __hip_atomic_fetch_add(&s_sum[e * 64 + lane], acc[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     __syncthreads();
 
+    if (TR && p.Qp) {
+        // re-quantising epilogue: the four channels of a quad make one packed byte of the next layer's activations
+        // (a wavefront's 64 elements share the accumulator register e, so the trip count is uniform and DPP is safe)
+        const float lo_f = (float)p.q_lo, hi_f = (float)(p.q_lo + 3);
+        for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
+            const int e = idx >> 6, l = idx & 63, c = l & 31;
+            const int m = m0 + c, n = n0 + 8 * (e / 4) + 4 * (l >> 5) + (e % 4);
+            const bool live = m < p.M;
+            const float y = __fmul_rn((float)s_sum[idx], sc);
+            const uint32_t code = live ? dg_quantize_code(y, p.q_scale, p.q_zero, lo_f, hi_f, p.q_lo) : 0u;
+            const uint32_t byte = dg_quad_or(code << (2 * (c & 3)));
+            if (live && (c & 3) == 0 && n < p.N) p.Qp[(int64_t)n * (p.M / 4) + m / 4] = (uint8_t)byte;
+        }
+        return;
+    }
     for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
         const int e = idx >> 6, l = idx & 63;
         const int32_t sum = s_sum[idx];

@@ -4,6 +4,7 @@
 // so the whole matrix is one flat run of rows*K codes.  HBM-bound: 1 byte read and 1/4 byte written
 // per code; each lane moves 16 codes per 128-bit load and writes one 32-bit word.
 #include "dg_common.h"
+#include "dg_quant.h"
 
 namespace {
 
@@ -54,16 +55,6 @@ pack_bytes_kernel(const uint8_t *__restrict__ codes, uint8_t *__restrict__ packe
     }
 }
 
-// Eq. 1 of the paper in binary32, operation by operation: multiply, add (not fused), round half to even, clip.
-// NaN fails every comparison and therefore yields code 0.
-__device__ __forceinline__ uint32_t quantize_code(float x, float s, float z, float lo_f, float hi_f, int lo)
-{
-    const float r = rintf(__fadd_rn(__fmul_rn(s, x), z));
-    int q = lo;
-    if (r > lo_f) q = r >= hi_f ? lo + 3 : (int)r;
-    return (uint32_t)(q - lo);
-}
-
 // 16 values per lane: four 128-bit loads, one 32-bit store (4.06 bytes of HBM traffic per code).
 __global__ void __launch_bounds__(256)
 quantize_pack_vec16_kernel(const float4 *__restrict__ x, uint32_t *__restrict__ packed, int64_t groups16, float s,
@@ -76,9 +67,9 @@ quantize_pack_vec16_kernel(const float4 *__restrict__ x, uint32_t *__restrict__ 
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float4 v = x[4 * g + j];
-            const uint32_t byte = quantize_code(v.x, s, z, lo_f, hi_f, lo) | (quantize_code(v.y, s, z, lo_f, hi_f, lo) << 2) |
-                                  (quantize_code(v.z, s, z, lo_f, hi_f, lo) << 4) |
-                                  (quantize_code(v.w, s, z, lo_f, hi_f, lo) << 6);
+            const uint32_t byte = dg_quantize_code(v.x, s, z, lo_f, hi_f, lo) | (dg_quantize_code(v.y, s, z, lo_f, hi_f, lo) << 2) |
+                                  (dg_quantize_code(v.z, s, z, lo_f, hi_f, lo) << 4) |
+                                  (dg_quantize_code(v.w, s, z, lo_f, hi_f, lo) << 6);
             word |= byte << (8 * j);
         }
         packed[g] = word;
@@ -93,9 +84,9 @@ quantize_pack_bytes_kernel(const float *__restrict__ x, uint8_t *__restrict__ pa
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t g = first_group + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups4; g += stride) {
         const float *v = x + 4 * g;
-        packed[g] = (uint8_t)(quantize_code(v[0], s, z, lo_f, hi_f, lo) | (quantize_code(v[1], s, z, lo_f, hi_f, lo) << 2) |
-                              (quantize_code(v[2], s, z, lo_f, hi_f, lo) << 4) |
-                              (quantize_code(v[3], s, z, lo_f, hi_f, lo) << 6));
+        packed[g] = (uint8_t)(dg_quantize_code(v[0], s, z, lo_f, hi_f, lo) | (dg_quantize_code(v[1], s, z, lo_f, hi_f, lo) << 2) |
+                              (dg_quantize_code(v[2], s, z, lo_f, hi_f, lo) << 4) |
+                              (dg_quantize_code(v[3], s, z, lo_f, hi_f, lo) << 6));
     }
 }
 

@@ -382,6 +382,55 @@ def test_dequantize_equals_the_scale_epilogue():
     assert e.value.status == 2
 
 
+@pytest.mark.parametrize("plan", ["auto", "split", "1", "2", "4", "7", "2k2", "4k4"])
+def test_fused_layer_equals_convolution_then_quantise_pack(plan, monkeypatch):
+    """dg_conv2d_lut_requant against the oracle's convolution -> scale epilogue -> Eq. 1 quantiser -> packing, byte for
+    byte, on every plan of the one-hot kernels; and against the library's own two-call path."""
+    if plan != "auto":
+        monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
+    rng = np.random.default_rng(31)
+    for table in ("signed_unsigned", "extreme_i16"):
+        lw, la, entry = LEVELS[table]
+        if table == "extreme_i16" and "k" in plan:
+            continue
+        for (B, H, W, Cin, Cout, KH, KW, stride, pad) in [(2, 24, 24, 32, 68, 3, 3, (1, 1), (1, 1)),
+                                                          (1, 30, 30, 128, 40, 3, 3, (2, 2), (1, 1)),
+                                                          (3, 16, 16, 64, 36, 1, 1, (1, 1), (0, 0)),
+                                                          (1, 9, 9, 64, 128, 3, 3, (1, 1), (1, 1))]:
+            c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
+            case = GpuCase(c, levels=(lw, la), entry=entry)
+            acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
+            y = oracle.scale_epilogue_nhwc(acc, c.scale)
+            # a quantiser that spreads the outputs over all four codes, with exact ties among them
+            qs = np.float32(3.0 / max(1e-6, float(np.percentile(np.abs(y), 90))))
+            for qz, lo in ((np.float32(0.5), 0), (np.float32(0.0), -2)):
+                codes = oracle.quantize_codes(y, float(qs), float(qz), lo, lo + 3)
+                want = oracle.pack_codes(codes.reshape(-1, Cout))
+                got = dg.dg_conv2d_lut_requant(case.lut, case.Wp, case.Ap, case.desc, case.scale, float(qs), float(qz), lo,
+                                               variant="onehot_mfma")
+                torch.cuda.synchronize()
+                _assert_same(got.cpu().numpy().reshape(-1, Cout // 4), want, f"fused layer {(B, H, W, Cin, Cout)} {table} {plan}")
+                yf = case.run("onehot_mfma", scale=True)
+                two_calls = dg.dg_quantize_pack_activations(yf, yf.numel() // Cout, Cout, float(qs), float(qz), lo)
+                torch.cuda.synchronize()
+                assert torch.equal(got, two_calls)
+    # what it declines: other variants, Cout % 4 != 0, a small output buffer
+    c = wl.small_conv(1, 8, 8, 32, 6, 3, 3, (1, 1), (1, 1), seed=3, scale=True)
+    case = GpuCase(c)
+    with pytest.raises(dg.DgError) as e:
+        dg.dg_conv2d_lut_requant(case.lut, case.Wp, case.Ap, case.desc, case.scale, 1.0, 0.0, 0)
+    assert e.value.status == 2
+    c = wl.small_conv(1, 8, 8, 32, 8, 3, 3, (1, 1), (1, 1), seed=3, scale=True)
+    case = GpuCase(c)
+    with pytest.raises(dg.DgError) as e:
+        dg.dg_conv2d_lut_requant(case.lut, case.Wp, case.Ap, case.desc, case.scale, 1.0, 0.0, 0, variant="perm")
+    assert e.value.status == 5
+    with pytest.raises(dg.DgError) as e:
+        dg.dg_conv2d_lut_requant(case.lut, case.Wp, case.Ap, case.desc, case.scale, 1.0, 0.0, 0,
+                                 out=torch.empty(10, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 4
+
+
 def test_quantize_pack_feeds_the_convolution():
     # fp32 NHWC input -> quantise+pack -> table convolution, against oracle quantiser -> oracle convolution
     rng = np.random.default_rng(41)
