@@ -20,6 +20,9 @@ HIPCC_FLAGS = [
     "-Wall", "-Wextra", "-Wno-unused-parameter",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the binary32 decisions (Eq. 1: multiply, then add; binary32 tables: add by add) are defined operation by
+    # operation: no contraction into fused multiply-adds (hipcc's default is to contract)
+    "-ffp-contract=off",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

@@ -361,6 +361,29 @@ def test_quantize_pack_matches_oracle_quantiser_and_packing():
     _assert_same(got.reshape(9, 13), oracle.pack_codes(oracle.quantize_codes(x, 2.0, 0.5, -2, 1)), "unaligned quantize")
 
 
+def test_quantiser_is_not_fused_on_the_gpu():
+    """The multiply and the add of Eq. 1 are two binary32 roundings on both sides (see the pin of the same name in
+    test_oracle_pins.py): a compiler that contracts them into an FMA turns this code 2 into a 1."""
+    s, x, z = float(np.float32(1 + 2.0 ** -23)), np.float32(0.5 - 2.0 ** -23), 1.0
+    for count in (4, 16, 64, 4096 + 16 + 4):                   # byte path, vector path, both
+        xs = np.full((1, count), x, np.float32)
+        got = dg.dg_quantize_pack_activations(torch.from_numpy(xs).cuda(), 1, count, s, z, 0).cpu().numpy()
+        assert np.array_equal(got.reshape(1, -1), oracle.pack_codes(oracle.quantize_codes(xs, s, z, 0, 3)))
+        assert int(got[0]) == 0b10101010
+    # the same decision inside the fused layer: sums of exactly 1 (one product of 1, the rest 0), scale = x
+    Cin, Cout = 32, 8
+    Wc = np.zeros((Cout, 1, 1, Cin), np.uint8)
+    Xc = np.zeros((1, 4, 4, Cin), np.uint8)
+    Wc[..., 0] = 1
+    Xc[..., 0] = 1
+    lut = dg.dg_build_lut((0, 1, 2, 3), (0, 1, 2, 3))
+    Wp = dg.dg_pack_weights(torch.from_numpy(Wc).cuda(), Cout, Cin)
+    Xp = dg.dg_pack_activations(torch.from_numpy(Xc).cuda(), 16, Cin)
+    scale = torch.full((Cout,), float(x), dtype=torch.float32, device="cuda")
+    got = dg.dg_conv2d_lut_requant(lut, Wp, Xp, dg.conv_desc(1, 4, 4, Cin, Cout, 1, 1), scale, s, z, 0).cpu().numpy()
+    assert np.all(got == 0b10101010)
+
+
 def test_dequantize_equals_the_scale_epilogue():
     # int32 sums -> separate dequantise stage == oracle epilogue == the kernels' fused epilogue, bit for bit
     rng = np.random.default_rng(77)

@@ -494,3 +494,15 @@ def test_f32_table_with_integer_levels_equals_integer_oracle():
     t = oracle.build_lut_f32(lw.astype(np.float32), la.astype(np.float32))
     got = oracle.conv2d_table_f32(c.Wc, c.Ac, t, pad=(1, 1))
     assert np.array_equal(got, oracle.conv2d(c.Wc, c.Ac, lw, la, pad=(1, 1)).astype(np.float32))
+
+
+def test_quantiser_multiply_and_add_are_two_roundings():
+    """Eq. 1 decided in binary32 as one multiply, then one add: with s = 1 + 2^-23, x = 0.5 - 2^-23, z = 1 the product
+    0.5 - 2^-24 - 2^-46 rounds to 0.5 - 2^-24, the sum 1.5 - 2^-24 is a tie that rounds to 1.5, and rint(1.5) = 2;
+    a fused multiply-add would keep the 2^-46, round the sum down to 1.5 - 2^-23 and give 1."""
+    s, x, z = np.float32(1 + 2.0 ** -23), np.float32(0.5 - 2.0 ** -23), np.float32(1.0)
+    two_step = np.rint(np.float32(np.float32(s * x) + z))
+    fused = np.rint(np.float32(np.float64(s) * np.float64(x) + np.float64(z)))
+    assert two_step == 2.0 and fused == 1.0                      # the case does tell the two apart
+    codes = oracle.quantize_codes(np.full((1, 4), x, np.float32), float(s), float(z), 0, 3)
+    assert codes.tolist() == [[2, 2, 2, 2]]
