@@ -80,14 +80,19 @@ __device__ __forceinline__ void dg_mfma_store_block(const DgProblem &p, const dg
     const int r = lane & 31, h = lane >> 5;
     const int col = (TR ? mb : nb) + r;
     if (col >= (TR ? p.M : p.N)) return;
+    // The lane's 16 elements sit in one MFMA column at MFMA rows row0 + 8*(e/4) + e%4: one base address, then steps
+    // of the row stride (no multiply per element); a block wholly inside the output needs no row checks.
+    const int row0 = (TR ? nb : mb) + 4 * h, row_limit = TR ? p.N : p.M;
+    const int64_t row_stride = TR ? p.stride_cn : p.stride_cm, col_stride = TR ? p.stride_cm : p.stride_cn;
+    const int64_t base = (int64_t)col * col_stride + (int64_t)row0 * row_stride;
+    const bool inside = (TR ? nb : mb) + 32 <= row_limit;              // (uniform over the wavefront)
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-        const int row = (TR ? nb : mb) + 8 * (e / 4) + 4 * h + (e % 4);
-        if (row >= (TR ? p.N : p.M)) continue;
-        const int m = TR ? col : row, n = TR ? row : col;
-        const int64_t o = (int64_t)m * p.stride_cm + (int64_t)n * p.stride_cn;
+        const int k = 8 * (e / 4) + (e % 4);
+        if (!inside && row0 + k >= row_limit) continue;
+        const int64_t o = base + k * row_stride;
         if (p.scale)
-            p.Cf[o] = (float)acc[e] * (TR ? sc : p.scale[m]);
+            p.Cf[o] = (float)acc[e] * (TR ? sc : p.scale[row0 + k]);
         else
             p.C[o] = acc[e];
     }
