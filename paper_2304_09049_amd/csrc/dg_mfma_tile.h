@@ -44,9 +44,10 @@ __device__ __forceinline__ uint32_t dg_quad_or(uint32_t v)
 }
 
 // Re-quantising store of one block (TR layout only: the lanes of a quad hold four consecutive channels of one output
-// pixel).  Each lane turns its 16 sums into 2-bit codes; the codes of a quad's four channels are OR'd into the packed
-// byte across the quad; of every four consecutive pixels (accumulator registers 4q .. 4q+3) lane i of the quad keeps
-// and stores the byte of pixel i, so all lanes store.  Call with all 64 lanes active.
+// pixel).  Each lane turns its 16 sums into 2-bit codes.  For four consecutive pixels (accumulator registers 4q .. 4q+3)
+// a lane places its four codes in the four bytes of a word, at the bit position of its channel within the packed byte;
+// one OR across the quad (two DPP permutes) completes the four packed bytes in every lane, and lane i of the quad
+// stores the byte of pixel i -- so all lanes store.  Call with all 64 lanes active.
 __device__ __forceinline__ void dg_mfma_requant_block(const DgProblem &p, const dg_v16i &acc, int mb, int nb, int lane,
                                                       float sc)
 {
@@ -56,16 +57,15 @@ __device__ __forceinline__ void dg_mfma_requant_block(const DgProblem &p, const 
     const int64_t row_bytes = p.M / 4;
 #pragma unroll
     for (int e4 = 0; e4 < 4; ++e4) {
-        uint32_t mine = 0;
+        uint32_t word = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float y = __fmul_rn((float)acc[4 * e4 + i], sc);
-            const uint32_t code = live ? dg_quantize_code(y, p.q_scale, p.q_zero, lo_f, hi_f, p.q_lo) : 0u;
-            const uint32_t byte = dg_quad_or(code << (2 * q));
-            if (q == i) mine = byte;
+            word |= dg_quantize_code_clamped(y, p.q_scale, p.q_zero, lo_f, hi_f) << (8 * i);
         }
-        const int n = nb + 8 * e4 + 4 * h + q;            // the pixel whose byte this lane kept
-        if (live && n < p.N) p.Qp[(int64_t)n * row_bytes + (mb + r) / 4] = (uint8_t)mine;
+        word = dg_quad_or(live ? word << (2 * q) : 0u);   // byte i = the packed byte of pixel i
+        const int n = nb + 8 * e4 + 4 * h + q;            // the pixel whose byte this lane stores
+        if (live && n < p.N) p.Qp[(int64_t)n * row_bytes + (mb + r) / 4] = (uint8_t)(word >> (8 * q));
     }
 }
 
