@@ -157,8 +157,9 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  * A/B measurement:
  *   PERM     table rows held in registers, entries fetched with the byte-permute instruction
  *   LDS      table held in LDS, one indexed read per product (any shape the library accepts)
- *   MFMA_I8  NOT a table kernel: decodes codes to int8 levels and multiplies on the matrix cores;
- *            kept only as the measured comparison
+ *   MFMA_I8  NOT a table kernel: decodes codes to int8 levels and multiplies on the matrix cores (the
+ *            one-hot kernels' frame with the selection replaced by a multiply); the measured comparison.
+ *            Needs a table built from level vectors, 2-bit codes and Cin % 32 == 0
  *   SMALLN   table kernel for few activation rows: K split across lanes + wavefront reduction
  *   LUT65K   the paper's second table (Sec. 3 "LUT-65k"): one entry per (weight byte, activation byte) holding
  *            the dot product of the four code pairs, kept in LDS; one fetch per four products

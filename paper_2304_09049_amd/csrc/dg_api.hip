@@ -276,7 +276,7 @@ Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     switch (variant) {
     case DG_KERNEL_PERM: return dg_perm_supports(lut, p) ? Pick::Perm : Pick::Unsupported;
     case DG_KERNEL_LDS: return Pick::Lds;
-    case DG_KERNEL_MFMA_I8: return lut->separable && dg_mfma_supports(lut, p) ? Pick::Mfma : Pick::Unsupported;
+    case DG_KERNEL_MFMA_I8: return dg_decode_supports(lut, p) ? Pick::Mfma : Pick::Unsupported;
     case DG_KERNEL_SMALLN: return dg_smalln_supports(lut, p) ? Pick::SmallN : Pick::Unsupported;
     case DG_KERNEL_LUT65K: return dg_lut65k_supports(lut, p) ? Pick::Lut65k : Pick::Unsupported;
     case DG_KERNEL_ONEHOT_MFMA: return dg_onehot_supports(lut, p) ? Pick::OneHot : Pick::Unsupported;
@@ -300,7 +300,7 @@ dg_status run(const dg_lut *lut, const DgProblem &p, dg_kernel variant, hipStrea
     case Pick::Perm: return dg_launch_perm(lut, p, stream);
     case Pick::Lds: return dg_launch_lds(lut, p, stream);
     case Pick::LdsF32: return dg_launch_lds_f32(lut, p, stream);
-    case Pick::Mfma: return dg_launch_mfma(lut, p, stream);
+    case Pick::Mfma: return dg_launch_decode(lut, p, stream);
     case Pick::SmallN: return dg_launch_smalln(lut, p, stream);
     case Pick::Lut65k: return dg_launch_lut65k(lut, p, stream);
     case Pick::OneHot: return dg_launch_onehot(lut, p, stream);
@@ -317,7 +317,7 @@ const char *pick_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case Pick::Perm: return dg_perm_config_name(lut, p);
     case Pick::Lds: return "lds";
     case Pick::LdsF32: return "lds_f32";
-    case Pick::Mfma: return "mfma_i8";
+    case Pick::Mfma: return dg_decode_config_name(lut, p);
     case Pick::SmallN: return "smalln";
     case Pick::Lut65k: return "lut65k";
     case Pick::OneHot: return dg_onehot_config_name(lut, p);

@@ -62,8 +62,9 @@ dg_status dg_launch_lds_f32(const dg_lut *lut, const DgProblem &p, hipStream_t s
 bool dg_perm_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_perm(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 const char *dg_perm_config_name(const dg_lut *lut, const DgProblem &p);
-bool dg_mfma_supports(const dg_lut *lut, const DgProblem &p);
-dg_status dg_launch_mfma(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+bool dg_decode_supports(const dg_lut *lut, const DgProblem &p);
+dg_status dg_launch_decode(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+const char *dg_decode_config_name(const dg_lut *lut, const DgProblem &p);
 bool dg_lut65k_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_lut65k(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 bool dg_onehot_supports(const dg_lut *lut, const DgProblem &p);

@@ -1,0 +1,10 @@
+// Decode-and-multiply comparison kernels (2-bit codes to int8 levels, int8 MFMA), output stride-1 axis = n (row-major GEMM) or neither, 4 wavefronts sharing a tile.
+// (One translation unit per variant keeps build times even.)
+#include "dg_onehot_kernel.h"
+
+namespace dgoh {
+void unit_main_b0_t0_k4(const DgProblem &p, const Pools &pools, const Plan &q, int64_t wave_tiles, hipStream_t stream)
+{
+    launch_main<0, false, false, 4>(p, pools, q, wave_tiles, stream);
+}
+}   // namespace dgoh

@@ -20,6 +20,12 @@
 //   activations  of a constant holding a single 1 at byte v % 4, in the lower or upper permute source as v / 4 says
 // A filter tap outside the image, or a column beyond N, gets selector bytes 0x0C: it selects nothing.
 //
+// BITS = 0 is not a table kernel but the measured comparison, built in the same frame so that it has every advantage
+// the table kernels have (tiles, K sharing, split K, epilogues): tables that are outer products of level vectors make
+// the layer a plain int8 contraction, so the operands are the decoded levels themselves -- a dword of 4 positions is a
+// byte permute of the 4 weight (activation) levels, an MFMA step consumes a whole packed word (16 positions) per lane,
+// and the MFMA work is a quarter of the 2-bit one-hot kernel's.
+//
 // Entries beyond int8 (2-bit codes only): the table is split into two int8 planes, T = 256 * hi + lo with
 // lo = ((T + 128) mod 256) - 128, each selected into an accumulator of its own (the two planes take the places of the
 // tile's two weight row blocks, so a tile covers 32 rows instead of 64), and the result is 256 * acc_hi + acc_lo.
@@ -79,16 +85,17 @@ struct SplitArgs {
 
 template <int BITS>
 struct Fmt {
-    static constexpr int SLOT = BITS == 2 ? 2 : 4;             // bits per code slot in a packed byte
+    static constexpr bool DECODE = BITS == 0;                   // the decode-and-multiply comparison (2-bit codes)
+    static constexpr int SLOT = (BITS == 2 || DECODE) ? 2 : 4;  // bits per code slot in a packed byte
     static constexpr int PER_BYTE = 8 / SLOT;                  // codes per packed byte
-    static constexpr int SELS = 8 / SLOT;                      // selectors (of 4 positions) per 32-bit word
-    static constexpr int GROUPS = (1 << BITS) / 4;             // MFMA steps per selector: groups of 4 values
+    static constexpr int SELS = DECODE ? 1 : 8 / SLOT;         // selectors per 32-bit word (decode: the word itself)
+    static constexpr int GROUPS = DECODE ? 1 : (1 << BITS) / 4; // MFMA steps per selector: groups of 4 values
     static constexpr int STEPS = SELS * GROUPS;                // MFMA steps per 32-bit word
-    static constexpr uint32_t MASK = ((1u << BITS) - 1u) * 0x01010101u;
-    static constexpr int QW = (1 << BITS) / 4;                 // pool words per value
+    static constexpr uint32_t MASK = ((1u << (DECODE ? 2 : BITS)) - 1u) * 0x01010101u;
+    static constexpr int QW = DECODE ? 1 : (1 << BITS) / 4;    // pool words per value
     // rough VALU instruction counts of building one operand of one step (for the scheduling groups)
-    static constexpr int VALU_W = BITS == 4 ? 14 : 6;
-    static constexpr int VALU_A = BITS == 4 ? 7 : 6;
+    static constexpr int VALU_W = BITS == 4 ? 14 : (DECODE ? 11 : 6);
+    static constexpr int VALU_A = BITS == 4 ? 7 : (DECODE ? 15 : 6);
 };
 
 template <int CH>
@@ -124,6 +131,8 @@ template <int BITS>
 __device__ __forceinline__ Sel make_sel(uint32_t word, int j, bool valid)
 {
     typedef Fmt<BITS> F;
+    // decoding: the packed word and what to OR into its selectors (an invalid tap: word 0, every selector "zero byte")
+    if (F::DECODE) return Sel{valid ? word : 0u, valid ? 0u : NOTHING};
     const uint32_t raw = (word >> (F::SLOT * j)) & F::MASK;
     Sel s;
     if (BITS == 4) {
@@ -145,6 +154,11 @@ __device__ __forceinline__ v4i weight_operand(const Pools &pl, Sel s, int g, int
 {
     typedef Fmt<BITS> F;
     v4i r;
+    if (F::DECODE) {                                           // dword i: the levels of code i of the word's four bytes
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = (int)__builtin_amdgcn_perm(0u, pl.w[0], (s.lo >> (2 * i)) & 0x03030303u);
+        return r;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t *c = pl.w + 32 * plane + (4 * g + i) * F::QW;
@@ -162,9 +176,14 @@ __device__ __forceinline__ v4i weight_operand(const Pools &pl, Sel s, int g, int
 
 // the activation operand of value group g: [a(k) == 4g + i]
 template <int BITS>
-__device__ __forceinline__ v4i onehot_operand(Sel s, int g)
+__device__ __forceinline__ v4i onehot_operand(const Pools &pl, Sel s, int g)
 {
     v4i r;
+    if (Fmt<BITS>::DECODE) {                                   // the activation levels (pool word 1); invalid: zeros
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = (int)__builtin_amdgcn_perm(0u, pl.w[1], ((s.lo >> (2 * i)) & 0x03030303u) | s.hi);
+        return r;
+    }
     const uint32_t sel = (BITS == 4 && g >= 2) ? s.hi : s.lo;   // values 8..15 of 4-bit codes use the upper selector
     const bool upper = (g & 1) != 0;                            // values 4..7 (12..15): the permute's upper source
 #pragma unroll
@@ -213,6 +232,7 @@ onehot_mfma_kernel(Args a)
 {
     typedef Fmt<BITS> F;
     static_assert(!TWO || (WM == 2 && BITS == 2), "two planes stand in for the two weight row blocks of 2-bit tiles");
+    static_assert(BITS == 0 || BITS == 2 || BITS == 3 || BITS == 4, "code widths 2, 3, 4; 0 = the decode comparison");
     constexpr int RB = TWO ? 1 : WM;                       // weight row blocks of 32 rows
     constexpr int TPW = 4 / SKW;                           // tiles per workgroup
     constexpr int NB = RB * WN;                            // 32x32 output blocks per tile
@@ -318,7 +338,7 @@ onehot_mfma_kernel(Args a)
                 fa[buf][u] = weight_operand<BITS>(a.pools, sa[rb], g, plane);
             } else {
                 if (g == 0) sb[u - WM] = make_sel<BITS>(cb[u - WM].v[word], j, valid[u - WM]);
-                fb[buf][u - WM] = onehot_operand<BITS>(sb[u - WM], g);
+                fb[buf][u - WM] = onehot_operand<BITS>(a.pools, sb[u - WM], g);
             }
         };
 #pragma unroll
@@ -452,7 +472,7 @@ onehot_splitk_kernel(SplitArgs a)
                     const Sel sa = make_sel<BITS>(ca.v[word], j, true), sb = make_sel<BITS>(cb.v[word], j, valid);
 #pragma unroll
                     for (int g = 0; g < F::GROUPS; ++g) {
-                        const v4i fb = onehot_operand<BITS>(sb, g);
+                        const v4i fb = onehot_operand<BITS>(a.pools, sb, g);
                         acc = dg_mfma_step<TR>(weight_operand<BITS>(a.pools, sa, g, 0), fb, acc);
                         if (TWO) acc_hi = dg_mfma_step<TR>(weight_operand<BITS>(a.pools, sa, g, 1), fb, acc_hi);
                     }
@@ -499,11 +519,14 @@ onehot_splitk_kernel(SplitArgs a)
     }
 }
 
-// What runs a problem: the split-K kernel with S wavefronts per block, or the large-layer kernel with a 64 x (32*wn) tile.
+// What runs a problem: the split-K kernel with S wavefronts per block, or the large-layer kernel with a
+// (32*wm) x (32*wn) tile.
 struct Plan {
     int ch;          // 32-bit words of packed codes per lane half and chunk
     bool two;        // entries beyond int8: two int8 planes
+    bool decode;     // the decode-and-multiply comparison instead of a table kernel
     bool split;
+    int wm;          // 2; 1 with two planes; 4 for the comparison's 128 x 128 tile
     int wn;
     int skw;         // large-layer kernel: wavefronts sharing a tile (1, 2 or 4)
     int S, cpw, chunks;
@@ -546,13 +569,17 @@ void launch_main(const DgProblem &p, const Pools &pools, const Plan &q, int64_t 
     Args a;
     a.p = p;
     a.pools = pools;
-    a.tiles_m = TWO ? (p.M + 31) / 32 : (p.M + 63) / 64;
+    a.tiles_m = (p.M + q.wm * 32 - 1) / (q.wm * 32);
     a.wave_tiles = wave_tiles;
     a.div_ow = make_div((uint32_t)p.OW), a.div_oh = make_div((uint32_t)p.OH);
     a.div_cin = make_div((uint32_t)p.Cin), a.div_kw = make_div((uint32_t)p.KW);
     constexpr int TPW = 4 / SKW;
     const dim3 grid((unsigned)((wave_tiles + TPW - 1) / TPW));
-    if (q.wn == 7) {
+    if (q.wm == 4) {
+        // (decoding costs VALU work per operand, not per MFMA: only a 128 x 128 tile has enough MFMAs per operand for
+        // the matrix pipe to be the limit, so the comparison gets one)
+        if constexpr (BITS == 0 && SKW == 1) launch_ch<0, 4, 4, TR, false, 1>(a, q.ch, grid, stream);
+    } else if (q.wn == 7) {
         if constexpr (SKW != 2) launch_ch<BITS, 2, 7, TR, TWO, SKW>(a, q.ch, grid, stream);
     } else if (q.wn == 4) {
         launch_ch<BITS, 2, 4, TR, TWO, SKW>(a, q.ch, grid, stream);
@@ -590,7 +617,8 @@ void launch_split(const DgProblem &p, const Pools &pools, const Plan &q, int64_t
 
 // One translation unit per (code width, output layout, K share) instantiates these (the kernels are many: 4 tiles x
 // 3 chunk sizes each).  TR: the output axis with stride 1 goes on the MFMA columns (see dg_mfma_tile.h).
-// Unit "bBtTkK" defines unit_main_bB_tT_kK, and for K = 1 also unit_split_bB_tT; B = 22 stands for 2-bit codes in two planes.
+// Unit "bBtTkK" defines unit_main_bB_tT_kK, and for K = 1 also unit_split_bB_tT; B = 22 stands for 2-bit codes in two
+// planes, B = 0 for the decode-and-multiply comparison.
 typedef void (*MainFn)(const DgProblem &, const Pools &, const Plan &, int64_t, hipStream_t);
 #define DGOH_UNIT(B, T, K) \
     void unit_main_b##B##_t##T##_k##K(const DgProblem &, const Pools &, const Plan &, int64_t, hipStream_t);
@@ -598,8 +626,9 @@ typedef void (*MainFn)(const DgProblem &, const Pools &, const Plan &, int64_t, 
     void unit_split_b##B##_t##T(const DgProblem &, const Pools &, const Plan &, int64_t, hipStream_t);
 DGOH_UNIT(2, 0, 1) DGOH_UNIT(2, 0, 2) DGOH_UNIT(2, 0, 4) DGOH_UNIT(2, 1, 1) DGOH_UNIT(2, 1, 2) DGOH_UNIT(2, 1, 4)
 DGOH_UNIT(3, 0, 1) DGOH_UNIT(3, 1, 1) DGOH_UNIT(4, 0, 1) DGOH_UNIT(4, 1, 1) DGOH_UNIT(22, 0, 1) DGOH_UNIT(22, 1, 1)
+DGOH_UNIT(0, 0, 1) DGOH_UNIT(0, 0, 2) DGOH_UNIT(0, 0, 4) DGOH_UNIT(0, 1, 1) DGOH_UNIT(0, 1, 2) DGOH_UNIT(0, 1, 4)
 DGOH_UNIT_SPLIT(2, 0) DGOH_UNIT_SPLIT(2, 1) DGOH_UNIT_SPLIT(3, 0) DGOH_UNIT_SPLIT(3, 1) DGOH_UNIT_SPLIT(4, 0)
-DGOH_UNIT_SPLIT(4, 1) DGOH_UNIT_SPLIT(22, 0) DGOH_UNIT_SPLIT(22, 1)
+DGOH_UNIT_SPLIT(4, 1) DGOH_UNIT_SPLIT(22, 0) DGOH_UNIT_SPLIT(22, 1) DGOH_UNIT_SPLIT(0, 0) DGOH_UNIT_SPLIT(0, 1)
 #undef DGOH_UNIT
 #undef DGOH_UNIT_SPLIT
 

@@ -1,5 +1,5 @@
-// Host side of the one-hot matrix-core kernels (dg_onehot_kernel.h): which problems they take, which of their
-// shapes runs a given problem, and the launch.
+// Host side of the one-hot matrix-core kernels and of the decode-and-multiply comparison built in the same frame
+// (dg_onehot_kernel.h): which problems they take, which of their shapes runs a given problem, and the launch.
 #include <cstdlib>
 #include <cstring>
 
@@ -11,6 +11,14 @@ using dgoh::Plan;
 
 int per_byte(const dg_lut *lut) { return lut->bits == 2 ? 4 : 2; }
 
+// VALU and matrix-pipe cycles of one step of a decoding wavefront's tile, whichever is more: each operand costs about
+// 11 (weights) or 15 (activations, with the padding mask) instructions of 4 cycles, each MFMA 32 cycles
+double decode_step_cycles(int wm, int wn)
+{
+    const double valu = 4.0 * (11 * wm + 15 * wn), mfma = 32.0 * wm * wn;
+    return 1.08 * (valu > mfma ? valu : mfma);
+}
+
 int64_t tile_count(const DgProblem &p, int wm, int wn)
 {
     return ((int64_t)(p.M + wm * 32 - 1) / (wm * 32)) * (((int64_t)p.N + wn * 32 - 1) / (wn * 32));
@@ -18,11 +26,13 @@ int64_t tile_count(const DgProblem &p, int wm, int wn)
 
 bool fits_int8(const dg_lut *lut) { return lut->min_entry >= -128 && lut->max_entry <= 127; }
 
-Plan plan_for(const dg_lut *lut, const DgProblem &p)
+Plan plan_for(const dg_lut *lut, const DgProblem &p, bool decode)
 {
     Plan q;
-    q.two = !fits_int8(lut);                               // two int8 planes; a tile is then 32 rows high, not 64
+    q.decode = decode;
+    q.two = !decode && !fits_int8(lut);                    // two int8 planes; a tile is then 32 rows high, not 64
     const int wm = q.two ? 1 : 2;
+    q.wm = wm;
     // a lane half reads 4*ch packed bytes of one filter tap per chunk
     const int tap_bytes = p.Cin / per_byte(lut);
     q.ch = tap_bytes % 32 == 0 ? 4 : (tap_bytes % 16 == 0 ? 2 : 1);
@@ -48,13 +58,13 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p)
     // least-regret fit to timings of 78 layer shapes x 12 plans with 2-bit codes (the plan chosen is within 14 % of
     // the best measured one on each, 1.3 % on average); ties go to the wider, less shared plan.
     static const int widths[4] = {7, 4, 2, 1};
-    const bool can_share = lut->bits == 2 && !q.two;
+    const bool can_share = lut->bits == 2 && !q.two;       // (the comparison takes 2-bit codes only)
     // (the wider codes and two-plane tables, with 2 to 4 times the MFMA work per load, keep the constants of an earlier
     // fit without sharing, under which their measured times are better: 32 cycles per MFMA, 33 and 42 for the two
     // narrowest tiles, 3000 + 600 per block for prologue and stores)
     static const double fitted_cycles[4] = {37.7, 28.9, 29.5, 34.0}, plain_cycles[4] = {32.0, 32.0, 33.0, 42.0};
     const double *mfma_cycles = can_share ? fitted_cycles : plain_cycles;
-    const double steps = (double)p.K * (1 << lut->bits) / 32.0;
+    const double steps = decode ? p.K / 32.0 : (double)p.K * (1 << lut->bits) / 32.0;
     double best = 0.0;
     bool first = true;
     for (int i = 0; i < 4; ++i)
@@ -64,13 +74,19 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p)
             const int64_t per_simd = (tile_count(p, wm, wn) * skw + 1023) / 1024;
             const double lone = !can_share ? 1.0 : (per_simd == 1 ? 0.84 : (per_simd == 2 ? 0.78 : 1.0));   // (rounding up overstates short queues)
             double cost = (double)per_simd * 2 * wn * (steps / skw) * mfma_cycles[i] * lone;
+            if (decode) cost = (double)per_simd * (steps / skw) * decode_step_cycles(2, wn) * lone;
             cost += can_share ? 2670.0 + 350.0 * 2 * wn / skw : 3000.0 + 600.0 * 2 * wn;
             if (skw > 1) cost += 955.0 + 147.0 * 2 * wn;
             if (first || cost < best * 0.999) best = cost, q.wn = wn, q.skw = skw, first = false;
         }
+    if (decode && p.M > 64) {                              // the comparison's own 128 x 128 tile
+        const int64_t per_simd = (tile_count(p, 4, 4) + 1023) / 1024;
+        const double cost = (double)per_simd * steps * decode_step_cycles(4, 4) + 2670.0 + 350.0 * 16;
+        if (cost < best * 0.999) best = cost, q.wm = 4, q.wn = 4, q.skw = 1;
+    }
     if (can_share) {
         const int64_t per_simd = (blocks11 * split_S + 1023) / 1024;
-        const double cost = (double)per_simd * (steps * split_cpw / q.chunks) * 50.6 + 3370.0;
+        const double cost = (double)per_simd * (steps * split_cpw / q.chunks) * (decode ? decode_step_cycles(1, 1) : 50.6) + 3370.0;
         q.split = q.chunks > 1 && cost < best;
     } else {
         // other code widths and two-plane tables (not in the fit): split K when there are too few 64 x 32 tiles to give
@@ -78,20 +94,22 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p)
         const int64_t t21 = tile_count(p, wm, 1);
         q.split = (t21 < 512 || (t21 < 1024 && q.chunks >= 32)) && q.chunks > 1;
     }
-    // DG_ONEHOT_PLAN = split | <wn> | <wn>k<skw> (wn = 1, 2, 4, 7; skw = 1, 2, 4) overrides the choice (tuning, and
-    // tests that must reach every plan)
+    // DG_ONEHOT_PLAN = split | <wn> | <wn>k<skw> (wn = 1, 2, 4, 7; skw = 1, 2, 4) | 44 (the comparison's 128 x 128 tile)
+    // overrides the choice (tuning, and tests that must reach every plan)
     if (const char *force = getenv("DG_ONEHOT_PLAN")) {
         const int v = atoi(force);
         if (force[0] == 's') q.split = true;
+        else if (v == 44 && decode) q.split = false, q.wm = 4, q.wn = 4, q.skw = 1;
         else if (v == 1 || v == 2 || v == 4 || v == 7) {
             int k = 1;
             if (const char *at = strchr(force, 'k')) k = atoi(at + 1);
             q.split = false;
+            q.wm = wm;
             q.wn = v;
             q.skw = (can_share && (k == 2 || k == 4) && k <= q.chunks && !(v == 7 && k == 2)) ? k : 1;
         }
     }
-    if (q.split) q.cpw = split_cpw, q.S = split_S;
+    if (q.split) q.cpw = split_cpw, q.S = split_S, q.wm = wm;
     if (lut->bits == 4 && q.wn == 7) q.ch = 1;             // (the 2-word kernel of this tile is not built: see launch_ch)
     return q;
 }
@@ -104,7 +122,17 @@ bool dg_onehot_supports(const dg_lut *lut, const DgProblem &p)
     // MFMA operands are int8: wider entries take two planes, T = 256 * hi + lo (2-bit codes only, hi within int8)
     if (!fits_int8(lut) && (lut->bits != 2 || lut->max_entry > 127 * 256 + 127)) return false;
     if (p.Cin % (8 * per_byte(lut)) != 0) return false;                // a lane half reads whole words of one tap
-    const Plan q = plan_for(lut, p);
+    const Plan q = plan_for(lut, p, false);
+    if ((uintptr_t)p.Wp % (4 * q.ch) != 0 || (uintptr_t)p.Xp % (4 * q.ch) != 0) return false;
+    return true;
+}
+
+bool dg_decode_supports(const dg_lut *lut, const DgProblem &p)
+{
+    // the levels themselves are the MFMA operands: the table must be their outer product, with 2-bit codes
+    if (lut->dtype == DG_LUT_F32 || !lut->separable || lut->bits != 2) return false;
+    if (p.Cin % 32 != 0) return false;                                 // a lane half reads whole words of one tap
+    const Plan q = plan_for(lut, p, true);
     if ((uintptr_t)p.Wp % (4 * q.ch) != 0 || (uintptr_t)p.Xp % (4 * q.ch) != 0) return false;
     return true;
 }
@@ -126,16 +154,58 @@ const char *dg_onehot_config_name(const dg_lut *lut, const DgProblem &p)
          {"onehot_mfma_64x224_k4", "onehot_mfma_64x128_k4", "onehot_mfma_64x64_k4", "onehot_mfma_64x32_k4"}},
         {{"onehot_mfma_2p_32x224", "onehot_mfma_2p_32x128", "onehot_mfma_2p_32x64", "onehot_mfma_2p_32x32"},
          {"", "", "", ""}, {"", "", "", ""}}};
-    const Plan q = plan_for(lut, p);
+    const Plan q = plan_for(lut, p, false);
     if (q.split) return split_names[q.two][q.S];
     return tile_names[q.two][q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)][q.wn == 7 ? 0 : (q.wn == 4 ? 1 : (q.wn == 2 ? 2 : 3))];
+}
+
+const char *dg_decode_config_name(const dg_lut *lut, const DgProblem &p)
+{
+    static const char *const split_names[17] = {
+        "", "mfma_i8_splitk_s1", "mfma_i8_splitk_s2", "mfma_i8_splitk_s3", "mfma_i8_splitk_s4", "mfma_i8_splitk_s5",
+        "mfma_i8_splitk_s6", "mfma_i8_splitk_s7", "mfma_i8_splitk_s8", "mfma_i8_splitk_s9", "mfma_i8_splitk_s10",
+        "mfma_i8_splitk_s11", "mfma_i8_splitk_s12", "mfma_i8_splitk_s13", "mfma_i8_splitk_s14", "mfma_i8_splitk_s15",
+        "mfma_i8_splitk_s16"};
+    static const char *const tile_names[3][4] = {
+        {"mfma_i8_64x224", "mfma_i8_64x128", "mfma_i8_64x64", "mfma_i8_64x32"},
+        {"", "mfma_i8_64x128_k2", "mfma_i8_64x64_k2", "mfma_i8_64x32_k2"},
+        {"mfma_i8_64x224_k4", "mfma_i8_64x128_k4", "mfma_i8_64x64_k4", "mfma_i8_64x32_k4"}};
+    const Plan q = plan_for(lut, p, true);
+    if (q.split) return split_names[q.S];
+    if (q.wm == 4) return "mfma_i8_128x128";
+    return tile_names[q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)][q.wn == 7 ? 0 : (q.wn == 4 ? 1 : (q.wn == 2 ? 2 : 3))];
+}
+
+dg_status dg_launch_decode(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
+{
+    const Plan q = plan_for(lut, p, true);
+    dgoh::Pools pools;
+    for (int i = 0; i < 64; ++i) pools.w[i] = 0;
+    for (int c = 0; c < 4; ++c) {                          // the two level vectors as byte-permute pools
+        pools.w[0] |= (uint32_t)(uint8_t)lut->levels_w[c] << (8 * c);
+        pools.w[1] |= (uint32_t)(uint8_t)lut->levels_a[c] << (8 * c);
+    }
+    const int64_t blocks11 = tile_count(p, 1, 1), wave_tiles = tile_count(p, q.wm, q.wn);
+    if ((q.split ? blocks11 : wave_tiles) > INT32_MAX)
+        return dg_fail(DG_ERR_UNSUPPORTED, "decode-and-multiply kernel: too many tiles for one grid");
+    const int tr = (p.stride_cm == 1 && p.stride_cn != 1) ? 1 : 0;
+    using namespace dgoh;
+    static const MainFn split_units[2] = {unit_split_b0_t0, unit_split_b0_t1};
+    static const MainFn main_units[3][2] = {{unit_main_b0_t0_k1, unit_main_b0_t1_k1}, {unit_main_b0_t0_k2, unit_main_b0_t1_k2},
+                                            {unit_main_b0_t0_k4, unit_main_b0_t1_k4}};
+    if (q.split) {
+        split_units[tr](p, pools, q, blocks11, stream);
+        return dg_check_launch("onehot_splitk_kernel<0>");
+    }
+    main_units[q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)][tr](p, pools, q, wave_tiles, stream);
+    return dg_check_launch("onehot_mfma_kernel<0>");
 }
 
 dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
 {
     // column v of the table, 4 weight codes per word: the permute pools.  Entries beyond int8 go in two planes,
     // T = 256 * hi + lo with lo in [-128, 127] (so hi is within [-128, 128) for every int16 T).
-    const Plan q = plan_for(lut, p);
+    const Plan q = plan_for(lut, p, false);
     dgoh::Pools pools;
     const int L = 1 << lut->bits, qw = L / 4;
     for (int i = 0; i < 64; ++i) pools.w[i] = 0;

@@ -177,7 +177,9 @@ def test_kernel_names_need_no_gpu():
     assert dg.dg_gemm_kernel_name(lut, 8192, 1, 8192) == "smalln"
     assert dg.dg_gemm_kernel_name(lut, 64, 196, 48).startswith("perm")        # Cin % 32 != 0, % 16 == 0
     assert dg.dg_gemm_kernel_name(lut, 5, 7, 12) == "lds"                      # Cin % 16 != 0
-    assert dg.dg_gemm_kernel_name(lut, 64, 196, 576, "mfma_i8") == "mfma_i8"
+    # the comparison kernel has the same plans, and a 128 x 128 tile of its own for the largest problems
+    assert dg.dg_gemm_kernel_name(lut, 64, 196, 576, "mfma_i8").startswith("mfma_i8_splitk_s")
+    assert dg.dg_gemm_kernel_name(lut, 8192, 8192, 8192, "mfma_i8") == "mfma_i8_128x128"
     wide = dg.dg_build_lut((127, -128, 5, 0), (-128, 127, 1, 0), dg.DG_LUT_I16)
     assert dg.dg_gemm_kernel_name(wide, 8192, 8192, 8192) == "onehot_mfma_2p_32x128"
     t4 = dg.dg_build_lut_bits(4, list(range(-8, 8)), list(range(16)), dg.DG_LUT_I8)

@@ -127,21 +127,31 @@ ONEHOT_PLANS = {"split": "onehot_mfma_splitk_s", "1": "onehot_mfma_64x32", "2": 
                 # 2 or 4 wavefronts sharing a tile and splitting K
                 "1k2": "onehot_mfma_64x32_k2", "1k4": "onehot_mfma_64x32_k4", "2k2": "onehot_mfma_64x64_k2",
                 "2k4": "onehot_mfma_64x64_k4", "4k2": "onehot_mfma_64x128_k2", "4k4": "onehot_mfma_64x128_k4",
-                "7k4": "onehot_mfma_64x224_k4"}
+                "7k4": "onehot_mfma_64x224_k4",
+                # the decode-and-multiply comparison's own 128 x 128 tile
+                "44": "mfma_i8_128x128"}
 
 
-@pytest.mark.parametrize("table", ["signed_unsigned", "extreme_i16"])
+@pytest.mark.parametrize("table", ["signed_unsigned", "extreme_i16", "decode"])
 @pytest.mark.parametrize("plan", sorted(ONEHOT_PLANS))
 def test_onehot_every_plan(plan, table, monkeypatch):
     """Every wave tile of the one-hot matrix-core kernel and its split-K form, forced on shapes with ragged edges in
     M and N (the library picks among them by a cost model that small test shapes would never move off one plan):
     GEMM with row-major and column-major output, convolution with padding and stride, int32 and scaled fp32 output.
-    Once with an int8 table (one plane) and once with entries up to 16384 (two int8 planes)."""
-    if "k" in plan and table != "signed_unsigned":
+    Once with an int8 table (one plane), once with entries up to 16384 (two int8 planes), and once as the
+    decode-and-multiply comparison kernel, which is built in the same frame and has the same plans."""
+    if "k" in plan and table == "extreme_i16":
         pytest.skip("tiles are shared only by the one-plane kernels")
+    if plan == "44" and table != "decode":
+        pytest.skip("only the comparison kernel has the 128 x 128 tile")
     monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
-    glw, gla, gentry = LEVELS[table]
-    prefix = ONEHOT_PLANS[plan] if table == "signed_unsigned" else ONEHOT_PLANS[plan].replace("onehot_mfma_", "onehot_mfma_2p_").replace("_64x", "_32x")
+    glw, gla, gentry = LEVELS["extreme_i16" if table == "decode" else table]
+    kernel = "mfma_i8" if table == "decode" else "onehot_mfma"
+    prefix = ONEHOT_PLANS[plan]
+    if table == "extreme_i16":
+        prefix = prefix.replace("onehot_mfma_", "onehot_mfma_2p_").replace("_64x", "_32x")
+    if table == "decode":
+        prefix = prefix.replace("onehot_mfma_", "mfma_i8_")
 
     def right_kernel(name, chunks):
         if plan == "split":
@@ -153,11 +163,11 @@ def test_onehot_every_plan(plan, table, monkeypatch):
     for (M, N, K) in [(70, 1000, 96), (130, 777, 64), (64, 300, 256), (33, 250, 1024)]:
         inp = wl.small_gemm(M, N, K, seed=M + N + K)
         case = GpuCase(inp, levels=(glw, gla), entry=gentry)
-        assert right_kernel(case.kernel_name("onehot_mfma"), K // (128 if K % 128 == 0 else (64 if K % 64 == 0 else 32)))
+        assert right_kernel(case.kernel_name(kernel), K // (128 if K % 128 == 0 else (64 if K % 64 == 0 else 32)))
         want = oracle.gemm(inp.Wc, inp.Ac, glw, gla)
-        _assert_same(case.run("onehot_mfma").cpu().numpy(), want, f"gemm {(M, N, K)} plan {plan}")
+        _assert_same(case.run(kernel).cpu().numpy(), want, f"gemm {(M, N, K)} plan {plan}")
         out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
-        dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant="onehot_mfma", strides=(1, M))
+        dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant=kernel, strides=(1, M))
         torch.cuda.synchronize()
         _assert_same(out.cpu().numpy(), want.T.copy(), f"gemm {(M, N, K)} column-major plan {plan}")
     # no zero activation level: padding must still add 0
@@ -168,11 +178,11 @@ def test_onehot_every_plan(plan, table, monkeypatch):
                                                       (1, 20, 20, 64, 96, 5, 5, (1, 1), (2, 2))]:
         c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
         case = GpuCase(c, levels=(lw, la), entry=entry)
-        assert right_kernel(case.kernel_name("onehot_mfma"),
+        assert right_kernel(case.kernel_name(kernel),
                             KH * KW * Cin // (128 if Cin % 128 == 0 else (64 if Cin % 64 == 0 else 32)))
         acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
-        _assert_same(case.run("onehot_mfma").cpu().numpy(), acc, f"conv {(B, H, W, Cin, Cout)} plan {plan}")
-        got = case.run("onehot_mfma", scale=True).cpu().numpy()
+        _assert_same(case.run(kernel).cpu().numpy(), acc, f"conv {(B, H, W, Cin, Cout)} plan {plan}")
+        got = case.run(kernel, scale=True).cpu().numpy()
         assert np.array_equal(got, oracle.scale_epilogue_nhwc(acc, c.scale)), f"scaled conv plan {plan}"
 
 
