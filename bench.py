@@ -38,6 +38,7 @@ PERM_ALU_PEAK_TOPS = VALU_LANE_INSTR_PER_S * (4 / 1.5) * 2 / 1e12
 MEASURED_TRAFFIC_KIB = {
     ("resnet18_conv3x3_b1", "onehot_mfma_splitk_s9"): (230.7 * 2.0, 784.0),
     ("vgg16_conv3x3_b16", "onehot_mfma_64x128"): (4607.8 * 2.0, 50176.0),
+    ("vgg16_conv3x3_b16", "onehot_smfmac_64x128"): (4430.8 * 2.0, 50176.0),
     ("gemm_8192x1x8192_i16", "smalln"): (8251.9 * 2.0, 32.0),
 }
 
@@ -53,7 +54,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default=None, help="name in workloads.CONFIGS (default: the headline conv)")
-    ap.add_argument("--variant", default="auto", help="auto | perm | lds | mfma_i8 | smalln | lut65k | onehot_mfma")
+    ap.add_argument("--variant", default="auto", help="auto | perm | lds | mfma_i8 | smalln | lut65k | onehot_mfma | onehot_smfmac")
     ap.add_argument("--no-graph", action="store_true", help="launch every step from the host instead of a HIP graph")
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-workload kernel sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -193,10 +194,14 @@ def single_launch_us(torch, fn):
 
 
 def mfma_ops_factor(name):
-    """int8 MFMA operations issued per effective operation: the one-hot kernel contracts over 4K (one operand byte per
-    table column), the decode-and-multiply comparison kernel over K; table kernels on the VALU issue none."""
+    """int8 multiply-accumulates the matrix cores perform per effective operation: the one-hot kernel contracts over 4K
+    (one operand byte per table column); on the sparse instruction, which skips the half of them that its index says
+    are zero, over 2K (so it too is priced against the DENSE peak); the decode-and-multiply comparison kernel over K;
+    table kernels on the VALU issue none."""
     if name.startswith("onehot_mfma"):
         return 4
+    if name.startswith("onehot_smfmac"):
+        return 2
     if name.startswith("mfma_i8"):
         return 1
     return None
@@ -230,8 +235,8 @@ def roofline_object(w, ms, name):
         return {"bound": "mfma", "achieved": round(ach, 3), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TFLOP/s",
                 "frac": round(ach / INT8_MFMA_PEAK_TOPS, 5), "traffic": measured_traffic(w, name), "kernel": name,
                 "algorithmic_bytes": w.algorithmic_bytes, "effective_tops": round(w.ops / (ms * 1e-3) / 1e12, 3),
-                "note": f"int8 MFMA operations issued = {f} x 2MNK (one-hot selection contracts over 4K); "
-                        "integer TOP/s against the dense int8 peak"}
+                "note": f"int8 MFMA operations performed = {f} x 2MNK (one-hot selection contracts over 4K, the sparse "
+                        "instruction performs half of them); integer TOP/s against the dense int8 peak"}
     if t_hbm >= t_alu:
         ach = w.algorithmic_bytes / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -444,13 +449,15 @@ def main():
         sweep = []
         for wname, ww in wl.CONFIGS.items():
             rr = r if ww is w else Runner(ww, "auto")
-            for variant in ("auto", "perm", "mfma_i8", "lut65k", "lds"):
+            for variant in ("auto", "onehot_mfma", "onehot_smfmac", "perm", "mfma_i8", "lut65k", "lds"):
                 if variant in ("lds", "lut65k") and ww.ops > 1e11:
                     continue
                 try:
                     kname = rr.kernel_name(variant)
                     if kname == "unsupported":
                         continue
+                    if variant != "auto" and kname == rr.kernel_name("auto"):
+                        continue                     # (already timed as AUTO's choice)
                     fn = lambda v=variant, q=rr: q.kernel(v)
                     ms = time_steady(torch, fn, use_graph)
                     rep = kernel_report(ww, ms, kname)

@@ -167,6 +167,11 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *            code, i.e. it selects one entry of the weight code's table row; any int8 entries, 2-, 3- or 4-bit
  *            codes (2^bits times the MFMA work of a plain int8 product); 2-bit tables with wider entries (up to
  *            32639) are selected from two int8 planes; needs Cin % 32 == 0 (2-bit) or % 16 (3-, 4-bit)
+ *   ONEHOT_SMFMAC  the same selection on the sparse matrix instruction, at half the matrix work: a one-hot run
+ *            of four bytes is 1-of-4 sparse, so the activation operand is a constant and its index register
+ *            is the packed code word itself -- the instruction's index multiplexer does the table lookup;
+ *            2-bit codes, int8 entries, Cin % 32 == 0; outputs whose stride-1 axis is the channel axis
+ *            (NHWC), or plain GEMMs without scale (run transposed)
  * A variant that cannot run the given shape or table returns DG_ERR_UNSUPPORTED.
  */
 typedef enum {
@@ -176,7 +181,8 @@ typedef enum {
     DG_KERNEL_MFMA_I8 = 3,
     DG_KERNEL_SMALLN = 4,
     DG_KERNEL_LUT65K = 5,
-    DG_KERNEL_ONEHOT_MFMA = 6
+    DG_KERNEL_ONEHOT_MFMA = 6,
+    DG_KERNEL_ONEHOT_SMFMAC = 7
 } dg_kernel;
 
 /*

@@ -19,9 +19,10 @@ STATUS_NAMES = ("DG_OK", "DG_ERR_NULL", "DG_ERR_SHAPE", "DG_ERR_RANGE", "DG_ERR_
 DG_LUT_I8, DG_LUT_I16, DG_LUT_F32 = 0, 1, 2
 DG_KERNEL_AUTO, DG_KERNEL_PERM, DG_KERNEL_LDS, DG_KERNEL_MFMA_I8, DG_KERNEL_SMALLN, DG_KERNEL_LUT65K = 0, 1, 2, 3, 4, 5
 DG_KERNEL_ONEHOT_MFMA = 6
+DG_KERNEL_ONEHOT_SMFMAC = 7
 KERNELS = {"auto": DG_KERNEL_AUTO, "perm": DG_KERNEL_PERM, "lds": DG_KERNEL_LDS,
            "mfma_i8": DG_KERNEL_MFMA_I8, "smalln": DG_KERNEL_SMALLN, "lut65k": DG_KERNEL_LUT65K,
-           "onehot_mfma": DG_KERNEL_ONEHOT_MFMA}
+           "onehot_mfma": DG_KERNEL_ONEHOT_MFMA, "onehot_smfmac": DG_KERNEL_ONEHOT_SMFMAC}
 
 # every symbol include/deepgemm_hip.h declares
 EXPORTS = (

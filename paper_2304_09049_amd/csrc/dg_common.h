@@ -70,5 +70,9 @@ dg_status dg_launch_lut65k(const dg_lut *lut, const DgProblem &p, hipStream_t st
 bool dg_onehot_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 const char *dg_onehot_config_name(const dg_lut *lut, const DgProblem &p);
+bool dg_sparse_supports(const dg_lut *lut, const DgProblem &p);
+bool dg_sparse_preferred(const dg_lut *lut, const DgProblem &p);     // AUTO's choice between the two one-hot kernels
+dg_status dg_launch_sparse(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+const char *dg_sparse_config_name(const dg_lut *lut, const DgProblem &p);
 bool dg_smalln_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_smalln(const dg_lut *lut, const DgProblem &p, hipStream_t stream);

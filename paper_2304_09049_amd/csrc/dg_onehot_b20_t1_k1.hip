@@ -1,0 +1,15 @@
+// 2-bit table kernels on the sparse matrix instruction (activations on the MFMA rows: output stride-1 axis = m).
+// (One translation unit per variant keeps build times even.)
+#include "dg_onehot_kernel.h"
+
+namespace dgoh {
+void unit_main_b20_t1_k1(const DgProblem &p, const Pools &pools, const Plan &q, int64_t wave_tiles, hipStream_t stream)
+{
+    launch_main<20, true, false, 1>(p, pools, q, wave_tiles, stream);
+}
+
+void unit_split_b20_t1(const DgProblem &p, const Pools &pools, const Plan &q, int64_t blocks11, hipStream_t stream)
+{
+    launch_split<20, true, false>(p, pools, q, blocks11, stream);
+}
+}   // namespace dgoh

@@ -26,6 +26,19 @@
 // byte permute of the 4 weight (activation) levels, an MFMA step consumes a whole packed word (16 positions) per lane,
 // and the MFMA work is a quarter of the 2-bit one-hot kernel's.
 //
+// BITS = 20 is the 2-bit table kernel on the SPARSE matrix instruction (v_smfmac_i32_32x32x64_i8), at half the matrix
+// work.  A one-hot run of 4 bytes is 1-of-4 sparse, and that instruction takes one operand as two kept bytes out of
+// every four plus their 2-bit positions -- which, for a one-hot run, are the constant bytes (1, 0) and the CODE itself.
+// So the activation operand needs no expansion at all: its values are a constant, its index register is the packed
+// word masked to every other code ((word >> 2s) & 0x33333333 for the even / odd codes), and the hardware's index
+// multiplexer performs the table lookup: it picks, out of the 4 bytes T[w(k)][0..3] that the dense operand holds for a
+// position, the entry of the activation code.  The dense operand is a dword per position, the table ROW of the weight
+// code, fetched from a 16-entry table of row pairs in LDS (one 8-byte read serves two positions, without bank
+// conflicts).  One instruction covers 16 positions per lane pair in the time the dense MFMA takes for 8.
+// Layout of that instruction (measured): with A the sparse operand (rows), lane (row, h) holds kept bytes j = 0..15
+// and 2-bit fields j of its index register; byte j multiplies byte 16h + 4((j % 8) / 2) + field_j of the dense lane
+// (column, j / 8).  The accumulator layout is the dense instruction's.
+//
 // Entries beyond int8 (2-bit codes only): the table is split into two int8 planes, T = 256 * hi + lo with
 // lo = ((T + 128) mod 256) - 128, each selected into an accumulator of its own (the two planes take the places of the
 // tile's two weight row blocks, so a tile covers 32 rows instead of 64), and the result is 256 * acc_hi + acc_lo.
@@ -86,7 +99,8 @@ struct SplitArgs {
 template <int BITS>
 struct Fmt {
     static constexpr bool DECODE = BITS == 0;                   // the decode-and-multiply comparison (2-bit codes)
-    static constexpr int SLOT = (BITS == 2 || DECODE) ? 2 : 4;  // bits per code slot in a packed byte
+    static constexpr bool SPARSE = BITS == 20;                  // 2-bit codes selected by the sparse MFMA's index
+    static constexpr int SLOT = (BITS == 2 || DECODE || SPARSE) ? 2 : 4;  // bits per code slot in a packed byte
     static constexpr int PER_BYTE = 8 / SLOT;                  // codes per packed byte
     static constexpr int SELS = DECODE ? 1 : 8 / SLOT;         // selectors per 32-bit word (decode: the word itself)
     static constexpr int GROUPS = DECODE ? 1 : (1 << BITS) / 4; // MFMA steps per selector: groups of 4 values
@@ -200,6 +214,37 @@ __device__ __forceinline__ void sched_valu()
     __builtin_amdgcn_sched_group_barrier(0x002, N, 0);
 }
 
+typedef int v8i __attribute__((ext_vector_type(8)));
+
+// Sparse-instruction form (BITS = 20).  Per wavefront, 16 entries of 8 bytes in LDS: entry (c0 | c1 << 2) holds the
+// table rows of weight codes c0 and c1, row w = bytes T[w][0..3] (pool words 0..3).  A wavefront writes and reads only
+// its own copy, so no barrier is involved (LDS operations of one wavefront execute in order).
+__device__ __forceinline__ void sparse_fill_rows(uint2 *rows, const Pools &pl, int lane)
+{
+    if (lane < 16) {
+        const int c0 = lane & 3, c1 = lane >> 2;
+        const uint32_t r0 = c0 == 0 ? pl.w[0] : (c0 == 1 ? pl.w[1] : (c0 == 2 ? pl.w[2] : pl.w[3]));
+        const uint32_t r1 = c1 == 0 ? pl.w[0] : (c1 == 1 ? pl.w[1] : (c1 == 2 ? pl.w[2] : pl.w[3]));
+        rows[lane] = make_uint2(r0, r1);
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// The dense operands of the two instructions (even codes, odd codes) that consume one packed word per lane half.  `w` is
+// the weight row's word at the positions of lane half hp's activation word; this lane supplies the rows of its codes
+// 8*half .. 8*half+7 (the 16-bit half `shift / 16` of the word) as dwords 4*hp .. 4*hp+3 of the two operands: the even
+// codes to `even`, the odd ones to `odd` (see the layout above).  Two codes two apart are first brought together as a
+// 4-bit table index, so that one 8-byte read fills two consecutive operand registers.
+__device__ __forceinline__ void sparse_dense_half(const uint2 *rows, uint32_t w, int shift, int hp, v8i &even, v8i &odd)
+{
+    const uint32_t v = w >> shift, t = v >> 2;
+    const uint32_t e = (v & 0x0303u) | (t & 0x0C0Cu);            // byte b: codes 4b and 4b+2
+    const uint32_t o = (t & 0x0303u) | ((v >> 4) & 0x0C0Cu);     // byte b: codes 4b+1 and 4b+3
+    const uint2 e0 = rows[e & 15u], e1 = rows[(e >> 8) & 15u], o0 = rows[o & 15u], o1 = rows[(o >> 8) & 15u];
+    even[4 * hp] = (int)e0.x, even[4 * hp + 1] = (int)e0.y, even[4 * hp + 2] = (int)e1.x, even[4 * hp + 3] = (int)e1.y;
+    odd[4 * hp] = (int)o0.x, odd[4 * hp + 1] = (int)o0.y, odd[4 * hp + 2] = (int)o1.x, odd[4 * hp + 3] = (int)o1.y;
+}
+
 // Position bookkeeping shared by the two kernels: output column n -> image coordinates, and the filter tap of a chunk.
 struct Column {
     bool ok;
@@ -232,8 +277,12 @@ onehot_mfma_kernel(Args a)
 {
     typedef Fmt<BITS> F;
     static_assert(!TWO || (WM == 2 && BITS == 2), "two planes stand in for the two weight row blocks of 2-bit tiles");
-    static_assert(BITS == 0 || BITS == 2 || BITS == 3 || BITS == 4, "code widths 2, 3, 4; 0 = the decode comparison");
+    static_assert(BITS == 0 || BITS == 2 || BITS == 3 || BITS == 4 || BITS == 20,
+                  "code widths 2, 3, 4; 0 = the decode comparison; 20 = 2-bit codes on the sparse instruction");
+    static_assert(!F::SPARSE || (TR && !TWO), "the sparse operand is the MFMA's row operand: activations on the rows");
     constexpr int RB = TWO ? 1 : WM;                       // weight row blocks of 32 rows
+    constexpr int WRUNS = F::SPARSE ? 2 : 1;               // runs of CH words a weight lane reads: its half's, or both
+    __shared__ uint2 s_rows[F::SPARSE ? 4 * 16 : 1];
     constexpr int TPW = 4 / SKW;                           // tiles per workgroup
     constexpr int NB = RB * WN;                            // 32x32 output blocks per tile
     extern __shared__ int32_t s_acc[];                      // SKW > 1: [TPW][NB][16][64] sums
@@ -243,6 +292,7 @@ onehot_mfma_kernel(Args a)
     const int64_t my_tile = (int64_t)blockIdx.x * TPW + tw;
     const bool active = my_tile < a.wave_tiles;
     if (SKW == 1 && !active) return;                       // whole waves leave; there is no barrier on this path
+    if (F::SPARSE) sparse_fill_rows(s_rows + 16 * w4, a.pools, lane);
     const int64_t wave_tile = active ? my_tile : 0;        // (an idle wavefront of a shared workgroup adds zeros)
     if (SKW > 1)
         for (int i = threadIdx.x; i < TPW * NB * 1024; i += 256) s_acc[i] = 0;
@@ -260,7 +310,7 @@ onehot_mfma_kernel(Args a)
     for (int bm = 0; bm < RB; ++bm) {
         int m = m0 + bm * 32 + r;
         if (m >= p.M) m = p.M - 1;
-        w_ptr[bm] = p.Wp + (int64_t)m * (p.K / F::PER_BYTE) + h * (4 * CH);
+        w_ptr[bm] = p.Wp + (int64_t)m * (p.K / F::PER_BYTE) + (F::SPARSE ? 0 : h * (4 * CH));
     }
     Column col[WN];
 #pragma unroll
@@ -284,12 +334,15 @@ onehot_mfma_kernel(Args a)
         kw = tap - kh * p.KW;
         ci = pos - tap * p.Cin;
     }
-    Words<CH> wa[RB], wb[WN];
+    Words<CH> wa[RB][WRUNS], wb[WN];
     bool vb[WN];
     auto fetch = [&](int chunk) {                            // `chunk` is clamped: a fetch past the share is unused
         const int cw = min(chunk, chunks - 1);
 #pragma unroll
-        for (int bm = 0; bm < RB; ++bm) wa[bm] = load_words<CH>(w_ptr[bm] + (int64_t)cw * (8 * CH));
+        for (int bm = 0; bm < RB; ++bm)
+#pragma unroll
+            for (int run = 0; run < WRUNS; ++run)
+                wa[bm][run] = load_words<CH>(w_ptr[bm] + (int64_t)cw * (8 * CH) + run * (4 * CH));
         const int64_t tap_off = ((int64_t)kh * p.W + kw) * cq + ci / F::PER_BYTE;
 #pragma unroll
         for (int bn = 0; bn < WN; ++bn) {
@@ -314,16 +367,66 @@ onehot_mfma_kernel(Args a)
     // this barrier (it waits for LDS only)
     if (SKW > 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     for (int c = c0; c < c1; ++c) {
-        Words<CH> ca[RB], cb[WN];
+        Words<CH> ca[RB], ca1[RB], cb[WN];
         bool valid[WN];
 #pragma unroll
-        for (int bm = 0; bm < RB; ++bm) ca[bm] = wa[bm];
+        for (int bm = 0; bm < RB; ++bm) ca[bm] = wa[bm][0], ca1[bm] = wa[bm][WRUNS - 1];
 #pragma unroll
         for (int bn = 0; bn < WN; ++bn) {
             cb[bn] = wb[bn];
             valid[bn] = vb[bn];
         }
         fetch(c + 1 < c1 ? c + 1 : c);                      // unconditional (the last one re-reads in bounds and is unused)
+        if constexpr (F::SPARSE) {
+            // the kept bytes of the one-hot operand: (1, 0) per position, or zeros for a tap outside the image
+            v4i ones[WN];
+#pragma unroll
+            for (int bn = 0; bn < WN; ++bn) {
+                const int x = valid[bn] ? 0x00010001 : 0;
+                ones[bn] = (v4i){x, x, x, x};
+            }
+            // Step t = the chunk's word t: two instructions (even codes, odd codes) per block of the tile.  The operands
+            // of step t+1 -- per weight block and lane half a unit of table reads, per activation block two masks -- are
+            // made between the instructions of step t.
+            v8i dn[2][WM][2];
+            int ix[2][WN][2];
+            const uint2 *rows = s_rows + 16 * w4;
+            auto prepare = [&](int t, int u, int buf) {      // unit u < 2 * WM: (weight block, word of lane half u % 2)
+                if (u < 2 * WM) {
+                    sparse_dense_half(rows, (u & 1) ? ca1[u / 2].v[t] : ca[u / 2].v[t], 16 * h, u & 1, dn[buf][u / 2][0], dn[buf][u / 2][1]);
+                } else {
+                    const uint32_t word = cb[u - 2 * WM].v[t];
+                    ix[buf][u - 2 * WM][0] = (int)(word & 0x33333333u);
+                    ix[buf][u - 2 * WM][1] = (int)((word >> 2) & 0x33333333u);
+                }
+            };
+            constexpr int U = 2 * WM + WN, MN = WM * WN;
+#pragma unroll
+            for (int u = 0; u < U; ++u) prepare(0, u, 0);
+#pragma unroll
+            for (int t = 0; t < CH; ++t) {
+                const int cur = t & 1;
+#pragma unroll
+                for (int i = 0; i < 2 * MN; ++i) {
+                    const int par = i / MN, bm = (i % MN) / WN, bn = i % WN;      // all blocks with the even codes, then the odd
+                    acc[bm][bn] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones[bn], dn[cur][bm][par], acc[bm][bn], ix[cur][bn][par], 0, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (t + 1 < CH) {
+                        // the table reads go first (over the first instructions) so that their latency is covered
+                        const int u0 = i * U / (2 * MN), u1 = (i + 1) * U / (2 * MN);
+#pragma unroll
+                        for (int u = u0; u < u1; ++u) {
+                            prepare(t + 1, u, cur ^ 1);
+                            if (u < 2 * WM)
+                                __builtin_amdgcn_sched_group_barrier(0x102, 19, 0);      // 15 VALU and 4 LDS reads
+                            else
+                                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+                        }
+                    }
+                }
+            }
+            continue;
+        }
         // Step t = one MFMA per block of the tile: word t / STEPS, selector j of it, value group g.  The operands of
         // step t+1 are built between the MFMAs of step t so that the matrix unit and the VALU of a single wavefront
         // overlap; the scheduling groups pin that interleaving.
@@ -411,7 +514,9 @@ __global__ void __launch_bounds__(1024)
 onehot_splitk_kernel(SplitArgs a)
 {
     typedef Fmt<BITS> F;
+    static_assert(!F::SPARSE || (TR && !TWO), "the sparse operand is the MFMA's row operand: activations on the rows");
     __shared__ int32_t s_sum[16 * 64];                      // the block's sums, [accumulator register][lane]
+    __shared__ uint2 s_rows[F::SPARSE ? 16 * 16 : 1];
     const DgProblem &p = a.p;
     const int lane = threadIdx.x & 63, ws = threadIdx.x >> 6;
     for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) s_sum[idx] = 0;
@@ -430,10 +535,12 @@ onehot_splitk_kernel(SplitArgs a)
     // The prologue is most of this kernel's life, so it is ordered for latency: the weight load needs no division and
     // goes first; the scale of the epilogue (NHWC: one channel per thread whatever element it sums) is fetched now.
     const int mw = min(m0 + r, p.M - 1);
-    const uint8_t *w_ptr = p.Wp + (int64_t)mw * (p.K / F::PER_BYTE) + h * (4 * CH);
-    Words<CH> wa = load_words<CH>(w_ptr + (int64_t)min(c0, a.chunks - 1) * (8 * CH)), wb;
+    const uint8_t *w_ptr = p.Wp + (int64_t)mw * (p.K / F::PER_BYTE) + (F::SPARSE ? 0 : h * (4 * CH));
+    Words<CH> wa = load_words<CH>(w_ptr + (int64_t)min(c0, a.chunks - 1) * (8 * CH)), wa1 = wa, wb;
+    if (F::SPARSE) wa1 = load_words<CH>(w_ptr + (int64_t)min(c0, a.chunks - 1) * (8 * CH) + 4 * CH);
     float sc = 0.0f;
     if (TR && p.scale) sc = p.scale[mw];
+    if (F::SPARSE) sparse_fill_rows(s_rows + 16 * ws, a.pools, lane);
     {
         const Column col = make_column(p, a.div_ow, a.div_oh, n0 + r, cq, h * (4 * CH));
         // filter tap of this wavefront's first chunk
@@ -460,11 +567,25 @@ onehot_splitk_kernel(SplitArgs a)
         // flight across this barrier (it waits for LDS only), so the wavefronts' staggered starts cost nothing here
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         for (int c = c0; c < c1; ++c) {
-            const Words<CH> ca = wa, cb = wb;
+            const Words<CH> ca = wa, ca1 = wa1, cb = wb;
             const bool valid = vb;
             // unconditional prefetch (the last one re-reads in bounds and is unused)
             wa = load_words<CH>(w_ptr + (int64_t)(c + 1 < c1 ? c + 1 : c) * (8 * CH));
+            if (F::SPARSE) wa1 = load_words<CH>(w_ptr + (int64_t)(c + 1 < c1 ? c + 1 : c) * (8 * CH) + 4 * CH);
             fetch_x();
+            if constexpr (F::SPARSE) {
+                const int x = valid ? 0x00010001 : 0;
+                const v4i ones = {x, x, x, x};
+#pragma unroll
+                for (int word = 0; word < CH; ++word) {
+                    v8i even, odd;
+                    sparse_dense_half(s_rows + 16 * ws, ca.v[word], 16 * h, 0, even, odd);
+                    sparse_dense_half(s_rows + 16 * ws, ca1.v[word], 16 * h, 1, even, odd);
+                    acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones, even, acc, (int)(cb.v[word] & 0x33333333u), 0, 0);
+                    acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones, odd, acc, (int)((cb.v[word] >> 2) & 0x33333333u), 0, 0);
+                }
+                continue;
+            }
 #pragma unroll
             for (int word = 0; word < CH; ++word)
 #pragma unroll
@@ -544,8 +665,9 @@ void launch_ch(const Args &a, int ch, dim3 grid, hipStream_t stream)
 {
     constexpr size_t lds = main_lds_bytes<WM, WN, TWO, SKW>();
     static_assert(lds <= 64 * 1024, "the host plans only shapes whose sums fit 64 KB of LDS");
-    // (4-bit codes: the host never plans 4-word chunks -- 32 MFMA steps -- so they are not instantiated)
-    if constexpr (BITS != 4) {
+    // (4-bit codes: the host never plans 4-word chunks -- 32 MFMA steps -- so they are not instantiated; nor for the
+    // sparse instruction, whose 64 x 128 tile would spill with them)
+    if constexpr (BITS != 4 && BITS != 20) {
         if (ch == 4) {
             hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 4, TR, TWO, SKW>), grid, dim3(256), lds, stream, a);
             return;
@@ -580,7 +702,8 @@ void launch_main(const DgProblem &p, const Pools &pools, const Plan &q, int64_t 
         // the matrix pipe to be the limit, so the comparison gets one)
         if constexpr (BITS == 0 && SKW == 1) launch_ch<0, 4, 4, TR, false, 1>(a, q.ch, grid, stream);
     } else if (q.wn == 7) {
-        if constexpr (SKW != 2) launch_ch<BITS, 2, 7, TR, TWO, SKW>(a, q.ch, grid, stream);
+        // (the sparse instruction's accumulators cannot live in the accumulation registers: 14 blocks do not fit)
+        if constexpr (SKW != 2 && BITS != 20) launch_ch<BITS, 2, 7, TR, TWO, SKW>(a, q.ch, grid, stream);
     } else if (q.wn == 4) {
         launch_ch<BITS, 2, 4, TR, TWO, SKW>(a, q.ch, grid, stream);
     } else if (q.wn == 2) {
@@ -603,7 +726,7 @@ void launch_split(const DgProblem &p, const Pools &pools, const Plan &q, int64_t
     b.div_ow = make_div((uint32_t)p.OW), b.div_oh = make_div((uint32_t)p.OH);
     b.div_cin = make_div((uint32_t)p.Cin), b.div_kw = make_div((uint32_t)p.KW);
     const dim3 grid((unsigned)blocks11), block(64 * q.S);
-    if constexpr (BITS != 4) {
+    if constexpr (BITS != 4 && BITS != 20) {
         if (q.ch == 4) {
             hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 4, TR, TWO>), grid, block, 0, stream, b);
             return;
@@ -618,7 +741,7 @@ void launch_split(const DgProblem &p, const Pools &pools, const Plan &q, int64_t
 // One translation unit per (code width, output layout, K share) instantiates these (the kernels are many: 4 tiles x
 // 3 chunk sizes each).  TR: the output axis with stride 1 goes on the MFMA columns (see dg_mfma_tile.h).
 // Unit "bBtTkK" defines unit_main_bB_tT_kK, and for K = 1 also unit_split_bB_tT; B = 22 stands for 2-bit codes in two
-// planes, B = 0 for the decode-and-multiply comparison.
+// planes, B = 0 for the decode-and-multiply comparison, B = 20 for 2-bit codes on the sparse instruction (T = 1 only).
 typedef void (*MainFn)(const DgProblem &, const Pools &, const Plan &, int64_t, hipStream_t);
 #define DGOH_UNIT(B, T, K) \
     void unit_main_b##B##_t##T##_k##K(const DgProblem &, const Pools &, const Plan &, int64_t, hipStream_t);
@@ -626,9 +749,10 @@ typedef void (*MainFn)(const DgProblem &, const Pools &, const Plan &, int64_t, 
     void unit_split_b##B##_t##T(const DgProblem &, const Pools &, const Plan &, int64_t, hipStream_t);
 DGOH_UNIT(2, 0, 1) DGOH_UNIT(2, 0, 2) DGOH_UNIT(2, 0, 4) DGOH_UNIT(2, 1, 1) DGOH_UNIT(2, 1, 2) DGOH_UNIT(2, 1, 4)
 DGOH_UNIT(3, 0, 1) DGOH_UNIT(3, 1, 1) DGOH_UNIT(4, 0, 1) DGOH_UNIT(4, 1, 1) DGOH_UNIT(22, 0, 1) DGOH_UNIT(22, 1, 1)
+DGOH_UNIT(20, 1, 1) DGOH_UNIT(20, 1, 2) DGOH_UNIT(20, 1, 4)
 DGOH_UNIT(0, 0, 1) DGOH_UNIT(0, 0, 2) DGOH_UNIT(0, 0, 4) DGOH_UNIT(0, 1, 1) DGOH_UNIT(0, 1, 2) DGOH_UNIT(0, 1, 4)
 DGOH_UNIT_SPLIT(2, 0) DGOH_UNIT_SPLIT(2, 1) DGOH_UNIT_SPLIT(3, 0) DGOH_UNIT_SPLIT(3, 1) DGOH_UNIT_SPLIT(4, 0)
-DGOH_UNIT_SPLIT(4, 1) DGOH_UNIT_SPLIT(22, 0) DGOH_UNIT_SPLIT(22, 1) DGOH_UNIT_SPLIT(0, 0) DGOH_UNIT_SPLIT(0, 1)
+DGOH_UNIT_SPLIT(4, 1) DGOH_UNIT_SPLIT(22, 0) DGOH_UNIT_SPLIT(22, 1) DGOH_UNIT_SPLIT(0, 0) DGOH_UNIT_SPLIT(0, 1) DGOH_UNIT_SPLIT(20, 1)
 #undef DGOH_UNIT
 #undef DGOH_UNIT_SPLIT
 

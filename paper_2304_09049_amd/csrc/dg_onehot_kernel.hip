@@ -1,5 +1,6 @@
-// Host side of the one-hot matrix-core kernels and of the decode-and-multiply comparison built in the same frame
-// (dg_onehot_kernel.h): which problems they take, which of their shapes runs a given problem, and the launch.
+// Host side of the one-hot matrix-core kernels (dense and sparse instruction) and of the decode-and-multiply comparison
+// built in the same frame (dg_onehot_kernel.h): which problems they take, which of their shapes runs a given problem,
+// and the launch.
 #include <cstdlib>
 #include <cstring>
 
@@ -8,6 +9,8 @@
 namespace {
 
 using dgoh::Plan;
+
+enum Mode { TABLE, DECODE, SPARSE };      // one-hot selection by the dense MFMA; decode-and-multiply; selection by the sparse MFMA
 
 int per_byte(const dg_lut *lut) { return lut->bits == 2 ? 4 : 2; }
 
@@ -26,17 +29,20 @@ int64_t tile_count(const DgProblem &p, int wm, int wn)
 
 bool fits_int8(const dg_lut *lut) { return lut->min_entry >= -128 && lut->max_entry <= 127; }
 
-Plan plan_for(const dg_lut *lut, const DgProblem &p, bool decode)
+// `tile` > 0 fixes an unshared tile of that many blocks' width instead of modelling (see sparse_plan)
+Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
 {
+    const bool decode = mode == DECODE;
     Plan q;
     q.decode = decode;
-    q.two = !decode && !fits_int8(lut);                    // two int8 planes; a tile is then 32 rows high, not 64
+    q.two = mode == TABLE && !fits_int8(lut);              // two int8 planes; a tile is then 32 rows high, not 64
     const int wm = q.two ? 1 : 2;
     q.wm = wm;
     // a lane half reads 4*ch packed bytes of one filter tap per chunk
     const int tap_bytes = p.Cin / per_byte(lut);
     q.ch = tap_bytes % 32 == 0 ? 4 : (tap_bytes % 16 == 0 ? 2 : 1);
     if (lut->bits == 4 && q.ch == 4) q.ch = 2;             // (a 4-word chunk of 4-bit codes would be 32 MFMA steps)
+    if (mode == SPARSE && q.ch == 4) q.ch = 2;             // (the sparse instruction's widest tile has no registers for 4)
     q.chunks = (p.K / per_byte(lut)) / (8 * q.ch);
     q.wn = 1, q.skw = 1, q.S = 1, q.cpw = q.chunks;
     q.split = false;
@@ -64,13 +70,15 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, bool decode)
     // narrowest tiles, 3000 + 600 per block for prologue and stores)
     static const double fitted_cycles[4] = {37.7, 28.9, 29.5, 34.0}, plain_cycles[4] = {32.0, 32.0, 33.0, 42.0};
     const double *mfma_cycles = can_share ? fitted_cycles : plain_cycles;
-    const double steps = decode ? p.K / 32.0 : (double)p.K * (1 << lut->bits) / 32.0;
+    // matrix instructions per 32 x 32 block: one per 32 positions decoding, per 32 / L selecting, per 16 on the sparse one
+    const double steps = decode ? p.K / 32.0 : (mode == SPARSE ? p.K / 16.0 : (double)p.K * (1 << lut->bits) / 32.0);
     double best = 0.0;
     bool first = true;
     for (int i = 0; i < 4; ++i)
         for (int skw = 1; skw <= (can_share ? 4 : 1); skw *= 2) {
             const int wn = widths[i];
             if (skw > q.chunks || (wn == 7 && skw == 2)) continue;      // (two 64x224 tiles of sums exceed 64 KB of LDS)
+            if (wn == 7 && mode == SPARSE) continue;                    // (14 blocks of sparse-instruction sums exceed the VGPRs)
             const int64_t per_simd = (tile_count(p, wm, wn) * skw + 1023) / 1024;
             const double lone = !can_share ? 1.0 : (per_simd == 1 ? 0.84 : (per_simd == 2 ? 0.78 : 1.0));   // (rounding up overstates short queues)
             double cost = (double)per_simd * 2 * wn * (steps / skw) * mfma_cycles[i] * lone;
@@ -94,13 +102,14 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, bool decode)
         const int64_t t21 = tile_count(p, wm, 1);
         q.split = (t21 < 512 || (t21 < 1024 && q.chunks >= 32)) && q.chunks > 1;
     }
+    if (tile > 0) q.split = false, q.wm = wm, q.wn = tile, q.skw = 1;
     // DG_ONEHOT_PLAN = split | <wn> | <wn>k<skw> (wn = 1, 2, 4, 7; skw = 1, 2, 4) | 44 (the comparison's 128 x 128 tile)
     // overrides the choice (tuning, and tests that must reach every plan)
     if (const char *force = getenv("DG_ONEHOT_PLAN")) {
         const int v = atoi(force);
         if (force[0] == 's') q.split = true;
         else if (v == 44 && decode) q.split = false, q.wm = 4, q.wn = 4, q.skw = 1;
-        else if (v == 1 || v == 2 || v == 4 || v == 7) {
+        else if (v == 1 || v == 2 || v == 4 || (v == 7 && mode != SPARSE)) {
             int k = 1;
             if (const char *at = strchr(force, 'k')) k = atoi(at + 1);
             q.split = false;
@@ -122,9 +131,112 @@ bool dg_onehot_supports(const dg_lut *lut, const DgProblem &p)
     // MFMA operands are int8: wider entries take two planes, T = 256 * hi + lo (2-bit codes only, hi within int8)
     if (!fits_int8(lut) && (lut->bits != 2 || lut->max_entry > 127 * 256 + 127)) return false;
     if (p.Cin % (8 * per_byte(lut)) != 0) return false;                // a lane half reads whole words of one tap
-    const Plan q = plan_for(lut, p, false);
+    const Plan q = plan_for(lut, p, TABLE);
     if ((uintptr_t)p.Wp % (4 * q.ch) != 0 || (uintptr_t)p.Xp % (4 * q.ch) != 0) return false;
     return true;
+}
+
+namespace {
+
+// The sparse instruction's one-hot operand is its row operand, so the activations sit on the MFMA rows and the channel
+// axis m on its columns: right for outputs whose stride-1 axis is m (NHWC).  A plain GEMM with n contiguous is the
+// same problem transposed -- activations as "weights", the table transposed -- and is run that way.
+bool sparse_transposes(const DgProblem &p)
+{
+    return p.stride_cn == 1 && p.stride_cm != 1;
+}
+
+bool sparse_can_transpose(const DgProblem &p)
+{
+    return p.H == 1 && p.W == 1 && p.KH == 1 && p.KW == 1 && p.sh == 1 && p.sw == 1 && p.ph == 0 && p.pw == 0 &&
+           p.scale == nullptr && p.Qp == nullptr;
+}
+
+DgProblem sparse_problem(const DgProblem &p)
+{
+    if (!sparse_transposes(p)) return p;
+    DgProblem t = p;
+    t.M = p.N, t.N = p.M;
+    t.Wp = p.Xp, t.Xp = p.Wp;
+    t.stride_cm = p.stride_cn, t.stride_cn = p.stride_cm;
+    return t;
+}
+
+// Measured on 29 layer shapes: where the dense-instruction planner picks an unshared tile at least 64 columns wide, the
+// sparse instruction with the same tile (at most 128 wide: its sums must stay in the vector registers) is 2 - 24 %
+// faster; on 64 x 32 tiles, shared tiles and the split-K kernel it is not (its weight operand costs more VALU and LDS
+// work per matrix instruction, which narrow tiles do not amortise).  `t` is the problem as the sparse kernel runs it.
+int sparse_tile_hint(const dg_lut *lut, const DgProblem &t)
+{
+    if (!fits_int8(lut) || lut->bits != 2) return 0;
+    const Plan dense = plan_for(lut, t, TABLE);
+    if (dense.split || dense.skw != 1 || dense.wn < 2) return 0;
+    return dense.wn > 4 ? 4 : dense.wn;
+}
+
+Plan sparse_plan(const dg_lut *lut, const DgProblem &t)
+{
+    return plan_for(lut, t, SPARSE, sparse_tile_hint(lut, t));
+}
+
+}   // namespace
+
+bool dg_sparse_preferred(const dg_lut *lut, const DgProblem &p)
+{
+    return dg_sparse_supports(lut, p) && sparse_tile_hint(lut, sparse_problem(p)) > 0 && getenv("DG_ONEHOT_PLAN") == nullptr;
+}
+
+bool dg_sparse_supports(const dg_lut *lut, const DgProblem &p)
+{
+    if (lut->dtype == DG_LUT_F32 || lut->bits != 2 || !fits_int8(lut)) return false;
+    if (p.Cin % 32 != 0) return false;                                 // a lane half reads whole words of one tap
+    if (sparse_transposes(p) && !sparse_can_transpose(p)) return false;
+    const DgProblem t = sparse_problem(p);
+    const Plan q = sparse_plan(lut, t);
+    if ((uintptr_t)t.Wp % (4 * q.ch) != 0 || (uintptr_t)t.Xp % (4 * q.ch) != 0) return false;
+    return true;
+}
+
+const char *dg_sparse_config_name(const dg_lut *lut, const DgProblem &p)
+{
+    static const char *const split_names[17] = {
+        "", "onehot_smfmac_splitk_s1", "onehot_smfmac_splitk_s2", "onehot_smfmac_splitk_s3", "onehot_smfmac_splitk_s4",
+        "onehot_smfmac_splitk_s5", "onehot_smfmac_splitk_s6", "onehot_smfmac_splitk_s7", "onehot_smfmac_splitk_s8",
+        "onehot_smfmac_splitk_s9", "onehot_smfmac_splitk_s10", "onehot_smfmac_splitk_s11", "onehot_smfmac_splitk_s12",
+        "onehot_smfmac_splitk_s13", "onehot_smfmac_splitk_s14", "onehot_smfmac_splitk_s15", "onehot_smfmac_splitk_s16"};
+    static const char *const tile_names[3][4] = {
+        {"onehot_smfmac_64x224", "onehot_smfmac_64x128", "onehot_smfmac_64x64", "onehot_smfmac_64x32"},
+        {"", "onehot_smfmac_64x128_k2", "onehot_smfmac_64x64_k2", "onehot_smfmac_64x32_k2"},
+        {"onehot_smfmac_64x224_k4", "onehot_smfmac_64x128_k4", "onehot_smfmac_64x64_k4", "onehot_smfmac_64x32_k4"}};
+    const Plan q = sparse_plan(lut, sparse_problem(p));
+    if (q.split) return split_names[q.S];
+    return tile_names[q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)][q.wn == 7 ? 0 : (q.wn == 4 ? 1 : (q.wn == 2 ? 2 : 3))];
+}
+
+dg_status dg_launch_sparse(const dg_lut *lut, const DgProblem &p0, hipStream_t stream)
+{
+    const bool transposed = sparse_transposes(p0);
+    const DgProblem p = sparse_problem(p0);
+    const Plan q = sparse_plan(lut, p);
+    // pool word w = the table row of "weight" code w, bytes over the "activation" code (the transposed problem swaps them)
+    dgoh::Pools pools;
+    for (int i = 0; i < 64; ++i) pools.w[i] = 0;
+    for (int w = 0; w < 4; ++w)
+        for (int v = 0; v < 4; ++v) {
+            const int T = transposed ? lut->entry[(v << 2) | w] : lut->entry[(w << 2) | v];
+            pools.w[w] |= (uint32_t)(uint8_t)(int8_t)T << (8 * v);
+        }
+    const int64_t blocks11 = tile_count(p, 1, 1), wave_tiles = tile_count(p, q.wm, q.wn);
+    if ((q.split ? blocks11 : wave_tiles) > INT32_MAX)
+        return dg_fail(DG_ERR_UNSUPPORTED, "sparse one-hot kernel: too many tiles for one grid");
+    using namespace dgoh;
+    if (q.split) {
+        unit_split_b20_t1(p, pools, q, blocks11, stream);
+        return dg_check_launch("onehot_splitk_kernel<20>");
+    }
+    static const MainFn main_units[3] = {unit_main_b20_t1_k1, unit_main_b20_t1_k2, unit_main_b20_t1_k4};
+    main_units[q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)](p, pools, q, wave_tiles, stream);
+    return dg_check_launch("onehot_mfma_kernel<20>");
 }
 
 bool dg_decode_supports(const dg_lut *lut, const DgProblem &p)
@@ -132,7 +244,7 @@ bool dg_decode_supports(const dg_lut *lut, const DgProblem &p)
     // the levels themselves are the MFMA operands: the table must be their outer product, with 2-bit codes
     if (lut->dtype == DG_LUT_F32 || !lut->separable || lut->bits != 2) return false;
     if (p.Cin % 32 != 0) return false;                                 // a lane half reads whole words of one tap
-    const Plan q = plan_for(lut, p, true);
+    const Plan q = plan_for(lut, p, DECODE);
     if ((uintptr_t)p.Wp % (4 * q.ch) != 0 || (uintptr_t)p.Xp % (4 * q.ch) != 0) return false;
     return true;
 }
@@ -154,7 +266,7 @@ const char *dg_onehot_config_name(const dg_lut *lut, const DgProblem &p)
          {"onehot_mfma_64x224_k4", "onehot_mfma_64x128_k4", "onehot_mfma_64x64_k4", "onehot_mfma_64x32_k4"}},
         {{"onehot_mfma_2p_32x224", "onehot_mfma_2p_32x128", "onehot_mfma_2p_32x64", "onehot_mfma_2p_32x32"},
          {"", "", "", ""}, {"", "", "", ""}}};
-    const Plan q = plan_for(lut, p, false);
+    const Plan q = plan_for(lut, p, TABLE);
     if (q.split) return split_names[q.two][q.S];
     return tile_names[q.two][q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)][q.wn == 7 ? 0 : (q.wn == 4 ? 1 : (q.wn == 2 ? 2 : 3))];
 }
@@ -170,7 +282,7 @@ const char *dg_decode_config_name(const dg_lut *lut, const DgProblem &p)
         {"mfma_i8_64x224", "mfma_i8_64x128", "mfma_i8_64x64", "mfma_i8_64x32"},
         {"", "mfma_i8_64x128_k2", "mfma_i8_64x64_k2", "mfma_i8_64x32_k2"},
         {"mfma_i8_64x224_k4", "mfma_i8_64x128_k4", "mfma_i8_64x64_k4", "mfma_i8_64x32_k4"}};
-    const Plan q = plan_for(lut, p, true);
+    const Plan q = plan_for(lut, p, DECODE);
     if (q.split) return split_names[q.S];
     if (q.wm == 4) return "mfma_i8_128x128";
     return tile_names[q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)][q.wn == 7 ? 0 : (q.wn == 4 ? 1 : (q.wn == 2 ? 2 : 3))];
@@ -178,7 +290,7 @@ const char *dg_decode_config_name(const dg_lut *lut, const DgProblem &p)
 
 dg_status dg_launch_decode(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
 {
-    const Plan q = plan_for(lut, p, true);
+    const Plan q = plan_for(lut, p, DECODE);
     dgoh::Pools pools;
     for (int i = 0; i < 64; ++i) pools.w[i] = 0;
     for (int c = 0; c < 4; ++c) {                          // the two level vectors as byte-permute pools
@@ -205,7 +317,7 @@ dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t st
 {
     // column v of the table, 4 weight codes per word: the permute pools.  Entries beyond int8 go in two planes,
     // T = 256 * hi + lo with lo in [-128, 127] (so hi is within [-128, 128) for every int16 T).
-    const Plan q = plan_for(lut, p, false);
+    const Plan q = plan_for(lut, p, TABLE);
     dgoh::Pools pools;
     const int L = 1 << lut->bits, qw = L / 4;
     for (int i = 0; i < 64; ++i) pools.w[i] = 0;

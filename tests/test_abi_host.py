@@ -172,7 +172,8 @@ def test_kernel_names_need_no_gpu():
     # the plan functions are host code: small layers split K, large ones get a wave tile, wide entries two planes
     lut = dg.dg_build_lut((-2, -1, 0, 1), (0, 1, 2, 3))
     assert dg.dg_gemm_kernel_name(lut, 64, 196, 576).startswith("onehot_mfma_splitk_s")
-    assert dg.dg_gemm_kernel_name(lut, 8192, 8192, 8192) == "onehot_mfma_64x128"
+    assert dg.dg_gemm_kernel_name(lut, 8192, 8192, 8192) == "onehot_smfmac_64x128"     # large unshared tiles: the sparse instruction
+    assert dg.dg_gemm_kernel_name(lut, 8192, 8192, 8192, "onehot_mfma") == "onehot_mfma_64x128"
     assert dg.dg_gemm_kernel_name(lut, 8192, 256, 8192) == "onehot_mfma_64x64_k4"      # wavefronts share tiles
     assert dg.dg_gemm_kernel_name(lut, 8192, 1, 8192) == "smalln"
     assert dg.dg_gemm_kernel_name(lut, 64, 196, 48).startswith("perm")        # Cin % 32 != 0, % 16 == 0

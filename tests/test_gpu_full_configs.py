@@ -10,7 +10,7 @@ from gpu_helpers import GpuCase, run_or_unsupported
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = ["auto", "perm", "lds", "mfma_i8", "smalln", "lut65k", "onehot_mfma"]
+VARIANTS = ["auto", "perm", "lds", "mfma_i8", "smalln", "lut65k", "onehot_mfma", "onehot_smfmac"]
 FULL = ["gemm_64x196x576", "resnet18_conv3x3_b1", "resnet50_conv1x1_b32", "gemm_8192x1x8192_i16",
         "gemm_8192x16x8192_i16"]
 SAMPLED = ["vgg16_conv3x3_b16", "gemm_8192x256x8192_i16", "gemm_8192x8192x8192_i16"]

@@ -14,7 +14,7 @@ from gpu_helpers import GpuCase, run_or_unsupported
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = ["auto", "lds", "perm", "mfma_i8", "smalln", "lut65k", "onehot_mfma"]
+VARIANTS = ["auto", "lds", "perm", "mfma_i8", "smalln", "lut65k", "onehot_mfma", "onehot_smfmac"]
 
 LEVELS = {
     "signed_unsigned": ((-2, -1, 0, 1), (0, 1, 2, 3), dg.DG_LUT_I8),
@@ -132,26 +132,34 @@ ONEHOT_PLANS = {"split": "onehot_mfma_splitk_s", "1": "onehot_mfma_64x32", "2": 
                 "44": "mfma_i8_128x128"}
 
 
-@pytest.mark.parametrize("table", ["signed_unsigned", "extreme_i16", "decode"])
+@pytest.mark.parametrize("table", ["signed_unsigned", "extreme_i16", "decode", "sparse"])
 @pytest.mark.parametrize("plan", sorted(ONEHOT_PLANS))
 def test_onehot_every_plan(plan, table, monkeypatch):
     """Every wave tile of the one-hot matrix-core kernel and its split-K form, forced on shapes with ragged edges in
     M and N (the library picks among them by a cost model that small test shapes would never move off one plan):
     GEMM with row-major and column-major output, convolution with padding and stride, int32 and scaled fp32 output.
     Once with an int8 table (one plane), once with entries up to 16384 (two int8 planes), and once as the
-    decode-and-multiply comparison kernel, which is built in the same frame and has the same plans."""
+    decode-and-multiply comparison kernel and once as the sparse-instruction table kernel, which are built in the same
+    frame and have the same plans."""
     if "k" in plan and table == "extreme_i16":
         pytest.skip("tiles are shared only by the one-plane kernels")
     if plan == "44" and table != "decode":
         pytest.skip("only the comparison kernel has the 128 x 128 tile")
+    if plan.startswith("7") and table == "sparse":
+        pytest.skip("the sparse instruction's sums stay in the vector registers: no 64 x 224 tile")
     monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
-    glw, gla, gentry = LEVELS["extreme_i16" if table == "decode" else table]
-    kernel = "mfma_i8" if table == "decode" else "onehot_mfma"
+    glw, gla, gentry = LEVELS[{"decode": "extreme_i16", "sparse": "nonuniform_i8"}.get(table, table)]
+    kernel = {"decode": "mfma_i8", "sparse": "onehot_smfmac"}.get(table, "onehot_mfma")
     prefix = ONEHOT_PLANS[plan]
     if table == "extreme_i16":
         prefix = prefix.replace("onehot_mfma_", "onehot_mfma_2p_").replace("_64x", "_32x")
     if table == "decode":
         prefix = prefix.replace("onehot_mfma_", "mfma_i8_")
+    if table == "sparse":
+        prefix = prefix.replace("onehot_mfma_", "onehot_smfmac_")
+
+    def chunk_codes(c):                  # codes a wavefront takes at a time: 4, 2 or 1 words per lane half (sparse: 2 or 1)
+        return 128 if c % 128 == 0 and table != "sparse" else (64 if c % 64 == 0 else 32)
 
     def right_kernel(name, chunks):
         if plan == "split":
@@ -163,7 +171,7 @@ def test_onehot_every_plan(plan, table, monkeypatch):
     for (M, N, K) in [(70, 1000, 96), (130, 777, 64), (64, 300, 256), (33, 250, 1024)]:
         inp = wl.small_gemm(M, N, K, seed=M + N + K)
         case = GpuCase(inp, levels=(glw, gla), entry=gentry)
-        assert right_kernel(case.kernel_name(kernel), K // (128 if K % 128 == 0 else (64 if K % 64 == 0 else 32)))
+        assert right_kernel(case.kernel_name(kernel), K // chunk_codes(K))
         want = oracle.gemm(inp.Wc, inp.Ac, glw, gla)
         _assert_same(case.run(kernel).cpu().numpy(), want, f"gemm {(M, N, K)} plan {plan}")
         out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
@@ -171,15 +179,14 @@ def test_onehot_every_plan(plan, table, monkeypatch):
         torch.cuda.synchronize()
         _assert_same(out.cpu().numpy(), want.T.copy(), f"gemm {(M, N, K)} column-major plan {plan}")
     # no zero activation level: padding must still add 0
-    lw, la, entry = LEVELS["nonuniform_i8"] if table == "signed_unsigned" else ((127, -128, 5, 3), (-128, 127, 1, 2), dg.DG_LUT_I16)
+    lw, la, entry = LEVELS["nonuniform_i8"] if table in ("signed_unsigned", "sparse") else ((127, -128, 5, 3), (-128, 127, 1, 2), dg.DG_LUT_I16)
     for (B, H, W, Cin, Cout, KH, KW, stride, pad) in [(2, 24, 24, 32, 70, 3, 3, (1, 1), (1, 1)),
                                                       (1, 30, 30, 128, 40, 3, 3, (2, 2), (1, 1)),
                                                       (3, 16, 16, 64, 33, 1, 1, (1, 1), (0, 0)),
                                                       (1, 20, 20, 64, 96, 5, 5, (1, 1), (2, 2))]:
         c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
         case = GpuCase(c, levels=(lw, la), entry=entry)
-        assert right_kernel(case.kernel_name(kernel),
-                            KH * KW * Cin // (128 if Cin % 128 == 0 else (64 if Cin % 64 == 0 else 32)))
+        assert right_kernel(case.kernel_name(kernel), KH * KW * Cin // chunk_codes(Cin))
         acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
         _assert_same(case.run(kernel).cpu().numpy(), acc, f"conv {(B, H, W, Cin, Cout)} plan {plan}")
         got = case.run(kernel, scale=True).cpu().numpy()
