@@ -666,8 +666,8 @@ void launch_ch(const Args &a, int ch, dim3 grid, hipStream_t stream)
     constexpr size_t lds = main_lds_bytes<WM, WN, TWO, SKW>();
     static_assert(lds <= 64 * 1024, "the host plans only shapes whose sums fit 64 KB of LDS");
     // (4-bit codes: the host never plans 4-word chunks -- 32 MFMA steps -- so they are not instantiated; nor for the
-    // sparse instruction, whose 64 x 128 tile would spill with them)
-    if constexpr (BITS != 4 && BITS != 20) {
+    // sparse instruction's 64 x 128 and shared tiles, which would spill with them)
+    if constexpr (BITS != 4 && !(BITS == 20 && (WN > 2 || SKW > 1))) {
         if (ch == 4) {
             hipLaunchKernelGGL((onehot_mfma_kernel<BITS, WM, WN, 4, TR, TWO, SKW>), grid, dim3(256), lds, stream, a);
             return;

@@ -120,6 +120,8 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
     }
     if (q.split) q.cpw = split_cpw, q.S = split_S, q.wm = wm;
     if (lut->bits == 4 && q.wn == 7) q.ch = 1;             // (the 2-word kernel of this tile is not built: see launch_ch)
+    // (the sparse instruction's narrower unshared tiles do have the registers for 4-word chunks)
+    if (mode == SPARSE && !q.split && q.skw == 1 && q.wn <= 2 && tap_bytes % 32 == 0) q.ch = 4, q.chunks /= 2;
     return q;
 }
 

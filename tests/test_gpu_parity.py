@@ -158,8 +158,8 @@ def test_onehot_every_plan(plan, table, monkeypatch):
     if table == "sparse":
         prefix = prefix.replace("onehot_mfma_", "onehot_smfmac_")
 
-    def chunk_codes(c):                  # codes a wavefront takes at a time: 4, 2 or 1 words per lane half (sparse: 2 or 1)
-        return 128 if c % 128 == 0 and table != "sparse" else (64 if c % 64 == 0 else 32)
+    def chunk_codes(c):                  # codes a wavefront takes at a time: 4, 2 or 1 words per lane half (sparse, where a
+        return 128 if c % 128 == 0 and table != "sparse" else (64 if c % 64 == 0 else 32)     # K share matters: 2 or 1)
 
     def right_kernel(name, chunks):
         if plan == "split":
