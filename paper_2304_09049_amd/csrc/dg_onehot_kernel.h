@@ -230,19 +230,29 @@ __device__ __forceinline__ void sparse_fill_rows(uint2 *rows, const Pools &pl, i
     __builtin_amdgcn_wave_barrier();
 }
 
-// The dense operands of the two instructions (even codes, odd codes) that consume one packed word per lane half.  `w` is
-// the weight row's word at the positions of lane half hp's activation word; this lane supplies the rows of its codes
-// 8*half .. 8*half+7 (the 16-bit half `shift / 16` of the word) as dwords 4*hp .. 4*hp+3 of the two operands: the even
-// codes to `even`, the odd ones to `odd` (see the layout above).  Two codes two apart are first brought together as a
-// 4-bit table index, so that one 8-byte read fills two consecutive operand registers.
-__device__ __forceinline__ void sparse_dense_half(const uint2 *rows, uint32_t w, int shift, int hp, v8i &even, v8i &odd)
+// The dense operands of the two instructions (even codes, odd codes) that consume one packed word per lane half.  w0
+// and w1 are the weight row's words at the positions of lane half 0's and lane half 1's activation words; this lane
+// supplies the rows of their codes 8*half .. 8*half+7, i.e. of one 16-bit half of each word -- `pick` is the byte
+// permute that puts those two halves side by side (see sparse_pick) -- as dwords 0-3 (from w0) and 4-7 (from w1) of the
+// two operands: the even codes to `even`, the odd ones to `odd` (see the layout above).  Two codes two apart are first
+// brought together as a 4-bit table index, for both words at once, so that one 8-byte read fills two consecutive
+// operand registers.
+__device__ __forceinline__ uint32_t sparse_pick(int half)
 {
-    const uint32_t v = w >> shift, t = v >> 2;
-    const uint32_t e = (v & 0x0303u) | (t & 0x0C0Cu);            // byte b: codes 4b and 4b+2
-    const uint32_t o = (t & 0x0303u) | ((v >> 4) & 0x0C0Cu);     // byte b: codes 4b+1 and 4b+3
-    const uint2 e0 = rows[e & 15u], e1 = rows[(e >> 8) & 15u], o0 = rows[o & 15u], o1 = rows[(o >> 8) & 15u];
-    even[4 * hp] = (int)e0.x, even[4 * hp + 1] = (int)e0.y, even[4 * hp + 2] = (int)e1.x, even[4 * hp + 3] = (int)e1.y;
-    odd[4 * hp] = (int)o0.x, odd[4 * hp + 1] = (int)o0.y, odd[4 * hp + 2] = (int)o1.x, odd[4 * hp + 3] = (int)o1.y;
+    return half ? 0x07060302u : 0x05040100u;                     // bytes 2,3 (or 0,1) of the lower source, then of the upper
+}
+
+__device__ __forceinline__ void sparse_dense_rows(const uint2 *rows, uint32_t w0, uint32_t w1, uint32_t pick, v8i &even, v8i &odd)
+{
+    const uint32_t v = __builtin_amdgcn_perm(w1, w0, pick), t = v >> 2;
+    const uint32_t e = (v & 0x03030303u) | (t & 0x0C0C0C0Cu);    // byte b: codes 4b and 4b+2 of the 32 bits
+    const uint32_t o = (t & 0x03030303u) | ((v >> 4) & 0x0C0C0C0Cu);    // byte b: codes 4b+1 and 4b+3
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const uint2 x = rows[(e >> (8 * b)) & 255u], y = rows[(o >> (8 * b)) & 255u];
+        even[2 * b] = (int)x.x, even[2 * b + 1] = (int)x.y;
+        odd[2 * b] = (int)y.x, odd[2 * b + 1] = (int)y.y;
+    }
 }
 
 // Position bookkeeping shared by the two kernels: output column n -> image coordinates, and the filter tap of a chunk.
@@ -386,21 +396,22 @@ onehot_mfma_kernel(Args a)
                 ones[bn] = (v4i){x, x, x, x};
             }
             // Step t = the chunk's word t: two instructions (even codes, odd codes) per block of the tile.  The operands
-            // of step t+1 -- per weight block and lane half a unit of table reads, per activation block two masks -- are
-            // made between the instructions of step t.
+            // of step t+1 -- per weight block a unit of table reads, per activation block two masks -- are made between
+            // the instructions of step t.
             v8i dn[2][WM][2];
             int ix[2][WN][2];
             const uint2 *rows = s_rows + 16 * w4;
-            auto prepare = [&](int t, int u, int buf) {      // unit u < 2 * WM: (weight block, word of lane half u % 2)
-                if (u < 2 * WM) {
-                    sparse_dense_half(rows, (u & 1) ? ca1[u / 2].v[t] : ca[u / 2].v[t], 16 * h, u & 1, dn[buf][u / 2][0], dn[buf][u / 2][1]);
+            const uint32_t pick = sparse_pick(h);
+            auto prepare = [&](int t, int u, int buf) {      // unit u < WM: a weight block; else an activation block
+                if (u < WM) {
+                    sparse_dense_rows(rows, ca[u].v[t], ca1[u].v[t], pick, dn[buf][u][0], dn[buf][u][1]);
                 } else {
-                    const uint32_t word = cb[u - 2 * WM].v[t];
-                    ix[buf][u - 2 * WM][0] = (int)(word & 0x33333333u);
-                    ix[buf][u - 2 * WM][1] = (int)((word >> 2) & 0x33333333u);
+                    const uint32_t word = cb[u - WM].v[t];
+                    ix[buf][u - WM][0] = (int)(word & 0x33333333u);
+                    ix[buf][u - WM][1] = (int)((word >> 2) & 0x33333333u);
                 }
             };
-            constexpr int U = 2 * WM + WN, MN = WM * WN;
+            constexpr int U = WM + WN, MN = WM * WN;
 #pragma unroll
             for (int u = 0; u < U; ++u) prepare(0, u, 0);
 #pragma unroll
@@ -417,8 +428,8 @@ onehot_mfma_kernel(Args a)
 #pragma unroll
                         for (int u = u0; u < u1; ++u) {
                             prepare(t + 1, u, cur ^ 1);
-                            if (u < 2 * WM)
-                                __builtin_amdgcn_sched_group_barrier(0x102, 19, 0);      // 15 VALU and 4 LDS reads
+                            if (u < WM)
+                                __builtin_amdgcn_sched_group_barrier(0x102, 31, 0);      // 23 VALU and 8 LDS reads
                             else
                                 __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
                         }
@@ -579,8 +590,7 @@ onehot_splitk_kernel(SplitArgs a)
 #pragma unroll
                 for (int word = 0; word < CH; ++word) {
                     v8i even, odd;
-                    sparse_dense_half(s_rows + 16 * ws, ca.v[word], 16 * h, 0, even, odd);
-                    sparse_dense_half(s_rows + 16 * ws, ca1.v[word], 16 * h, 1, even, odd);
+                    sparse_dense_rows(s_rows + 16 * ws, ca.v[word], ca1.v[word], sparse_pick(h), even, odd);
                     acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones, even, acc, (int)(cb.v[word] & 0x33333333u), 0, 0);
                     acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones, odd, acc, (int)((cb.v[word] >> 2) & 0x33333333u), 0, 0);
                 }

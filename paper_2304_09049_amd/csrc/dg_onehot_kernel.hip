@@ -79,6 +79,7 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
             const int wn = widths[i];
             if (skw > q.chunks || (wn == 7 && skw == 2)) continue;      // (two 64x224 tiles of sums exceed 64 KB of LDS)
             if (wn == 7 && mode == SPARSE) continue;                    // (14 blocks of sparse-instruction sums exceed the VGPRs)
+            if (wn == 7 && decode && skw == 1) continue;                // (measured slower than 64x128 and 128x128 when decoding)
             const int64_t per_simd = (tile_count(p, wm, wn) * skw + 1023) / 1024;
             const double lone = !can_share ? 1.0 : (per_simd == 1 ? 0.84 : (per_simd == 2 ? 0.78 : 1.0));   // (rounding up overstates short queues)
             double cost = (double)per_simd * 2 * wn * (steps / skw) * mfma_cycles[i] * lone;
