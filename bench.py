@@ -310,8 +310,8 @@ def stage_kernels(torch, w):
 def wide_code_kernels(torch, w, use_graph):
     """Tables beyond the 16 int8 entries of the headline path, on the shape of workload `w` (a convolution): 2-bit codes
     with int16 entries (two int8 planes), and the 3- and 4-bit tables of Sec. 3.3 / Table 2; each on the one-hot
-    matrix-core kernel AUTO picks and on the plain LDS kernel.  The MFMA fraction counts the operations issued:
-    2^bits per effective operation (8 for the two planes of 2-bit codes)."""
+    matrix-core kernel AUTO picks (4-bit codes: the sparse-instruction form, so also the dense one) and on the plain LDS
+    kernel.  The MFMA fraction counts the multiply-accumulates performed."""
     from paper_2304_09049_amd import binding as dg
     dev = torch.device("cuda:0")
     report = []
@@ -329,15 +329,23 @@ def wide_code_kernels(torch, w, use_graph):
         Xp = dg.dg_pack_codes_bits(Xc, w.B * w.H * w.W, w.Cin, bits)
         desc = dg.conv_desc(w.B, w.H, w.W, w.Cin, w.Cout, w.KH, w.KW, w.stride, w.pad)
         out = dg.dg_conv2d_lut(lut, Wp, Xp, desc)
-        for variant in ("auto", "lds"):
+        for variant in ("auto", "onehot_mfma", "lds"):
+            name = dg.dg_conv_kernel_name(lut, desc, variant)
+            if variant == "onehot_mfma" and name == dg.dg_conv_kernel_name(lut, desc, "auto"):
+                continue                                 # (already timed as AUTO's choice)
             fn = lambda v=variant: dg.dg_conv2d_lut(lut, Wp, Xp, desc, out=out, variant=v)
             ms = time_steady(torch, fn, use_graph)
-            name = dg.dg_conv_kernel_name(lut, desc, variant)
             tops = w.ops / (ms * 1e-3) / 1e12
+            # multiply-accumulates performed per effective operation: 2^bits when selecting with the dense instruction
+            # (8 for the two planes of 2-bit codes), half of that with the sparse one
+            factor = None
+            if name.startswith("onehot_mfma"):
+                factor = 8 if bits == 2 else nlev
+            elif name.startswith("onehot_smfmac"):
+                factor = nlev // 2
             report.append({"bits": bits, "workload_shape": w.name, "variant": variant, "kernel": name,
                            "us": round(ms * 1e3, 3), "gops": round(tops * 1e3, 1),
-                           "frac_int8_mfma_peak": round((8 if bits == 2 else nlev) * tops / INT8_MFMA_PEAK_TOPS, 4)
-                           if name.startswith("onehot_mfma") else None})
+                           "frac_int8_mfma_peak": None if factor is None else round(factor * tops / INT8_MFMA_PEAK_TOPS, 4)})
     return report
 
 

@@ -260,7 +260,7 @@ int64_t dg_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad)
 
 namespace {
 
-enum class Pick { Perm, Lds, LdsF32, Mfma, SmallN, Lut65k, OneHot, Sparse, Unsupported };
+enum class Pick { Perm, Lds, LdsF32, Mfma, SmallN, Lut65k, OneHot, Sparse, Sparse4, Unsupported };
 
 Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
 {
@@ -269,8 +269,12 @@ Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
         return (variant == DG_KERNEL_AUTO || variant == DG_KERNEL_LDS) ? Pick::LdsF32 : Pick::Unsupported;
     if (lut->bits != 2) {
         if (variant == DG_KERNEL_LDS) return Pick::Lds;
-        if (variant == DG_KERNEL_AUTO) return dg_onehot_supports(lut, p) ? Pick::OneHot : Pick::Lds;
+        if (variant == DG_KERNEL_AUTO) {
+            if (dg_sparse4_preferred(lut, p)) return Pick::Sparse4;
+            return dg_onehot_supports(lut, p) ? Pick::OneHot : Pick::Lds;
+        }
         if (variant == DG_KERNEL_ONEHOT_MFMA && dg_onehot_supports(lut, p)) return Pick::OneHot;
+        if (variant == DG_KERNEL_ONEHOT_SMFMAC && dg_sparse4_supports(lut, p)) return Pick::Sparse4;
         return Pick::Unsupported;
     }
     switch (variant) {
@@ -307,6 +311,7 @@ dg_status run(const dg_lut *lut, const DgProblem &p, dg_kernel variant, hipStrea
     case Pick::Lut65k: return dg_launch_lut65k(lut, p, stream);
     case Pick::OneHot: return dg_launch_onehot(lut, p, stream);
     case Pick::Sparse: return dg_launch_sparse(lut, p, stream);
+    case Pick::Sparse4: return dg_launch_sparse4(lut, p, stream);
     case Pick::Unsupported: break;
     }
     return dg_fail(DG_ERR_UNSUPPORTED,
@@ -325,6 +330,7 @@ const char *pick_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case Pick::Lut65k: return "lut65k";
     case Pick::OneHot: return dg_onehot_config_name(lut, p);
     case Pick::Sparse: return dg_sparse_config_name(lut, p);
+    case Pick::Sparse4: return "onehot_smfmac4_64x128";
     case Pick::Unsupported: break;
     }
     return "unsupported";

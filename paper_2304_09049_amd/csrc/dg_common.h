@@ -74,5 +74,8 @@ bool dg_sparse_supports(const dg_lut *lut, const DgProblem &p);
 bool dg_sparse_preferred(const dg_lut *lut, const DgProblem &p);     // AUTO's choice between the two one-hot kernels
 dg_status dg_launch_sparse(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 const char *dg_sparse_config_name(const dg_lut *lut, const DgProblem &p);
+bool dg_sparse4_supports(const dg_lut *lut, const DgProblem &p);      // 4-bit codes on the sparse instruction
+bool dg_sparse4_preferred(const dg_lut *lut, const DgProblem &p);
+dg_status dg_launch_sparse4(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 bool dg_smalln_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_smalln(const dg_lut *lut, const DgProblem &p, hipStream_t stream);

@@ -242,6 +242,51 @@ dg_status dg_launch_sparse(const dg_lut *lut, const DgProblem &p0, hipStream_t s
     return dg_check_launch("onehot_mfma_kernel<20>");
 }
 
+// ---- 4-bit codes on the sparse instruction (dg_sparse4_kernel.h): 64 x 128 tiles only, so large layers only
+
+namespace {
+
+int sparse4_ch(const DgProblem &t) { return (t.Cin / 2) % 16 == 0 ? 2 : 1; }
+
+bool sparse4_takes(const dg_lut *lut, const DgProblem &p)
+{
+    if (lut->dtype == DG_LUT_F32 || lut->bits != 4 || !fits_int8(lut)) return false;
+    if (p.Cin % 16 != 0) return false;                                 // a lane half reads whole words of one tap
+    if (sparse_transposes(p) && !sparse_can_transpose(p)) return false;
+    const DgProblem t = sparse_problem(p);
+    const int ch = sparse4_ch(t);
+    if ((uintptr_t)t.Wp % (4 * ch) != 0 || (uintptr_t)t.Xp % (4 * ch) != 0) return false;
+    return tile_count(t, 2, 4) <= INT32_MAX;
+}
+
+}   // namespace
+
+bool dg_sparse4_supports(const dg_lut *lut, const DgProblem &p) { return sparse4_takes(lut, p); }
+
+// AUTO: where the 64 x 128 tiles give at least every second SIMD a wavefront (measured: 784 tiles 22 % faster than the
+// dense-instruction kernel, 196 tiles 12 % slower; that kernel's narrower tiles and split-K form serve the smaller layers)
+bool dg_sparse4_preferred(const dg_lut *lut, const DgProblem &p)
+{
+    return sparse4_takes(lut, p) && tile_count(sparse_problem(p), 2, 4) >= 512 && getenv("DG_ONEHOT_PLAN") == nullptr;
+}
+
+dg_status dg_launch_sparse4(const dg_lut *lut, const DgProblem &p0, hipStream_t stream)
+{
+    const bool transposed = sparse_transposes(p0);
+    const DgProblem p = sparse_problem(p0);
+    uint32_t rows[16][4];                                  // rows[w] = T[w][0..15] (the transposed problem swaps the codes)
+    for (int w = 0; w < 16; ++w)
+        for (int i = 0; i < 4; ++i) {
+            rows[w][i] = 0;
+            for (int b = 0; b < 4; ++b) {
+                const int v = 4 * i + b, T = transposed ? lut->entry[(v << 4) | w] : lut->entry[(w << 4) | v];
+                rows[w][i] |= (uint32_t)(uint8_t)(int8_t)T << (8 * b);
+            }
+        }
+    dgoh::unit_sparse4(p, rows, sparse4_ch(p), stream);
+    return dg_check_launch("sparse4_kernel");
+}
+
 bool dg_decode_supports(const dg_lut *lut, const DgProblem &p)
 {
     // the levels themselves are the MFMA operands: the table must be their outer product, with 2-bit codes

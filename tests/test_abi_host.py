@@ -184,7 +184,9 @@ def test_kernel_names_need_no_gpu():
     wide = dg.dg_build_lut((127, -128, 5, 0), (-128, 127, 1, 0), dg.DG_LUT_I16)
     assert dg.dg_gemm_kernel_name(wide, 8192, 8192, 8192) == "onehot_mfma_2p_32x128"
     t4 = dg.dg_build_lut_bits(4, list(range(-8, 8)), list(range(16)), dg.DG_LUT_I8)
-    assert dg.dg_gemm_kernel_name(t4, 256, 50176, 2304).startswith("onehot_mfma_64x")
+    assert dg.dg_gemm_kernel_name(t4, 256, 50176, 2304) == "onehot_smfmac4_64x128"      # large layers: the sparse instruction
+    assert dg.dg_gemm_kernel_name(t4, 256, 50176, 2304, "onehot_mfma").startswith("onehot_mfma_64x")
+    assert dg.dg_gemm_kernel_name(t4, 256, 1568, 2304).startswith("onehot_mfma_")
     assert dg.dg_gemm_kernel_name(t4, 256, 50176, 2304, "perm") == "unsupported"
 
 

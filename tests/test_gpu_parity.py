@@ -493,16 +493,19 @@ WIDE = {
 }
 
 
-@pytest.mark.parametrize("plan", ["auto", "lds", "split", "1", "2", "4", "7"])
+@pytest.mark.parametrize("plan", ["auto", "lds", "split", "1", "2", "4", "7", "sparse"])
 @pytest.mark.parametrize("bits", [3, 4])
 def test_wide_codes_gemm_and_conv(bits, plan, monkeypatch):
     """Sec. 3.3 / Table 2: 64- and 256-entry tables.  They run on the LDS kernel (every shape) and on the one-hot
-    matrix-core kernels (Cin % 16 == 0), whose every plan is forced in turn; the 2-bit-only kernels decline."""
+    matrix-core kernels (Cin % 16 == 0), whose every plan is forced in turn -- 4-bit codes also in the
+    sparse-instruction form; the 2-bit-only kernels decline."""
+    if plan == "sparse" and bits != 4:
+        pytest.skip("the sparse-instruction form exists for 2- and 4-bit codes")
     lw, la = WIDE[bits]
     nlev = 1 << bits
     rng = np.random.default_rng(50 + bits)
     lut = dg.dg_build_lut_bits(bits, lw, la, dg.DG_LUT_I8)
-    variant = plan if plan in ("auto", "lds") else "onehot_mfma"
+    variant = plan if plan in ("auto", "lds") else ("onehot_smfmac" if plan == "sparse" else "onehot_mfma")
     if variant == "onehot_mfma":
         monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
     for M, N, K in ((5, 7, 6), (64, 196, 576), (33, 130, 40), (70, 300, 64), (40, 1000, 96), (130, 257, 1024)):
@@ -512,9 +515,9 @@ def test_wide_codes_gemm_and_conv(bits, plan, monkeypatch):
         _assert_same(Ap.cpu().numpy().reshape(N, K // 2), oracle.pack_codes(Ac, bits), f"{bits}-bit pack")
         name = dg.dg_gemm_kernel_name(lut, M, N, K, variant)
         if K % 16 != 0:
-            assert name == ("lds" if variant != "onehot_mfma" else "unsupported")
+            assert name == ("lds" if variant in ("auto", "lds") else "unsupported")
         else:
-            assert name.startswith("lds" if variant == "lds" else "onehot_mfma")
+            assert name.startswith({"lds": "lds", "onehot_smfmac": "onehot_smfmac4"}.get(variant, "onehot_mfma"))
         if name == "unsupported":
             continue
         got = dg.dg_gemm_lut(lut, Wp, Ap, M, N, K, variant=variant)
