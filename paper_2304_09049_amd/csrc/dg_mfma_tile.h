@@ -87,14 +87,15 @@ __device__ __forceinline__ void dg_mfma_store_block(const DgProblem &p, const dg
     const int64_t base = (int64_t)col * col_stride + (int64_t)row0 * row_stride;
     const bool inside = (TR ? nb : mb) + 32 <= row_limit;              // (uniform over the wavefront)
 #pragma unroll
+    // (streaming stores: the output is written once and read by a later kernel, it has no business in this one's caches)
     for (int e = 0; e < 16; ++e) {
         const int k = 8 * (e / 4) + (e % 4);
         if (!inside && row0 + k >= row_limit) continue;
         const int64_t o = base + k * row_stride;
         if (p.scale)
-            p.Cf[o] = (float)acc[e] * (TR ? sc : p.scale[row0 + k]);
+            __builtin_nontemporal_store((float)acc[e] * (TR ? sc : p.scale[row0 + k]), p.Cf + o);
         else
-            p.C[o] = acc[e];
+            __builtin_nontemporal_store(acc[e], p.C + o);
     }
 }
 
