@@ -236,7 +236,8 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
  * packed_out_dev: device, dg_packed_activation_bytes(B*OH*OW, Cout) bytes, the public layout ([pixel][Cout/4]).
  * Every decision is taken in binary32, operation by operation, so the result equals dg_conv2d_lut followed by
  * dg_quantize_pack_activations bit for bit.  Needs Cout % 4 == 0 and a table and shape the one-hot matrix-core
- * kernel accepts (variant AUTO or ONEHOT_MFMA; otherwise DG_ERR_UNSUPPORTED -- run the two calls instead).
+ * kernel accepts (variant AUTO, ONEHOT_MFMA or ONEHOT_SMFMAC; otherwise DG_ERR_UNSUPPORTED -- run the two calls
+ * instead).
  * Errors: as dg_conv2d_lut; DG_ERR_SHAPE if Cout % 4 != 0; DG_ERR_BUFFER if packed_bytes is too small.
  */
 dg_status dg_conv2d_lut_requant(const dg_lut *lut, const void *Wp_dev, const void *Xp_dev,

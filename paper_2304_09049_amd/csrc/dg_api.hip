@@ -467,7 +467,9 @@ dg_status dg_conv2d_lut_requant(const dg_lut *lut, const void *Wp_dev, const voi
     p.q_scale = q_scale;
     p.q_zero = q_zero;
     p.q_lo = lo;
-    // the re-quantising epilogue lives in the one-hot matrix-core kernels
+    // the re-quantising epilogue lives in the one-hot matrix-core kernels (both instruction forms share it)
+    if (variant == DG_KERNEL_ONEHOT_SMFMAC && lut->bits == 2 && dg_sparse_supports(lut, p))
+        return dg_launch_sparse(lut, p, (hipStream_t)hip_stream);
     if ((variant != DG_KERNEL_AUTO && variant != DG_KERNEL_ONEHOT_MFMA) || lut->dtype == DG_LUT_F32 ||
         !dg_onehot_supports(lut, p))
         return dg_fail(DG_ERR_UNSUPPORTED, "%s: needs the one-hot matrix-core kernel (variant %d, Cin=%d, table range %d..%d)",

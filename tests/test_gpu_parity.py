@@ -425,14 +425,17 @@ def test_dequantize_equals_the_scale_epilogue():
 @pytest.mark.parametrize("plan", ["auto", "split", "1", "2", "4", "7", "2k2", "4k4"])
 def test_fused_layer_equals_convolution_then_quantise_pack(plan, monkeypatch):
     """dg_conv2d_lut_requant against the oracle's convolution -> scale epilogue -> Eq. 1 quantiser -> packing, byte for
-    byte, on every plan of the one-hot kernels; and against the library's own two-call path."""
+    byte, on every plan of the one-hot kernels (dense and sparse instruction); and against the library's own two-call
+    path."""
     if plan != "auto":
         monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
     rng = np.random.default_rng(31)
-    for table in ("signed_unsigned", "extreme_i16"):
+    for table, kernel in (("signed_unsigned", "onehot_mfma"), ("extreme_i16", "onehot_mfma"), ("nonuniform_i8", "onehot_smfmac")):
         lw, la, entry = LEVELS[table]
         if table == "extreme_i16" and "k" in plan:
             continue
+        if kernel == "onehot_smfmac" and plan.startswith("7"):
+            continue                                   # (the sparse-instruction form has no 64 x 224 tile)
         for (B, H, W, Cin, Cout, KH, KW, stride, pad) in [(2, 24, 24, 32, 68, 3, 3, (1, 1), (1, 1)),
                                                           (1, 30, 30, 128, 40, 3, 3, (2, 2), (1, 1)),
                                                           (3, 16, 16, 64, 36, 1, 1, (1, 1), (0, 0)),
@@ -447,10 +450,10 @@ def test_fused_layer_equals_convolution_then_quantise_pack(plan, monkeypatch):
                 codes = oracle.quantize_codes(y, float(qs), float(qz), lo, lo + 3)
                 want = oracle.pack_codes(codes.reshape(-1, Cout))
                 got = dg.dg_conv2d_lut_requant(case.lut, case.Wp, case.Ap, case.desc, case.scale, float(qs), float(qz), lo,
-                                               variant="onehot_mfma")
+                                               variant=kernel)
                 torch.cuda.synchronize()
                 _assert_same(got.cpu().numpy().reshape(-1, Cout // 4), want, f"fused layer {(B, H, W, Cin, Cout)} {table} {plan}")
-                yf = case.run("onehot_mfma", scale=True)
+                yf = case.run(kernel, scale=True)
                 two_calls = dg.dg_quantize_pack_activations(yf, yf.numel() // Cout, Cout, float(qs), float(qz), lo)
                 torch.cuda.synchronize()
                 assert torch.equal(got, two_calls)
