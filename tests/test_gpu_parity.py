@@ -607,3 +607,44 @@ def test_f32_table():
     with pytest.raises(dg.DgError) as e:
         dg.dg_conv2d_lut(lut, Wp, Xp, desc, variant="perm")
     assert e.value.status == 5
+
+
+def test_graph_replays_equal_eager_launches():
+    """bench.py replays its steps from a HIP graph: a captured step (pack, then convolution; and the fused layer) must
+    give, on every replay and with other work between the replays, what the same calls give launched one by one -- on a
+    small layer (split-K kernel, LDS sums zeroed inside the kernel) and on one large enough for the sparse-instruction
+    kernel."""
+    for (B, H, W, Cin, Cout, KH, KW, stride, pad) in [(1, 28, 28, 64, 64, 3, 3, (1, 1), (1, 1)),
+                                                      (16, 56, 56, 64, 128, 1, 1, (1, 1), (0, 0))]:
+        c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=B + H + Cout, scale=True)
+        case = GpuCase(c)
+        assert case.kernel_name().startswith("onehot_mfma_splitk" if B == 1 else "onehot_smfmac_")
+        dev = case.Wp.device
+        codes = torch.from_numpy(c.Ac).to(dev)
+        want = oracle.scale_epilogue_nhwc(oracle.conv2d(c.Wc, c.Ac, c.levels_w, c.levels_a, stride=stride, pad=pad), c.scale)
+        Xp = torch.empty_like(case.Ap)
+        y = torch.empty(want.shape, dtype=torch.float32, device=dev)
+        q = torch.empty(B * want.shape[1] * want.shape[2] * Cout // 4, dtype=torch.uint8, device=dev)
+
+        def step():
+            dg.dg_pack_activations(codes, B * H * W, Cin, out=Xp)
+            dg.dg_conv2d_lut(case.lut, case.Wp, Xp, case.desc, out=y, scale=case.scale)
+            dg.dg_conv2d_lut_requant(case.lut, case.Wp, Xp, case.desc, case.scale, 8.0, 0.5, 0, out=q)
+
+        step()
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), want)
+        q_eager = q.clone()
+        side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        for replay in range(4):
+            Xp.zero_(), y.fill_(-1.0), q.fill_(255)                       # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(y.cpu().numpy(), want), f"replay {replay} of {(B, H, W, Cin, Cout)}"
+            assert torch.equal(q, q_eager), f"replay {replay}: fused layer"
+            assert torch.equal(Xp, case.Ap), f"replay {replay}: packed activations"
