@@ -648,3 +648,29 @@ def test_graph_replays_equal_eager_launches():
             assert np.array_equal(y.cpu().numpy(), want), f"replay {replay} of {(B, H, W, Cin, Cout)}"
             assert torch.equal(q, q_eager), f"replay {replay}: fused layer"
             assert torch.equal(Xp, case.Ap), f"replay {replay}: packed activations"
+
+
+def test_four_bit_auto_takes_the_sparse_kernel_on_large_layers():
+    """AUTO's choice for 4-bit tables from 512 tiles of 64 x 128 up is the sparse-instruction kernel: a GEMM and an NHWC
+    convolution of that size against the oracle (the forced-variant tests above only reach it on small shapes)."""
+    lw, la = WIDE[4]
+    lut = dg.dg_build_lut_bits(4, lw, la, dg.DG_LUT_I8)
+    rng = np.random.default_rng(77)
+    M, N, K = 130, 32770, 48                                # ragged in M and N; 3 x 257 tiles
+    Wc, Ac = wl.draw_codes(rng, (M, K), nlev=16), wl.draw_codes(rng, (N, K), nlev=16)
+    Wp = dg.dg_pack_codes_bits(torch.from_numpy(Wc).cuda(), M, K, 4)
+    Ap = dg.dg_pack_codes_bits(torch.from_numpy(Ac).cuda(), N, K, 4)
+    assert dg.dg_gemm_kernel_name(lut, M, N, K) == "onehot_smfmac4_64x128"
+    got = dg.dg_gemm_lut(lut, Wp, Ap, M, N, K)
+    torch.cuda.synchronize()
+    _assert_same(got.cpu().numpy(), oracle.gemm(Wc, Ac, lw, la), "4-bit gemm, AUTO")
+    B, H, W, Cin, Cout = 16, 56, 56, 32, 96
+    Wc = wl.draw_codes(rng, (Cout, 3, 3, Cin), nlev=16)
+    Xc = wl.draw_codes(rng, (B, H, W, Cin), nlev=16)
+    Wp = dg.dg_pack_codes_bits(torch.from_numpy(Wc).cuda(), Cout, 9 * Cin, 4)
+    Xp = dg.dg_pack_codes_bits(torch.from_numpy(Xc).cuda(), B * H * W, Cin, 4)
+    desc = dg.conv_desc(B, H, W, Cin, Cout, 3, 3, (1, 1), (1, 1))
+    assert dg.dg_conv_kernel_name(lut, desc) == "onehot_smfmac4_64x128"
+    y = dg.dg_conv2d_lut(lut, Wp, Xp, desc)
+    torch.cuda.synchronize()
+    _assert_same(y.cpu().numpy(), oracle.conv2d(Wc, Xc, lw, la, stride=(1, 1), pad=(1, 1)), "4-bit conv, AUTO")
