@@ -310,8 +310,8 @@ def stage_kernels(torch, w):
 def wide_code_kernels(torch, w, use_graph):
     """Tables beyond the 16 int8 entries of the headline path, on the shape of workload `w` (a convolution): 2-bit codes
     with int16 entries (two int8 planes), and the 3- and 4-bit tables of Sec. 3.3 / Table 2; each on the one-hot
-    matrix-core kernel AUTO picks (4-bit codes: the sparse-instruction form, so also the dense one) and on the plain LDS
-    kernel.  The MFMA fraction counts the multiply-accumulates performed."""
+    matrix-core kernel AUTO picks (two planes and 4-bit codes: a sparse-instruction form, so also the dense one) and on
+    the plain LDS kernel.  The MFMA fraction counts the multiply-accumulates performed."""
     from paper_2304_09049_amd import binding as dg
     dev = torch.device("cuda:0")
     report = []
@@ -342,7 +342,7 @@ def wide_code_kernels(torch, w, use_graph):
             if name.startswith("onehot_mfma"):
                 factor = 8 if bits == 2 else nlev
             elif name.startswith("onehot_smfmac"):
-                factor = nlev // 2
+                factor = 4 if bits == 2 else nlev // 2
             report.append({"bits": bits, "workload_shape": w.name, "variant": variant, "kernel": name,
                            "us": round(ms * 1e3, 3), "gops": round(tops * 1e3, 1),
                            "frac_int8_mfma_peak": None if factor is None else round(factor * tops / INT8_MFMA_PEAK_TOPS, 4)})

@@ -170,8 +170,9 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *   ONEHOT_SMFMAC  the same selection on the sparse matrix instruction, at half the matrix work: a one-hot run
  *            of four bytes is 1-of-4 sparse, so the activation operand is a constant and its index register
  *            is the packed code word itself -- the instruction's index multiplexer does the table lookup;
- *            2-bit codes (Cin % 32 == 0) or 4-bit codes (Cin % 16 == 0), int8 entries; outputs whose
- *            stride-1 axis is the channel axis (NHWC), or plain GEMMs without scale (run transposed)
+ *            2-bit codes (Cin % 32 == 0; entries up to 32639, those beyond int8 as two planes under the
+ *            same index registers) or 4-bit codes (Cin % 16 == 0, int8 entries); outputs whose stride-1
+ *            axis is the channel axis (NHWC), or plain GEMMs without scale (run transposed)
  * A variant that cannot run the given shape or table returns DG_ERR_UNSUPPORTED.
  */
 typedef enum {

@@ -260,7 +260,7 @@ int64_t dg_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad)
 
 namespace {
 
-enum class Pick { Perm, Lds, LdsF32, Mfma, SmallN, Lut65k, OneHot, Sparse, Sparse4, Unsupported };
+enum class Pick { Perm, Lds, LdsF32, Mfma, SmallN, Lut65k, OneHot, Sparse, Sparse4, Sparse2p, Unsupported };
 
 Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
 {
@@ -284,7 +284,9 @@ Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case DG_KERNEL_SMALLN: return dg_smalln_supports(lut, p) ? Pick::SmallN : Pick::Unsupported;
     case DG_KERNEL_LUT65K: return dg_lut65k_supports(lut, p) ? Pick::Lut65k : Pick::Unsupported;
     case DG_KERNEL_ONEHOT_MFMA: return dg_onehot_supports(lut, p) ? Pick::OneHot : Pick::Unsupported;
-    case DG_KERNEL_ONEHOT_SMFMAC: return dg_sparse_supports(lut, p) ? Pick::Sparse : Pick::Unsupported;
+    case DG_KERNEL_ONEHOT_SMFMAC:
+        if (dg_sparse2p_supports(lut, p)) return Pick::Sparse2p;
+        return dg_sparse_supports(lut, p) ? Pick::Sparse : Pick::Unsupported;
     case DG_KERNEL_AUTO:
         // AUTO stays within the table kernels: the decode-and-multiply matrix-core kernel is a comparison only.
         // one or two columns: K across the lanes of a wavefront streams the weights once at full width
@@ -292,6 +294,7 @@ Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
         // int8 tables: selecting entries with one-hot operands on the matrix cores outruns the permute loop at every
         // size measured (1.5x on a 0.2 GOP layer, 5x - 10x from 3 GOP upwards)
         // (large layers: the same selection on the sparse instruction, about half the matrix work)
+        if (dg_sparse2p_preferred(lut, p)) return Pick::Sparse2p;
         if (dg_onehot_supports(lut, p)) return dg_sparse_preferred(lut, p) ? Pick::Sparse : Pick::OneHot;
         if (p.N <= 32 && p.K >= 1024 && dg_smalln_supports(lut, p)) return Pick::SmallN;
         if (dg_perm_supports(lut, p)) return Pick::Perm;
@@ -312,6 +315,7 @@ dg_status run(const dg_lut *lut, const DgProblem &p, dg_kernel variant, hipStrea
     case Pick::OneHot: return dg_launch_onehot(lut, p, stream);
     case Pick::Sparse: return dg_launch_sparse(lut, p, stream);
     case Pick::Sparse4: return dg_launch_sparse4(lut, p, stream);
+    case Pick::Sparse2p: return dg_launch_sparse2p(lut, p, stream);
     case Pick::Unsupported: break;
     }
     return dg_fail(DG_ERR_UNSUPPORTED,
@@ -331,6 +335,7 @@ const char *pick_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case Pick::OneHot: return dg_onehot_config_name(lut, p);
     case Pick::Sparse: return dg_sparse_config_name(lut, p);
     case Pick::Sparse4: return "onehot_smfmac4_64x128";
+    case Pick::Sparse2p: return "onehot_smfmac_2p_32x128";
     case Pick::Unsupported: break;
     }
     return "unsupported";
@@ -470,6 +475,8 @@ dg_status dg_conv2d_lut_requant(const dg_lut *lut, const void *Wp_dev, const voi
     // the re-quantising epilogue lives in the one-hot matrix-core kernels (both instruction forms share it)
     if (variant == DG_KERNEL_ONEHOT_SMFMAC && lut->bits == 2 && dg_sparse_supports(lut, p))
         return dg_launch_sparse(lut, p, (hipStream_t)hip_stream);
+    if (variant == DG_KERNEL_ONEHOT_SMFMAC && dg_sparse2p_supports(lut, p))
+        return dg_launch_sparse2p(lut, p, (hipStream_t)hip_stream);
     if ((variant != DG_KERNEL_AUTO && variant != DG_KERNEL_ONEHOT_MFMA) || lut->dtype == DG_LUT_F32 ||
         !dg_onehot_supports(lut, p))
         return dg_fail(DG_ERR_UNSUPPORTED, "%s: needs the one-hot matrix-core kernel (variant %d, Cin=%d, table range %d..%d)",

@@ -77,5 +77,8 @@ const char *dg_sparse_config_name(const dg_lut *lut, const DgProblem &p);
 bool dg_sparse4_supports(const dg_lut *lut, const DgProblem &p);      // 4-bit codes on the sparse instruction
 bool dg_sparse4_preferred(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_sparse4(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+bool dg_sparse2p_supports(const dg_lut *lut, const DgProblem &p);     // two-plane 2-bit tables on the sparse instruction
+bool dg_sparse2p_preferred(const dg_lut *lut, const DgProblem &p);
+dg_status dg_launch_sparse2p(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 bool dg_smalln_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_smalln(const dg_lut *lut, const DgProblem &p, hipStream_t stream);

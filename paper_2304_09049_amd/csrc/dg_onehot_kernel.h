@@ -764,6 +764,7 @@ DGOH_UNIT(0, 0, 1) DGOH_UNIT(0, 0, 2) DGOH_UNIT(0, 0, 4) DGOH_UNIT(0, 1, 1) DGOH
 DGOH_UNIT_SPLIT(2, 0) DGOH_UNIT_SPLIT(2, 1) DGOH_UNIT_SPLIT(3, 0) DGOH_UNIT_SPLIT(3, 1) DGOH_UNIT_SPLIT(4, 0)
 DGOH_UNIT_SPLIT(4, 1) DGOH_UNIT_SPLIT(22, 0) DGOH_UNIT_SPLIT(22, 1) DGOH_UNIT_SPLIT(0, 0) DGOH_UNIT_SPLIT(0, 1) DGOH_UNIT_SPLIT(20, 1)
 void unit_sparse4(const DgProblem &, const uint32_t (&)[16][4], int, hipStream_t);      // dg_sparse4_kernel.h
+void unit_sparse2p(const DgProblem &, const uint32_t (&)[2][4], int, hipStream_t);      // dg_sparse2p_kernel.h
 #undef DGOH_UNIT
 #undef DGOH_UNIT_SPLIT
 

@@ -287,6 +287,54 @@ dg_status dg_launch_sparse4(const dg_lut *lut, const DgProblem &p0, hipStream_t 
     return dg_check_launch("sparse4_kernel");
 }
 
+// ---- 2-bit codes with entries beyond int8 on the sparse instruction (dg_sparse2p_kernel.h): 32 x 128 tiles only
+
+namespace {
+
+int sparse2p_ch(const DgProblem &t) { return (t.Cin / 4) % 16 == 0 ? 2 : 1; }    // (4 words per chunk would spill)
+
+bool sparse2p_takes(const dg_lut *lut, const DgProblem &p)
+{
+    if (lut->dtype == DG_LUT_F32 || lut->bits != 2 || fits_int8(lut) || lut->max_entry > 127 * 256 + 127) return false;
+    if (p.Cin % 32 != 0) return false;                                 // a lane half reads whole words of one tap
+    if (sparse_transposes(p) && !sparse_can_transpose(p)) return false;
+    const DgProblem t = sparse_problem(p);
+    const int ch = sparse2p_ch(t);
+    if ((uintptr_t)t.Wp % (4 * ch) != 0 || (uintptr_t)t.Xp % (4 * ch) != 0) return false;
+    return tile_count(t, 1, 4) <= INT32_MAX;
+}
+
+}   // namespace
+
+bool dg_sparse2p_supports(const dg_lut *lut, const DgProblem &p) { return sparse2p_takes(lut, p); }
+
+// AUTO: where the 32 x 128 tiles give every SIMD a wavefront and K is long enough to amortise the tile's stores
+// (measured: 20 - 27 % faster than the dense-instruction kernel from 1568 tiles with K >= 576, even at 784 tiles, 23 %
+// slower at K = 64; that kernel's narrower tiles and split-K form serve the smaller layers)
+bool dg_sparse2p_preferred(const dg_lut *lut, const DgProblem &p)
+{
+    return sparse2p_takes(lut, p) && tile_count(sparse_problem(p), 1, 4) >= 1024 && p.K >= 512 &&
+           getenv("DG_ONEHOT_PLAN") == nullptr;
+}
+
+dg_status dg_launch_sparse2p(const dg_lut *lut, const DgProblem &p0, hipStream_t stream)
+{
+    const bool transposed = sparse_transposes(p0);
+    const DgProblem p = sparse_problem(p0);
+    uint32_t rows[2][4];                                   // rows[plane][w] = plane(T[w][0..3]) (transposed: codes swapped)
+    for (int w = 0; w < 4; ++w) {
+        rows[0][w] = rows[1][w] = 0;
+        for (int v = 0; v < 4; ++v) {
+            const int T = transposed ? lut->entry[(v << 2) | w] : lut->entry[(w << 2) | v];
+            const int lo = ((T + 128) & 255) - 128, hi = (T - lo) / 256;
+            rows[0][w] |= (uint32_t)(uint8_t)(int8_t)lo << (8 * v);
+            rows[1][w] |= (uint32_t)(uint8_t)(int8_t)hi << (8 * v);
+        }
+    }
+    dgoh::unit_sparse2p(p, rows, sparse2p_ch(p), stream);
+    return dg_check_launch("sparse2p_kernel");
+}
+
 bool dg_decode_supports(const dg_lut *lut, const DgProblem &p)
 {
     // the levels themselves are the MFMA operands: the table must be their outer product, with 2-bit codes

@@ -182,7 +182,9 @@ def test_kernel_names_need_no_gpu():
     assert dg.dg_gemm_kernel_name(lut, 64, 196, 576, "mfma_i8").startswith("mfma_i8_splitk_s")
     assert dg.dg_gemm_kernel_name(lut, 8192, 8192, 8192, "mfma_i8") == "mfma_i8_128x128"
     wide = dg.dg_build_lut((127, -128, 5, 0), (-128, 127, 1, 0), dg.DG_LUT_I16)
-    assert dg.dg_gemm_kernel_name(wide, 8192, 8192, 8192) == "onehot_mfma_2p_32x128"
+    assert dg.dg_gemm_kernel_name(wide, 8192, 8192, 8192) == "onehot_smfmac_2p_32x128"   # large layers: the sparse instruction
+    assert dg.dg_gemm_kernel_name(wide, 8192, 8192, 8192, "onehot_mfma") == "onehot_mfma_2p_32x128"
+    assert dg.dg_gemm_kernel_name(wide, 256, 1568, 2304).startswith("onehot_mfma_2p_")
     t4 = dg.dg_build_lut_bits(4, list(range(-8, 8)), list(range(16)), dg.DG_LUT_I8)
     assert dg.dg_gemm_kernel_name(t4, 256, 50176, 2304) == "onehot_smfmac4_64x128"      # large layers: the sparse instruction
     assert dg.dg_gemm_kernel_name(t4, 256, 50176, 2304, "onehot_mfma").startswith("onehot_mfma_64x")

@@ -193,6 +193,44 @@ def test_onehot_every_plan(plan, table, monkeypatch):
         assert np.array_equal(got, oracle.scale_epilogue_nhwc(acc, c.scale)), f"scaled conv plan {plan}"
 
 
+def test_two_plane_tables_on_the_sparse_instruction():
+    """Entries beyond int8 through the sparse-instruction kernel (two int8 planes selected by the same index registers):
+    GEMMs with ragged edges in both output layouts, convolutions with padding and stride under a table with no zero
+    activation level, int32 and scaled fp32 output, chunk widths of one and two words."""
+    kernel = "onehot_smfmac"
+    glw, gla, gentry = LEVELS["extreme_i16"]
+    for (M, N, K) in [(70, 1000, 96), (130, 777, 64), (33, 250, 1024), (1, 129, 32), (300, 5, 128)]:
+        inp = wl.small_gemm(M, N, K, seed=M + N + K)
+        case = GpuCase(inp, levels=(glw, gla), entry=gentry)
+        assert case.kernel_name(kernel) == "onehot_smfmac_2p_32x128"
+        want = oracle.gemm(inp.Wc, inp.Ac, glw, gla)
+        _assert_same(case.run(kernel).cpu().numpy(), want, f"gemm {(M, N, K)}")
+        out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
+        dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant=kernel, strides=(1, M))
+        torch.cuda.synchronize()
+        _assert_same(out.cpu().numpy(), want.T.copy(), f"gemm {(M, N, K)} column-major")
+    lw, la, entry = (127, -128, 5, 3), (-128, 127, 1, 2), dg.DG_LUT_I16
+    for (B, H, W, Cin, Cout, KH, KW, stride, pad) in [(2, 24, 24, 32, 70, 3, 3, (1, 1), (1, 1)),
+                                                      (1, 30, 30, 128, 40, 3, 3, (2, 2), (1, 1)),
+                                                      (3, 16, 16, 64, 33, 1, 1, (1, 1), (0, 0)),
+                                                      (1, 20, 20, 64, 96, 5, 5, (1, 1), (2, 2)),
+                                                      (1, 7, 9, 96, 3, 3, 3, (1, 1), (2, 2))]:
+        c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        assert case.kernel_name(kernel) == "onehot_smfmac_2p_32x128"
+        acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
+        _assert_same(case.run(kernel).cpu().numpy(), acc, f"conv {(B, H, W, Cin, Cout)}")
+        got = case.run(kernel, scale=True).cpu().numpy()
+        assert np.array_equal(got, oracle.scale_epilogue_nhwc(acc, c.scale)), "scaled conv"
+    # AUTO takes it where its 32 x 128 tiles fill the chip, and the dense-instruction kernel below that
+    big = GpuCase(wl.small_conv(16, 56, 56, 64, 96, 3, 3, (1, 1), (1, 1), seed=5), levels=(lw, la), entry=entry)
+    assert big.kernel_name("auto") == "onehot_smfmac_2p_32x128"
+    want = oracle.conv2d(big.inp.Wc, big.inp.Ac, lw, la, stride=(1, 1), pad=(1, 1))
+    _assert_same(big.run("auto").cpu().numpy(), want, "AUTO on a large two-plane layer")
+    small = GpuCase(wl.small_conv(1, 14, 14, 32, 96, 1, 1, (1, 1), (0, 0), seed=5), levels=(lw, la), entry=entry)
+    assert small.kernel_name("auto").startswith("onehot_mfma_2p_")
+
+
 def test_random_convolution_shapes():
     """Seeded random convolution geometries (image, filter, stride, padding, channel counts, batch) through AUTO and
     every variant that accepts them: the oracle is the plain nested loop, so any disagreement is a kernel indexing bug."""
@@ -430,8 +468,11 @@ def test_fused_layer_equals_convolution_then_quantise_pack(plan, monkeypatch):
     if plan != "auto":
         monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
     rng = np.random.default_rng(31)
-    for table, kernel in (("signed_unsigned", "onehot_mfma"), ("extreme_i16", "onehot_mfma"), ("nonuniform_i8", "onehot_smfmac")):
+    for table, kernel in (("signed_unsigned", "onehot_mfma"), ("extreme_i16", "onehot_mfma"), ("nonuniform_i8", "onehot_smfmac"),
+                          ("extreme_i16", "onehot_smfmac")):
         lw, la, entry = LEVELS[table]
+        if table == "extreme_i16" and kernel == "onehot_smfmac" and plan != "auto":
+            continue                                   # (its two-plane form has one tile)
         if table == "extreme_i16" and "k" in plan:
             continue
         if kernel == "onehot_smfmac" and plan.startswith("7"):
