@@ -79,3 +79,25 @@ def test_sampled_output(name):
         flat = got.reshape(-1)[pos]
         assert np.array_equal(flat, want), f"{name} {variant}: {np.count_nonzero(flat != want)} sampled outputs differ"
     assert "auto" in ran
+
+
+@pytest.mark.parametrize("name", ["vgg16_conv3x3_b16", "gemm_8192x8192x8192_i16"])
+def test_sampled_output_two_plane_table(name):
+    """The same full-size shapes under a table with entries beyond int8 (levels up to +-127, no zero activation
+    level): AUTO's sparse-instruction two-plane kernel and the dense-instruction one, against sampled oracle outputs."""
+    from paper_2304_09049_amd import binding as dg
+    w = wl.CONFIGS[name]
+    inp = wl.make_inputs(w)
+    lw, la = (127, -128, 5, 3), (-128, 127, 1, 2)
+    case = GpuCase(inp, levels=(lw, la), entry=dg.DG_LUT_I16)
+    assert case.kernel_name("auto") == "onehot_smfmac_2p_32x128"
+    assert case.kernel_name("onehot_mfma").startswith("onehot_mfma_2p_")
+    rng = np.random.default_rng(321)
+    pos = _border_heavy_positions(w, rng, int(min(200000, 3e9 // w.K)))
+    if w.kind == "conv":
+        want = oracle.conv2d_sampled(inp.Wc, inp.Ac, lw, la, pos, stride=w.stride, pad=w.pad)
+    else:
+        want = oracle.gemm_sampled(inp.Wc, inp.Ac, lw, la, pos // w.N, pos % w.N)
+    for variant in ("auto", "onehot_mfma"):
+        flat = case.run(variant).cpu().numpy().reshape(-1)[pos]
+        assert np.array_equal(flat, want), f"{name} {variant}: {np.count_nonzero(flat != want)} sampled outputs differ"
