@@ -2,10 +2,13 @@
 """Benchmark of the 2-bit lookup-table convolution on one MI355X.
 
 One "step" is one pass of the run-time hot path over one batch of synthetic codes already resident in
-HBM: pack the activation codes four per byte (dg_pack_activations), then the table convolution / GEMM with
-its epilogue (dg_conv2d_lut / dg_gemm_lut).  The table and the packed weights are built once, before the
-timed region (the paper packs weights offline, Sec. 5.2).  Steps are replayed from a HIP graph so that the
-host's launch cost does not cap a microsecond-scale kernel.
+HBM: pack the activation codes four per byte, then the table convolution / GEMM with its epilogue.  A
+convolution goes through the one-call entry point dg_conv2d_lut_codes, which on small layers (the headline
+one) runs a single kernel that packs the codes in registers as it loads them, and on the others the packing
+kernel followed by the convolution kernel; a GEMM is dg_pack_activations + dg_gemm_lut.  The two-call time
+of the same work is reported beside it.  The table and the packed weights are built once, before the timed
+region (the paper packs weights offline, Sec. 5.2).  Steps are replayed from a HIP graph so that the host's
+launch cost does not cap a microsecond-scale kernel.
 
 Prints ONE JSON line.  `value` = 2*M*N*K / time per step, in GOPS, for the headline workload
 (ResNet18-style 3x3 convolution, batch 1, 56x56x64 -> 64, fp32 scale epilogue).
@@ -37,6 +40,7 @@ PERM_ALU_PEAK_TOPS = VALU_LANE_INSTR_PER_S * (4 / 1.5) * 2 / 1e12
 # Keyed by (workload, kernel name); a kernel or workload that was not profiled reports null.
 MEASURED_TRAFFIC_KIB = {
     ("resnet18_conv3x3_b1", "onehot_mfma_splitk_s9"): (230.7 * 2.0, 784.0),
+    ("resnet18_conv3x3_b1", "codes_onehot_mfma_splitk_s9"): None,
     ("vgg16_conv3x3_b16", "onehot_mfma_64x128"): (4607.8 * 2.0, 50176.0),
     ("vgg16_conv3x3_b16", "onehot_smfmac_64x128"): (4430.8 * 2.0, 50176.0),
     ("gemm_8192x1x8192_i16", "smalln"): (8251.9 * 2.0, 32.0),
@@ -106,8 +110,23 @@ class Runner:
                                 scale=self.scale, variant=v)
 
     def step(self):
+        """The whole hot path on the resident codes: a convolution through the one-call entry point, which packs inside
+        the convolution kernel on small layers and runs the packing kernel first on the others; a GEMM as two calls."""
+        if self.desc is not None:
+            self.dg.dg_conv2d_lut_codes(self.lut, self.Wp, self.codes, self.desc, work=self.Ap, out=self.out,
+                                        scale=self.scale, variant=self.variant)
+        else:
+            self.two_calls()
+
+    def two_calls(self):
         self.pack()
         self.kernel()
+
+    def step_kernel_name(self):
+        """The convolution / GEMM kernel of a step ("codes_..." when it does the packing itself)."""
+        if self.desc is not None:
+            return self.dg.dg_conv_codes_kernel_name(self.lut, self.desc, self.variant)
+        return self.kernel_name()
 
     def make_cold_weights(self, total_bytes=640 << 20):
         """Copies of the packed weights that together exceed the 256 MB last-level cache."""
@@ -198,7 +217,7 @@ def mfma_ops_factor(name):
     (one operand byte per table column); on the sparse instruction, which skips the half of them that its index says
     are zero, over 2K (so it too is priced against the DENSE peak); the decode-and-multiply comparison kernel over K;
     table kernels on the VALU issue none."""
-    if name.startswith("onehot_mfma"):
+    if name.startswith("onehot_mfma") or name.startswith("codes_onehot_mfma"):
         return 4
     if name.startswith("onehot_smfmac"):
         return 2
@@ -207,10 +226,17 @@ def mfma_ops_factor(name):
     return None
 
 
+def algorithmic_bytes(w, name):
+    """Bytes a launch of kernel `name` has to move: the workload's packed operands and output; a kernel that reads the
+    activation codes one per byte reads four times the packed activations."""
+    extra = 3 * (w.B * w.H * w.W * w.Cin // 4) if name.startswith("codes_") else 0
+    return w.algorithmic_bytes + extra
+
+
 def kernel_report(w, ms, name):
     """Achieved rates of one kernel launch of duration `ms` against the three ceilings."""
     gops = w.ops / (ms * 1e-3) / 1e9
-    gbs = w.algorithmic_bytes / (ms * 1e-3) / 1e9
+    gbs = algorithmic_bytes(w, name) / (ms * 1e-3) / 1e9
     f = mfma_ops_factor(name)
     return {
         "kernel": name, "us": round(ms * 1e3, 3), "gops": round(gops, 1), "algorithmic_GBps": round(gbs, 1),
@@ -227,25 +253,26 @@ def roofline_object(w, ms, name):
     """The roofline entry of the dominant kernel.  Matrix-core kernels: int8 MFMA operations issued (4 per effective
     operation for the one-hot table kernel) against the dense int8 peak.  VALU table kernels: HBM when the HBM time
     of the algorithmic bytes exceeds the ALU time of the products at the permute kernel's issue ceiling, else ALU."""
-    t_hbm = w.algorithmic_bytes / (HBM_PEAK_GBS * 1e9)
+    alg = algorithmic_bytes(w, name)
+    t_hbm = alg / (HBM_PEAK_GBS * 1e9)
     t_alu = w.ops / (PERM_ALU_PEAK_TOPS * 1e12)
     f = mfma_ops_factor(name)
     if f is not None:
         ach = f * w.ops / (ms * 1e-3) / 1e12
         return {"bound": "mfma", "achieved": round(ach, 3), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TFLOP/s",
                 "frac": round(ach / INT8_MFMA_PEAK_TOPS, 5), "traffic": measured_traffic(w, name), "kernel": name,
-                "algorithmic_bytes": w.algorithmic_bytes, "effective_tops": round(w.ops / (ms * 1e-3) / 1e12, 3),
+                "algorithmic_bytes": alg, "effective_tops": round(w.ops / (ms * 1e-3) / 1e12, 3),
                 "note": f"int8 MFMA operations performed = {f} x 2MNK (one-hot selection contracts over 4K, the sparse "
                         "instruction performs half of them); integer TOP/s against the dense int8 peak"}
     if t_hbm >= t_alu:
-        ach = w.algorithmic_bytes / (ms * 1e-3) / 1e9
+        ach = alg / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(ach / HBM_PEAK_GBS, 5), "traffic": measured_traffic(w, name), "kernel": name,
-                "algorithmic_bytes": w.algorithmic_bytes}
+                "algorithmic_bytes": alg}
     ach = w.ops / (ms * 1e-3) / 1e12
     return {"bound": "alu", "achieved": round(ach, 3), "peak": round(PERM_ALU_PEAK_TOPS, 1), "unit": "TFLOP/s",
             "frac": round(ach / PERM_ALU_PEAK_TOPS, 5), "traffic": measured_traffic(w, name), "kernel": name,
-            "algorithmic_bytes": w.algorithmic_bytes,
+            "algorithmic_bytes": alg,
             "note": "integer table lookups+adds counted as 2 ops per product; peak = VALU issue ceiling of the permute loop"}
 
 
@@ -253,6 +280,8 @@ def launch_floor_us(torch, w, name, use_graph):
     """Duration of an empty kernel with the grid of the split-K one-hot kernel (the shape is in its name): what the
     launch alone costs.  None for other kernels."""
     from paper_2304_09049_amd import binding as dg
+    if name.startswith("codes_"):
+        name = name[len("codes_"):]
     prefix = "onehot_mfma_splitk_s"
     if not name.startswith(prefix):
         return None
@@ -430,9 +459,12 @@ def main():
         r.step()
     torch.cuda.synchronize()
     ms_step = time_calls(torch, r.step, args.steps, use_graph)
-    ms_kernel = time_calls(torch, r.kernel, args.steps, use_graph)       # the dominant kernel alone
+    ms_kernel = time_calls(torch, r.kernel, args.steps, use_graph)       # the convolution / GEMM kernel on packed input
     ms_pack = time_calls(torch, r.pack, args.steps, use_graph)
-    name = r.kernel_name()
+    ms_two = time_calls(torch, r.two_calls, args.steps, use_graph)
+    name, step_name = r.kernel_name(), r.step_kernel_name()
+    fused = step_name.startswith("codes_")        # the step is ONE kernel, which packs the codes as it loads them
+    dom_name, ms_dom = (step_name, ms_step) if fused else (name, ms_kernel)
 
     line = {
         "metric": "effective GOPS (2*M*N*K/s), 2-bit LUT conv",
@@ -443,13 +475,17 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32 accumulation of int8 table entries (2-bit codes); fp32 scale epilogue",
         "data": "synthetic",
-        "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "variant": args.variant, "kernel": name,
-                   "step": "dg_pack_activations + " + ("dg_conv2d_lut" if w.kind == "conv" else "dg_gemm_lut"),
+        "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "variant": args.variant, "kernel": dom_name,
+                   "step": ("dg_conv2d_lut_codes: unpacked codes in, one kernel that packs them as it loads them" if fused else
+                            "dg_conv2d_lut_codes: packing kernel + convolution kernel" if w.kind == "conv" else
+                            "dg_pack_activations + dg_gemm_lut"),
                    "launch": "hip graph replay" if use_graph else "host launches"},
+        # the same work as two calls, and its parts, for comparison
+        "two_call_step_us": round(ms_two * 1e3, 3),
         "kernel_only": kernel_report(w, ms_kernel, name),
         "pack_activations_us": round(ms_pack * 1e3, 3),
-        "roofline": roofline_object(w, ms_kernel, name),
-        "empty_launch_same_grid_us": launch_floor_us(torch, w, name, use_graph),
+        "roofline": roofline_object(w, ms_dom, dom_name),
+        "empty_launch_same_grid_us": launch_floor_us(torch, w, dom_name, use_graph),
         "paper_context": "up to 1.74x over QNNPACK INT8 on an Intel i7-9700K (speedup ratios only; no absolute figure)",
     }
 

@@ -230,6 +230,25 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
                         float *Yf_dev, dg_kernel variant, void *hip_stream);
 
 /*
+ * The run-time packing stage (Sec. 5.2) and the convolution as ONE call, from activations that are still one code
+ * per byte: Xc_dev is device memory, [B][H][W][Cin] uint8, values below 2^bits (higher bits of 2-bit codes are
+ * masked off, as dg_pack_activations does), 16-byte aligned for the fused form.  On layers so small that a second
+ * kernel launch costs as much as the layer itself (those the library runs on the one-hot split-K kernel: 2-bit
+ * codes, Cin % 32 == 0, variant AUTO or ONEHOT_MFMA) the kernel reads the codes as they are and packs them in
+ * registers while loading -- one launch, and Xp_work_dev is not touched.  Every other layer is packed into
+ * Xp_work_dev (device, work_bytes >= dg_packed_bytes_bits(B*H*W, Cin, bits), else DG_ERR_BUFFER; DG_ERR_NULL if it
+ * is needed and NULL) by the packing kernel and then run as dg_conv2d_lut would run it, on the same stream.
+ * Outputs, scale, variant and the other errors as dg_conv2d_lut; the results are identical to dg_pack_activations
+ * followed by dg_conv2d_lut.  dg_conv_codes_kernel_name names the convolution kernel that would run: "codes_..."
+ * for the fused form, else dg_conv_kernel_name's answer.
+ */
+dg_status dg_conv2d_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8_t *Xc_dev,
+                              const dg_conv_desc *desc, void *Xp_work_dev, size_t work_bytes,
+                              int32_t *Y_dev, const float *scale_cout_dev, float *Yf_dev,
+                              dg_kernel variant, void *hip_stream);
+const char *dg_conv_codes_kernel_name(const dg_lut *lut, const dg_conv_desc *desc, dg_kernel variant);
+
+/*
  * A whole layer in one kernel: table convolution, dequantise, re-quantise (Sec. 2.1, Eq. 1) and pack -- the stages
  * Sec. 5.4 lists after one another -- so that the output is the packed activation tensor of the next layer:
  *     y    = (float)sum * scale_cout_dev[co]                               (as in dg_conv2d_lut)

@@ -31,6 +31,7 @@ EXPORTS = (
     "dg_packed_activation_bytes", "dg_packed_weight_bytes", "dg_packed_bytes_bits", "dg_pack_weights",
     "dg_pack_activations", "dg_pack_codes_bits", "dg_quantize_pack_activations",
     "dg_gemm_lut", "dg_conv_out_dim", "dg_conv2d_lut", "dg_gemm_kernel_name", "dg_conv_kernel_name",
+    "dg_conv2d_lut_codes", "dg_conv_codes_kernel_name",
     "dg_launch_empty", "dg_dequantize", "dg_conv2d_lut_requant",
 )
 
@@ -90,6 +91,10 @@ def lib() -> ctypes.CDLL:
     L.dg_gemm_kernel_name.argtypes, L.dg_gemm_kernel_name.restype = [c_vp, c_i64, c_i64, c_i64, c_int], ctypes.c_char_p
     L.dg_conv_kernel_name.argtypes = [c_vp, ctypes.POINTER(ConvDesc), c_int]
     L.dg_conv_kernel_name.restype = ctypes.c_char_p
+    L.dg_conv2d_lut_codes.argtypes = [c_vp, c_vp, c_vp, ctypes.POINTER(ConvDesc), c_vp, c_sz, c_vp, c_vp, c_vp, c_int, c_vp]
+    L.dg_conv2d_lut_codes.restype = c_int
+    L.dg_conv_codes_kernel_name.argtypes = [c_vp, ctypes.POINTER(ConvDesc), c_int]
+    L.dg_conv_codes_kernel_name.restype = ctypes.c_char_p
     L.dg_launch_empty.argtypes, L.dg_launch_empty.restype = [c_i64, c_int, c_vp], c_int
     L.dg_dequantize.argtypes, L.dg_dequantize.restype = [c_vp, c_i64, c_i64, c_vp, c_vp, c_vp], c_int
     L.dg_conv2d_lut_requant.argtypes = [c_vp, c_vp, c_vp, ctypes.POINTER(ConvDesc), c_vp, ctypes.c_float, ctypes.c_float,
@@ -288,6 +293,29 @@ def dg_conv2d_lut(lut: Lut, Wp, Xp, desc: ConvDesc, out=None, scale=None, varian
                                ctypes.byref(desc), y_int, _dev_ptr(scale, torch.float32, "scale"), y_f32,
                                _kernel(variant), _stream_ptr(stream)))
     return out
+
+
+def dg_conv2d_lut_codes(lut: Lut, Wp, Xc, desc: ConvDesc, work=None, out=None, scale=None, variant="auto", stream=None):
+    """Packing stage + NHWC convolution as one call, from codes one per byte (`Xc`: uint8 [B][H][W][Cin]).  `work` is
+    the packed-activation buffer the library uses when it does not fuse the packing into the kernel (may be None)."""
+    import torch
+    OH = dg_conv_out_dim(desc.H, desc.KH, desc.stride_h, desc.pad_h)
+    OW = dg_conv_out_dim(desc.W, desc.KW, desc.stride_w, desc.pad_w)
+    as_float = scale is not None or lut.is_f32
+    dtype = torch.float32 if as_float else torch.int32
+    if out is None:
+        out = torch.empty((desc.B, max(OH, 0), max(OW, 0), desc.Cout), dtype=dtype, device=Wp.device)
+    y_int = _dev_ptr(out, torch.int32, "out") if not as_float else ctypes.c_void_p(0)
+    y_f32 = _dev_ptr(out, torch.float32, "out") if as_float else ctypes.c_void_p(0)
+    work_bytes = 0 if work is None else work.numel()
+    _check(lib().dg_conv2d_lut_codes(lut.handle, _dev_ptr(Wp, torch.uint8, "Wp"), _dev_ptr(Xc, torch.uint8, "Xc"),
+                                     ctypes.byref(desc), _dev_ptr(work, torch.uint8, "work"), work_bytes, y_int,
+                                     _dev_ptr(scale, torch.float32, "scale"), y_f32, _kernel(variant), _stream_ptr(stream)))
+    return out
+
+
+def dg_conv_codes_kernel_name(lut: Lut, desc: ConvDesc, variant="auto") -> str:
+    return lib().dg_conv_codes_kernel_name(lut.handle, ctypes.byref(desc), _kernel(variant)).decode()
 
 
 def dg_gemm_kernel_name(lut: Lut, M: int, N: int, K: int, variant="auto") -> str:

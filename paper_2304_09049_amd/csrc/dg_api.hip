@@ -449,6 +449,55 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
     return run(lut, p, variant, (hipStream_t)hip_stream);
 }
 
+namespace {
+
+// dg_conv2d_lut_codes fuses the packing into the kernel where the library's own choice for the layer (or the caller's
+// ONEHOT_MFMA) is the one-hot split-K kernel, i.e. on layers so small that a second launch costs as much as the layer.
+bool fuses_packing(const dg_lut *lut, const DgProblem &p_codes, dg_kernel variant)
+{
+    if (variant != DG_KERNEL_AUTO && variant != DG_KERNEL_ONEHOT_MFMA) return false;
+    if (!dg_onehot_codes_supports(lut, p_codes)) return false;
+    // (the unpacked buffer's 16-byte alignment satisfies every kernel's test of the packed one)
+    return variant == DG_KERNEL_ONEHOT_MFMA || pick_kernel(lut, p_codes, DG_KERNEL_AUTO) == Pick::OneHot;
+}
+
+}   // namespace
+
+dg_status dg_conv2d_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8_t *Xc_dev, const dg_conv_desc *desc,
+                              void *Xp_work_dev, size_t work_bytes, int32_t *Y_dev, const float *scale_cout_dev,
+                              float *Yf_dev, dg_kernel variant, void *hip_stream)
+{
+    const char *name = "dg_conv2d_lut_codes";
+    DgProblem p;
+    dg_status s = fill_conv(name, lut, desc, &p);
+    if (s != DG_OK) return s;
+    if (!Wp_dev || !Xc_dev) return dg_fail(DG_ERR_NULL, "%s: NULL operand", name);
+    if ((scale_cout_dev || lut->dtype == DG_LUT_F32) ? !Yf_dev : !Y_dev) return dg_fail(DG_ERR_NULL, "%s: NULL output", name);
+    p.Wp = (const uint8_t *)Wp_dev;
+    p.Xp = Xc_dev;
+    p.C = Y_dev;
+    p.Cf = Yf_dev;
+    p.scale = scale_cout_dev;
+    p.stride_cm = 1;
+    p.stride_cn = p.M;
+    if (fuses_packing(lut, p, variant)) return dg_launch_onehot_codes(lut, p, (hipStream_t)hip_stream);
+    const int64_t rows = (int64_t)desc->B * desc->H * desc->W;
+    s = pack_common(name, Xc_dev, rows, desc->Cin, lut->bits, Xp_work_dev, work_bytes, hip_stream);
+    if (s != DG_OK) return s;
+    p.Xp = (const uint8_t *)Xp_work_dev;
+    return run(lut, p, variant, (hipStream_t)hip_stream);
+}
+
+const char *dg_conv_codes_kernel_name(const dg_lut *lut, const dg_conv_desc *desc, dg_kernel variant)
+{
+    DgProblem p;
+    if (fill_conv("dg_conv_codes_kernel_name", lut, desc, &p) != DG_OK) return "invalid";
+    p.stride_cm = 1;
+    p.stride_cn = p.M;
+    if (fuses_packing(lut, p, variant)) return dg_onehot_codes_config_name(lut, p);
+    return pick_name(lut, p, variant);
+}
+
 dg_status dg_conv2d_lut_requant(const dg_lut *lut, const void *Wp_dev, const void *Xp_dev, const dg_conv_desc *desc,
                                 const float *scale_cout_dev, float q_scale, float q_zero, int32_t lo,
                                 void *packed_out_dev, size_t packed_bytes, dg_kernel variant, void *hip_stream)

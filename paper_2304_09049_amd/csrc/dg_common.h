@@ -70,6 +70,10 @@ dg_status dg_launch_lut65k(const dg_lut *lut, const DgProblem &p, hipStream_t st
 bool dg_onehot_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 const char *dg_onehot_config_name(const dg_lut *lut, const DgProblem &p);
+// the one-hot split-K kernel reading activations one code per byte (p.Xp = those bytes) and packing them as it loads
+bool dg_onehot_codes_supports(const dg_lut *lut, const DgProblem &p);
+dg_status dg_launch_onehot_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+const char *dg_onehot_codes_config_name(const dg_lut *lut, const DgProblem &p);
 bool dg_sparse_supports(const dg_lut *lut, const DgProblem &p);
 bool dg_sparse_preferred(const dg_lut *lut, const DgProblem &p);     // AUTO's choice between the two one-hot kernels
 dg_status dg_launch_sparse(const dg_lut *lut, const DgProblem &p, hipStream_t stream);

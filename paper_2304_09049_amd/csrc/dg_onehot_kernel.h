@@ -133,6 +133,34 @@ __device__ __forceinline__ Words<CH> load_words(const uint8_t *ptr)
     return w;
 }
 
+// The same words from codes that are still one per byte (the run-time packing stage done in the load stage): 16 bytes
+// make one word, code i at bits 2i; bits above a code's two are dropped, as the packing kernel drops them.  The four
+// dwords are transposed bytewise (8 permutes), so that dword b holds codes b, 4+b, 8+b, 12+b, one per byte; shifted left
+// by 2b and merged bit-field-wise they are the word (every bit of it has exactly one source: 14 instructions).
+__device__ __forceinline__ uint32_t pack_codes16(uint4 t)
+{
+    const uint32_t a0 = __builtin_amdgcn_perm(t.y, t.x, 0x05010400u), a1 = __builtin_amdgcn_perm(t.y, t.x, 0x07030602u);
+    const uint32_t b0 = __builtin_amdgcn_perm(t.w, t.z, 0x05010400u), b1 = __builtin_amdgcn_perm(t.w, t.z, 0x07030602u);
+    const uint32_t z0 = __builtin_amdgcn_perm(b0, a0, 0x05040100u), z1 = __builtin_amdgcn_perm(b0, a0, 0x07060302u);
+    const uint32_t z2 = __builtin_amdgcn_perm(b1, a1, 0x05040100u), z3 = __builtin_amdgcn_perm(b1, a1, 0x07060302u);
+    auto merge = [](uint32_t mask, uint32_t x, uint32_t rest) { return (x & mask) | (rest & ~mask); };
+    uint32_t w = merge(0x0C0C0C0Cu, z1 << 2, z0);
+    w = merge(0x30303030u, z2 << 4, w);
+    return merge(0xC0C0C0C0u, z3 << 6, w);
+}
+
+template <int CH>
+__device__ __forceinline__ Words<CH> load_codes(const uint8_t *ptr)
+{
+    uint4 t[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) t[i] = ((const uint4 *)ptr)[i];
+    Words<CH> w;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) w.v[i] = pack_codes16(t[i]);
+    return w;
+}
+
 // Selector of 4 reduction positions.  BITS < 4: `lo` holds the codes.  BITS 4: `lo` the codes below 8 (0x0C
 // elsewhere), `hi` the codes from 8 up, minus 8 (0x0C elsewhere).
 struct Sel {
@@ -256,6 +284,15 @@ __device__ __forceinline__ void sparse_dense_rows(const uint2 *rows, uint32_t w0
 }
 
 // Position bookkeeping shared by the two kernels: output column n -> image coordinates, and the filter tap of a chunk.
+// Workgroups are dealt to the 8 XCDs, each with an L2 of its own, round-robin.  Renumbered this way each XCD works on a
+// contiguous run of tiles, so that neighbouring pixels' filter windows and a tile row's weights meet in one L2
+// (any bijection is correct; this one is a guess at the dealing order that costs nothing when it is wrong).
+__device__ __forceinline__ uint32_t xcd_contiguous(uint32_t block, uint32_t blocks)
+{
+    const uint32_t per = blocks / 8, rem = blocks % 8, x = block % 8, i = block / 8;
+    return x * per + min(x, rem) + i;
+}
+
 struct Column {
     bool ok;
     int ih0, iw0;
@@ -299,7 +336,7 @@ onehot_mfma_kernel(Args a)
     const DgProblem &p = a.p;
     const int lane = threadIdx.x & 63, w4 = threadIdx.x >> 6;
     const int ks = w4 % SKW, tw = w4 / SKW;                 // this wavefront's share of K, and its tile within the workgroup
-    const int64_t my_tile = (int64_t)blockIdx.x * TPW + tw;
+    const int64_t my_tile = (int64_t)xcd_contiguous(blockIdx.x, gridDim.x) * TPW + tw;
     const bool active = my_tile < a.wave_tiles;
     if (SKW == 1 && !active) return;                       // whole waves leave; there is no barrier on this path
     if (F::SPARSE) sparse_fill_rows(s_rows + 16 * w4, a.pools, lane);
@@ -520,20 +557,24 @@ onehot_mfma_kernel(Args a)
 // or twice.  Partial blocks meet in LDS: every wavefront adds its 16 accumulator registers to the block's sums with
 // LDS integer atomics (exact in any order), one barrier, then the threads scale and store the sums -- 128 contiguous
 // bytes per half wavefront, as in the large-layer kernel.
-template <int BITS, int CH, bool TR, bool TWO>
+// RAW: the activations are codes one per byte ([pixel][Cin] bytes at p.Xp) and are packed in registers as they are
+// loaded, which saves a layer this small the launch of the packing kernel (as long as the whole layer itself).
+template <int BITS, int CH, bool TR, bool TWO, bool RAW = false>
 __global__ void __launch_bounds__(1024)
 onehot_splitk_kernel(SplitArgs a)
 {
     typedef Fmt<BITS> F;
     static_assert(!F::SPARSE || (TR && !TWO), "the sparse operand is the MFMA's row operand: activations on the rows");
+    static_assert(!RAW || BITS == 2, "unpacked activations: 2-bit codes on the dense instruction");
     __shared__ int32_t s_sum[16 * 64];                      // the block's sums, [accumulator register][lane]
     __shared__ uint2 s_rows[F::SPARSE ? 16 * 16 : 1];
     const DgProblem &p = a.p;
     const int lane = threadIdx.x & 63, ws = threadIdx.x >> 6;
     for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) s_sum[idx] = 0;
     const int r = lane & 31, h = lane >> 5;
-    const int m0 = ((int)blockIdx.x % a.tiles_m) * 32;
-    const int n0 = ((int)blockIdx.x / a.tiles_m) * 32;
+    const int block = (int)xcd_contiguous(blockIdx.x, gridDim.x);
+    const int m0 = (block % a.tiles_m) * 32;
+    const int n0 = (block / a.tiles_m) * 32;
     const int cq = p.Cin / F::PER_BYTE;
     constexpr int CHUNK = 8 * CH * F::PER_BYTE;
     // every wavefront has at least one chunk (the host sizes S that way); the max only keeps an odd launch harmless
@@ -553,7 +594,9 @@ onehot_splitk_kernel(SplitArgs a)
     if (TR && p.scale) sc = p.scale[mw];
     if (F::SPARSE) sparse_fill_rows(s_rows + 16 * ws, a.pools, lane);
     {
-        const Column col = make_column(p, a.div_ow, a.div_oh, n0 + r, cq, h * (4 * CH));
+        constexpr int LANE_BYTE = RAW ? 16 * CH : 4 * CH;  // bytes a lane half reads per chunk
+        const int bpp = RAW ? p.Cin : cq;                  // activation bytes per pixel
+        const Column col = make_column(p, a.div_ow, a.div_oh, n0 + r, bpp, h * LANE_BYTE);
         // filter tap of this wavefront's first chunk
         const int pos = c0 * CHUNK, tap = (int)fdiv((uint32_t)pos, a.div_cin), tkh = (int)fdiv((uint32_t)tap, a.div_kw);
         int ci = pos - tap * p.Cin, kh = tkh, kw = tap - tkh * p.KW;
@@ -562,8 +605,12 @@ onehot_splitk_kernel(SplitArgs a)
         auto fetch_x = [&]() {
             const int ih = col.ih0 + kh, iw = col.iw0 + kw;
             vb = col.ok & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
-            const int64_t tap_off = ((int64_t)kh * p.W + kw) * cq + ci / F::PER_BYTE;
-            wb = load_words<CH>(vb ? p.Xp + col.off0 + tap_off : p.Xp + h * (4 * CH));
+            const int64_t tap_off = ((int64_t)kh * p.W + kw) * bpp + (RAW ? ci : ci / F::PER_BYTE);
+            const uint8_t *ptr = vb ? p.Xp + col.off0 + tap_off : p.Xp + h * LANE_BYTE;
+            if constexpr (RAW)
+                wb = load_codes<CH>(ptr);
+            else
+                wb = load_words<CH>(ptr);
             ci += CHUNK;
             if (ci == p.Cin) {
                 ci = 0;
@@ -724,7 +771,7 @@ void launch_main(const DgProblem &p, const Pools &pools, const Plan &q, int64_t 
 }
 
 // The split-K kernel on `blocks11` 32 x 32 blocks of the output.
-template <int BITS, bool TR, bool TWO>
+template <int BITS, bool TR, bool TWO, bool RAW = false>
 void launch_split(const DgProblem &p, const Pools &pools, const Plan &q, int64_t blocks11, hipStream_t stream)
 {
     SplitArgs b;
@@ -738,14 +785,14 @@ void launch_split(const DgProblem &p, const Pools &pools, const Plan &q, int64_t
     const dim3 grid((unsigned)blocks11), block(64 * q.S);
     if constexpr (BITS != 4 && BITS != 20) {
         if (q.ch == 4) {
-            hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 4, TR, TWO>), grid, block, 0, stream, b);
+            hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 4, TR, TWO, RAW>), grid, block, 0, stream, b);
             return;
         }
     }
     if (q.ch == 2)
-        hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 2, TR, TWO>), grid, block, 0, stream, b);
+        hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 2, TR, TWO, RAW>), grid, block, 0, stream, b);
     else
-        hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 1, TR, TWO>), grid, block, 0, stream, b);
+        hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 1, TR, TWO, RAW>), grid, block, 0, stream, b);
 }
 
 // One translation unit per (code width, output layout, K share) instantiates these (the kernels are many: 4 tiles x
@@ -765,6 +812,8 @@ DGOH_UNIT_SPLIT(2, 0) DGOH_UNIT_SPLIT(2, 1) DGOH_UNIT_SPLIT(3, 0) DGOH_UNIT_SPLI
 DGOH_UNIT_SPLIT(4, 1) DGOH_UNIT_SPLIT(22, 0) DGOH_UNIT_SPLIT(22, 1) DGOH_UNIT_SPLIT(0, 0) DGOH_UNIT_SPLIT(0, 1) DGOH_UNIT_SPLIT(20, 1)
 void unit_sparse4(const DgProblem &, const uint32_t (&)[16][4], int, hipStream_t);      // dg_sparse4_kernel.h
 void unit_sparse2p(const DgProblem &, const uint32_t (&)[2][4], int, hipStream_t);      // dg_sparse2p_kernel.h
+// the split-K kernel on activations still one code per byte (NHWC output; one- and two-plane tables)
+void unit_split_codes(const DgProblem &, const Pools &, const Plan &, bool two, int64_t, hipStream_t);
 #undef DGOH_UNIT
 #undef DGOH_UNIT_SPLIT
 

@@ -409,7 +409,55 @@ dg_status dg_launch_decode(const dg_lut *lut, const DgProblem &p, hipStream_t st
     return dg_check_launch("onehot_mfma_kernel<0>");
 }
 
+namespace {
+
+dg_status launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream, bool codes);
+
+}   // namespace
+
 dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
+{
+    return launch_onehot(lut, p, stream, false);
+}
+
+// ---- activations still one code per byte (p.Xp = [pixel][Cin] bytes): the split-K kernel packs them as it loads them
+
+bool dg_onehot_codes_supports(const dg_lut *lut, const DgProblem &p)
+{
+    if (lut->dtype == DG_LUT_F32 || lut->bits != 2) return false;
+    if (!fits_int8(lut) && lut->max_entry > 127 * 256 + 127) return false;
+    if (p.Cin % 32 != 0 || p.stride_cm != 1 || p.stride_cn == 1) return false;      // NHWC output order
+    const Plan q = plan_for(lut, p, TABLE);
+    return q.split && (uintptr_t)p.Wp % (4 * q.ch) == 0 && (uintptr_t)p.Xp % 16 == 0;
+}
+
+const char *dg_onehot_codes_config_name(const dg_lut *lut, const DgProblem &p)
+{
+    static const char *const names[2][17] = {
+        {"", "codes_onehot_mfma_splitk_s1", "codes_onehot_mfma_splitk_s2", "codes_onehot_mfma_splitk_s3",
+         "codes_onehot_mfma_splitk_s4", "codes_onehot_mfma_splitk_s5", "codes_onehot_mfma_splitk_s6",
+         "codes_onehot_mfma_splitk_s7", "codes_onehot_mfma_splitk_s8", "codes_onehot_mfma_splitk_s9",
+         "codes_onehot_mfma_splitk_s10", "codes_onehot_mfma_splitk_s11", "codes_onehot_mfma_splitk_s12",
+         "codes_onehot_mfma_splitk_s13", "codes_onehot_mfma_splitk_s14", "codes_onehot_mfma_splitk_s15",
+         "codes_onehot_mfma_splitk_s16"},
+        {"", "codes_onehot_mfma_2p_splitk_s1", "codes_onehot_mfma_2p_splitk_s2", "codes_onehot_mfma_2p_splitk_s3",
+         "codes_onehot_mfma_2p_splitk_s4", "codes_onehot_mfma_2p_splitk_s5", "codes_onehot_mfma_2p_splitk_s6",
+         "codes_onehot_mfma_2p_splitk_s7", "codes_onehot_mfma_2p_splitk_s8", "codes_onehot_mfma_2p_splitk_s9",
+         "codes_onehot_mfma_2p_splitk_s10", "codes_onehot_mfma_2p_splitk_s11", "codes_onehot_mfma_2p_splitk_s12",
+         "codes_onehot_mfma_2p_splitk_s13", "codes_onehot_mfma_2p_splitk_s14", "codes_onehot_mfma_2p_splitk_s15",
+         "codes_onehot_mfma_2p_splitk_s16"}};
+    const Plan q = plan_for(lut, p, TABLE);
+    return names[q.two][q.S];
+}
+
+dg_status dg_launch_onehot_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
+{
+    return launch_onehot(lut, p, stream, true);
+}
+
+namespace {
+
+dg_status launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream, bool codes)
 {
     // column v of the table, 4 weight codes per word: the permute pools.  Entries beyond int8 go in two planes,
     // T = 256 * hi + lo with lo in [-128, 127] (so hi is within [-128, 128) for every int16 T).
@@ -436,6 +484,12 @@ dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t st
                                             {unit_main_b4_t0_k1, unit_main_b4_t1_k1}, {unit_main_b22_t0_k1, unit_main_b22_t1_k1}};
     static const MainFn shared_units[2][2] = {{unit_main_b2_t0_k2, unit_main_b2_t1_k2}, {unit_main_b2_t0_k4, unit_main_b2_t1_k4}};
     const int width = q.two ? 3 : lut->bits - 2;
+    if (codes) {
+        if (!q.split || !tr || lut->bits != 2)
+            return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel on unpacked codes: small NHWC layers with 2-bit codes only");
+        unit_split_codes(p, pools, q, q.two, blocks11, stream);
+        return dg_check_launch("onehot_splitk_kernel (unpacked codes)");
+    }
     if (q.split) {
         split_units[width][tr](p, pools, q, blocks11, stream);
         return dg_check_launch("onehot_splitk_kernel");
@@ -446,3 +500,5 @@ dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t st
         main_units[width][tr](p, pools, q, wave_tiles, stream);
     return dg_check_launch("onehot_mfma_kernel");
 }
+
+}   // namespace

@@ -27,7 +27,7 @@ sparse2p_kernel(Sparse2pArgs a)
     __shared__ uint2 s_rows[4 * 32];                        // per wavefront: 16 row pairs of the low plane, then of the high
     const DgProblem &p = a.p;
     const int lane = threadIdx.x & 63, w4 = threadIdx.x >> 6;
-    const int64_t wave_tile = (int64_t)blockIdx.x * 4 + w4;
+    const int64_t wave_tile = (int64_t)xcd_contiguous(blockIdx.x, gridDim.x) * 4 + w4;
     if (wave_tile >= a.wave_tiles) return;                  // whole waves leave; there is no barrier
     uint2 *rows = s_rows + 32 * w4;
     if (lane < 32) {

@@ -35,7 +35,7 @@ sparse4_kernel(Sparse4Args a)
     __shared__ uint4 s_rows[4 * 16];
     const DgProblem &p = a.p;
     const int lane = threadIdx.x & 63, w4 = threadIdx.x >> 6;
-    const int64_t wave_tile = (int64_t)blockIdx.x * 4 + w4;
+    const int64_t wave_tile = (int64_t)xcd_contiguous(blockIdx.x, gridDim.x) * 4 + w4;
     if (wave_tile >= a.wave_tiles) return;                  // whole waves leave; there is no barrier
     uint4 *rows = s_rows + 16 * w4;
     if (lane < 16) rows[lane] = make_uint4(a.rows[lane][0], a.rows[lane][1], a.rows[lane][2], a.rows[lane][3]);

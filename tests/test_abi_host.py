@@ -190,6 +190,12 @@ def test_kernel_names_need_no_gpu():
     assert dg.dg_gemm_kernel_name(t4, 256, 50176, 2304, "onehot_mfma").startswith("onehot_mfma_64x")
     assert dg.dg_gemm_kernel_name(t4, 256, 1568, 2304).startswith("onehot_mfma_")
     assert dg.dg_gemm_kernel_name(t4, 256, 50176, 2304, "perm") == "unsupported"
+    # packing + convolution in one call: fused into the split-K kernel on small layers only
+    small = dg.conv_desc(1, 56, 56, 64, 64, 3, 3, (1, 1), (1, 1))
+    large = dg.conv_desc(16, 56, 56, 256, 256, 3, 3, (1, 1), (1, 1))
+    assert dg.dg_conv_codes_kernel_name(lut, small) == "codes_onehot_mfma_splitk_s9"
+    assert dg.dg_conv_codes_kernel_name(lut, small, "onehot_smfmac") == dg.dg_conv_kernel_name(lut, small, "onehot_smfmac")
+    assert dg.dg_conv_codes_kernel_name(lut, large) == dg.dg_conv_kernel_name(lut, large) == "onehot_smfmac_64x128"
 
 
 def test_dequantize_argument_errors():

@@ -231,6 +231,58 @@ def test_two_plane_tables_on_the_sparse_instruction():
     assert small.kernel_name("auto").startswith("onehot_mfma_2p_")
 
 
+def test_convolution_from_unpacked_codes(monkeypatch):
+    """dg_conv2d_lut_codes (packing stage + convolution in one call) against the oracle's convolution of the same
+    codes: small layers, where the split-K kernel packs the codes itself as it loads them (padding, stride, ragged
+    Cout and pixel counts, chunk widths of 1, 2 and 4 words, one- and two-plane tables, int32 and scaled output, codes
+    with garbage above their two bits), and layers it hands to the packing kernel and another convolution kernel."""
+    cases = [(2, 24, 24, 32, 70, 3, 3, (1, 1), (1, 1)), (1, 30, 30, 128, 40, 3, 3, (2, 2), (1, 1)),
+             (3, 16, 16, 64, 33, 1, 1, (1, 1), (0, 0)), (1, 20, 20, 64, 96, 5, 5, (1, 1), (2, 2)),
+             (1, 7, 9, 96, 3, 3, 3, (1, 1), (2, 2)), (1, 56, 56, 64, 64, 3, 3, (1, 1), (1, 1)),
+             (1, 5, 5, 256, 130, 3, 3, (1, 1), (1, 1))]
+    rng = np.random.default_rng(77)
+    for table in ("nonuniform_i8", "extreme_i16"):
+        monkeypatch.setenv("DG_ONEHOT_PLAN", "split")       # (the 1 x 1 layer would otherwise run on a tiled kernel)
+        lw, la, entry = LEVELS[table] if table == "nonuniform_i8" else ((127, -128, 5, 3), (-128, 127, 1, 2), dg.DG_LUT_I16)
+        for (B, H, W, Cin, Cout, KH, KW, stride, pad) in cases:
+            c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
+            case = GpuCase(c, levels=(lw, la), entry=entry)
+            name = dg.dg_conv_codes_kernel_name(case.lut, case.desc)
+            assert name.startswith("codes_onehot_mfma_2p_splitk_s" if table == "extreme_i16" else "codes_onehot_mfma_splitk_s"), name
+            dirty = c.Ac | (rng.integers(0, 64, size=c.Ac.shape, dtype=np.uint8) << 2)      # garbage above bit 1
+            Xc = torch.from_numpy(dirty).cuda()
+            acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
+            got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc)                   # no work buffer: must fuse
+            torch.cuda.synchronize()
+            _assert_same(got.cpu().numpy(), acc, f"codes conv {(B, H, W, Cin, Cout)} {table}")
+            got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, scale=case.scale)
+            torch.cuda.synchronize()
+            assert np.array_equal(got.cpu().numpy(), oracle.scale_epilogue_nhwc(acc, c.scale)), "scaled codes conv"
+    # layers that are not fused: a channel count the one-hot kernels do not take, a variant that never fuses, and a
+    # layer large enough for the tiled kernels -- packed into the work buffer, then run as dg_conv2d_lut runs them
+    monkeypatch.delenv("DG_ONEHOT_PLAN")
+    lw, la, entry = LEVELS["nonuniform_i8"]
+    for (shape, variant) in (((2, 9, 9, 16, 20, 3, 3, (1, 1), (1, 1)), "auto"), ((1, 14, 14, 64, 64, 3, 3, (1, 1), (1, 1)), "lds"),
+                             ((8, 56, 56, 64, 64, 3, 3, (1, 1), (1, 1)), "auto")):
+        B, H, W, Cin, Cout, KH, KW, stride, pad = shape
+        c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=5)
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        name = dg.dg_conv_codes_kernel_name(case.lut, case.desc, variant)
+        assert not name.startswith("codes_") and name == case.kernel_name(variant)
+        Xc = torch.from_numpy(c.Ac).cuda()
+        work = torch.zeros(B * H * W * Cin // 4, dtype=torch.uint8, device="cuda")
+        got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, work=work, variant=variant)
+        torch.cuda.synchronize()
+        _assert_same(got.cpu().numpy(), oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad), f"unfused {shape}")
+        _assert_same(work.cpu().numpy().reshape(-1, Cin // 4), oracle.pack_codes(c.Ac.reshape(-1, Cin)), "work buffer")
+        with pytest.raises(dg.DgError) as e:                                                  # needed and missing / too small
+            dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, variant=variant)
+        assert e.value.status == 1
+        with pytest.raises(dg.DgError) as e:
+            dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, work=work[:-1], variant=variant)
+        assert e.value.status == 4
+
+
 def test_random_convolution_shapes():
     """Seeded random convolution geometries (image, filter, stride, padding, channel counts, batch) through AUTO and
     every variant that accepts them: the oracle is the plain nested loop, so any disagreement is a kernel indexing bug."""
