@@ -39,10 +39,10 @@ PERM_ALU_PEAK_TOPS = VALU_LANE_INSTR_PER_S * (4 / 1.5) * 2 / 1e12
 # bytes -> x2.0; WRITE_SIZE reads them exactly -> x1.0).  Summaries with the commands are under profiles/.
 # Keyed by (workload, kernel name); a kernel or workload that was not profiled reports null.
 MEASURED_TRAFFIC_KIB = {
-    ("resnet18_conv3x3_b1", "onehot_mfma_splitk_s9"): (230.7 * 2.0, 784.0),
-    ("resnet18_conv3x3_b1", "codes_onehot_mfma_splitk_s9"): None,
-    ("vgg16_conv3x3_b16", "onehot_mfma_64x128"): (4607.8 * 2.0, 50176.0),
-    ("vgg16_conv3x3_b16", "onehot_smfmac_64x128"): (4430.8 * 2.0, 50176.0),
+    ("resnet18_conv3x3_b1", "onehot_mfma_splitk_s9"): (107.6 * 2.0, 784.0),
+    ("resnet18_conv3x3_b1", "codes_onehot_mfma_splitk_s9"): (207.2 * 2.0, 784.0),
+    ("vgg16_conv3x3_b16", "onehot_mfma_64x128"): (2375.5 * 2.0, 50176.0),
+    ("vgg16_conv3x3_b16", "onehot_smfmac_64x128"): (2327.5 * 2.0, 50176.0),
     ("gemm_8192x1x8192_i16", "smalln"): (8251.9 * 2.0, 32.0),
 }
 
