@@ -31,6 +31,17 @@ def _border_heavy_positions(w, rng, count):
     return np.unique(np.concatenate(pos))
 
 
+def _one_call(case, inp):
+    """The step bench.py times: dg_conv2d_lut_codes on the unpacked codes (AUTO), with a work buffer for the layers whose
+    packing is not fused into the convolution kernel."""
+    import torch
+    from paper_2304_09049_amd import binding as dg
+    Xc = torch.from_numpy(inp.Ac).cuda()
+    got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, work=torch.empty_like(case.Ap))
+    torch.cuda.synchronize()
+    return got.cpu().numpy()
+
+
 @pytest.mark.parametrize("name", FULL)
 def test_full_output(name):
     w = wl.CONFIGS[name]
@@ -48,6 +59,8 @@ def test_full_output(name):
         ran.append(variant)
         assert np.array_equal(got, want), f"{name} {variant}: {np.count_nonzero(got != want)} outputs differ"
     assert "auto" in ran and "lds" in ran
+    if w.kind == "conv":
+        assert np.array_equal(_one_call(case, inp), want), f"{name}: packing + convolution as one call"
     if w.scale:
         got = case.run("auto", scale=True).cpu().numpy()
         ref = oracle.scale_epilogue_nhwc(want, inp.scale)
@@ -79,6 +92,8 @@ def test_sampled_output(name):
         flat = got.reshape(-1)[pos]
         assert np.array_equal(flat, want), f"{name} {variant}: {np.count_nonzero(flat != want)} sampled outputs differ"
     assert "auto" in ran
+    if w.kind == "conv":
+        assert np.array_equal(_one_call(case, inp).reshape(-1)[pos], want), f"{name}: packing + convolution as one call"
 
 
 @pytest.mark.parametrize("name", ["vgg16_conv3x3_b16", "gemm_8192x8192x8192_i16"])

@@ -703,7 +703,7 @@ def test_f32_table():
 
 
 def test_graph_replays_equal_eager_launches():
-    """bench.py replays its steps from a HIP graph: a captured step (pack, then convolution; and the fused layer) must
+    """bench.py replays its steps from a HIP graph: a captured step (pack, then convolution; the fused layer; and the one-call path) must
     give, on every replay and with other work between the replays, what the same calls give launched one by one -- on a
     small layer (split-K kernel, LDS sums zeroed inside the kernel) and on one large enough for the sparse-instruction
     kernel."""
@@ -718,11 +718,13 @@ def test_graph_replays_equal_eager_launches():
         Xp = torch.empty_like(case.Ap)
         y = torch.empty(want.shape, dtype=torch.float32, device=dev)
         q = torch.empty(B * want.shape[1] * want.shape[2] * Cout // 4, dtype=torch.uint8, device=dev)
+        y1, work = torch.empty_like(y), torch.empty_like(case.Ap)         # the one-call path (bench.py's step)
 
         def step():
             dg.dg_pack_activations(codes, B * H * W, Cin, out=Xp)
             dg.dg_conv2d_lut(case.lut, case.Wp, Xp, case.desc, out=y, scale=case.scale)
             dg.dg_conv2d_lut_requant(case.lut, case.Wp, Xp, case.desc, case.scale, 8.0, 0.5, 0, out=q)
+            dg.dg_conv2d_lut_codes(case.lut, case.Wp, codes, case.desc, work=work, out=y1, scale=case.scale)
 
         step()
         torch.cuda.synchronize()
@@ -734,13 +736,14 @@ def test_graph_replays_equal_eager_launches():
                 step()
         torch.cuda.synchronize()
         for replay in range(4):
-            Xp.zero_(), y.fill_(-1.0), q.fill_(255)                       # eager work between the replays
+            Xp.zero_(), y.fill_(-1.0), q.fill_(255), y1.fill_(-2.0), work.fill_(7)       # eager work between the replays
             torch.cuda.synchronize()
             graph.replay()
             torch.cuda.synchronize()
             assert np.array_equal(y.cpu().numpy(), want), f"replay {replay} of {(B, H, W, Cin, Cout)}"
             assert torch.equal(q, q_eager), f"replay {replay}: fused layer"
             assert torch.equal(Xp, case.Ap), f"replay {replay}: packed activations"
+            assert np.array_equal(y1.cpu().numpy(), want), f"replay {replay}: one-call path"
 
 
 def test_four_bit_auto_takes_the_sparse_kernel_on_large_layers():
