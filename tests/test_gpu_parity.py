@@ -258,6 +258,17 @@ def test_convolution_from_unpacked_codes(monkeypatch):
             got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, scale=case.scale)
             torch.cuda.synchronize()
             assert np.array_equal(got.cpu().numpy(), oracle.scale_epilogue_nhwc(acc, c.scale)), "scaled codes conv"
+    # codes at an address that is not 16-byte aligned: not fused (the packing kernel takes any address), same result
+    c = wl.small_conv(1, 12, 12, 64, 40, 3, 3, (1, 1), (1, 1), seed=9)
+    case = GpuCase(c, levels=LEVELS["nonuniform_i8"][:2], entry=dg.DG_LUT_I8)
+    base = torch.zeros(c.Ac.size + 3, dtype=torch.uint8, device="cuda")
+    base[3:].copy_(torch.from_numpy(c.Ac.reshape(-1)))
+    got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, base[3:], case.desc, work=torch.empty_like(case.Ap))
+    torch.cuda.synchronize()
+    _assert_same(got.cpu().numpy(), oracle.conv2d(c.Wc, c.Ac, *LEVELS["nonuniform_i8"][:2], stride=(1, 1), pad=(1, 1)), "unaligned codes")
+    with pytest.raises(dg.DgError) as e:
+        dg.dg_conv2d_lut_codes(case.lut, case.Wp, base[3:], case.desc)
+    assert e.value.status == 1
     # layers that are not fused: a channel count the one-hot kernels do not take, a variant that never fuses, and a
     # layer large enough for the tiled kernels -- packed into the work buffer, then run as dg_conv2d_lut runs them
     monkeypatch.delenv("DG_ONEHOT_PLAN")
