@@ -3,9 +3,9 @@
 
 One "step" is one pass of the run-time hot path over one batch of synthetic codes already resident in
 HBM: pack the activation codes four per byte, then the table convolution / GEMM with its epilogue.  A
-convolution goes through the one-call entry point dg_conv2d_lut_codes, which on small layers (the headline
-one) runs a single kernel that packs the codes in registers as it loads them, and on the others the packing
-kernel followed by the convolution kernel; a GEMM is dg_pack_activations + dg_gemm_lut.  The two-call time
+step goes through the one-call entry points dg_conv2d_lut_codes / dg_gemm_lut_codes, which on small layers (the
+headline one) run a single kernel that packs the codes in registers as it loads them, and on the others the
+packing kernel followed by the convolution / GEMM kernel.  The two-call time
 of the same work is reported beside it.  The table and the packed weights are built once, before the timed
 region (the paper packs weights offline, Sec. 5.2).  Steps are replayed from a HIP graph so that the host's
 launch cost does not cap a microsecond-scale kernel.
@@ -110,13 +110,14 @@ class Runner:
                                 scale=self.scale, variant=v)
 
     def step(self):
-        """The whole hot path on the resident codes: a convolution through the one-call entry point, which packs inside
-        the convolution kernel on small layers and runs the packing kernel first on the others; a GEMM as two calls."""
+        """The whole hot path on the resident codes, through the one-call entry points, which pack inside the kernel on
+        small problems and run the packing kernel first on the others."""
         if self.desc is not None:
             self.dg.dg_conv2d_lut_codes(self.lut, self.Wp, self.codes, self.desc, work=self.Ap, out=self.out,
                                         scale=self.scale, variant=self.variant)
         else:
-            self.two_calls()
+            self.dg.dg_gemm_lut_codes(self.lut, self.Wp, self.codes, self.w.M, self.w.N, self.w.K, work=self.Ap,
+                                      out=self.out, scale=self.scale, variant=self.variant)
 
     def two_calls(self):
         self.pack()
@@ -126,7 +127,7 @@ class Runner:
         """The convolution / GEMM kernel of a step ("codes_..." when it does the packing itself)."""
         if self.desc is not None:
             return self.dg.dg_conv_codes_kernel_name(self.lut, self.desc, self.variant)
-        return self.kernel_name()
+        return self.dg.dg_gemm_codes_kernel_name(self.lut, self.w.M, self.w.N, self.w.K, self.variant)
 
     def make_cold_weights(self, total_bytes=640 << 20):
         """Copies of the packed weights that together exceed the 256 MB last-level cache."""
@@ -229,7 +230,8 @@ def mfma_ops_factor(name):
 def algorithmic_bytes(w, name):
     """Bytes a launch of kernel `name` has to move: the workload's packed operands and output; a kernel that reads the
     activation codes one per byte reads four times the packed activations."""
-    extra = 3 * (w.B * w.H * w.W * w.Cin // 4) if name.startswith("codes_") else 0
+    packed = (w.B * w.H * w.W * w.Cin // 4) if w.kind == "conv" else w.N * w.K // 4
+    extra = 3 * packed if name.startswith("codes_") else 0
     return w.algorithmic_bytes + extra
 
 
@@ -476,9 +478,9 @@ def main():
         "dtype": "int32 accumulation of int8 table entries (2-bit codes); fp32 scale epilogue",
         "data": "synthetic",
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "variant": args.variant, "kernel": dom_name,
-                   "step": ("dg_conv2d_lut_codes: unpacked codes in, one kernel that packs them as it loads them" if fused else
-                            "dg_conv2d_lut_codes: packing kernel + convolution kernel" if w.kind == "conv" else
-                            "dg_pack_activations + dg_gemm_lut"),
+                   "step": ("dg_conv2d_lut_codes" if w.kind == "conv" else "dg_gemm_lut_codes") +
+                           (": unpacked codes in, one kernel that packs them as it loads them" if fused else
+                            ": packing kernel + " + ("convolution" if w.kind == "conv" else "GEMM") + " kernel"),
                    "launch": "hip graph replay" if use_graph else "host launches"},
         # the same work as two calls, and its parts, for comparison
         "two_call_step_us": round(ms_two * 1e3, 3),

@@ -247,6 +247,16 @@ dg_status dg_conv2d_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8
                               int32_t *Y_dev, const float *scale_cout_dev, float *Yf_dev,
                               dg_kernel variant, void *hip_stream);
 const char *dg_conv_codes_kernel_name(const dg_lut *lut, const dg_conv_desc *desc, dg_kernel variant);
+/*
+ * The same for a GEMM: Ac_dev is device memory, [N][K] uint8 codes; Ap_work_dev (work_bytes >=
+ * dg_packed_bytes_bits(N, K, bits)) is used when the packing is not fused (K % 32 != 0, a large problem, one or two
+ * columns, another variant, 3- or 4-bit codes).  Outputs, strides, scale and the other errors as dg_gemm_lut.
+ */
+dg_status dg_gemm_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8_t *Ac_dev, int64_t M, int64_t N,
+                            int64_t K, void *Ap_work_dev, size_t work_bytes, int32_t *C_dev, int64_t stride_cm,
+                            int64_t stride_cn, const float *scale_m_dev, float *Cf_dev, dg_kernel variant,
+                            void *hip_stream);
+const char *dg_gemm_codes_kernel_name(const dg_lut *lut, int64_t M, int64_t N, int64_t K, dg_kernel variant);
 
 /*
  * A whole layer in one kernel: table convolution, dequantise, re-quantise (Sec. 2.1, Eq. 1) and pack -- the stages

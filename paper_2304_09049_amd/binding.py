@@ -31,7 +31,7 @@ EXPORTS = (
     "dg_packed_activation_bytes", "dg_packed_weight_bytes", "dg_packed_bytes_bits", "dg_pack_weights",
     "dg_pack_activations", "dg_pack_codes_bits", "dg_quantize_pack_activations",
     "dg_gemm_lut", "dg_conv_out_dim", "dg_conv2d_lut", "dg_gemm_kernel_name", "dg_conv_kernel_name",
-    "dg_conv2d_lut_codes", "dg_conv_codes_kernel_name",
+    "dg_conv2d_lut_codes", "dg_conv_codes_kernel_name", "dg_gemm_lut_codes", "dg_gemm_codes_kernel_name",
     "dg_launch_empty", "dg_dequantize", "dg_conv2d_lut_requant",
 )
 
@@ -93,6 +93,10 @@ def lib() -> ctypes.CDLL:
     L.dg_conv_kernel_name.restype = ctypes.c_char_p
     L.dg_conv2d_lut_codes.argtypes = [c_vp, c_vp, c_vp, ctypes.POINTER(ConvDesc), c_vp, c_sz, c_vp, c_vp, c_vp, c_int, c_vp]
     L.dg_conv2d_lut_codes.restype = c_int
+    L.dg_gemm_lut_codes.argtypes = [c_vp, c_vp, c_vp, c_i64, c_i64, c_i64, c_vp, c_sz, c_vp, c_i64, c_i64, c_vp, c_vp, c_int, c_vp]
+    L.dg_gemm_lut_codes.restype = c_int
+    L.dg_gemm_codes_kernel_name.argtypes = [c_vp, c_i64, c_i64, c_i64, c_int]
+    L.dg_gemm_codes_kernel_name.restype = ctypes.c_char_p
     L.dg_conv_codes_kernel_name.argtypes = [c_vp, ctypes.POINTER(ConvDesc), c_int]
     L.dg_conv_codes_kernel_name.restype = ctypes.c_char_p
     L.dg_launch_empty.argtypes, L.dg_launch_empty.restype = [c_i64, c_int, c_vp], c_int
@@ -272,6 +276,29 @@ def dg_gemm_lut(lut: Lut, Wp, Ap, M: int, N: int, K: int, out=None, scale=None, 
                              M, N, K, c_int, scm, scn, _dev_ptr(scale, torch.float32, "scale"), c_f32,
                              _kernel(variant), _stream_ptr(stream)))
     return out
+
+
+def dg_gemm_lut_codes(lut: Lut, Wp, Ac, M: int, N: int, K: int, work=None, out=None, scale=None, variant="auto",
+                      stream=None, strides: Optional[Sequence[int]] = None):
+    """Packing stage + GEMM as one call, from codes one per byte (`Ac`: uint8 [N][K]).  `work` is the packed-activation
+    buffer the library uses when it does not fuse the packing into the kernel (may be None)."""
+    import torch
+    as_float = scale is not None or lut.is_f32
+    dtype = torch.float32 if as_float else torch.int32
+    if out is None:
+        out = torch.empty((M, N), dtype=dtype, device=Wp.device)
+    scm, scn = (N, 1) if strides is None else strides
+    c_int = _dev_ptr(out, torch.int32, "out") if not as_float else ctypes.c_void_p(0)
+    c_f32 = _dev_ptr(out, torch.float32, "out") if as_float else ctypes.c_void_p(0)
+    _check(lib().dg_gemm_lut_codes(lut.handle, _dev_ptr(Wp, torch.uint8, "Wp"), _dev_ptr(Ac, torch.uint8, "Ac"), M, N, K,
+                                   _dev_ptr(work, torch.uint8, "work"), 0 if work is None else work.numel(), c_int,
+                                   scm, scn, _dev_ptr(scale, torch.float32, "scale"), c_f32, _kernel(variant),
+                                   _stream_ptr(stream)))
+    return out
+
+
+def dg_gemm_codes_kernel_name(lut: Lut, M: int, N: int, K: int, variant="auto") -> str:
+    return lib().dg_gemm_codes_kernel_name(lut.handle, M, N, K, _kernel(variant)).decode()
 
 
 def conv_desc(B, H, W, Cin, Cout, KH, KW, stride=(1, 1), pad=(0, 0)) -> ConvDesc:

@@ -463,6 +463,40 @@ bool fuses_packing(const dg_lut *lut, const DgProblem &p_codes, dg_kernel varian
 
 }   // namespace
 
+dg_status dg_gemm_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8_t *Ac_dev, int64_t M, int64_t N,
+                            int64_t K, void *Ap_work_dev, size_t work_bytes, int32_t *C_dev, int64_t stride_cm,
+                            int64_t stride_cn, const float *scale_m_dev, float *Cf_dev, dg_kernel variant,
+                            void *hip_stream)
+{
+    const char *name = "dg_gemm_lut_codes";
+    DgProblem p;
+    dg_status s = fill_gemm(name, lut, M, N, K, &p);
+    if (s != DG_OK) return s;
+    if (!Wp_dev || !Ac_dev) return dg_fail(DG_ERR_NULL, "%s: NULL operand", name);
+    if ((scale_m_dev || lut->dtype == DG_LUT_F32) ? !Cf_dev : !C_dev) return dg_fail(DG_ERR_NULL, "%s: NULL output", name);
+    if (stride_cm == 0 || stride_cn == 0) return dg_fail(DG_ERR_SHAPE, "%s: zero output stride", name);
+    p.Wp = (const uint8_t *)Wp_dev;
+    p.Xp = Ac_dev;
+    p.C = C_dev;
+    p.Cf = Cf_dev;
+    p.scale = scale_m_dev;
+    p.stride_cm = stride_cm;
+    p.stride_cn = stride_cn;
+    if (fuses_packing(lut, p, variant)) return dg_launch_onehot_codes(lut, p, (hipStream_t)hip_stream);
+    s = pack_common(name, Ac_dev, N, K, lut->bits, Ap_work_dev, work_bytes, hip_stream);
+    if (s != DG_OK) return s;
+    p.Xp = (const uint8_t *)Ap_work_dev;
+    return run(lut, p, variant, (hipStream_t)hip_stream);
+}
+
+const char *dg_gemm_codes_kernel_name(const dg_lut *lut, int64_t M, int64_t N, int64_t K, dg_kernel variant)
+{
+    DgProblem p;
+    if (fill_gemm("dg_gemm_codes_kernel_name", lut, M, N, K, &p) != DG_OK) return "invalid";
+    if (fuses_packing(lut, p, variant)) return dg_onehot_codes_config_name(lut, p);
+    return pick_name(lut, p, variant);
+}
+
 dg_status dg_conv2d_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8_t *Xc_dev, const dg_conv_desc *desc,
                               void *Xp_work_dev, size_t work_bytes, int32_t *Y_dev, const float *scale_cout_dev,
                               float *Yf_dev, dg_kernel variant, void *hip_stream)

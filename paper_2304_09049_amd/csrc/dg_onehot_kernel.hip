@@ -426,7 +426,7 @@ bool dg_onehot_codes_supports(const dg_lut *lut, const DgProblem &p)
 {
     if (lut->dtype == DG_LUT_F32 || lut->bits != 2) return false;
     if (!fits_int8(lut) && lut->max_entry > 127 * 256 + 127) return false;
-    if (p.Cin % 32 != 0 || p.stride_cm != 1 || p.stride_cn == 1) return false;      // NHWC output order
+    if (p.Cin % 32 != 0) return false;                                 // a lane half reads whole words of one tap
     const Plan q = plan_for(lut, p, TABLE);
     return q.split && (uintptr_t)p.Wp % (4 * q.ch) == 0 && (uintptr_t)p.Xp % 16 == 0;
 }
@@ -485,9 +485,9 @@ dg_status launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t strea
     static const MainFn shared_units[2][2] = {{unit_main_b2_t0_k2, unit_main_b2_t1_k2}, {unit_main_b2_t0_k4, unit_main_b2_t1_k4}};
     const int width = q.two ? 3 : lut->bits - 2;
     if (codes) {
-        if (!q.split || !tr || lut->bits != 2)
-            return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel on unpacked codes: small NHWC layers with 2-bit codes only");
-        unit_split_codes(p, pools, q, q.two, blocks11, stream);
+        if (!q.split || lut->bits != 2)
+            return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel on unpacked codes: small layers with 2-bit codes only");
+        unit_split_codes(p, pools, q, q.two, tr != 0, blocks11, stream);
         return dg_check_launch("onehot_splitk_kernel (unpacked codes)");
     }
     if (q.split) {

@@ -32,12 +32,16 @@ def _border_heavy_positions(w, rng, count):
 
 
 def _one_call(case, inp):
-    """The step bench.py times: dg_conv2d_lut_codes on the unpacked codes (AUTO), with a work buffer for the layers whose
-    packing is not fused into the convolution kernel."""
+    """The step bench.py times: dg_conv2d_lut_codes / dg_gemm_lut_codes on the unpacked codes (AUTO), with a work buffer
+    for the problems whose packing is not fused into the kernel."""
     import torch
     from paper_2304_09049_amd import binding as dg
     Xc = torch.from_numpy(inp.Ac).cuda()
-    got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, work=torch.empty_like(case.Ap))
+    w = inp.workload
+    if w.kind == "conv":
+        got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, work=torch.empty_like(case.Ap))
+    else:
+        got = dg.dg_gemm_lut_codes(case.lut, case.Wp, Xc, w.M, w.N, w.K, work=torch.empty_like(case.Ap))
     torch.cuda.synchronize()
     return got.cpu().numpy()
 
@@ -59,8 +63,7 @@ def test_full_output(name):
         ran.append(variant)
         assert np.array_equal(got, want), f"{name} {variant}: {np.count_nonzero(got != want)} outputs differ"
     assert "auto" in ran and "lds" in ran
-    if w.kind == "conv":
-        assert np.array_equal(_one_call(case, inp), want), f"{name}: packing + convolution as one call"
+    assert np.array_equal(_one_call(case, inp), want), f"{name}: packing + convolution / GEMM as one call"
     if w.scale:
         got = case.run("auto", scale=True).cpu().numpy()
         ref = oracle.scale_epilogue_nhwc(want, inp.scale)
@@ -92,8 +95,7 @@ def test_sampled_output(name):
         flat = got.reshape(-1)[pos]
         assert np.array_equal(flat, want), f"{name} {variant}: {np.count_nonzero(flat != want)} sampled outputs differ"
     assert "auto" in ran
-    if w.kind == "conv":
-        assert np.array_equal(_one_call(case, inp).reshape(-1)[pos], want), f"{name}: packing + convolution as one call"
+    assert np.array_equal(_one_call(case, inp).reshape(-1)[pos], want), f"{name}: packing + convolution / GEMM as one call"
 
 
 @pytest.mark.parametrize("name", ["vgg16_conv3x3_b16", "gemm_8192x8192x8192_i16"])

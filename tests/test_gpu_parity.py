@@ -294,6 +294,46 @@ def test_convolution_from_unpacked_codes(monkeypatch):
         assert e.value.status == 4
 
 
+def test_gemm_from_unpacked_codes(monkeypatch):
+    """dg_gemm_lut_codes against the oracle: small GEMMs where the split-K kernel packs the codes itself (row-major and
+    column-major output, scaled output, one- and two-plane tables, ragged M and N, chunk widths of 1, 2 and 4 words), and
+    GEMMs it hands to the packing kernel first (K % 32 != 0, one column, a large problem, another variant)."""
+    for table in ("nonuniform_i8", "extreme_i16"):
+        lw, la, entry = LEVELS[table]
+        for (M, N, K) in [(64, 196, 576), (70, 300, 96), (33, 250, 1024), (130, 77, 64), (5, 16, 4096), (1, 40, 32)]:
+            monkeypatch.setenv("DG_ONEHOT_PLAN", "split")
+            g = wl.make_inputs(wl.Workload(name="g", kind="gemm", M=M, N=N, K=K, scale=True, seed=M + N + K))
+            case = GpuCase(g, levels=(lw, la), entry=entry)
+            assert dg.dg_gemm_codes_kernel_name(case.lut, M, N, K).startswith("codes_onehot_mfma_")
+            Ac = torch.from_numpy(g.Ac).cuda()
+            want = oracle.gemm(g.Wc, g.Ac, lw, la)
+            got = dg.dg_gemm_lut_codes(case.lut, case.Wp, Ac, M, N, K)                       # no work buffer: must fuse
+            torch.cuda.synchronize()
+            _assert_same(got.cpu().numpy(), want, f"codes gemm {(M, N, K)} {table}")
+            out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
+            dg.dg_gemm_lut_codes(case.lut, case.Wp, Ac, M, N, K, out=out, strides=(1, M))
+            torch.cuda.synchronize()
+            _assert_same(out.cpu().numpy(), want.T.copy(), f"codes gemm {(M, N, K)} {table} column-major")
+            got = dg.dg_gemm_lut_codes(case.lut, case.Wp, Ac, M, N, K, scale=case.scale)
+            torch.cuda.synchronize()
+            assert np.array_equal(got.cpu().numpy(), oracle.scale_epilogue_rows(want, g.scale)), "scaled codes gemm"
+    monkeypatch.delenv("DG_ONEHOT_PLAN")
+    lw, la, entry = LEVELS["nonuniform_i8"]
+    for (M, N, K, variant) in [(17, 9, 20, "auto"), (200, 1, 2048, "auto"), (256, 4096, 512, "auto"), (64, 196, 576, "perm")]:
+        g = wl.small_gemm(M, N, K, seed=3)
+        case = GpuCase(g, levels=(lw, la), entry=entry)
+        name = dg.dg_gemm_codes_kernel_name(case.lut, M, N, K, variant)
+        assert not name.startswith("codes_") and name == case.kernel_name(variant)
+        Ac = torch.from_numpy(g.Ac).cuda()
+        work = torch.zeros(N * K // 4, dtype=torch.uint8, device="cuda")
+        got = dg.dg_gemm_lut_codes(case.lut, case.Wp, Ac, M, N, K, work=work, variant=variant)
+        torch.cuda.synchronize()
+        _assert_same(got.cpu().numpy(), oracle.gemm(g.Wc, g.Ac, lw, la), f"unfused gemm {(M, N, K)}")
+        with pytest.raises(dg.DgError) as e:
+            dg.dg_gemm_lut_codes(case.lut, case.Wp, Ac, M, N, K, variant=variant)
+        assert e.value.status == 1
+
+
 def test_random_convolution_shapes():
     """Seeded random convolution geometries (image, filter, stride, padding, channel counts, batch) through AUTO and
     every variant that accepts them: the oracle is the plain nested loop, so any disagreement is a kernel indexing bug."""
