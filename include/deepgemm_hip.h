@@ -174,6 +174,14 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *            same index registers) or 4-bit codes (Cin % 16 == 0, int8 entries); outputs whose stride-1
  *            axis is the channel axis (NHWC), or plain GEMMs without scale (run transposed)
  * A variant that cannot run the given shape or table returns DG_ERR_UNSUPPORTED.
+ *
+ * Test and measurement overrides, read from the environment at every call (leave them unset otherwise; the
+ * results are the same under any of them, only the kernel shape changes):
+ *   DG_ONEHOT_PLAN   forces the one-hot kernels' shape: "split" (split-K kernel), "<wn>" (tile 32*wn columns wide,
+ *                    wn = 1, 2, 4, 7) or "<wn>k<s>" (s = 2, 4 wavefronts sharing a tile); "44" is the comparison
+ *                    kernel's 128 x 128 tile.  While it is set AUTO does not move to the sparse-instruction forms.
+ *   DG_ONEHOT_WAVES  target number of wavefronts of the split-K kernel (default 2048)
+ *   DG_PERM_PLAN     index of the permute kernel's tile shape
  */
 typedef enum {
     DG_KERNEL_AUTO = 0,
