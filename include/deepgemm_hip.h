@@ -241,9 +241,10 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
  * The run-time packing stage (Sec. 5.2) and the convolution as ONE call, from activations that are still one code
  * per byte: Xc_dev is device memory, [B][H][W][Cin] uint8, values below 2^bits (higher bits of 2-bit codes are
  * masked off, as dg_pack_activations does), 16-byte aligned for the fused form.  On layers so small that a second
- * kernel launch costs as much as the layer itself (those the library runs on the one-hot split-K kernel: 2-bit
- * codes, Cin % 32 == 0, variant AUTO or ONEHOT_MFMA) the kernel reads the codes as they are and packs them in
- * registers while loading -- one launch, and Xp_work_dev is not touched.  Every other layer is packed into
+ * kernel launch costs a good part of the layer itself (those the library runs on the one-hot split-K kernel --
+ * 2-bit codes, Cin % 32 == 0, variant AUTO or ONEHOT_MFMA -- or on the few-columns kernel, variant AUTO or SMALLN)
+ * the kernel reads the codes as they are and packs them in registers while loading -- one launch, and Xp_work_dev
+ * is not touched.  Every other layer is packed into
  * Xp_work_dev (device, work_bytes >= dg_packed_bytes_bits(B*H*W, Cin, bits), else DG_ERR_BUFFER; DG_ERR_NULL if it
  * is needed and NULL) by the packing kernel and then run as dg_conv2d_lut would run it, on the same stream.
  * Outputs, scale, variant and the other errors as dg_conv2d_lut; the results are identical to dg_pack_activations
@@ -257,8 +258,8 @@ dg_status dg_conv2d_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8
 const char *dg_conv_codes_kernel_name(const dg_lut *lut, const dg_conv_desc *desc, dg_kernel variant);
 /*
  * The same for a GEMM: Ac_dev is device memory, [N][K] uint8 codes; Ap_work_dev (work_bytes >=
- * dg_packed_bytes_bits(N, K, bits)) is used when the packing is not fused (K % 32 != 0, a large problem, one or two
- * columns, another variant, 3- or 4-bit codes).  Outputs, strides, scale and the other errors as dg_gemm_lut.
+ * dg_packed_bytes_bits(N, K, bits)) is used when the packing is not fused (K % 32 != 0, a large problem, another
+ * variant, 3- or 4-bit codes).  Outputs, strides, scale and the other errors as dg_gemm_lut.
  */
 dg_status dg_gemm_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8_t *Ac_dev, int64_t M, int64_t N,
                             int64_t K, void *Ap_work_dev, size_t work_bytes, int32_t *C_dev, int64_t stride_cm,

@@ -451,14 +451,47 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
 
 namespace {
 
-// dg_conv2d_lut_codes fuses the packing into the kernel where the library's own choice for the layer (or the caller's
-// ONEHOT_MFMA) is the one-hot split-K kernel, i.e. on layers so small that a second launch costs as much as the layer.
-bool fuses_packing(const dg_lut *lut, const DgProblem &p_codes, dg_kernel variant)
+// The one-call entry points fuse the packing into the kernel where the library's own choice for the problem (or the
+// variant the caller names) is the one-hot split-K kernel or the few-columns kernel, i.e. on problems so small that a
+// second launch costs a good part of the whole.
+enum class Fuse { None, OneHot, SmallN };
+
+Fuse fuses_packing(const dg_lut *lut, const DgProblem &p_codes, dg_kernel variant)
 {
-    if (variant != DG_KERNEL_AUTO && variant != DG_KERNEL_ONEHOT_MFMA) return false;
-    if (!dg_onehot_codes_supports(lut, p_codes)) return false;
     // (the unpacked buffer's 16-byte alignment satisfies every kernel's test of the packed one)
-    return variant == DG_KERNEL_ONEHOT_MFMA || pick_kernel(lut, p_codes, DG_KERNEL_AUTO) == Pick::OneHot;
+    if ((uintptr_t)p_codes.Xp % 16 != 0 || lut->bits != 2) return Fuse::None;
+    if ((variant == DG_KERNEL_AUTO || variant == DG_KERNEL_ONEHOT_MFMA) && dg_onehot_codes_supports(lut, p_codes) &&
+        (variant == DG_KERNEL_ONEHOT_MFMA || pick_kernel(lut, p_codes, DG_KERNEL_AUTO) == Pick::OneHot))
+        return Fuse::OneHot;
+    if ((variant == DG_KERNEL_AUTO || variant == DG_KERNEL_SMALLN) && pick_kernel(lut, p_codes, variant) == Pick::SmallN)
+        return Fuse::SmallN;
+    return Fuse::None;
+}
+
+// Launch the fused form, or pack into the work buffer and run the problem as the two-call path would.
+dg_status run_codes(const char *name, const dg_lut *lut, DgProblem &p, const uint8_t *codes, int64_t rows, int64_t row_codes,
+                    void *work, size_t work_bytes, dg_kernel variant, void *hip_stream)
+{
+    p.Xp = codes;
+    switch (fuses_packing(lut, p, variant)) {
+    case Fuse::OneHot: return dg_launch_onehot_codes(lut, p, (hipStream_t)hip_stream);
+    case Fuse::SmallN: return dg_launch_smalln_codes(lut, p, (hipStream_t)hip_stream);
+    case Fuse::None: break;
+    }
+    const dg_status s = pack_common(name, codes, rows, row_codes, lut->bits, work, work_bytes, hip_stream);
+    if (s != DG_OK) return s;
+    p.Xp = (const uint8_t *)work;
+    return run(lut, p, variant, (hipStream_t)hip_stream);
+}
+
+const char *codes_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
+{
+    switch (fuses_packing(lut, p, variant)) {
+    case Fuse::OneHot: return dg_onehot_codes_config_name(lut, p);
+    case Fuse::SmallN: return "codes_smalln";
+    case Fuse::None: break;
+    }
+    return pick_name(lut, p, variant);
 }
 
 }   // namespace
@@ -476,25 +509,19 @@ dg_status dg_gemm_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8_t
     if ((scale_m_dev || lut->dtype == DG_LUT_F32) ? !Cf_dev : !C_dev) return dg_fail(DG_ERR_NULL, "%s: NULL output", name);
     if (stride_cm == 0 || stride_cn == 0) return dg_fail(DG_ERR_SHAPE, "%s: zero output stride", name);
     p.Wp = (const uint8_t *)Wp_dev;
-    p.Xp = Ac_dev;
     p.C = C_dev;
     p.Cf = Cf_dev;
     p.scale = scale_m_dev;
     p.stride_cm = stride_cm;
     p.stride_cn = stride_cn;
-    if (fuses_packing(lut, p, variant)) return dg_launch_onehot_codes(lut, p, (hipStream_t)hip_stream);
-    s = pack_common(name, Ac_dev, N, K, lut->bits, Ap_work_dev, work_bytes, hip_stream);
-    if (s != DG_OK) return s;
-    p.Xp = (const uint8_t *)Ap_work_dev;
-    return run(lut, p, variant, (hipStream_t)hip_stream);
+    return run_codes(name, lut, p, Ac_dev, N, K, Ap_work_dev, work_bytes, variant, hip_stream);
 }
 
 const char *dg_gemm_codes_kernel_name(const dg_lut *lut, int64_t M, int64_t N, int64_t K, dg_kernel variant)
 {
     DgProblem p;
     if (fill_gemm("dg_gemm_codes_kernel_name", lut, M, N, K, &p) != DG_OK) return "invalid";
-    if (fuses_packing(lut, p, variant)) return dg_onehot_codes_config_name(lut, p);
-    return pick_name(lut, p, variant);
+    return codes_name(lut, p, variant);
 }
 
 dg_status dg_conv2d_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8_t *Xc_dev, const dg_conv_desc *desc,
@@ -508,18 +535,13 @@ dg_status dg_conv2d_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8
     if (!Wp_dev || !Xc_dev) return dg_fail(DG_ERR_NULL, "%s: NULL operand", name);
     if ((scale_cout_dev || lut->dtype == DG_LUT_F32) ? !Yf_dev : !Y_dev) return dg_fail(DG_ERR_NULL, "%s: NULL output", name);
     p.Wp = (const uint8_t *)Wp_dev;
-    p.Xp = Xc_dev;
     p.C = Y_dev;
     p.Cf = Yf_dev;
     p.scale = scale_cout_dev;
     p.stride_cm = 1;
     p.stride_cn = p.M;
-    if (fuses_packing(lut, p, variant)) return dg_launch_onehot_codes(lut, p, (hipStream_t)hip_stream);
-    const int64_t rows = (int64_t)desc->B * desc->H * desc->W;
-    s = pack_common(name, Xc_dev, rows, desc->Cin, lut->bits, Xp_work_dev, work_bytes, hip_stream);
-    if (s != DG_OK) return s;
-    p.Xp = (const uint8_t *)Xp_work_dev;
-    return run(lut, p, variant, (hipStream_t)hip_stream);
+    return run_codes(name, lut, p, Xc_dev, (int64_t)desc->B * desc->H * desc->W, desc->Cin, Xp_work_dev, work_bytes, variant,
+                     hip_stream);
 }
 
 const char *dg_conv_codes_kernel_name(const dg_lut *lut, const dg_conv_desc *desc, dg_kernel variant)
@@ -528,8 +550,7 @@ const char *dg_conv_codes_kernel_name(const dg_lut *lut, const dg_conv_desc *des
     if (fill_conv("dg_conv_codes_kernel_name", lut, desc, &p) != DG_OK) return "invalid";
     p.stride_cm = 1;
     p.stride_cn = p.M;
-    if (fuses_packing(lut, p, variant)) return dg_onehot_codes_config_name(lut, p);
-    return pick_name(lut, p, variant);
+    return codes_name(lut, p, variant);
 }
 
 dg_status dg_conv2d_lut_requant(const dg_lut *lut, const void *Wp_dev, const void *Xp_dev, const dg_conv_desc *desc,

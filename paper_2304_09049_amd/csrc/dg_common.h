@@ -86,3 +86,4 @@ bool dg_sparse2p_preferred(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_sparse2p(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 bool dg_smalln_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_smalln(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+dg_status dg_launch_smalln_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream);   // p.Xp: codes one per byte

@@ -44,6 +44,7 @@
 // tile's two weight row blocks, so a tile covers 32 rows instead of 64), and the result is 256 * acc_hi + acc_lo.
 #pragma once
 
+#include "dg_codes.h"
 #include "dg_mfma_tile.h"
 
 namespace dgoh {
@@ -133,22 +134,7 @@ __device__ __forceinline__ Words<CH> load_words(const uint8_t *ptr)
     return w;
 }
 
-// The same words from codes that are still one per byte (the run-time packing stage done in the load stage): 16 bytes
-// make one word, code i at bits 2i; bits above a code's two are dropped, as the packing kernel drops them.  The four
-// dwords are transposed bytewise (8 permutes), so that dword b holds codes b, 4+b, 8+b, 12+b, one per byte; shifted left
-// by 2b and merged bit-field-wise they are the word (every bit of it has exactly one source: 14 instructions).
-__device__ __forceinline__ uint32_t pack_codes16(uint4 t)
-{
-    const uint32_t a0 = __builtin_amdgcn_perm(t.y, t.x, 0x05010400u), a1 = __builtin_amdgcn_perm(t.y, t.x, 0x07030602u);
-    const uint32_t b0 = __builtin_amdgcn_perm(t.w, t.z, 0x05010400u), b1 = __builtin_amdgcn_perm(t.w, t.z, 0x07030602u);
-    const uint32_t z0 = __builtin_amdgcn_perm(b0, a0, 0x05040100u), z1 = __builtin_amdgcn_perm(b0, a0, 0x07060302u);
-    const uint32_t z2 = __builtin_amdgcn_perm(b1, a1, 0x05040100u), z3 = __builtin_amdgcn_perm(b1, a1, 0x07060302u);
-    auto merge = [](uint32_t mask, uint32_t x, uint32_t rest) { return (x & mask) | (rest & ~mask); };
-    uint32_t w = merge(0x0C0C0C0Cu, z1 << 2, z0);
-    w = merge(0x30303030u, z2 << 4, w);
-    return merge(0xC0C0C0C0u, z3 << 6, w);
-}
-
+// The same words from codes that are still one per byte (the run-time packing stage done in the load stage).
 template <int CH>
 __device__ __forceinline__ Words<CH> load_codes(const uint8_t *ptr)
 {
@@ -157,7 +143,7 @@ __device__ __forceinline__ Words<CH> load_codes(const uint8_t *ptr)
     for (int i = 0; i < CH; ++i) t[i] = ((const uint4 *)ptr)[i];
     Words<CH> w;
 #pragma unroll
-    for (int i = 0; i < CH; ++i) w.v[i] = pack_codes16(t[i]);
+    for (int i = 0; i < CH; ++i) w.v[i] = dg_pack_codes16(t[i]);
     return w;
 }
 

@@ -12,6 +12,7 @@
 // a weight row is read with fully coalesced 8-byte loads).  Every lane thus holds a partial sum of every
 // row; the partial sums of a wavefront are added with DPP row operations (the paper's Listing 1 plays this
 // role for an AVX2 register), the four wavefronts meet in LDS.
+#include "dg_codes.h"
 #include "dg_common.h"
 
 namespace {
@@ -62,7 +63,9 @@ __device__ __forceinline__ void selectors(uint32_t x0, uint32_t x1, uint32_t am,
 }
 
 // NC activation rows per pass; RB weight rows per block (all of a block's words are loaded before any is used).
-template <int NC, int RB>
+// RAW: the activations are codes one per byte ([N][K] bytes at p.Xp), packed in registers as they are loaded -- for a
+// problem this small the packing kernel's launch would cost a third of the whole.
+template <int NC, int RB, bool RAW>
 __global__ void __launch_bounds__(256)
 smalln_kernel(SmallNArgs a)
 {
@@ -102,7 +105,13 @@ smalln_kernel(SmallNArgs a)
                 for (int c = 0; c < NC; ++c) {
                     int n = n0 + c;
                     if (n >= p.N) n = p.N - 1;
-                    const uint2 x = *(const uint2 *)(p.Xp + (int64_t)n * row_bytes + koff);
+                    uint2 x;
+                    if constexpr (RAW) {
+                        const uint4 *codes = (const uint4 *)(p.Xp + (int64_t)n * p.K + 4 * koff);
+                        x = make_uint2(dg_pack_codes16(codes[0]), dg_pack_codes16(codes[1]));
+                    } else {
+                        x = *(const uint2 *)(p.Xp + (int64_t)n * row_bytes + koff);
+                    }
 #pragma unroll
                     for (int q = 0; q < 8; ++q) {
                         pool[c][q] = s_table[(x.x >> (4 * q)) & 15u];
@@ -166,7 +175,10 @@ bool dg_smalln_supports(const dg_lut *lut, const DgProblem &p)
     return true;
 }
 
-dg_status dg_launch_smalln(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
+namespace {
+
+template <bool RAW>
+dg_status launch(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
 {
     SmallNArgs a;
     a.p = p;
@@ -186,10 +198,23 @@ dg_status dg_launch_smalln(const dg_lut *lut, const DgProblem &p, hipStream_t st
     a.blocks_per_wg = per_wg;
     const dim3 grid((unsigned)((total_blocks + per_wg - 1) / per_wg));
     if (p.N >= 4)
-        hipLaunchKernelGGL((smalln_kernel<4, 16>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((smalln_kernel<4, 16, RAW>), grid, dim3(256), 0, stream, a);
     else if (p.N >= 2)
-        hipLaunchKernelGGL((smalln_kernel<2, 16>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((smalln_kernel<2, 16, RAW>), grid, dim3(256), 0, stream, a);
     else
-        hipLaunchKernelGGL((smalln_kernel<1, 8>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((smalln_kernel<1, 8, RAW>), grid, dim3(256), 0, stream, a);
     return dg_check_launch("smalln_kernel");
+}
+
+}   // namespace
+
+dg_status dg_launch_smalln(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
+{
+    return launch<false>(lut, p, stream);
+}
+
+// p.Xp = the activation codes one per byte, 16-byte aligned
+dg_status dg_launch_smalln_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
+{
+    return launch<true>(lut, p, stream);
 }

@@ -197,7 +197,7 @@ def test_kernel_names_need_no_gpu():
     assert dg.dg_conv_codes_kernel_name(lut, small, "onehot_smfmac") == dg.dg_conv_kernel_name(lut, small, "onehot_smfmac")
     assert dg.dg_conv_codes_kernel_name(lut, large) == dg.dg_conv_kernel_name(lut, large) == "onehot_smfmac_64x128"
     assert dg.dg_gemm_codes_kernel_name(lut, 64, 196, 576) == "codes_onehot_mfma_splitk_s9"
-    assert dg.dg_gemm_codes_kernel_name(lut, 8192, 1, 8192) == "smalln"
+    assert dg.dg_gemm_codes_kernel_name(lut, 8192, 1, 8192) == "codes_smalln"
     assert dg.dg_gemm_codes_kernel_name(lut, 8192, 8192, 8192) == "onehot_smfmac_64x128"
 
 

@@ -297,7 +297,8 @@ def test_convolution_from_unpacked_codes(monkeypatch):
 def test_gemm_from_unpacked_codes(monkeypatch):
     """dg_gemm_lut_codes against the oracle: small GEMMs where the split-K kernel packs the codes itself (row-major and
     column-major output, scaled output, one- and two-plane tables, ragged M and N, chunk widths of 1, 2 and 4 words), and
-    GEMMs it hands to the packing kernel first (K % 32 != 0, one column, a large problem, another variant)."""
+    GEMMs with one to a few columns on the few-columns kernel, which does the same, and GEMMs it hands to the packing
+    kernel first (K % 32 != 0, a large problem, another variant)."""
     for table in ("nonuniform_i8", "extreme_i16"):
         lw, la, entry = LEVELS[table]
         for (M, N, K) in [(64, 196, 576), (70, 300, 96), (33, 250, 1024), (130, 77, 64), (5, 16, 4096), (1, 40, 32)]:
@@ -319,7 +320,21 @@ def test_gemm_from_unpacked_codes(monkeypatch):
             assert np.array_equal(got.cpu().numpy(), oracle.scale_epilogue_rows(want, g.scale)), "scaled codes gemm"
     monkeypatch.delenv("DG_ONEHOT_PLAN")
     lw, la, entry = LEVELS["nonuniform_i8"]
-    for (M, N, K, variant) in [(17, 9, 20, "auto"), (200, 1, 2048, "auto"), (256, 4096, 512, "auto"), (64, 196, 576, "perm")]:
+    # one or two columns: the few-columns kernel reads the codes as they are (AUTO for N <= 2, or asked for by name)
+    for (M, N, K, variant) in [(200, 1, 2048, "auto"), (37, 2, 4096, "auto"), (64, 3, 1024, "smalln"), (130, 5, 8192, "smalln"),
+                               (9, 7, 96, "smalln")]:
+        g = wl.make_inputs(wl.Workload(name="g", kind="gemm", M=M, N=N, K=K, scale=True, seed=M + N + K))
+        case = GpuCase(g, levels=(lw, la), entry=entry)
+        assert dg.dg_gemm_codes_kernel_name(case.lut, M, N, K, variant) == "codes_smalln"
+        Ac = torch.from_numpy(g.Ac | 0xA8).cuda()                                           # garbage above bit 1
+        want = oracle.gemm(g.Wc, g.Ac, lw, la)
+        got = dg.dg_gemm_lut_codes(case.lut, case.Wp, Ac, M, N, K, variant=variant)
+        torch.cuda.synchronize()
+        _assert_same(got.cpu().numpy(), want, f"codes gemm {(M, N, K)} few columns")
+        got = dg.dg_gemm_lut_codes(case.lut, case.Wp, Ac, M, N, K, scale=case.scale, variant=variant)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), oracle.scale_epilogue_rows(want, g.scale)), "scaled codes gemm, few columns"
+    for (M, N, K, variant) in [(17, 9, 20, "auto"), (256, 4096, 512, "auto"), (64, 196, 576, "perm")]:
         g = wl.small_gemm(M, N, K, seed=3)
         case = GpuCase(g, levels=(lw, la), entry=entry)
         name = dg.dg_gemm_codes_kernel_name(case.lut, M, N, K, variant)
