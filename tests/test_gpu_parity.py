@@ -227,6 +227,15 @@ def test_two_plane_tables_on_the_sparse_instruction():
     assert big.kernel_name("auto") == "onehot_smfmac_2p_32x128"
     want = oracle.conv2d(big.inp.Wc, big.inp.Ac, lw, la, stride=(1, 1), pad=(1, 1))
     _assert_same(big.run("auto").cpu().numpy(), want, "AUTO on a large two-plane layer")
+    # the fused layer on the same large layer (AUTO: the same sparse-instruction kernel with the re-quantising epilogue)
+    cb = wl.small_conv(16, 56, 56, 64, 96, 3, 3, (1, 1), (1, 1), seed=5, scale=True)
+    bigs = GpuCase(cb, levels=(lw, la), entry=entry)
+    y = oracle.scale_epilogue_nhwc(want, cb.scale)
+    qs = float(np.float32(3.0 / max(1e-6, float(np.percentile(np.abs(y), 90)))))
+    packed = oracle.pack_codes(oracle.quantize_codes(y, qs, 0.5, 0, 3).reshape(-1, 96))
+    got = dg.dg_conv2d_lut_requant(bigs.lut, bigs.Wp, bigs.Ap, bigs.desc, bigs.scale, qs, 0.5, 0)
+    torch.cuda.synchronize()
+    _assert_same(got.cpu().numpy().reshape(-1, 24), packed, "fused large two-plane layer")
     small = GpuCase(wl.small_conv(1, 14, 14, 32, 96, 1, 1, (1, 1), (0, 0), seed=5), levels=(lw, la), entry=entry)
     assert small.kernel_name("auto").startswith("onehot_mfma_2p_")
 
