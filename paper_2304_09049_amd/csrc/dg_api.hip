@@ -581,11 +581,14 @@ dg_status dg_conv2d_lut_requant(const dg_lut *lut, const void *Wp_dev, const voi
         return dg_launch_sparse(lut, p, (hipStream_t)hip_stream);
     if (variant == DG_KERNEL_ONEHOT_SMFMAC && dg_sparse2p_supports(lut, p))
         return dg_launch_sparse2p(lut, p, (hipStream_t)hip_stream);
+    if (variant == DG_KERNEL_ONEHOT_SMFMAC && dg_sparse4_supports(lut, p))
+        return dg_launch_sparse4(lut, p, (hipStream_t)hip_stream);
     if ((variant != DG_KERNEL_AUTO && variant != DG_KERNEL_ONEHOT_MFMA) || lut->dtype == DG_LUT_F32 ||
         !dg_onehot_supports(lut, p))
         return dg_fail(DG_ERR_UNSUPPORTED, "%s: needs the one-hot matrix-core kernel (variant %d, Cin=%d, table range %d..%d)",
                        name, (int)variant, p.Cin, lut->min_entry, lut->max_entry);
     if (variant == DG_KERNEL_AUTO && dg_sparse2p_preferred(lut, p)) return dg_launch_sparse2p(lut, p, (hipStream_t)hip_stream);
+    if (variant == DG_KERNEL_AUTO && dg_sparse4_preferred(lut, p)) return dg_launch_sparse4(lut, p, (hipStream_t)hip_stream);
     if (variant == DG_KERNEL_AUTO && dg_sparse_preferred(lut, p)) return dg_launch_sparse(lut, p, (hipStream_t)hip_stream);
     return dg_launch_onehot(lut, p, (hipStream_t)hip_stream);
 }

@@ -714,6 +714,17 @@ def test_wide_codes_gemm_and_conv(bits, plan, monkeypatch):
         torch.cuda.synchronize()
         _assert_same(y.cpu().numpy(), oracle.conv2d(Wc, Xc, lw, la, stride=stride, pad=pad),
                      f"{bits}-bit conv {(B, H, W, Cin, Cout)} {plan}")
+        if Cout % 4 == 0 and variant != "lds":
+            # the fused layer takes these tables too: wide codes in, the next layer's 2-bit codes out
+            scale = torch.from_numpy(np.linspace(0.5, 1.5, Cout, dtype=np.float32)).cuda()
+            acc = oracle.conv2d(Wc, Xc, lw, la, stride=stride, pad=pad)
+            yf = oracle.scale_epilogue_nhwc(acc, scale.cpu().numpy())
+            qs = float(np.float32(3.0 / max(1e-6, float(np.percentile(np.abs(yf), 90)))))
+            want = oracle.pack_codes(oracle.quantize_codes(yf, qs, 0.5, 0, 3).reshape(-1, Cout))
+            got = dg.dg_conv2d_lut_requant(lut, Wp, Xp, dg.conv_desc(B, H, W, Cin, Cout, KH, KW, stride, pad), scale, qs, 0.5, 0,
+                                           variant=variant)
+            torch.cuda.synchronize()
+            _assert_same(got.cpu().numpy().reshape(-1, Cout // 4), want, f"{bits}-bit fused layer {(B, H, W, Cin, Cout)} {plan}")
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -844,4 +855,12 @@ def test_four_bit_auto_takes_the_sparse_kernel_on_large_layers():
     assert dg.dg_conv_kernel_name(lut, desc) == "onehot_smfmac4_64x128"
     y = dg.dg_conv2d_lut(lut, Wp, Xp, desc)
     torch.cuda.synchronize()
-    _assert_same(y.cpu().numpy(), oracle.conv2d(Wc, Xc, lw, la, stride=(1, 1), pad=(1, 1)), "4-bit conv, AUTO")
+    acc = oracle.conv2d(Wc, Xc, lw, la, stride=(1, 1), pad=(1, 1))
+    _assert_same(y.cpu().numpy(), acc, "4-bit conv, AUTO")
+    scale = torch.from_numpy(np.linspace(0.5, 1.5, Cout, dtype=np.float32)).cuda()
+    yf = oracle.scale_epilogue_nhwc(acc, scale.cpu().numpy())
+    qs = float(np.float32(3.0 / max(1e-6, float(np.percentile(np.abs(yf), 90)))))
+    want = oracle.pack_codes(oracle.quantize_codes(yf, qs, 0.5, 0, 3).reshape(-1, Cout))
+    got = dg.dg_conv2d_lut_requant(lut, Wp, Xp, desc, scale, qs, 0.5, 0)
+    torch.cuda.synchronize()
+    _assert_same(got.cpu().numpy().reshape(-1, Cout // 4), want, "4-bit fused layer, AUTO (sparse-instruction kernel)")
