@@ -475,7 +475,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int32 accumulation of int8 table entries (2-bit codes); fp32 scale epilogue",
+        "dtype": "int32",
+        "dtype_note": "int32 accumulation of int8 table entries selected by 2-bit codes; one fp32 multiply per output in the scale epilogue",
         "data": "synthetic",
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "variant": args.variant, "kernel": dom_name,
                    "step": ("dg_conv2d_lut_codes" if w.kind == "conv" else "dg_gemm_lut_codes") +
