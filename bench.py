@@ -509,6 +509,11 @@ def main():
                     ms = time_steady(torch, fn, use_graph)
                     rep = kernel_report(ww, ms, kname)
                     rep.update({"workload": wname, "variant": variant})
+                    if variant == "auto":
+                        # the whole step on this shape (unpacked codes in, through the one-call entry point) beside its
+                        # convolution / GEMM kernel alone
+                        rep["step_kernel"] = rr.step_kernel_name()
+                        rep["step_us"] = round(time_steady(torch, rr.step, use_graph) * 1e3, 3)
                     if ww.ops < 1e9:
                         # roofline time far below the launch overhead: also what one isolated launch costs
                         rep["single_launch_us"] = single_launch_us(torch, fn)

@@ -242,7 +242,8 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
  * per byte: Xc_dev is device memory, [B][H][W][Cin] uint8, values below 2^bits (higher bits of 2-bit codes are
  * masked off, as dg_pack_activations does), 16-byte aligned for the fused form.  On layers so small that a second
  * kernel launch costs a good part of the layer itself (those the library runs on the one-hot split-K kernel --
- * 2-bit codes, Cin % 32 == 0, variant AUTO or ONEHOT_MFMA -- or on the few-columns kernel, variant AUTO or SMALLN)
+ * 2-bit codes, Cin % 32 == 0, variant ONEHOT_MFMA, or AUTO while Cout is small enough that packing once per 32
+ * output channels costs less than the launch -- or on the few-columns kernel, variant AUTO or SMALLN)
  * the kernel reads the codes as they are and packs them in registers while loading -- one launch, and Xp_work_dev
  * is not touched.  Every other layer is packed into
  * Xp_work_dev (device, work_bytes >= dg_packed_bytes_bits(B*H*W, Cin, bits), else DG_ERR_BUFFER; DG_ERR_NULL if it

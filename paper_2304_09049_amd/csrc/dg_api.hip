@@ -461,7 +461,8 @@ Fuse fuses_packing(const dg_lut *lut, const DgProblem &p_codes, dg_kernel varian
     // (the unpacked buffer's 16-byte alignment satisfies every kernel's test of the packed one)
     if ((uintptr_t)p_codes.Xp % 16 != 0 || lut->bits != 2) return Fuse::None;
     if ((variant == DG_KERNEL_AUTO || variant == DG_KERNEL_ONEHOT_MFMA) && dg_onehot_codes_supports(lut, p_codes) &&
-        (variant == DG_KERNEL_ONEHOT_MFMA || pick_kernel(lut, p_codes, DG_KERNEL_AUTO) == Pick::OneHot))
+        (variant == DG_KERNEL_ONEHOT_MFMA ||
+         (dg_onehot_codes_pays(p_codes) && pick_kernel(lut, p_codes, DG_KERNEL_AUTO) == Pick::OneHot)))
         return Fuse::OneHot;
     if ((variant == DG_KERNEL_AUTO || variant == DG_KERNEL_SMALLN) && pick_kernel(lut, p_codes, variant) == Pick::SmallN)
         return Fuse::SmallN;

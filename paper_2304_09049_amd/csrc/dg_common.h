@@ -72,6 +72,7 @@ dg_status dg_launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t st
 const char *dg_onehot_config_name(const dg_lut *lut, const DgProblem &p);
 // the one-hot split-K kernel reading activations one code per byte (p.Xp = those bytes) and packing them as it loads
 bool dg_onehot_codes_supports(const dg_lut *lut, const DgProblem &p);
+bool dg_onehot_codes_pays(const DgProblem &p);      // AUTO: the repeated packing costs less than the saved launch
 dg_status dg_launch_onehot_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 const char *dg_onehot_codes_config_name(const dg_lut *lut, const DgProblem &p);
 bool dg_sparse_supports(const dg_lut *lut, const DgProblem &p);

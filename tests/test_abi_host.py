@@ -198,6 +198,9 @@ def test_kernel_names_need_no_gpu():
     assert dg.dg_conv_codes_kernel_name(lut, large) == dg.dg_conv_kernel_name(lut, large) == "onehot_smfmac_64x128"
     assert dg.dg_gemm_codes_kernel_name(lut, 64, 196, 576) == "codes_onehot_mfma_splitk_s9"
     assert dg.dg_gemm_codes_kernel_name(lut, 8192, 1, 8192) == "codes_smalln"
+    # 256 row blocks would each pack the activations for themselves: two kernels unless the fused form is asked for by name
+    assert dg.dg_gemm_codes_kernel_name(lut, 8192, 16, 8192) == dg.dg_gemm_kernel_name(lut, 8192, 16, 8192)
+    assert dg.dg_gemm_codes_kernel_name(lut, 8192, 16, 8192, "onehot_mfma").startswith("codes_onehot_mfma_splitk_s")
     assert dg.dg_gemm_codes_kernel_name(lut, 8192, 8192, 8192) == "onehot_smfmac_64x128"
 
 
