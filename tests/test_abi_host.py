@@ -118,6 +118,29 @@ def test_conv_argument_errors_are_caught_before_any_launch():
     assert call(dg.conv_desc(0, 8, 8, 8, 4, 3, 3)) == 2                    # empty batch
 
 
+def test_one_call_entry_points_check_their_arguments_before_any_launch():
+    L = dg.lib()
+    lut = dg.dg_build_lut((-2, -1, 0, 1), (0, 1, 2, 3))
+    fake = ctypes.c_void_p(0x1000)
+    g = lambda w, a, M, N, K, work, wb, c: L.dg_gemm_lut_codes(lut.handle, w, a, M, N, K, work, wb, c, N, 1, None, None, 0, None)
+    assert g(None, fake, 4, 4, 8, fake, 100, fake) == 1                      # NULL operand
+    assert g(fake, fake, 4, 4, 8, fake, 100, None) == 1                      # NULL output
+    assert g(fake, fake, 4, 4, 6, fake, 100, fake) == 2                      # K % 4 != 0
+    assert g(fake, fake, 4, 0, 8, fake, 100, fake) == 2
+    assert g(fake, fake, 4, 4, 8, None, 0, fake) == 1                        # K % 32 != 0 is never fused: the work buffer is needed
+    assert g(fake, fake, 4, 4, 8, fake, 7, fake) == 4                        # ... and must hold 4 * 8 / 4 bytes
+    assert L.dg_gemm_lut_codes(None, fake, fake, 4, 4, 8, fake, 100, fake, 4, 1, None, None, 0, None) == 1
+    desc = dg.conv_desc(1, 8, 8, 8, 4, 3, 3, (1, 1), (1, 1))
+    c = lambda w, x, d, work, wb, y: L.dg_conv2d_lut_codes(lut.handle, w, x, ctypes.byref(d) if d is not None else None, work, wb,
+                                                           y, None, None, 0, None)
+    assert c(None, fake, desc, fake, 1000, fake) == 1
+    assert c(fake, fake, None, fake, 1000, fake) == 1
+    assert c(fake, fake, desc, fake, 1000, None) == 1
+    assert c(fake, fake, dg.conv_desc(1, 8, 8, 6, 4, 3, 3), fake, 1000, fake) == 2     # Cin % 4 != 0
+    assert c(fake, fake, desc, None, 0, fake) == 1                           # Cin = 8 is never fused: the work buffer is needed
+    assert c(fake, fake, desc, fake, 8 * 8 * 8 // 4 - 1, fake) == 4
+
+
 def test_pack_argument_errors():
     L = dg.lib()
     fake = ctypes.c_void_p(0x1000)
