@@ -464,7 +464,10 @@ Fuse fuses_packing(const dg_lut *lut, const DgProblem &p_codes, dg_kernel varian
         (variant == DG_KERNEL_ONEHOT_MFMA ||
          (dg_onehot_codes_pays(p_codes) && pick_kernel(lut, p_codes, DG_KERNEL_AUTO) == Pick::OneHot)))
         return Fuse::OneHot;
-    if ((variant == DG_KERNEL_AUTO || variant == DG_KERNEL_SMALLN) && pick_kernel(lut, p_codes, variant) == Pick::SmallN)
+    // (the few-columns kernel packs once per row block and pass of four columns, about 7 % more work for it: less than
+    // a launch while the columns are few, which is where AUTO uses that kernel anyway)
+    if ((variant == DG_KERNEL_SMALLN || (variant == DG_KERNEL_AUTO && p_codes.N <= 4)) &&
+        pick_kernel(lut, p_codes, variant) == Pick::SmallN)
         return Fuse::SmallN;
     return Fuse::None;
 }
