@@ -197,7 +197,9 @@ def test_kernel_names_need_no_gpu():
     assert dg.dg_gemm_kernel_name(lut, 64, 196, 576).startswith("onehot_mfma_splitk_s")
     assert dg.dg_gemm_kernel_name(lut, 8192, 8192, 8192) == "onehot_smfmac_64x128"     # large unshared tiles: the sparse instruction
     assert dg.dg_gemm_kernel_name(lut, 8192, 8192, 8192, "onehot_mfma") == "onehot_mfma_64x128"
-    assert dg.dg_gemm_kernel_name(lut, 8192, 256, 8192) == "onehot_mfma_64x64_k4"      # wavefronts share tiles
+    assert dg.dg_gemm_kernel_name(lut, 8192, 256, 8192) == "onehot_smfmac_64x64_k4"    # wavefronts share tiles (512 of them: sparse)
+    assert dg.dg_gemm_kernel_name(lut, 8192, 256, 8192, "onehot_mfma") == "onehot_mfma_64x64_k4"
+    assert dg.dg_gemm_kernel_name(lut, 8192, 64, 8192) == "onehot_mfma_64x32_k4"       # narrow shared tiles stay dense
     assert dg.dg_gemm_kernel_name(lut, 8192, 1, 8192) == "smalln"
     assert dg.dg_gemm_kernel_name(lut, 64, 196, 48).startswith("perm")        # Cin % 32 != 0, % 16 == 0
     assert dg.dg_gemm_kernel_name(lut, 5, 7, 12) == "lds"                      # Cin % 16 != 0
