@@ -271,11 +271,13 @@ bool sparse4_takes(const dg_lut *lut, const DgProblem &p)
 
 bool dg_sparse4_supports(const dg_lut *lut, const DgProblem &p) { return sparse4_takes(lut, p); }
 
-// AUTO: where the 64 x 128 tiles give at least every second SIMD a wavefront (measured: 784 tiles 22 % faster than the
-// dense-instruction kernel, 196 tiles 12 % slower; that kernel's narrower tiles and split-K form serve the smaller layers)
+// AUTO: where the 64 x 128 tiles give at least every second SIMD a wavefront and K is not too short for such a tile
+// (measured on 14 layers: 784 tiles and more 22 - 41 % faster than the dense-instruction kernel, 392 tiles even, 196
+// tiles 12 % slower, K = 64 at 784 tiles 13 % slower; that kernel's narrower tiles and split-K form serve the rest)
 bool dg_sparse4_preferred(const dg_lut *lut, const DgProblem &p)
 {
-    return sparse4_takes(lut, p) && tile_count(sparse_problem(p), 2, 4) >= 512 && getenv("DG_ONEHOT_PLAN") == nullptr;
+    return sparse4_takes(lut, p) && tile_count(sparse_problem(p), 2, 4) >= 512 && p.K >= 256 &&
+           getenv("DG_ONEHOT_PLAN") == nullptr;
 }
 
 dg_status dg_launch_sparse4(const dg_lut *lut, const DgProblem &p0, hipStream_t stream)

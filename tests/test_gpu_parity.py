@@ -838,7 +838,7 @@ def test_four_bit_auto_takes_the_sparse_kernel_on_large_layers():
     lw, la = WIDE[4]
     lut = dg.dg_build_lut_bits(4, lw, la, dg.DG_LUT_I8)
     rng = np.random.default_rng(77)
-    M, N, K = 130, 32770, 48                                # ragged in M and N; 3 x 257 tiles
+    M, N, K = 130, 32770, 272                               # ragged in M and N; 3 x 257 tiles; one-word chunks
     Wc, Ac = wl.draw_codes(rng, (M, K), nlev=16), wl.draw_codes(rng, (N, K), nlev=16)
     Wp = dg.dg_pack_codes_bits(torch.from_numpy(Wc).cuda(), M, K, 4)
     Ap = dg.dg_pack_codes_bits(torch.from_numpy(Ac).cuda(), N, K, 4)
