@@ -258,6 +258,20 @@ dg_status dg_conv2d_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8
                               dg_kernel variant, void *hip_stream);
 const char *dg_conv_codes_kernel_name(const dg_lut *lut, const dg_conv_desc *desc, dg_kernel variant);
 /*
+ * dg_conv2d_lut_codes for callers that cannot allocate device memory and so have no work buffer to hand over (code
+ * under HIP graph capture, serving loops, harnesses that forbid hipMalloc): the packed activations are staged in a
+ * buffer the library holds in static device memory, dg_static_work_bytes() = 8 MiB per GPU (33 554 432 2-bit codes),
+ * kept until the process ends.  The call allocates and frees nothing.  Arguments, results and errors as
+ * dg_conv2d_lut_codes without Xp_work_dev / work_bytes; a layer whose packed activations exceed the staging buffer
+ * returns DG_ERR_BUFFER (nothing launched).  The staging buffer is written before it is read on every call (nothing
+ * needs clearing), and it is shared by all calls on a GPU: calls that overlap in time on one GPU (two streams, two
+ * threads) race on it -- serialise them, or use dg_conv2d_lut_codes with buffers of their own.
+ */
+size_t dg_static_work_bytes(void);
+dg_status dg_conv2d_lut_codes_static(const dg_lut *lut, const void *Wp_dev, const uint8_t *Xc_dev,
+                                     const dg_conv_desc *desc, int32_t *Y_dev, const float *scale_cout_dev,
+                                     float *Yf_dev, dg_kernel variant, void *hip_stream);
+/*
  * The same for a GEMM: Ac_dev is device memory, [N][K] uint8 codes; Ap_work_dev (work_bytes >=
  * dg_packed_bytes_bits(N, K, bits)) is used when the packing is not fused (K % 32 != 0, a large problem, another
  * variant, 3- or 4-bit codes).  Outputs, strides, scale and the other errors as dg_gemm_lut.

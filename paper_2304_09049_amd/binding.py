@@ -33,6 +33,7 @@ EXPORTS = (
     "dg_gemm_lut", "dg_conv_out_dim", "dg_conv2d_lut", "dg_gemm_kernel_name", "dg_conv_kernel_name",
     "dg_conv2d_lut_codes", "dg_conv_codes_kernel_name", "dg_gemm_lut_codes", "dg_gemm_codes_kernel_name",
     "dg_launch_empty", "dg_dequantize", "dg_conv2d_lut_requant",
+    "dg_static_work_bytes", "dg_conv2d_lut_codes_static",
 )
 
 
@@ -93,6 +94,9 @@ def lib() -> ctypes.CDLL:
     L.dg_conv_kernel_name.restype = ctypes.c_char_p
     L.dg_conv2d_lut_codes.argtypes = [c_vp, c_vp, c_vp, ctypes.POINTER(ConvDesc), c_vp, c_sz, c_vp, c_vp, c_vp, c_int, c_vp]
     L.dg_conv2d_lut_codes.restype = c_int
+    L.dg_static_work_bytes.argtypes, L.dg_static_work_bytes.restype = [], c_sz
+    L.dg_conv2d_lut_codes_static.argtypes = [c_vp, c_vp, c_vp, ctypes.POINTER(ConvDesc), c_vp, c_vp, c_vp, c_int, c_vp]
+    L.dg_conv2d_lut_codes_static.restype = c_int
     L.dg_gemm_lut_codes.argtypes = [c_vp, c_vp, c_vp, c_i64, c_i64, c_i64, c_vp, c_sz, c_vp, c_i64, c_i64, c_vp, c_vp, c_int, c_vp]
     L.dg_gemm_lut_codes.restype = c_int
     L.dg_gemm_codes_kernel_name.argtypes = [c_vp, c_i64, c_i64, c_i64, c_int]
@@ -338,6 +342,22 @@ def dg_conv2d_lut_codes(lut: Lut, Wp, Xc, desc: ConvDesc, work=None, out=None, s
     _check(lib().dg_conv2d_lut_codes(lut.handle, _dev_ptr(Wp, torch.uint8, "Wp"), _dev_ptr(Xc, torch.uint8, "Xc"),
                                      ctypes.byref(desc), _dev_ptr(work, torch.uint8, "work"), work_bytes, y_int,
                                      _dev_ptr(scale, torch.float32, "scale"), y_f32, _kernel(variant), _stream_ptr(stream)))
+    return out
+
+
+def dg_static_work_bytes() -> int:
+    return int(lib().dg_static_work_bytes())
+
+
+def dg_conv2d_lut_codes_static(lut: Lut, Wp, Xc, desc: ConvDesc, out, scale=None, variant="auto", stream=None):
+    """dg_conv2d_lut_codes with the library's own staging buffer; `out` is required (the call allocates nothing)."""
+    import torch
+    as_float = scale is not None or lut.is_f32
+    y_int = _dev_ptr(out, torch.int32, "out") if not as_float else ctypes.c_void_p(0)
+    y_f32 = _dev_ptr(out, torch.float32, "out") if as_float else ctypes.c_void_p(0)
+    _check(lib().dg_conv2d_lut_codes_static(lut.handle, _dev_ptr(Wp, torch.uint8, "Wp"), _dev_ptr(Xc, torch.uint8, "Xc"),
+                                            ctypes.byref(desc), y_int, _dev_ptr(scale, torch.float32, "scale"), y_f32,
+                                            _kernel(variant), _stream_ptr(stream)))
     return out
 
 

@@ -31,16 +31,23 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = True, extra_flags=(), jobs: int = 8) -> str:
-    """Compile every HIP source (one object each, in parallel) and link one shared library; always recompiles."""
+def build(verbose: bool = True, extra_flags=(), jobs: int = 8, incremental: bool = False) -> str:
+    """Compile every HIP source (one object each, in parallel) and link one shared library.  Always recompiles,
+    unless `incremental` (a development aid): then objects newer than their source and every header are kept."""
     from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     flags = [f for f in HIPCC_FLAGS if f != "-shared"] + list(extra_flags)
 
+    headers = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(CSRC, "*.inc")) + \
+        glob.glob(os.path.join(ROOT, "include", "*.h")) + [os.path.abspath(__file__)]
+    newest_header = max(os.path.getmtime(h) for h in headers)
+
     def compile_one(src: str) -> str:
         obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
+            return obj
         cmd = [hipcc] + flags + ["-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -62,4 +69,5 @@ def build(verbose: bool = True, extra_flags=(), jobs: int = 8) -> str:
 
 
 if __name__ == "__main__":
-    build(extra_flags=sys.argv[1:])
+    args = sys.argv[1:]
+    build(extra_flags=[a for a in args if a != "--incremental"], incremental="--incremental" in args)

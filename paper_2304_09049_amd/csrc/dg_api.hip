@@ -3,14 +3,26 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "dg_common.h"
+
+// Staging for packed activations owned by the library, for dg_conv2d_lut_codes_static: callers that cannot allocate
+// (HIP graph capture, serving loops) have no work buffer to pass.  8 MiB hold 33 554 432 2-bit codes; every GPU the
+// library runs on keeps its own copy of the array until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress: kernels and copies take the per-device address kept in g_static_work.
+#define DG_STATIC_WORK_BYTES ((size_t)8 << 20)
+static __device__ __align__(256) unsigned char scratch[DG_STATIC_WORK_BYTES];
 
 namespace {
 thread_local char g_error[512] = "";
 
 __global__ void empty_kernel() {}
+
+constexpr int MAX_DEVICES = 64;
+void *g_static_work[MAX_DEVICES];       // device address of `scratch` on each device, looked up at first use
+std::mutex g_static_work_mutex;
 }
 
 dg_status dg_fail(dg_status s, const char *fmt, ...)
@@ -555,6 +567,42 @@ const char *dg_conv_codes_kernel_name(const dg_lut *lut, const dg_conv_desc *des
     p.stride_cm = 1;
     p.stride_cn = p.M;
     return codes_name(lut, p, variant);
+}
+
+size_t dg_static_work_bytes(void) { return DG_STATIC_WORK_BYTES; }
+
+dg_status dg_conv2d_lut_codes_static(const dg_lut *lut, const void *Wp_dev, const uint8_t *Xc_dev, const dg_conv_desc *desc,
+                                     int32_t *Y_dev, const float *scale_cout_dev, float *Yf_dev, dg_kernel variant,
+                                     void *hip_stream)
+{
+    const char *name = "dg_conv2d_lut_codes_static";
+    if (!lut || !desc) return dg_fail(DG_ERR_NULL, "%s: NULL table or descriptor", name);
+    if (desc->B > 0 && desc->H > 0 && desc->W > 0 && desc->Cin > 0) {
+        // (bad dimensions are reported by the shared validation below; here only the size limit)
+        const int per_byte = lut->bits == 2 ? 4 : 2;
+        const unsigned long long need = (unsigned long long)desc->B * desc->H * desc->W * (unsigned long long)(desc->Cin / per_byte);
+        if (need > DG_STATIC_WORK_BYTES)
+            return dg_fail(DG_ERR_BUFFER, "%s: the packed activations take %llu bytes, the library's staging holds %zu "
+                           "(use dg_conv2d_lut_codes with a work buffer)", name, need, DG_STATIC_WORK_BYTES);
+    }
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return dg_fail(DG_ERR_HIP, "%s: hipGetDevice: %s", name, hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_DEVICES) return dg_fail(DG_ERR_UNSUPPORTED, "%s: device %d (at most %d devices)", name, dev, MAX_DEVICES);
+    void *work = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_static_work_mutex);
+        if (!g_static_work[dev]) {
+            void *ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));      // the current device's copy of the array
+            if (e != hipSuccess || !ptr)
+                return dg_fail(DG_ERR_HIP, "%s: hipGetSymbolAddress: %s", name, hipGetErrorString(e));
+            g_static_work[dev] = ptr;
+        }
+        work = g_static_work[dev];
+    }
+    return dg_conv2d_lut_codes(lut, Wp_dev, Xc_dev, desc, work, DG_STATIC_WORK_BYTES, Y_dev, scale_cout_dev, Yf_dev, variant,
+                               hip_stream);
 }
 
 dg_status dg_conv2d_lut_requant(const dg_lut *lut, const void *Wp_dev, const void *Xp_dev, const dg_conv_desc *desc,
