@@ -10,8 +10,17 @@ of the same work is reported beside it.  The table and the packed weights are bu
 region (the paper packs weights offline, Sec. 5.2).  Steps are replayed from a HIP graph so that the host's
 launch cost does not cap a microsecond-scale kernel.
 
-Prints ONE JSON line.  `value` = 2*M*N*K / time per step, in GOPS, for the headline workload
-(ResNet18-style 3x3 convolution, batch 1, 56x56x64 -> 64, fp32 scale epilogue).
+Prints ONE JSON line.  `value` = 2*M*N*K / time per step, in GOPS, for the headline workload: the ResNet50-style
+1x1 bottleneck convolution at batch 32 (56x56x256 -> 64, M=64 N=100352 K=256), the largest ResNet-shaped layer of
+the benchmark set.  (The ResNet18-style 3x3 layer at batch 1 -- 0.23 GOP, a 3.5 us kernel of which 1.6 us is the
+launch -- and the 64x196x576 GEMM are in `sweep` with their launch floors: their roofline fraction measures launch
+latency, not the kernel.)
+
+`roofline` (headline) and every `sweep` row price the kernel's EFFECTIVE work -- 2*M*N*K table operations (one
+lookup and one add per product) and the algorithmic bytes -- against the ceiling that binds the shape:
+t_roof = max(bytes / 8 TB/s, 2MNK / 5 POPS), frac = t_roof / t_kernel.  The int8 multiply-accumulates the matrix
+cores actually perform (4 per product when selecting with one-hot operands, 2 on the sparse instruction) are
+reported apart as `mfma_pipe_frac`: pipe utilisation, not a roofline fraction.
 """
 from __future__ import annotations
 
@@ -34,17 +43,23 @@ INT8_MFMA_PEAK_TOPS = 5000.0
 VALU_LANE_INSTR_PER_S = 256 * 4 * 16 * 2.4e9
 PERM_ALU_PEAK_TOPS = VALU_LANE_INSTR_PER_S * (4 / 1.5) * 2 / 1e12
 
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch),
-# each scaled by what the same counter reads for a 1 GiB elementwise copy (FETCH_SIZE reads 0.5 of the true
-# bytes -> x2.0; WRITE_SIZE reads them exactly -> x1.0).  Summaries with the commands are under profiles/.
-# Keyed by (workload, kernel name); a kernel or workload that was not profiled reports null.
-MEASURED_TRAFFIC_KIB = {
-    ("resnet18_conv3x3_b1", "onehot_mfma_splitk_s9"): (107.6 * 2.0, 784.0),
-    ("resnet18_conv3x3_b1", "codes_onehot_mfma_splitk_s9"): (207.2 * 2.0, 784.0),
-    ("vgg16_conv3x3_b16", "onehot_mfma_64x128"): (2375.5 * 2.0, 50176.0),
-    ("vgg16_conv3x3_b16", "onehot_smfmac_64x128"): (2327.5 * 2.0, 50176.0),
-    ("gemm_8192x1x8192_i16", "smalln"): (8251.9 * 2.0, 32.0),
-}
+# HBM bytes per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each scaled by what the same
+# counter reads for a plain copy of known size.  The figures and the commands that produced them live in
+# profiles/hbm_traffic_counters.txt; its lines "traffic <workload> <kernel> <fetch KiB> <write KiB>" (already scaled)
+# are read here.  A (workload, kernel) pair that was not profiled reports null.
+def load_measured_traffic():
+    table = {}
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
+    if os.path.exists(path):
+        with open(path) as f:
+            for line in f:
+                t = line.split()
+                if len(t) == 5 and t[0] == "traffic":
+                    table[(t[1], t[2])] = (float(t[3]), float(t[4]))
+    return table
+
+
+MEASURED_TRAFFIC_KIB = load_measured_traffic()
 
 
 def measured_traffic(w, name):
@@ -216,11 +231,11 @@ def single_launch_us(torch, fn):
 def mfma_ops_factor(name):
     """int8 multiply-accumulates the matrix cores perform per effective operation: the one-hot kernel contracts over 4K
     (one operand byte per table column); on the sparse instruction, which skips the half of them that its index says
-    are zero, over 2K (so it too is priced against the DENSE peak); the decode-and-multiply comparison kernel over K;
+    are zero, over 2K (priced against the DENSE peak all the same); the decode-and-multiply comparison kernel over K;
     table kernels on the VALU issue none."""
     if name.startswith("onehot_mfma") or name.startswith("codes_onehot_mfma"):
         return 4
-    if name.startswith("onehot_smfmac"):
+    if name.startswith("onehot_smfmac") or name.startswith("smfmac_"):
         return 2
     if name.startswith("mfma_i8"):
         return 1
@@ -235,47 +250,38 @@ def algorithmic_bytes(w, name):
     return w.algorithmic_bytes + extra
 
 
-def kernel_report(w, ms, name):
-    """Achieved rates of one kernel launch of duration `ms` against the three ceilings."""
-    gops = w.ops / (ms * 1e-3) / 1e9
-    gbs = algorithmic_bytes(w, name) / (ms * 1e-3) / 1e9
-    f = mfma_ops_factor(name)
-    return {
-        "kernel": name, "us": round(ms * 1e3, 3), "gops": round(gops, 1), "algorithmic_GBps": round(gbs, 1),
-        # the three ceilings side by side, all in effective operations (2MNK) or algorithmic bytes
-        "frac_hbm": round(gbs / HBM_PEAK_GBS, 4),
-        "frac_int8_mfma_peak_effective": round(gops / 1e3 / INT8_MFMA_PEAK_TOPS, 4),
-        "frac_valu_lookup_ceiling": round(gops / 1e3 / PERM_ALU_PEAK_TOPS, 4),
-        # matrix-core kernels: int8 MFMA operations actually issued (4 per effective operation for one-hot selection)
-        "frac_int8_mfma_peak": None if f is None else round(f * gops / 1e3 / INT8_MFMA_PEAK_TOPS, 4),
-    }
-
-
 def roofline_object(w, ms, name):
-    """The roofline entry of the dominant kernel.  Matrix-core kernels: int8 MFMA operations issued (4 per effective
-    operation for the one-hot table kernel) against the dense int8 peak.  VALU table kernels: HBM when the HBM time
-    of the algorithmic bytes exceeds the ALU time of the products at the permute kernel's issue ceiling, else ALU."""
+    """Effective work of one launch of duration `ms` against the binding ceiling of the shape: the HBM time of the
+    algorithmic bytes or the int8 matrix-core time of 2MNK operations, whichever is longer."""
     alg = algorithmic_bytes(w, name)
+    t = ms * 1e-3
     t_hbm = alg / (HBM_PEAK_GBS * 1e9)
-    t_alu = w.ops / (PERM_ALU_PEAK_TOPS * 1e12)
+    t_mfma = w.ops / (INT8_MFMA_PEAK_TOPS * 1e12)
     f = mfma_ops_factor(name)
-    if f is not None:
-        ach = f * w.ops / (ms * 1e-3) / 1e12
-        return {"bound": "mfma", "achieved": round(ach, 3), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TFLOP/s",
-                "frac": round(ach / INT8_MFMA_PEAK_TOPS, 5), "traffic": measured_traffic(w, name), "kernel": name,
-                "algorithmic_bytes": alg, "effective_tops": round(w.ops / (ms * 1e-3) / 1e12, 3),
-                "note": f"int8 MFMA operations performed = {f} x 2MNK (one-hot selection contracts over 4K, the sparse "
-                        "instruction performs half of them); integer TOP/s against the dense int8 peak"}
-    if t_hbm >= t_alu:
-        ach = alg / (ms * 1e-3) / 1e9
+    common = {"traffic": measured_traffic(w, name), "kernel": name, "us": round(ms * 1e3, 3),
+              "algorithmic_bytes": alg, "ops_2mnk": w.ops,
+              "hbm_frac": round(t_hbm / t, 5), "int8_mfma_frac_effective": round(t_mfma / t, 5),
+              "valu_lookup_frac": round(w.ops / (PERM_ALU_PEAK_TOPS * 1e12) / t, 5),
+              # int8 multiply-accumulates performed on the matrix cores (pipe utilisation, not a roofline fraction)
+              "mfma_pipe_frac": None if f is None else round(f * t_mfma / t, 5)}
+    if t_hbm >= t_mfma:
+        ach = alg / t / 1e9
         return {"bound": "hbm", "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBS, 5), "traffic": measured_traffic(w, name), "kernel": name,
-                "algorithmic_bytes": alg}
-    ach = w.ops / (ms * 1e-3) / 1e12
-    return {"bound": "alu", "achieved": round(ach, 3), "peak": round(PERM_ALU_PEAK_TOPS, 1), "unit": "TFLOP/s",
-            "frac": round(ach / PERM_ALU_PEAK_TOPS, 5), "traffic": measured_traffic(w, name), "kernel": name,
-            "algorithmic_bytes": alg,
-            "note": "integer table lookups+adds counted as 2 ops per product; peak = VALU issue ceiling of the permute loop"}
+                "frac": round(ach / HBM_PEAK_GBS, 5), **common}
+    ach = w.ops / t / 1e12
+    return {"bound": "mfma", "achieved": round(ach, 3), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+            "frac": round(ach / INT8_MFMA_PEAK_TOPS, 5), **common,
+            "note": "effective table operations (2MNK) against the dense int8 peak; selecting with one-hot operands "
+                    "performs 4 (dense instruction) or 2 (sparse instruction) multiply-accumulates per product, so "
+                    "0.25 / 0.5 is the most a table kernel can reach on this ceiling"}
+
+
+def kernel_report(w, ms, name):
+    """One sweep row: the launch's effective rates and its fraction of each ceiling."""
+    r = roofline_object(w, ms, name)
+    r["gops"] = round(w.ops / (ms * 1e-3) / 1e9, 1)
+    r["algorithmic_GBps"] = round(algorithmic_bytes(w, name) / (ms * 1e-3) / 1e9, 1)
+    return r
 
 
 def launch_floor_us(torch, w, name, use_graph):
@@ -342,7 +348,7 @@ def wide_code_kernels(torch, w, use_graph):
     """Tables beyond the 16 int8 entries of the headline path, on the shape of workload `w` (a convolution): 2-bit codes
     with int16 entries (two int8 planes), and the 3- and 4-bit tables of Sec. 3.3 / Table 2; each on the one-hot
     matrix-core kernel AUTO picks (two planes and 4-bit codes: a sparse-instruction form, so also the dense one) and on
-    the plain LDS kernel.  The MFMA fraction counts the multiply-accumulates performed."""
+    the plain LDS kernel.  `mfma_pipe_frac` counts the multiply-accumulates performed, `int8_mfma_frac_effective` 2MNK."""
     from paper_2304_09049_amd import binding as dg
     dev = torch.device("cuda:0")
     report = []
@@ -376,7 +382,8 @@ def wide_code_kernels(torch, w, use_graph):
                 factor = 4 if bits == 2 else nlev // 2
             report.append({"bits": bits, "workload_shape": w.name, "variant": variant, "kernel": name,
                            "us": round(ms * 1e3, 3), "gops": round(tops * 1e3, 1),
-                           "frac_int8_mfma_peak": None if factor is None else round(factor * tops / INT8_MFMA_PEAK_TOPS, 4)})
+                           "int8_mfma_frac_effective": round(tops / INT8_MFMA_PEAK_TOPS, 4),
+                           "mfma_pipe_frac": None if factor is None else round(factor * tops / INT8_MFMA_PEAK_TOPS, 4)})
     return report
 
 
@@ -476,7 +483,8 @@ def main():
         "ms_per_step": round(ms_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32",
-        "dtype_note": "int32 accumulation of int8 table entries selected by 2-bit codes; one fp32 multiply per output in the scale epilogue",
+        "dtype_note": "int32 accumulation of int8 table entries selected by 2-bit codes" +
+                      ("; one fp32 multiply per output in the scale epilogue" if w.scale else ""),
         "data": "synthetic",
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "variant": args.variant, "kernel": dom_name,
                    "step": ("dg_conv2d_lut_codes" if w.kind == "conv" else "dg_gemm_lut_codes") +
@@ -491,6 +499,15 @@ def main():
         "empty_launch_same_grid_us": launch_floor_us(torch, w, dom_name, use_graph),
         "paper_context": "up to 1.74x over QNNPACK INT8 on an Intel i7-9700K (speedup ratios only; no absolute figure)",
     }
+    if w.act_dist != "uniform":
+        # Sec. 5.3: a table kernel's latency does not depend on the codes -- the same shape with uniform codes
+        import dataclasses
+        ru = Runner(dataclasses.replace(w, act_dist="uniform", name=w.name + "_uniform_codes"), args.variant)
+        ms_uniform = time_calls(torch, ru.kernel, args.steps, use_graph)
+        line["code_distribution_check"] = {"codes_as_specified": w.act_dist, "kernel_us": round(ms_kernel * 1e3, 3),
+                                           "kernel_us_uniform_codes": round(ms_uniform * 1e3, 3),
+                                           "ratio": round(ms_uniform / ms_kernel, 4)}
+        del ru
 
     if not args.no_sweep:
         sweep = []

@@ -66,9 +66,16 @@ void dgo_unpack_codes(const uint8_t *packed, int64_t count, int bits, uint8_t *c
             codes[per * j + i] = (uint8_t)((packed[j] >> (sb * i)) & mask);
 }
 
+/* The code in slot `slot` of a packed byte (slots are `sb` bits apart, a code is `bits` bits wide). */
+static unsigned code_in_slot(uint8_t packed, int slot, int sb, int bits)
+{
+    return (unsigned)(packed >> (slot * sb)) & ((1u << bits) - 1u);
+}
+
 /*
- * GEMM by table lookup on packed operands.  Wp is [M][K/4], Ap is [N][K/4],
- * C is [M][N].  The inner loop is Algorithm 1 on one byte at a time.
+ * GEMM by table lookup on packed operands (Algorithm 1 over all rows).  Wp is [M][K/per], Ap is [N][K/per],
+ * C is [M][N].  A dot product walks the two rows byte by byte; in every slot of a byte pair the weight code and
+ * the activation code side by side (weight code in the high bits) address the table, and the entries are added.
  */
 int dgo_lut_gemm_packed(const uint8_t *Wp, const uint8_t *Ap,
                         const int32_t *table, int bits,
@@ -77,21 +84,16 @@ int dgo_lut_gemm_packed(const uint8_t *Wp, const uint8_t *Ap,
     if (bits < 2 || bits > 4) return 3;
     const int sb = slot_bits(bits), per = 8 / sb;
     if (M < 0 || N < 0 || K < 0 || K % per != 0) return 3;
-    const int64_t KB = K / per;
-    const uint8_t mask = (uint8_t)((1 << bits) - 1);
+    const int64_t row_bytes = K / per;
     for (int64_t m = 0; m < M; ++m)
         for (int64_t n = 0; n < N; ++n) {
+            const uint8_t *wrow = Wp + m * row_bytes, *arow = Ap + n * row_bytes;
             int64_t sum = 0;
-            for (int64_t j = 0; j < KB; ++j) {
-                const uint8_t vec_w = Wp[m * KB + j];
-                const uint8_t vec_a = Ap[n * KB + j];
-                for (int i = 0; i < per; ++i) {
-                    const int shift = i * sb;
-                    const int indx = (((vec_w >> shift) & mask) << bits) |
-                                     ((vec_a >> shift) & mask);
-                    sum += table[indx];
+            for (int64_t j = 0; j < row_bytes; ++j)
+                for (int slot = 0; slot < per; ++slot) {
+                    const unsigned w = code_in_slot(wrow[j], slot, sb, bits), a = code_in_slot(arow[j], slot, sb, bits);
+                    sum += table[(w << bits) | a];
                 }
-            }
             if (sum > INT32_MAX || sum < INT32_MIN) return 2;
             C[m * N + n] = (int32_t)sum;
         }

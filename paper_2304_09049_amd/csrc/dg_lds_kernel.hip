@@ -23,16 +23,17 @@ __device__ __forceinline__ int32_t lookup_run(const int32_t *lut, const uint8_t 
     constexpr int SLOT = BITS == 2 ? 2 : 4;                  // bits per code slot
     constexpr uint32_t MASK = (1u << BITS) - 1u;
     constexpr int WB = sizeof(WordT);
+    constexpr int SLOTS = 8 * WB / SLOT;                     // codes per loaded word
+    const WordT *wwords = (const WordT *)w, *xwords = (const WordT *)x;
     int32_t acc = 0;
-    const WordT *w4 = (const WordT *)w;
-    const WordT *x4 = (const WordT *)x;
     for (int j = 0; j < bytes / WB; ++j) {
-        const uint32_t vw = w4[j], va = x4[j];
+        // walk the two words from the low slot up: the low fields of the shifted words are the current code pair
+        uint32_t wrest = wwords[j], xrest = xwords[j];
 #pragma unroll
-        for (int i = 0; i < 8 * WB / SLOT; ++i) {
-            const int shift = SLOT * i;
-            const uint32_t indx = (((vw >> shift) & MASK) << BITS) | ((va >> shift) & MASK);
-            acc += lut[indx];
+        for (int slot = 0; slot < SLOTS; ++slot) {
+            acc += lut[((wrest & MASK) << BITS) | (xrest & MASK)];     // table address: weight code, then activation code
+            wrest >>= SLOT;
+            xrest >>= SLOT;
         }
     }
     return acc;

@@ -488,6 +488,50 @@ def test_f32_sum_is_sequential_in_k():
         assert got[m, n] == np.add.accumulate(terms, dtype=np.float32)[-1]
 
 
+def test_f32_conv_sum_order_is_kh_then_kw_then_ci():
+    """Order-sensitive pin of the binary32 convolution (the reading: ascending kh, then kw, then ci, taps outside the
+    image skipped, from +0).  Entries depend on the weight code only: 1e8, -1e8, 1, 0.5 (activation levels all 1), and
+    1e8 absorbs any 1 or 0.5 added to it in binary32.  Filter, Cin = 2 (code of channel 0 | channel 1 per tap):
+        kh=0:  big|0.5   1|0.5   1|0.5
+        kh=1: -big|0.5   1|0.5   1|0.5
+        kh=2:    1|0.5   1|0.5   1|0.5
+    Centre pixel of a 3x3 input with pad 1 (all 9 taps), in the order kh, kw, ci:
+        row 0: 1e8, then five absorbed terms -> 1e8;  row 1: -1e8 -> 0, then 0.5 + 1 + 0.5 + 1 + 0.5 = 3.5;
+        row 2: + 4.5 = 8.0.
+    Other orders give other values: kw before kh 11.0, ci outermost 9.5, any axis descending differs too.
+    Corner pixel (0, 0): taps (1,1), (1,2), (2,1), (2,2) only = 4 * 1.5 = 6.0 (the big entries are outside)."""
+    table = oracle.build_lut_f32(np.array([1.0e8, -1.0e8, 1.0, 0.5], np.float32), np.ones(4, np.float32))
+    BIG, NEG, ONE, HALF = 0, 1, 2, 3
+    Wc = np.full((1, 3, 3, 2), ONE, np.uint8)
+    Wc[0, :, :, 1] = HALF
+    Wc[0, 0, 0, 0], Wc[0, 1, 0, 0] = BIG, NEG
+    Xc = np.zeros((1, 3, 3, 2), np.uint8)
+    y = oracle.conv2d_table_f32(Wc, Xc, table, pad=(1, 1))
+    assert y.shape == (1, 3, 3, 1)
+    assert y[0, 1, 1, 0] == 8.0
+    assert y[0, 0, 0, 0] == 6.0
+    # bottom-right corner (2, 2): taps (0,0), (0,1), (1,0), (1,1): 1e8 (+0.5, +1, +0.5 absorbed) - 1e8 = 0, + 0.5 + 1 + 0.5 = 2.0
+    assert y[0, 2, 2, 0] == 2.0
+
+
+def test_f32_conv_equals_f32_gemm_on_explicit_im2col():
+    """With no padding every tap is inside the image, so the convolution is the GEMM on rows gathered in the order
+    k = (kh * KW + kw) * Cin + ci -- and the GEMM's sequential order is pinned by test_f32_sum_is_sequential_in_k."""
+    rng = np.random.default_rng(31)
+    table = rng.normal(0.0, 1.0, 16).astype(np.float32)
+    c = wl.small_conv(2, 6, 7, 4, 5, 3, 2, (2, 1), (0, 0), seed=32)
+    B, H, W, Cin = c.Ac.shape
+    Cout, KH, KW, _ = c.Wc.shape
+    sh, sw = 2, 1
+    OH, OW = (H - KH) // sh + 1, (W - KW) // sw + 1
+    rows = np.empty((B * OH * OW, KH * KW * Cin), np.uint8)
+    for b, oh, ow in itertools.product(range(B), range(OH), range(OW)):
+        rows[(b * OH + oh) * OW + ow] = c.Ac[b, oh * sh:oh * sh + KH, ow * sw:ow * sw + KW, :].reshape(-1)
+    want = oracle.gemm_table_f32(c.Wc.reshape(Cout, -1), rows, table)             # [Cout][N]
+    got = oracle.conv2d_table_f32(c.Wc, c.Ac, table, stride=(sh, sw))
+    assert np.array_equal(got.reshape(B * OH * OW, Cout), want.T)
+
+
 def test_f32_table_with_integer_levels_equals_integer_oracle():
     lw, la = LEVEL_SETS[0]
     c = wl.small_conv(1, 6, 6, 8, 4, 3, 3, pad=(1, 1), seed=27)
