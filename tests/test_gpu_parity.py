@@ -75,16 +75,17 @@ def test_gemm_parity(shape, variant):
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("shape", [(64, 196, 576), (37, 41, 4096), (130, 70, 64)], ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("levels", sorted(LEVELS))
-def test_gemm_parity_level_tables(levels, variant):
+def test_gemm_parity_level_tables(levels, shape, variant):
     lw, la, entry = LEVELS[levels]
-    for (M, N, K) in [(64, 196, 576), (37, 41, 4096), (130, 70, 64)]:
-        inp = wl.small_gemm(M, N, K, seed=11 + K)
-        case = GpuCase(inp, levels=(lw, la), entry=entry)
-        got = run_or_unsupported(case, variant)
-        if got is None:
-            pytest.skip(f"{variant} declares {levels} unsupported")
-        _assert_same(got, oracle.gemm(inp.Wc, inp.Ac, lw, la), f"gemm {levels} {(M, N, K)} {variant}")
+    M, N, K = shape
+    inp = wl.small_gemm(M, N, K, seed=11 + K)
+    case = GpuCase(inp, levels=(lw, la), entry=entry)
+    got = run_or_unsupported(case, variant)
+    if got is None:
+        pytest.skip(f"{variant} declares {levels} {shape} unsupported")
+    _assert_same(got, oracle.gemm(inp.Wc, inp.Ac, lw, la), f"gemm {levels} {shape} {variant}")
 
 
 CONV_CASES = [
@@ -108,18 +109,18 @@ CONV_CASES = [
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("levels", ["signed_unsigned", "nonuniform_i8"])      # the second has no zero activation level
 @pytest.mark.parametrize("case_", CONV_CASES, ids=lambda c: "-".join(map(str, c[:7])))
-def test_conv_parity(case_, variant):
+def test_conv_parity(case_, levels, variant):
     B, H, W, Cin, Cout, KH, KW, stride, pad = case_
-    for levels in ("signed_unsigned", "nonuniform_i8"):     # the second has no zero activation level
-        lw, la, entry = LEVELS[levels]
-        inp = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H * W + Cin + Cout)
-        case = GpuCase(inp, levels=(lw, la), entry=entry)
-        got = run_or_unsupported(case, variant)
-        if got is None:
-            pytest.skip(f"{variant} declares {case_} unsupported")
-        want = oracle.conv2d(inp.Wc, inp.Ac, lw, la, stride=stride, pad=pad)
-        _assert_same(got, want, f"conv {case_} {levels} {variant}")
+    lw, la, entry = LEVELS[levels]
+    inp = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H * W + Cin + Cout)
+    case = GpuCase(inp, levels=(lw, la), entry=entry)
+    got = run_or_unsupported(case, variant)
+    if got is None:
+        pytest.skip(f"{variant} declares {case_} {levels} unsupported")
+    want = oracle.conv2d(inp.Wc, inp.Ac, lw, la, stride=stride, pad=pad)
+    _assert_same(got, want, f"conv {case_} {levels} {variant}")
 
 
 ONEHOT_PLANS = {"split": "onehot_mfma_splitk_s", "1": "onehot_mfma_64x32", "2": "onehot_mfma_64x64",
