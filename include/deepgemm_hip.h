@@ -29,6 +29,8 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+/* the library is built with hidden visibility: only what this header declares is exported */
+#pragma GCC visibility push(default)
 
 typedef enum {
     DG_OK = 0,
@@ -64,8 +66,8 @@ dg_status dg_build_lut(const int8_t levels_w[4], const int8_t levels_a[4], dg_lu
 /*
  * The same table for b-bit codes, b = 2, 3 or 4 (Sec. 3.3 and Table 2: index b + b bits, 2^(2b) = 16 / 64 / 256
  * entries; the paper describes this scaling without implementing it).  levels_w / levels_a hold 2^b levels each;
- * entry index = (w << b) | a.  Tables with b > 2 run on the LDS kernel only.  bits outside 2..4 ->
- * DG_ERR_UNSUPPORTED.  dg_build_lut is the b = 2 case.
+ * entry index = (w << b) | a.  Tables with b > 2 run on the one-hot matrix-core kernels (int8 entries, Cin % 16 == 0)
+ * or on the LDS kernel.  bits outside 2..4 -> DG_ERR_UNSUPPORTED.  dg_build_lut is the b = 2 case.
  */
 dg_status dg_build_lut_bits(int32_t bits, const int8_t *levels_w, const int8_t *levels_a,
                             dg_lut_dtype entry, dg_lut **out);
@@ -175,11 +177,15 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *            axis is the channel axis (NHWC), or plain GEMMs without scale (run transposed)
  * A variant that cannot run the given shape or table returns DG_ERR_UNSUPPORTED.
  *
- * Test and measurement overrides, read from the environment at every call (leave them unset otherwise; the
- * results are the same under any of them, only the kernel shape changes):
+ * Test and measurement overrides.  They are honoured only when the environment variable DG_TEST_OVERRIDES is "1" at
+ * the library's first call (that one is read once); otherwise none of them is looked at.  The results are the same
+ * under any of them, only the kernel shape changes:
  *   DG_ONEHOT_PLAN   forces the one-hot kernels' shape: "split" (split-K kernel), "<wn>" (tile 32*wn columns wide,
  *                    wn = 1, 2, 4, 7) or "<wn>k<s>" (s = 2, 4 wavefronts sharing a tile); "44" is the comparison
- *                    kernel's 128 x 128 tile.  While it is set AUTO does not move to the sparse-instruction forms.
+ *                    kernel's 128 x 128 tile; "ws" the sparse-instruction kernel with stationary weight operands
+ *                    (K = 64, 128, 256 without a filter window) whatever the size.  While it is set AUTO does not
+ *                    move to the sparse-instruction forms on its own.
+ *   DG_WS_WAVES      target number of wavefronts of that kernel (default: one per SIMD)
  *   DG_ONEHOT_WAVES  target number of wavefronts of the split-K kernel (default 2048)
  *   DG_PERM_PLAN     index of the permute kernel's tile shape
  */
@@ -310,6 +316,7 @@ const char *dg_gemm_kernel_name(const dg_lut *lut, int64_t M, int64_t N, int64_t
                                 dg_kernel variant);
 const char *dg_conv_kernel_name(const dg_lut *lut, const dg_conv_desc *desc, dg_kernel variant);
 
+#pragma GCC visibility pop
 #ifdef __cplusplus
 }
 #endif

@@ -18,6 +18,8 @@ LIB = os.path.join(HERE, "libdeepgemm_hip.so")
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
+    # only the functions include/deepgemm_hip.h declares are exported
+    "-fvisibility=hidden",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     # the binary32 decisions (Eq. 1: multiply, then add; binary32 tables: add by add) are defined operation by

@@ -2,6 +2,7 @@
 // Every entry point validates on the host before launching anything and never synchronises.
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -32,6 +33,27 @@ dg_status dg_fail(dg_status s, const char *fmt, ...)
     vsnprintf(g_error, sizeof(g_error), fmt, ap);
     va_end(ap);
     return s;
+}
+
+const char *dg_override(const char *name)
+{
+    static const bool enabled = [] {
+        const char *e = getenv("DG_TEST_OVERRIDES");
+        return e != nullptr && e[0] == '1' && e[1] == 0;
+    }();
+    return enabled ? getenv(name) : nullptr;
+}
+
+int dg_simd_count()
+{
+    static const int simds = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;                                      // (no device to ask: the MI355X figure)
+        return 4 * cus;
+    }();
+    return simds;
 }
 
 dg_status dg_check_launch(const char *what)
@@ -272,7 +294,7 @@ int64_t dg_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad)
 
 namespace {
 
-enum class Pick { Perm, Lds, LdsF32, Mfma, SmallN, Lut65k, OneHot, Sparse, Sparse4, Sparse2p, Unsupported };
+enum class Pick { Perm, Lds, LdsF32, Mfma, SmallN, Lut65k, OneHot, Sparse, Sparse4, Sparse2p, SparseWs, Unsupported };
 
 Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
 {
@@ -297,6 +319,7 @@ Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case DG_KERNEL_LUT65K: return dg_lut65k_supports(lut, p) ? Pick::Lut65k : Pick::Unsupported;
     case DG_KERNEL_ONEHOT_MFMA: return dg_onehot_supports(lut, p) ? Pick::OneHot : Pick::Unsupported;
     case DG_KERNEL_ONEHOT_SMFMAC:
+        if (dg_sparse_ws_preferred(lut, p)) return Pick::SparseWs;
         if (dg_sparse2p_supports(lut, p)) return Pick::Sparse2p;
         return dg_sparse_supports(lut, p) ? Pick::Sparse : Pick::Unsupported;
     case DG_KERNEL_AUTO:
@@ -307,6 +330,8 @@ Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
         // size measured (1.5x on a 0.2 GOP layer, 5x - 10x from 3 GOP upwards)
         // (large layers: the same selection on the sparse instruction, about half the matrix work)
         if (dg_sparse2p_preferred(lut, p)) return Pick::Sparse2p;
+        // short reductions with many output blocks: the dense operand of the weights is built once per wavefront
+        if (dg_sparse_ws_preferred(lut, p)) return Pick::SparseWs;
         if (dg_onehot_supports(lut, p)) return dg_sparse_preferred(lut, p) ? Pick::Sparse : Pick::OneHot;
         if (p.N <= 32 && p.K >= 1024 && dg_smalln_supports(lut, p)) return Pick::SmallN;
         if (dg_perm_supports(lut, p)) return Pick::Perm;
@@ -328,6 +353,7 @@ dg_status run(const dg_lut *lut, const DgProblem &p, dg_kernel variant, hipStrea
     case Pick::Sparse: return dg_launch_sparse(lut, p, stream);
     case Pick::Sparse4: return dg_launch_sparse4(lut, p, stream);
     case Pick::Sparse2p: return dg_launch_sparse2p(lut, p, stream);
+    case Pick::SparseWs: return dg_launch_sparse_ws(lut, p, stream);
     case Pick::Unsupported: break;
     }
     return dg_fail(DG_ERR_UNSUPPORTED,
@@ -348,6 +374,7 @@ const char *pick_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case Pick::Sparse: return dg_sparse_config_name(lut, p);
     case Pick::Sparse4: return "onehot_smfmac4_64x128";
     case Pick::Sparse2p: return "onehot_smfmac_2p_32x128";
+    case Pick::SparseWs: return "onehot_smfmac_ws_32xK";
     case Pick::Unsupported: break;
     }
     return "unsupported";
@@ -378,6 +405,8 @@ dg_status fill_gemm(const char *name, const dg_lut *lut, int64_t M, int64_t N, i
     p->K = (int32_t)K;
     p->H = p->W = p->KH = p->KW = p->sh = p->sw = p->OH = p->OW = 1;
     p->Cin = (int32_t)K;
+    p->stride_cm = N;             // row-major [M][N] unless the caller says otherwise
+    p->stride_cn = 1;
     return check_range(name, lut, K);
 }
 
@@ -413,6 +442,8 @@ dg_status fill_conv(const char *name, const dg_lut *lut, const dg_conv_desc *d, 
     p->pw = d->pad_w;
     p->OH = (int32_t)OH;
     p->OW = (int32_t)OW;
+    p->stride_cm = 1;             // NHWC: channel fastest
+    p->stride_cn = p->M;
     return check_range(name, lut, K);
 }
 
@@ -629,6 +660,8 @@ dg_status dg_conv2d_lut_requant(const dg_lut *lut, const void *Wp_dev, const voi
     p.q_zero = q_zero;
     p.q_lo = lo;
     // the re-quantising epilogue lives in the one-hot matrix-core kernels (both instruction forms share it)
+    if ((variant == DG_KERNEL_ONEHOT_SMFMAC || variant == DG_KERNEL_AUTO) && dg_sparse_ws_preferred(lut, p))
+        return dg_launch_sparse_ws(lut, p, (hipStream_t)hip_stream);
     if (variant == DG_KERNEL_ONEHOT_SMFMAC && lut->bits == 2 && dg_sparse_supports(lut, p))
         return dg_launch_sparse(lut, p, (hipStream_t)hip_stream);
     if (variant == DG_KERNEL_ONEHOT_SMFMAC && dg_sparse2p_supports(lut, p))

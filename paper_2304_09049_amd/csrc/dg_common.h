@@ -45,6 +45,34 @@ struct DgProblem {
     int32_t q_lo;
 };
 
+// n / d for 0 <= n < 2^31 by multiply-high and shift, d fixed per launch and prepared on the host:
+// n / d == umulhi(n, mul) >> shift for d >= 2 with L = ceil(log2 d), mul = ceil(2^(31+L) / d) < 2^32 and shift = L - 1
+// (the error mul * d - 2^(31+L) is below d <= 2^L = 2^((31+L) - 31)); d = 1 is passed through.
+struct DgFastDiv {
+    uint32_t mul, shift, d;
+};
+
+__device__ __forceinline__ uint32_t dg_fdiv(uint32_t n, const DgFastDiv &f)
+{
+    return f.d == 1 ? n : __umulhi(n, f.mul) >> f.shift;
+}
+
+inline DgFastDiv dg_make_div(uint32_t d)
+{
+    DgFastDiv f = {0u, 0u, d};
+    if (d < 2) return f;
+    uint32_t L = 0;
+    while ((1ull << L) < d) ++L;
+    f.mul = (uint32_t)(((1ull << (31 + L)) + d - 1) / d);
+    f.shift = L - 1;
+    return f;
+}
+
+// Value of a test / measurement override (an environment variable), or nullptr.  Overrides are looked at only when
+// DG_TEST_OVERRIDES=1 was set when the library was first called; otherwise this returns nullptr without reading anything.
+const char *dg_override(const char *name);
+// Number of SIMD units of the current device (compute units x 4), asked from the runtime once.
+int dg_simd_count();
 // Record the calling thread's error detail and return `s`.
 dg_status dg_fail(dg_status s, const char *fmt, ...);
 // Turn the launch status of the last kernel into a dg_status.
@@ -85,6 +113,9 @@ dg_status dg_launch_sparse4(const dg_lut *lut, const DgProblem &p, hipStream_t s
 bool dg_sparse2p_supports(const dg_lut *lut, const DgProblem &p);     // two-plane 2-bit tables on the sparse instruction
 bool dg_sparse2p_preferred(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_sparse2p(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+bool dg_sparse_ws_supports(const dg_lut *lut, const DgProblem &p);    // short K: weight operands stationary in registers
+bool dg_sparse_ws_preferred(const dg_lut *lut, const DgProblem &p);
+dg_status dg_launch_sparse_ws(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 bool dg_smalln_supports(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_smalln(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 dg_status dg_launch_smalln_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream);   // p.Xp: codes one per byte

@@ -78,20 +78,46 @@ __device__ __forceinline__ void dg_mfma_store_block(const DgProblem &p, const dg
         return;
     }
     const int r = lane & 31, h = lane >> 5;
-    const int col = (TR ? mb : nb) + r;
-    if (col >= (TR ? p.M : p.N)) return;
-    // The lane's 16 elements sit in one MFMA column at MFMA rows row0 + 8*(e/4) + e%4: one base address, then steps
-    // of the row stride (no multiply per element); a block wholly inside the output needs no row checks.
-    const int row0 = (TR ? nb : mb) + 4 * h, row_limit = TR ? p.N : p.M;
+    // (mb and nb are the same in every lane of the wavefront: say so, and the block's base address is scalar arithmetic)
+    const int colb = __builtin_amdgcn_readfirstlane(TR ? mb : nb), rowb = __builtin_amdgcn_readfirstlane(TR ? nb : mb);
+    const int col_limit = TR ? p.M : p.N, row_limit = TR ? p.N : p.M;
     const int64_t row_stride = TR ? p.stride_cn : p.stride_cm, col_stride = TR ? p.stride_cm : p.stride_cn;
-    const int64_t base = (int64_t)col * col_stride + (int64_t)row0 * row_stride;
-    const bool inside = (TR ? nb : mb) + 32 <= row_limit;              // (uniform over the wavefront)
+    // A block wholly inside the output whose 32 x 32 footprint spans less than 2^30 elements (strides may be negative):
+    // one uniform base address, a 32-bit offset per lane, then steps of the row stride -- no bounds test and no 64-bit
+    // arithmetic per element.  The stores are streaming (non-temporal) stores: the output is written once and read by
+    // a later kernel, it has no business in this one's caches.
+    const int64_t span = 32 * ((row_stride < 0 ? -row_stride : row_stride) + (col_stride < 0 ? -col_stride : col_stride));
+    if (colb + 32 <= col_limit && rowb + 32 <= row_limit && span < ((int64_t)1 << 30)) {
+        const int64_t base = (int64_t)colb * col_stride + (int64_t)rowb * row_stride;
+        const int rs = (int)row_stride, off0 = r * (int)col_stride + 4 * h * rs;
+        if (p.scale) {
+            float *out = p.Cf + base;
+            const float *scale_rows = p.scale + rowb + 4 * h;          // (row-major GEMM output: the scale goes with the row)
 #pragma unroll
-    // (streaming stores: the output is written once and read by a later kernel, it has no business in this one's caches)
+            for (int e = 0; e < 16; ++e) {
+                const int k = 8 * (e / 4) + (e % 4);
+                __builtin_nontemporal_store((float)acc[e] * (TR ? sc : scale_rows[k]), out + (off0 + k * rs));
+            }
+        } else {
+            int32_t *out = p.C + base;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int k = 8 * (e / 4) + (e % 4);
+                __builtin_nontemporal_store(acc[e], out + (off0 + k * rs));
+            }
+        }
+        return;
+    }
+    // a block on the output's edge: every element tested
+    const int col = colb + r;
+    if (col >= col_limit) return;
+    const int row0 = rowb + 4 * h;
+    const int64_t first = (int64_t)col * col_stride + (int64_t)row0 * row_stride;
+#pragma unroll
     for (int e = 0; e < 16; ++e) {
         const int k = 8 * (e / 4) + (e % 4);
-        if (!inside && row0 + k >= row_limit) continue;
-        const int64_t o = base + k * row_stride;
+        if (row0 + k >= row_limit) continue;
+        const int64_t o = first + k * row_stride;
         if (p.scale)
             __builtin_nontemporal_store((float)acc[e] * (TR ? sc : p.scale[row0 + k]), p.Cf + o);
         else

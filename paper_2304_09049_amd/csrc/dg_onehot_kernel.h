@@ -58,27 +58,10 @@ struct Pools {
     uint32_t w[64];
 };
 
-// n / d for 0 <= n < 2^31 by multiply-high and shift (d fixed per launch, prepared on the host: with
-// L = ceil(log2 d), mul = ceil(2^(31+L) / d) and shift = L - 1; d = 1 is passed through)
-struct FastDiv {
-    uint32_t mul, shift, d;
-};
+typedef DgFastDiv FastDiv;
 
-__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f)
-{
-    return f.d == 1 ? n : __umulhi(n, f.mul) >> f.shift;
-}
-
-inline FastDiv make_div(uint32_t d)
-{
-    FastDiv f = {0u, 0u, d};
-    if (d < 2) return f;
-    uint32_t L = 0;
-    while ((1ull << L) < d) ++L;
-    f.mul = (uint32_t)(((1ull << (31 + L)) + d - 1) / d);
-    f.shift = L - 1;
-    return f;
-}
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) { return dg_fdiv(n, f); }
+inline FastDiv make_div(uint32_t d) { return dg_make_div(d); }
 
 struct Args {
     DgProblem p;
@@ -132,6 +115,22 @@ __device__ __forceinline__ Words<CH> load_words(const uint8_t *ptr)
         w.v[0] = *(const uint32_t *)ptr;
     }
     return w;
+}
+
+// CH up to 8: two 128-bit loads
+template <int CH>
+__device__ __forceinline__ Words<CH> load_words_any(const uint8_t *ptr)
+{
+    if constexpr (CH <= 4) {
+        return load_words<CH>(ptr);
+    } else {
+        static_assert(CH == 8, "1, 2, 4 or 8 words");
+        const Words<4> lo = load_words<4>(ptr), hi = load_words<4>(ptr + 16);
+        Words<CH> w;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w.v[i] = lo.v[i], w.v[4 + i] = hi.v[i];
+        return w;
+    }
 }
 
 // The same words from codes that are still one per byte (the run-time packing stage done in the load stage).
@@ -798,6 +797,7 @@ DGOH_UNIT_SPLIT(2, 0) DGOH_UNIT_SPLIT(2, 1) DGOH_UNIT_SPLIT(3, 0) DGOH_UNIT_SPLI
 DGOH_UNIT_SPLIT(4, 1) DGOH_UNIT_SPLIT(22, 0) DGOH_UNIT_SPLIT(22, 1) DGOH_UNIT_SPLIT(0, 0) DGOH_UNIT_SPLIT(0, 1) DGOH_UNIT_SPLIT(20, 1)
 void unit_sparse4(const DgProblem &, const uint32_t (&)[16][4], int, hipStream_t);      // dg_sparse4_kernel.h
 void unit_sparse2p(const DgProblem &, const uint32_t (&)[2][4], int, hipStream_t);      // dg_sparse2p_kernel.h
+void unit_sparse_ws(const DgProblem &, const uint32_t (&)[4], int, hipStream_t);        // dg_sparse_ws_kernel.h
 // the split-K kernel on activations still one code per byte (one- and two-plane tables, either output layout)
 void unit_split_codes(const DgProblem &, const Pools &, const Plan &, bool two, bool tr, int64_t, hipStream_t);
 #undef DGOH_UNIT

@@ -49,7 +49,7 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
     // the split-K kernel's shape: about 2048 wavefronts in all, at most 16 per workgroup, whole chunks each
     const int64_t blocks11 = tile_count(p, 1, 1);
     int64_t target = 2048;
-    if (const char *e = getenv("DG_ONEHOT_WAVES")) target = atoi(e) > 0 ? atoi(e) : target;   // tuning override
+    if (const char *e = dg_override("DG_ONEHOT_WAVES")) target = atoi(e) > 0 ? atoi(e) : target;   // tuning override
     int S = (int)((target + blocks11 - 1) / blocks11);
     S = S < 1 ? 1 : (S > 16 ? 16 : S);
     if (S > q.chunks) S = q.chunks;
@@ -64,6 +64,7 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
     // least-regret fit to timings of 78 layer shapes x 12 plans with 2-bit codes (the plan chosen is within 14 % of
     // the best measured one on each, 1.3 % on average); ties go to the wider, less shared plan.
     static const int widths[4] = {7, 4, 2, 1};
+    const int64_t simds = dg_simd_count();
     const bool can_share = lut->bits == 2 && !q.two;       // (the comparison takes 2-bit codes only)
     // (the wider codes and two-plane tables, with 2 to 4 times the MFMA work per load, keep the constants of an earlier
     // fit without sharing, under which their measured times are better: 32 cycles per MFMA, 33 and 42 for the two
@@ -80,7 +81,7 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
             if (skw > q.chunks || (wn == 7 && skw == 2)) continue;      // (two 64x224 tiles of sums exceed 64 KB of LDS)
             if (wn == 7 && mode == SPARSE) continue;                    // (14 blocks of sparse-instruction sums exceed the VGPRs)
             if (wn == 7 && decode && skw == 1) continue;                // (measured slower than 64x128 and 128x128 when decoding)
-            const int64_t per_simd = (tile_count(p, wm, wn) * skw + 1023) / 1024;
+            const int64_t per_simd = (tile_count(p, wm, wn) * skw + simds - 1) / simds;
             const double lone = !can_share ? 1.0 : (per_simd == 1 ? 0.84 : (per_simd == 2 ? 0.78 : 1.0));   // (rounding up overstates short queues)
             double cost = (double)per_simd * 2 * wn * (steps / skw) * mfma_cycles[i] * lone;
             if (decode) cost = (double)per_simd * (steps / skw) * decode_step_cycles(2, wn) * lone;
@@ -89,24 +90,24 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
             if (first || cost < best * 0.999) best = cost, q.wn = wn, q.skw = skw, first = false;
         }
     if (decode && p.M > 64) {                              // the comparison's own 128 x 128 tile
-        const int64_t per_simd = (tile_count(p, 4, 4) + 1023) / 1024;
+        const int64_t per_simd = (tile_count(p, 4, 4) + simds - 1) / simds;
         const double cost = (double)per_simd * steps * decode_step_cycles(4, 4) + 2670.0 + 350.0 * 16;
         if (cost < best * 0.999) best = cost, q.wm = 4, q.wn = 4, q.skw = 1;
     }
     if (can_share) {
-        const int64_t per_simd = (blocks11 * split_S + 1023) / 1024;
+        const int64_t per_simd = (blocks11 * split_S + simds - 1) / simds;
         const double cost = (double)per_simd * (steps * split_cpw / q.chunks) * (decode ? decode_step_cycles(1, 1) : 50.6) + 3370.0;
         q.split = q.chunks > 1 && cost < best;
     } else {
         // other code widths and two-plane tables (not in the fit): split K when there are too few 64 x 32 tiles to give
         // every SIMD a wavefront, or barely enough and a long K to walk
         const int64_t t21 = tile_count(p, wm, 1);
-        q.split = (t21 < 512 || (t21 < 1024 && q.chunks >= 32)) && q.chunks > 1;
+        q.split = (t21 < simds / 2 || (t21 < simds && q.chunks >= 32)) && q.chunks > 1;
     }
     if (tile > 0) q.split = false, q.wm = wm, q.wn = tile, q.skw = 1;
     // DG_ONEHOT_PLAN = split | <wn> | <wn>k<skw> (wn = 1, 2, 4, 7; skw = 1, 2, 4) | 44 (the comparison's 128 x 128 tile)
     // overrides the choice (tuning, and tests that must reach every plan)
-    if (const char *force = getenv("DG_ONEHOT_PLAN")) {
+    if (const char *force = dg_override("DG_ONEHOT_PLAN")) {
         const int v = atoi(force);
         if (force[0] == 's') q.split = true;
         else if (v == 44 && decode) q.split = false, q.wm = 4, q.wn = 4, q.skw = 1;
@@ -186,7 +187,7 @@ Plan sparse_plan(const dg_lut *lut, const DgProblem &t)
 
 bool dg_sparse_preferred(const dg_lut *lut, const DgProblem &p)
 {
-    if (!dg_sparse_supports(lut, p) || getenv("DG_ONEHOT_PLAN") != nullptr) return false;
+    if (!dg_sparse_supports(lut, p) || dg_override("DG_ONEHOT_PLAN") != nullptr) return false;
     const DgProblem t = sparse_problem(p);
     if (sparse_tile_hint(lut, t) > 0) return true;
     // Also where the dense-instruction planner shares tiles at least 64 columns wide and there are 384 of them or more:
@@ -250,6 +251,65 @@ dg_status dg_launch_sparse(const dg_lut *lut, const DgProblem &p0, hipStream_t s
     return dg_check_launch("onehot_mfma_kernel<20>");
 }
 
+// ---- weights stationary in registers on the sparse instruction (dg_sparse_ws_kernel.h): short reductions without filter window
+
+namespace {
+
+bool sparse_ws_takes(const dg_lut *lut, const DgProblem &p)
+{
+    if (lut->dtype == DG_LUT_F32 || lut->bits != 2 || !fits_int8(lut)) return false;
+    if (p.K != 64 && p.K != 128 && p.K != 256) return false;          // the whole dense operand of 32 rows stays in registers
+    // every "pixel" is one contiguous row of K codes: a GEMM, or a 1x1 convolution without stride or padding
+    if (p.KH != 1 || p.KW != 1 || p.sh != 1 || p.sw != 1 || p.ph != 0 || p.pw != 0) return false;
+    if (sparse_transposes(p) && !sparse_can_transpose(p)) return false;
+    const DgProblem t = sparse_problem(p);
+    if (t.stride_cm != 1) return false;                               // the 32 channels of a lane half are stored side by side
+    if ((uintptr_t)t.Wp % 16 != 0 || (uintptr_t)t.Xp % 16 != 0) return false;
+    return ((int64_t)(t.M + 31) / 32) * (((int64_t)t.N + 31) / 32) <= INT32_MAX;
+}
+
+// runs of pixel blocks: about one wavefront per SIMD in all (measured on seven 1x1 layers: as fast as two or faster, and
+// runs of up to 8 blocks are loaded whole before the first store), each with at least one block
+int sparse_ws_streams(const DgProblem &t)
+{
+    const int64_t row_blocks = (t.M + 31) / 32, pixel_blocks = ((int64_t)t.N + 31) / 32;
+    int64_t waves = (int64_t)dg_simd_count();
+    if (const char *e = dg_override("DG_WS_WAVES")) waves = atoi(e) > 0 ? atoi(e) : waves;
+    int64_t streams = waves / row_blocks;
+    if (streams < 1) streams = 1;
+    if (streams > pixel_blocks) streams = pixel_blocks;
+    return (int)streams;
+}
+
+}   // namespace
+
+bool dg_sparse_ws_supports(const dg_lut *lut, const DgProblem &p) { return sparse_ws_takes(lut, p); }
+
+// AUTO: layers with enough 32 x 32 blocks that every wavefront streams several (measured against the tiled kernels)
+bool dg_sparse_ws_preferred(const dg_lut *lut, const DgProblem &p)
+{
+    if (!sparse_ws_takes(lut, p)) return false;
+    if (const char *force = dg_override("DG_ONEHOT_PLAN")) return strcmp(force, "ws") == 0;     // (tests reach it on small shapes)
+    const DgProblem t = sparse_problem(p);
+    return ((int64_t)(t.M + 31) / 32) * (((int64_t)t.N + 31) / 32) >= (int64_t)dg_simd_count() / 2;
+}
+
+dg_status dg_launch_sparse_ws(const dg_lut *lut, const DgProblem &p0, hipStream_t stream)
+{
+    const bool transposed = sparse_transposes(p0);
+    const DgProblem p = sparse_problem(p0);
+    uint32_t rows[4];                                      // rows[w] = T[w][0..3] (the transposed problem swaps the codes)
+    for (int w = 0; w < 4; ++w) {
+        rows[w] = 0;
+        for (int v = 0; v < 4; ++v) {
+            const int T = transposed ? lut->entry[(v << 2) | w] : lut->entry[(w << 2) | v];
+            rows[w] |= (uint32_t)(uint8_t)(int8_t)T << (8 * v);
+        }
+    }
+    dgoh::unit_sparse_ws(p, rows, sparse_ws_streams(p), stream);
+    return dg_check_launch("smfmac_ws_kernel");
+}
+
 // ---- 4-bit codes on the sparse instruction (dg_sparse4_kernel.h): 64 x 128 tiles only, so large layers only
 
 namespace {
@@ -277,7 +337,7 @@ bool dg_sparse4_supports(const dg_lut *lut, const DgProblem &p) { return sparse4
 bool dg_sparse4_preferred(const dg_lut *lut, const DgProblem &p)
 {
     return sparse4_takes(lut, p) && tile_count(sparse_problem(p), 2, 4) >= 512 && p.K >= 256 &&
-           getenv("DG_ONEHOT_PLAN") == nullptr;
+           dg_override("DG_ONEHOT_PLAN") == nullptr;
 }
 
 dg_status dg_launch_sparse4(const dg_lut *lut, const DgProblem &p0, hipStream_t stream)
@@ -324,7 +384,7 @@ bool dg_sparse2p_supports(const dg_lut *lut, const DgProblem &p) { return sparse
 bool dg_sparse2p_preferred(const dg_lut *lut, const DgProblem &p)
 {
     return sparse2p_takes(lut, p) && tile_count(sparse_problem(p), 1, 4) >= 1024 && p.K >= 512 &&
-           getenv("DG_ONEHOT_PLAN") == nullptr;
+           dg_override("DG_ONEHOT_PLAN") == nullptr;
 }
 
 dg_status dg_launch_sparse2p(const dg_lut *lut, const DgProblem &p0, hipStream_t stream)

@@ -37,10 +37,7 @@
 
 namespace dgperm {
 
-// n / d for 0 <= n < 2^31 by multiply-high and shift (d fixed per launch, prepared on the host).
-struct FastDiv {
-    uint32_t mul, shift, d;
-};
+typedef DgFastDiv FastDiv;
 
 struct PermArgs {
     DgProblem p;
@@ -53,10 +50,7 @@ struct PermArgs {
     int32_t step_ci, step_kw, step_kh;
 };
 
-__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f)
-{
-    return f.d == 1 ? n : __umulhi(n, f.mul) >> f.shift;
-}
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) { return dg_fdiv(n, f); }
 
 __device__ __forceinline__ uint32_t perm(uint32_t hi, uint32_t lo, uint32_t sel)
 {

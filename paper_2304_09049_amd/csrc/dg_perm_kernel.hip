@@ -51,7 +51,7 @@ const PermPlan *plan_for(const dg_lut *lut, const DgProblem &p)
     const int mode = mode_for(lut);
     if (mode < 0) return nullptr;
     // DG_PERM_PLAN=<index> forces a tile shape of the right mode (A/B measurement only)
-    if (const char *e = getenv("DG_PERM_PLAN")) {
+    if (const char *e = dg_override("DG_PERM_PLAN")) {
         const int i = atoi(e);
         if (i >= 0 && i < kNumPlans && kPlans[i].MODE == mode) return &kPlans[i];
     }
@@ -86,18 +86,7 @@ const PermPlan *plan_for(const dg_lut *lut, const DgProblem &p)
     return best;
 }
 
-// n / d == umulhi(n, mul) >> shift for every 0 <= n < 2^31 (d >= 2): with L = ceil(log2 d) and
-// mul = ceil(2^(31+L) / d) < 2^32, the error mul*d - 2^(31+L) is below d <= 2^L = 2^((31+L)-31).
-dgperm::FastDiv make_div(uint32_t d)
-{
-    dgperm::FastDiv f = {0u, 0u, d};
-    if (d < 2) return f;
-    uint32_t L = 0;
-    while ((1ull << L) < d) ++L;
-    f.mul = (uint32_t)(((1ull << (31 + L)) + d - 1) / d);
-    f.shift = L - 1;
-    return f;
-}
+dgperm::FastDiv make_div(uint32_t d) { return dg_make_div(d); }
 
 }   // namespace
 

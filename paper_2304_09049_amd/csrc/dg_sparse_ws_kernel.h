@@ -1,0 +1,136 @@
+// 2-bit table kernel on the sparse matrix instruction with the WEIGHT OPERANDS STATIONARY in registers, for layers
+// with a short reduction (1x1 convolutions / GEMMs with K = 64, 128 or 256) whose time is the output's way to memory.
+//
+// In the tiled sparse-instruction kernel (dg_onehot_kernel.h, BITS = 20) every wavefront rebuilds the dense operand --
+// the table rows of its weight codes, 4 bytes per (row, position) -- for every tile it owns: about 23 VALU instructions
+// and 8 LDS reads per pair of matrix instructions.  With K <= 256 the dense operand of 32 weight rows over ALL of K is
+// at most 128 registers per lane, so here a wavefront builds it once, keeps it, and then only streams pixels: per 32
+// pixels it loads their packed words (the index registers of the instruction, masked: no expansion), issues K / 16
+// matrix instructions and stores the 32 x 32 sums.  Stores of one block overlap the loads and matrix instructions of the
+// next (a store reads its registers when it issues, nothing waits for it), and nothing but two masks per instruction is
+// left on the VALU.  Operand layout and the row-pair table in LDS are those of dg_onehot_kernel.h.
+//
+// Work split: a wavefront owns one block of 32 output channels (its stationary weights) and a contiguous run of
+// 32-pixel blocks; the wavefronts of the other channel blocks of the same pixels sit next to it in the workgroup, so
+// the pixels' words are fetched from memory once and the halves of an output row are written together.
+#pragma once
+
+#include "dg_onehot_kernel.h"
+
+namespace dgoh {
+
+struct WsArgs {
+    DgProblem p;
+    uint32_t rows[4];            // rows[w] = bytes T[w][0..3]
+    int32_t row_blocks;          // ceil(M / 32)
+    int32_t pixel_blocks;        // ceil(N / 32)
+    int32_t streams;             // runs of pixel blocks; wavefronts = row_blocks * streams
+};
+
+// T = K / 32: matrix-instruction pairs per 32 x 32 block; a lane half reads T words of a pixel (or weight row).
+// Order of memory operations: a wavefront's vector memory instructions leave its compute unit in the order they were
+// issued, so a load issued behind a burst of stores waits until the memory system has taken those stores -- and this
+// layer's stores saturate it.  Hence the words of a whole group of G pixel blocks are loaded BEFORE that group's first
+// store is issued (the first group before anything else, so that its latency and the weights' overlap), and a
+// wavefront's run is normally one group.
+// G: pixel blocks per group (their words are in registers together).
+template <int T, int G>
+__global__ void __launch_bounds__(256, (T * G > 32 ? 1 : 2))
+smfmac_ws_kernel(WsArgs a)
+{
+    static_assert(T == 2 || T == 4 || T == 8, "K = 64, 128 or 256");
+    __shared__ uint2 s_rows[4 * 16];
+    const DgProblem &p = a.p;
+    const int lane = threadIdx.x & 63, w4 = threadIdx.x >> 6;
+    const int64_t wave = (int64_t)xcd_contiguous(blockIdx.x, gridDim.x) * 4 + __builtin_amdgcn_readfirstlane(w4);
+    const int rb = (int)(wave % a.row_blocks);
+    const int64_t stream = wave / a.row_blocks;
+    if (stream >= a.streams) return;                        // whole waves leave; there is no barrier
+    const int r = lane & 31, h = lane >> 5;
+    const int row_bytes = p.K / 4;                          // = 8 * T
+    const int m0 = rb * 32;
+
+    // this wavefront's run of pixel blocks, and the loads of its first group
+    const int64_t b0 = stream * a.pixel_blocks / a.streams, b1 = (stream + 1) * a.pixel_blocks / a.streams;
+    const int last_row = p.N - 1;
+    const uint8_t *x_base = p.Xp + h * (4 * T);
+    Words<T> x[G];
+    auto fetch = [&](int64_t blk) {                         // rows beyond N re-read row N - 1 (their sums are not stored)
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int64_t n = min((blk + g) * 32 + r, (int64_t)last_row);
+            if (blk + g < b1) x[g] = load_words_any<T>(x_base + n * row_bytes);
+        }
+    };
+    fetch(b0);
+
+    // the stationary dense operands: for word t of either half of the weight row, the even and the odd codes' table rows
+    v8i dn[T][2];
+    {
+        const uint8_t *wrow = p.Wp + (int64_t)min(m0 + r, p.M - 1) * row_bytes;
+        const Words<T> w0 = load_words_any<T>(wrow), w1 = load_words_any<T>(wrow + 4 * T);
+        uint2 *rows = s_rows + 16 * w4;
+        Pools pl;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pl.w[i] = a.rows[i];
+        sparse_fill_rows(rows, pl, lane);
+        const uint32_t pick = sparse_pick(h);
+#pragma unroll
+        for (int t = 0; t < T; ++t) sparse_dense_rows(rows, w0.v[t], w1.v[t], pick, dn[t][0], dn[t][1]);
+    }
+    float sc_cols[1];
+    dg_mfma_column_scales<1, true>(p, m0, lane, sc_cols);
+    const v4i ones = {0x00010001, 0x00010001, 0x00010001, 0x00010001};      // the kept bytes: (1, 0) per position
+
+    for (int64_t blk = b0; blk < b1; blk += G) {
+        // one block at a time, so that the first stores go out as early as possible: the layer's time is the time its
+        // output takes to drain, counted from the first store (the other wavefront of the SIMD fills the gaps between
+        // the dependent matrix instructions)
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (blk + g >= b1) break;                       // (uniform)
+            v16i acc;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = 0;
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int par = 0; par < 2; ++par)
+                    acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones, dn[t][par], acc,
+                                                                  (int)((x[g].v[t] >> (2 * par)) & 0x33333333u), 0, 0);
+            dg_mfma_store_block<true>(p, acc, m0, (int)((blk + g) * 32), lane, sc_cols[0]);
+        }
+        // (only a run longer than one group comes here; these loads do queue behind the group's stores, which is why
+        // the host sizes runs to one group where it can)
+        if (blk + G < b1) fetch(blk + G);
+    }
+}
+
+inline void launch_sparse_ws(const DgProblem &p, const uint32_t (&rows)[4], int streams, hipStream_t stream)
+{
+    WsArgs a;
+    a.p = p;
+    for (int w = 0; w < 4; ++w) a.rows[w] = rows[w];
+    a.row_blocks = (p.M + 31) / 32;
+    a.pixel_blocks = (p.N + 31) / 32;
+    a.streams = streams;
+    const int64_t waves = (int64_t)a.row_blocks * streams;
+    const dim3 grid((unsigned)((waves + 3) / 4));
+    // a wavefront's whole run in one group where the registers allow it (up to 8 blocks)
+    const int t = p.K / 32;
+    const bool wide = (a.pixel_blocks + streams - 1) / streams > 4;
+    if (t == 8 && wide)
+        hipLaunchKernelGGL((smfmac_ws_kernel<8, 8>), grid, dim3(256), 0, stream, a);
+    else if (t == 8)
+        hipLaunchKernelGGL((smfmac_ws_kernel<8, 4>), grid, dim3(256), 0, stream, a);
+    else if (t == 4 && wide)
+        hipLaunchKernelGGL((smfmac_ws_kernel<4, 8>), grid, dim3(256), 0, stream, a);
+    else if (t == 4)
+        hipLaunchKernelGGL((smfmac_ws_kernel<4, 4>), grid, dim3(256), 0, stream, a);
+    else if (wide)
+        hipLaunchKernelGGL((smfmac_ws_kernel<2, 8>), grid, dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL((smfmac_ws_kernel<2, 4>), grid, dim3(256), 0, stream, a);
+}
+
+}   // namespace dgoh

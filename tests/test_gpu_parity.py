@@ -865,3 +865,44 @@ def test_four_bit_auto_takes_the_sparse_kernel_on_large_layers():
     got = dg.dg_conv2d_lut_requant(lut, Wp, Xp, desc, scale, qs, 0.5, 0)
     torch.cuda.synchronize()
     _assert_same(got.cpu().numpy().reshape(-1, Cout // 4), want, "4-bit fused layer, AUTO (sparse-instruction kernel)")
+
+
+@pytest.mark.parametrize("waves", [0, 3, 7, 100000])
+@pytest.mark.parametrize("K", [64, 128, 256])
+def test_stationary_weight_kernel(K, waves, monkeypatch):
+    """The sparse-instruction kernel with stationary weight operands (K = 64, 128, 256, no filter window), forced on
+    shapes with ragged M and N: runs of one, of an even and of an odd number of pixel blocks per wavefront (`waves`: 0 =
+    the default count, 3 and 7 = long runs, 100000 = one block per wavefront); GEMM with column-major output (run as it
+    is) and row-major output (run transposed), 1x1 convolution with int32, scaled fp32 and re-quantised packed output."""
+    monkeypatch.setenv("DG_ONEHOT_PLAN", "ws")
+    if waves:
+        monkeypatch.setenv("DG_WS_WAVES", str(waves))
+    lw, la, entry = LEVELS["nonuniform_i8"]
+    for (M, N) in [(70, 1000), (64, 333), (33, 64), (130, 2049), (5, 31)]:
+        inp = wl.small_gemm(M, N, K, seed=M + N + K)
+        case = GpuCase(inp, levels=(lw, la), entry=entry)
+        assert case.kernel_name("onehot_smfmac") == "onehot_smfmac_ws_32xK"
+        want = oracle.gemm(inp.Wc, inp.Ac, lw, la)
+        _assert_same(case.run("onehot_smfmac").cpu().numpy(), want, f"ws gemm {(M, N, K)} row-major")
+        out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
+        dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant="onehot_smfmac", strides=(1, M))
+        torch.cuda.synchronize()
+        _assert_same(out.cpu().numpy(), want.T.copy(), f"ws gemm {(M, N, K)} column-major")
+    for (B, H, W, Cout) in [(3, 9, 7, 36), (1, 31, 33, 64), (2, 16, 16, 100)]:
+        c = wl.small_conv(B, H, W, K, Cout, 1, 1, (1, 1), (0, 0), seed=H + K + Cout, scale=True)
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        assert case.kernel_name("onehot_smfmac") == "onehot_smfmac_ws_32xK"
+        acc = oracle.conv2d(c.Wc, c.Ac, lw, la)
+        _assert_same(case.run("onehot_smfmac").cpu().numpy(), acc, f"ws conv {(B, H, W, K, Cout)}")
+        y = oracle.scale_epilogue_nhwc(acc, c.scale)
+        got = case.run("onehot_smfmac", scale=True).cpu().numpy()
+        np.testing.assert_allclose(got, y, rtol=1e-6, atol=0)
+        assert np.array_equal(got, y)
+        qs = np.float32(3.0 / max(1e-6, float(np.percentile(np.abs(y), 90))))
+        codes = oracle.quantize_codes(y, float(qs), 0.5, 0, 3)
+        q = dg.dg_conv2d_lut_requant(case.lut, case.Wp, case.Ap, case.desc, case.scale, float(qs), 0.5, 0, variant="onehot_smfmac")
+        torch.cuda.synchronize()
+        _assert_same(q.cpu().numpy().reshape(-1, Cout // 4), oracle.pack_codes(codes.reshape(-1, Cout)), f"ws fused layer {(B, H, W, K, Cout)}")
+    # a filter window, a stride or another K is not its case: the tiled sparse-instruction kernel takes over
+    c = wl.small_conv(1, 8, 8, 64, 32, 3, 3, (1, 1), (1, 1), seed=1)
+    assert GpuCase(c, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac") != "onehot_smfmac_ws_32xK"
