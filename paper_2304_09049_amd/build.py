@@ -42,15 +42,22 @@ def build(verbose: bool = True, extra_flags=(), jobs: int = 8, incremental: bool
     os.makedirs(objdir, exist_ok=True)
     flags = [f for f in HIPCC_FLAGS if f != "-shared"] + list(extra_flags)
 
-    headers = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(CSRC, "*.inc")) + \
-        glob.glob(os.path.join(ROOT, "include", "*.h")) + [os.path.abspath(__file__)]
-    newest_header = max(os.path.getmtime(h) for h in headers)
+    def up_to_date(obj: str) -> bool:
+        """The object is newer than every file the compiler read for it (listed in the .d file written beside it)."""
+        dep = obj + ".d"
+        if not (os.path.exists(obj) and os.path.exists(dep)):
+            return False
+        with open(dep) as f:
+            text = f.read().replace("\\\n", " ")
+        files = text.split(":", 1)[1].split() if ":" in text else []
+        stamp = os.path.getmtime(obj)
+        return bool(files) and all(os.path.exists(x) and os.path.getmtime(x) < stamp for x in files + [os.path.abspath(__file__)])
 
     def compile_one(src: str) -> str:
         obj = os.path.join(objdir, os.path.basename(src) + ".o")
-        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
+        if incremental and up_to_date(obj):
             return obj
-        cmd = [hipcc] + flags + ["-c", src, "-o", obj]
+        cmd = [hipcc] + flags + ["-MD", "-MF", obj + ".d", "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -23,17 +23,22 @@ struct WsArgs {
     DgProblem p;
     uint32_t rows[4];            // rows[w] = bytes T[w][0..3]
     int32_t row_blocks;          // ceil(M / 32)
-    int32_t pixel_blocks;        // ceil(N / 32)
     int32_t streams;             // runs of pixel blocks; wavefronts = row_blocks * streams
+    int32_t run, longer;         // the first `longer` runs have run + 1 pixel blocks, the others `run`
+    FastDiv div_row_blocks;
 };
 
 // T = K / 32: matrix-instruction pairs per 32 x 32 block; a lane half reads T words of a pixel (or weight row).
-// Order of memory operations: a wavefront's vector memory instructions leave its compute unit in the order they were
-// issued, so a load issued behind a burst of stores waits until the memory system has taken those stores -- and this
-// layer's stores saturate it.  Hence the words of a whole group of G pixel blocks are loaded BEFORE that group's first
-// store is issued (the first group before anything else, so that its latency and the weights' overlap), and a
-// wavefront's run is normally one group.
 // G: pixel blocks per group (their words are in registers together).
+// What was measured on the 56x56x256 -> 64 layer at batch 32 (25.7 MB of output, which alone takes 4.0 us to drain plus
+// 1.6 us of launch): the layer's time is the launch, the time to the first stores and the drain, so
+//   - the words of a whole group of pixel blocks are loaded before the group's first store is issued: a wavefront's
+//     vector memory instructions leave the compute unit in issue order, and a load queued behind a burst of stores
+//     waits until the memory system has taken them; a wavefront's run is normally one group;
+//   - there is no division in the prologue (0.3 us);
+//   - blocks are computed and stored one at a time: two blocks sharing the instruction stream (independent sums back to
+//     back) store in larger bursts and were 0.7 us slower; so was building the operands interleaved with the first block;
+//   - pixel words are asked for before the weight words (0.15 us faster than the other way round).
 template <int T, int G>
 __global__ void __launch_bounds__(256, (T * G > 32 ? 1 : 2))
 smfmac_ws_kernel(WsArgs a)
@@ -42,16 +47,18 @@ smfmac_ws_kernel(WsArgs a)
     __shared__ uint2 s_rows[4 * 16];
     const DgProblem &p = a.p;
     const int lane = threadIdx.x & 63, w4 = threadIdx.x >> 6;
-    const int64_t wave = (int64_t)xcd_contiguous(blockIdx.x, gridDim.x) * 4 + __builtin_amdgcn_readfirstlane(w4);
-    const int rb = (int)(wave % a.row_blocks);
-    const int64_t stream = wave / a.row_blocks;
-    if (stream >= a.streams) return;                        // whole waves leave; there is no barrier
+    // (no division in the prologue: it is on the way to the first store)
+    const uint32_t wave = xcd_contiguous(blockIdx.x, gridDim.x) * 4u + (uint32_t)__builtin_amdgcn_readfirstlane(w4);
+    const uint32_t stream = fdiv(wave, a.div_row_blocks);
+    const int rb = (int)(wave - stream * (uint32_t)a.row_blocks);
+    if (stream >= (uint32_t)a.streams) return;              // whole waves leave; there is no barrier
     const int r = lane & 31, h = lane >> 5;
     const int row_bytes = p.K / 4;                          // = 8 * T
     const int m0 = rb * 32;
 
-    // this wavefront's run of pixel blocks, and the loads of its first group
-    const int64_t b0 = stream * a.pixel_blocks / a.streams, b1 = (stream + 1) * a.pixel_blocks / a.streams;
+    // this wavefront's run of pixel blocks
+    const int64_t b0 = (int64_t)stream * a.run + min(stream, (uint32_t)a.longer);
+    const int64_t b1 = b0 + a.run + (stream < (uint32_t)a.longer ? 1 : 0);
     const int last_row = p.N - 1;
     const uint8_t *x_base = p.Xp + h * (4 * T);
     Words<T> x[G];
@@ -112,13 +119,16 @@ inline void launch_sparse_ws(const DgProblem &p, const uint32_t (&rows)[4], int 
     a.p = p;
     for (int w = 0; w < 4; ++w) a.rows[w] = rows[w];
     a.row_blocks = (p.M + 31) / 32;
-    a.pixel_blocks = (p.N + 31) / 32;
+    const int pixel_blocks = (p.N + 31) / 32;
     a.streams = streams;
+    a.run = pixel_blocks / streams;
+    a.longer = pixel_blocks % streams;
+    a.div_row_blocks = make_div((uint32_t)a.row_blocks);
     const int64_t waves = (int64_t)a.row_blocks * streams;
     const dim3 grid((unsigned)((waves + 3) / 4));
     // a wavefront's whole run in one group where the registers allow it (up to 8 blocks)
     const int t = p.K / 32;
-    const bool wide = (a.pixel_blocks + streams - 1) / streams > 4;
+    const bool wide = a.run + (a.longer ? 1 : 0) > 4;
     if (t == 8 && wide)
         hipLaunchKernelGGL((smfmac_ws_kernel<8, 8>), grid, dim3(256), 0, stream, a);
     else if (t == 8)
