@@ -185,7 +185,9 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *                    kernel's 128 x 128 tile; "ws" the sparse-instruction kernel with stationary weight operands
  *                    (K = 64, 128, 256 without a filter window) whatever the size.  While it is set AUTO does not
  *                    move to the sparse-instruction forms on its own.
- *   DG_WS_WAVES      target number of wavefronts of that kernel (default: one per SIMD)
+ *                    "fewn" the few-columns kernel on the sparse instruction (K % 256 == 0, no filter window).
+ *   DG_WS_WAVES      target number of wavefronts of the "ws" kernel (default: one per SIMD)
+ *   DG_FEWN_WAVES    wavefronts per workgroup of the "fewn" kernel (1..8)
  *   DG_ONEHOT_WAVES  target number of wavefronts of the split-K kernel (default 2048)
  *   DG_PERM_PLAN     index of the permute kernel's tile shape
  */

@@ -294,7 +294,7 @@ int64_t dg_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad)
 
 namespace {
 
-enum class Pick { Perm, Lds, LdsF32, Mfma, SmallN, Lut65k, OneHot, Sparse, Sparse4, Sparse2p, SparseWs, Unsupported };
+enum class Pick { Perm, Lds, LdsF32, Mfma, SmallN, Lut65k, OneHot, Sparse, Sparse4, Sparse2p, SparseWs, FewN, Unsupported };
 
 Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
 {
@@ -319,11 +319,14 @@ Pick pick_kernel(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case DG_KERNEL_LUT65K: return dg_lut65k_supports(lut, p) ? Pick::Lut65k : Pick::Unsupported;
     case DG_KERNEL_ONEHOT_MFMA: return dg_onehot_supports(lut, p) ? Pick::OneHot : Pick::Unsupported;
     case DG_KERNEL_ONEHOT_SMFMAC:
+        if (dg_fewn_preferred(lut, p)) return Pick::FewN;
         if (dg_sparse_ws_preferred(lut, p)) return Pick::SparseWs;
         if (dg_sparse2p_supports(lut, p)) return Pick::Sparse2p;
         return dg_sparse_supports(lut, p) ? Pick::Sparse : Pick::Unsupported;
     case DG_KERNEL_AUTO:
         // AUTO stays within the table kernels: the decode-and-multiply matrix-core kernel is a comparison only.
+        // few columns, long rows: the weights stream once through the sparse instruction's index operand
+        if (dg_fewn_preferred(lut, p)) return Pick::FewN;
         // one or two columns: K across the lanes of a wavefront streams the weights once at full width
         if (p.N <= 2 && p.K >= 1024 && dg_smalln_supports(lut, p)) return Pick::SmallN;
         // int8 tables: selecting entries with one-hot operands on the matrix cores outruns the permute loop at every
@@ -354,6 +357,7 @@ dg_status run(const dg_lut *lut, const DgProblem &p, dg_kernel variant, hipStrea
     case Pick::Sparse4: return dg_launch_sparse4(lut, p, stream);
     case Pick::Sparse2p: return dg_launch_sparse2p(lut, p, stream);
     case Pick::SparseWs: return dg_launch_sparse_ws(lut, p, stream);
+    case Pick::FewN: return dg_launch_fewn(lut, p, stream);
     case Pick::Unsupported: break;
     }
     return dg_fail(DG_ERR_UNSUPPORTED,
@@ -375,6 +379,7 @@ const char *pick_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     case Pick::Sparse4: return "onehot_smfmac4_64x128";
     case Pick::Sparse2p: return "onehot_smfmac_2p_32x128";
     case Pick::SparseWs: return "onehot_smfmac_ws_32xK";
+    case Pick::FewN: return "onehot_smfmac_fewn_16";
     case Pick::Unsupported: break;
     }
     return "unsupported";

@@ -906,3 +906,32 @@ def test_stationary_weight_kernel(K, waves, monkeypatch):
     # a filter window, a stride or another K is not its case: the tiled sparse-instruction kernel takes over
     c = wl.small_conv(1, 8, 8, 64, 32, 3, 3, (1, 1), (1, 1), seed=1)
     assert GpuCase(c, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac") != "onehot_smfmac_ws_32xK"
+
+
+@pytest.mark.parametrize("waves", [0, 1, 3, 16])
+@pytest.mark.parametrize("K", [256, 1280, 4096, 8192])
+def test_few_columns_sparse_kernel(K, waves, monkeypatch):
+    """The few-columns kernel on the sparse instruction (weights as the index operand), forced on shapes with ragged M
+    and 1 to 40 columns (up to three passes of 16), any split of K over the wavefronts; row-major and column-major
+    output, int32 and scaled fp32."""
+    monkeypatch.setenv("DG_ONEHOT_PLAN", "fewn")
+    if waves:
+        monkeypatch.setenv("DG_FEWN_WAVES", str(waves))
+    lw, la, entry = LEVELS["nonuniform_i8"]
+    for (M, N) in [(70, 1), (33, 2), (8, 5), (130, 16), (64, 17), (300, 40)]:
+        inp = wl.make_inputs(wl.Workload(name="g", kind="gemm", M=M, N=N, K=K, scale=True, seed=M + N + K))
+        case = GpuCase(inp, levels=(lw, la), entry=entry)
+        assert case.kernel_name("onehot_smfmac") == "onehot_smfmac_fewn_16"
+        want = oracle.gemm(inp.Wc, inp.Ac, lw, la)
+        _assert_same(case.run("onehot_smfmac").cpu().numpy(), want, f"fewn gemm {(M, N, K)}")
+        out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
+        dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant="onehot_smfmac", strides=(1, M))
+        torch.cuda.synchronize()
+        _assert_same(out.cpu().numpy(), want.T.copy(), f"fewn gemm {(M, N, K)} column-major")
+        got = case.run("onehot_smfmac", scale=True).cpu().numpy()
+        ref = oracle.scale_epilogue_rows(want, inp.scale)
+        np.testing.assert_allclose(got, ref, rtol=1e-6, atol=0)
+        assert np.array_equal(got, ref)
+    # K must be whole super-steps of 256 positions
+    inp = wl.small_gemm(64, 4, 320, seed=2)
+    assert GpuCase(inp, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac") != "onehot_smfmac_fewn_16"
