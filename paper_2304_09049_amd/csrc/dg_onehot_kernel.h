@@ -268,6 +268,37 @@ __device__ __forceinline__ void sparse_dense_rows(const uint2 *rows, uint32_t w0
     }
 }
 
+// The same with ONE table for the whole workgroup, at a fixed LDS address: threads 0-15 fill it and the workgroup meets
+// at a barrier before the first read.  A read's address is then nothing but the 4-bit index times 8, and with the
+// indices kept pre-multiplied, a byte each, it is one bit-field extract per read (three instructions per read otherwise:
+// shift, mask, add the wavefront's table base).
+__device__ __forceinline__ void sparse_fill_table(uint2 *table, const Pools &pl, int tid)
+{
+    if (tid < 16) {
+        const int c0 = tid & 3, c1 = tid >> 2;
+        const uint32_t r0 = c0 == 0 ? pl.w[0] : (c0 == 1 ? pl.w[1] : (c0 == 2 ? pl.w[2] : pl.w[3]));
+        const uint32_t r1 = c1 == 0 ? pl.w[0] : (c1 == 1 ? pl.w[1] : (c1 == 2 ? pl.w[2] : pl.w[3]));
+        table[tid] = make_uint2(r0, r1);
+    }
+}
+
+__device__ __forceinline__ void sparse_dense_rows_shared(const uint2 *table, uint32_t w0, uint32_t w1, uint32_t pick, v8i &even, v8i &odd)
+{
+    const uint32_t v = __builtin_amdgcn_perm(w1, w0, pick), t = v >> 2;
+    uint32_t e = ((v & 0x03030303u) | (t & 0x0C0C0C0Cu)) << 3;          // byte b: 8 * (code 4b | code 4b+2 << 2)
+    uint32_t o = ((t & 0x03030303u) | ((v >> 4) & 0x0C0C0C0Cu)) << 3;   // byte b: 8 * (code 4b+1 | code 4b+3 << 2)
+    // (kept as they are: a byte of them IS an LDS offset; left to itself the compiler folds the multiplication into a
+    // shift and a mask per read)
+    asm volatile("" : "+v"(e), "+v"(o));
+    const char *base = (const char *)table;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const uint2 x = *(const uint2 *)(base + ((e >> (8 * b)) & 255u)), y = *(const uint2 *)(base + ((o >> (8 * b)) & 255u));
+        even[2 * b] = (int)x.x, even[2 * b + 1] = (int)x.y;
+        odd[2 * b] = (int)y.x, odd[2 * b + 1] = (int)y.y;
+    }
+}
+
 // Position bookkeeping shared by the two kernels: output column n -> image coordinates, and the filter tap of a chunk.
 // Workgroups are dealt to the 8 XCDs, each with an L2 of its own, round-robin.  Renumbered this way each XCD works on a
 // contiguous run of tiles, so that neighbouring pixels' filter windows and a tile row's weights meet in one L2
@@ -314,7 +345,7 @@ onehot_mfma_kernel(Args a)
     static_assert(!F::SPARSE || (TR && !TWO), "the sparse operand is the MFMA's row operand: activations on the rows");
     constexpr int RB = TWO ? 1 : WM;                       // weight row blocks of 32 rows
     constexpr int WRUNS = F::SPARSE ? 2 : 1;               // runs of CH words a weight lane reads: its half's, or both
-    __shared__ uint2 s_rows[F::SPARSE ? 4 * 16 : 1];
+    __shared__ uint2 s_rows[F::SPARSE ? 16 : 1];            // the sparse form's table of row pairs, one for the workgroup
     constexpr int TPW = 4 / SKW;                           // tiles per workgroup
     constexpr int NB = RB * WN;                            // 32x32 output blocks per tile
     extern __shared__ int32_t s_acc[];                      // SKW > 1: [TPW][NB][16][64] sums
@@ -323,8 +354,11 @@ onehot_mfma_kernel(Args a)
     const int ks = w4 % SKW, tw = w4 / SKW;                 // this wavefront's share of K, and its tile within the workgroup
     const int64_t my_tile = (int64_t)xcd_contiguous(blockIdx.x, gridDim.x) * TPW + tw;
     const bool active = my_tile < a.wave_tiles;
-    if (SKW == 1 && !active) return;                       // whole waves leave; there is no barrier on this path
-    if (F::SPARSE) sparse_fill_rows(s_rows + 16 * w4, a.pools, lane);
+    if (F::SPARSE) {
+        sparse_fill_table(s_rows, a.pools, threadIdx.x);
+        __syncthreads();                                   // (every wavefront of the workgroup, also one without a tile)
+    }
+    if (SKW == 1 && !active) return;                       // whole waves leave; no barrier follows on this path
     const int64_t wave_tile = active ? my_tile : 0;        // (an idle wavefront of a shared workgroup adds zeros)
     if (SKW > 1)
         for (int i = threadIdx.x; i < TPW * NB * 1024; i += 256) s_acc[i] = 0;
@@ -422,11 +456,10 @@ onehot_mfma_kernel(Args a)
             // the instructions of step t.
             v8i dn[2][WM][2];
             int ix[2][WN][2];
-            const uint2 *rows = s_rows + 16 * w4;
             const uint32_t pick = sparse_pick(h);
             auto prepare = [&](int t, int u, int buf) {      // unit u < WM: a weight block; else an activation block
                 if (u < WM) {
-                    sparse_dense_rows(rows, ca[u].v[t], ca1[u].v[t], pick, dn[buf][u][0], dn[buf][u][1]);
+                    sparse_dense_rows_shared(s_rows, ca[u].v[t], ca1[u].v[t], pick, dn[buf][u][0], dn[buf][u][1]);
                 } else {
                     const uint32_t word = cb[u - WM].v[t];
                     ix[buf][u - WM][0] = (int)(word & 0x33333333u);
