@@ -44,14 +44,20 @@ __global__ void __launch_bounds__(256, (T * G > 32 ? 1 : 2))
 smfmac_ws_kernel(WsArgs a)
 {
     static_assert(T == 2 || T == 4 || T == 8, "K = 64, 128 or 256");
-    __shared__ uint2 s_rows[4 * 16];
+    __shared__ uint2 s_rows[16];                            // the table of row pairs, one for the workgroup
     const DgProblem &p = a.p;
     const int lane = threadIdx.x & 63, w4 = threadIdx.x >> 6;
+    {
+        Pools pl;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pl.w[i] = a.rows[i];
+        sparse_fill_table(s_rows, pl, threadIdx.x);
+    }
     // (no division in the prologue: it is on the way to the first store)
     const uint32_t wave = xcd_contiguous(blockIdx.x, gridDim.x) * 4u + (uint32_t)__builtin_amdgcn_readfirstlane(w4);
     const uint32_t stream = fdiv(wave, a.div_row_blocks);
     const int rb = (int)(wave - stream * (uint32_t)a.row_blocks);
-    if (stream >= (uint32_t)a.streams) return;              // whole waves leave; there is no barrier
+    const bool idle = stream >= (uint32_t)a.streams;        // (a wavefront beyond the last run: it only joins the barrier)
     const int r = lane & 31, h = lane >> 5;
     const int row_bytes = p.K / 4;                          // = 8 * T
     const int m0 = rb * 32;
@@ -76,14 +82,13 @@ smfmac_ws_kernel(WsArgs a)
     {
         const uint8_t *wrow = p.Wp + (int64_t)min(m0 + r, p.M - 1) * row_bytes;
         const Words<T> w0 = load_words_any<T>(wrow), w1 = load_words_any<T>(wrow + 4 * T);
-        uint2 *rows = s_rows + 16 * w4;
-        Pools pl;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pl.w[i] = a.rows[i];
-        sparse_fill_rows(rows, pl, lane);
+        // (the table is in LDS once every wavefront is here; the loads above stay in flight across this barrier,
+        // which waits for LDS operations only)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (idle) return;
         const uint32_t pick = sparse_pick(h);
 #pragma unroll
-        for (int t = 0; t < T; ++t) sparse_dense_rows(rows, w0.v[t], w1.v[t], pick, dn[t][0], dn[t][1]);
+        for (int t = 0; t < T; ++t) sparse_dense_rows_shared(s_rows, w0.v[t], w1.v[t], pick, dn[t][0], dn[t][1]);
     }
     float sc_cols[1];
     dg_mfma_column_scales<1, true>(p, m0, lane, sc_cols);
