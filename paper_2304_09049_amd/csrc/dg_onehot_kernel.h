@@ -401,7 +401,41 @@ onehot_mfma_kernel(Args a)
         ci = pos - tap * p.Cin;
     }
     Words<CH> wa[RB][WRUNS], wb[WN];
+    // Where the next chunk's words of each column are read, and whether that filter tap lies inside the image.  A tap
+    // outside the image points at the first pixel instead and is masked by its selector: the loads are unconditional,
+    // because a load under a branch would make the compiler wait for it at once and the prefetch would hide nothing.
+    // STEPPED (the sparse instruction's widest tile, where every VALU instruction is paid in full -- that instruction
+    // does not overlap with them): offsets and validity are recomputed only when the walk enters a new tap and just
+    // stepped by a chunk otherwise, and the kept bytes are rebuilt per tap too (VGG layer 61.4 -> 58.6 us, 8192-cube
+    // 946 -> 931 us).  On the other tiles and forms that was measured 2 - 20 % slower, so they recompute per chunk.
+    // (32-bit byte offsets from the activations' base: the host sends only inputs of less than 2^31 packed bytes here)
+    constexpr bool STEPPED = F::SPARSE && SKW == 1 && WN == 4;
+    uint32_t x_off[STEPPED ? WN : 1];
     bool vb[WN];
+    bool starts_tap = true;                                  // the chunk fetched last is the first of its tap (or of the share)
+    auto next_position = [&]() {                             // (kh, kw, ci) of the chunk after this one; true: a new tap
+        ci += CHUNK;
+        if (ci != p.Cin) return false;
+        ci = 0;
+        if (++kw == p.KW) {
+            kw = 0;
+            ++kh;
+        }
+        return true;
+    };
+    auto enter_tap = [&]() {
+        if constexpr (STEPPED) {
+            const int32_t tap_off = (kh * p.W + kw) * cq + ci / F::PER_BYTE;
+#pragma unroll
+            for (int bn = 0; bn < WN; ++bn) {
+                const int ih = col[bn].ih0 + kh, iw = col[bn].iw0 + kw;
+                vb[bn] = col[bn].ok & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
+                // (outside: the first pixel at the same channel offset, so that stepping stays inside that pixel)
+                x_off[bn] = vb[bn] ? (uint32_t)((int32_t)col[bn].off0 + tap_off) : (uint32_t)(h * (4 * CH) + ci / F::PER_BYTE);
+            }
+        }
+    };
+    enter_tap();
     auto fetch = [&](int chunk) {                            // `chunk` is clamped: a fetch past the share is unused
         const int cw = min(chunk, chunks - 1);
 #pragma unroll
@@ -409,22 +443,27 @@ onehot_mfma_kernel(Args a)
 #pragma unroll
             for (int run = 0; run < WRUNS; ++run)
                 wa[bm][run] = load_words<CH>(w_ptr[bm] + (int64_t)cw * (8 * CH) + run * (4 * CH));
-        const int64_t tap_off = ((int64_t)kh * p.W + kw) * cq + ci / F::PER_BYTE;
+        if constexpr (STEPPED) {
 #pragma unroll
-        for (int bn = 0; bn < WN; ++bn) {
-            const int ih = col[bn].ih0 + kh, iw = col[bn].iw0 + kw;
-            vb[bn] = col[bn].ok & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
-            // always load (a tap outside the image reads the first pixel instead and is masked by its selector): a
-            // load under a branch would make the compiler wait for it at once, and the prefetch would hide nothing
-            wb[bn] = load_words<CH>(vb[bn] ? p.Xp + col[bn].off0 + tap_off : p.Xp + h * (4 * CH));
-        }
-        ci += CHUNK;
-        if (ci == p.Cin) {
-            ci = 0;
-            if (++kw == p.KW) {
-                kw = 0;
-                ++kh;
+            for (int bn = 0; bn < WN; ++bn) wb[bn] = load_words<CH>(p.Xp + x_off[bn]);
+        } else {
+            const int64_t tap_off = ((int64_t)kh * p.W + kw) * cq + ci / F::PER_BYTE;
+#pragma unroll
+            for (int bn = 0; bn < WN; ++bn) {
+                const int ih = col[bn].ih0 + kh, iw = col[bn].iw0 + kw;
+                vb[bn] = col[bn].ok & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
+                wb[bn] = load_words<CH>(vb[bn] ? p.Xp + col[bn].off0 + tap_off : p.Xp + h * (4 * CH));
             }
+            next_position();
+        }
+    };
+    auto advance = [&]() {                                   // STEPPED: to the chunk after the one fetched last
+        starts_tap = next_position();
+        if (starts_tap) {                                    // (uniform)
+            enter_tap();
+        } else {
+#pragma unroll
+            for (int bn = 0; bn < WN; ++bn) x_off[bn] += CHUNK / F::PER_BYTE;
         }
     };
 
@@ -432,6 +471,7 @@ onehot_mfma_kernel(Args a)
     // every wavefront's zeroes are in LDS before any wavefront adds to them; the loads above stay in flight across
     // this barrier (it waits for LDS only)
     if (SKW > 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    v4i ones[F::SPARSE ? WN : 1];                            // sparse form: the kept bytes of the one-hot operand
     for (int c = c0; c < c1; ++c) {
         Words<CH> ca[RB], ca1[RB], cb[WN];
         bool valid[WN];
@@ -442,14 +482,17 @@ onehot_mfma_kernel(Args a)
             cb[bn] = wb[bn];
             valid[bn] = vb[bn];
         }
+        const bool new_tap = starts_tap;                    // of the chunk about to be computed
+        if constexpr (STEPPED) advance();
         fetch(c + 1 < c1 ? c + 1 : c);                      // unconditional (the last one re-reads in bounds and is unused)
         if constexpr (F::SPARSE) {
-            // the kept bytes of the one-hot operand: (1, 0) per position, or zeros for a tap outside the image
-            v4i ones[WN];
+            // the kept bytes: (1, 0) per position, or zeros for a tap outside the image; they change with the tap only
+            if (!STEPPED || new_tap) {
 #pragma unroll
-            for (int bn = 0; bn < WN; ++bn) {
-                const int x = valid[bn] ? 0x00010001 : 0;
-                ones[bn] = (v4i){x, x, x, x};
+                for (int bn = 0; bn < WN; ++bn) {
+                    const int x = valid[bn] ? 0x00010001 : 0;
+                    ones[bn] = (v4i){x, x, x, x};
+                }
             }
             // Step t = the chunk's word t: two instructions (even codes, odd codes) per block of the tile.  The operands
             // of step t+1 -- per weight block a unit of table reads, per activation block two masks -- are made between

@@ -29,6 +29,13 @@ int64_t tile_count(const DgProblem &p, int wm, int wn)
 
 bool fits_int8(const dg_lut *lut) { return lut->min_entry >= -128 && lut->max_entry <= 127; }
 
+// the tiled kernels address the packed activations with 32-bit byte offsets
+bool offsets_fit(const DgProblem &p, int codes_per_byte)
+{
+    const int64_t images = (int64_t)p.N / ((int64_t)p.OH * p.OW);
+    return images * p.H * p.W * (p.Cin / codes_per_byte) < ((int64_t)1 << 31);
+}
+
 // `tile` > 0 fixes an unshared tile of that many blocks' width instead of modelling (see sparse_plan)
 Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
 {
@@ -135,6 +142,7 @@ bool dg_onehot_supports(const dg_lut *lut, const DgProblem &p)
     // MFMA operands are int8: wider entries take two planes, T = 256 * hi + lo (2-bit codes only, hi within int8)
     if (!fits_int8(lut) && (lut->bits != 2 || lut->max_entry > 127 * 256 + 127)) return false;
     if (p.Cin % (8 * per_byte(lut)) != 0) return false;                // a lane half reads whole words of one tap
+    if (!offsets_fit(p, per_byte(lut))) return false;
     const Plan q = plan_for(lut, p, TABLE);
     if ((uintptr_t)p.Wp % (4 * q.ch) != 0 || (uintptr_t)p.Xp % (4 * q.ch) != 0) return false;
     return true;
@@ -204,6 +212,7 @@ bool dg_sparse_supports(const dg_lut *lut, const DgProblem &p)
     if (p.Cin % 32 != 0) return false;                                 // a lane half reads whole words of one tap
     if (sparse_transposes(p) && !sparse_can_transpose(p)) return false;
     const DgProblem t = sparse_problem(p);
+    if (!offsets_fit(t, 4)) return false;
     const Plan q = sparse_plan(lut, t);
     if ((uintptr_t)t.Wp % (4 * q.ch) != 0 || (uintptr_t)t.Xp % (4 * q.ch) != 0) return false;
     return true;
@@ -410,6 +419,7 @@ bool dg_decode_supports(const dg_lut *lut, const DgProblem &p)
     // the levels themselves are the MFMA operands: the table must be their outer product, with 2-bit codes
     if (lut->dtype == DG_LUT_F32 || !lut->separable || lut->bits != 2) return false;
     if (p.Cin % 32 != 0) return false;                                 // a lane half reads whole words of one tap
+    if (!offsets_fit(p, 4)) return false;
     const Plan q = plan_for(lut, p, DECODE);
     if ((uintptr_t)p.Wp % (4 * q.ch) != 0 || (uintptr_t)p.Xp % (4 * q.ch) != 0) return false;
     return true;
