@@ -1,9 +1,9 @@
 // 2-bit table kernel for GEMMs with few activation rows (N <= 16 per pass; large M and K: the weights are streamed once
 // and are all of the traffic), on the sparse matrix instruction v_smfmac_i32_16x16x128_i8.
 //
-// Here the WEIGHTS are the instruction's sparse operand: its kept bytes are the constants (1, 0) and its index register
-// is the packed weight word masked to every other code -- so the streamed operand costs one AND (or shift + AND) per
-// instruction and no expansion at all -- and the instruction's index multiplexer picks, out of the four bytes the dense
+// Here the WEIGHTS are the instruction's sparse operand: its kept bytes are the constants (1, 0) (even codes) or (0, 1)
+// (odd codes) and its index register is the packed weight word as loaded -- so the streamed operand costs no
+// instruction at all -- and the instruction's index multiplexer picks, out of the four bytes the dense
 // operand holds per reduction position, the entry of the weight code: the dense operand is the table COLUMN of the
 // activation code, T[0..3][a(n,k)], fetched from a 16-entry table of column pairs in LDS as in the tiled
 // sparse-instruction kernel (dg_onehot_kernel.h, with the roles of weights and activations exchanged).
@@ -77,7 +77,11 @@ fewn_kernel(FewNArgs a)
     // activation row (columns beyond N re-read row N - 1): the words whose codes this lane's dense registers cover
     const uint8_t *x_ptr = p.Xp + (int64_t)min(n0 + i16, p.N - 1) * row_bytes + 16 * (q >> 1);
     const uint32_t pick = dgoh::sparse_pick(q & 1);
-    const v4i ones = {0x00010001, 0x00010001, 0x00010001, 0x00010001};      // the kept bytes: (1, 0) per position
+    // the kept bytes: (1, 0) per position with the even codes, (0, 1) with the odd; the index of both is the packed word
+    // (of a 4-bit field the low half is the first kept byte's index, the high half the second's; the byte that is 0 may
+    // pick anything)
+    const v4i ones_even = {0x00010001, 0x00010001, 0x00010001, 0x00010001};
+    const v4i ones_odd = {0x01000100, 0x01000100, 0x01000100, 0x01000100};
 
     v4i acc[R];
 #pragma unroll
@@ -118,8 +122,8 @@ fewn_kernel(FewNArgs a)
 #pragma unroll
             for (int rb = 0; rb < R; ++rb) {
                 const uint32_t word = t == 0 ? wq[u][rb].x : (t == 1 ? wq[u][rb].y : (t == 2 ? wq[u][rb].z : wq[u][rb].w));
-                acc[rb] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(ones, even[cur], acc[rb], (int)(word & 0x33333333u), 0, 0);
-                acc[rb] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(ones, odd[cur], acc[rb], (int)((word >> 2) & 0x33333333u), 0, 0);
+                acc[rb] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(ones_even, even[cur], acc[rb], (int)word, 0, 0);
+                acc[rb] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(ones_odd, odd[cur], acc[rb], (int)word, 0, 0);
             }
         }
     }

@@ -29,9 +29,11 @@
 // BITS = 20 is the 2-bit table kernel on the SPARSE matrix instruction (v_smfmac_i32_32x32x64_i8), at half the matrix
 // work.  A one-hot run of 4 bytes is 1-of-4 sparse, and that instruction takes one operand as two kept bytes out of
 // every four plus their 2-bit positions -- which, for a one-hot run, are the constant bytes (1, 0) and the CODE itself.
-// So the activation operand needs no expansion at all: its values are a constant, its index register is the packed
-// word masked to every other code ((word >> 2s) & 0x33333333 for the even / odd codes), and the hardware's index
-// multiplexer performs the table lookup: it picks, out of the 4 bytes T[w(k)][0..3] that the dense operand holds for a
+// So the activation operand needs no expansion at all: its values are a constant and its index register is the packed
+// word itself -- a 4-bit field of it holds an even and an odd code, the indices of the first and the second kept byte,
+// so with kept bytes (1, 0) the instruction selects by the even codes, and by the odd ones with kept bytes (0, 1) or
+// with the word shifted by one code (the byte that is 0 may select anything) -- and the hardware's index multiplexer
+// performs the table lookup: it picks, out of the 4 bytes T[w(k)][0..3] that the dense operand holds for a
 // position, the entry of the activation code.  The dense operand is a dword per position, the table ROW of the weight
 // code, fetched from a 16-entry table of row pairs in LDS (one 8-byte read serves two positions, without bank
 // conflicts).  One instruction covers 16 positions per lane pair in the time the dense MFMA takes for 8.
@@ -486,7 +488,11 @@ onehot_mfma_kernel(Args a)
         if constexpr (STEPPED) advance();
         fetch(c + 1 < c1 ? c + 1 : c);                      // unconditional (the last one re-reads in bounds and is unused)
         if constexpr (F::SPARSE) {
-            // the kept bytes: (1, 0) per position, or zeros for a tap outside the image; they change with the tap only
+            // The kept bytes: (1, 0) per position, or zeros for a tap outside the image; they change with the tap only.
+            // The index register is the packed word as it is for the even codes and shifted by one code for the odd
+            // ones: of a 4-bit field the low half is the index of the first kept byte (the 1), and what the high half
+            // makes the second kept byte (the 0) pick does not matter.  (Kept bytes (0, 1) would spare the shift too,
+            // but a second set of them does not fit the widest tile's registers.)
             if (!STEPPED || new_tap) {
 #pragma unroll
                 for (int bn = 0; bn < WN; ++bn) {
@@ -495,19 +501,16 @@ onehot_mfma_kernel(Args a)
                 }
             }
             // Step t = the chunk's word t: two instructions (even codes, odd codes) per block of the tile.  The operands
-            // of step t+1 -- per weight block a unit of table reads, per activation block two masks -- are made between
+            // of step t+1 -- per weight block a unit of table reads, per activation block a shift -- are made between
             // the instructions of step t.
             v8i dn[2][WM][2];
-            int ix[2][WN][2];
+            int odd_ix[2][WN];
             const uint32_t pick = sparse_pick(h);
             auto prepare = [&](int t, int u, int buf) {      // unit u < WM: a weight block; else an activation block
-                if (u < WM) {
+                if (u < WM)
                     sparse_dense_rows_shared(s_rows, ca[u].v[t], ca1[u].v[t], pick, dn[buf][u][0], dn[buf][u][1]);
-                } else {
-                    const uint32_t word = cb[u - WM].v[t];
-                    ix[buf][u - WM][0] = (int)(word & 0x33333333u);
-                    ix[buf][u - WM][1] = (int)((word >> 2) & 0x33333333u);
-                }
+                else
+                    odd_ix[buf][u - WM] = (int)(cb[u - WM].v[t] >> 2);
             };
             constexpr int U = WM + WN, MN = WM * WN;
 #pragma unroll
@@ -518,7 +521,8 @@ onehot_mfma_kernel(Args a)
 #pragma unroll
                 for (int i = 0; i < 2 * MN; ++i) {
                     const int par = i / MN, bm = (i % MN) / WN, bn = i % WN;      // all blocks with the even codes, then the odd
-                    acc[bm][bn] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones[bn], dn[cur][bm][par], acc[bm][bn], ix[cur][bn][par], 0, 0);
+                    acc[bm][bn] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones[bn], dn[cur][bm][par], acc[bm][bn],
+                                                                          par ? odd_ix[cur][bn] : (int)cb[bn].v[t], 0, 0);
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                     if (t + 1 < CH) {
                         // the table reads go first (over the first instructions) so that their latency is covered
@@ -529,7 +533,7 @@ onehot_mfma_kernel(Args a)
                             if (u < WM)
                                 __builtin_amdgcn_sched_group_barrier(0x102, 31, 0);      // 23 VALU and 8 LDS reads
                             else
-                                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+                                __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
                         }
                     }
                 }
@@ -693,14 +697,15 @@ onehot_splitk_kernel(SplitArgs a)
             if (F::SPARSE) wa1 = load_words<CH>(w_ptr + (int64_t)(c + 1 < c1 ? c + 1 : c) * (8 * CH) + 4 * CH);
             fetch_x();
             if constexpr (F::SPARSE) {
-                const int x = valid ? 0x00010001 : 0;
-                const v4i ones = {x, x, x, x};
+                // (kept bytes (1, 0) with the even codes, (0, 1) with the odd; the packed word is the index of both)
+                const int x = valid ? 0x00010001 : 0, y = valid ? 0x01000100 : 0;
+                const v4i ones_even = {x, x, x, x}, ones_odd = {y, y, y, y};
 #pragma unroll
                 for (int word = 0; word < CH; ++word) {
                     v8i even, odd;
                     sparse_dense_rows(s_rows + 16 * ws, ca.v[word], ca1.v[word], sparse_pick(h), even, odd);
-                    acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones, even, acc, (int)(cb.v[word] & 0x33333333u), 0, 0);
-                    acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones, odd, acc, (int)((cb.v[word] >> 2) & 0x33333333u), 0, 0);
+                    acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones_even, even, acc, (int)cb.v[word], 0, 0);
+                    acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones_odd, odd, acc, (int)cb.v[word], 0, 0);
                 }
                 continue;
             }
@@ -874,6 +879,7 @@ DGOH_UNIT_SPLIT(4, 1) DGOH_UNIT_SPLIT(22, 0) DGOH_UNIT_SPLIT(22, 1) DGOH_UNIT_SP
 void unit_sparse4(const DgProblem &, const uint32_t (&)[16][4], int, hipStream_t);      // dg_sparse4_kernel.h
 void unit_sparse2p(const DgProblem &, const uint32_t (&)[2][4], int, hipStream_t);      // dg_sparse2p_kernel.h
 void unit_sparse_ws(const DgProblem &, const uint32_t (&)[4], int, hipStream_t);        // dg_sparse_ws_kernel.h
+void unit_sparse_staged(const DgProblem &, const Pools &, const Plan &, int64_t, hipStream_t);      // dg_sparse_staged_kernel.h
 // the split-K kernel on activations still one code per byte (one- and two-plane tables, either output layout)
 void unit_split_codes(const DgProblem &, const Pools &, const Plan &, bool two, bool tr, int64_t, hipStream_t);
 #undef DGOH_UNIT

@@ -186,10 +186,35 @@ int sparse_tile_hint(const dg_lut *lut, const DgProblem &t)
     return dense.wn > 4 ? 4 : dense.wn;
 }
 
+// The tiled kernel with operands staged through LDS (dg_sparse_staged_kernel.h) takes the unshared tiles of layers
+// whose filter taps are whole 32-byte runs of packed codes.  DG_ONEHOT_STAGED=0 keeps the direct loads (A/B measurement).
+bool staged_takes(const DgProblem &t)
+{
+    if (t.Cin % 128 != 0 || (uintptr_t)t.Wp % 16 != 0 || (uintptr_t)t.Xp % 16 != 0) return false;
+    if (const char *e = dg_override("DG_ONEHOT_STAGED")) return atoi(e) != 0;
+    return true;
+}
+
 Plan sparse_plan(const dg_lut *lut, const DgProblem &t)
 {
-    return plan_for(lut, t, SPARSE, sparse_tile_hint(lut, t));
+    Plan q = plan_for(lut, t, SPARSE, sparse_tile_hint(lut, t));
+    if (!staged_takes(t)) return q;
+    // The staged kernel also has a tile one block high and six wide (32 x 192), whose weight operand serves six pixel
+    // blocks: taken instead of 64 x 128 where the busiest SIMD then has no more blocks to do (measured 2 % faster at
+    // equal work per SIMD, and 15 % where 64 x 128 tiles come to 1.5 per SIMD and these to 2).  DG_ONEHOT_PLAN=16 forces it.
+    const char *force = dg_override("DG_ONEHOT_PLAN");
+    bool wide = force != nullptr && atoi(force) == 16;
+    if (force == nullptr && !q.split && q.skw == 1 && q.wm == 2 && q.wn == 4) {
+        const int64_t simds = dg_simd_count();
+        const int64_t blocks_24 = (tile_count(t, 2, 4) + simds - 1) / simds * 8;
+        const int64_t blocks_16 = (tile_count(t, 1, 6) + simds - 1) / simds * 6;
+        wide = blocks_16 <= blocks_24;
+    }
+    if (wide) q.split = false, q.skw = 1, q.wm = 1, q.wn = 6, q.ch = 2;
+    return q;
 }
+
+bool sparse_staged(const DgProblem &t, const Plan &q) { return staged_takes(t) && !q.split && q.skw == 1; }
 
 }   // namespace
 
@@ -229,8 +254,13 @@ const char *dg_sparse_config_name(const dg_lut *lut, const DgProblem &p)
         {"onehot_smfmac_64x224", "onehot_smfmac_64x128", "onehot_smfmac_64x64", "onehot_smfmac_64x32"},
         {"", "onehot_smfmac_64x128_k2", "onehot_smfmac_64x64_k2", "onehot_smfmac_64x32_k2"},
         {"onehot_smfmac_64x224_k4", "onehot_smfmac_64x128_k4", "onehot_smfmac_64x64_k4", "onehot_smfmac_64x32_k4"}};
-    const Plan q = sparse_plan(lut, sparse_problem(p));
+    const DgProblem t = sparse_problem(p);
+    const Plan q = sparse_plan(lut, t);
     if (q.split) return split_names[q.S];
+    if (sparse_staged(t, q)) {
+        if (q.wm == 1) return "onehot_smfmac_staged_32x192";
+        return q.wn == 4 ? "onehot_smfmac_staged_64x128" : (q.wn == 2 ? "onehot_smfmac_staged_64x64" : "onehot_smfmac_staged_64x32");
+    }
     return tile_names[q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)][q.wn == 7 ? 0 : (q.wn == 4 ? 1 : (q.wn == 2 ? 2 : 3))];
 }
 
@@ -254,6 +284,10 @@ dg_status dg_launch_sparse(const dg_lut *lut, const DgProblem &p0, hipStream_t s
     if (q.split) {
         unit_split_b20_t1(p, pools, q, blocks11, stream);
         return dg_check_launch("onehot_splitk_kernel<20>");
+    }
+    if (sparse_staged(p, q)) {
+        unit_sparse_staged(p, pools, q, wave_tiles, stream);
+        return dg_check_launch("smfmac_staged_kernel");
     }
     static const MainFn main_units[3] = {unit_main_b20_t1_k1, unit_main_b20_t1_k2, unit_main_b20_t1_k4};
     main_units[q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)](p, pools, q, wave_tiles, stream);

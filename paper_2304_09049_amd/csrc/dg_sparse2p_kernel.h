@@ -89,13 +89,15 @@ sparse2p_kernel(Sparse2pArgs a)
     fetch(0);
     for (int c = 0; c < chunks; ++c) {
         Words<CH> ca[2], cb[WN];
-        v4i ones[WN];
+        v4i ones[WN][2];
         ca[0] = wa[0], ca[1] = wa[1];
 #pragma unroll
         for (int bn = 0; bn < WN; ++bn) {
             cb[bn] = wb[bn];
-            const int x = vb[bn] ? 0x00010001 : 0;            // the kept bytes: (1, 0) per position; zeros outside the image
-            ones[bn] = (v4i){x, x, x, x};
+            // the kept bytes: (1, 0) per position with the even codes, (0, 1) with the odd; zeros outside the image
+            const int x = vb[bn] ? 0x00010001 : 0, y = vb[bn] ? 0x01000100 : 0;
+            ones[bn][0] = (v4i){x, x, x, x};
+            ones[bn][1] = (v4i){y, y, y, y};
         }
         fetch(c + 1);                                        // unconditional (the last one re-reads in bounds and is unused)
 #pragma unroll
@@ -107,10 +109,10 @@ sparse2p_kernel(Sparse2pArgs a)
             for (int par = 0; par < 2; ++par)
 #pragma unroll
                 for (int bn = 0; bn < WN; ++bn) {
-                    const int idx = (int)((cb[bn].v[t] >> (2 * par)) & 0x33333333u);
+                    const int idx = (int)cb[bn].v[t];      // as packed: the byte that is 1 picks by its own code
 #pragma unroll
                     for (int pl = 0; pl < 2; ++pl)
-                        acc[pl][bn] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones[bn], dn[pl][par], acc[pl][bn], idx, 0, 0);
+                        acc[pl][bn] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones[bn][par], dn[pl][par], acc[pl][bn], idx, 0, 0);
                 }
         }
     }

@@ -1,0 +1,235 @@
+// 2-bit table kernel on the sparse matrix instruction, tiles as in dg_onehot_kernel.h (BITS = 20, one wavefront per
+// tile, all of K), with the packed operands fetched in WHOLE 32-BYTE RUNS and handed to their lanes through LDS.
+//
+// Why: the matrix instruction wants lane (r, half) to hold words of row r, so a direct load has 32 lanes reading 8
+// bytes each from 32 different rows.  The address unit of a compute unit takes such a load one lane (one cache line)
+// per cycle: 64 cycles for 512 or 1024 bytes, and on a GEMM with K = 8192 it was busy 93 % of the kernel's time
+// (counters TA_TA_BUSY / TCP_GATE_EN) while the matrix pipe idled -- the loads, not the arithmetic, set the time.
+// Here two neighbouring lanes read the two 16-byte halves of one row's run, so a load instruction covers 32 rows x 32
+// bytes -- four times the bytes per address cycle, with a quarter of the cache-line requests.  The loads write LDS
+// directly (global_load_lds_dwordx4: lane l's 16 bytes land at the instruction's LDS base + 16 l; no registers are
+// held while they are in flight), into staging rows of the wavefront's own, from which lane (r, half) reads its 8
+// bytes per 64 positions of K.  Staging rows belong to one wavefront, so no barrier is involved: a wavefront waits
+// for its own loads (vmcnt) before it reads a run, and runs alternate between two buffers, fetched two ahead.
+// The multiplication is one software pipeline over all of K: the dense operands of a step are made between the matrix
+// instructions of the step before, across chunks, runs and filter taps alike.
+//
+// A run is 128 positions of K inside one filter tap (Cin % 128 == 0).  A tap outside the image is fetched from a
+// clamped address and contributes nothing because the kept bytes of its lanes are zero.
+#pragma once
+
+#include "dg_onehot_kernel.h"
+
+namespace dgoh {
+
+// 16 bytes per lane from global memory straight into LDS: lane l's land at byte `lds` + 16 l (`lds`: a wavefront-uniform
+// LDS byte address, handed over in M0; one wait state between writing M0 and the load).  Written as assembly because
+// the compiler, which cannot tell the staging buffers apart, would wait for every such load before the next LDS read
+// of any kind; here the wavefront counts its own loads (s_waitcnt vmcnt), and the "memory" clobbers keep the
+// compiler's LDS reads on their side of the loads and the waits.
+__device__ __forceinline__ void load16_to_lds(const uint8_t *base, int32_t offset, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(offset), "s"(base), "s"(lds) : "memory", "m0");
+}
+__device__ __forceinline__ void load16_to_lds(const uint8_t *address, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(address), "s"(lds) : "memory", "m0");
+}
+__device__ __forceinline__ void wait_for_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+template <int WM, int WN>
+__global__ void __launch_bounds__(256, 2)
+smfmac_staged_kernel(Args a)
+{
+    constexpr int ROWS = (WM + WN) * 32;                    // staged rows of a wavefront: its weight rows, then its pixels
+    constexpr int BUF = ROWS * 32;                          // bytes of one wavefront's buffer
+    // A block of 32 rows is 64 slots of 16 bytes, slot j = what loader lane j fetched: row j / 2, segment
+    // (j % 2) ^ (j / 16 % 2) of the row's 32 bytes -- the exchange puts rows r and r + 8 of a segment on different
+    // LDS banks, which leaves the consumers' reads (32 rows of one segment) two to a bank instead of four.
+    __shared__ uint2 s_rows[16];                            // the table of row pairs, one for the workgroup
+    __shared__ uint4 s_stage[4][2][ROWS * 2];               // [wavefront][buffer][block * 64 + slot]
+    // the narrower tiles have the registers for a second set of kept bytes, (0, 1), which spares the odd codes' shift
+    constexpr bool SHIFT_ODD = WM * WN >= 8;
+    const DgProblem &p = a.p;
+    const int lane = threadIdx.x & 63, w4 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t my_tile = (int64_t)xcd_contiguous(blockIdx.x, gridDim.x) * 4 + w4;
+    sparse_fill_table(s_rows, a.pools, threadIdx.x);
+    __syncthreads();                                       // (every wavefront of the workgroup, also one without a tile)
+    if (my_tile >= a.wave_tiles) return;                    // whole wavefronts leave; no barrier follows
+    const int r = lane & 31, h = lane >> 5;
+    const int m0 = (int)(my_tile % a.tiles_m) * (WM * 32);
+    const int n0 = (int)(my_tile / a.tiles_m) * (WN * 32);
+    const int cq = p.Cin / 4;                               // packed bytes per pixel
+
+    // as a loader, this lane fetches 16-byte segment lseg of row lrow of every 32-row block
+    const int lrow = lane >> 1, lseg = (lane & 1) ^ ((lane >> 4) & 1);
+    const uint8_t *w_ld[WM];
+#pragma unroll
+    for (int bm = 0; bm < WM; ++bm)
+        w_ld[bm] = p.Wp + (int64_t)min(m0 + bm * 32 + lrow, p.M - 1) * (p.K / 4) + lseg * 16;
+    int32_t x_ld[WN];                                       // (32-bit offsets: the host sends inputs below 2^31 bytes)
+#pragma unroll
+    for (int bn = 0; bn < WN; ++bn)
+        x_ld[bn] = (int32_t)make_column(p, a.div_ow, a.div_oh, n0 + bn * 32 + lrow, cq, lseg * 16).off0;
+    const int images = (int)fdiv(fdiv((uint32_t)p.N, a.div_ow), a.div_oh);
+    const int32_t x_last = images * p.H * p.W * cq - 16;    // the last 16 bytes of the packed activations
+    // as a consumer, it is row / pixel r (lane half h) of every block: its slot of segment s is slot0 ^ s
+    const int slot0 = 2 * r + ((r >> 3) & 1);
+    Column col[WN];
+#pragma unroll
+    for (int bn = 0; bn < WN; ++bn) col[bn] = make_column(p, a.div_ow, a.div_oh, n0 + bn * 32 + r, cq, 0);
+
+    v16i acc[WM][WN];
+#pragma unroll
+    for (int bm = 0; bm < WM; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < WN; ++bn)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[bm][bn][e] = 0;
+    float sc_cols[WM];
+    dg_mfma_column_scales<WM, true>(p, m0, lane, sc_cols);
+
+    // ---- the loader's side: runs are fetched two ahead of the one being multiplied
+    const char *stage = (const char *)s_stage[w4];
+    // (the numeric value of a pointer into LDS is its LDS byte address)
+    const uint32_t stage_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)s_stage[w4];
+    const int runs = p.K / 128;
+    int kh = 0, kw = 0, cib = 0, fetched = 0;               // filter tap and byte within the pixel of the run fetched next
+    auto fetch = [&]() {                                    // the next run, into the buffer of its parity
+        const int g = min(fetched, runs - 1);               // (past the end: a run inside the tensors, unused)
+        const uint32_t dst = stage_lds + (fetched & 1) * BUF;
+#pragma unroll
+        for (int bm = 0; bm < WM; ++bm) load16_to_lds(w_ld[bm] + g * 32, dst + bm * 1024);
+        const int32_t tap_off = (kh * p.W + kw) * cq + cib;
+#pragma unroll
+        for (int bn = 0; bn < WN; ++bn) {
+            // (a tap outside the image or past the end: any address inside the tensor will do; the kept bytes of a
+            // lane outside the image are zero)
+            const int32_t off = max(0, min(x_ld[bn] + tap_off, x_last));
+            load16_to_lds(p.Xp, off, dst + (WM + bn) * 1024);
+        }
+        ++fetched;
+        cib += 32;
+        if (cib == cq) {                                    // (uniform)
+            cib = 0;
+            if (++kw == p.KW) {
+                kw = 0;
+                ++kh;
+            }
+        }
+    };
+
+    // ---- the consumer's side.  Words of a chunk (64 positions): of weight row r both halves' 8 bytes, of pixel r its
+    // own half's.  Lane offsets into a buffer, for the run's two chunks:
+    const int w_at[2] = {slot0 * 16, (slot0 ^ 1) * 16}, x_at[2] = {slot0 * 16 + h * 8, (slot0 ^ 1) * 16 + h * 8};
+    struct Words2 {
+        uint2 ca[WM], ca1[WM], cb[WN];
+    };
+    auto read_words = [&](Words2 &w, int buf, int s) {
+        const char *src = stage + buf * BUF;
+#pragma unroll
+        for (int bm = 0; bm < WM; ++bm) {
+            const uint4 q = *(const uint4 *)(src + bm * 1024 + w_at[s]);
+            w.ca[bm] = make_uint2(q.x, q.y), w.ca1[bm] = make_uint2(q.z, q.w);
+        }
+#pragma unroll
+        for (int bn = 0; bn < WN; ++bn) w.cb[bn] = *(const uint2 *)(src + (WM + bn) * 1024 + x_at[s]);
+    };
+    const uint32_t pick = sparse_pick(h);
+    auto word = [](const uint2 &v, int t) { return t ? v.y : v.x; };
+    // One step = one word of the chunk: two instructions (even codes, odd codes) per block of the tile, with the dense
+    // operands `next` of the following step -- per weight block a unit of table reads -- made between them.
+    // (see dg_onehot_kernel.h for the index register and the kept bytes)
+    v4i ones[WN], ones_odd[SHIFT_ODD ? 1 : WN];
+    auto step = [&](const v8i (&dn)[WM][2], const Words2 &w, int t, v8i (&next)[WM][2], const Words2 &nw, int nt) {
+        constexpr int MN = WM * WN;
+        int odd_ix[SHIFT_ODD ? WN : 1];
+        if constexpr (SHIFT_ODD) {
+#pragma unroll
+            for (int bn = 0; bn < WN; ++bn) odd_ix[bn] = (int)(word(w.cb[bn], t) >> 2);
+        }
+#pragma unroll
+        for (int i = 0; i < 2 * MN; ++i) {
+            const int par = i / MN, bm = (i % MN) / WN, bn = i % WN;
+            if (par && !SHIFT_ODD)
+                acc[bm][bn] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones_odd[SHIFT_ODD ? 0 : bn], dn[bm][1], acc[bm][bn], (int)word(w.cb[bn], t), 0, 0);
+            else
+                acc[bm][bn] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones[bn], dn[bm][par], acc[bm][bn],
+                                                                      par ? odd_ix[SHIFT_ODD ? bn : 0] : (int)word(w.cb[bn], t), 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            const int u0 = i * WM / MN, u1 = (i + 1) * WM / MN;      // the weight blocks' units go over the first instructions
+#pragma unroll
+            for (int u = u0; u < u1 && u < WM; ++u) {
+                sparse_dense_rows_shared(s_rows, word(nw.ca[u], nt), word(nw.ca1[u], nt), pick, next[u][0], next[u][1]);
+                __builtin_amdgcn_sched_group_barrier(0x102, 31, 0);              // 23 VALU and 8 LDS reads
+            }
+        }
+    };
+
+    fetch();
+    fetch();
+    Words2 wa, wb;
+    v8i dn0[WM][2], dn1[WM][2];
+    wait_for_loads();                                       // (both runs: the first is needed now)
+    read_words(wa, 0, 0);
+#pragma unroll
+    for (int u = 0; u < WM; ++u) sparse_dense_rows_shared(s_rows, wa.ca[u].x, wa.ca1[u].x, pick, dn0[u][0], dn0[u][1]);
+    const int runs_per_tap = cq / 32;
+    int g = 0;
+    for (int khc = 0; khc < p.KH; ++khc)
+        for (int kwc = 0; kwc < p.KW; ++kwc) {
+            // which of this lane's pixels see the tap: the kept bytes, (1, 0) per position (and (0, 1) for the odd
+            // codes), or zeros outside the image
+#pragma unroll
+            for (int bn = 0; bn < WN; ++bn) {
+                const int ih = col[bn].ih0 + khc, iw = col[bn].iw0 + kwc;
+                const bool v = col[bn].ok & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
+                const int x = v ? 0x00010001 : 0;
+                ones[bn] = (v4i){x, x, x, x};
+                if constexpr (!SHIFT_ODD) {
+                    const int y = v ? 0x01000100 : 0;
+                    ones_odd[bn] = (v4i){y, y, y, y};
+                }
+            }
+            for (int rt = 0; rt < runs_per_tap; ++rt, ++g) {
+                // run g, in buffer g & 1: wa holds its first chunk's words, dn0 the dense operands of that chunk's word 0
+                step(dn0, wa, 0, dn1, wa, 1);
+                read_words(wb, g & 1, 1);
+                step(dn1, wa, 1, dn0, wb, 0);
+                step(dn0, wb, 0, dn1, wb, 1);
+                // every read of run g has been issued: its buffer takes run g + 2, once run g + 1 is known to be in
+                // (one counter serves all loads, and they complete in order)
+                wait_for_loads();
+                fetch();
+                read_words(wa, (g + 1) & 1, 0);
+                step(dn1, wb, 1, dn0, wa, 0);
+            }
+        }
+    wait_for_loads();                                       // (unused fetches past the end: their LDS writes end before the wavefront does)
+    dg_mfma_store_tile<WM, WN, true>(p, acc, m0, n0, lane, sc_cols);
+}
+
+// `wave_tiles` tiles of q.wm x q.wn blocks
+inline void launch_sparse_staged(const DgProblem &p, const Pools &pools, const Plan &q, int64_t wave_tiles, hipStream_t stream)
+{
+    Args a;
+    a.p = p;
+    a.pools = pools;
+    a.tiles_m = (p.M + q.wm * 32 - 1) / (q.wm * 32);
+    a.wave_tiles = wave_tiles;
+    a.div_ow = make_div((uint32_t)p.OW), a.div_oh = make_div((uint32_t)p.OH);
+    a.div_cin = make_div((uint32_t)p.Cin), a.div_kw = make_div((uint32_t)p.KW);
+    const dim3 grid((unsigned)((wave_tiles + 3) / 4));
+    if (q.wm == 1 && q.wn == 6)
+        hipLaunchKernelGGL((smfmac_staged_kernel<1, 6>), grid, dim3(256), 0, stream, a);
+    else if (q.wn == 4)
+        hipLaunchKernelGGL((smfmac_staged_kernel<2, 4>), grid, dim3(256), 0, stream, a);
+    else if (q.wn == 2)
+        hipLaunchKernelGGL((smfmac_staged_kernel<2, 2>), grid, dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL((smfmac_staged_kernel<2, 1>), grid, dim3(256), 0, stream, a);
+}
+
+}   // namespace dgoh

@@ -5,10 +5,10 @@
 // the table rows of its weight codes, 4 bytes per (row, position) -- for every tile it owns: about 23 VALU instructions
 // and 8 LDS reads per pair of matrix instructions.  With K <= 256 the dense operand of 32 weight rows over ALL of K is
 // at most 128 registers per lane, so here a wavefront builds it once, keeps it, and then only streams pixels: per 32
-// pixels it loads their packed words (the index registers of the instruction, masked: no expansion), issues K / 16
+// pixels it loads their packed words (the index registers of the instruction as they are: no expansion), issues K / 16
 // matrix instructions and stores the 32 x 32 sums.  Stores of one block overlap the loads and matrix instructions of the
-// next (a store reads its registers when it issues, nothing waits for it), and nothing but two masks per instruction is
-// left on the VALU.  Operand layout and the row-pair table in LDS are those of dg_onehot_kernel.h.
+// next (a store reads its registers when it issues, nothing waits for it), and nothing of the contraction is left on
+// the VALU.  Operand layout and the row-pair table in LDS are those of dg_onehot_kernel.h.
 //
 // Work split: a wavefront owns one block of 32 output channels (its stationary weights) and a contiguous run of
 // 32-pixel blocks; the wavefronts of the other channel blocks of the same pixels sit next to it in the workgroup, so
@@ -92,7 +92,8 @@ smfmac_ws_kernel(WsArgs a)
     }
     float sc_cols[1];
     dg_mfma_column_scales<1, true>(p, m0, lane, sc_cols);
-    const v4i ones = {0x00010001, 0x00010001, 0x00010001, 0x00010001};      // the kept bytes: (1, 0) per position
+    // the kept bytes: (1, 0) per position with the even codes, (0, 1) with the odd; the index of both is the packed word
+    const v4i ones[2] = {{0x00010001, 0x00010001, 0x00010001, 0x00010001}, {0x01000100, 0x01000100, 0x01000100, 0x01000100}};
 
     for (int64_t blk = b0; blk < b1; blk += G) {
         // one block at a time, so that the first stores go out as early as possible: the layer's time is the time its
@@ -108,8 +109,7 @@ smfmac_ws_kernel(WsArgs a)
             for (int t = 0; t < T; ++t)
 #pragma unroll
                 for (int par = 0; par < 2; ++par)
-                    acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones, dn[t][par], acc,
-                                                                  (int)((x[g].v[t] >> (2 * par)) & 0x33333333u), 0, 0);
+                    acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones[par], dn[t][par], acc, (int)x[g].v[t], 0, 0);
             dg_mfma_store_block<true>(p, acc, m0, (int)((blk + g) * 32), lane, sc_cols[0]);
         }
         // (only a run longer than one group comes here; these loads do queue behind the group's stores, which is why

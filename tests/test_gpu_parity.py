@@ -162,17 +162,20 @@ def test_onehot_every_plan(plan, table, monkeypatch):
     def chunk_codes(c):                  # codes a wavefront takes at a time: 4, 2 or 1 words per lane half (sparse, where a
         return 128 if c % 128 == 0 and table != "sparse" else (64 if c % 64 == 0 else 32)     # K share matters: 2 or 1)
 
-    def right_kernel(name, chunks):
+    def right_kernel(name, chunks, channels):
         if plan == "split":
             return name.startswith(prefix)
+        want = prefix
         if "k" in plan and chunks < int(plan.split("k")[1]):
-            return name == prefix.rsplit("_k", 1)[0]        # fewer chunks than sharers: the unshared kernel
-        return name == prefix
+            want = prefix.rsplit("_k", 1)[0]                # fewer chunks than sharers: the unshared kernel
+        if table == "sparse" and "_k" not in want and channels % 128 == 0:
+            want = want.replace("onehot_smfmac_", "onehot_smfmac_staged_")      # whole 32-byte runs per tap: through LDS
+        return name == want
 
     for (M, N, K) in [(70, 1000, 96), (130, 777, 64), (64, 300, 256), (33, 250, 1024)]:
         inp = wl.small_gemm(M, N, K, seed=M + N + K)
         case = GpuCase(inp, levels=(glw, gla), entry=gentry)
-        assert right_kernel(case.kernel_name(kernel), K // chunk_codes(K))
+        assert right_kernel(case.kernel_name(kernel), K // chunk_codes(K), K)
         want = oracle.gemm(inp.Wc, inp.Ac, glw, gla)
         _assert_same(case.run(kernel).cpu().numpy(), want, f"gemm {(M, N, K)} plan {plan}")
         out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
@@ -187,7 +190,7 @@ def test_onehot_every_plan(plan, table, monkeypatch):
                                                       (1, 20, 20, 64, 96, 5, 5, (1, 1), (2, 2))]:
         c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
         case = GpuCase(c, levels=(lw, la), entry=entry)
-        assert right_kernel(case.kernel_name(kernel), KH * KW * Cin // chunk_codes(Cin))
+        assert right_kernel(case.kernel_name(kernel), KH * KW * Cin // chunk_codes(Cin), Cin)
         acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
         _assert_same(case.run(kernel).cpu().numpy(), acc, f"conv {(B, H, W, Cin, Cout)} plan {plan}")
         got = case.run(kernel, scale=True).cpu().numpy()
@@ -906,6 +909,49 @@ def test_stationary_weight_kernel(K, waves, monkeypatch):
     # a filter window, a stride or another K is not its case: the tiled sparse-instruction kernel takes over
     c = wl.small_conv(1, 8, 8, 64, 32, 3, 3, (1, 1), (1, 1), seed=1)
     assert GpuCase(c, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac") != "onehot_smfmac_ws_32xK"
+
+
+@pytest.mark.parametrize("plan,name", [("1", "onehot_smfmac_staged_64x32"), ("2", "onehot_smfmac_staged_64x64"),
+                                       ("4", "onehot_smfmac_staged_64x128"), ("16", "onehot_smfmac_staged_32x192")])
+def test_staged_sparse_kernel(plan, name, monkeypatch):
+    """The tiled sparse-instruction kernel whose operands go through LDS in 32-byte runs (Cin % 128 == 0), every tile
+    shape forced: convolutions with a padded 3x3 window (taps outside the image at every border), a stride, one, two and
+    three runs per tap, a single run in all (K = 128), ragged M and N (tiles partly outside, fewer columns than a tile),
+    scaled fp32 and re-quantised packed output; GEMMs in both output layouts (the row-major one runs transposed)."""
+    monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
+    lw, la, entry = LEVELS["nonuniform_i8"]
+    convs = [(2, 9, 7, 128, 36, 3, 3, (1, 1), (1, 1)), (1, 13, 11, 256, 70, 3, 3, (2, 2), (1, 1)),
+             (3, 6, 5, 384, 64, 1, 1, (1, 1), (0, 0)), (1, 5, 4, 128, 33, 1, 1, (1, 1), (0, 0)),
+             (1, 20, 17, 128, 130, 3, 2, (1, 2), (1, 0)), (2, 15, 15, 256, 100, 5, 5, (1, 1), (2, 2))]
+    for (B, H, W, Cin, Cout, KH, KW, stride, pad) in convs:
+        c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        assert case.kernel_name("onehot_smfmac") == name
+        acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
+        _assert_same(case.run("onehot_smfmac").cpu().numpy(), acc, f"staged conv {(B, H, W, Cin, Cout, KH, KW, stride, pad)}")
+        y = oracle.scale_epilogue_nhwc(acc, c.scale)
+        got = case.run("onehot_smfmac", scale=True).cpu().numpy()
+        assert np.array_equal(got, y)
+        if Cout % 4 == 0:
+            qs = np.float32(3.0 / max(1e-6, float(np.percentile(np.abs(y), 90))))
+            codes = oracle.quantize_codes(y, float(qs), 0.5, 0, 3)
+            q = dg.dg_conv2d_lut_requant(case.lut, case.Wp, case.Ap, case.desc, case.scale, float(qs), 0.5, 0, variant="onehot_smfmac")
+            torch.cuda.synchronize()
+            _assert_same(q.cpu().numpy().reshape(-1, Cout // 4), oracle.pack_codes(codes.reshape(-1, Cout)),
+                         f"staged fused layer {(B, H, W, Cin, Cout)}")
+    for (M, N, K) in [(70, 1000, 128), (64, 333, 512), (200, 64, 1280), (33, 5, 256)]:
+        inp = wl.small_gemm(M, N, K, seed=M + N + K)
+        case = GpuCase(inp, levels=(lw, la), entry=entry)
+        assert case.kernel_name("onehot_smfmac") == name
+        want = oracle.gemm(inp.Wc, inp.Ac, lw, la)
+        _assert_same(case.run("onehot_smfmac").cpu().numpy(), want, f"staged gemm {(M, N, K)} row-major")
+        out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
+        dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant="onehot_smfmac", strides=(1, M))
+        torch.cuda.synchronize()
+        _assert_same(out.cpu().numpy(), want.T.copy(), f"staged gemm {(M, N, K)} column-major")
+    # channels that are not whole 32-byte runs: the direct-load kernel of the same tile
+    c = wl.small_conv(1, 8, 8, 64, 32, 3, 3, (1, 1), (1, 1), seed=1)
+    assert "staged" not in GpuCase(c, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac")
 
 
 @pytest.mark.parametrize("waves", [0, 1, 3, 16])
