@@ -71,6 +71,7 @@ struct Args {
     FastDiv div_ow, div_oh, div_cin, div_kw;
     int32_t tiles_m;
     int64_t wave_tiles;
+    FastDiv div_runs;        // (dg_sparse_staged_kernel.h) by the 32-byte runs of packed codes per filter tap
 };
 
 struct SplitArgs {
@@ -774,6 +775,7 @@ struct Plan {
     int wn;
     int skw;         // large-layer kernel: wavefronts sharing a tile (1, 2 or 4)
     int S, cpw, chunks;
+    bool staged;     // sparse instruction: the kernel that stages its operands through LDS (dg_sparse_staged_kernel.h)
 };
 
 // dynamic LDS of the large-layer kernel: the shared tiles' sums

@@ -41,6 +41,7 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
 {
     const bool decode = mode == DECODE;
     Plan q;
+    q.staged = false;
     q.decode = decode;
     q.two = mode == TABLE && !fits_int8(lut);              // two int8 planes; a tile is then 32 rows high, not 64
     const int wm = q.two ? 1 : 2;
@@ -195,26 +196,39 @@ bool staged_takes(const DgProblem &t)
     return true;
 }
 
+// The staged kernel's tiles are one block of 32 channels high -- the weight operand of a block, the expensive one,
+// then serves every pixel block of the tile -- and 64, 128 or 192 pixels wide; at equal area they were measured 3 - 20 %
+// faster than the 64-row tiles on every layer tried, so a plan made for the 64-row tiles is run on the tile of the
+// same area (64 x 32 -> 32 x 64, 64 x 64 -> 32 x 128, with the same sharing of K).  Instead of 64 x 128 there is
+// 32 x 192, taken where the busiest SIMD then has no more blocks to do (2 % faster at equal work per SIMD, 15 % where
+// 64 x 128 tiles come to 1.5 per SIMD and these to 2); otherwise 64 x 128 itself runs staged.
+// DG_ONEHOT_PLAN = 12 | 14 [k2 | k4] | 16 | 24 forces a staged tile (32 x 64, 32 x 128, 32 x 192, 64 x 128); the other
+// values of that override force the direct-load kernels.
 Plan sparse_plan(const dg_lut *lut, const DgProblem &t)
 {
     Plan q = plan_for(lut, t, SPARSE, sparse_tile_hint(lut, t));
+    q.staged = false;
     if (!staged_takes(t)) return q;
-    // The staged kernel also has a tile one block high and six wide (32 x 192), whose weight operand serves six pixel
-    // blocks: taken instead of 64 x 128 where the busiest SIMD then has no more blocks to do (measured 2 % faster at
-    // equal work per SIMD, and 15 % where 64 x 128 tiles come to 1.5 per SIMD and these to 2).  DG_ONEHOT_PLAN=16 forces it.
-    const char *force = dg_override("DG_ONEHOT_PLAN");
-    bool wide = force != nullptr && atoi(force) == 16;
-    if (force == nullptr && !q.split && q.skw == 1 && q.wm == 2 && q.wn == 4) {
+    if (const char *force = dg_override("DG_ONEHOT_PLAN")) {
+        const int v = atoi(force), k = strstr(force, "k4") ? 4 : (strstr(force, "k2") ? 2 : 1);
+        if (v == 12 || v == 14) q.staged = true, q.split = false, q.wm = 1, q.wn = v == 12 ? 2 : 4, q.skw = k, q.ch = 2;
+        if (v == 16 || v == 24) q.staged = true, q.split = false, q.wm = v == 16 ? 1 : 2, q.wn = v == 16 ? 6 : 4, q.skw = 1, q.ch = 2;
+        return q;
+    }
+    if (q.split || q.wm != 2) return q;
+    if (q.wn <= 2) {
+        q.staged = true, q.wm = 1, q.wn *= 2, q.ch = 2;
+    } else if (q.wn == 4 && q.skw == 1) {
         const int64_t simds = dg_simd_count();
         const int64_t blocks_24 = (tile_count(t, 2, 4) + simds - 1) / simds * 8;
         const int64_t blocks_16 = (tile_count(t, 1, 6) + simds - 1) / simds * 6;
-        wide = blocks_16 <= blocks_24;
+        q.staged = true, q.ch = 2;
+        if (blocks_16 <= blocks_24) q.wm = 1, q.wn = 6;
     }
-    if (wide) q.split = false, q.skw = 1, q.wm = 1, q.wn = 6, q.ch = 2;
     return q;
 }
 
-bool sparse_staged(const DgProblem &t, const Plan &q) { return staged_takes(t) && !q.split && q.skw == 1; }
+bool sparse_staged(const DgProblem &, const Plan &q) { return q.staged; }
 
 }   // namespace
 
@@ -223,6 +237,9 @@ bool dg_sparse_preferred(const dg_lut *lut, const DgProblem &p)
     if (!dg_sparse_supports(lut, p) || dg_override("DG_ONEHOT_PLAN") != nullptr) return false;
     const DgProblem t = sparse_problem(p);
     if (sparse_tile_hint(lut, t) > 0) return true;
+    // the staged kernel, where the layer is its case and large enough for tiles, was faster than the dense
+    // instruction's kernels on all 9 such layers measured (by 7 - 25 %)
+    if (sparse_plan(lut, t).staged) return true;
     // Also where the dense-instruction planner shares tiles at least 64 columns wide and there are 384 of them or more:
     // the sparse kernel in the shape its own planner picks was 1 - 15 % faster on all 9 such layers measured (it lost
     // on shared 64 x 32 tiles, on 200 shared 64 x 64 tiles, and with one-word chunks, Cin % 64 != 0).
@@ -257,9 +274,14 @@ const char *dg_sparse_config_name(const dg_lut *lut, const DgProblem &p)
     const DgProblem t = sparse_problem(p);
     const Plan q = sparse_plan(lut, t);
     if (q.split) return split_names[q.S];
-    if (sparse_staged(t, q)) {
-        if (q.wm == 1) return "onehot_smfmac_staged_32x192";
-        return q.wn == 4 ? "onehot_smfmac_staged_64x128" : (q.wn == 2 ? "onehot_smfmac_staged_64x64" : "onehot_smfmac_staged_64x32");
+    if (q.staged) {
+        static const char *const staged_names[3][2] = {
+            {"onehot_smfmac_staged_32x64", "onehot_smfmac_staged_32x128"},
+            {"onehot_smfmac_staged_32x64_k2", "onehot_smfmac_staged_32x128_k2"},
+            {"onehot_smfmac_staged_32x64_k4", "onehot_smfmac_staged_32x128_k4"}};
+        if (q.wm == 2) return "onehot_smfmac_staged_64x128";
+        if (q.wn == 6) return "onehot_smfmac_staged_32x192";
+        return staged_names[q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)][q.wn == 4 ? 1 : 0];
     }
     return tile_names[q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)][q.wn == 7 ? 0 : (q.wn == 4 ? 1 : (q.wn == 2 ? 2 : 3))];
 }

@@ -39,29 +39,47 @@ __device__ __forceinline__ void load16_to_lds(const uint8_t *address, uint32_t l
 }
 __device__ __forceinline__ void wait_for_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-template <int WM, int WN>
+// SKW = 1: a wavefront walks all of K.  SKW = 2 or 4 (layers whose tiles alone would leave SIMDs idle): SKW wavefronts
+// of the workgroup share a tile and split K between them in contiguous runs; their sums meet in LDS by integer atomics
+// (exact in any order) and each of them stores a share of the tile's blocks, as in dg_onehot_kernel.h.
+template <int WM, int WN, int SKW>
 __global__ void __launch_bounds__(256, 2)
 smfmac_staged_kernel(Args a)
 {
     constexpr int ROWS = (WM + WN) * 32;                    // staged rows of a wavefront: its weight rows, then its pixels
     constexpr int BUF = ROWS * 32;                          // bytes of one wavefront's buffer
+    constexpr int TPW = 4 / SKW;                           // tiles per workgroup
+    constexpr int NB = WM * WN;                            // 32x32 output blocks per tile
     // A block of 32 rows is 64 slots of 16 bytes, slot j = what loader lane j fetched: row j / 2, segment
     // (j % 2) ^ (j / 16 % 2) of the row's 32 bytes -- the exchange puts rows r and r + 8 of a segment on different
     // LDS banks, which leaves the consumers' reads (32 rows of one segment) two to a bank instead of four.
     __shared__ uint2 s_rows[16];                            // the table of row pairs, one for the workgroup
-    __shared__ uint4 s_stage[4][2][ROWS * 2];               // [wavefront][buffer][block * 64 + slot]
+    // staging rows [wavefront][buffer][block * 64 + slot]; once the walk over K is over, the same memory holds the
+    // shared tiles' sums [tile][block][sum register][lane]
+    constexpr int STAGE_BYTES = 4 * 2 * BUF, SUM_BYTES = SKW > 1 ? TPW * NB * 4096 : 0;
+    __shared__ uint4 s_mem[(STAGE_BYTES > SUM_BYTES ? STAGE_BYTES : SUM_BYTES) / 16];
+    static_assert(sizeof(s_mem) <= 64 * 1024 - 256, "two workgroups per compute unit");
+    int32_t *s_acc = (int32_t *)s_mem;
     // the narrower tiles have the registers for a second set of kept bytes, (0, 1), which spares the odd codes' shift
     constexpr bool SHIFT_ODD = WM * WN >= 8;
     const DgProblem &p = a.p;
     const int lane = threadIdx.x & 63, w4 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t my_tile = (int64_t)xcd_contiguous(blockIdx.x, gridDim.x) * 4 + w4;
+    const int ks = w4 % SKW, tw = w4 / SKW;                 // this wavefront's share of K, and its tile within the workgroup
+    const int64_t my_tile = (int64_t)xcd_contiguous(blockIdx.x, gridDim.x) * TPW + tw;
+    const bool active = my_tile < a.wave_tiles;
     sparse_fill_table(s_rows, a.pools, threadIdx.x);
     __syncthreads();                                       // (every wavefront of the workgroup, also one without a tile)
-    if (my_tile >= a.wave_tiles) return;                    // whole wavefronts leave; no barrier follows
+    if (SKW == 1 && !active) return;                       // whole wavefronts leave; no barrier follows on this path
+    const int64_t wave_tile = active ? my_tile : 0;        // (an idle wavefront of a shared workgroup adds nothing)
     const int r = lane & 31, h = lane >> 5;
-    const int m0 = (int)(my_tile % a.tiles_m) * (WM * 32);
-    const int n0 = (int)(my_tile / a.tiles_m) * (WN * 32);
+    const int m0 = (int)(wave_tile % a.tiles_m) * (WM * 32);
+    const int n0 = (int)(wave_tile / a.tiles_m) * (WN * 32);
     const int cq = p.Cin / 4;                               // packed bytes per pixel
+    // this wavefront's runs of K: [g0, g1)
+    const int runs = p.K / 128, share = (runs + SKW - 1) / SKW;
+    const int g0 = min(ks * share, runs), g1 = active ? min(g0 + share, runs) : g0;
+    const int runs_per_tap = cq / 32;
+    const int tap0 = (int)fdiv((uint32_t)g0, a.div_runs), rt0 = g0 - tap0 * runs_per_tap;
 
     // as a loader, this lane fetches 16-byte segment lseg of row lrow of every 32-row block
     const int lrow = lane >> 1, lseg = (lane & 1) ^ ((lane >> 4) & 1);
@@ -92,11 +110,11 @@ smfmac_staged_kernel(Args a)
     dg_mfma_column_scales<WM, true>(p, m0, lane, sc_cols);
 
     // ---- the loader's side: runs are fetched two ahead of the one being multiplied
-    const char *stage = (const char *)s_stage[w4];
+    const char *stage = (const char *)s_mem + w4 * (2 * BUF);
     // (the numeric value of a pointer into LDS is its LDS byte address)
-    const uint32_t stage_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)s_stage[w4];
-    const int runs = p.K / 128;
-    int kh = 0, kw = 0, cib = 0, fetched = 0;               // filter tap and byte within the pixel of the run fetched next
+    const uint32_t stage_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)s_mem + w4 * (2 * BUF);
+    // filter tap and byte within the pixel of the run fetched next
+    int kh = (int)fdiv((uint32_t)tap0, a.div_kw), kw = tap0 - kh * p.KW, cib = rt0 * 32, fetched = g0;
     auto fetch = [&]() {                                    // the next run, into the buffer of its parity
         const int g = min(fetched, runs - 1);               // (past the end: a run inside the tensors, unused)
         const uint32_t dst = stage_lds + (fetched & 1) * BUF;
@@ -168,20 +186,20 @@ smfmac_staged_kernel(Args a)
         }
     };
 
-    fetch();
-    fetch();
-    Words2 wa, wb;
-    v8i dn0[WM][2], dn1[WM][2];
-    wait_for_loads();                                       // (both runs: the first is needed now)
-    read_words(wa, 0, 0);
+    if (g0 < g1) {                                          // (uniform; a wavefront without a share of K only joins the barrier)
+        fetch();
+        fetch();
+        Words2 wa, wb;
+        v8i dn0[WM][2], dn1[WM][2];
+        wait_for_loads();                                   // (both runs: the first is needed now)
+        read_words(wa, g0 & 1, 0);
 #pragma unroll
-    for (int u = 0; u < WM; ++u) sparse_dense_rows_shared(s_rows, wa.ca[u].x, wa.ca1[u].x, pick, dn0[u][0], dn0[u][1]);
-    const int runs_per_tap = cq / 32;
-    int g = 0;
-    for (int khc = 0; khc < p.KH; ++khc)
-        for (int kwc = 0; kwc < p.KW; ++kwc) {
+        for (int u = 0; u < WM; ++u) sparse_dense_rows_shared(s_rows, wa.ca[u].x, wa.ca1[u].x, pick, dn0[u][0], dn0[u][1]);
+        int g = g0, rt = rt0;
+        for (int tap = tap0; g < g1; ++tap) {
             // which of this lane's pixels see the tap: the kept bytes, (1, 0) per position (and (0, 1) for the odd
             // codes), or zeros outside the image
+            const int khc = (int)fdiv((uint32_t)tap, a.div_kw), kwc = tap - khc * p.KW;
 #pragma unroll
             for (int bn = 0; bn < WN; ++bn) {
                 const int ih = col[bn].ih0 + khc, iw = col[bn].iw0 + kwc;
@@ -193,7 +211,7 @@ smfmac_staged_kernel(Args a)
                     ones_odd[bn] = (v4i){y, y, y, y};
                 }
             }
-            for (int rt = 0; rt < runs_per_tap; ++rt, ++g) {
+            for (; rt < runs_per_tap && g < g1; ++rt, ++g) {
                 // run g, in buffer g & 1: wa holds its first chunk's words, dn0 the dense operands of that chunk's word 0
                 step(dn0, wa, 0, dn1, wa, 1);
                 read_words(wb, g & 1, 1);
@@ -206,12 +224,46 @@ smfmac_staged_kernel(Args a)
                 read_words(wa, (g + 1) & 1, 0);
                 step(dn1, wb, 1, dn0, wa, 0);
             }
+            rt = 0;
         }
-    wait_for_loads();                                       // (unused fetches past the end: their LDS writes end before the wavefront does)
-    dg_mfma_store_tile<WM, WN, true>(p, acc, m0, n0, lane, sc_cols);
+        wait_for_loads();                                   // (unused fetches past the end: their LDS writes end before the wavefront does)
+    }
+    if (SKW == 1) {
+        dg_mfma_store_tile<WM, WN, true>(p, acc, m0, n0, lane, sc_cols);
+        return;
+    }
+    // The sums take the place of the staging rows: every wavefront is done with its rows (and its last loads have
+    // landed) at the first barrier; the tile's first wavefront writes its sums, the others add theirs.
+    int32_t *sums = s_acc + tw * (NB * 1024);
+    __syncthreads();
+    if (ks == 0) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sums[(i * 16 + e) * 64 + lane] = acc[i / WN][i % WN][e];
+    }
+    __syncthreads();
+    if (ks != 0 && g0 < g1) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                __hip_atomic_fetch_add(&sums[(i * 16 + e) * 64 + lane], acc[i / WN][i % WN][e], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    __syncthreads();
+    if (!active) return;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        if (i % SKW != ks) continue;                        // each wavefront of the tile stores a share of its blocks
+        v16i blk;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) blk[e] = sums[(i * 16 + e) * 64 + lane];
+        dg_mfma_store_block<true>(p, blk, m0 + (i / WN) * 32, n0 + (i % WN) * 32, lane, sc_cols[i / WN]);
+    }
 }
 
-// `wave_tiles` tiles of q.wm x q.wn blocks
+// `wave_tiles` tiles of q.wm x q.wn blocks, 4 / q.skw of them per workgroup
 inline void launch_sparse_staged(const DgProblem &p, const Pools &pools, const Plan &q, int64_t wave_tiles, hipStream_t stream)
 {
     Args a;
@@ -221,15 +273,19 @@ inline void launch_sparse_staged(const DgProblem &p, const Pools &pools, const P
     a.wave_tiles = wave_tiles;
     a.div_ow = make_div((uint32_t)p.OW), a.div_oh = make_div((uint32_t)p.OH);
     a.div_cin = make_div((uint32_t)p.Cin), a.div_kw = make_div((uint32_t)p.KW);
-    const dim3 grid((unsigned)((wave_tiles + 3) / 4));
-    if (q.wm == 1 && q.wn == 6)
-        hipLaunchKernelGGL((smfmac_staged_kernel<1, 6>), grid, dim3(256), 0, stream, a);
-    else if (q.wn == 4)
-        hipLaunchKernelGGL((smfmac_staged_kernel<2, 4>), grid, dim3(256), 0, stream, a);
-    else if (q.wn == 2)
-        hipLaunchKernelGGL((smfmac_staged_kernel<2, 2>), grid, dim3(256), 0, stream, a);
-    else
-        hipLaunchKernelGGL((smfmac_staged_kernel<2, 1>), grid, dim3(256), 0, stream, a);
+    a.div_runs = make_div((uint32_t)(p.Cin / 128));
+    const int tpw = 4 / q.skw;
+    const dim3 grid((unsigned)((wave_tiles + tpw - 1) / tpw));
+#define DG_STAGED(WM, WN, SKW) hipLaunchKernelGGL((smfmac_staged_kernel<WM, WN, SKW>), grid, dim3(256), 0, stream, a)
+    if (q.wm == 2) DG_STAGED(2, 4, 1);
+    else if (q.wn == 6) DG_STAGED(1, 6, 1);
+    else if (q.wn == 4 && q.skw == 4) DG_STAGED(1, 4, 4);
+    else if (q.wn == 4 && q.skw == 2) DG_STAGED(1, 4, 2);
+    else if (q.wn == 4) DG_STAGED(1, 4, 1);
+    else if (q.skw == 4) DG_STAGED(1, 2, 4);
+    else if (q.skw == 2) DG_STAGED(1, 2, 2);
+    else DG_STAGED(1, 2, 1);
+#undef DG_STAGED
 }
 
 }   // namespace dgoh

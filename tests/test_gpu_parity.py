@@ -168,8 +168,6 @@ def test_onehot_every_plan(plan, table, monkeypatch):
         want = prefix
         if "k" in plan and chunks < int(plan.split("k")[1]):
             want = prefix.rsplit("_k", 1)[0]                # fewer chunks than sharers: the unshared kernel
-        if table == "sparse" and "_k" not in want and channels % 128 == 0:
-            want = want.replace("onehot_smfmac_", "onehot_smfmac_staged_")      # whole 32-byte runs per tap: through LDS
         return name == want
 
     for (M, N, K) in [(70, 1000, 96), (130, 777, 64), (64, 300, 256), (33, 250, 1024)]:
@@ -911,13 +909,16 @@ def test_stationary_weight_kernel(K, waves, monkeypatch):
     assert GpuCase(c, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac") != "onehot_smfmac_ws_32xK"
 
 
-@pytest.mark.parametrize("plan,name", [("1", "onehot_smfmac_staged_64x32"), ("2", "onehot_smfmac_staged_64x64"),
-                                       ("4", "onehot_smfmac_staged_64x128"), ("16", "onehot_smfmac_staged_32x192")])
+@pytest.mark.parametrize("plan,name", [("12", "onehot_smfmac_staged_32x64"), ("12k2", "onehot_smfmac_staged_32x64_k2"),
+                                       ("12k4", "onehot_smfmac_staged_32x64_k4"), ("14", "onehot_smfmac_staged_32x128"),
+                                       ("14k2", "onehot_smfmac_staged_32x128_k2"), ("14k4", "onehot_smfmac_staged_32x128_k4"),
+                                       ("16", "onehot_smfmac_staged_32x192"), ("24", "onehot_smfmac_staged_64x128")])
 def test_staged_sparse_kernel(plan, name, monkeypatch):
     """The tiled sparse-instruction kernel whose operands go through LDS in 32-byte runs (Cin % 128 == 0), every tile
     shape forced: convolutions with a padded 3x3 window (taps outside the image at every border), a stride, one, two and
-    three runs per tap, a single run in all (K = 128), ragged M and N (tiles partly outside, fewer columns than a tile),
-    scaled fp32 and re-quantised packed output; GEMMs in both output layouts (the row-major one runs transposed)."""
+    three runs per tap, a single run in all (K = 128: shared tiles then leave wavefronts without a share), ragged M and N
+    (tiles partly outside, fewer columns than a tile), scaled fp32 and re-quantised packed output; GEMMs in both output
+    layouts (the row-major one runs transposed)."""
     monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
     lw, la, entry = LEVELS["nonuniform_i8"]
     convs = [(2, 9, 7, 128, 36, 3, 3, (1, 1), (1, 1)), (1, 13, 11, 256, 70, 3, 3, (2, 2), (1, 1)),
