@@ -18,6 +18,7 @@
 #include <cstdlib>
 #include <cstring>
 
+#include "dg_lds_dma.h"
 #include "dg_onehot_kernel.h"
 
 namespace {
@@ -30,8 +31,6 @@ struct FewNArgs {
     uint32_t cols[4];            // cols[a] = bytes T[0..3][a]: the table column of activation code a
     int32_t supersteps;          // K / 256
 };
-
-constexpr int SPW = 4;           // super-steps a wavefront loads at a time
 
 // The dense operands of the two instructions (even codes, odd codes) that consume one packed weight word per lane
 // group: dwords 0-3 from activation word w0, dwords 4-7 from w1, each the table column of one code of the 16-bit half
@@ -55,27 +54,41 @@ __device__ __forceinline__ void dense_columns(const uint2 *table, uint32_t w0, u
     }
 }
 
-// R: row blocks of 16 rows per workgroup.
-// (one workgroup of up to 16 wavefronts per compute unit)
+// R: row blocks of 16 rows per workgroup.  Up to 8 wavefronts.
+//
+// Loads: a super-step of a row block is 16 rows x 64 bytes.  With the operand layout's lane order (row = lane % 16)
+// every lane of a load would touch a cache line of its own -- 60 address cycles per instruction, which made the
+// address unit the kernel's longest phase (39 % of its time busy) -- so the loads are staged (dg_lds_dma.h): four
+// neighbouring lanes read the 64 bytes of one row, 15 cycles per instruction, straight into LDS, and lane (row, q)
+// reads its 16 bytes from there.  Slot j of a staged block (16 bytes, written by loader lane j) holds row j / 4,
+// segment (j % 4) ^ (j / 16 % 4): the exchange spreads the 16 rows of one segment over all LDS banks.
 template <int R>
-__global__ void __launch_bounds__(1024, 1)
+__global__ void __launch_bounds__(512, R == 1 ? 2 : 1)
 fewn_kernel(FewNArgs a)
 {
+    constexpr int SS = (R + 1) * 1024;                      // staged bytes of a super-step: R weight blocks, the activations
     __shared__ uint2 s_table[16];                           // entry (c0 | c1 << 2) = {column of code c0, column of code c1}
     __shared__ int32_t s_sum[R * 4 * 64];                   // [row block][sum register][lane]
+    __shared__ uint4 s_stage[8][2][SS / 16];                // [wavefront][buffer][block * 64 + slot]
     const DgProblem &p = a.p;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, waves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), waves = blockDim.x >> 6;
     for (int i = threadIdx.x; i < R * 256; i += blockDim.x) s_sum[i] = 0;
     if (threadIdx.x < 16) s_table[threadIdx.x] = make_uint2(a.cols[threadIdx.x & 3], a.cols[threadIdx.x >> 2]);
     const int i16 = lane & 15, q = lane >> 4;
     const int m0 = blockIdx.x * (16 * R), n0 = blockIdx.y * 16;
     const int64_t row_bytes = p.K / 4;
-    // weight rows (rows beyond M re-read row M - 1: their sums are not stored), this lane's 16 bytes of a super-step
-    const uint8_t *w_ptr[R];
+    // as a loader: segment lseg of row lrow of every block (rows beyond M or N re-read the last one: never stored)
+    const int lrow = lane >> 2, lseg = (lane & 3) ^ ((lane >> 4) & 3);
+    const uint8_t *w_ld[R];
 #pragma unroll
-    for (int rb = 0; rb < R; ++rb) w_ptr[rb] = p.Wp + (int64_t)min(m0 + 16 * rb + i16, p.M - 1) * row_bytes + 16 * q;
-    // activation row (columns beyond N re-read row N - 1): the words whose codes this lane's dense registers cover
-    const uint8_t *x_ptr = p.Xp + (int64_t)min(n0 + i16, p.N - 1) * row_bytes + 16 * (q >> 1);
+    for (int rb = 0; rb < R; ++rb) w_ld[rb] = p.Wp + (int64_t)min(m0 + 16 * rb + lrow, p.M - 1) * row_bytes + 16 * lseg;
+    const uint8_t *x_ld = p.Xp + (int64_t)min(n0 + lrow, p.N - 1) * row_bytes + 16 * lseg;
+    // as a consumer: of weight row i16 segment q (the sparse operand's index words), of activation row i16 the two
+    // segments whose codes this lane's dense registers cover
+    auto slot_at = [&](int seg) { return (4 * i16 + (seg ^ ((i16 >> 2) & 3))) * 16; };
+    const int w_at = slot_at(q), x0_at = slot_at(q >> 1), x1_at = slot_at(2 + (q >> 1));
+    const char *stage = (const char *)s_stage[wv];
+    const uint32_t stage_lds = dg_lds_address(s_stage) + wv * (2 * SS);
     const uint32_t pick = dgoh::sparse_pick(q & 1);
     // the kept bytes: (1, 0) per position with the even codes, (0, 1) with the odd; the index of both is the packed word
     // (of a 4-bit field the low half is the first kept byte's index, the high half the second's; the byte that is 0 may
@@ -87,48 +100,54 @@ fewn_kernel(FewNArgs a)
 #pragma unroll
     for (int rb = 0; rb < R; ++rb) acc[rb] = (v4i){0, 0, 0, 0};
 
-    // this wavefront's super-steps: a contiguous run, SPW at a time (all their loads in flight together)
+    // this wavefront's super-steps: a contiguous run, fetched two ahead into two buffers
     const int per = (a.supersteps + waves - 1) / waves;
     const int s0 = min(wv * per, a.supersteps), s1 = min(s0 + per, a.supersteps);
-    bool table_ready = false;
-    for (int sg = s0; sg < s1; sg += SPW) {
-        uint4 wq[SPW][R], x0[SPW], x1[SPW];
+    int fetched = s0;
+    auto fetch = [&]() {                                    // (past the run's end: its last super-step again, unused)
+        const int64_t off = (int64_t)min(fetched, s1 - 1) * 64;
+        const uint32_t dst = stage_lds + ((fetched - s0) & 1) * SS;
 #pragma unroll
-        for (int u = 0; u < SPW; ++u) {
-            const int64_t off = (int64_t)min(sg + u, s1 - 1) * 64;      // (a step past the run re-reads the last one, unused)
+        for (int rb = 0; rb < R; ++rb) dg_load16_to_lds(w_ld[rb] + off, dst + rb * 1024);
+        dg_load16_to_lds(x_ld + off, dst + R * 1024);
+        ++fetched;
+    };
+    if (s0 < s1) {
+        fetch();
+        fetch();
+    }
+    // (the table and the zeroed sums are in LDS once every wavefront is here; the loads above stay in flight across
+    // this barrier, which waits for LDS operations only)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    for (int ss = s0; ss < s1; ++ss) {
+        // the older of the two fetches in flight is in (loads complete in order; the newer one is R + 1 instructions)
+        dg_wait_for_loads<R + 1>();
+        const char *src = stage + ((ss - s0) & 1) * SS;
+        uint4 wq[R];
 #pragma unroll
-            for (int rb = 0; rb < R; ++rb) wq[u][rb] = *(const uint4 *)(w_ptr[rb] + off);
-            x0[u] = *(const uint4 *)(x_ptr + off);
-            x1[u] = *(const uint4 *)(x_ptr + off + 32);
-        }
-        // (the table and the zeroed sums are in LDS once every wavefront is here; the loads above stay in flight across
-        // this barrier, which waits for LDS operations only)
-        if (!table_ready) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        table_ready = true;
-        // Step tt = word tt % 4 of super-step tt / 4.  The dense operands of step tt + 1 are fetched while the matrix
-        // instructions of step tt run (two register sets), so the table reads' latency is covered.
-        const uint32_t xa[SPW][4] = {{x0[0].x, x0[0].y, x0[0].z, x0[0].w}, {x0[1].x, x0[1].y, x0[1].z, x0[1].w},
-                                     {x0[2].x, x0[2].y, x0[2].z, x0[2].w}, {x0[3].x, x0[3].y, x0[3].z, x0[3].w}};
-        const uint32_t xb[SPW][4] = {{x1[0].x, x1[0].y, x1[0].z, x1[0].w}, {x1[1].x, x1[1].y, x1[1].z, x1[1].w},
-                                     {x1[2].x, x1[2].y, x1[2].z, x1[2].w}, {x1[3].x, x1[3].y, x1[3].z, x1[3].w}};
+        for (int rb = 0; rb < R; ++rb) wq[rb] = *(const uint4 *)(src + rb * 1024 + w_at);
+        const uint4 x0 = *(const uint4 *)(src + R * 1024 + x0_at), x1 = *(const uint4 *)(src + R * 1024 + x1_at);
+        const uint32_t xa[4] = {x0.x, x0.y, x0.z, x0.w}, xb[4] = {x1.x, x1.y, x1.z, x1.w};
+        // Step t = word t of the super-step.  The dense operands of step t + 1 are fetched while the matrix
+        // instructions of step t run (two register sets), so the table reads' latency is covered.
         v8i even[2], odd[2];
-        dense_columns(s_table, xa[0][0], xb[0][0], pick, even[0], odd[0]);
+        dense_columns(s_table, xa[0], xb[0], pick, even[0], odd[0]);
+        // (the buffer's words are in registers -- dense_columns used them: the fetch after next may overwrite it)
+        fetch();
 #pragma unroll
-        for (int tt = 0; tt < 4 * SPW; ++tt) {
-            const int u = tt / 4, t = tt % 4, cur = tt & 1;
-            if (sg + u >= s1) break;                        // (uniform)
-            if (tt + 1 < 4 * SPW)                           // (past the run's end: built from re-read words, unused)
-                dense_columns(s_table, xa[(tt + 1) / 4][(tt + 1) % 4], xb[(tt + 1) / 4][(tt + 1) % 4], pick, even[cur ^ 1], odd[cur ^ 1]);
+        for (int t = 0; t < 4; ++t) {
+            const int cur = t & 1;
+            if (t + 1 < 4) dense_columns(s_table, xa[t + 1], xb[t + 1], pick, even[cur ^ 1], odd[cur ^ 1]);
 #pragma unroll
             for (int rb = 0; rb < R; ++rb) {
-                const uint32_t word = t == 0 ? wq[u][rb].x : (t == 1 ? wq[u][rb].y : (t == 2 ? wq[u][rb].z : wq[u][rb].w));
+                const uint32_t word = t == 0 ? wq[rb].x : (t == 1 ? wq[rb].y : (t == 2 ? wq[rb].z : wq[rb].w));
                 acc[rb] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(ones_even, even[cur], acc[rb], (int)word, 0, 0);
                 acc[rb] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(ones_odd, odd[cur], acc[rb], (int)word, 0, 0);
             }
         }
     }
+    dg_wait_for_loads();                                    // (the unused fetches past the end: their LDS writes end before the wavefront does)
 
-    if (!table_ready) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // (a wavefront without super-steps)
 #pragma unroll
     for (int rb = 0; rb < R; ++rb)
 #pragma unroll
@@ -166,9 +185,10 @@ bool dg_fewn_preferred(const dg_lut *lut, const DgProblem &p)
 {
     if (!dg_fewn_supports(lut, p)) return false;
     if (const char *force = dg_override("DG_ONEHOT_PLAN")) return strcmp(force, "fewn") == 0;      // (tests reach it on small shapes)
-    // (one column: the permute kernel with K across the lanes is faster, 5.4 against 6.5 us on 8192 x 8192 weights;
-    // from 17 columns on the weights would be streamed twice and the split-K matrix-core kernel is faster)
-    return p.N >= 2 && p.N <= 16 && p.K >= 2048 && (int64_t)p.M * p.K >= ((int64_t)1 << 22);
+    // (measured on 8192 x 8192 weights: 5.1 - 5.25 us for 1 to 16 columns, against 5.4 us of the permute kernel with K
+    // across the lanes on one column; from 17 columns on the weights would be streamed twice and the tiled kernels
+    // are faster)
+    return p.N >= 1 && p.N <= 16 && p.K >= 2048 && (int64_t)p.M * p.K >= ((int64_t)1 << 22);
 }
 
 dg_status dg_launch_fewn(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
@@ -180,13 +200,13 @@ dg_status dg_launch_fewn(const dg_lut *lut, const DgProblem &p, hipStream_t stre
         a.cols[c] = 0;
         for (int w = 0; w < 4; ++w) a.cols[c] |= (uint32_t)(uint8_t)(int8_t)lut->entry[(w << 2) | c] << (8 * w);
     }
-    // as many wavefronts as there are runs of 4 super-steps (what a wavefront loads at a time), up to 8 (measured: 16
-    // wavefronts of 2 super-steps each are slower); 32 rows per workgroup while that gives every compute unit a
-    // workgroup, else 16
-    int waves = (a.supersteps + SPW - 1) / SPW;
+    // a wavefront per 4 super-steps, up to 8 (the staging buffers' number); 32 rows per workgroup while that gives
+    // every compute unit a workgroup, else 16
+    int waves = (a.supersteps + 3) / 4;
     waves = waves < 1 ? 1 : (waves > 8 ? 8 : waves);
-    if (const char *e = dg_override("DG_FEWN_WAVES")) waves = atoi(e) >= 1 && atoi(e) <= 16 ? atoi(e) : waves;
-    const bool two = (p.M + 31) / 32 >= dg_simd_count() / 4;
+    if (const char *e = dg_override("DG_FEWN_WAVES")) waves = atoi(e) >= 1 && atoi(e) <= 8 ? atoi(e) : waves;
+    bool two = (p.M + 31) / 32 >= dg_simd_count() / 4;
+    if (const char *e = dg_override("DG_FEWN_ROWS")) two = atoi(e) == 32;      // (A/B measurement)
     const dim3 grid((unsigned)((p.M + (two ? 31 : 15)) / (two ? 32 : 16)), (unsigned)((p.N + 15) / 16)), block(64 * waves);
     if (two)
         hipLaunchKernelGGL((fewn_kernel<2>), grid, block, 0, stream, a);

@@ -2,13 +2,13 @@
 // tile, all of K), with the packed operands fetched in WHOLE 32-BYTE RUNS and handed to their lanes through LDS.
 //
 // Why: the matrix instruction wants lane (r, half) to hold words of row r, so a direct load has 32 lanes reading 8
-// bytes each from 32 different rows.  The address unit of a compute unit takes such a load one lane (one cache line)
-// per cycle: 64 cycles for 512 or 1024 bytes, and on a GEMM with K = 8192 it was busy 93 % of the kernel's time
-// (counters TA_TA_BUSY / TCP_GATE_EN) while the matrix pipe idled -- the loads, not the arithmetic, set the time.
-// Here two neighbouring lanes read the two 16-byte halves of one row's run, so a load instruction covers 32 rows x 32
-// bytes -- four times the bytes per address cycle, with a quarter of the cache-line requests.  The loads write LDS
-// directly (global_load_lds_dwordx4: lane l's 16 bytes land at the instruction's LDS base + 16 l; no registers are
-// held while they are in flight), into staging rows of the wavefront's own, from which lane (r, half) reads its 8
+// bytes each from 32 different rows.  The address unit of a compute unit takes such a load one cache line per cycle
+// (dg_lds_dma.h): 64 cycles and more for 512 or 1024 bytes, and on a GEMM with K = 8192 it was busy 93 % of the
+// kernel's time (counters TA_TA_BUSY / TCP_GATE_EN) while the matrix pipe idled -- the loads, not the arithmetic, set
+// the time.  Here two neighbouring lanes read the two 16-byte halves of one row's run, so a load instruction covers 32
+// rows x 32 bytes, at half the address cycles per byte (30 % busy on the same GEMM).  The loads write LDS directly
+// (lane l's 16 bytes land at the instruction's LDS base + 16 l; no registers are held while they are in flight), into
+// staging rows of the wavefront's own, from which lane (r, half) reads its 8
 // bytes per 64 positions of K.  Staging rows belong to one wavefront, so no barrier is involved: a wavefront waits
 // for its own loads (vmcnt) before it reads a run, and runs alternate between two buffers, fetched two ahead.
 // The multiplication is one software pipeline over all of K: the dense operands of a step are made between the matrix
@@ -18,26 +18,10 @@
 // clamped address and contributes nothing because the kept bytes of its lanes are zero.
 #pragma once
 
+#include "dg_lds_dma.h"
 #include "dg_onehot_kernel.h"
 
 namespace dgoh {
-
-// 16 bytes per lane from global memory straight into LDS: lane l's land at byte `lds` + 16 l (`lds`: a wavefront-uniform
-// LDS byte address, handed over in M0; one wait state between writing M0 and the load).  Written as assembly because
-// the compiler, which cannot tell the staging buffers apart, would wait for every such load before the next LDS read
-// of any kind; here the wavefront counts its own loads (s_waitcnt vmcnt), and the "memory" clobbers keep the
-// compiler's LDS reads on their side of the loads and the waits.
-__device__ __forceinline__ void load16_to_lds(const uint8_t *base, int32_t offset, uint32_t lds)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(offset), "s"(base), "s"(lds) : "memory", "m0");
-}
-__device__ __forceinline__ void load16_to_lds(const uint8_t *address, uint32_t lds)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(address), "s"(lds) : "memory", "m0");
-}
-__device__ __forceinline__ void wait_for_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // SKW = 1: a wavefront walks all of K.  SKW = 2 or 4 (layers whose tiles alone would leave SIMDs idle): SKW wavefronts
 // of the workgroup share a tile and split K between them in contiguous runs; their sums meet in LDS by integer atomics
@@ -111,22 +95,21 @@ smfmac_staged_kernel(Args a)
 
     // ---- the loader's side: runs are fetched two ahead of the one being multiplied
     const char *stage = (const char *)s_mem + w4 * (2 * BUF);
-    // (the numeric value of a pointer into LDS is its LDS byte address)
-    const uint32_t stage_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)s_mem + w4 * (2 * BUF);
+    const uint32_t stage_lds = dg_lds_address(s_mem) + w4 * (2 * BUF);
     // filter tap and byte within the pixel of the run fetched next
     int kh = (int)fdiv((uint32_t)tap0, a.div_kw), kw = tap0 - kh * p.KW, cib = rt0 * 32, fetched = g0;
     auto fetch = [&]() {                                    // the next run, into the buffer of its parity
         const int g = min(fetched, runs - 1);               // (past the end: a run inside the tensors, unused)
         const uint32_t dst = stage_lds + (fetched & 1) * BUF;
 #pragma unroll
-        for (int bm = 0; bm < WM; ++bm) load16_to_lds(w_ld[bm] + g * 32, dst + bm * 1024);
+        for (int bm = 0; bm < WM; ++bm) dg_load16_to_lds(w_ld[bm] + g * 32, dst + bm * 1024);
         const int32_t tap_off = (kh * p.W + kw) * cq + cib;
 #pragma unroll
         for (int bn = 0; bn < WN; ++bn) {
             // (a tap outside the image or past the end: any address inside the tensor will do; the kept bytes of a
             // lane outside the image are zero)
             const int32_t off = max(0, min(x_ld[bn] + tap_off, x_last));
-            load16_to_lds(p.Xp, off, dst + (WM + bn) * 1024);
+            dg_load16_to_lds(p.Xp, off, dst + (WM + bn) * 1024);
         }
         ++fetched;
         cib += 32;
@@ -191,7 +174,7 @@ smfmac_staged_kernel(Args a)
         fetch();
         Words2 wa, wb;
         v8i dn0[WM][2], dn1[WM][2];
-        wait_for_loads();                                   // (both runs: the first is needed now)
+        dg_wait_for_loads();                                   // (both runs: the first is needed now)
         read_words(wa, g0 & 1, 0);
 #pragma unroll
         for (int u = 0; u < WM; ++u) sparse_dense_rows_shared(s_rows, wa.ca[u].x, wa.ca1[u].x, pick, dn0[u][0], dn0[u][1]);
@@ -219,14 +202,14 @@ smfmac_staged_kernel(Args a)
                 step(dn0, wb, 0, dn1, wb, 1);
                 // every read of run g has been issued: its buffer takes run g + 2, once run g + 1 is known to be in
                 // (one counter serves all loads, and they complete in order)
-                wait_for_loads();
+                dg_wait_for_loads();
                 fetch();
                 read_words(wa, (g + 1) & 1, 0);
                 step(dn1, wb, 1, dn0, wa, 0);
             }
             rt = 0;
         }
-        wait_for_loads();                                   // (unused fetches past the end: their LDS writes end before the wavefront does)
+        dg_wait_for_loads();                                   // (unused fetches past the end: their LDS writes end before the wavefront does)
     }
     if (SKW == 1) {
         dg_mfma_store_tile<WM, WN, true>(p, acc, m0, n0, lane, sc_cols);

@@ -195,12 +195,17 @@ def test_kernel_names_need_no_gpu():
     # the plan functions are host code: small layers split K, large ones get a wave tile, wide entries two planes
     lut = dg.dg_build_lut((-2, -1, 0, 1), (0, 1, 2, 3))
     assert dg.dg_gemm_kernel_name(lut, 64, 196, 576).startswith("onehot_mfma_splitk_s")
-    assert dg.dg_gemm_kernel_name(lut, 8192, 8192, 8192) == "onehot_smfmac_64x128"     # large unshared tiles: the sparse instruction
+    # large layers: the sparse instruction, operands staged through LDS where the taps are whole 32-byte runs
+    assert dg.dg_gemm_kernel_name(lut, 8192, 8192, 8192) == "onehot_smfmac_staged_64x128"
+    assert dg.dg_gemm_kernel_name(lut, 8192, 8192, 8192 + 64) == "onehot_smfmac_64x128"
     assert dg.dg_gemm_kernel_name(lut, 8192, 8192, 8192, "onehot_mfma") == "onehot_mfma_64x128"
-    assert dg.dg_gemm_kernel_name(lut, 8192, 256, 8192) == "onehot_smfmac_64x64_k4"    # wavefronts share tiles (512 of them: sparse)
+    assert dg.dg_gemm_kernel_name(lut, 8192, 256, 8192) == "onehot_smfmac_staged_32x128_k4"      # wavefronts share tiles
+    assert dg.dg_gemm_kernel_name(lut, 8192, 256, 8192 + 64) == "onehot_smfmac_64x64_k4"
     assert dg.dg_gemm_kernel_name(lut, 8192, 256, 8192, "onehot_mfma") == "onehot_mfma_64x64_k4"
-    assert dg.dg_gemm_kernel_name(lut, 8192, 64, 8192) == "onehot_mfma_64x32_k4"       # narrow shared tiles stay dense
-    assert dg.dg_gemm_kernel_name(lut, 8192, 1, 8192) == "smalln"
+    assert dg.dg_gemm_kernel_name(lut, 8192, 64, 8192) == "onehot_smfmac_staged_32x64_k4"
+    assert dg.dg_gemm_kernel_name(lut, 8192, 64, 8192 + 64) == "onehot_mfma_64x32_k4"  # narrow shared tiles, direct loads: dense
+    assert dg.dg_gemm_kernel_name(lut, 8192, 1, 8192) == "onehot_smfmac_fewn_16"       # 1 to 16 columns, long rows
+    assert dg.dg_gemm_kernel_name(lut, 8192, 1, 8192 + 64) == "smalln"
     assert dg.dg_gemm_kernel_name(lut, 64, 196, 48).startswith("perm")        # Cin % 32 != 0, % 16 == 0
     assert dg.dg_gemm_kernel_name(lut, 5, 7, 12) == "lds"                      # Cin % 16 != 0
     # the comparison kernel has the same plans, and a 128 x 128 tile of its own for the largest problems
@@ -220,13 +225,13 @@ def test_kernel_names_need_no_gpu():
     large = dg.conv_desc(16, 56, 56, 256, 256, 3, 3, (1, 1), (1, 1))
     assert dg.dg_conv_codes_kernel_name(lut, small) == "codes_onehot_mfma_splitk_s9"
     assert dg.dg_conv_codes_kernel_name(lut, small, "onehot_smfmac") == dg.dg_conv_kernel_name(lut, small, "onehot_smfmac")
-    assert dg.dg_conv_codes_kernel_name(lut, large) == dg.dg_conv_kernel_name(lut, large) == "onehot_smfmac_64x128"
+    assert dg.dg_conv_codes_kernel_name(lut, large) == dg.dg_conv_kernel_name(lut, large) == "onehot_smfmac_staged_64x128"
     assert dg.dg_gemm_codes_kernel_name(lut, 64, 196, 576) == "codes_onehot_mfma_splitk_s9"
     assert dg.dg_gemm_codes_kernel_name(lut, 8192, 1, 8192) == "codes_smalln"
     # 256 row blocks would each pack the activations for themselves: two kernels unless the fused form is asked for by name
     assert dg.dg_gemm_codes_kernel_name(lut, 8192, 16, 8192) == dg.dg_gemm_kernel_name(lut, 8192, 16, 8192)
     assert dg.dg_gemm_codes_kernel_name(lut, 8192, 16, 8192, "onehot_mfma").startswith("codes_onehot_mfma_splitk_s")
-    assert dg.dg_gemm_codes_kernel_name(lut, 8192, 8192, 8192) == "onehot_smfmac_64x128"
+    assert dg.dg_gemm_codes_kernel_name(lut, 8192, 8192, 8192) == "onehot_smfmac_staged_64x128"
 
 
 def test_dequantize_argument_errors():

@@ -955,7 +955,7 @@ def test_staged_sparse_kernel(plan, name, monkeypatch):
     assert "staged" not in GpuCase(c, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac")
 
 
-@pytest.mark.parametrize("waves", [0, 1, 3, 16])
+@pytest.mark.parametrize("waves", [0, 1, 3, 8])
 @pytest.mark.parametrize("K", [256, 1280, 4096, 8192])
 def test_few_columns_sparse_kernel(K, waves, monkeypatch):
     """The few-columns kernel on the sparse instruction (weights as the index operand), forced on shapes with ragged M
