@@ -502,7 +502,7 @@ namespace {
 // The one-call entry points fuse the packing into the kernel where the library's own choice for the problem (or the
 // variant the caller names) is the one-hot split-K kernel or the few-columns kernel, i.e. on problems so small that a
 // second launch costs a good part of the whole.
-enum class Fuse { None, OneHot, SmallN };
+enum class Fuse { None, OneHot, SmallN, SparseWs };
 
 Fuse fuses_packing(const dg_lut *lut, const DgProblem &p_codes, dg_kernel variant)
 {
@@ -517,6 +517,10 @@ Fuse fuses_packing(const dg_lut *lut, const DgProblem &p_codes, dg_kernel varian
     if ((variant == DG_KERNEL_SMALLN || (variant == DG_KERNEL_AUTO && p_codes.N <= 4)) &&
         pick_kernel(lut, p_codes, variant) == Pick::SmallN)
         return Fuse::SmallN;
+    // the stationary-weight kernel stages and packs the codes of its pixel blocks itself
+    if ((variant == DG_KERNEL_AUTO || variant == DG_KERNEL_ONEHOT_SMFMAC) && dg_sparse_ws_codes_supports(lut, p_codes) &&
+        pick_kernel(lut, p_codes, variant) == Pick::SparseWs)
+        return Fuse::SparseWs;
     // (one column: on packed activations the few-columns sparse-instruction kernel is the faster by 6 %, which is less
     // than the packing launch it would need here)
     if (variant == DG_KERNEL_AUTO && p_codes.N == 1 && p_codes.K >= 1024 && dg_smalln_supports(lut, p_codes) &&
@@ -533,6 +537,7 @@ dg_status run_codes(const char *name, const dg_lut *lut, DgProblem &p, const uin
     switch (fuses_packing(lut, p, variant)) {
     case Fuse::OneHot: return dg_launch_onehot_codes(lut, p, (hipStream_t)hip_stream);
     case Fuse::SmallN: return dg_launch_smalln_codes(lut, p, (hipStream_t)hip_stream);
+    case Fuse::SparseWs: return dg_launch_sparse_ws_codes(lut, p, (hipStream_t)hip_stream);
     case Fuse::None: break;
     }
     const dg_status s = pack_common(name, codes, rows, row_codes, lut->bits, work, work_bytes, hip_stream);
@@ -546,6 +551,7 @@ const char *codes_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
     switch (fuses_packing(lut, p, variant)) {
     case Fuse::OneHot: return dg_onehot_codes_config_name(lut, p);
     case Fuse::SmallN: return "codes_smalln";
+    case Fuse::SparseWs: return "codes_onehot_smfmac_ws_32xK";
     case Fuse::None: break;
     }
     return pick_name(lut, p, variant);

@@ -116,6 +116,8 @@ dg_status dg_launch_sparse2p(const dg_lut *lut, const DgProblem &p, hipStream_t 
 bool dg_sparse_ws_supports(const dg_lut *lut, const DgProblem &p);    // short K: weight operands stationary in registers
 bool dg_sparse_ws_preferred(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_sparse_ws(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
+bool dg_sparse_ws_codes_supports(const dg_lut *lut, const DgProblem &p);                       // p.Xp: codes one per byte
+dg_status dg_launch_sparse_ws_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 bool dg_fewn_supports(const dg_lut *lut, const DgProblem &p);         // few activation rows: weights as the sparse operand
 bool dg_fewn_preferred(const dg_lut *lut, const DgProblem &p);
 dg_status dg_launch_fewn(const dg_lut *lut, const DgProblem &p, hipStream_t stream);

@@ -18,12 +18,12 @@
 __device__ __forceinline__ void dg_load16_to_lds(const uint8_t *base, int32_t offset, uint32_t lds)
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(offset), "s"(base), "s"(lds) : "memory", "m0");
+                 :: "v"(offset), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds)) : "memory", "m0");
 }
 __device__ __forceinline__ void dg_load16_to_lds(const uint8_t *address, uint32_t lds)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(address), "s"(lds) : "memory", "m0");
+                 :: "v"(address), "s"(__builtin_amdgcn_readfirstlane(lds)) : "memory", "m0");
 }
 template <int OUTSTANDING = 0>
 __device__ __forceinline__ void dg_wait_for_loads()

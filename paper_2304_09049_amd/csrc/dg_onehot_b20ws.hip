@@ -3,8 +3,8 @@
 #include "dg_sparse_ws_kernel.h"
 
 namespace dgoh {
-void unit_sparse_ws(const DgProblem &p, const uint32_t (&rows)[4], int streams, hipStream_t stream)
+void unit_sparse_ws(const DgProblem &p, const uint32_t (&rows)[4], int streams, bool raw, hipStream_t stream)
 {
-    launch_sparse_ws(p, rows, streams, stream);
+    launch_sparse_ws(p, rows, streams, raw, stream);
 }
 }   // namespace dgoh

@@ -334,11 +334,13 @@ bool sparse_ws_takes(const dg_lut *lut, const DgProblem &p)
 }
 
 // runs of pixel blocks: about one wavefront per SIMD in all (measured on seven 1x1 layers: as fast as two or faster, and
-// runs of up to 8 blocks are loaded whole before the first store), each with at least one block
-int sparse_ws_streams(const DgProblem &t)
+// runs of up to 8 blocks are loaded whole before the first store), each with at least one block.  `raw` (the form that
+// packs the codes itself, block by block): two per SIMD, whose packing and stores overlap (four layers measured: 9.5
+// against 10.9 us on 56x56x256 -> 64, 4 - 10 % on two others; the layer with K = 128 was 6 % slower and keeps one)
+int sparse_ws_streams(const DgProblem &t, bool raw)
 {
     const int64_t row_blocks = (t.M + 31) / 32, pixel_blocks = ((int64_t)t.N + 31) / 32;
-    int64_t waves = (int64_t)dg_simd_count();
+    int64_t waves = (int64_t)dg_simd_count() * (raw && t.K != 128 ? 2 : 1);
     if (const char *e = dg_override("DG_WS_WAVES")) waves = atoi(e) > 0 ? atoi(e) : waves;
     int64_t streams = waves / row_blocks;
     if (streams < 1) streams = 1;
@@ -359,7 +361,9 @@ bool dg_sparse_ws_preferred(const dg_lut *lut, const DgProblem &p)
     return ((int64_t)(t.M + 31) / 32) * (((int64_t)t.N + 31) / 32) >= (int64_t)dg_simd_count() / 2;
 }
 
-dg_status dg_launch_sparse_ws(const dg_lut *lut, const DgProblem &p0, hipStream_t stream)
+namespace {
+
+dg_status launch_ws(const dg_lut *lut, const DgProblem &p0, bool raw, hipStream_t stream)
 {
     const bool transposed = sparse_transposes(p0);
     const DgProblem p = sparse_problem(p0);
@@ -371,9 +375,22 @@ dg_status dg_launch_sparse_ws(const dg_lut *lut, const DgProblem &p0, hipStream_
             rows[w] |= (uint32_t)(uint8_t)(int8_t)T << (8 * v);
         }
     }
-    dgoh::unit_sparse_ws(p, rows, sparse_ws_streams(p), stream);
+    dgoh::unit_sparse_ws(p, rows, sparse_ws_streams(p, raw), raw, stream);
     return dg_check_launch("smfmac_ws_kernel");
 }
+
+}   // namespace
+
+dg_status dg_launch_sparse_ws(const dg_lut *lut, const DgProblem &p0, hipStream_t stream) { return launch_ws(lut, p0, false, stream); }
+
+// The same on activations still one code per byte (p.Xp: [N][K] bytes): where the kernel runs the problem as it is
+// (the activations are its pixels, not, as in a transposed GEMM, its stationary operand).
+bool dg_sparse_ws_codes_supports(const dg_lut *lut, const DgProblem &p)
+{
+    return sparse_ws_takes(lut, p) && !sparse_transposes(p);
+}
+
+dg_status dg_launch_sparse_ws_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream) { return launch_ws(lut, p, true, stream); }
 
 // ---- 4-bit codes on the sparse instruction (dg_sparse4_kernel.h): 64 x 128 tiles only, so large layers only
 

@@ -15,6 +15,7 @@
 // the pixels' words are fetched from memory once and the halves of an output row are written together.
 #pragma once
 
+#include "dg_lds_dma.h"
 #include "dg_onehot_kernel.h"
 
 namespace dgoh {
@@ -39,12 +40,22 @@ struct WsArgs {
 //   - blocks are computed and stored one at a time: two blocks sharing the instruction stream (independent sums back to
 //     back) store in larger bursts and were 0.7 us slower; so was building the operands interleaved with the first block;
 //   - pixel words are asked for before the weight words (0.15 us faster than the other way round).
-template <int T, int G>
-__global__ void __launch_bounds__(256, (T * G > 32 ? 1 : 2))
+//
+// RAW: the activations are codes one per byte ([pixel][K] bytes at p.Xp) and are packed by the kernel itself, which
+// spares a layer the packing kernel (as long as this one on the 56x56x256 -> 64 layer) and the packed tensor's round
+// trip through memory.  A lane needs half a pixel's codes, 16 T contiguous bytes -- as direct loads that is a cache
+// line of its own per lane and instruction, which the address unit takes a line per cycle -- so the codes of a pixel
+// block are staged (dg_lds_dma.h): 2 T neighbouring lanes read the 32 T bytes of one pixel straight into LDS, two
+// blocks in flight per wavefront, and lane (pixel, half) reads its 16-byte segments from there and packs each into a
+// word.  Slot j of a staged pixel holds its segment j ^ (pixel % 2T): the exchange spreads the 32 pixels' reads of one
+// segment over the LDS banks.  All of a group's blocks are packed before the group's first store, as above.
+template <int T, int G, bool RAW>
+__global__ void __launch_bounds__(256, (!RAW && T * G > 32 ? 1 : 2))
 smfmac_ws_kernel(WsArgs a)
 {
     static_assert(T == 2 || T == 4 || T == 8, "K = 64, 128 or 256");
     __shared__ uint2 s_rows[16];                            // the table of row pairs, one for the workgroup
+    extern __shared__ uint4 s_codes[];                      // RAW: [wavefront][2][32 pixels x 2 T segments]
     const DgProblem &p = a.p;
     const int lane = threadIdx.x & 63, w4 = threadIdx.x >> 6;
     {
@@ -68,6 +79,18 @@ smfmac_ws_kernel(WsArgs a)
     const int last_row = p.N - 1;
     const uint8_t *x_base = p.Xp + h * (4 * T);
     Words<T> x[G];
+    constexpr int SP = 2 * T, BLOCK = 32 * SP;              // RAW: 16-byte segments per pixel, and per staged pixel block
+    const int wv = __builtin_amdgcn_readfirstlane(w4);
+    const uint32_t codes_lds = dg_lds_address(s_codes) + wv * (2 * BLOCK * 16);
+    auto stage = [&](int64_t blk, int buf) {                // RAW: pixel block `blk` (clamped into the tensor) into buffer `buf`
+        const int lp = lane / SP, ls = lane % SP;           // as a loader: pixel within the instruction, slot within the pixel
+#pragma unroll
+        for (int j = 0; j < T; ++j) {                       // 64 / SP pixels per instruction
+            const int pj = j * (64 / SP) + lp;
+            const int64_t n = min(blk * 32 + pj, (int64_t)last_row);
+            dg_load16_to_lds(p.Xp + n * p.K + ((ls ^ (pj % SP)) * 16), codes_lds + (buf * BLOCK + j * 64) * 16);
+        }
+    };
     auto fetch = [&](int64_t blk) {                         // rows beyond N re-read row N - 1 (their sums are not stored)
 #pragma unroll
         for (int g = 0; g < G; ++g) {
@@ -75,7 +98,18 @@ smfmac_ws_kernel(WsArgs a)
             if (blk + g < b1) x[g] = load_words_any<T>(x_base + n * row_bytes);
         }
     };
-    fetch(b0);
+    if constexpr (RAW) {
+        // two blocks in flight (past the run's end the loads re-read pixels inside the tensor and are not used: one
+        // block's loads are always behind the one waited for, so the wait can count them).  A wavefront never ends
+        // with such a load in flight -- its LDS could be another workgroup's by the time the data lands -- so one
+        // without a run starts none.
+        if (!idle) {
+            stage(b0, 0);
+            stage(b0 + 1, 1);
+        }
+    } else {
+        fetch(b0);
+    }
 
     // the stationary dense operands: for word t of either half of the weight row, the even and the odd codes' table rows
     v8i dn[T][2];
@@ -95,6 +129,33 @@ smfmac_ws_kernel(WsArgs a)
     // the kept bytes: (1, 0) per position with the even codes, (0, 1) with the odd; the index of both is the packed word
     const v4i ones[2] = {{0x00010001, 0x00010001, 0x00010001, 0x00010001}, {0x01000100, 0x01000100, 0x01000100, 0x01000100}};
 
+    if constexpr (RAW) {
+        // a block's codes are packed and multiplied while the block after next is on its way: its loads are issued as
+        // soon as the buffer's codes are in registers, ahead of this block's stores
+        for (int64_t blk = b0; blk < b1; ++blk) {
+            const int buf = (int)(blk - b0) & 1;
+            dg_wait_for_loads<T>();                         // (loads complete in order: all but the newer block's T)
+            const uint4 *src = s_codes + (wv * 2 + buf) * BLOCK + r * SP;
+            uint4 c[T];
+#pragma unroll
+            for (int i = 0; i < T; ++i) c[i] = src[(h * T + i) ^ (r % SP)];
+            Words<T> xw;
+#pragma unroll
+            for (int i = 0; i < T; ++i) xw.v[i] = dg_pack_codes16(c[i]);
+            stage(blk + 2, buf);
+            v16i acc;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = 0;
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int par = 0; par < 2; ++par)
+                    acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones[par], dn[t][par], acc, (int)xw.v[t], 0, 0);
+            dg_mfma_store_block<true>(p, acc, m0, (int)(blk * 32), lane, sc_cols[0]);
+        }
+        dg_wait_for_loads();                                // (the unused loads past the end: their LDS writes end before the wavefront does)
+        return;
+    }
     for (int64_t blk = b0; blk < b1; blk += G) {
         // one block at a time, so that the first stores go out as early as possible: the layer's time is the time its
         // output takes to drain, counted from the first store (the other wavefront of the SIMD fills the gaps between
@@ -118,7 +179,8 @@ smfmac_ws_kernel(WsArgs a)
     }
 }
 
-inline void launch_sparse_ws(const DgProblem &p, const uint32_t (&rows)[4], int streams, hipStream_t stream)
+// `raw`: p.Xp holds codes one per byte
+inline void launch_sparse_ws(const DgProblem &p, const uint32_t (&rows)[4], int streams, bool raw, hipStream_t stream)
 {
     WsArgs a;
     a.p = p;
@@ -134,18 +196,24 @@ inline void launch_sparse_ws(const DgProblem &p, const uint32_t (&rows)[4], int 
     // a wavefront's whole run in one group where the registers allow it (up to 8 blocks)
     const int t = p.K / 32;
     const bool wide = a.run + (a.longer ? 1 : 0) > 4;
-    if (t == 8 && wide)
-        hipLaunchKernelGGL((smfmac_ws_kernel<8, 8>), grid, dim3(256), 0, stream, a);
-    else if (t == 8)
-        hipLaunchKernelGGL((smfmac_ws_kernel<8, 4>), grid, dim3(256), 0, stream, a);
-    else if (t == 4 && wide)
-        hipLaunchKernelGGL((smfmac_ws_kernel<4, 8>), grid, dim3(256), 0, stream, a);
-    else if (t == 4)
-        hipLaunchKernelGGL((smfmac_ws_kernel<4, 4>), grid, dim3(256), 0, stream, a);
-    else if (wide)
-        hipLaunchKernelGGL((smfmac_ws_kernel<2, 8>), grid, dim3(256), 0, stream, a);
-    else
-        hipLaunchKernelGGL((smfmac_ws_kernel<2, 4>), grid, dim3(256), 0, stream, a);
+    // (the staging buffers of the form that packs: 4 wavefronts x 2 blocks x 32 pixels x K bytes, up to 64 KB)
+#define DG_WS(T, G)                                                                                                   \
+    do {                                                                                                              \
+        if (raw) {                                                                                                    \
+            const int lds = 4 * 2 * 32 * 32 * T;                                                                      \
+            (void)hipFuncSetAttribute((const void *)smfmac_ws_kernel<T, G, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); \
+            hipLaunchKernelGGL((smfmac_ws_kernel<T, G, true>), grid, dim3(256), lds, stream, a);                      \
+        } else {                                                                                                      \
+            hipLaunchKernelGGL((smfmac_ws_kernel<T, G, false>), grid, dim3(256), 0, stream, a);                       \
+        }                                                                                                             \
+    } while (0)
+    if (t == 8 && wide) DG_WS(8, 8);
+    else if (t == 8) DG_WS(8, 4);
+    else if (t == 4 && wide) DG_WS(4, 8);
+    else if (t == 4) DG_WS(4, 4);
+    else if (wide) DG_WS(2, 8);
+    else DG_WS(2, 4);
+#undef DG_WS
 }
 
 }   // namespace dgoh

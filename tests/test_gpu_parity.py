@@ -907,6 +907,33 @@ def test_stationary_weight_kernel(K, waves, monkeypatch):
     # a filter window, a stride or another K is not its case: the tiled sparse-instruction kernel takes over
     c = wl.small_conv(1, 8, 8, 64, 32, 3, 3, (1, 1), (1, 1), seed=1)
     assert GpuCase(c, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac") != "onehot_smfmac_ws_32xK"
+    # on codes one per byte it packs them itself (no work buffer needed): convolutions, and GEMMs whose output has the
+    # weight rows' axis contiguous (the other layout runs transposed, with the packing kernel first)
+    for (B, H, W, Cout) in [(3, 9, 7, 36), (1, 31, 33, 64), (2, 16, 16, 100), (1, 1, 5, 8)]:
+        c = wl.small_conv(B, H, W, K, Cout, 1, 1, (1, 1), (0, 0), seed=H + K + Cout + 1, scale=True)
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        assert dg.dg_conv_codes_kernel_name(case.lut, case.desc, "onehot_smfmac") == "codes_onehot_smfmac_ws_32xK"
+        acc = oracle.conv2d(c.Wc, c.Ac, lw, la)
+        Xc = torch.from_numpy(c.Ac).cuda()
+        got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, variant="onehot_smfmac")
+        torch.cuda.synchronize()
+        _assert_same(got.cpu().numpy(), acc, f"ws conv on codes {(B, H, W, K, Cout)}")
+        got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, scale=case.scale, variant="onehot_smfmac")
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), oracle.scale_epilogue_nhwc(acc, c.scale))
+    for (M, N) in [(70, 1000), (33, 64), (130, 2049)]:
+        inp = wl.small_gemm(M, N, K, seed=M + N + K + 1)
+        case = GpuCase(inp, levels=(lw, la), entry=entry)
+        Ac = torch.from_numpy(inp.Ac).cuda()
+        want = oracle.gemm(inp.Wc, inp.Ac, lw, la)
+        out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
+        dg.dg_gemm_lut_codes(case.lut, case.Wp, Ac, M, N, K, out=out, strides=(1, M), variant="onehot_smfmac")
+        torch.cuda.synchronize()
+        _assert_same(out.cpu().numpy(), want.T.copy(), f"ws gemm on codes {(M, N, K)} column-major")
+        assert dg.dg_gemm_codes_kernel_name(case.lut, M, N, K, "onehot_smfmac") == "onehot_smfmac_ws_32xK"     # row-major
+        got = dg.dg_gemm_lut_codes(case.lut, case.Wp, Ac, M, N, K, work=torch.empty_like(case.Ap), variant="onehot_smfmac")
+        torch.cuda.synchronize()
+        _assert_same(got.cpu().numpy(), want, f"ws gemm on codes {(M, N, K)} row-major")
 
 
 @pytest.mark.parametrize("plan,name", [("12", "onehot_smfmac_staged_32x64"), ("12k2", "onehot_smfmac_staged_32x64_k2"),
