@@ -71,7 +71,10 @@ struct Args {
     FastDiv div_ow, div_oh, div_cin, div_kw;
     int32_t tiles_m;
     int64_t wave_tiles;
-    FastDiv div_runs;        // (dg_sparse_staged_kernel.h) by the 32-byte runs of packed codes per filter tap
+    // dg_sparse_staged_kernel.h: division by the 32-byte runs of packed codes per filter tap; tile numbering in bands
+    FastDiv div_runs, div_band, div_last;
+    int32_t tiles_n, band_log2, m_log2;
+    uint32_t band_tiles;
 };
 
 struct SplitArgs {

@@ -56,8 +56,25 @@ smfmac_staged_kernel(Args a)
     if (SKW == 1 && !active) return;                       // whole wavefronts leave; no barrier follows on this path
     const int64_t wave_tile = active ? my_tile : 0;        // (an idle wavefront of a shared workgroup adds nothing)
     const int r = lane & 31, h = lane >> 5;
-    const int m0 = (int)(wave_tile % a.tiles_m) * (WM * 32);
-    const int n0 = (int)(wave_tile / a.tiles_m) * (WN * 32);
+    // Tiles are numbered in bands of 2^band_log2 pixel tiles; inside a band groups of 2^m_log2 channel tiles (the four
+    // wavefronts of a workgroup, which then share their pixels' loads) follow each other along the pixels first.  The
+    // tiles in flight on an XCD at one time (consecutive numbers, see xcd_contiguous) then form a patch about as high
+    // as it is wide, whose weight rows and pixels that XCD's L2 fetches once (numbered along the channels first, every
+    // column of tiles streamed all of the weights through the L2 again: 4.3 times the operands' bytes on an 8192-cube).
+    int m_tile, n_tile;
+    {
+        const uint32_t t = (uint32_t)wave_tile, band = fdiv(t, a.div_band), t_in = t - band * a.band_tiles;
+        const uint32_t g = t_in >> a.m_log2, mi = t_in & ((1u << a.m_log2) - 1u);
+        const int first = (int)band << a.band_log2, width = min(1 << a.band_log2, a.tiles_n - first);
+        uint32_t mg;
+        if (width == 1 << a.band_log2)
+            mg = g >> a.band_log2;
+        else
+            mg = fdiv(g, a.div_last);                       // (the last band, narrower)
+        n_tile = first + (int)(g - mg * (uint32_t)width);
+        m_tile = (int)((mg << a.m_log2) + mi);
+    }
+    const int m0 = m_tile * (WM * 32), n0 = n_tile * (WN * 32);
     const int cq = p.Cin / 4;                               // packed bytes per pixel
     // this wavefront's runs of K: [g0, g1)
     const int runs = p.K / 128, share = (runs + SKW - 1) / SKW;
@@ -257,6 +274,13 @@ inline void launch_sparse_staged(const DgProblem &p, const Pools &pools, const P
     a.div_ow = make_div((uint32_t)p.OW), a.div_oh = make_div((uint32_t)p.OH);
     a.div_cin = make_div((uint32_t)p.Cin), a.div_kw = make_div((uint32_t)p.KW);
     a.div_runs = make_div((uint32_t)(p.Cin / 128));
+    a.tiles_n = (int32_t)((p.N + q.wn * 32 - 1) / (q.wn * 32));
+    a.band_log2 = 3;                                       // bands of 8 pixel tiles
+    a.m_log2 = a.tiles_m % 4 == 0 ? 2 : 0;                 // (unshared tiles: a workgroup's four wavefronts)
+    a.band_tiles = (uint32_t)a.tiles_m << a.band_log2;
+    a.div_band = make_div(a.band_tiles);
+    const int last = a.tiles_n & ((1 << a.band_log2) - 1);
+    a.div_last = make_div((uint32_t)(last ? last : 1));
     const int tpw = 4 / q.skw;
     const dim3 grid((unsigned)((wave_tiles + tpw - 1) / tpw));
 #define DG_STAGED(WM, WN, SKW) hipLaunchKernelGGL((smfmac_staged_kernel<WM, WN, SKW>), grid, dim3(256), 0, stream, a)
