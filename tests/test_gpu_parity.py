@@ -914,7 +914,9 @@ def test_stationary_weight_kernel(K, waves, monkeypatch):
         case = GpuCase(c, levels=(lw, la), entry=entry)
         assert dg.dg_conv_codes_kernel_name(case.lut, case.desc, "onehot_smfmac") == "codes_onehot_smfmac_ws_32xK"
         acc = oracle.conv2d(c.Wc, c.Ac, lw, la)
-        Xc = torch.from_numpy(c.Ac).cuda()
+        # (garbage above bit 1 of every code byte: the packing drops it, as the packing kernel does)
+        dirty = c.Ac | (np.random.default_rng(H + Cout).integers(0, 64, size=c.Ac.shape, dtype=np.uint8) << 2)
+        Xc = torch.from_numpy(dirty).cuda()
         got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, variant="onehot_smfmac")
         torch.cuda.synchronize()
         _assert_same(got.cpu().numpy(), acc, f"ws conv on codes {(B, H, W, K, Cout)}")
@@ -980,6 +982,20 @@ def test_staged_sparse_kernel(plan, name, monkeypatch):
     # channels that are not whole 32-byte runs: the direct-load kernel of the same tile
     c = wl.small_conv(1, 8, 8, 64, 32, 3, 3, (1, 1), (1, 1), seed=1)
     assert "staged" not in GpuCase(c, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac")
+    # seeded random geometries: filter, stride, padding, image, channels, batch
+    rng = np.random.default_rng(77 + len(plan))
+    for _ in range(12):
+        KH, KW = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        sh, sw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        ph, pw = int(rng.integers(0, KH)), int(rng.integers(0, KW))
+        H, W = int(rng.integers(KH, 20)), int(rng.integers(KW, 20))
+        Cin, Cout, B = int(rng.choice([128, 256, 384])), int(rng.integers(1, 140)), int(rng.integers(1, 4))
+        c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, (sh, sw), (ph, pw), seed=int(rng.integers(1 << 30)))
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        assert case.kernel_name("onehot_smfmac") == name
+        want = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=(sh, sw), pad=(ph, pw))
+        _assert_same(case.run("onehot_smfmac").cpu().numpy(), want,
+                     f"staged conv B={B} {H}x{W} Cin={Cin} Cout={Cout} {KH}x{KW} s=({sh},{sw}) p=({ph},{pw}) plan {plan}")
 
 
 @pytest.mark.parametrize("waves", [0, 1, 3, 8])
