@@ -1,16 +1,17 @@
-// 2-bit table kernel on the sparse matrix instruction, tiles as in dg_onehot_kernel.h (BITS = 20, one wavefront per
-// tile, all of K), with the packed operands fetched in WHOLE 32-BYTE RUNS and handed to their lanes through LDS.
+// 2-bit table kernel on the sparse matrix instruction (operand layout, index register and row-pair table as in
+// dg_onehot_kernel.h, BITS = 20), with the packed operands fetched in WHOLE 32-BYTE RUNS and handed to their lanes
+// through LDS.  A wavefront owns a tile of 32 (or 64) channels x 64 ... 192 pixels and walks all of K, or a share of it.
 //
 // Why: the matrix instruction wants lane (r, half) to hold words of row r, so a direct load has 32 lanes reading 8
 // bytes each from 32 different rows.  The address unit of a compute unit takes such a load one cache line per cycle
 // (dg_lds_dma.h): 64 cycles and more for 512 or 1024 bytes, and on a GEMM with K = 8192 it was busy 93 % of the
 // kernel's time (counters TA_TA_BUSY / TCP_GATE_EN) while the matrix pipe idled -- the loads, not the arithmetic, set
 // the time.  Here two neighbouring lanes read the two 16-byte halves of one row's run, so a load instruction covers 32
-// rows x 32 bytes, at half the address cycles per byte (30 % busy on the same GEMM).  The loads write LDS directly
+// rows x 32 bytes, at half the address cycles per byte (26 % busy on the same GEMM).  The loads write LDS directly
 // (lane l's 16 bytes land at the instruction's LDS base + 16 l; no registers are held while they are in flight), into
-// staging rows of the wavefront's own, from which lane (r, half) reads its 8
-// bytes per 64 positions of K.  Staging rows belong to one wavefront, so no barrier is involved: a wavefront waits
-// for its own loads (vmcnt) before it reads a run, and runs alternate between two buffers, fetched two ahead.
+// staging rows of the wavefront's own, from which lane (r, half) reads its 8 bytes per 64 positions of K.  Staging
+// rows belong to one wavefront, so no barrier is involved: a wavefront waits for its own loads (vmcnt) before it reads
+// a run, and runs alternate between two buffers, fetched two ahead.
 // The multiplication is one software pipeline over all of K: the dense operands of a step are made between the matrix
 // instructions of the step before, across chunks, runs and filter taps alike.
 //
