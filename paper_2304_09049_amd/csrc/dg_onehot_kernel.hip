@@ -199,11 +199,12 @@ bool staged_takes(const DgProblem &t)
 // The staged kernel's tiles are one block of 32 channels high -- the weight operand of a block, the expensive one,
 // then serves every pixel block of the tile -- and 64, 128 or 192 pixels wide; at equal area they were measured 3 - 20 %
 // faster than the 64-row tiles on every layer tried, so a plan made for the 64-row tiles is run on the tile of the
-// same area (64 x 32 -> 32 x 64, 64 x 64 -> 32 x 128, with the same sharing of K).  Instead of 64 x 128 there is
-// 32 x 192, taken where the busiest SIMD then has no more blocks to do (2 % faster at equal work per SIMD, 15 % where
-// 64 x 128 tiles come to 1.5 per SIMD and these to 2); otherwise 64 x 128 itself runs staged.
-// DG_ONEHOT_PLAN = 12 | 14 [k2 | k4] | 16 | 24 forces a staged tile (32 x 64, 32 x 128, 32 x 192, 64 x 128); the other
-// values of that override force the direct-load kernels.
+// same area (64 x 32 -> 32 x 64, 64 x 64 -> 32 x 128, with the same sharing of K).  Beside 64 x 128 there are 32 x 192
+// and 32 x 224, taken where they leave the busiest SIMD fewer blocks to do (the 1568 pixel blocks x 8 channel blocks of
+// the 56x56x256 -> 256 layer at batch 16: 1568 tiles of 64 x 128 are two per SIMD for half the SIMDs, 16 blocks; 1792
+// tiles of 32 x 224 are 14; measured 54.6 and 49.2 us).
+// DG_ONEHOT_PLAN = 12 | 14 [k2 | k4] | 16 | 17 | 24 forces a staged tile (32 x 64, 32 x 128, 32 x 192, 32 x 224,
+// 64 x 128); the other values of that override force the direct-load kernels.
 Plan sparse_plan(const dg_lut *lut, const DgProblem &t)
 {
     Plan q = plan_for(lut, t, SPARSE, sparse_tile_hint(lut, t));
@@ -213,17 +214,22 @@ Plan sparse_plan(const dg_lut *lut, const DgProblem &t)
         const int v = atoi(force), k = strstr(force, "k4") ? 4 : (strstr(force, "k2") ? 2 : 1);
         if (v == 12 || v == 14) q.staged = true, q.split = false, q.wm = 1, q.wn = v == 12 ? 2 : 4, q.skw = k, q.ch = 2;
         if (v == 16 || v == 24) q.staged = true, q.split = false, q.wm = v == 16 ? 1 : 2, q.wn = v == 16 ? 6 : 4, q.skw = 1, q.ch = 2;
+        if (v == 17) q.staged = true, q.split = false, q.wm = 1, q.wn = 7, q.skw = 1, q.ch = 2;
         return q;
     }
     if (q.split || q.wm != 2) return q;
     if (q.wn <= 2) {
         q.staged = true, q.wm = 1, q.wn *= 2, q.ch = 2;
     } else if (q.wn == 4 && q.skw == 1) {
+        // 64 x 128, 32 x 192 or 32 x 224: the one that leaves the busiest SIMD the fewest blocks (ties: 32 x 192, which
+        // at equal work per SIMD measured 2 % faster than the others, then 64 x 128)
         const int64_t simds = dg_simd_count();
         const int64_t blocks_24 = (tile_count(t, 2, 4) + simds - 1) / simds * 8;
         const int64_t blocks_16 = (tile_count(t, 1, 6) + simds - 1) / simds * 6;
+        const int64_t blocks_17 = (tile_count(t, 1, 7) + simds - 1) / simds * 7;
         q.staged = true, q.ch = 2;
-        if (blocks_16 <= blocks_24) q.wm = 1, q.wn = 6;
+        if (blocks_16 <= blocks_24 && blocks_16 <= blocks_17) q.wm = 1, q.wn = 6;
+        else if (blocks_17 < blocks_24) q.wm = 1, q.wn = 7;
     }
     return q;
 }
@@ -280,6 +286,7 @@ const char *dg_sparse_config_name(const dg_lut *lut, const DgProblem &p)
             {"onehot_smfmac_staged_32x64_k2", "onehot_smfmac_staged_32x128_k2"},
             {"onehot_smfmac_staged_32x64_k4", "onehot_smfmac_staged_32x128_k4"}};
         if (q.wm == 2) return "onehot_smfmac_staged_64x128";
+        if (q.wn == 7) return "onehot_smfmac_staged_32x224";
         if (q.wn == 6) return "onehot_smfmac_staged_32x192";
         return staged_names[q.skw == 4 ? 2 : (q.skw == 2 ? 1 : 0)][q.wn == 4 ? 1 : 0];
     }

@@ -1,6 +1,6 @@
 // 2-bit table kernel on the sparse matrix instruction (operand layout, index register and row-pair table as in
 // dg_onehot_kernel.h, BITS = 20), with the packed operands fetched in WHOLE 32-BYTE RUNS and handed to their lanes
-// through LDS.  A wavefront owns a tile of 32 (or 64) channels x 64 ... 192 pixels and walks all of K, or a share of it.
+// through LDS.  A wavefront owns a tile of 32 (or 64) channels x 64 ... 224 pixels and walks all of K, or a share of it.
 //
 // Why: the matrix instruction wants lane (r, half) to hold words of row r, so a direct load has 32 lanes reading 8
 // bytes each from 32 different rows.  The address unit of a compute unit takes such a load one cache line per cycle
@@ -43,7 +43,7 @@ smfmac_staged_kernel(Args a)
     // shared tiles' sums [tile][block][sum register][lane]
     constexpr int STAGE_BYTES = 4 * 2 * BUF, SUM_BYTES = SKW > 1 ? TPW * NB * 4096 : 0;
     __shared__ uint4 s_mem[(STAGE_BYTES > SUM_BYTES ? STAGE_BYTES : SUM_BYTES) / 16];
-    static_assert(sizeof(s_mem) <= 64 * 1024 - 256, "two workgroups per compute unit");
+    static_assert(sizeof(s_mem) <= 80 * 1024 - 256, "two workgroups per compute unit (160 KB of LDS)");
     int32_t *s_acc = (int32_t *)s_mem;
     // the narrower tiles have the registers for a second set of kept bytes, (0, 1), which spares the odd codes' shift
     constexpr bool SHIFT_ODD = WM * WN >= 8;
@@ -286,6 +286,7 @@ inline void launch_sparse_staged(const DgProblem &p, const Pools &pools, const P
     const dim3 grid((unsigned)((wave_tiles + tpw - 1) / tpw));
 #define DG_STAGED(WM, WN, SKW) hipLaunchKernelGGL((smfmac_staged_kernel<WM, WN, SKW>), grid, dim3(256), 0, stream, a)
     if (q.wm == 2) DG_STAGED(2, 4, 1);
+    else if (q.wn == 7) DG_STAGED(1, 7, 1);
     else if (q.wn == 6) DG_STAGED(1, 6, 1);
     else if (q.wn == 4 && q.skw == 4) DG_STAGED(1, 4, 4);
     else if (q.wn == 4 && q.skw == 2) DG_STAGED(1, 4, 2);

@@ -225,7 +225,8 @@ def test_kernel_names_need_no_gpu():
     large = dg.conv_desc(16, 56, 56, 256, 256, 3, 3, (1, 1), (1, 1))
     assert dg.dg_conv_codes_kernel_name(lut, small) == "codes_onehot_mfma_splitk_s9"
     assert dg.dg_conv_codes_kernel_name(lut, small, "onehot_smfmac") == dg.dg_conv_kernel_name(lut, small, "onehot_smfmac")
-    assert dg.dg_conv_codes_kernel_name(lut, large) == dg.dg_conv_kernel_name(lut, large) == "onehot_smfmac_staged_64x128"
+    # (1568 pixel blocks x 8 channel blocks: 32 x 224 tiles leave the busiest SIMD 14 blocks, 64 x 128 tiles 16)
+    assert dg.dg_conv_codes_kernel_name(lut, large) == dg.dg_conv_kernel_name(lut, large) == "onehot_smfmac_staged_32x224"
     assert dg.dg_gemm_codes_kernel_name(lut, 64, 196, 576) == "codes_onehot_mfma_splitk_s9"
     assert dg.dg_gemm_codes_kernel_name(lut, 8192, 1, 8192) == "codes_smalln"
     # 256 row blocks would each pack the activations for themselves: two kernels unless the fused form is asked for by name

@@ -941,7 +941,8 @@ def test_stationary_weight_kernel(K, waves, monkeypatch):
 @pytest.mark.parametrize("plan,name", [("12", "onehot_smfmac_staged_32x64"), ("12k2", "onehot_smfmac_staged_32x64_k2"),
                                        ("12k4", "onehot_smfmac_staged_32x64_k4"), ("14", "onehot_smfmac_staged_32x128"),
                                        ("14k2", "onehot_smfmac_staged_32x128_k2"), ("14k4", "onehot_smfmac_staged_32x128_k4"),
-                                       ("16", "onehot_smfmac_staged_32x192"), ("24", "onehot_smfmac_staged_64x128")])
+                                       ("16", "onehot_smfmac_staged_32x192"), ("17", "onehot_smfmac_staged_32x224"),
+                                       ("24", "onehot_smfmac_staged_64x128")])
 def test_staged_sparse_kernel(plan, name, monkeypatch):
     """The tiled sparse-instruction kernel whose operands go through LDS in 32-byte runs (Cin % 128 == 0), every tile
     shape forced: convolutions with a padded 3x3 window (taps outside the image at every border), a stride, one, two and
