@@ -193,6 +193,7 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *   DG_ONEHOT_STAGED "0" keeps the staged kernel out altogether (the direct-load kernels run instead)
  *   DG_WS_WAVES      target number of wavefronts of the "ws" kernel (default: one per SIMD)
  *   DG_FEWN_WAVES    wavefronts per workgroup of the "fewn" kernel (1..8)
+ *   DG_FEWN_ROWS     weight rows per workgroup of the "fewn" kernel (16 or 32)
  *   DG_ONEHOT_WAVES  target number of wavefronts of the split-K kernel (default 2048)
  *   DG_PERM_PLAN     index of the permute kernel's tile shape
  */
