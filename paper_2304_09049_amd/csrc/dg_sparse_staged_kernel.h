@@ -24,6 +24,29 @@
 
 namespace dgoh {
 
+// The dense operands of all WM weight blocks for word `t` of `w` (as sparse_dense_rows_shared, but with the opaque
+// statement that keeps the indices pre-multiplied NOT volatile, so that the scheduler may move these instructions
+// between matrix instructions).
+template <int WM, class W>
+__device__ __forceinline__ void dense_rows_movable(const uint2 *table, const W &w, int t, uint32_t pick, v8i (&out)[WM][2])
+{
+#pragma unroll
+    for (int u = 0; u < WM; ++u) {
+        const uint32_t w0 = t ? w.ca[u].y : w.ca[u].x, w1 = t ? w.ca1[u].y : w.ca1[u].x;
+        const uint32_t v = __builtin_amdgcn_perm(w1, w0, pick), s2 = v >> 2;
+        uint32_t e = ((v & 0x03030303u) | (s2 & 0x0C0C0C0Cu)) << 3;          // byte b: 8 * (code 4b | code 4b+2 << 2)
+        uint32_t o = ((s2 & 0x03030303u) | ((v >> 4) & 0x0C0C0C0Cu)) << 3;   // byte b: 8 * (code 4b+1 | code 4b+3 << 2)
+        asm("" : "+v"(e), "+v"(o));
+        const char *base = (const char *)table;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const uint2 x = *(const uint2 *)(base + ((e >> (8 * b)) & 255u)), y = *(const uint2 *)(base + ((o >> (8 * b)) & 255u));
+            out[u][0][2 * b] = (int)x.x, out[u][0][2 * b + 1] = (int)x.y;
+            out[u][1][2 * b] = (int)y.x, out[u][1][2 * b + 1] = (int)y.y;
+        }
+    }
+}
+
 // SKW = 1: a wavefront walks all of K.  SKW = 2 or 4 (layers whose tiles alone would leave SIMDs idle): SKW wavefronts
 // of the workgroup share a tile and split K between them in contiguous runs; their sums meet in LDS by integer atomics
 // (exact in any order) and each of them stores a share of the tile's blocks, as in dg_onehot_kernel.h.
@@ -46,7 +69,7 @@ smfmac_staged_kernel(Args a)
     static_assert(sizeof(s_mem) <= 80 * 1024 - 256, "two workgroups per compute unit (160 KB of LDS)");
     int32_t *s_acc = (int32_t *)s_mem;
     // the narrower tiles have the registers for a second set of kept bytes, (0, 1), which spares the odd codes' shift
-    constexpr bool SHIFT_ODD = WM * WN >= 8;
+    constexpr bool SHIFT_ODD = WM * WN >= 7;
     const DgProblem &p = a.p;
     const int lane = threadIdx.x & 63, w4 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ks = w4 % SKW, tw = w4 / SKW;                 // this wavefront's share of K, and its tile within the workgroup
@@ -164,11 +187,15 @@ smfmac_staged_kernel(Args a)
     v4i ones[WN], ones_odd[SHIFT_ODD ? 1 : WN];
     auto step = [&](const v8i (&dn)[WM][2], const Words2 &w, int t, v8i (&next)[WM][2], const Words2 &nw, int nt) {
         constexpr int MN = WM * WN;
+        // the next step's dense operands: written here, spread by the scheduling groups below a few instructions at a
+        // time between this step's matrix instructions, in whose shadow they then issue
+        dense_rows_movable(s_rows, nw, nt, pick, next);
         int odd_ix[SHIFT_ODD ? WN : 1];
         if constexpr (SHIFT_ODD) {
 #pragma unroll
             for (int bn = 0; bn < WN; ++bn) odd_ix[bn] = (int)(word(w.cb[bn], t) >> 2);
         }
+        constexpr int PER = (31 * WM + (SHIFT_ODD ? WN : 0) + 2 * MN - 1) / (2 * MN);      // other instructions per matrix instruction
 #pragma unroll
         for (int i = 0; i < 2 * MN; ++i) {
             const int par = i / MN, bm = (i % MN) / WN, bn = i % WN;
@@ -178,12 +205,7 @@ smfmac_staged_kernel(Args a)
                 acc[bm][bn] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones[bn], dn[bm][par], acc[bm][bn],
                                                                       par ? odd_ix[SHIFT_ODD ? bn : 0] : (int)word(w.cb[bn], t), 0, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            const int u0 = i * WM / MN, u1 = (i + 1) * WM / MN;      // the weight blocks' units go over the first instructions
-#pragma unroll
-            for (int u = u0; u < u1 && u < WM; ++u) {
-                sparse_dense_rows_shared(s_rows, word(nw.ca[u], nt), word(nw.ca1[u], nt), pick, next[u][0], next[u][1]);
-                __builtin_amdgcn_sched_group_barrier(0x102, 31, 0);              // 23 VALU and 8 LDS reads
-            }
+            __builtin_amdgcn_sched_group_barrier(0x102, PER, 0);
         }
     };
 
