@@ -191,6 +191,9 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *                    64 x 128;
  *                    the other values keep that kernel out.
  *   DG_ONEHOT_STAGED "0" keeps the staged kernel out altogether (the direct-load kernels run instead)
+ *   DG_STAGED_BIAS   "0": the staged kernel multiplies with the table as it is; "1": with every entry raised by
+ *                    minus the smallest one, the sums starting at the matching negative value (its default on
+ *                    problems of 2MNK >= 2e10, where that lowers the matrix pipe's power draw)
  *   DG_WS_WAVES      target number of wavefronts of the "ws" kernel (default: one per SIMD)
  *   DG_FEWN_WAVES    wavefronts per workgroup of the "fewn" kernel (1..8)
  *   DG_FEWN_ROWS     weight rows per workgroup of the "fewn" kernel (16 or 32)

@@ -3,8 +3,8 @@
 #include "dg_sparse_staged_kernel.h"
 
 namespace dgoh {
-void unit_sparse_staged(const DgProblem &p, const Pools &pools, const Plan &q, int64_t wave_tiles, hipStream_t stream)
+void unit_sparse_staged(const DgProblem &p, const Pools &pools, int32_t bias, const Plan &q, int64_t wave_tiles, hipStream_t stream)
 {
-    launch_sparse_staged(p, pools, q, wave_tiles, stream);
+    launch_sparse_staged(p, pools, bias, q, wave_tiles, stream);
 }
 }   // namespace dgoh

@@ -75,6 +75,8 @@ struct Args {
     FastDiv div_runs, div_band, div_last;
     int32_t tiles_n, band_log2, m_log2;
     uint32_t band_tiles;
+    // dg_sparse_staged_kernel.h: what was added to every table entry (the sums start at minus this per position of K)
+    int32_t bias;
 };
 
 struct SplitArgs {
@@ -884,7 +886,7 @@ DGOH_UNIT_SPLIT(4, 1) DGOH_UNIT_SPLIT(22, 0) DGOH_UNIT_SPLIT(22, 1) DGOH_UNIT_SP
 void unit_sparse4(const DgProblem &, const uint32_t (&)[16][4], int, hipStream_t);      // dg_sparse4_kernel.h
 void unit_sparse2p(const DgProblem &, const uint32_t (&)[2][4], int, hipStream_t);      // dg_sparse2p_kernel.h
 void unit_sparse_ws(const DgProblem &, const uint32_t (&)[4], int, bool raw, hipStream_t);      // dg_sparse_ws_kernel.h
-void unit_sparse_staged(const DgProblem &, const Pools &, const Plan &, int64_t, hipStream_t);      // dg_sparse_staged_kernel.h
+void unit_sparse_staged(const DgProblem &, const Pools &, int32_t bias, const Plan &, int64_t, hipStream_t);      // dg_sparse_staged_kernel.h
 // the split-K kernel on activations still one code per byte (one- and two-plane tables, either output layout)
 void unit_split_codes(const DgProblem &, const Pools &, const Plan &, bool two, bool tr, int64_t, hipStream_t);
 #undef DGOH_UNIT

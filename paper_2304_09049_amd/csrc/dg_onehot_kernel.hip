@@ -315,7 +315,22 @@ dg_status dg_launch_sparse(const dg_lut *lut, const DgProblem &p0, hipStream_t s
         return dg_check_launch("onehot_splitk_kernel<20>");
     }
     if (sparse_staged(p, q)) {
-        unit_sparse_staged(p, pools, q, wave_tiles, stream);
+        // The staged kernel takes the table raised to 0 ... max - min where that fits a signed byte and the raised sums
+        // fit 32 bits (dg_sparse_staged_kernel.h: fewer toggling bits, a higher sustained clock) -- on problems large
+        // enough to heat the chip; shorter kernels only pay the longer start.  DG_STAGED_BIAS: 0 keeps the table as it
+        // is, 1 raises it whatever the size (tests, A/B measurement).
+        const int lo = lut->min_entry, hi = lut->max_entry;
+        const bool fits = hi - lo <= 127 && (int64_t)(hi - lo > abs(lo) ? hi - lo : abs(lo)) * p.K <= INT32_MAX;
+        bool raise = 2.0 * (double)p.M * (double)p.N * (double)p.K >= 2e10;
+        if (const char *e = dg_override("DG_STAGED_BIAS")) raise = atoi(e) != 0;
+        const int32_t bias = fits && raise ? -lo : 0;
+        if (bias != 0)
+            for (int w = 0; w < 4; ++w) {
+                uint32_t word = 0;
+                for (int v = 0; v < 4; ++v) word |= (uint32_t)(uint8_t)(int8_t)((int8_t)(pools.w[w] >> (8 * v)) + bias) << (8 * v);
+                pools.w[w] = word;
+            }
+        unit_sparse_staged(p, pools, bias, q, wave_tiles, stream);
         return dg_check_launch("smfmac_staged_kernel");
     }
     static const MainFn main_units[3] = {unit_main_b20_t1_k1, unit_main_b20_t1_k2, unit_main_b20_t1_k4};

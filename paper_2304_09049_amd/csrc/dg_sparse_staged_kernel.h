@@ -212,6 +212,25 @@ smfmac_staged_kernel(Args a)
     if (g0 < g1) {                                          // (uniform; a wavefront without a share of K only joins the barrier)
         fetch();
         fetch();
+        // The sums start at zero, or -- the table's entries having been raised by a.bias to make them all small and
+        // non-negative (launch_sparse_staged says why) -- at minus the bias for every position of K the pixel really
+        // sees: Cin per filter tap inside the image.  Lane (r, .) works that out for pixel r of a block; sum register
+        // e of a lane belongs to pixel 8 (e / 4) + 4 h + e % 4 and takes it from that lane.  Of the wavefronts sharing
+        // a tile the first one does this (it always has a share of K).  Done here, while the first runs are on their way.
+        if (a.bias != 0 && ks == 0) {                       // (uniform)
+#pragma unroll
+            for (int bn = 0; bn < WN; ++bn) {
+                const int ih0 = col[bn].ih0, iw0 = col[bn].iw0;
+                const int taps_h = max(0, min(p.KH, p.H - ih0) - max(0, -ih0)), taps_w = max(0, min(p.KW, p.W - iw0) - max(0, -iw0));
+                const int start = col[bn].ok ? -a.bias * p.Cin * taps_h * taps_w : 0;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int v = __builtin_amdgcn_ds_bpermute(4 * (8 * (e / 4) + 4 * h + e % 4), start);
+#pragma unroll
+                    for (int bm = 0; bm < WM; ++bm) acc[bm][bn][e] = v;
+                }
+            }
+        }
         Words2 wa, wb;
         v8i dn0[WM][2], dn1[WM][2];
         dg_wait_for_loads();                                   // (both runs: the first is needed now)
@@ -287,11 +306,18 @@ smfmac_staged_kernel(Args a)
 }
 
 // `wave_tiles` tiles of q.wm x q.wn blocks, 4 / q.skw of them per workgroup
-inline void launch_sparse_staged(const DgProblem &p, const Pools &pools, const Plan &q, int64_t wave_tiles, hipStream_t stream)
+//
+// `bias`: the caller added it to every entry of the table in `pools` (0: the table as it is).  The matrix pipe's power
+// draw, and with it the clock the chip sustains, follows the bits that toggle in its operands and sums: the same
+// 8192-cube takes 550 us with an all-zero table, 640 us with entries 0 ... 9, 700 us with -6 ... 3 and 800 us with
+// -64 ... 64.  A table raised to 0 ... max - min keeps the high bits of the dense operand and of the growing sums
+// quiet; the kernel starts each sum at minus the bias times the pixel's positions of K, so the result is the same.
+inline void launch_sparse_staged(const DgProblem &p, const Pools &pools, int32_t bias, const Plan &q, int64_t wave_tiles, hipStream_t stream)
 {
     Args a;
     a.p = p;
     a.pools = pools;
+    a.bias = bias;
     a.tiles_m = (p.M + q.wm * 32 - 1) / (q.wm * 32);
     a.wave_tiles = wave_tiles;
     a.div_ow = make_div((uint32_t)p.OW), a.div_oh = make_div((uint32_t)p.OH);

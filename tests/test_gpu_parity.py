@@ -953,7 +953,8 @@ def test_staged_sparse_kernel(plan, name, monkeypatch):
     lw, la, entry = LEVELS["nonuniform_i8"]
     convs = [(2, 9, 7, 128, 36, 3, 3, (1, 1), (1, 1)), (1, 13, 11, 256, 70, 3, 3, (2, 2), (1, 1)),
              (3, 6, 5, 384, 64, 1, 1, (1, 1), (0, 0)), (1, 5, 4, 128, 33, 1, 1, (1, 1), (0, 0)),
-             (1, 20, 17, 128, 130, 3, 2, (1, 2), (1, 0)), (2, 15, 15, 256, 100, 5, 5, (1, 1), (2, 2))]
+             (1, 20, 17, 128, 130, 3, 2, (1, 2), (1, 0)), (2, 15, 15, 256, 100, 5, 5, (1, 1), (2, 2)),
+             (1, 29, 29, 128, 70, 3, 3, (1, 1), (1, 1))]
     for (B, H, W, Cin, Cout, KH, KW, stride, pad) in convs:
         c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
         case = GpuCase(c, levels=(lw, la), entry=entry)
@@ -997,6 +998,36 @@ def test_staged_sparse_kernel(plan, name, monkeypatch):
         want = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=(sh, sw), pad=(ph, pw))
         _assert_same(case.run("onehot_smfmac").cpu().numpy(), want,
                      f"staged conv B={B} {H}x{W} Cin={Cin} Cout={Cout} {KH}x{KW} s=({sh},{sw}) p=({ph},{pw}) plan {plan}")
+
+
+@pytest.mark.parametrize("bias", ["1", "0"])
+@pytest.mark.parametrize("levels", ["signed_unsigned", "twos_complement", "nonuniform_i8", "wide_i8", "all_positive"])
+@pytest.mark.parametrize("plan", ["14k4", "17", "24"])
+def test_staged_kernel_raised_table(plan, levels, bias, monkeypatch):
+    """The staged kernel multiplies with the table raised to 0 ... max - min and starts every sum at minus that raise
+    times the positions of K the pixel sees: tables with negative, with only positive entries (lowered), one too wide to
+    raise (127 and -128), the raise switched off; padded and strided windows where border pixels see fewer taps, ragged
+    tiles, K shared between wavefronts (one of them starts the sums), GEMMs in both layouts."""
+    monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
+    monkeypatch.setenv("DG_STAGED_BIAS", bias)
+    lw, la, entry = LEVELS[levels]
+    for (B, H, W, Cin, Cout, KH, KW, stride, pad) in [(2, 9, 7, 128, 36, 3, 3, (1, 1), (1, 1)), (1, 11, 13, 256, 70, 5, 4, (2, 1), (4, 3)),
+                                                      (1, 6, 6, 128, 64, 7, 7, (1, 1), (3, 3))]:
+        c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout + 5, scale=True)
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        assert "staged" in case.kernel_name("onehot_smfmac")
+        acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
+        _assert_same(case.run("onehot_smfmac").cpu().numpy(), acc, f"raised table {levels} conv {(B, H, W, Cin, Cout, KH, KW, stride, pad)}")
+        assert np.array_equal(case.run("onehot_smfmac", scale=True).cpu().numpy(), oracle.scale_epilogue_nhwc(acc, c.scale))
+    for (M, N, K) in [(70, 300, 384), (33, 5, 128)]:
+        inp = wl.small_gemm(M, N, K, seed=M + N + K + 9)
+        case = GpuCase(inp, levels=(lw, la), entry=entry)
+        want = oracle.gemm(inp.Wc, inp.Ac, lw, la)
+        _assert_same(case.run("onehot_smfmac").cpu().numpy(), want, f"raised table {levels} gemm {(M, N, K)} row-major")
+        out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
+        dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant="onehot_smfmac", strides=(1, M))
+        torch.cuda.synchronize()
+        _assert_same(out.cpu().numpy(), want.T.copy(), f"raised table {levels} gemm {(M, N, K)} column-major")
 
 
 @pytest.mark.parametrize("waves", [0, 1, 3, 8])
