@@ -195,6 +195,8 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *                    minus the smallest one, the sums starting at the matching negative value (its default on
  *                    problems of 2MNK >= 2e10, where that lowers the matrix pipe's power draw)
  *   DG_WS_WAVES      target number of wavefronts of the "ws" kernel (default: one per SIMD)
+ *   DG_WS_COUNT_STORES "0": the "ws" kernel that packs codes itself waits for its stores too whenever it waits for
+ *                    staged codes (by default it counts the stores it has issued and lets them drain)
  *   DG_FEWN_WAVES    wavefronts per workgroup of the "fewn" kernel (1..8)
  *   DG_FEWN_ROWS     weight rows per workgroup of the "fewn" kernel (16 or 32)
  *   DG_ONEHOT_WAVES  target number of wavefronts of the split-K kernel (default 2048)

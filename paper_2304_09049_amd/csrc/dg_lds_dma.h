@@ -30,6 +30,24 @@ __device__ __forceinline__ void dg_wait_for_loads()
 {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(OUTSTANDING) : "memory");
 }
+// The same with a count known at run time only (the same in every lane), rounded down to a multiple of 4 (waiting for
+// more than asked is always correct).  The counter counts every vector memory instruction of the wavefront, stores
+// included, and they complete in the order they were issued: a kernel that stores between its staged loads allows for
+// the stores it knows it has issued since.
+__device__ __forceinline__ void dg_wait_for_loads_at_most(int n)
+{
+    if (n >= 40) dg_wait_for_loads<40>();
+    else if (n >= 36) dg_wait_for_loads<36>();
+    else if (n >= 32) dg_wait_for_loads<32>();
+    else if (n >= 28) dg_wait_for_loads<28>();
+    else if (n >= 24) dg_wait_for_loads<24>();
+    else if (n >= 20) dg_wait_for_loads<20>();
+    else if (n >= 16) dg_wait_for_loads<16>();
+    else if (n >= 12) dg_wait_for_loads<12>();
+    else if (n >= 8) dg_wait_for_loads<8>();
+    else if (n >= 4) dg_wait_for_loads<4>();
+    else dg_wait_for_loads<0>();
+}
 // (the numeric value of a pointer into LDS is its LDS byte address)
 __device__ __forceinline__ uint32_t dg_lds_address(const void *p)
 {

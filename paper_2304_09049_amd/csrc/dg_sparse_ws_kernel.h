@@ -15,6 +15,8 @@
 // the pixels' words are fetched from memory once and the halves of an output row are written together.
 #pragma once
 
+#include <type_traits>
+
 #include "dg_lds_dma.h"
 #include "dg_onehot_kernel.h"
 
@@ -27,6 +29,7 @@ struct WsArgs {
     int32_t streams;             // runs of pixel blocks; wavefronts = row_blocks * streams
     int32_t run, longer;         // the first `longer` runs have run + 1 pixel blocks, the others `run`
     FastDiv div_row_blocks;
+    int32_t count_stores;        // RAW: 0 = a wait for staged codes also waits for the stores issued so far (A/B measurement)
 };
 
 // T = K / 32: matrix-instruction pairs per 32 x 32 block; a lane half reads T words of a pixel (or weight row).
@@ -48,7 +51,13 @@ struct WsArgs {
 // block are staged (dg_lds_dma.h): 2 T neighbouring lanes read the 32 T bytes of one pixel straight into LDS, two
 // blocks in flight per wavefront, and lane (pixel, half) reads its 16-byte segments from there and packs each into a
 // word.  Slot j of a staged pixel holds its segment j ^ (pixel % 2T): the exchange spreads the 32 pixels' reads of one
-// segment over the LDS banks.  All of a group's blocks are packed before the group's first store, as above.
+// segment over the LDS banks.
+// What a timeline of this form showed (timestamps per wavefront, 56x56x256 -> 64 at batch 32): writing the 25.7 MB of
+// output takes 5.2 us whatever the store pattern, and the kernel's time is that plus the time to the first stores.  So
+// the weight rows are asked for BEFORE the first block's codes (loads complete in issue order, and the weights waited
+// behind two blocks of codes), the second block only after the dense operands are built (the address unit serves
+// every wavefront's first block first), and a wait for staged codes does not wait for the stores issued since: the
+// wavefront counts them (9.5 -> 8.9 us on that layer; the same at batch 8: 5.2 -> 4.7 us).
 template <int T, int G, bool RAW>
 __global__ void __launch_bounds__(256, (!RAW && T * G > 32 ? 1 : 2))
 smfmac_ws_kernel(WsArgs a)
@@ -82,14 +91,23 @@ smfmac_ws_kernel(WsArgs a)
     constexpr int SP = 2 * T, BLOCK = 32 * SP;              // RAW: 16-byte segments per pixel, and per staged pixel block
     const int wv = __builtin_amdgcn_readfirstlane(w4);
     const uint32_t codes_lds = dg_lds_address(s_codes) + wv * (2 * BLOCK * 16);
-    auto stage = [&](int64_t blk, int buf) {                // RAW: pixel block `blk` (clamped into the tensor) into buffer `buf`
-        const int lp = lane / SP, ls = lane % SP;           // as a loader: pixel within the instruction, slot within the pixel
+    // RAW, as a loader: instruction j of a block fetches pixels j * (64 / SP) + lp, this lane segment seg_off[j] / 16 of
+    // each (slot ls of the staged pixel).  Rows beyond N re-read row N - 1: the pixel is clamped, branch-free.
+    uint32_t seg_off[RAW ? T : 1];
+    uint32_t lp_bytes = 0;
+    if constexpr (RAW) {
+        const int lp = lane / SP, ls = lane % SP;
+        lp_bytes = (uint32_t)(lp * p.K);
 #pragma unroll
-        for (int j = 0; j < T; ++j) {                       // 64 / SP pixels per instruction
-            const int pj = j * (64 / SP) + lp;
-            const int64_t n = min(blk * 32 + pj, (int64_t)last_row);
-            dg_load16_to_lds(p.Xp + n * p.K + ((ls ^ (pj % SP)) * 16), codes_lds + (buf * BLOCK + j * 64) * 16);
-        }
+        for (int j = 0; j < T; ++j) seg_off[j] = (uint32_t)((ls ^ ((j * (64 / SP) + lp) % SP)) * 16);
+    }
+    auto stage = [&](int64_t blk, int buf) {                // RAW: pixel block `blk` into buffer `buf`
+        const uint32_t dst = codes_lds + buf * BLOCK * 16;
+        const uint8_t *base = p.Xp + blk * 32 * p.K;        // (uniform: one base address, the lanes' offsets)
+        const uint32_t last = (uint32_t)min((int64_t)31, (int64_t)last_row - blk * 32) * (uint32_t)p.K;
+#pragma unroll
+        for (int j = 0; j < T; ++j)
+            dg_load16_to_lds(base, (int32_t)(min(lp_bytes + (uint32_t)(j * (64 / SP) * p.K), last) + seg_off[j]), dst + j * 64 * 16);
     };
     auto fetch = [&](int64_t blk) {                         // rows beyond N re-read row N - 1 (their sums are not stored)
 #pragma unroll
@@ -98,14 +116,25 @@ smfmac_ws_kernel(WsArgs a)
             if (blk + g < b1) x[g] = load_words_any<T>(x_base + n * row_bytes);
         }
     };
+    float sc_cols[1] = {0.0f};
     if constexpr (RAW) {
-        // two blocks in flight (past the run's end the loads re-read pixels inside the tensor and are not used: one
-        // block's loads are always behind the one waited for, so the wait can count them).  A wavefront never ends
-        // with such a load in flight -- its LDS could be another workgroup's by the time the data lands -- so one
-        // without a run starts none.
+        // The order in which a wavefront asks: its scale, its weight rows (staged like the codes, into the second
+        // buffer), its first block of codes.  Loads complete in that order, so the dense operands are built while the
+        // first block is still on its way; the second block is asked for once they are (a compute unit's address unit
+        // serves its wavefronts' first blocks first).  These loads are assembly so that the wavefront itself counts
+        // what it waits for: the compiler would wait for everything, staged codes included.
+        // A wavefront never ends with a staged load in flight -- its LDS could be another workgroup's by the time the
+        // data lands: it starts loads for blocks of its run only, and waits for each.
         if (!idle) {
+            const float *sc_at = p.scale ? p.scale + min(m0 + r, p.M - 1) : (const float *)p.Wp;      // (no scales: any readable word)
+            asm volatile("global_load_dword %0, %1, off" : "=v"(sc_cols[0]) : "v"(sc_at) : "memory");
+            constexpr int LPR = T >= 4 ? T / 2 : 1, NWI = T >= 4 ? T / 4 : 1;      // lanes per weight row; instructions
+#pragma unroll
+            for (int j = 0; j < NWI; ++j) {
+                const int row = min(j * (64 / LPR) + lane / LPR, 31);
+                dg_load16_to_lds(p.Wp + (int64_t)min(m0 + row, p.M - 1) * row_bytes + (lane % LPR) * 16, codes_lds + BLOCK * 16 + j * 1024);
+            }
             stage(b0, 0);
-            stage(b0 + 1, 1);
         }
     } else {
         fetch(b0);
@@ -113,7 +142,27 @@ smfmac_ws_kernel(WsArgs a)
 
     // the stationary dense operands: for word t of either half of the weight row, the even and the odd codes' table rows
     v8i dn[T][2];
-    {
+    if constexpr (RAW) {
+        // (the table is in LDS once every wavefront is here; the loads above stay in flight across this barrier, which
+        // waits for LDS operations only)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (idle) return;
+        // the scale and the weight rows are in; the first block's T loads may be under way
+        asm volatile("s_waitcnt vmcnt(%1)" : "+v"(sc_cols[0]) : "n"(T) : "memory");
+        const uint4 *wsrc = (const uint4 *)((const char *)s_codes + wv * (2 * BLOCK * 16) + BLOCK * 16 + r * row_bytes);
+        uint32_t ww[2 * T];
+#pragma unroll
+        for (int i = 0; i < (T >= 2 ? T / 2 : 1); ++i) {
+            const uint4 q = wsrc[i];
+            ww[4 * i] = q.x, ww[4 * i + 1] = q.y, ww[4 * i + 2] = q.z, ww[4 * i + 3] = q.w;
+        }
+        const uint32_t pick = sparse_pick(h);
+#pragma unroll
+        for (int t = 0; t < T; ++t) sparse_dense_rows_shared(s_rows, ww[t], ww[T + t], pick, dn[t][0], dn[t][1]);
+        // (the weight rows are in registers: their buffer takes the second block)
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (b0 + 1 < b1) stage(b0 + 1, 1);
+    } else {
         const uint8_t *wrow = p.Wp + (int64_t)min(m0 + r, p.M - 1) * row_bytes;
         const Words<T> w0 = load_words_any<T>(wrow), w1 = load_words_any<T>(wrow + 4 * T);
         // (the table is in LDS once every wavefront is here; the loads above stay in flight across this barrier,
@@ -123,18 +172,30 @@ smfmac_ws_kernel(WsArgs a)
         const uint32_t pick = sparse_pick(h);
 #pragma unroll
         for (int t = 0; t < T; ++t) sparse_dense_rows_shared(s_rows, w0.v[t], w1.v[t], pick, dn[t][0], dn[t][1]);
+        dg_mfma_column_scales<1, true>(p, m0, lane, sc_cols);
     }
-    float sc_cols[1];
-    dg_mfma_column_scales<1, true>(p, m0, lane, sc_cols);
     // the kept bytes: (1, 0) per position with the even codes, (0, 1) with the odd; the index of both is the packed word
     const v4i ones[2] = {{0x00010001, 0x00010001, 0x00010001, 0x00010001}, {0x01000100, 0x01000100, 0x01000100, 0x01000100}};
 
     if constexpr (RAW) {
-        // a block's codes are packed and multiplied while the block after next is on its way: its loads are issued as
-        // soon as the buffer's codes are in registers, ahead of this block's stores
-        for (int64_t blk = b0; blk < b1; ++blk) {
+        // A block's codes are packed and multiplied while the next block is on its way; the loads of the block after
+        // next are issued as soon as the buffer's codes are in registers, ahead of this block's stores.
+        // Waiting for a block's loads: the counter counts stores as well, and everything completes in issue order.
+        // Issued after block blk's loads were: the stores of block blk - 2, the loads of block blk + 1, the stores of
+        // block blk - 1 -- all of which may still be under way.  The stores of a block wholly inside the output are 16
+        // instructions (dg_mfma_store_block: one per sum register); of any other block they count as none here, which
+        // only waits longer.
+        auto stores_of = [&](int64_t blk) -> int {
+            const int64_t span = 32 * ((p.stride_cn < 0 ? -p.stride_cn : p.stride_cn) + (p.stride_cm < 0 ? -p.stride_cm : p.stride_cm));
+            const bool whole = m0 + 32 <= p.M && (blk + 1) * 32 <= (int64_t)p.N && span < ((int64_t)1 << 30);
+            return a.count_stores && p.Qp == nullptr && whole ? 16 : 0;
+        };
+        int stores1 = 0, stores2 = 0;                       // of the last block, of the one before
+        // (the body twice, with and without the loads of the block after next, so that each is straight-line code: the
+        // compiler then issues those loads between the matrix instructions, whose chain they do not hold up)
+        auto block = [&](int64_t blk, auto ahead) {
             const int buf = (int)(blk - b0) & 1;
-            dg_wait_for_loads<T>();                         // (loads complete in order: all but the newer block's T)
+            dg_wait_for_loads_at_most(stores2 + (blk + 1 < b1 ? T : 0) + stores1);
             const uint4 *src = s_codes + (wv * 2 + buf) * BLOCK + r * SP;
             uint4 c[T];
 #pragma unroll
@@ -142,7 +203,11 @@ smfmac_ws_kernel(WsArgs a)
             Words<T> xw;
 #pragma unroll
             for (int i = 0; i < T; ++i) xw.v[i] = dg_pack_codes16(c[i]);
-            stage(blk + 2, buf);
+            if constexpr (decltype(ahead)::value) {
+                // (the buffer's codes are in registers, not merely asked for, before loads that overwrite it are issued)
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                stage(blk + 2, buf);
+            }
             v16i acc;
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[e] = 0;
@@ -152,8 +217,11 @@ smfmac_ws_kernel(WsArgs a)
                 for (int par = 0; par < 2; ++par)
                     acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(ones[par], dn[t][par], acc, (int)xw.v[t], 0, 0);
             dg_mfma_store_block<true>(p, acc, m0, (int)(blk * 32), lane, sc_cols[0]);
-        }
-        dg_wait_for_loads();                                // (the unused loads past the end: their LDS writes end before the wavefront does)
+            stores2 = stores1, stores1 = stores_of(blk);
+        };
+        int64_t blk = b0;
+        for (; blk + 2 < b1; ++blk) block(blk, std::true_type{});
+        for (; blk < b1; ++blk) block(blk, std::false_type{});
         return;
     }
     for (int64_t blk = b0; blk < b1; blk += G) {
@@ -191,6 +259,8 @@ inline void launch_sparse_ws(const DgProblem &p, const uint32_t (&rows)[4], int 
     a.run = pixel_blocks / streams;
     a.longer = pixel_blocks % streams;
     a.div_row_blocks = make_div((uint32_t)a.row_blocks);
+    a.count_stores = 1;
+    if (const char *e = dg_override("DG_WS_COUNT_STORES")) a.count_stores = atoi(e) != 0;
     const int64_t waves = (int64_t)a.row_blocks * streams;
     const dim3 grid((unsigned)((waves + 3) / 4));
     // a wavefront's whole run in one group where the registers allow it (up to 8 blocks)

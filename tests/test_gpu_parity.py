@@ -868,7 +868,7 @@ def test_four_bit_auto_takes_the_sparse_kernel_on_large_layers():
     _assert_same(got.cpu().numpy().reshape(-1, Cout // 4), want, "4-bit fused layer, AUTO (sparse-instruction kernel)")
 
 
-@pytest.mark.parametrize("waves", [0, 3, 7, 100000])
+@pytest.mark.parametrize("waves", [0, 3, 7, 100000, -3])
 @pytest.mark.parametrize("K", [64, 128, 256])
 def test_stationary_weight_kernel(K, waves, monkeypatch):
     """The sparse-instruction kernel with stationary weight operands (K = 64, 128, 256, no filter window), forced on
@@ -877,7 +877,9 @@ def test_stationary_weight_kernel(K, waves, monkeypatch):
     is) and row-major output (run transposed), 1x1 convolution with int32, scaled fp32 and re-quantised packed output."""
     monkeypatch.setenv("DG_ONEHOT_PLAN", "ws")
     if waves:
-        monkeypatch.setenv("DG_WS_WAVES", str(waves))
+        monkeypatch.setenv("DG_WS_WAVES", str(abs(waves)))
+    if waves < 0:       # (the form that packs codes itself: waiting for its stores whenever it waits for staged codes)
+        monkeypatch.setenv("DG_WS_COUNT_STORES", "0")
     lw, la, entry = LEVELS["nonuniform_i8"]
     for (M, N) in [(70, 1000), (64, 333), (33, 64), (130, 2049), (5, 31)]:
         inp = wl.small_gemm(M, N, K, seed=M + N + K)
