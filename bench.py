@@ -77,6 +77,9 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch every step from the host instead of a HIP graph")
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-workload kernel sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--table-values", action="store_true",
+                    help="also time the workload's kernel (AUTO and the comparison) with other tables of the same shape: "
+                         "the matrix pipe's power draw, and with it the clock, follows the operands' values")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="also run one plain device-to-device copy of this many MiB (a known-size dispatch "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled)")
@@ -451,6 +454,25 @@ def cpu_baseline(w):
             "single_thread_gops": round(w.ops / dt_one / 1e9, 3)}
 
 
+def table_values(torch, r, use_graph):
+    """The runner's kernel on the same codes with other level vectors: same instructions, different operand values."""
+    import numpy as np
+    dg, w = r.dg, r.w
+    entry = dg.DG_LUT_I16 if w.lut_entry == "i16" else dg.DG_LUT_I8
+    tables = [("as specified", tuple(int(x) for x in r.inp.levels_w), tuple(int(x) for x in r.inp.levels_a)),
+              ("all zero", (0, 0, 0, 0), (0, 1, 2, 3)), ("0 ... 9", (0, 1, 2, 3), (0, 1, 2, 3)),
+              ("-6 ... 3", (-2, -1, 0, 1), (0, 1, 2, 3)), ("2 ... 49", (1, 3, 5, 7), (2, 4, 6, 7)),
+              ("-64 ... 64", (-8, -3, 3, 7), (-8, -3, 3, 7))]
+    keep, out = r.lut, []
+    for what, lw, la in tables:
+        r.lut = dg.dg_build_lut(np.array(lw, np.int8), np.array(la, np.int8), entry)
+        out.append({"entries": what, "levels_w": list(lw), "levels_a": list(la), "kernel": r.kernel_name("auto"),
+                    "us": round(time_steady(torch, lambda: r.kernel("auto"), use_graph) * 1e3, 2),
+                    "mfma_i8_us": round(time_steady(torch, lambda: r.kernel("mfma_i8"), use_graph) * 1e3, 2)})
+    r.lut = keep
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -561,6 +583,8 @@ def main():
         line["fused_layers"] = fused_layers(torch, ["resnet18_conv3x3_b1", "resnet50_conv1x1_b32", "vgg16_conv3x3_b16"],
                                             use_graph)
 
+    if args.table_values:
+        line["table_values"] = table_values(torch, r, use_graph)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(line))
