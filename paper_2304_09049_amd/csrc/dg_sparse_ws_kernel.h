@@ -32,8 +32,8 @@ struct WsArgs {
 
 // T = K / 32: matrix-instruction pairs per 32 x 32 block; a lane half reads T words of a pixel (or weight row).
 // G: pixel blocks per group (their words are in registers together).
-// What was measured on the 56x56x256 -> 64 layer at batch 32 (25.7 MB of output, which alone takes 4.0 us to drain plus
-// 1.6 us of launch): the layer's time is the launch, the time to the first stores and the drain, so
+// What was measured on the 56x56x256 -> 64 layer at batch 32 (25.7 MB of output, which alone takes 5.2 us to write in
+// HIP-graph replays, whatever the store pattern): the layer's time is the time to the first stores and the drain, so
 //   - the words of a whole group of pixel blocks are loaded before the group's first store is issued: a wavefront's
 //     vector memory instructions leave the compute unit in issue order, and a load queued behind a burst of stores
 //     waits until the memory system has taken them; a wavefront's run is normally one group;
