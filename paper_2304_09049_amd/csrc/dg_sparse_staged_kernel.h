@@ -48,9 +48,9 @@ __device__ __forceinline__ void dense_rows_movable(const uint2 *table, const W &
 }
 
 // SKW = 1: a wavefront walks all of K.  SKW = 2 or 4 (layers whose tiles alone would leave SIMDs idle): SKW wavefronts
-// of the workgroup share a tile and split K between them in contiguous runs; their sums meet in LDS by integer atomics
+// of the workgroup share a tile and split K between them (run by run, or in contiguous shares); their sums meet in LDS by integer atomics
 // (exact in any order) and each of them stores a share of the tile's blocks, as in dg_onehot_kernel.h.
-template <int WM, int WN, int SKW>
+template <int WM, int WN, int SKW, bool TURNS>
 __global__ void __launch_bounds__(256, 2)
 smfmac_staged_kernel(Args a)
 {
@@ -100,9 +100,17 @@ smfmac_staged_kernel(Args a)
     }
     const int m0 = m_tile * (WM * 32), n0 = n_tile * (WN * 32);
     const int cq = p.Cin / 4;                               // packed bytes per pixel
-    // this wavefront's runs of K: [g0, g1)
+    // This wavefront's runs of K: g0, g0 + stride, ... below g1.  TURNS (layers without a filter window): wavefronts sharing
+    // a tile take turns run by run (stride SKW), so that at any time the four of them read the four 32-byte runs of the SAME
+    // cache lines -- one fetch into the compute unit's cache serves all; with a contiguous quarter of K each, every
+    // wavefront streamed lines of its own, which the cache lost before their next run came up (66 address cycles per
+    // load against 34; 8192 x 256 x 8192: 28.7 -> 24.4 us).  With a window they keep contiguous shares: taking turns
+    // puts every run of a wavefront in another filter tap, and the kept bytes made anew per run cost more than the
+    // cache gives (3x3 layers 7 - 14 % slower).
+    static_assert(!TURNS || SKW > 1, "taking turns is for wavefronts that share a tile");
+    constexpr int stride = TURNS ? SKW : 1;
     const int runs = p.K / 128, share = (runs + SKW - 1) / SKW;
-    const int g0 = min(ks * share, runs), g1 = active ? min(g0 + share, runs) : g0;
+    const int g0 = min(TURNS ? ks : ks * share, runs), g1 = !active ? g0 : (TURNS ? runs : min(g0 + share, runs));
     const int runs_per_tap = cq / 32;
     const int tap0 = (int)fdiv((uint32_t)g0, a.div_runs), rt0 = g0 - tap0 * runs_per_tap;
 
@@ -138,10 +146,10 @@ smfmac_staged_kernel(Args a)
     const char *stage = (const char *)s_mem + w4 * (2 * BUF);
     const uint32_t stage_lds = dg_lds_address(s_mem) + w4 * (2 * BUF);
     // filter tap and byte within the pixel of the run fetched next
-    int kh = (int)fdiv((uint32_t)tap0, a.div_kw), kw = tap0 - kh * p.KW, cib = rt0 * 32, fetched = g0;
-    auto fetch = [&]() {                                    // the next run, into the buffer of its parity
+    int kh = (int)fdiv((uint32_t)tap0, a.div_kw), kw = tap0 - kh * p.KW, cib = rt0 * 32, fetched = g0, fetches = 0;
+    auto fetch = [&]() {                                    // this wavefront's next run, into the buffer of its parity
         const int g = min(fetched, runs - 1);               // (past the end: a run inside the tensors, unused)
-        const uint32_t dst = stage_lds + (fetched & 1) * BUF;
+        const uint32_t dst = stage_lds + ((TURNS ? fetches : fetched) & 1) * BUF;
 #pragma unroll
         for (int bm = 0; bm < WM; ++bm) dg_load16_to_lds(w_ld[bm] + g * 32, dst + bm * 1024);
         const int32_t tap_off = (kh * p.W + kw) * cq + cib;
@@ -152,9 +160,12 @@ smfmac_staged_kernel(Args a)
             const int32_t off = max(0, min(x_ld[bn] + tap_off, x_last));
             dg_load16_to_lds(p.Xp, off, dst + (WM + bn) * 1024);
         }
-        ++fetched;
-        cib += 32;
-        if (cib == cq) {                                    // (uniform)
+        ++fetches;
+        fetched += stride;
+        cib += 32 * stride;
+        if constexpr (TURNS) {
+            while (cib >= cq) cib -= cq;                    // (uniform; no filter window: the tap stays)
+        } else if (cib == cq) {                             // (uniform)
             cib = 0;
             if (++kw == p.KW) {
                 kw = 0;
@@ -234,11 +245,11 @@ smfmac_staged_kernel(Args a)
         Words2 wa, wb;
         v8i dn0[WM][2], dn1[WM][2];
         dg_wait_for_loads();                                   // (both runs: the first is needed now)
-        read_words(wa, g0 & 1, 0);
+        read_words(wa, TURNS ? 0 : g0 & 1, 0);
 #pragma unroll
         for (int u = 0; u < WM; ++u) sparse_dense_rows_shared(s_rows, wa.ca[u].x, wa.ca1[u].x, pick, dn0[u][0], dn0[u][1]);
-        int g = g0, rt = rt0;
-        for (int tap = tap0; g < g1; ++tap) {
+        int g = g0, rt = rt0, n = 0;                        // the run, its place in its tap, runs done
+        for (int tap = tap0; g < g1;) {
             // which of this lane's pixels see the tap: the kept bytes, (1, 0) per position (and (0, 1) for the odd
             // codes), or zeros outside the image
             const int khc = (int)fdiv((uint32_t)tap, a.div_kw), kwc = tap - khc * p.KW;
@@ -253,20 +264,24 @@ smfmac_staged_kernel(Args a)
                     ones_odd[bn] = (v4i){y, y, y, y};
                 }
             }
-            for (; rt < runs_per_tap && g < g1; ++rt, ++g) {
-                // run g, in buffer g & 1: wa holds its first chunk's words, dn0 the dense operands of that chunk's word 0
+            for (; rt < runs_per_tap && g < g1; rt += stride, g += stride, ++n) {
+                // run g, in the buffer of its parity (of its count where wavefronts take turns): wa holds its first chunk's words, dn0 the dense operands of that chunk's word 0
                 step(dn0, wa, 0, dn1, wa, 1);
-                read_words(wb, g & 1, 1);
+                read_words(wb, (TURNS ? n : g) & 1, 1);
                 step(dn1, wa, 1, dn0, wb, 0);
                 step(dn0, wb, 0, dn1, wb, 1);
-                // every read of run g has been issued: its buffer takes run g + 2, once run g + 1 is known to be in
-                // (one counter serves all loads, and they complete in order)
+                // every read of run g has been issued: its buffer takes the wavefront's run after next, once its next
+                // run is known to be in (one counter serves all loads, and they complete in order)
                 dg_wait_for_loads();
                 fetch();
-                read_words(wa, (g + 1) & 1, 0);
+                read_words(wa, ((TURNS ? n : g) + 1) & 1, 0);
                 step(dn1, wb, 1, dn0, wa, 0);
             }
-            rt = 0;
+            if constexpr (TURNS) {
+                while (rt >= runs_per_tap) rt -= runs_per_tap;      // (uniform; no filter window: the tap stays)
+            } else {
+                rt = 0, ++tap;
+            }
         }
         dg_wait_for_loads();                                   // (unused fetches past the end: their LDS writes end before the wavefront does)
     }
@@ -332,16 +347,21 @@ inline void launch_sparse_staged(const DgProblem &p, const Pools &pools, int32_t
     a.div_last = make_div((uint32_t)(last ? last : 1));
     const int tpw = 4 / q.skw;
     const dim3 grid((unsigned)((wave_tiles + tpw - 1) / tpw));
-#define DG_STAGED(WM, WN, SKW) hipLaunchKernelGGL((smfmac_staged_kernel<WM, WN, SKW>), grid, dim3(256), 0, stream, a)
-    if (q.wm == 2) DG_STAGED(2, 4, 1);
-    else if (q.wn == 7) DG_STAGED(1, 7, 1);
-    else if (q.wn == 6) DG_STAGED(1, 6, 1);
-    else if (q.wn == 4 && q.skw == 4) DG_STAGED(1, 4, 4);
-    else if (q.wn == 4 && q.skw == 2) DG_STAGED(1, 4, 2);
-    else if (q.wn == 4) DG_STAGED(1, 4, 1);
-    else if (q.skw == 4) DG_STAGED(1, 2, 4);
-    else if (q.skw == 2) DG_STAGED(1, 2, 2);
-    else DG_STAGED(1, 2, 1);
+    const bool turns = p.KH * p.KW == 1;                   // (see the kernel: run by run without a filter window)
+#define DG_STAGED(WM, WN, SKW, TURNS) hipLaunchKernelGGL((smfmac_staged_kernel<WM, WN, SKW, TURNS>), grid, dim3(256), 0, stream, a)
+    if (q.wm == 2) DG_STAGED(2, 4, 1, false);
+    else if (q.wn == 7) DG_STAGED(1, 7, 1, false);
+    else if (q.wn == 6) DG_STAGED(1, 6, 1, false);
+    else if (q.wn == 4 && q.skw == 4 && turns) DG_STAGED(1, 4, 4, true);
+    else if (q.wn == 4 && q.skw == 4) DG_STAGED(1, 4, 4, false);
+    else if (q.wn == 4 && q.skw == 2 && turns) DG_STAGED(1, 4, 2, true);
+    else if (q.wn == 4 && q.skw == 2) DG_STAGED(1, 4, 2, false);
+    else if (q.wn == 4) DG_STAGED(1, 4, 1, false);
+    else if (q.skw == 4 && turns) DG_STAGED(1, 2, 4, true);
+    else if (q.skw == 4) DG_STAGED(1, 2, 4, false);
+    else if (q.skw == 2 && turns) DG_STAGED(1, 2, 2, true);
+    else if (q.skw == 2) DG_STAGED(1, 2, 2, false);
+    else DG_STAGED(1, 2, 1, false);
 #undef DG_STAGED
 }
 
