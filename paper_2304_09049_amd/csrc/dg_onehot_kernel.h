@@ -72,7 +72,7 @@ struct Args {
     int32_t tiles_m;
     int64_t wave_tiles;
     // dg_sparse_staged_kernel.h: division by the 32-byte runs of packed codes per filter tap; tile numbering in bands
-    FastDiv div_runs, div_band, div_last;
+    FastDiv div_runs, div_band, div_last, div_cpt;
     int32_t tiles_n, band_log2, m_log2;
     uint32_t band_tiles;
     // dg_sparse_staged_kernel.h: what was added to every table entry (the sums start at minus this per position of K)

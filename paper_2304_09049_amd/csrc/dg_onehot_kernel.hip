@@ -188,10 +188,11 @@ int sparse_tile_hint(const dg_lut *lut, const DgProblem &t)
 }
 
 // The tiled kernel with operands staged through LDS (dg_sparse_staged_kernel.h) takes the unshared tiles of layers
-// whose filter taps are whole 32-byte runs of packed codes.  DG_ONEHOT_STAGED=0 keeps the direct loads (A/B measurement).
+// whose filter taps are whole 32-byte runs of packed codes, or -- its two narrow tiles, unshared -- whole 16-byte chunks.
+// DG_ONEHOT_STAGED=0 keeps the direct loads (A/B measurement).
 bool staged_takes(const DgProblem &t)
 {
-    if (t.Cin % 128 != 0 || (uintptr_t)t.Wp % 16 != 0 || (uintptr_t)t.Xp % 16 != 0) return false;
+    if (t.Cin % 64 != 0 || (uintptr_t)t.Wp % 16 != 0 || (uintptr_t)t.Xp % 16 != 0) return false;
     if (const char *e = dg_override("DG_ONEHOT_STAGED")) return atoi(e) != 0;
     return true;
 }
@@ -210,15 +211,34 @@ Plan sparse_plan(const dg_lut *lut, const DgProblem &t)
     Plan q = plan_for(lut, t, SPARSE, sparse_tile_hint(lut, t));
     q.staged = false;
     if (!staged_takes(t)) return q;
+    const bool half = t.Cin % 128 != 0;                     // only the unshared 32 x 64 and 32 x 128 tiles
     if (const char *force = dg_override("DG_ONEHOT_PLAN")) {
         const int v = atoi(force), k = strstr(force, "k4") ? 4 : (strstr(force, "k2") ? 2 : 1);
+        if (half && ((v != 12 && v != 14) || k != 1)) return q;
         if (v == 12 || v == 14) q.staged = true, q.split = false, q.wm = 1, q.wn = v == 12 ? 2 : 4, q.skw = k, q.ch = 2;
         if (v == 16 || v == 24) q.staged = true, q.split = false, q.wm = v == 16 ? 1 : 2, q.wn = v == 16 ? 6 : 4, q.skw = 1, q.ch = 2;
         if (v == 17) q.staged = true, q.split = false, q.wm = 1, q.wn = 7, q.skw = 1, q.ch = 2;
         return q;
     }
     if (q.split || q.wm != 2) return q;
-    if (q.wn <= 2) {
+    // Wavefronts that share a tile need two runs of K each: with one (K = 512 shared by four), the 28x28x512 -> 128 and
+    // 7x7x512 -> 2048 layers at batch 8 measured 8 and 11 % slower than the dense instruction's direct-load kernel;
+    // with two (K = 1024 by four) from equal to 6 % faster.
+    if (q.skw > 1 && t.K / 128 < 2 * q.skw) return q;
+    if (half) {
+        // Layers with a filter window and three or more chunks per tap, where the planner does not share tiles or
+        // there are so many tiles that sharing is not needed to fill the chip: the wider of the two tiles that leaves
+        // every SIMD more than one tile.  Measured against the direct loads, batch 32: 28x28x192 -> 96 3x3 18.4
+        // against 20.9 us, 28x28x320 -> 320 3x3 43.4 against 50.0, 56x56x192 -> 192 3x3 67.4 against 82.7 (shared
+        // 64 x 64 tiles; unshared 70.3).  Elsewhere the direct loads stay: with 64 channels (seven 3x3 layers) the
+        // staged tiles measured within +-2 %, on GEMMs and 1x1 layers from 13 % slower to 6 % faster, with the few
+        // tiles of the planner's shared plans 6 - 40 % slower.
+        const int64_t simds = dg_simd_count();
+        if (t.KH * t.KW == 1 || t.Cin < 192) return q;
+        if (q.skw != 1 && tile_count(t, 1, 4) <= 4 * simds) return q;
+        if (tile_count(t, 1, 4) > simds) q.staged = true, q.wm = 1, q.wn = 4, q.skw = 1, q.ch = 2;
+        else if (q.skw == 1 && tile_count(t, 1, 2) > simds) q.staged = true, q.wm = 1, q.wn = 2, q.ch = 2;
+    } else if (q.wn <= 2) {
         q.staged = true, q.wm = 1, q.wn *= 2, q.ch = 2;
     } else if (q.wn == 4 && q.skw == 1) {
         // 64 x 128, 32 x 192 or 32 x 224: the one that leaves the busiest SIMD the fewest blocks (ties: 32 x 192, which
@@ -245,13 +265,29 @@ bool dg_sparse_preferred(const dg_lut *lut, const DgProblem &p)
     if (sparse_tile_hint(lut, t) > 0) return true;
     // the staged kernel, where the layer is its case and large enough for tiles, was faster than the dense
     // instruction's kernels on all 9 such layers measured (by 7 - 25 %)
-    if (sparse_plan(lut, t).staged) return true;
+    const Plan sparse = sparse_plan(lut, t);
+    if (sparse.staged) return true;
     // Also where the dense-instruction planner shares tiles at least 64 columns wide and there are 384 of them or more:
     // the sparse kernel in the shape its own planner picks was 1 - 15 % faster on all 9 such layers measured (it lost
     // on shared 64 x 32 tiles, on 200 shared 64 x 64 tiles, and with one-word chunks, Cin % 64 != 0).
     const Plan dense = plan_for(lut, t, TABLE);
-    return fits_int8(lut) && t.Cin % 64 == 0 && !dense.split && dense.skw > 1 && dense.wn >= 2 &&
-           tile_count(t, 2, dense.wn) >= 384;
+    if (fits_int8(lut) && t.Cin % 64 == 0 && !dense.split && dense.skw > 1 && dense.wn >= 2 && tile_count(t, 2, dense.wn) >= 384)
+        return true;
+    // Split K: the dense instruction's split kernel walks K in chunks of 128 positions, so K = 256 gives each tile two
+    // wavefronts at most; the sparse one's chunks are 64, and four wavefronts per tile measured 11 - 19 % faster on
+    // the four 1x1 layers with 256 input channels of ResNet-50 at batch 1 (3.3 - 3.7 against 3.8 - 4.6 us).  With
+    // more chunks than that the dense instruction's split kernel is the faster by 3 - 15 %.
+    if (dense.split && sparse.split && dense.S <= 2 && sparse.S >= 4) return true;
+    // And on unshared 64 x 32 tiles where there is more than one per SIMD: 8 - 13 % faster on eight layers measured (3x3
+    // layers with 64 channels at 1568 tiles, 1x1 layers and GEMMs with K = 320 and 576 at 1764 and 2048); at 1024 and
+    // 784 tiles the two were within 2 % of each other either way.
+    return fits_int8(lut) && t.Cin % 64 == 0 && !dense.split && dense.skw == 1 && dense.wn == 1 &&
+           tile_count(t, 2, 1) > dg_simd_count();
+}
+
+bool dg_sparse_splits(const dg_lut *lut, const DgProblem &p)
+{
+    return dg_sparse_supports(lut, p) && sparse_plan(lut, sparse_problem(p)).split;
 }
 
 bool dg_sparse_supports(const dg_lut *lut, const DgProblem &p)
@@ -362,7 +398,10 @@ bool sparse_ws_takes(const dg_lut *lut, const DgProblem &p)
 int sparse_ws_streams(const DgProblem &t, bool raw)
 {
     const int64_t row_blocks = (t.M + 31) / 32, pixel_blocks = ((int64_t)t.N + 31) / 32;
-    int64_t waves = (int64_t)dg_simd_count() * (raw && t.K != 128 ? 2 : 1);
+    // K = 64 on packed codes: three per SIMD -- a block is then 8 matrix instructions against 16 stores, and one
+    // wavefront's stores in flight do not fill the write path (56x56x64 -> 64 at batch 32: 6.2 against 6.8 us, -> 256:
+    // 21.1 against 22.0, the same at batch 8: 6.4 against 6.8; four per SIMD were slower again)
+    int64_t waves = (int64_t)dg_simd_count() * (raw ? (t.K != 128 ? 2 : 1) : (t.K == 64 ? 3 : 1));
     if (const char *e = dg_override("DG_WS_WAVES")) waves = atoi(e) > 0 ? atoi(e) : waves;
     int64_t streams = waves / row_blocks;
     if (streams < 1) streams = 1;

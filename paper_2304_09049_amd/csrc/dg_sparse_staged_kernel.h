@@ -50,10 +50,16 @@ __device__ __forceinline__ void dense_rows_movable(const uint2 *table, const W &
 // SKW = 1: a wavefront walks all of K.  SKW = 2 or 4 (layers whose tiles alone would leave SIMDs idle): SKW wavefronts
 // of the workgroup share a tile and split K between them (run by run, or in contiguous shares); their sums meet in LDS by integer atomics
 // (exact in any order) and each of them stores a share of the tile's blocks, as in dg_onehot_kernel.h.
-template <int WM, int WN, int SKW, bool TURNS>
+//
+// HALF (unshared tiles, Cin % 128 == 64: the layers with 64 channels above all): a filter tap is an odd number of
+// 64-position chunks, so the two chunks of a run may lie in different taps -- two different pixels for the loader's two
+// lanes of a row, two sets of kept bytes for the run's two halves -- and the last run of K may be half a run, whose
+// second chunk is fetched from the first's place and multiplied by kept bytes of zero.
+template <int WM, int WN, int SKW, bool TURNS, bool HALF>
 __global__ void __launch_bounds__(256, 2)
 smfmac_staged_kernel(Args a)
 {
+    static_assert(!HALF || SKW == 1, "taps of half runs: unshared tiles only");
     constexpr int ROWS = (WM + WN) * 32;                    // staged rows of a wavefront: its weight rows, then its pixels
     constexpr int BUF = ROWS * 32;                          // bytes of one wavefront's buffer
     constexpr int TPW = 4 / SKW;                           // tiles per workgroup
@@ -109,7 +115,8 @@ smfmac_staged_kernel(Args a)
     // cache gives (3x3 layers 7 - 14 % slower).
     static_assert(!TURNS || SKW > 1, "taking turns is for wavefronts that share a tile");
     constexpr int stride = TURNS ? SKW : 1;
-    const int runs = p.K / 128, share = (runs + SKW - 1) / SKW;
+    const int runs = HALF ? (p.K + 127) / 128 : p.K / 128, share = (runs + SKW - 1) / SKW;
+    const int chunks = p.K / 64, cpt = p.Cin / 64;          // HALF: 64-position chunks in all, and per filter tap
     const int g0 = min(TURNS ? ks : ks * share, runs), g1 = !active ? g0 : (TURNS ? runs : min(g0 + share, runs));
     const int runs_per_tap = cq / 32;
     const int tap0 = (int)fdiv((uint32_t)g0, a.div_runs), rt0 = g0 - tap0 * runs_per_tap;
@@ -119,11 +126,11 @@ smfmac_staged_kernel(Args a)
     const uint8_t *w_ld[WM];
 #pragma unroll
     for (int bm = 0; bm < WM; ++bm)
-        w_ld[bm] = p.Wp + (int64_t)min(m0 + bm * 32 + lrow, p.M - 1) * (p.K / 4) + lseg * 16;
+        w_ld[bm] = p.Wp + (int64_t)min(m0 + bm * 32 + lrow, p.M - 1) * (p.K / 4) + (HALF ? 0 : lseg * 16);
     int32_t x_ld[WN];                                       // (32-bit offsets: the host sends inputs below 2^31 bytes)
 #pragma unroll
     for (int bn = 0; bn < WN; ++bn)
-        x_ld[bn] = (int32_t)make_column(p, a.div_ow, a.div_oh, n0 + bn * 32 + lrow, cq, lseg * 16).off0;
+        x_ld[bn] = (int32_t)make_column(p, a.div_ow, a.div_oh, n0 + bn * 32 + lrow, cq, HALF ? 0 : lseg * 16).off0;
     const int images = (int)fdiv(fdiv((uint32_t)p.N, a.div_ow), a.div_oh);
     const int32_t x_last = images * p.H * p.W * cq - 16;    // the last 16 bytes of the packed activations
     // as a consumer, it is row / pixel r (lane half h) of every block: its slot of segment s is slot0 ^ s
@@ -150,6 +157,22 @@ smfmac_staged_kernel(Args a)
     auto fetch = [&]() {                                    // this wavefront's next run, into the buffer of its parity
         const int g = min(fetched, runs - 1);               // (past the end: a run inside the tensors, unused)
         const uint32_t dst = stage_lds + ((TURNS ? fetches : fetched) & 1) * BUF;
+        if constexpr (HALF) {
+            // this lane's chunk of the run: 2 g + lseg (past the end of K: the chunk before), its tap and place in it
+            const int c0 = 2 * g, c1 = min(2 * g + 1, chunks - 1);
+            auto pixel_offset = [&](int c) {
+                const int tap = (int)fdiv((uint32_t)c, a.div_cpt), th = (int)fdiv((uint32_t)tap, a.div_kw);
+                return (int32_t)((th * p.W + (tap - th * p.KW)) * cq + (c - tap * cpt) * 16);
+            };
+            const int32_t off0 = pixel_offset(c0), off1 = pixel_offset(c1);
+            const int32_t w_off = (lseg ? c1 : c0) * 16, x_off = lseg ? off1 : off0;
+#pragma unroll
+            for (int bm = 0; bm < WM; ++bm) dg_load16_to_lds(w_ld[bm] + w_off, dst + bm * 1024);
+#pragma unroll
+            for (int bn = 0; bn < WN; ++bn) dg_load16_to_lds(p.Xp, max(0, min(x_ld[bn] + x_off, x_last)), dst + (WM + bn) * 1024);
+            ++fetches, ++fetched;
+            return;
+        }
 #pragma unroll
         for (int bm = 0; bm < WM; ++bm) dg_load16_to_lds(w_ld[bm] + g * 32, dst + bm * 1024);
         const int32_t tap_off = (kh * p.W + kw) * cq + cib;
@@ -196,7 +219,24 @@ smfmac_staged_kernel(Args a)
     // operands `next` of the following step -- per weight block a unit of table reads -- made between them.
     // (see dg_onehot_kernel.h for the index register and the kept bytes)
     v4i ones[WN], ones_odd[SHIFT_ODD ? 1 : WN];
-    auto step = [&](const v8i (&dn)[WM][2], const Words2 &w, int t, v8i (&next)[WM][2], const Words2 &nw, int nt) {
+    // which of this lane's pixels see a filter tap: the kept bytes, (1, 0) per position (and (0, 1) for the odd codes),
+    // or zeros outside the image (or for a chunk past the end of K)
+    auto kept_bytes = [&](int tap, bool live, v4i (&on)[WN], v4i (&on_odd)[SHIFT_ODD ? 1 : WN]) {
+        const int khc = (int)fdiv((uint32_t)tap, a.div_kw), kwc = tap - khc * p.KW;
+#pragma unroll
+        for (int bn = 0; bn < WN; ++bn) {
+            const int ih = col[bn].ih0 + khc, iw = col[bn].iw0 + kwc;
+            const bool v = live & col[bn].ok & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
+            const int x = v ? 0x00010001 : 0;
+            on[bn] = (v4i){x, x, x, x};
+            if constexpr (!SHIFT_ODD) {
+                const int y = v ? 0x01000100 : 0;
+                on_odd[bn] = (v4i){y, y, y, y};
+            }
+        }
+    };
+    auto step = [&](const v8i (&dn)[WM][2], const Words2 &w, int t, v8i (&next)[WM][2], const Words2 &nw, int nt,
+                    const v4i (&ones)[WN], const v4i (&ones_odd)[SHIFT_ODD ? 1 : WN]) {
         constexpr int MN = WM * WN;
         // the next step's dense operands: written here, spread by the scheduling groups below a few instructions at a
         // time between this step's matrix instructions, in whose shadow they then issue
@@ -248,34 +288,36 @@ smfmac_staged_kernel(Args a)
         read_words(wa, TURNS ? 0 : g0 & 1, 0);
 #pragma unroll
         for (int u = 0; u < WM; ++u) sparse_dense_rows_shared(s_rows, wa.ca[u].x, wa.ca1[u].x, pick, dn0[u][0], dn0[u][1]);
-        int g = g0, rt = rt0, n = 0;                        // the run, its place in its tap, runs done
-        for (int tap = tap0; g < g1;) {
-            // which of this lane's pixels see the tap: the kept bytes, (1, 0) per position (and (0, 1) for the odd
-            // codes), or zeros outside the image
-            const int khc = (int)fdiv((uint32_t)tap, a.div_kw), kwc = tap - khc * p.KW;
-#pragma unroll
-            for (int bn = 0; bn < WN; ++bn) {
-                const int ih = col[bn].ih0 + khc, iw = col[bn].iw0 + kwc;
-                const bool v = col[bn].ok & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
-                const int x = v ? 0x00010001 : 0;
-                ones[bn] = (v4i){x, x, x, x};
-                if constexpr (!SHIFT_ODD) {
-                    const int y = v ? 0x01000100 : 0;
-                    ones_odd[bn] = (v4i){y, y, y, y};
-                }
+        if constexpr (HALF) {
+            v4i ones_b[WN], ones_b_odd[SHIFT_ODD ? 1 : WN];     // the kept bytes of a run's second chunk
+            for (int g = 0; g < runs; ++g) {
+                kept_bytes((int)fdiv((uint32_t)(2 * g), a.div_cpt), true, ones, ones_odd);
+                kept_bytes((int)fdiv((uint32_t)min(2 * g + 1, chunks - 1), a.div_cpt), 2 * g + 1 < chunks, ones_b, ones_b_odd);
+                step(dn0, wa, 0, dn1, wa, 1, ones, ones_odd);
+                read_words(wb, g & 1, 1);
+                step(dn1, wa, 1, dn0, wb, 0, ones, ones_odd);
+                step(dn0, wb, 0, dn1, wb, 1, ones_b, ones_b_odd);
+                dg_wait_for_loads();
+                fetch();
+                read_words(wa, (g + 1) & 1, 0);
+                step(dn1, wb, 1, dn0, wa, 0, ones_b, ones_b_odd);
             }
+        }
+        int g = HALF ? g1 : g0, rt = rt0, n = 0;            // the run, its place in its tap, runs done
+        for (int tap = tap0; g < g1;) {
+            kept_bytes(tap, true, ones, ones_odd);
             for (; rt < runs_per_tap && g < g1; rt += stride, g += stride, ++n) {
                 // run g, in the buffer of its parity (of its count where wavefronts take turns): wa holds its first chunk's words, dn0 the dense operands of that chunk's word 0
-                step(dn0, wa, 0, dn1, wa, 1);
+                step(dn0, wa, 0, dn1, wa, 1, ones, ones_odd);
                 read_words(wb, (TURNS ? n : g) & 1, 1);
-                step(dn1, wa, 1, dn0, wb, 0);
-                step(dn0, wb, 0, dn1, wb, 1);
+                step(dn1, wa, 1, dn0, wb, 0, ones, ones_odd);
+                step(dn0, wb, 0, dn1, wb, 1, ones, ones_odd);
                 // every read of run g has been issued: its buffer takes the wavefront's run after next, once its next
                 // run is known to be in (one counter serves all loads, and they complete in order)
                 dg_wait_for_loads();
                 fetch();
                 read_words(wa, ((TURNS ? n : g) + 1) & 1, 0);
-                step(dn1, wb, 1, dn0, wa, 0);
+                step(dn1, wb, 1, dn0, wa, 0, ones, ones_odd);
             }
             if constexpr (TURNS) {
                 while (rt >= runs_per_tap) rt -= runs_per_tap;      // (uniform; no filter window: the tap stays)
@@ -337,7 +379,9 @@ inline void launch_sparse_staged(const DgProblem &p, const Pools &pools, int32_t
     a.wave_tiles = wave_tiles;
     a.div_ow = make_div((uint32_t)p.OW), a.div_oh = make_div((uint32_t)p.OH);
     a.div_cin = make_div((uint32_t)p.Cin), a.div_kw = make_div((uint32_t)p.KW);
-    a.div_runs = make_div((uint32_t)(p.Cin / 128));
+    const bool half = p.Cin % 128 != 0;                    // (see the kernel: taps of an odd number of 64-position chunks)
+    a.div_runs = make_div((uint32_t)(half ? 1 : p.Cin / 128));
+    a.div_cpt = make_div((uint32_t)(p.Cin / 64));
     a.tiles_n = (int32_t)((p.N + q.wn * 32 - 1) / (q.wn * 32));
     a.band_log2 = 3;                                       // bands of 8 pixel tiles
     a.m_log2 = a.tiles_m % 4 == 0 ? 2 : 0;                 // (unshared tiles: a workgroup's four wavefronts)
@@ -348,8 +392,10 @@ inline void launch_sparse_staged(const DgProblem &p, const Pools &pools, int32_t
     const int tpw = 4 / q.skw;
     const dim3 grid((unsigned)((wave_tiles + tpw - 1) / tpw));
     const bool turns = p.KH * p.KW == 1;                   // (see the kernel: run by run without a filter window)
-#define DG_STAGED(WM, WN, SKW, TURNS) hipLaunchKernelGGL((smfmac_staged_kernel<WM, WN, SKW, TURNS>), grid, dim3(256), 0, stream, a)
-    if (q.wm == 2) DG_STAGED(2, 4, 1, false);
+#define DG_STAGED(WM, WN, SKW, TURNS) hipLaunchKernelGGL((smfmac_staged_kernel<WM, WN, SKW, TURNS, false>), grid, dim3(256), 0, stream, a)
+    if (half && q.wn == 4) hipLaunchKernelGGL((smfmac_staged_kernel<1, 4, 1, false, true>), grid, dim3(256), 0, stream, a);
+    else if (half) hipLaunchKernelGGL((smfmac_staged_kernel<1, 2, 1, false, true>), grid, dim3(256), 0, stream, a);
+    else if (q.wm == 2) DG_STAGED(2, 4, 1, false);
     else if (q.wn == 7) DG_STAGED(1, 7, 1, false);
     else if (q.wn == 6) DG_STAGED(1, 6, 1, false);
     else if (q.wn == 4 && q.skw == 4 && turns) DG_STAGED(1, 4, 4, true);

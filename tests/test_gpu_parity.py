@@ -983,9 +983,12 @@ def test_staged_sparse_kernel(plan, name, monkeypatch):
         dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant="onehot_smfmac", strides=(1, M))
         torch.cuda.synchronize()
         _assert_same(out.cpu().numpy(), want.T.copy(), f"staged gemm {(M, N, K)} column-major")
-    # channels that are not whole 32-byte runs: the direct-load kernel of the same tile
-    c = wl.small_conv(1, 8, 8, 64, 32, 3, 3, (1, 1), (1, 1), seed=1)
+    # channels that are not whole 16-byte chunks: the direct-load kernel of the same tile; whole chunks but not whole
+    # 32-byte runs: the staged kernel's two narrow unshared tiles only (test_staged_kernel_half_runs)
+    c = wl.small_conv(1, 8, 8, 32, 32, 3, 3, (1, 1), (1, 1), seed=1)
     assert "staged" not in GpuCase(c, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac")
+    c = wl.small_conv(1, 8, 8, 64, 32, 3, 3, (1, 1), (1, 1), seed=1)
+    assert ("staged" in GpuCase(c, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac")) == (plan in ("12", "14"))
     # seeded random geometries: filter, stride, padding, image, channels, batch
     rng = np.random.default_rng(77 + len(plan))
     for _ in range(12):
@@ -1000,6 +1003,53 @@ def test_staged_sparse_kernel(plan, name, monkeypatch):
         want = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=(sh, sw), pad=(ph, pw))
         _assert_same(case.run("onehot_smfmac").cpu().numpy(), want,
                      f"staged conv B={B} {H}x{W} Cin={Cin} Cout={Cout} {KH}x{KW} s=({sh},{sw}) p=({ph},{pw}) plan {plan}")
+
+
+@pytest.mark.parametrize("bias", ["0", "1"])
+@pytest.mark.parametrize("plan,name", [("12", "onehot_smfmac_staged_32x64"), ("14", "onehot_smfmac_staged_32x128")])
+def test_staged_kernel_half_runs(plan, name, bias, monkeypatch):
+    """The staged kernel on layers whose filter taps are an odd number of 64-position chunks (Cin = 64, 192, 320): the
+    two chunks of a 32-byte run may then lie in different taps, and the last run of K may be half a run.  Padded windows,
+    strides, ragged M and N, one chunk in all (K = 64), with the table as it is and raised; scaled output; GEMMs in both
+    output layouts."""
+    monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
+    monkeypatch.setenv("DG_STAGED_BIAS", bias)
+    lw, la, entry = LEVELS["nonuniform_i8"]
+    convs = [(2, 9, 7, 64, 36, 3, 3, (1, 1), (1, 1)), (1, 13, 11, 192, 70, 3, 3, (2, 2), (1, 1)),
+             (3, 6, 5, 320, 64, 1, 1, (1, 1), (0, 0)), (1, 5, 4, 64, 33, 1, 1, (1, 1), (0, 0)),
+             (1, 20, 17, 64, 130, 3, 2, (1, 2), (1, 0)), (2, 15, 15, 64, 100, 5, 5, (1, 1), (2, 2)),
+             (1, 29, 29, 64, 70, 3, 3, (1, 1), (1, 1)), (1, 12, 12, 192, 40, 2, 2, (1, 1), (1, 1))]
+    for (B, H, W, Cin, Cout, KH, KW, stride, pad) in convs:
+        c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        assert case.kernel_name("onehot_smfmac") == name
+        acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
+        _assert_same(case.run("onehot_smfmac").cpu().numpy(), acc, f"staged conv, half runs {(B, H, W, Cin, Cout, KH, KW, stride, pad)}")
+        got = case.run("onehot_smfmac", scale=True).cpu().numpy()
+        assert np.array_equal(got, oracle.scale_epilogue_nhwc(acc, c.scale))
+    for (M, N, K) in [(70, 1000, 64), (64, 333, 192), (200, 64, 1216), (33, 5, 320)]:
+        inp = wl.small_gemm(M, N, K, seed=M + N + K)
+        case = GpuCase(inp, levels=(lw, la), entry=entry)
+        assert case.kernel_name("onehot_smfmac") == name
+        want = oracle.gemm(inp.Wc, inp.Ac, lw, la)
+        _assert_same(case.run("onehot_smfmac").cpu().numpy(), want, f"staged gemm, half runs {(M, N, K)} row-major")
+        out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
+        dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant="onehot_smfmac", strides=(1, M))
+        torch.cuda.synchronize()
+        _assert_same(out.cpu().numpy(), want.T.copy(), f"staged gemm, half runs {(M, N, K)} column-major")
+    rng = np.random.default_rng(177 + len(plan))
+    for _ in range(12):
+        KH, KW = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        sh, sw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        ph, pw = int(rng.integers(0, KH)), int(rng.integers(0, KW))
+        H, W = int(rng.integers(KH, 20)), int(rng.integers(KW, 20))
+        Cin, Cout, B = int(rng.choice([64, 192, 320])), int(rng.integers(1, 140)), int(rng.integers(1, 4))
+        c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, (sh, sw), (ph, pw), seed=int(rng.integers(1 << 30)))
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        assert case.kernel_name("onehot_smfmac") == name
+        want = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=(sh, sw), pad=(ph, pw))
+        _assert_same(case.run("onehot_smfmac").cpu().numpy(), want,
+                     f"staged conv, half runs B={B} {H}x{W} Cin={Cin} Cout={Cout} {KH}x{KW} s=({sh},{sw}) p=({ph},{pw}) plan {plan}")
 
 
 @pytest.mark.parametrize("bias", ["1", "0"])
