@@ -187,8 +187,8 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *                    move to the sparse-instruction forms on its own.
  *                    "fewn" the few-columns kernel on the sparse instruction (K % 256 == 0, no filter window).
  *                    "12", "14" (optionally followed by "k2" or "k4"), "16", "17", "24": the sparse-instruction kernel
- *                    that stages its operands through LDS (Cin % 128 == 0), tile 32 x 64, 32 x 128, 32 x 192, 32 x 224,
- *                    64 x 128;
+ *                    that stages its operands through LDS (Cin % 128 == 0; "12" and "14" alone also
+ *                    Cin % 128 == 64), tile 32 x 64, 32 x 128, 32 x 192, 32 x 224, 64 x 128;
  *                    the other values keep that kernel out.
  *   DG_ONEHOT_STAGED "0" keeps the staged kernel out altogether (the direct-load kernels run instead)
  *   DG_STAGED_BIAS   "0": the staged kernel multiplies with the table as it is; "1": with every entry raised by

@@ -15,7 +15,7 @@
 // The multiplication is one software pipeline over all of K: the dense operands of a step are made between the matrix
 // instructions of the step before, across chunks, runs and filter taps alike.
 //
-// A run is 128 positions of K inside one filter tap (Cin % 128 == 0).  A tap outside the image is fetched from a
+// A run is 128 positions of K inside one filter tap (Cin % 128 == 0; Cin % 128 == 64: HALF below).  A tap outside the image is fetched from a
 // clamped address and contributes nothing because the kept bytes of its lanes are zero.
 #pragma once
 
@@ -51,7 +51,7 @@ __device__ __forceinline__ void dense_rows_movable(const uint2 *table, const W &
 // of the workgroup share a tile and split K between them (run by run, or in contiguous shares); their sums meet in LDS by integer atomics
 // (exact in any order) and each of them stores a share of the tile's blocks, as in dg_onehot_kernel.h.
 //
-// HALF (unshared tiles, Cin % 128 == 64: the layers with 64 channels above all): a filter tap is an odd number of
+// HALF (unshared tiles, Cin % 128 == 64): a filter tap is an odd number of
 // 64-position chunks, so the two chunks of a run may lie in different taps -- two different pixels for the loader's two
 // lanes of a row, two sets of kept bytes for the run's two halves -- and the last run of K may be half a run, whose
 // second chunk is fetched from the first's place and multiplied by kept bytes of zero.
