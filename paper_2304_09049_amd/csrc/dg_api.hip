@@ -508,14 +508,10 @@ Fuse fuses_packing(const dg_lut *lut, const DgProblem &p_codes, dg_kernel varian
 {
     // (the unpacked buffer's 16-byte alignment satisfies every kernel's test of the packed one)
     if ((uintptr_t)p_codes.Xp % 16 != 0 || lut->bits != 2) return Fuse::None;
-    // (where AUTO takes the sparse instruction's split-K kernel on packed codes -- it is ahead by 0.4 - 0.9 us with
-    // K = 256 -- the dense one's, which packs as it loads, still saves the 1.4 us of a packing launch: 4.2 against 5.2 us)
-    if ((variant == DG_KERNEL_AUTO || variant == DG_KERNEL_ONEHOT_MFMA) && dg_onehot_codes_supports(lut, p_codes)) {
-        if (variant == DG_KERNEL_ONEHOT_MFMA) return Fuse::OneHot;
-        const Pick pick = pick_kernel(lut, p_codes, DG_KERNEL_AUTO);
-        if (dg_onehot_codes_pays(p_codes) && (pick == Pick::OneHot || (pick == Pick::Sparse && dg_sparse_splits(lut, p_codes))))
-            return Fuse::OneHot;
-    }
+    if ((variant == DG_KERNEL_AUTO || variant == DG_KERNEL_ONEHOT_MFMA) && dg_onehot_codes_supports(lut, p_codes) &&
+        (variant == DG_KERNEL_ONEHOT_MFMA ||
+         (dg_onehot_codes_pays(p_codes) && pick_kernel(lut, p_codes, DG_KERNEL_AUTO) == Pick::OneHot)))
+        return Fuse::OneHot;
     // (the few-columns kernel packs once per row block and pass of four columns, about 7 % more work for it: less than
     // a launch while the columns are few, which is where AUTO uses that kernel anyway)
     if ((variant == DG_KERNEL_SMALLN || (variant == DG_KERNEL_AUTO && p_codes.N <= 4)) &&

@@ -105,7 +105,6 @@ dg_status dg_launch_onehot_codes(const dg_lut *lut, const DgProblem &p, hipStrea
 const char *dg_onehot_codes_config_name(const dg_lut *lut, const DgProblem &p);
 bool dg_sparse_supports(const dg_lut *lut, const DgProblem &p);
 bool dg_sparse_preferred(const dg_lut *lut, const DgProblem &p);     // AUTO's choice between the two one-hot kernels
-bool dg_sparse_splits(const dg_lut *lut, const DgProblem &p);        // its plan for the problem is the split-K kernel
 dg_status dg_launch_sparse(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 const char *dg_sparse_config_name(const dg_lut *lut, const DgProblem &p);
 bool dg_sparse4_supports(const dg_lut *lut, const DgProblem &p);      // 4-bit codes on the sparse instruction

@@ -60,6 +60,7 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
     if (const char *e = dg_override("DG_ONEHOT_WAVES")) target = atoi(e) > 0 ? atoi(e) : target;   // tuning override
     int S = (int)((target + blocks11 - 1) / blocks11);
     S = S < 1 ? 1 : (S > 16 ? 16 : S);
+    const int S_wanted = S;
     if (S > q.chunks) S = q.chunks;
     const int split_cpw = (q.chunks + S - 1) / S, split_S = (q.chunks + split_cpw - 1) / split_cpw;
 
@@ -129,6 +130,23 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
         }
     }
     if (q.split) q.cpw = split_cpw, q.S = split_S, q.wm = wm;
+    // The dense instruction's chunks of 128 positions cap the wavefronts per tile at K / 128 and make their shares of K
+    // coarse.  It walks K in chunks of 64 instead: up to K = 512 where at least twice as many wavefronts are wanted
+    // (measured at batch 1: K = 256, four wavefronts instead of two, 3.8 -> 3.1 us on five layers of ResNet-50; K = 384
+    // 3.6 -> 3.1; K = 512, eight instead of four, 3.3 -> 3.1), and where the finer shares give more wavefronts, up to 12
+    // (K = 2304, 12 of 3 chunks instead of 9 of 2: 5.5 -> 5.1 us, the one-call step 7.1 -> 6.2; K = 768, 12 instead of
+    // 6: the step 4.5 -> 4.05).  More than 12 were slower (K = 1024, 16 for 8: 3.5 -> 3.9; K = 4608, 15 for 12: 6.9 -> 8.0).
+    // DG_ONEHOT_CH2_MAX, DG_ONEHOT_CH2_SMAX: the most 128-position chunks for the first rule (default 4; 0: never),
+    // the most wavefronts for the second (default 12; 0: never).
+    int ch2_max = 4, s_max = 12;
+    if (const char *e = dg_override("DG_ONEHOT_CH2_MAX")) ch2_max = atoi(e);
+    if (const char *e = dg_override("DG_ONEHOT_CH2_SMAX")) s_max = atoi(e);
+    if (q.split && mode != SPARSE && can_share && q.ch == 4) {
+        const int chunks2 = 2 * q.chunks, S2 = S_wanted > chunks2 ? chunks2 : S_wanted;
+        const int cpw2 = (chunks2 + S2 - 1) / S2, waves2 = (chunks2 + cpw2 - 1) / cpw2;
+        if ((q.chunks <= ch2_max && S_wanted >= 2 * q.chunks) || (waves2 > q.S && waves2 <= s_max))
+            q.ch = 2, q.chunks = chunks2, q.cpw = cpw2, q.S = waves2;
+    }
     if (lut->bits == 4 && q.wn == 7) q.ch = 1;             // (the 2-word kernel of this tile is not built: see launch_ch)
     // (the sparse instruction's narrower unshared tiles do have the registers for 4-word chunks)
     if (mode == SPARSE && !q.split && q.skw == 1 && q.wn <= 2 && tap_bytes % 32 == 0) q.ch = 4, q.chunks /= 2;
@@ -273,21 +291,11 @@ bool dg_sparse_preferred(const dg_lut *lut, const DgProblem &p)
     const Plan dense = plan_for(lut, t, TABLE);
     if (fits_int8(lut) && t.Cin % 64 == 0 && !dense.split && dense.skw > 1 && dense.wn >= 2 && tile_count(t, 2, dense.wn) >= 384)
         return true;
-    // Split K: the dense instruction's split kernel walks K in chunks of 128 positions, so K = 256 gives each tile two
-    // wavefronts at most; the sparse one's chunks are 64, and four wavefronts per tile measured 11 - 19 % faster on
-    // the four 1x1 layers with 256 input channels of ResNet-50 at batch 1 (3.3 - 3.7 against 3.8 - 4.6 us).  With
-    // more chunks than that the dense instruction's split kernel is the faster by 3 - 15 %.
-    if (dense.split && sparse.split && dense.S <= 2 && sparse.S >= 4) return true;
     // And on unshared 64 x 32 tiles where there is more than one per SIMD: 8 - 13 % faster on eight layers measured (3x3
     // layers with 64 channels at 1568 tiles, 1x1 layers and GEMMs with K = 320 and 576 at 1764 and 2048); at 1024 and
     // 784 tiles the two were within 2 % of each other either way.
     return fits_int8(lut) && t.Cin % 64 == 0 && !dense.split && dense.skw == 1 && dense.wn == 1 &&
            tile_count(t, 2, 1) > dg_simd_count();
-}
-
-bool dg_sparse_splits(const dg_lut *lut, const DgProblem &p)
-{
-    return dg_sparse_supports(lut, p) && sparse_plan(lut, sparse_problem(p)).split;
 }
 
 bool dg_sparse_supports(const dg_lut *lut, const DgProblem &p)

@@ -228,11 +228,13 @@ def test_kernel_names_need_no_gpu():
     # (1568 pixel blocks x 8 channel blocks: 32 x 224 tiles leave the busiest SIMD 14 blocks, 64 x 128 tiles 16)
     assert dg.dg_conv_codes_kernel_name(lut, large) == dg.dg_conv_kernel_name(lut, large) == "onehot_smfmac_staged_32x224"
     assert dg.dg_gemm_codes_kernel_name(lut, 64, 196, 576) == "codes_onehot_mfma_splitk_s9"
-    # K = 256 split: the sparse instruction's split kernel (chunks of 64 positions, four wavefronts per tile) on packed
-    # codes; on codes one per byte the dense one's, which packs as it loads
+    # K up to 512 split: the dense instruction walks K in chunks of 64 positions where 128 would cap the wavefronts per tile
     k256 = dg.conv_desc(1, 56, 56, 256, 64, 1, 1, (1, 1), (0, 0))
-    assert dg.dg_conv_kernel_name(lut, k256) == "onehot_smfmac_splitk_s4"
-    assert dg.dg_conv_codes_kernel_name(lut, k256) == "codes_onehot_mfma_splitk_s2"
+    assert dg.dg_conv_kernel_name(lut, k256) == "onehot_mfma_splitk_s4"
+    assert dg.dg_conv_codes_kernel_name(lut, k256) == "codes_onehot_mfma_splitk_s4"
+    assert dg.dg_conv_kernel_name(lut, k256, "mfma_i8") == "mfma_i8_splitk_s4"
+    assert dg.dg_conv_kernel_name(lut, dg.conv_desc(1, 28, 28, 512, 128, 1, 1, (1, 1), (0, 0))) == "onehot_mfma_splitk_s8"
+    assert dg.dg_conv_kernel_name(lut, dg.conv_desc(1, 14, 14, 1024, 256, 1, 1, (1, 1), (0, 0))) == "onehot_mfma_splitk_s8"
     # taps of an odd number of 64-position chunks: staged with a window and 192 channels or more, direct loads with 64
     assert dg.dg_conv_kernel_name(lut, dg.conv_desc(32, 28, 28, 320, 320, 3, 3, (1, 1), (1, 1))) == "onehot_smfmac_staged_32x128"
     assert dg.dg_conv_kernel_name(lut, dg.conv_desc(32, 28, 28, 192, 96, 3, 3, (1, 1), (1, 1))) == "onehot_smfmac_staged_32x64"
