@@ -856,7 +856,7 @@ void launch_split(const DgProblem &p, const Pools &pools, const Plan &q, int64_t
     b.div_ow = make_div((uint32_t)p.OW), b.div_oh = make_div((uint32_t)p.OH);
     b.div_cin = make_div((uint32_t)p.Cin), b.div_kw = make_div((uint32_t)p.KW);
     const dim3 grid((unsigned)blocks11), block(64 * q.S);
-    if constexpr (BITS != 4 && BITS != 20) {
+    if constexpr (BITS != 4 && BITS != 20 && !RAW) {        // (on unpacked codes the host plans 2-word chunks at most)
         if (q.ch == 4) {
             hipLaunchKernelGGL((onehot_splitk_kernel<BITS, 4, TR, TWO, RAW>), grid, block, 0, stream, b);
             return;

@@ -660,7 +660,9 @@ bool dg_onehot_codes_supports(const dg_lut *lut, const DgProblem &p)
 bool dg_onehot_codes_pays(const DgProblem &p)
 {
     const double row_blocks = (p.M + 31) / 32, columns = 32.0 * ((p.N + 31) / 32);
-    return row_blocks * columns * p.K <= 2.0e7;
+    // (and not with the longest reductions: 3x3 windows over 512 channels, K = 4608, measured 9.4 - 9.7 us in one call
+    // against 8.6 - 8.8 us as two kernels on 7x7 and 14x14 images; K = 2304 and 2048 6.1 - 6.2 against 6.4 - 6.7)
+    return row_blocks * columns * p.K <= 2.0e7 && p.K <= 3072;
 }
 
 const char *dg_onehot_codes_config_name(const dg_lut *lut, const DgProblem &p)
@@ -693,7 +695,11 @@ dg_status launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t strea
 {
     // column v of the table, 4 weight codes per word: the permute pools.  Entries beyond int8 go in two planes,
     // T = 256 * hi + lo with lo in [-128, 127] (so hi is within [-128, 128) for every int16 T).
-    const Plan q = plan_for(lut, p, TABLE);
+    Plan q = plan_for(lut, p, TABLE);
+    // On unpacked codes the same wavefronts walk their shares of K in chunks of 64 positions, not 128: four 16-byte loads
+    // of codes and their packing per chunk instead of eight (measured on nine small layers: the one-call step 0.1 - 0.7 us
+    // shorter, 7x7x2048 -> 512 at batch 1 6.85 -> 6.13 us).
+    if (codes && q.split && q.ch == 4) q.ch = 2, q.chunks *= 2, q.cpw *= 2;
     dgoh::Pools pools;
     const int L = 1 << lut->bits, qw = L / 4;
     for (int i = 0; i < 64; ++i) pools.w[i] = 0;
