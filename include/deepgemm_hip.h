@@ -203,6 +203,8 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *   DG_ONEHOT_CH2_MAX  the dense instruction's split-K kernel walks K in chunks of 64 positions instead of 128 where K
  *                    has at most this many chunks of 128 and twice as many wavefronts per tile are wanted (default 4)
  *   DG_ONEHOT_CH2_SMAX and where that gives a tile more wavefronts, up to this many (default 12)
+ *   DG_ONEHOT_CODES_TILED "0": the one-call entry points never use the tiled kernel that packs the codes itself,
+ *                    "1": wherever it applies (default: where it was measured shorter than two kernels)
  *   DG_PERM_PLAN     index of the permute kernel's tile shape
  */
 typedef enum {
@@ -262,12 +264,15 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
 /*
  * The run-time packing stage (Sec. 5.2) and the convolution as ONE call, from activations that are still one code
  * per byte: Xc_dev is device memory, [B][H][W][Cin] uint8, values below 2^bits (higher bits of 2-bit codes are
- * masked off, as dg_pack_activations does), 16-byte aligned for the fused form.  On layers so small that a second
- * kernel launch costs a good part of the layer itself (those the library runs on the one-hot split-K kernel --
- * 2-bit codes, Cin % 32 == 0, variant ONEHOT_MFMA, or AUTO while Cout is small enough that packing once per 32
- * output channels costs less than the launch -- or on the few-columns kernel, variant AUTO or SMALLN)
- * the kernel reads the codes as they are and packs them in registers while loading -- one launch, and Xp_work_dev
- * is not touched.  Every other layer is packed into
+ * masked off, as dg_pack_activations does), 16-byte aligned for the fused form.  Where a second kernel launch
+ * costs a good part of the layer itself the kernel reads the codes as they are and packs them while loading -- one
+ * launch, and Xp_work_dev is not touched.  Those are, for 2-bit codes: the layers the library runs on the one-hot
+ * split-K kernel (Cin % 32 == 0, K <= 3072; variant ONEHOT_MFMA, or AUTO while Cout is small enough that packing
+ * once per 32 output channels costs less than the launch); layers of a few microseconds on the one-hot tiled
+ * kernel's 64 x 32 and 64 x 64 tiles (Cin % 64 == 0; AUTO or ONEHOT_MFMA, up to about 10^9 table operations, more
+ * where the packing kernel would pack pixels a strided 1x1 layer never reads); the layers of the stationary-weight
+ * kernel (K = 64, 128, 256 without a filter window; AUTO or ONEHOT_SMFMAC); and the few-columns kernel (AUTO or
+ * SMALLN).  Every other layer is packed into
  * Xp_work_dev (device, work_bytes >= dg_packed_bytes_bits(B*H*W, Cin, bits), else DG_ERR_BUFFER; DG_ERR_NULL if it
  * is needed and NULL) by the packing kernel and then run as dg_conv2d_lut would run it, on the same stream.
  * Outputs, scale, variant and the other errors as dg_conv2d_lut; the results are identical to dg_pack_activations
@@ -296,7 +301,7 @@ dg_status dg_conv2d_lut_codes_static(const dg_lut *lut, const void *Wp_dev, cons
 /*
  * The same for a GEMM: Ac_dev is device memory, [N][K] uint8 codes; Ap_work_dev (work_bytes >=
  * dg_packed_bytes_bits(N, K, bits)) is used when the packing is not fused (K % 32 != 0, a large problem, another
- * variant, 3- or 4-bit codes).  Outputs, strides, scale and the other errors as dg_gemm_lut.
+ * variant, 3- or 4-bit codes: the conditions above with Cin = K).  Outputs, strides, scale and the other errors as dg_gemm_lut.
  */
 dg_status dg_gemm_lut_codes(const dg_lut *lut, const void *Wp_dev, const uint8_t *Ac_dev, int64_t M, int64_t N,
                             int64_t K, void *Ap_work_dev, size_t work_bytes, int32_t *C_dev, int64_t stride_cm,

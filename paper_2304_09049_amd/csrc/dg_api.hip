@@ -512,6 +512,12 @@ Fuse fuses_packing(const dg_lut *lut, const DgProblem &p_codes, dg_kernel varian
         (variant == DG_KERNEL_ONEHOT_MFMA ||
          (dg_onehot_codes_pays(p_codes) && pick_kernel(lut, p_codes, DG_KERNEL_AUTO) == Pick::OneHot)))
         return Fuse::OneHot;
+    // layers of a few microseconds on the tiled kernels: the dense instruction's narrow tiles pack per 64-row tile
+    if ((variant == DG_KERNEL_AUTO || variant == DG_KERNEL_ONEHOT_MFMA) && dg_onehot_codes_tiled_supports(lut, p_codes) &&
+        dg_onehot_codes_tiled_pays(lut, p_codes)) {
+        const Pick pick = variant == DG_KERNEL_AUTO ? pick_kernel(lut, p_codes, DG_KERNEL_AUTO) : Pick::OneHot;
+        if (pick == Pick::OneHot || pick == Pick::Sparse) return Fuse::OneHot;
+    }
     // (the few-columns kernel packs once per row block and pass of four columns, about 7 % more work for it: less than
     // a launch while the columns are few, which is where AUTO uses that kernel anyway)
     if ((variant == DG_KERNEL_SMALLN || (variant == DG_KERNEL_AUTO && p_codes.N <= 4)) &&

@@ -103,6 +103,9 @@ bool dg_onehot_codes_supports(const dg_lut *lut, const DgProblem &p);
 bool dg_onehot_codes_pays(const DgProblem &p);      // AUTO: the repeated packing costs less than the saved launch
 dg_status dg_launch_onehot_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
 const char *dg_onehot_codes_config_name(const dg_lut *lut, const DgProblem &p);
+// the one-hot tiled kernel (64 x 32 and 64 x 64 tiles of the dense instruction) doing the same on layers of a few microseconds
+bool dg_onehot_codes_tiled_supports(const dg_lut *lut, const DgProblem &p);
+bool dg_onehot_codes_tiled_pays(const dg_lut *lut, const DgProblem &p);    // AUTO: shorter than packing kernel + AUTO's kernel
 bool dg_sparse_supports(const dg_lut *lut, const DgProblem &p);
 bool dg_sparse_preferred(const dg_lut *lut, const DgProblem &p);     // AUTO's choice between the two one-hot kernels
 dg_status dg_launch_sparse(const dg_lut *lut, const DgProblem &p, hipStream_t stream);

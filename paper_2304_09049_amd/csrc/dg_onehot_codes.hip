@@ -18,4 +18,40 @@ void unit_split_codes(const DgProblem &p, const Pools &pools, const Plan &q, boo
             launch_split<2, false, false, true>(p, pools, q, blocks11, stream);
     }
 }
+
+namespace {
+template <int WN, bool TR>
+void launch_codes_tile(const Args &a, int skw, int64_t wave_tiles, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((wave_tiles + 4 / skw - 1) / (4 / skw)));
+    if (skw == 4)
+        hipLaunchKernelGGL((onehot_mfma_kernel<2, 2, WN, 2, TR, false, 4, true>), grid, dim3(256), (main_lds_bytes<2, WN, false, 4>()), stream, a);
+    else if (skw == 2)
+        hipLaunchKernelGGL((onehot_mfma_kernel<2, 2, WN, 2, TR, false, 2, true>), grid, dim3(256), (main_lds_bytes<2, WN, false, 2>()), stream, a);
+    else
+        hipLaunchKernelGGL((onehot_mfma_kernel<2, 2, WN, 2, TR, false, 1, true>), grid, dim3(256), 0, stream, a);
+}
+}   // namespace
+
+void unit_main_codes(const DgProblem &p, const Pools &pools, const Plan &q, bool tr, int64_t wave_tiles, hipStream_t stream)
+{
+    Args a{};
+    a.p = p;
+    a.pools = pools;
+    a.tiles_m = (p.M + 63) / 64;
+    a.wave_tiles = wave_tiles;
+    a.div_ow = make_div((uint32_t)p.OW), a.div_oh = make_div((uint32_t)p.OH);
+    a.div_cin = make_div((uint32_t)p.Cin), a.div_kw = make_div((uint32_t)p.KW);
+    if (q.wn == 2) {
+        if (tr)
+            launch_codes_tile<2, true>(a, q.skw, wave_tiles, stream);
+        else
+            launch_codes_tile<2, false>(a, q.skw, wave_tiles, stream);
+    } else {
+        if (tr)
+            launch_codes_tile<1, true>(a, q.skw, wave_tiles, stream);
+        else
+            launch_codes_tile<1, false>(a, q.skw, wave_tiles, stream);
+    }
+}
 }   // namespace dgoh

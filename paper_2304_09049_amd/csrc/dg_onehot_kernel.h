@@ -342,11 +342,15 @@ __device__ __forceinline__ Column make_column(const DgProblem &p, const FastDiv 
 // alone would leave SIMDs idle or with a single wavefront): SKW wavefronts of the workgroup share a tile and split K
 // between them in contiguous runs of chunks; their accumulators meet in LDS by integer atomics (exact in any order)
 // and each of them stores a share of the tile's blocks.
-template <int BITS, int WM, int WN, int CH, bool TR, bool TWO, int SKW>
+// RAW (the narrow tiles of 2-bit codes on the dense instruction): the activations are codes one per byte and are
+// packed in registers as they are loaded -- once per 64-row tile; on layers of a few microseconds that is less than
+// the launch of the packing kernel.
+template <int BITS, int WM, int WN, int CH, bool TR, bool TWO, int SKW, bool RAW = false>
 __global__ void __launch_bounds__(256, (WM * WN > 8 ? 1 : 2))
 onehot_mfma_kernel(Args a)
 {
     typedef Fmt<BITS> F;
+    static_assert(!RAW || (BITS == 2 && !TWO), "unpacked activations: 2-bit codes on the dense instruction, one plane");
     static_assert(!TWO || (WM == 2 && BITS == 2), "two planes stand in for the two weight row blocks of 2-bit tiles");
     static_assert(BITS == 0 || BITS == 2 || BITS == 3 || BITS == 4 || BITS == 20,
                   "code widths 2, 3, 4; 0 = the decode comparison; 20 = 2-bit codes on the sparse instruction");
@@ -387,8 +391,10 @@ onehot_mfma_kernel(Args a)
         w_ptr[bm] = p.Wp + (int64_t)m * (p.K / F::PER_BYTE) + (F::SPARSE ? 0 : h * (4 * CH));
     }
     Column col[WN];
+    constexpr int LANE_BYTE = RAW ? 16 * CH : 4 * CH;      // activation bytes a lane half reads per chunk
+    const int bpp = RAW ? p.Cin : cq;                       // activation bytes per pixel
 #pragma unroll
-    for (int bn = 0; bn < WN; ++bn) col[bn] = make_column(p, a.div_ow, a.div_oh, n0 + bn * 32 + r, cq, h * (4 * CH));
+    for (int bn = 0; bn < WN; ++bn) col[bn] = make_column(p, a.div_ow, a.div_oh, n0 + bn * 32 + r, bpp, h * LANE_BYTE);
 
     v16i acc[WM][WN];
 #pragma unroll
@@ -455,12 +461,16 @@ onehot_mfma_kernel(Args a)
 #pragma unroll
             for (int bn = 0; bn < WN; ++bn) wb[bn] = load_words<CH>(p.Xp + x_off[bn]);
         } else {
-            const int64_t tap_off = ((int64_t)kh * p.W + kw) * cq + ci / F::PER_BYTE;
+            const int64_t tap_off = ((int64_t)kh * p.W + kw) * bpp + (RAW ? ci : ci / F::PER_BYTE);
 #pragma unroll
             for (int bn = 0; bn < WN; ++bn) {
                 const int ih = col[bn].ih0 + kh, iw = col[bn].iw0 + kw;
                 vb[bn] = col[bn].ok & ((uint32_t)ih < (uint32_t)p.H) & ((uint32_t)iw < (uint32_t)p.W);
-                wb[bn] = load_words<CH>(vb[bn] ? p.Xp + col[bn].off0 + tap_off : p.Xp + h * (4 * CH));
+                const uint8_t *ptr = vb[bn] ? p.Xp + col[bn].off0 + tap_off : p.Xp + h * LANE_BYTE;
+                if constexpr (RAW)
+                    wb[bn] = load_codes<CH>(ptr);
+                else
+                    wb[bn] = load_words<CH>(ptr);
             }
             next_position();
         }
@@ -889,6 +899,8 @@ void unit_sparse_ws(const DgProblem &, const uint32_t (&)[4], int, bool raw, hip
 void unit_sparse_staged(const DgProblem &, const Pools &, int32_t bias, const Plan &, int64_t, hipStream_t);      // dg_sparse_staged_kernel.h
 // the split-K kernel on activations still one code per byte (one- and two-plane tables, either output layout)
 void unit_split_codes(const DgProblem &, const Pools &, const Plan &, bool two, bool tr, int64_t, hipStream_t);
+// the tiled kernel on unpacked codes: 64 x 32 and 64 x 64 tiles (q.wn = 1, 2), 2-word chunks, any sharing of K
+void unit_main_codes(const DgProblem &, const Pools &, const Plan &, bool tr, int64_t wave_tiles, hipStream_t);
 #undef DGOH_UNIT
 #undef DGOH_UNIT_SPLIT
 

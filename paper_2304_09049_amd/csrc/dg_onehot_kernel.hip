@@ -665,8 +665,49 @@ bool dg_onehot_codes_pays(const DgProblem &p)
     return row_blocks * columns * p.K <= 2.0e7 && p.K <= 3072;
 }
 
+// The plan of the tiled kernel on unpacked codes: the dense instruction's, in 2-word chunks.
+static bool codes_tiled_plan(const dg_lut *lut, const DgProblem &p, Plan *out)
+{
+    if (lut->dtype == DG_LUT_F32 || lut->bits != 2 || !fits_int8(lut)) return false;
+    if (p.Cin % 64 != 0 || !offsets_fit(p, 1)) return false;
+    Plan q = plan_for(lut, p, TABLE);
+    if (q.split || q.two || q.wm != 2 || q.wn > 2) return false;
+    if (q.ch == 4) q.ch = 2, q.chunks *= 2;
+    if (q.ch != 2 || (uintptr_t)p.Wp % 8 != 0 || (uintptr_t)p.Xp % 16 != 0) return false;
+    *out = q;
+    return true;
+}
+
+bool dg_onehot_codes_tiled_supports(const dg_lut *lut, const DgProblem &p)
+{
+    Plan q;
+    return codes_tiled_plan(lut, p, &q);
+}
+
+// Measured on 44 layer shapes (ResNet-50 and ResNet-18 layers at batch 4 to 32): packing in this kernel costs about
+// 1.6 us per 10^9 table operations (2MNK) over the best kernel on packed codes -- the narrow tiles of the dense
+// instruction, loads of 16 bytes per 16 codes, the packing repeated per 64-row tile -- and the packing kernel 1.8 us
+// plus 0.17 us per MB of codes, ALL the input's codes, also the three quarters that a 1x1 layer with stride 2 never
+// reads.  So: layers up to about 10^9 operations (14x14x1024 -> 256 at batch 8: 5.7 against 6.7 us; 56x56x64 -> 64 3x3 at
+// batch 4: 6.1 against 7.4), and strided ones further up (56x56x256 -> 128 with stride 2 at batch 32: 7.8 against 11.7).
+// DG_ONEHOT_CODES_TILED: 0 never, 1 always (A/B measurement).
+bool dg_onehot_codes_tiled_pays(const dg_lut *, const DgProblem &p)
+{
+    if (const char *e = dg_override("DG_ONEHOT_CODES_TILED")) return atoi(e) != 0;
+    const double ops = 2.0 * (double)p.M * (double)p.N * (double)p.K;
+    const double images = (double)p.N / ((double)p.OH * p.OW), code_bytes = images * p.H * p.W * p.Cin;
+    return 1.6e-9 * ops + 0.2 < 1.8 + 0.17e-6 * code_bytes;
+}
+
 const char *dg_onehot_codes_config_name(const dg_lut *lut, const DgProblem &p)
 {
+    Plan t;
+    if (!plan_for(lut, p, TABLE).split && codes_tiled_plan(lut, p, &t)) {
+        static const char *const tiled[3][2] = {{"codes_onehot_mfma_64x32", "codes_onehot_mfma_64x64"},
+                                                {"codes_onehot_mfma_64x32_k2", "codes_onehot_mfma_64x64_k2"},
+                                                {"codes_onehot_mfma_64x32_k4", "codes_onehot_mfma_64x64_k4"}};
+        return tiled[t.skw == 4 ? 2 : (t.skw == 2 ? 1 : 0)][t.wn == 2 ? 1 : 0];
+    }
     static const char *const names[2][17] = {
         {"", "codes_onehot_mfma_splitk_s1", "codes_onehot_mfma_splitk_s2", "codes_onehot_mfma_splitk_s3",
          "codes_onehot_mfma_splitk_s4", "codes_onehot_mfma_splitk_s5", "codes_onehot_mfma_splitk_s6",
@@ -722,9 +763,18 @@ dg_status launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t strea
                                             {unit_main_b4_t0_k1, unit_main_b4_t1_k1}, {unit_main_b22_t0_k1, unit_main_b22_t1_k1}};
     static const MainFn shared_units[2][2] = {{unit_main_b2_t0_k2, unit_main_b2_t1_k2}, {unit_main_b2_t0_k4, unit_main_b2_t1_k4}};
     const int width = q.two ? 3 : lut->bits - 2;
+    if (codes && !q.split) {
+        Plan t;
+        if (!codes_tiled_plan(lut, p, &t))
+            return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel on unpacked codes: this layer's plan has no such form");
+        const int64_t tiles = tile_count(p, 2, t.wn);
+        if (tiles > INT32_MAX) return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel: too many tiles for one grid");
+        unit_main_codes(p, pools, t, tr != 0, tiles, stream);
+        return dg_check_launch("onehot_mfma_kernel (unpacked codes)");
+    }
     if (codes) {
-        if (!q.split || lut->bits != 2)
-            return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel on unpacked codes: small layers with 2-bit codes only");
+        if (lut->bits != 2)
+            return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel on unpacked codes: 2-bit codes only");
         unit_split_codes(p, pools, q, q.two, tr != 0, blocks11, stream);
         return dg_check_launch("onehot_splitk_kernel (unpacked codes)");
     }

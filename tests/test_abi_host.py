@@ -235,6 +235,15 @@ def test_kernel_names_need_no_gpu():
     assert dg.dg_conv_kernel_name(lut, k256, "mfma_i8") == "mfma_i8_splitk_s4"
     assert dg.dg_conv_kernel_name(lut, dg.conv_desc(1, 28, 28, 512, 128, 1, 1, (1, 1), (0, 0))) == "onehot_mfma_splitk_s8"
     assert dg.dg_conv_kernel_name(lut, dg.conv_desc(1, 14, 14, 1024, 256, 1, 1, (1, 1), (0, 0))) == "onehot_mfma_splitk_s8"
+    # layers of a few microseconds on the tiled kernels: one call packs in the dense instruction's narrow tiles (up to
+    # about 1e9 table operations, more where a strided 1x1 layer leaves most of the input unread), larger ones do not
+    mid = dg.conv_desc(8, 14, 14, 1024, 256, 1, 1, (1, 1), (0, 0))
+    assert dg.dg_conv_kernel_name(lut, mid) == "onehot_smfmac_staged_32x64_k4"
+    assert dg.dg_conv_codes_kernel_name(lut, mid) == "codes_onehot_mfma_64x32_k4"
+    strided = dg.conv_desc(32, 56, 56, 256, 128, 1, 1, (2, 2), (0, 0))
+    assert dg.dg_conv_codes_kernel_name(lut, strided) == "codes_onehot_mfma_64x32"
+    big = dg.conv_desc(32, 14, 14, 1024, 256, 1, 1, (1, 1), (0, 0))
+    assert dg.dg_conv_codes_kernel_name(lut, big) == dg.dg_conv_kernel_name(lut, big) == "onehot_smfmac_staged_32x64"
     # taps of an odd number of 64-position chunks: staged with a window and 192 channels or more, direct loads with 64
     assert dg.dg_conv_kernel_name(lut, dg.conv_desc(32, 28, 28, 320, 320, 3, 3, (1, 1), (1, 1))) == "onehot_smfmac_staged_32x128"
     assert dg.dg_conv_kernel_name(lut, dg.conv_desc(32, 28, 28, 192, 96, 3, 3, (1, 1), (1, 1))) == "onehot_smfmac_staged_32x64"

@@ -281,11 +281,12 @@ def test_convolution_from_unpacked_codes(monkeypatch):
         dg.dg_conv2d_lut_codes(case.lut, case.Wp, base[3:], case.desc)
     assert e.value.status == 1
     # layers that are not fused: a channel count the one-hot kernels do not take, a variant that never fuses, and a
-    # layer large enough for the tiled kernels -- packed into the work buffer, then run as dg_conv2d_lut runs them
+    # layer for the tiled kernels whose channels are not whole 64-code chunks -- packed into the work buffer, then run
+    # as dg_conv2d_lut runs them
     monkeypatch.delenv("DG_ONEHOT_PLAN")
     lw, la, entry = LEVELS["nonuniform_i8"]
     for (shape, variant) in (((2, 9, 9, 16, 20, 3, 3, (1, 1), (1, 1)), "auto"), ((1, 14, 14, 64, 64, 3, 3, (1, 1), (1, 1)), "lds"),
-                             ((8, 56, 56, 64, 64, 3, 3, (1, 1), (1, 1)), "auto")):
+                             ((8, 56, 56, 96, 64, 3, 3, (1, 1), (1, 1)), "auto")):
         B, H, W, Cin, Cout, KH, KW, stride, pad = shape
         c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=5)
         case = GpuCase(c, levels=(lw, la), entry=entry)
@@ -305,11 +306,54 @@ def test_convolution_from_unpacked_codes(monkeypatch):
         assert e.value.status == 4
 
 
+@pytest.mark.parametrize("plan,name", [("1", "codes_onehot_mfma_64x32"), ("2", "codes_onehot_mfma_64x64"),
+                                       ("1k2", "codes_onehot_mfma_64x32_k2"), ("2k2", "codes_onehot_mfma_64x64_k2"),
+                                       ("1k4", "codes_onehot_mfma_64x32_k4"), ("2k4", "codes_onehot_mfma_64x64_k4")])
+def test_tiled_kernel_on_unpacked_codes(plan, name, monkeypatch):
+    """The one-call entry points on the dense instruction's tiled kernel packing the codes itself (64 x 32 and 64 x 64
+    tiles, K unshared or shared by 2 or 4 wavefronts): convolutions with windows, strides and padding, 64 to 320 channels,
+    ragged M and N, garbage above bit 1 of the code bytes, scaled output; GEMMs in both output layouts; no work buffer."""
+    monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
+    lw, la, entry = LEVELS["nonuniform_i8"]
+    convs = [(2, 9, 7, 64, 36, 3, 3, (1, 1), (1, 1)), (1, 13, 11, 192, 70, 3, 3, (2, 2), (1, 1)), (3, 6, 5, 320, 64, 1, 1, (1, 1), (0, 0)),
+             (1, 20, 17, 128, 130, 3, 2, (1, 2), (1, 0)), (2, 15, 15, 64, 100, 5, 5, (1, 1), (2, 2)), (1, 29, 29, 256, 70, 3, 3, (1, 1), (1, 1))]
+    for (B, H, W, Cin, Cout, KH, KW, stride, pad) in convs:
+        c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        for variant in ("auto", "onehot_mfma"):
+            assert dg.dg_conv_codes_kernel_name(case.lut, case.desc, variant) == name
+        acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
+        dirty = c.Ac | (np.random.default_rng(H + Cout).integers(0, 64, size=c.Ac.shape, dtype=np.uint8) << 2)
+        Xc = torch.from_numpy(dirty).cuda()
+        got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, variant="onehot_mfma")
+        torch.cuda.synchronize()
+        _assert_same(got.cpu().numpy(), acc, f"tiled conv on codes {(B, H, W, Cin, Cout, KH, KW, stride, pad)}")
+        got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, scale=case.scale)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), oracle.scale_epilogue_nhwc(acc, c.scale))
+    for (M, N, K) in [(70, 1000, 512), (64, 333, 576), (200, 64, 1280), (33, 5, 640)]:
+        inp = wl.small_gemm(M, N, K, seed=M + N + K)
+        case = GpuCase(inp, levels=(lw, la), entry=entry)
+        assert dg.dg_gemm_codes_kernel_name(case.lut, M, N, K) == name
+        Ac = torch.from_numpy(inp.Ac).cuda()
+        want = oracle.gemm(inp.Wc, inp.Ac, lw, la)
+        got = dg.dg_gemm_lut_codes(case.lut, case.Wp, Ac, M, N, K)
+        torch.cuda.synchronize()
+        _assert_same(got.cpu().numpy(), want, f"tiled gemm on codes {(M, N, K)} row-major")
+        out = torch.full((N, M), -7, dtype=torch.int32, device="cuda")
+        dg.dg_gemm_lut_codes(case.lut, case.Wp, Ac, M, N, K, out=out, strides=(1, M))
+        torch.cuda.synchronize()
+        _assert_same(out.cpu().numpy(), want.T.copy(), f"tiled gemm on codes {(M, N, K)} column-major")
+    # channels that are not whole 64-code chunks, or a wider tile: the packing kernel first
+    c = wl.small_conv(1, 8, 8, 96, 32, 3, 3, (1, 1), (1, 1), seed=1)
+    assert not dg.dg_conv_codes_kernel_name(GpuCase(c, levels=(lw, la), entry=entry).lut, GpuCase(c, levels=(lw, la), entry=entry).desc).startswith("codes_")
+
+
 def test_gemm_from_unpacked_codes(monkeypatch):
     """dg_gemm_lut_codes against the oracle: small GEMMs where the split-K kernel packs the codes itself (row-major and
     column-major output, scaled output, one- and two-plane tables, ragged M and N, chunk widths of 1 and 2 words), and
     GEMMs with one to a few columns on the few-columns kernel, which does the same, and GEMMs it hands to the packing
-    kernel first (K % 32 != 0, a large problem, another variant)."""
+    kernel first (K % 32 != 0, a tiled-kernel problem with K % 64 != 0, another variant)."""
     for table in ("nonuniform_i8", "extreme_i16"):
         lw, la, entry = LEVELS[table]
         for (M, N, K) in [(64, 196, 576), (70, 300, 96), (33, 250, 1024), (130, 77, 64), (5, 16, 3072), (1, 40, 32)]:
@@ -345,7 +389,7 @@ def test_gemm_from_unpacked_codes(monkeypatch):
         got = dg.dg_gemm_lut_codes(case.lut, case.Wp, Ac, M, N, K, scale=case.scale, variant=variant)
         torch.cuda.synchronize()
         assert np.array_equal(got.cpu().numpy(), oracle.scale_epilogue_rows(want, g.scale)), "scaled codes gemm, few columns"
-    for (M, N, K, variant) in [(17, 9, 20, "auto"), (256, 4096, 512, "auto"), (64, 196, 576, "perm")]:
+    for (M, N, K, variant) in [(17, 9, 20, "auto"), (256, 4096, 544, "auto"), (64, 196, 576, "perm")]:
         g = wl.small_gemm(M, N, K, seed=3)
         case = GpuCase(g, levels=(lw, la), entry=entry)
         name = dg.dg_gemm_codes_kernel_name(case.lut, M, N, K, variant)
