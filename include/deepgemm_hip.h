@@ -274,7 +274,9 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
  * kernel (K = 64, 128, 256 without a filter window; AUTO or ONEHOT_SMFMAC); and the few-columns kernel (AUTO or
  * SMALLN).  Every other layer is packed into
  * Xp_work_dev (device, work_bytes >= dg_packed_bytes_bits(B*H*W, Cin, bits), else DG_ERR_BUFFER; DG_ERR_NULL if it
- * is needed and NULL) by the packing kernel and then run as dg_conv2d_lut would run it, on the same stream.
+ * is needed and NULL) by the packing kernel and then run as dg_conv2d_lut would run it, on the same stream (of a
+ * 1x1 layer with a stride and no padding only the pixels it reads are packed, [B][OH][OW][Cin/4] at the start of the
+ * buffer, and the layer runs on those without the stride).
  * Outputs, scale, variant and the other errors as dg_conv2d_lut; the results are identical to dg_pack_activations
  * followed by dg_conv2d_lut.  dg_conv_codes_kernel_name names the convolution kernel that would run: "codes_..."
  * for the fused form, else dg_conv_kernel_name's answer.

@@ -81,6 +81,10 @@ dg_status dg_check_launch(const char *what);
 // Kernel launchers (each validates nothing: the API layer has done that).
 dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits, uint8_t *packed,
                          hipStream_t stream);
+// 2-bit codes of the pixels (b, oh * sh, ow * sw) only, [B][H][W][Cin] -> [B][OH][OW][Cin / 4]; Cin % 16 == 0, codes
+// 16-byte and packed 4-byte aligned (the caller checks)
+dg_status dg_launch_pack_strided_pixels(const uint8_t *codes, int64_t B, int32_t H, int32_t W, int32_t OH, int32_t OW, int32_t sh,
+                                        int32_t sw, int32_t Cin, uint8_t *packed, hipStream_t stream);
 dg_status dg_launch_quantize_pack(const float *x, int64_t rows, int64_t K, float scale, float zero_point,
                                   int32_t lo, uint8_t *packed, hipStream_t stream);
 dg_status dg_launch_dequantize(const int32_t *acc, int64_t rows, int64_t C, const float *scale, float *out,

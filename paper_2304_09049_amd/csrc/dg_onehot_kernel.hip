@@ -687,15 +687,17 @@ bool dg_onehot_codes_tiled_supports(const dg_lut *lut, const DgProblem &p)
 // Measured on 44 layer shapes (ResNet-50 and ResNet-18 layers at batch 4 to 32): packing in this kernel costs about
 // 1.6 us per 10^9 table operations (2MNK) over the best kernel on packed codes -- the narrow tiles of the dense
 // instruction, loads of 16 bytes per 16 codes, the packing repeated per 64-row tile -- and the packing kernel 1.8 us
-// plus 0.17 us per MB of codes, ALL the input's codes, also the three quarters that a 1x1 layer with stride 2 never
-// reads.  So: layers up to about 10^9 operations (14x14x1024 -> 256 at batch 8: 5.7 against 6.7 us; 56x56x64 -> 64 3x3 at
-// batch 4: 6.1 against 7.4), and strided ones further up (56x56x256 -> 128 with stride 2 at batch 32: 7.8 against 11.7).
+// plus 0.17 us per MB of codes it packs (all the input's, except that of a 1x1 layer with a stride only the pixels
+// read).  So: layers up to about 10^9 operations (14x14x1024 -> 256 at batch 8: 5.7 against 6.7 us; 56x56x64 -> 64 3x3 at
+// batch 4: 6.1 against 7.4), and a little further up where there is much to pack.
 // DG_ONEHOT_CODES_TILED: 0 never, 1 always (A/B measurement).
 bool dg_onehot_codes_tiled_pays(const dg_lut *, const DgProblem &p)
 {
     if (const char *e = dg_override("DG_ONEHOT_CODES_TILED")) return atoi(e) != 0;
     const double ops = 2.0 * (double)p.M * (double)p.N * (double)p.K;
-    const double images = (double)p.N / ((double)p.OH * p.OW), code_bytes = images * p.H * p.W * p.Cin;
+    const bool strided_1x1 = p.KH == 1 && p.KW == 1 && p.ph == 0 && p.pw == 0;     // (packed pixel by pixel: only those read)
+    const double images = (double)p.N / ((double)p.OH * p.OW);
+    const double code_bytes = strided_1x1 ? (double)p.N * p.Cin : images * p.H * p.W * p.Cin;
     return 1.6e-9 * ops + 0.2 < 1.8 + 0.17e-6 * code_bytes;
 }
 

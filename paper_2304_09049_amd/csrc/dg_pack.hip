@@ -43,6 +43,22 @@ pack_vec16_unrolled_kernel(const uint4 *__restrict__ codes, uint32_t *__restrict
     }
 }
 
+// Only the pixels a 1x1 convolution with a stride reads: output pixel (b, oh, ow) of the packed tensor [B][OH][OW][Cin/4]
+// is input pixel (b, oh * sh, ow * sw).  `groups` 16-code groups per pixel, fewer than 2^31 in all; a lane moves one group.
+__global__ void __launch_bounds__(256)
+pack_strided_pixels_kernel(const uint4 *__restrict__ codes, uint32_t *__restrict__ packed, uint32_t groups16, uint32_t groups,
+                           DgFastDiv div_groups, DgFastDiv div_ow, DgFastDiv div_oh, int32_t OH, int32_t OW, int32_t H, int32_t W,
+                           int32_t sh, int32_t sw)
+{
+    const uint32_t stride = gridDim.x * blockDim.x;
+    for (uint32_t g = blockIdx.x * blockDim.x + threadIdx.x; g < groups16; g += stride) {
+        const uint32_t pixel = dg_fdiv(g, div_groups), row = dg_fdiv(pixel, div_ow), b = dg_fdiv(row, div_oh);
+        const uint32_t within = g - pixel * groups, ow = pixel - row * (uint32_t)OW, oh = row - b * (uint32_t)OH;
+        const uint4 v = codes[(((int64_t)b * H + (int64_t)oh * sh) * W + (int64_t)ow * sw) * groups + within];
+        packed[g] = pack4(v.x) | (pack4(v.y) << 8) | (pack4(v.z) << 16) | (pack4(v.w) << 24);
+    }
+}
+
 // Any alignment, any count that is a multiple of 4: one packed byte per lane per step.
 __global__ void __launch_bounds__(256)
 pack_bytes_kernel(const uint8_t *__restrict__ codes, uint8_t *__restrict__ packed, int64_t first_group,
@@ -172,6 +188,20 @@ dg_status dg_launch_pack(const uint8_t *codes, int64_t rows, int64_t K, int bits
         return dg_check_launch("pack_bytes_kernel");
     }
     return DG_OK;
+}
+
+dg_status dg_launch_pack_strided_pixels(const uint8_t *codes, int64_t B, int32_t H, int32_t W, int32_t OH, int32_t OW, int32_t sh,
+                                        int32_t sw, int32_t Cin, uint8_t *packed, hipStream_t stream)
+{
+    const int64_t groups16 = B * OH * OW * (Cin / 16);
+    if (groups16 >= ((int64_t)1 << 31)) return dg_fail(DG_ERR_UNSUPPORTED, "pack_strided_pixels_kernel: 2^35 codes or more");
+    int64_t blocks = (groups16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (blocks < 1) return DG_OK;
+    hipLaunchKernelGGL(pack_strided_pixels_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint4 *)codes,
+                       (uint32_t *)packed, (uint32_t)groups16, (uint32_t)(Cin / 16), dg_make_div((uint32_t)(Cin / 16)),
+                       dg_make_div((uint32_t)OW), dg_make_div((uint32_t)OH), OH, OW, H, W, sh, sw);
+    return dg_check_launch("pack_strided_pixels_kernel");
 }
 
 namespace {

@@ -286,18 +286,29 @@ def test_convolution_from_unpacked_codes(monkeypatch):
     monkeypatch.delenv("DG_ONEHOT_PLAN")
     lw, la, entry = LEVELS["nonuniform_i8"]
     for (shape, variant) in (((2, 9, 9, 16, 20, 3, 3, (1, 1), (1, 1)), "auto"), ((1, 14, 14, 64, 64, 3, 3, (1, 1), (1, 1)), "lds"),
-                             ((8, 56, 56, 96, 64, 3, 3, (1, 1), (1, 1)), "auto")):
+                             ((8, 56, 56, 96, 64, 3, 3, (1, 1), (1, 1)), "auto"),
+                             # 1x1 with a stride, no padding: only the pixels read are packed, and the layer runs on them
+                             # without the stride (odd image sizes, different strides, a layer for the stationary-weight kernel)
+                             ((8, 56, 56, 48, 64, 1, 1, (2, 2), (0, 0)), "auto"), ((4, 30, 31, 16, 40, 1, 1, (2, 3), (0, 0)), "auto"),
+                             ((3, 29, 30, 256, 64, 1, 1, (2, 2), (0, 0)), "lds"), ((16, 57, 56, 256, 96, 1, 1, (2, 2), (0, 0)), "onehot_smfmac")):
         B, H, W, Cin, Cout, KH, KW, stride, pad = shape
         c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=5)
         case = GpuCase(c, levels=(lw, la), entry=entry)
         name = dg.dg_conv_codes_kernel_name(case.lut, case.desc, variant)
-        assert not name.startswith("codes_") and name == case.kernel_name(variant)
+        assert not name.startswith("codes_")
         Xc = torch.from_numpy(c.Ac).cuda()
         work = torch.zeros(B * H * W * Cin // 4, dtype=torch.uint8, device="cuda")
         got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, work=work, variant=variant)
         torch.cuda.synchronize()
         _assert_same(got.cpu().numpy(), oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad), f"unfused {shape}")
-        _assert_same(work.cpu().numpy().reshape(-1, Cin // 4), oracle.pack_codes(c.Ac.reshape(-1, Cin)), "work buffer")
+        if stride == (1, 1):
+            assert name == case.kernel_name(variant)
+            _assert_same(work.cpu().numpy().reshape(-1, Cin // 4), oracle.pack_codes(c.Ac.reshape(-1, Cin)), "work buffer")
+        else:
+            read = np.ascontiguousarray(c.Ac.reshape(B, H, W, Cin)[:, ::stride[0], ::stride[1], :]).reshape(-1, Cin)
+            _assert_same(work.cpu().numpy()[:read.shape[0] * Cin // 4].reshape(-1, Cin // 4), oracle.pack_codes(read), "work buffer")
+            if variant == "onehot_smfmac":
+                assert name == "onehot_smfmac_ws_32xK"
         with pytest.raises(dg.DgError) as e:                                                  # needed and missing / too small
             dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, variant=variant)
         assert e.value.status == 1
