@@ -195,6 +195,7 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *                    minus the smallest one, the sums starting at the matching negative value (its default on
  *                    problems of 2MNK >= 2e10, where that lowers the matrix pipe's power draw)
  *   DG_WS_WAVES      target number of wavefronts of the "ws" kernel (default: one per SIMD)
+ *   DG_WS_STRIDED    "0": AUTO never takes the "ws" kernel for a 1x1 layer with a stride, "1": for every such layer
  *   DG_WS_COUNT_STORES "0": the "ws" kernel that packs codes itself waits for its stores too whenever it waits for
  *                    staged codes (by default it counts the stores it has issued and lets them drain)
  *   DG_FEWN_WAVES    wavefronts per workgroup of the "fewn" kernel (1..8)

@@ -386,12 +386,14 @@ dg_status dg_launch_sparse(const dg_lut *lut, const DgProblem &p0, hipStream_t s
 
 namespace {
 
-bool sparse_ws_takes(const dg_lut *lut, const DgProblem &p)
+// `packed`: the activations are packed (then a 1x1 convolution may have a stride: a lane works out its pixel's row)
+bool sparse_ws_takes(const dg_lut *lut, const DgProblem &p, bool packed = true)
 {
     if (lut->dtype == DG_LUT_F32 || lut->bits != 2 || !fits_int8(lut)) return false;
     if (p.K != 64 && p.K != 128 && p.K != 256) return false;          // the whole dense operand of 32 rows stays in registers
-    // every "pixel" is one contiguous row of K codes: a GEMM, or a 1x1 convolution without stride or padding
-    if (p.KH != 1 || p.KW != 1 || p.sh != 1 || p.sw != 1 || p.ph != 0 || p.pw != 0) return false;
+    // every "pixel" is one contiguous row of K codes: a GEMM, or a 1x1 convolution without padding
+    if (p.KH != 1 || p.KW != 1 || p.ph != 0 || p.pw != 0) return false;
+    if ((p.sh != 1 || p.sw != 1) && (!packed || sparse_transposes(p))) return false;
     if (sparse_transposes(p) && !sparse_can_transpose(p)) return false;
     const DgProblem t = sparse_problem(p);
     if (t.stride_cm != 1) return false;                               // the 32 channels of a lane half are stored side by side
@@ -427,7 +429,16 @@ bool dg_sparse_ws_preferred(const dg_lut *lut, const DgProblem &p)
     if (!sparse_ws_takes(lut, p)) return false;
     if (const char *force = dg_override("DG_ONEHOT_PLAN")) return strcmp(force, "ws") == 0;     // (tests reach it on small shapes)
     const DgProblem t = sparse_problem(p);
-    return ((int64_t)(t.M + 31) / 32) * (((int64_t)t.N + 31) / 32) >= (int64_t)dg_simd_count() / 2;
+    const int64_t blocks = ((int64_t)(t.M + 31) / 32) * (((int64_t)t.N + 31) / 32);
+    if (p.sh != 1 || p.sw != 1) {
+        // With a stride a pixel's row is a part of a cache line whose rest is not read.  Measured against AUTO's other
+        // choices on 60 layers with stride 2 (K = 64, 128, 256; 64 to 1024 output channels; batch 4 to 64): ahead only
+        // with K = 256 from about 12 blocks per SIMD up (8 - 13 % at 12544 blocks, 40 % from 25088), 0 - 10 % behind
+        // on most others.  DG_WS_STRIDED: 0 never, 1 always.
+        if (const char *e = dg_override("DG_WS_STRIDED")) return atoi(e) != 0;
+        return t.K == 256 && blocks >= 12 * (int64_t)dg_simd_count();
+    }
+    return blocks >= (int64_t)dg_simd_count() / 2;
 }
 
 namespace {
@@ -456,7 +467,7 @@ dg_status dg_launch_sparse_ws(const dg_lut *lut, const DgProblem &p0, hipStream_
 // (the activations are its pixels, not, as in a transposed GEMM, its stationary operand).
 bool dg_sparse_ws_codes_supports(const dg_lut *lut, const DgProblem &p)
 {
-    return sparse_ws_takes(lut, p) && !sparse_transposes(p);
+    return sparse_ws_takes(lut, p, false) && !sparse_transposes(p);
 }
 
 dg_status dg_launch_sparse_ws_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream) { return launch_ws(lut, p, true, stream); }

@@ -29,6 +29,7 @@ struct WsArgs {
     int32_t streams;             // runs of pixel blocks; wavefronts = row_blocks * streams
     int32_t run, longer;         // the first `longer` runs have run + 1 pixel blocks, the others `run`
     FastDiv div_row_blocks;
+    FastDiv div_ow, div_oh;      // STRIDED: output pixel -> (image, row, column)
     int32_t count_stores;        // RAW: 0 = a wait for staged codes also waits for the stores issued so far (A/B measurement)
 };
 
@@ -58,11 +59,14 @@ struct WsArgs {
 // behind two blocks of codes), the second block only after the dense operands are built (the address unit serves
 // every wavefront's first block first), and a wait for staged codes does not wait for the stores issued since: the
 // wavefront counts them (9.5 -> 8.9 us on that layer; the same at batch 8: 5.2 -> 4.7 us).
-template <int T, int G, bool RAW>
+// STRIDED (packed activations): a 1x1 convolution with a stride and no padding -- output pixel (b, oh, ow) reads the
+// row of input pixel (b, oh * sh, ow * sw).
+template <int T, int G, bool RAW, bool STRIDED = false>
 __global__ void __launch_bounds__(256, (!RAW && T * G > 32 ? 1 : 2))
 smfmac_ws_kernel(WsArgs a)
 {
     static_assert(T == 2 || T == 4 || T == 8, "K = 64, 128 or 256");
+    static_assert(!(RAW && STRIDED), "the form that packs reads contiguous pixels");
     __shared__ uint2 s_rows[16];                            // the table of row pairs, one for the workgroup
     extern __shared__ uint4 s_codes[];                      // RAW: [wavefront][2][32 pixels x 2 T segments]
     const DgProblem &p = a.p;
@@ -112,7 +116,12 @@ smfmac_ws_kernel(WsArgs a)
     auto fetch = [&](int64_t blk) {                         // rows beyond N re-read row N - 1 (their sums are not stored)
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const int64_t n = min((blk + g) * 32 + r, (int64_t)last_row);
+            int64_t n = min((blk + g) * 32 + r, (int64_t)last_row);
+            if constexpr (STRIDED) {
+                const uint32_t line = fdiv((uint32_t)n, a.div_ow), image = fdiv(line, a.div_oh);
+                const int64_t ow = n - (int64_t)line * p.OW, oh = (int64_t)line - (int64_t)image * p.OH;
+                n = ((int64_t)image * p.H + oh * p.sh) * p.W + ow * p.sw;
+            }
             if (blk + g < b1) x[g] = load_words_any<T>(x_base + n * row_bytes);
         }
     };
@@ -261,6 +270,8 @@ inline void launch_sparse_ws(const DgProblem &p, const uint32_t (&rows)[4], int 
     a.run = pixel_blocks / streams;
     a.longer = pixel_blocks % streams;
     a.div_row_blocks = make_div((uint32_t)a.row_blocks);
+    a.div_ow = make_div((uint32_t)p.OW), a.div_oh = make_div((uint32_t)p.OH);
+    const bool strided = p.sh != 1 || p.sw != 1;           // (the host sends these on packed activations only)
     a.count_stores = 1;
     if (const char *e = dg_override("DG_WS_COUNT_STORES")) a.count_stores = atoi(e) != 0;
     const int64_t waves = (int64_t)a.row_blocks * streams;
@@ -275,6 +286,8 @@ inline void launch_sparse_ws(const DgProblem &p, const uint32_t (&rows)[4], int 
             const int lds = 4 * 2 * 32 * 32 * T;                                                                      \
             (void)hipFuncSetAttribute((const void *)smfmac_ws_kernel<T, G, true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds); \
             hipLaunchKernelGGL((smfmac_ws_kernel<T, G, true>), grid, dim3(256), lds, stream, a);                      \
+        } else if (strided) {                                                                                         \
+            hipLaunchKernelGGL((smfmac_ws_kernel<T, G, false, true>), grid, dim3(256), 0, stream, a);                 \
         } else {                                                                                                      \
             hipLaunchKernelGGL((smfmac_ws_kernel<T, G, false>), grid, dim3(256), 0, stream, a);                       \
         }                                                                                                             \

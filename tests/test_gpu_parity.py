@@ -929,7 +929,8 @@ def test_stationary_weight_kernel(K, waves, monkeypatch):
     """The sparse-instruction kernel with stationary weight operands (K = 64, 128, 256, no filter window), forced on
     shapes with ragged M and N: runs of one, of an even and of an odd number of pixel blocks per wavefront (`waves`: 0 =
     the default count, 3 and 7 = long runs, 100000 = one block per wavefront); GEMM with column-major output (run as it
-    is) and row-major output (run transposed), 1x1 convolution with int32, scaled fp32 and re-quantised packed output."""
+    is) and row-major output (run transposed), 1x1 convolution -- also with strides, equal and unequal, on odd image
+    sizes -- with int32, scaled fp32 and re-quantised packed output."""
     monkeypatch.setenv("DG_ONEHOT_PLAN", "ws")
     if waves:
         monkeypatch.setenv("DG_WS_WAVES", str(abs(waves)))
@@ -946,12 +947,13 @@ def test_stationary_weight_kernel(K, waves, monkeypatch):
         dg.dg_gemm_lut(case.lut, case.Wp, case.Ap, M, N, K, out=out, variant="onehot_smfmac", strides=(1, M))
         torch.cuda.synchronize()
         _assert_same(out.cpu().numpy(), want.T.copy(), f"ws gemm {(M, N, K)} column-major")
-    for (B, H, W, Cout) in [(3, 9, 7, 36), (1, 31, 33, 64), (2, 16, 16, 100)]:
-        c = wl.small_conv(B, H, W, K, Cout, 1, 1, (1, 1), (0, 0), seed=H + K + Cout, scale=True)
+    for (B, H, W, Cout, stride) in [(3, 9, 7, 36, (1, 1)), (1, 31, 33, 64, (1, 1)), (2, 16, 16, 100, (1, 1)),
+                                    (3, 19, 18, 36, (2, 2)), (2, 31, 33, 72, (3, 2)), (1, 9, 40, 64, (1, 2))]:
+        c = wl.small_conv(B, H, W, K, Cout, 1, 1, stride, (0, 0), seed=H + K + Cout, scale=True)
         case = GpuCase(c, levels=(lw, la), entry=entry)
         assert case.kernel_name("onehot_smfmac") == "onehot_smfmac_ws_32xK"
-        acc = oracle.conv2d(c.Wc, c.Ac, lw, la)
-        _assert_same(case.run("onehot_smfmac").cpu().numpy(), acc, f"ws conv {(B, H, W, K, Cout)}")
+        acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride)
+        _assert_same(case.run("onehot_smfmac").cpu().numpy(), acc, f"ws conv {(B, H, W, K, Cout, stride)}")
         y = oracle.scale_epilogue_nhwc(acc, c.scale)
         got = case.run("onehot_smfmac", scale=True).cpu().numpy()
         np.testing.assert_allclose(got, y, rtol=1e-6, atol=0)
@@ -961,7 +963,7 @@ def test_stationary_weight_kernel(K, waves, monkeypatch):
         q = dg.dg_conv2d_lut_requant(case.lut, case.Wp, case.Ap, case.desc, case.scale, float(qs), 0.5, 0, variant="onehot_smfmac")
         torch.cuda.synchronize()
         _assert_same(q.cpu().numpy().reshape(-1, Cout // 4), oracle.pack_codes(codes.reshape(-1, Cout)), f"ws fused layer {(B, H, W, K, Cout)}")
-    # a filter window, a stride or another K is not its case: the tiled sparse-instruction kernel takes over
+    # a filter window, padding or another K is not its case: the tiled sparse-instruction kernel takes over
     c = wl.small_conv(1, 8, 8, 64, 32, 3, 3, (1, 1), (1, 1), seed=1)
     assert GpuCase(c, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac") != "onehot_smfmac_ws_32xK"
     # on codes one per byte it packs them itself (no work buffer needed): convolutions, and GEMMs whose output has the
