@@ -82,12 +82,21 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
     const double *mfma_cycles = can_share ? fitted_cycles : plain_cycles;
     // matrix instructions per 32 x 32 block: one per 32 positions decoding, per 32 / L selecting, per 16 on the sparse one
     const double steps = decode ? p.K / 32.0 : (mode == SPARSE ? p.K / 16.0 : (double)p.K * (1 << lut->bits) / 32.0);
+    // Sharing fills SIMDs that tiles alone would leave idle.  With two or more tiles of a width per SIMD there is nothing
+    // to fill, and what the model then sees in sharing is the rounding of its own queue lengths (6.125 tiles per SIMD
+    // count as 7, 24.5 quarter tiles as 6.25): measured without it on the layers where the model had chosen it,
+    // 56x56x512 -> 1024 at batch 64 379 -> 246 us, 56x56x128 -> 256 3x3 at batch 32 79 -> 58 us, 224x224x64 -> 64 3x3 at
+    // batch 8 55 -> 40 us, 56x56x256 -> 256 3x3 at batch 32 112 -> 94 us.  DG_ONEHOT_SHARE_BELOW: tiles per SIMD from
+    // which a tile width is not shared (default 2).
+    int64_t share_below = 2;
+    if (const char *e = dg_override("DG_ONEHOT_SHARE_BELOW")) share_below = atoi(e) > 0 ? atoi(e) : share_below;
     double best = 0.0;
     bool first = true;
     for (int i = 0; i < 4; ++i)
         for (int skw = 1; skw <= (can_share ? 4 : 1); skw *= 2) {
             const int wn = widths[i];
             if (skw > q.chunks || (wn == 7 && skw == 2)) continue;      // (two 64x224 tiles of sums exceed 64 KB of LDS)
+            if (skw > 1 && tile_count(p, wm, wn) >= share_below * simds) continue;
             if (wn == 7 && mode == SPARSE) continue;                    // (14 blocks of sparse-instruction sums exceed the VGPRs)
             if (wn == 7 && decode && skw == 1) continue;                // (measured slower than 64x128 and 128x128 when decoding)
             const int64_t per_simd = (tile_count(p, wm, wn) * skw + simds - 1) / simds;
