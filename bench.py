@@ -80,6 +80,11 @@ def parse_args():
     ap.add_argument("--table-values", action="store_true",
                     help="also time the workload's kernel (AUTO and the comparison) with other tables of the same shape: "
                          "the matrix pipe's power draw, and with it the clock, follows the operands' values")
+    ap.add_argument("--layers", default=None, metavar="BATCHES",
+                    help="instead of the benchmark line: every quantised convolution of ResNet-18, ResNet-50 and VGG-16 "
+                         "(224 x 224 inputs; the first layer, on 3 input channels, is not one) at these batch sizes, e.g. "
+                         "1,8,32 -- per layer the one-call step from unpacked codes and AUTO's kernel on packed codes "
+                         "against the two one-hot forms and the decode-and-multiply comparison; one JSON line")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="also run one plain device-to-device copy of this many MiB (a known-size dispatch "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled)")
@@ -473,6 +478,61 @@ def table_values(torch, r, use_graph):
     return out
 
 
+def network_layers():
+    """(H, Cin, Cout, filter, stride, count) of the quantised convolutions of three ImageNet networks, H the input's side.
+    ResNet-50 with the stride on the 3x3 convolution of a stage's first block; shortcuts are 1x1 with stride 2."""
+    resnet50 = [(56, 64, 64, 1, 1, 1), (56, 64, 64, 3, 1, 3), (56, 64, 256, 1, 1, 4), (56, 256, 64, 1, 1, 2),
+                (56, 256, 128, 1, 1, 1), (56, 128, 128, 3, 2, 1), (28, 128, 128, 3, 1, 3), (28, 128, 512, 1, 1, 4),
+                (28, 512, 128, 1, 1, 3), (56, 256, 512, 1, 2, 1),
+                (28, 512, 256, 1, 1, 1), (28, 256, 256, 3, 2, 1), (14, 256, 256, 3, 1, 5), (14, 256, 1024, 1, 1, 6),
+                (14, 1024, 256, 1, 1, 5), (28, 512, 1024, 1, 2, 1),
+                (14, 1024, 512, 1, 1, 1), (14, 512, 512, 3, 2, 1), (7, 512, 512, 3, 1, 2), (7, 512, 2048, 1, 1, 3),
+                (7, 2048, 512, 1, 1, 2), (14, 1024, 2048, 1, 2, 1)]
+    resnet18 = [(56, 64, 64, 3, 1, 4), (56, 64, 128, 3, 2, 1), (28, 128, 128, 3, 1, 3), (56, 64, 128, 1, 2, 1),
+                (28, 128, 256, 3, 2, 1), (14, 256, 256, 3, 1, 3), (28, 128, 256, 1, 2, 1),
+                (14, 256, 512, 3, 2, 1), (7, 512, 512, 3, 1, 3), (14, 256, 512, 1, 2, 1)]
+    vgg16 = [(224, 64, 64, 3, 1, 1), (112, 64, 128, 3, 1, 1), (112, 128, 128, 3, 1, 1), (56, 128, 256, 3, 1, 1),
+             (56, 256, 256, 3, 1, 2), (28, 256, 512, 3, 1, 1), (28, 512, 512, 3, 1, 2), (14, 512, 512, 3, 1, 3)]
+    return {"resnet18": resnet18, "resnet50": resnet50, "vgg16": vgg16}
+
+
+def layers(torch, batches, use_graph):
+    """Every layer of network_layers() at every batch size: the one-call step (AUTO, from unpacked codes), and the
+    kernels on packed codes -- AUTO, the dense and the sparse one-hot form each in its own plan, the comparison.  Totals
+    per network and batch weigh each layer by its count."""
+    from paper_2304_09049_amd import workloads as wl
+    rows, totals, seen = [], [], {}
+    for net, shapes in network_layers().items():
+        for B in batches:
+            tot = {"network": net, "batch": B, "layers": 0, "gop": 0.0, "step_us": 0.0, "auto_us": 0.0, "onehot_mfma_us": 0.0,
+                   "onehot_smfmac_us": 0.0, "mfma_i8_us": 0.0}
+            for (H, Cin, Cout, k, s, count) in shapes:
+                key = (B, H, Cin, Cout, k, s)
+                if key not in seen:
+                    if B * H * H * Cin > (1 << 30):
+                        continue                                   # (not at this batch: the codes alone exceed 1 GiB)
+                    w = wl._conv(f"{H}x{H}x{Cin}_{Cout}_{k}x{k}s{s}_b{B}", B, H, H, Cin, Cout, k, k, (s, s), (k // 2, k // 2))
+                    r = Runner(w, "auto")
+                    row = {"layer": w.name, "gop": round(w.ops / 1e9, 3), "step_kernel": r.step_kernel_name(),
+                           "step_us": round(time_steady(torch, r.step, use_graph) * 1e3, 2), "kernel": r.kernel_name("auto")}
+                    for v in ("auto", "onehot_mfma", "onehot_smfmac", "mfma_i8"):
+                        row[v + "_us"] = round(time_steady(torch, lambda: r.kernel(v), use_graph) * 1e3, 2)
+                    seen[key] = row
+                    rows.append(row)
+                    del r
+                row = seen[key]
+                tot["layers"] += count
+                tot["gop"] += count * row["gop"]
+                for f in ("step_us", "auto_us", "onehot_mfma_us", "onehot_smfmac_us", "mfma_i8_us"):
+                    tot[f] += count * row[f]
+            for f in tot:
+                if isinstance(tot[f], float):
+                    tot[f] = round(tot[f], 2)
+            tot["step_effective_tops"] = round(tot["gop"] / tot["step_us"] * 1e3, 1) if tot["step_us"] else None
+            totals.append(tot)
+    return {"layers": rows, "totals": totals}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -492,6 +552,12 @@ def main():
             torch.add(src, 1, out=dst)             # an elementwise kernel: reads and writes exactly that many bytes
         torch.cuda.synchronize()
         del src, dst
+    if args.layers:
+        out = layers(torch, [int(b) for b in args.layers.split(",")], use_graph)
+        out.update({"what": "quantised convolutions of three networks, per layer and in total (us)", "data": "synthetic",
+                    "launch": "hip graph replay" if use_graph else "host launches"})
+        print(json.dumps(out))
+        return
     w = wl.CONFIGS[args.workload or wl.HEADLINE]
     r = Runner(w, args.variant)
 
