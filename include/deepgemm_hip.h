@@ -200,7 +200,7 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *                    staged codes (by default it counts the stores it has issued and lets them drain)
  *   DG_FEWN_WAVES    wavefronts per workgroup of the "fewn" kernel (1..8)
  *   DG_FEWN_ROWS     weight rows per workgroup of the "fewn" kernel (16 or 32)
- *   DG_ONEHOT_WAVES  target number of wavefronts of the split-K kernel (default 2048; 3072 from K = 2304)
+ *   DG_ONEHOT_WAVES  target number of wavefronts of the split-K kernel (default 2048; 3072 for K = 2304 ... 4608)
  *   DG_ONEHOT_SHARE_BELOW  tiles per SIMD from which the planner does not let wavefronts share a tile (default 2)
  *   DG_ONEHOT_CH2_MAX  the dense instruction's split-K kernel walks K in chunks of 64 positions instead of 128 where K
  *                    has at most this many chunks of 128 and twice as many wavefronts per tile are wanted (default 4)

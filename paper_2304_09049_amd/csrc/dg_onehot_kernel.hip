@@ -54,12 +54,13 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
     q.chunks = (p.K / per_byte(lut)) / (8 * q.ch);
     q.wn = 1, q.skw = 1, q.S = 1, q.cpw = q.chunks;
     q.split = false;
-    // the split-K kernel's shape: about 2048 wavefronts in all (3072 for long K), at most 16 per workgroup, whole chunks each
+    // the split-K kernel's shape: about 2048 wavefronts in all (3072 for K = 2304 ... 4608), at most 16 per workgroup, whole chunks each
     const int64_t blocks11 = tile_count(p, 1, 1);
     // (3072 from K = 2304: a wavefront's share of a long K is a chain of load latencies, and 12 wavefronts per block
     // instead of 9 measured 5.6 -> 5.2 us on 14x14x256 -> 256 3x3 at batch 4 and 8.4 -> 7.1 us on 7x7x512 -> 512 3x3 at
-    // batch 8; with K = 2048 and below the larger target was slower, 4.65 -> 5.15 us)
-    int64_t target = p.K >= 2304 ? 3072 : 2048;
+    // batch 8; with K = 2048 and below the larger target was slower, 4.65 -> 5.15 us, and so it was on the 8192 x 1 x 8192
+    // GEMM, whose weights stream from memory: 10.5 -> 11.6 us)
+    int64_t target = p.K >= 2304 && p.K <= 4608 ? 3072 : 2048;
     if (const char *e = dg_override("DG_ONEHOT_WAVES")) target = atoi(e) > 0 ? atoi(e) : target;   // tuning override
     int S = (int)((target + blocks11 - 1) / blocks11);
     S = S < 1 ? 1 : (S > 16 ? 16 : S);
