@@ -102,7 +102,7 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
             if (skw > q.chunks || (wn == 7 && skw == 2)) continue;      // (two 64x224 tiles of sums exceed 64 KB of LDS)
             if (skw > 1 && tile_count(p, wm, wn) >= share_below * simds) continue;
             if (wn == 7 && mode == SPARSE) continue;                    // (14 blocks of sparse-instruction sums exceed the VGPRs)
-            if (wn == 7 && decode && skw == 1) continue;                // (measured slower than 64x128 and 128x128 when decoding)
+            if (wn == 7 && decode) continue;                            // (measured slower than 64x128 when decoding, shared or not)
             const int64_t per_simd = (tile_count(p, wm, wn) * skw + simds - 1) / simds;
             const double lone = !can_share ? 1.0 : (per_simd == 1 ? 0.84 : (per_simd == 2 ? 0.78 : 1.0));   // (rounding up overstates short queues)
             double cost = (double)per_simd * 2 * wn * (steps / skw) * mfma_cycles[i] * lone;
@@ -111,7 +111,11 @@ Plan plan_for(const dg_lut *lut, const DgProblem &p, Mode mode, int tile = 0)
             if (skw > 1) cost += 955.0 + 147.0 * 2 * wn;
             if (first || cost < best * 0.999) best = cost, q.wn = wn, q.skw = skw, first = false;
         }
-    if (decode && p.M > 64) {                              // the comparison's own 128 x 128 tile
+    // the comparison's own 128 x 128 tile, one wavefront per SIMD with 64 KB of sums to store at the end: for long
+    // reductions without a filter window (8192-cube 500 against 528 us for 64 x 128, 4096-cube 69.7 against 70.9).  With a
+    // 3x3 window it measured 1.2 - 2.7 times the 64 x 128 tile's time on six layers, with K = 512 and 1024 1.2 - 2.5
+    // times on five, none of which the model sees.
+    if (decode && p.M > 64 && p.KH * p.KW == 1 && p.K >= 4096) {
         const int64_t per_simd = (tile_count(p, 4, 4) + simds - 1) / simds;
         const double cost = (double)per_simd * steps * decode_step_cycles(4, 4) + 2670.0 + 350.0 * 16;
         if (cost < best * 0.999) best = cost, q.wm = 4, q.wn = 4, q.skw = 1;
