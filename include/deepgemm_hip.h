@@ -207,6 +207,8 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *   DG_ONEHOT_CH2_SMAX and where that gives a tile more wavefronts, up to this many (default 12)
  *   DG_ONEHOT_CODES_TILED "0": the one-call entry points never use the tiled kernel that packs the codes itself,
  *                    "1": wherever it applies (default: where it was measured shorter than two kernels)
+ *   DG_ONEHOT_CODES_SPARSE "0": that kernel on the dense instruction only, "1": on the sparse one wherever the output's
+ *                    channel axis is contiguous (the default)
  *   DG_PERM_PLAN     index of the permute kernel's tile shape
  */
 typedef enum {
@@ -271,8 +273,9 @@ dg_status dg_conv2d_lut(const dg_lut *lut, const void *Wp_dev, const void *Xp_de
  * launch, and Xp_work_dev is not touched.  Those are, for 2-bit codes: the layers the library runs on the one-hot
  * split-K kernel (Cin % 32 == 0, K <= 3072; variant ONEHOT_MFMA, or AUTO while Cout is small enough that packing
  * once per 32 output channels costs less than the launch); layers of a few microseconds on the one-hot tiled
- * kernel's 64 x 32 and 64 x 64 tiles (Cin % 64 == 0; AUTO or ONEHOT_MFMA, up to about 10^9 table operations, more
- * where the packing kernel would pack pixels a strided 1x1 layer never reads); the layers of the stationary-weight
+ * kernel's 64 x 32 and 64 x 64 tiles (Cin % 64 == 0; AUTO, ONEHOT_MFMA or ONEHOT_SMFMAC -- on the sparse instruction
+ * where the output's channel axis is contiguous unless ONEHOT_MFMA is named -- up to about 2 * 10^9 table operations,
+ * more where there is much to pack or Cin % 128 != 0); the layers of the stationary-weight
  * kernel (K = 64, 128, 256 without a filter window; AUTO or ONEHOT_SMFMAC); and the few-columns kernel (AUTO or
  * SMALLN).  Every other layer is packed into
  * Xp_work_dev (device, work_bytes >= dg_packed_bytes_bits(B*H*W, Cin, bits), else DG_ERR_BUFFER; DG_ERR_NULL if it

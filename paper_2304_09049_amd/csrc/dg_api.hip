@@ -502,7 +502,7 @@ namespace {
 // The one-call entry points fuse the packing into the kernel where the library's own choice for the problem (or the
 // variant the caller names) is the one-hot split-K kernel or the few-columns kernel, i.e. on problems so small that a
 // second launch costs a good part of the whole.
-enum class Fuse { None, OneHot, SmallN, SparseWs };
+enum class Fuse { None, OneHot, OneHotSparse, SmallN, SparseWs };
 
 Fuse fuses_packing(const dg_lut *lut, const DgProblem &p_codes, dg_kernel variant)
 {
@@ -512,11 +512,15 @@ Fuse fuses_packing(const dg_lut *lut, const DgProblem &p_codes, dg_kernel varian
         (variant == DG_KERNEL_ONEHOT_MFMA ||
          (dg_onehot_codes_pays(p_codes) && pick_kernel(lut, p_codes, DG_KERNEL_AUTO) == Pick::OneHot)))
         return Fuse::OneHot;
-    // layers of a few microseconds on the tiled kernels: the dense instruction's narrow tiles pack per 64-row tile
-    if ((variant == DG_KERNEL_AUTO || variant == DG_KERNEL_ONEHOT_MFMA) && dg_onehot_codes_tiled_supports(lut, p_codes) &&
-        dg_onehot_codes_tiled_pays(lut, p_codes)) {
-        const Pick pick = variant == DG_KERNEL_AUTO ? pick_kernel(lut, p_codes, DG_KERNEL_AUTO) : Pick::OneHot;
-        if (pick == Pick::OneHot || pick == Pick::Sparse) return Fuse::OneHot;
+    // layers of a few microseconds on the tiled kernels: the narrow tiles pack per 64-row tile -- on the sparse instruction
+    // where the output's channel axis is the contiguous one and the caller has not named the dense one's variant
+    if ((variant == DG_KERNEL_AUTO || variant == DG_KERNEL_ONEHOT_MFMA || variant == DG_KERNEL_ONEHOT_SMFMAC) &&
+        dg_onehot_codes_tiled_supports(lut, p_codes)) {
+        const bool sparse = variant != DG_KERNEL_ONEHOT_MFMA && dg_onehot_codes_tiled_sparse(lut, p_codes);
+        if ((sparse || variant != DG_KERNEL_ONEHOT_SMFMAC) && dg_onehot_codes_tiled_pays(lut, p_codes, sparse)) {
+            const Pick pick = pick_kernel(lut, p_codes, variant);
+            if (pick == Pick::OneHot || pick == Pick::Sparse) return sparse ? Fuse::OneHotSparse : Fuse::OneHot;
+        }
     }
     // (the few-columns kernel packs once per row block and pass of four columns, about 7 % more work for it: less than
     // a launch while the columns are few, which is where AUTO uses that kernel anyway)
@@ -559,6 +563,7 @@ dg_status run_codes(const char *name, const dg_lut *lut, DgProblem &p, const uin
     p.Xp = codes;
     switch (fuses_packing(lut, p, variant)) {
     case Fuse::OneHot: return dg_launch_onehot_codes(lut, p, (hipStream_t)hip_stream);
+    case Fuse::OneHotSparse: return dg_launch_onehot_codes(lut, p, (hipStream_t)hip_stream, true);
     case Fuse::SmallN: return dg_launch_smalln_codes(lut, p, (hipStream_t)hip_stream);
     case Fuse::SparseWs: return dg_launch_sparse_ws_codes(lut, p, (hipStream_t)hip_stream);
     case Fuse::None: break;
@@ -585,6 +590,7 @@ const char *codes_name(const dg_lut *lut, const DgProblem &p, dg_kernel variant)
 {
     switch (fuses_packing(lut, p, variant)) {
     case Fuse::OneHot: return dg_onehot_codes_config_name(lut, p);
+    case Fuse::OneHotSparse: return dg_onehot_codes_config_name(lut, p, true);
     case Fuse::SmallN: return "codes_smalln";
     case Fuse::SparseWs: return "codes_onehot_smfmac_ws_32xK";
     case Fuse::None: break;

@@ -105,11 +105,13 @@ const char *dg_onehot_config_name(const dg_lut *lut, const DgProblem &p);
 // the one-hot split-K kernel reading activations one code per byte (p.Xp = those bytes) and packing them as it loads
 bool dg_onehot_codes_supports(const dg_lut *lut, const DgProblem &p);
 bool dg_onehot_codes_pays(const DgProblem &p);      // AUTO: the repeated packing costs less than the saved launch
-dg_status dg_launch_onehot_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream);
-const char *dg_onehot_codes_config_name(const dg_lut *lut, const DgProblem &p);
-// the one-hot tiled kernel (64 x 32 and 64 x 64 tiles of the dense instruction) doing the same on layers of a few microseconds
+// (`sparse_tiles`: the tiled form on the sparse instruction, where dg_onehot_codes_tiled_sparse says it applies)
+dg_status dg_launch_onehot_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream, bool sparse_tiles = false);
+const char *dg_onehot_codes_config_name(const dg_lut *lut, const DgProblem &p, bool sparse_tiles = false);
+// the one-hot tiled kernel (64 x 32 and 64 x 64 tiles) doing the same on layers of a few microseconds
 bool dg_onehot_codes_tiled_supports(const dg_lut *lut, const DgProblem &p);
-bool dg_onehot_codes_tiled_pays(const dg_lut *lut, const DgProblem &p);    // AUTO: shorter than packing kernel + AUTO's kernel
+bool dg_onehot_codes_tiled_sparse(const dg_lut *lut, const DgProblem &p);  // on the sparse instruction (channel axis contiguous)
+bool dg_onehot_codes_tiled_pays(const dg_lut *lut, const DgProblem &p, bool sparse_tiles);   // AUTO: shorter than packing kernel + AUTO's kernel
 bool dg_sparse_supports(const dg_lut *lut, const DgProblem &p);
 bool dg_sparse_preferred(const dg_lut *lut, const DgProblem &p);     // AUTO's choice between the two one-hot kernels
 dg_status dg_launch_sparse(const dg_lut *lut, const DgProblem &p, hipStream_t stream);

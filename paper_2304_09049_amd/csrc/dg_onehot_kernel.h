@@ -350,7 +350,7 @@ __global__ void __launch_bounds__(256, (WM * WN > 8 ? 1 : 2))
 onehot_mfma_kernel(Args a)
 {
     typedef Fmt<BITS> F;
-    static_assert(!RAW || (BITS == 2 && !TWO), "unpacked activations: 2-bit codes on the dense instruction, one plane");
+    static_assert(!RAW || ((BITS == 2 || BITS == 20) && !TWO), "unpacked activations: 2-bit codes, one plane");
     static_assert(!TWO || (WM == 2 && BITS == 2), "two planes stand in for the two weight row blocks of 2-bit tiles");
     static_assert(BITS == 0 || BITS == 2 || BITS == 3 || BITS == 4 || BITS == 20,
                   "code widths 2, 3, 4; 0 = the decode comparison; 20 = 2-bit codes on the sparse instruction");
@@ -899,8 +899,9 @@ void unit_sparse_ws(const DgProblem &, const uint32_t (&)[4], int, bool raw, hip
 void unit_sparse_staged(const DgProblem &, const Pools &, int32_t bias, const Plan &, int64_t, hipStream_t);      // dg_sparse_staged_kernel.h
 // the split-K kernel on activations still one code per byte (one- and two-plane tables, either output layout)
 void unit_split_codes(const DgProblem &, const Pools &, const Plan &, bool two, bool tr, int64_t, hipStream_t);
-// the tiled kernel on unpacked codes: 64 x 32 and 64 x 64 tiles (q.wn = 1, 2), 2-word chunks, any sharing of K
-void unit_main_codes(const DgProblem &, const Pools &, const Plan &, bool tr, int64_t wave_tiles, hipStream_t);
+// the tiled kernel on unpacked codes: 64 x 32 and 64 x 64 tiles (q.wn = 1, 2), 2-word chunks, any sharing of K;
+// `sparse`: on the sparse instruction (its pools; outputs whose channel axis has stride 1 only)
+void unit_main_codes(const DgProblem &, const Pools &, const Plan &, bool tr, bool sparse, int64_t wave_tiles, hipStream_t);
 #undef DGOH_UNIT
 #undef DGOH_UNIT_SPLIT
 

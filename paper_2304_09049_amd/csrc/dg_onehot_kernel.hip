@@ -669,7 +669,7 @@ dg_status dg_launch_decode(const dg_lut *lut, const DgProblem &p, hipStream_t st
 
 namespace {
 
-dg_status launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream, bool codes);
+dg_status launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream, bool codes, bool sparse_tiles = false);
 
 }   // namespace
 
@@ -714,37 +714,54 @@ static bool codes_tiled_plan(const dg_lut *lut, const DgProblem &p, Plan *out)
     return true;
 }
 
+// On the sparse instruction where the output's channel axis has stride 1 (the activations are then the instruction's row
+// operand as they stand) and the caller has not named the dense instruction's variant.  DG_ONEHOT_CODES_SPARSE: 0 / 1
+// (A/B measurement).
+bool dg_onehot_codes_tiled_sparse(const dg_lut *, const DgProblem &p)
+{
+    if (p.stride_cm != 1) return false;
+    if (const char *e = dg_override("DG_ONEHOT_CODES_SPARSE")) return atoi(e) != 0;
+    return true;                                           // (3 - 17 % shorter than the dense instruction's on 30 layer shapes)
+}
+
 bool dg_onehot_codes_tiled_supports(const dg_lut *lut, const DgProblem &p)
 {
     Plan q;
     return codes_tiled_plan(lut, p, &q);
 }
 
-// Measured on 44 layer shapes (ResNet-50 and ResNet-18 layers at batch 4 to 32): packing in this kernel costs about
-// 1.6 us per 10^9 table operations (2MNK) over the best kernel on packed codes -- the narrow tiles of the dense
-// instruction, loads of 16 bytes per 16 codes, the packing repeated per 64-row tile -- and the packing kernel 1.8 us
-// plus 0.17 us per MB of codes it packs (all the input's, except that of a 1x1 layer with a stride only the pixels
-// read).  So: layers up to about 10^9 operations (14x14x1024 -> 256 at batch 8: 5.7 against 6.7 us; 56x56x64 -> 64 3x3 at
-// batch 4: 6.1 against 7.4), and a little further up where there is much to pack.
+// Measured on 44 layer shapes (ResNet-50 and ResNet-18 layers at batch 4 to 32): over the best kernel on packed codes,
+// packing in this kernel costs about 0.9 us per 10^9 table operations (2MNK) on the sparse instruction where the best
+// kernel is the staged one (Cin % 128 == 0), 0.35 us where it is this kernel's own direct-load form, and 1.6 us on
+// the dense instruction (outputs whose channel axis is not the contiguous one) -- narrow tiles, loads of 16 bytes per
+// 16 codes, the packing repeated per 64-row tile; the packing kernel costs 1.8 us plus 0.17 us per MB of codes it
+// packs (all the input's, except that of a 1x1 layer with a stride only the pixels read).  So: layers up to about
+// 2 * 10^9 operations (14x14x1024 -> 256 at batch 8: 5.5 against 6.7 us; 56x56x64 -> 64 3x3 at batch 8: 8.2 against 9.6),
+// and further up where there is much to pack or the channels are not whole 128s (56x56x64 -> 64 3x3 at batch 32: 14.8
+// against 15.2).  Total regret of this rule against the better of the two on 40 shapes: 1.5 us, 0.6 at most.
 // DG_ONEHOT_CODES_TILED: 0 never, 1 always (A/B measurement).
-bool dg_onehot_codes_tiled_pays(const dg_lut *, const DgProblem &p)
+bool dg_onehot_codes_tiled_pays(const dg_lut *, const DgProblem &p, bool sparse_tiles)
 {
     if (const char *e = dg_override("DG_ONEHOT_CODES_TILED")) return atoi(e) != 0;
     const double ops = 2.0 * (double)p.M * (double)p.N * (double)p.K;
     const bool strided_1x1 = p.KH == 1 && p.KW == 1 && p.ph == 0 && p.pw == 0;     // (packed pixel by pixel: only those read)
     const double images = (double)p.N / ((double)p.OH * p.OW);
     const double code_bytes = strided_1x1 ? (double)p.N * p.Cin : images * p.H * p.W * p.Cin;
-    return 1.6e-9 * ops + 0.2 < 1.8 + 0.17e-6 * code_bytes;
+    const double per_op = !sparse_tiles ? 1.6e-9 : (p.Cin % 128 == 0 ? 0.9e-9 : 0.35e-9);
+    return per_op * ops + 0.2 < 1.8 + 0.17e-6 * code_bytes;
 }
 
-const char *dg_onehot_codes_config_name(const dg_lut *lut, const DgProblem &p)
+const char *dg_onehot_codes_config_name(const dg_lut *lut, const DgProblem &p, bool sparse_tiles)
 {
     Plan t;
     if (!plan_for(lut, p, TABLE).split && codes_tiled_plan(lut, p, &t)) {
-        static const char *const tiled[3][2] = {{"codes_onehot_mfma_64x32", "codes_onehot_mfma_64x64"},
-                                                {"codes_onehot_mfma_64x32_k2", "codes_onehot_mfma_64x64_k2"},
-                                                {"codes_onehot_mfma_64x32_k4", "codes_onehot_mfma_64x64_k4"}};
-        return tiled[t.skw == 4 ? 2 : (t.skw == 2 ? 1 : 0)][t.wn == 2 ? 1 : 0];
+        static const char *const tiled[2][3][2] = {{{"codes_onehot_mfma_64x32", "codes_onehot_mfma_64x64"},
+                                                    {"codes_onehot_mfma_64x32_k2", "codes_onehot_mfma_64x64_k2"},
+                                                    {"codes_onehot_mfma_64x32_k4", "codes_onehot_mfma_64x64_k4"}},
+                                                   {{"codes_onehot_smfmac_64x32", "codes_onehot_smfmac_64x64"},
+                                                    {"codes_onehot_smfmac_64x32_k2", "codes_onehot_smfmac_64x64_k2"},
+                                                    {"codes_onehot_smfmac_64x32_k4", "codes_onehot_smfmac_64x64_k4"}}};
+        return tiled[sparse_tiles ? 1 : 0][t.skw == 4 ? 2 : (t.skw == 2 ? 1 : 0)][t.wn == 2 ? 1 : 0];
     }
     static const char *const names[2][17] = {
         {"", "codes_onehot_mfma_splitk_s1", "codes_onehot_mfma_splitk_s2", "codes_onehot_mfma_splitk_s3",
@@ -763,14 +780,14 @@ const char *dg_onehot_codes_config_name(const dg_lut *lut, const DgProblem &p)
     return names[q.two][q.S];
 }
 
-dg_status dg_launch_onehot_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream)
+dg_status dg_launch_onehot_codes(const dg_lut *lut, const DgProblem &p, hipStream_t stream, bool sparse_tiles)
 {
-    return launch_onehot(lut, p, stream, true);
+    return launch_onehot(lut, p, stream, true, sparse_tiles);
 }
 
 namespace {
 
-dg_status launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream, bool codes)
+dg_status launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t stream, bool codes, bool sparse_tiles)
 {
     // column v of the table, 4 weight codes per word: the permute pools.  Entries beyond int8 go in two planes,
     // T = 256 * hi + lo with lo in [-128, 127] (so hi is within [-128, 128) for every int16 T).
@@ -807,7 +824,16 @@ dg_status launch_onehot(const dg_lut *lut, const DgProblem &p, hipStream_t strea
             return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel on unpacked codes: this layer's plan has no such form");
         const int64_t tiles = tile_count(p, 2, t.wn);
         if (tiles > INT32_MAX) return dg_fail(DG_ERR_UNSUPPORTED, "one-hot kernel: too many tiles for one grid");
-        unit_main_codes(p, pools, t, tr != 0, tiles, stream);
+        if (sparse_tiles) {
+            // (the sparse instruction's pools: word w = the table row of weight code w, bytes over the activation code)
+            dgoh::Pools sp;
+            for (int i = 0; i < 64; ++i) sp.w[i] = 0;
+            for (int w = 0; w < 4; ++w)
+                for (int v = 0; v < 4; ++v) sp.w[w] |= (uint32_t)(uint8_t)(int8_t)lut->entry[(w << 2) | v] << (8 * v);
+            unit_main_codes(p, sp, t, true, true, tiles, stream);
+            return dg_check_launch("onehot_mfma_kernel<20> (unpacked codes)");
+        }
+        unit_main_codes(p, pools, t, tr != 0, false, tiles, stream);
         return dg_check_launch("onehot_mfma_kernel (unpacked codes)");
     }
     if (codes) {

@@ -239,9 +239,10 @@ def test_kernel_names_need_no_gpu():
     # about 1e9 table operations, more where a strided 1x1 layer leaves most of the input unread), larger ones do not
     mid = dg.conv_desc(8, 14, 14, 1024, 256, 1, 1, (1, 1), (0, 0))
     assert dg.dg_conv_kernel_name(lut, mid) == "onehot_smfmac_staged_32x64_k4"
-    assert dg.dg_conv_codes_kernel_name(lut, mid) == "codes_onehot_mfma_64x32_k4"
+    assert dg.dg_conv_codes_kernel_name(lut, mid) == "codes_onehot_smfmac_64x32_k4"
+    assert dg.dg_conv_codes_kernel_name(lut, mid, "onehot_mfma") == "codes_onehot_mfma_64x32_k4"
     strided = dg.conv_desc(32, 56, 56, 256, 128, 1, 1, (2, 2), (0, 0))
-    assert dg.dg_conv_codes_kernel_name(lut, strided) == "codes_onehot_mfma_64x32"
+    assert dg.dg_conv_codes_kernel_name(lut, strided) == "codes_onehot_smfmac_64x32"
     big = dg.conv_desc(32, 14, 14, 1024, 256, 1, 1, (1, 1), (0, 0))
     assert dg.dg_conv_codes_kernel_name(lut, big) == dg.dg_conv_kernel_name(lut, big) == "onehot_smfmac_staged_32x64"
     # taps of an odd number of 64-position chunks: staged with a window and 192 channels or more, direct loads with 64

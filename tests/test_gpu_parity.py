@@ -284,6 +284,7 @@ def test_convolution_from_unpacked_codes(monkeypatch):
     # layer for the tiled kernels whose channels are not whole 64-code chunks -- packed into the work buffer, then run
     # as dg_conv2d_lut runs them
     monkeypatch.delenv("DG_ONEHOT_PLAN")
+    monkeypatch.setenv("DG_ONEHOT_CODES_TILED", "0")      # (the tiled kernel that packs would take the last one)
     lw, la, entry = LEVELS["nonuniform_i8"]
     for (shape, variant) in (((2, 9, 9, 16, 20, 3, 3, (1, 1), (1, 1)), "auto"), ((1, 14, 14, 64, 64, 3, 3, (1, 1), (1, 1)), "lds"),
                              ((8, 56, 56, 96, 64, 3, 3, (1, 1), (1, 1)), "auto"),
@@ -317,28 +318,35 @@ def test_convolution_from_unpacked_codes(monkeypatch):
         assert e.value.status == 4
 
 
-@pytest.mark.parametrize("plan,name", [("1", "codes_onehot_mfma_64x32"), ("2", "codes_onehot_mfma_64x64"),
-                                       ("1k2", "codes_onehot_mfma_64x32_k2"), ("2k2", "codes_onehot_mfma_64x64_k2"),
-                                       ("1k4", "codes_onehot_mfma_64x32_k4"), ("2k4", "codes_onehot_mfma_64x64_k4")])
-def test_tiled_kernel_on_unpacked_codes(plan, name, monkeypatch):
-    """The one-call entry points on the dense instruction's tiled kernel packing the codes itself (64 x 32 and 64 x 64
-    tiles, K unshared or shared by 2 or 4 wavefronts): convolutions with windows, strides and padding, 64 to 320 channels,
-    ragged M and N, garbage above bit 1 of the code bytes, scaled output; GEMMs in both output layouts; no work buffer."""
+@pytest.mark.parametrize("plan,tile", [("1", "64x32"), ("2", "64x64"), ("1k2", "64x32_k2"), ("2k2", "64x64_k2"),
+                                       ("1k4", "64x32_k4"), ("2k4", "64x64_k4")])
+def test_tiled_kernel_on_unpacked_codes(plan, tile, monkeypatch):
+    """The one-call entry points on the tiled kernel packing the codes itself (64 x 32 and 64 x 64 tiles, K unshared or
+    shared by 2 or 4 wavefronts) -- on the sparse instruction where the output's channel axis is the contiguous one
+    (convolutions, column-major GEMMs) unless the dense one's variant is named, else on the dense instruction:
+    convolutions with windows, strides and padding, 64 to 320 channels, ragged M and N, garbage above bit 1 of the code
+    bytes, scaled output; GEMMs in both output layouts; no work buffer."""
     monkeypatch.setenv("DG_ONEHOT_PLAN", plan)
+    name, sparse_name = "codes_onehot_mfma_" + tile, "codes_onehot_smfmac_" + tile
     lw, la, entry = LEVELS["nonuniform_i8"]
     convs = [(2, 9, 7, 64, 36, 3, 3, (1, 1), (1, 1)), (1, 13, 11, 192, 70, 3, 3, (2, 2), (1, 1)), (3, 6, 5, 320, 64, 1, 1, (1, 1), (0, 0)),
              (1, 20, 17, 128, 130, 3, 2, (1, 2), (1, 0)), (2, 15, 15, 64, 100, 5, 5, (1, 1), (2, 2)), (1, 29, 29, 256, 70, 3, 3, (1, 1), (1, 1))]
     for (B, H, W, Cin, Cout, KH, KW, stride, pad) in convs:
         c = wl.small_conv(B, H, W, Cin, Cout, KH, KW, stride, pad, seed=H + Cin + Cout, scale=True)
         case = GpuCase(c, levels=(lw, la), entry=entry)
-        for variant in ("auto", "onehot_mfma"):
-            assert dg.dg_conv_codes_kernel_name(case.lut, case.desc, variant) == name
+        assert dg.dg_conv_codes_kernel_name(case.lut, case.desc, "auto") == sparse_name
+        assert dg.dg_conv_codes_kernel_name(case.lut, case.desc, "onehot_smfmac") == sparse_name
+        assert dg.dg_conv_codes_kernel_name(case.lut, case.desc, "onehot_mfma") == name
         acc = oracle.conv2d(c.Wc, c.Ac, lw, la, stride=stride, pad=pad)
         dirty = c.Ac | (np.random.default_rng(H + Cout).integers(0, 64, size=c.Ac.shape, dtype=np.uint8) << 2)
         Xc = torch.from_numpy(dirty).cuda()
-        got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, variant="onehot_mfma")
+        for variant in ("onehot_mfma", "onehot_smfmac", "auto"):
+            got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, variant=variant)
+            torch.cuda.synchronize()
+            _assert_same(got.cpu().numpy(), acc, f"tiled conv on codes {(B, H, W, Cin, Cout, KH, KW, stride, pad)} {variant}")
+        got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, scale=case.scale, variant="onehot_mfma")
         torch.cuda.synchronize()
-        _assert_same(got.cpu().numpy(), acc, f"tiled conv on codes {(B, H, W, Cin, Cout, KH, KW, stride, pad)}")
+        assert np.array_equal(got.cpu().numpy(), oracle.scale_epilogue_nhwc(acc, c.scale))
         got = dg.dg_conv2d_lut_codes(case.lut, case.Wp, Xc, case.desc, scale=case.scale)
         torch.cuda.synchronize()
         assert np.array_equal(got.cpu().numpy(), oracle.scale_epilogue_nhwc(acc, c.scale))

@@ -26,7 +26,7 @@ def _case(B, H, W, Cin, Cout, seed, scale):
 def test_static_staging_matches_work_buffer_two_calls():
     # the first layer is one AUTO runs as two kernels (packing kernel into the staging buffer, then the convolution);
     # the second, smaller one is forced onto that path by naming a variant that never fuses the packing
-    runs = [(_case(8, 28, 28, 64, 256, 11, False), "auto"), (_case(2, 14, 14, 64, 64, 12, True), "onehot_smfmac"),
+    runs = [(_case(8, 28, 28, 96, 256, 11, False), "auto"), (_case(2, 14, 14, 96, 64, 12, True), "onehot_smfmac"),
             (_case(1, 9, 7, 32, 40, 13, False), "perm")]
     assert not dg.dg_conv_codes_kernel_name(runs[0][0][0], runs[0][0][3], "auto").startswith("codes_")
     for (lut, Wp, Xc, desc, sc, w), variant in runs:
