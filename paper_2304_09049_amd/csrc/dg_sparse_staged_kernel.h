@@ -289,18 +289,18 @@ smfmac_staged_kernel(Args a)
 #pragma unroll
         for (int u = 0; u < WM; ++u) sparse_dense_rows_shared(s_rows, wa.ca[u].x, wa.ca1[u].x, pick, dn0[u][0], dn0[u][1]);
         if constexpr (HALF) {
-            v4i ones_b[WN], ones_b_odd[SHIFT_ODD ? 1 : WN];     // the kept bytes of a run's second chunk
             for (int g = 0; g < runs; ++g) {
                 kept_bytes((int)fdiv((uint32_t)(2 * g), a.div_cpt), true, ones, ones_odd);
-                kept_bytes((int)fdiv((uint32_t)min(2 * g + 1, chunks - 1), a.div_cpt), 2 * g + 1 < chunks, ones_b, ones_b_odd);
                 step(dn0, wa, 0, dn1, wa, 1, ones, ones_odd);
                 read_words(wb, g & 1, 1);
                 step(dn1, wa, 1, dn0, wb, 0, ones, ones_odd);
-                step(dn0, wb, 0, dn1, wb, 1, ones_b, ones_b_odd);
+                // (the second chunk's kept bytes take the first's registers)
+                kept_bytes((int)fdiv((uint32_t)min(2 * g + 1, chunks - 1), a.div_cpt), 2 * g + 1 < chunks, ones, ones_odd);
+                step(dn0, wb, 0, dn1, wb, 1, ones, ones_odd);
                 dg_wait_for_loads();
                 fetch();
                 read_words(wa, (g + 1) & 1, 0);
-                step(dn1, wb, 1, dn0, wa, 0, ones_b, ones_b_odd);
+                step(dn1, wb, 1, dn0, wa, 0, ones, ones_odd);
             }
         }
         int g = HALF ? g1 : g0, rt = rt0, n = 0;            // the run, its place in its tap, runs done
