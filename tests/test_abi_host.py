@@ -269,3 +269,20 @@ def test_dequantize_argument_errors():
     assert L.dg_dequantize(fake, 4, 4, None, fake, None) == 1
     assert L.dg_dequantize(fake, 0, 4, fake, fake, None) == 2
     assert L.dg_dequantize(fake, 4, -1, fake, fake, None) == 2
+
+
+def test_network_layer_tables_add_up():
+    """bench.py --layers: the layer tables against the networks' published sizes.  Multiply-accumulates of all
+    convolutions on a 224 x 224 input, less the first layer's (7x7x3 -> 64 at stride 2 on 112 x 112 outputs for the
+    ResNets, 3x3x3 -> 64 on 224 x 224 for VGG-16), which is not quantised: ResNet-18 1.81 G less 0.118 G and the
+    classifier, ResNet-50 4.09 G less 0.118 G, VGG-16 15.35 G less 0.087 G."""
+    import bench
+    nets = bench.network_layers()
+    macs, count = {}, {}
+    for net, shapes in nets.items():
+        macs[net] = sum(n * ((H + 2 * (k // 2) - k) // s + 1) ** 2 * Cin * Cout * k * k for (H, Cin, Cout, k, s, n) in shapes)
+        count[net] = sum(n for (*_, n) in shapes)
+    assert count == {"resnet18": 19, "resnet50": 52, "vgg16": 12}
+    assert abs(macs["resnet18"] / 1e9 - 1.69) < 0.01
+    assert abs(macs["resnet50"] / 1e9 - 3.97) < 0.01
+    assert abs(macs["vgg16"] / 1e9 - 15.26) < 0.01
