@@ -183,7 +183,7 @@ dg_status dg_dequantize(const int32_t *acc_dev, int64_t rows, int64_t C, const f
  *   DG_ONEHOT_PLAN   forces the one-hot kernels' shape: "split" (split-K kernel), "<wn>" (tile 32*wn columns wide,
  *                    wn = 1, 2, 4, 7) or "<wn>k<s>" (s = 2, 4 wavefronts sharing a tile); "44" is the comparison
  *                    kernel's 128 x 128 tile; "ws" the sparse-instruction kernel with stationary weight operands
- *                    (K = 64, 128, 256 without a filter window) whatever the size.  While it is set AUTO does not
+ *                    (K = 64, 128, 256, and 512 on packed codes, without a filter window) whatever the size.  While it is set AUTO does not
  *                    move to the sparse-instruction forms on its own.
  *                    "fewn" the few-columns kernel on the sparse instruction (K % 256 == 0, no filter window).
  *                    "12", "14" (optionally followed by "k2" or "k4"), "16", "17", "24": the sparse-instruction kernel

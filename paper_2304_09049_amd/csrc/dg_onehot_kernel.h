@@ -132,11 +132,14 @@ __device__ __forceinline__ Words<CH> load_words_any(const uint8_t *ptr)
     if constexpr (CH <= 4) {
         return load_words<CH>(ptr);
     } else {
-        static_assert(CH == 8, "1, 2, 4 or 8 words");
-        const Words<4> lo = load_words<4>(ptr), hi = load_words<4>(ptr + 16);
+        static_assert(CH == 8 || CH == 16, "1, 2, 4, 8 or 16 words");
         Words<CH> w;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) w.v[i] = lo.v[i], w.v[4 + i] = hi.v[i];
+        for (int q = 0; q < CH / 4; ++q) {
+            const Words<4> part = load_words<4>(ptr + 16 * q);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) w.v[4 * q + i] = part.v[i];
+        }
         return w;
     }
 }

@@ -415,7 +415,8 @@ namespace {
 bool sparse_ws_takes(const dg_lut *lut, const DgProblem &p, bool packed = true)
 {
     if (lut->dtype == DG_LUT_F32 || lut->bits != 2 || !fits_int8(lut)) return false;
-    if (p.K != 64 && p.K != 128 && p.K != 256) return false;          // the whole dense operand of 32 rows stays in registers
+    // the whole dense operand of 32 rows stays in registers (K = 512: all 512 of a lone wavefront's, packed activations only)
+    if (p.K != 64 && p.K != 128 && p.K != 256 && !(p.K == 512 && packed)) return false;
     // every "pixel" is one contiguous row of K codes: a GEMM, or a 1x1 convolution without padding
     if (p.KH != 1 || p.KW != 1 || p.ph != 0 || p.pw != 0) return false;
     if ((p.sh != 1 || p.sw != 1) && (!packed || sparse_transposes(p))) return false;
@@ -463,6 +464,10 @@ bool dg_sparse_ws_preferred(const dg_lut *lut, const DgProblem &p)
         if (const char *e = dg_override("DG_WS_STRIDED")) return atoi(e) != 0;
         return t.K == 256 && blocks >= 12 * (int64_t)dg_simd_count();
     }
+    // K = 512: the operands are all of a lone wavefront's registers and take 1.5 us to build, which pays from about 12
+    // blocks per SIMD (28x28x512 -> 512 at batch 32 17.7 against 19.7 us for the staged tiles, at batch 64 29.0 against
+    // 34.1; at 6272 blocks and below 10 - 25 % slower)
+    if (t.K == 512) return blocks >= 12 * (int64_t)dg_simd_count();
     return blocks >= (int64_t)dg_simd_count() / 2;
 }
 

@@ -34,6 +34,7 @@ struct WsArgs {
 };
 
 // T = K / 32: matrix-instruction pairs per 32 x 32 block; a lane half reads T words of a pixel (or weight row).
+// (T = 16, K = 512, on packed activations: 256 registers of dense operands -- a lone wavefront per SIMD has 512.)
 // G: pixel blocks per group (their words are in registers together).
 // What was measured on the 56x56x256 -> 64 layer at batch 32 (25.7 MB of output, which alone takes 5.2 us to write in
 // HIP-graph replays, whatever the store pattern): the layer's time is the time to the first stores and the drain, so
@@ -65,7 +66,7 @@ template <int T, int G, bool RAW, bool STRIDED = false>
 __global__ void __launch_bounds__(256, (!RAW && T * G > 32 ? 1 : 2))
 smfmac_ws_kernel(WsArgs a)
 {
-    static_assert(T == 2 || T == 4 || T == 8, "K = 64, 128 or 256");
+    static_assert(T == 2 || T == 4 || T == 8 || (T == 16 && !RAW), "K = 64, 128 or 256; 512 on packed activations");
     static_assert(!(RAW && STRIDED), "the form that packs reads contiguous pixels");
     __shared__ uint2 s_rows[16];                            // the table of row pairs, one for the workgroup
     extern __shared__ uint4 s_codes[];                      // RAW: [wavefront][2][32 pixels x 2 T segments]
@@ -292,7 +293,12 @@ inline void launch_sparse_ws(const DgProblem &p, const uint32_t (&rows)[4], int 
             hipLaunchKernelGGL((smfmac_ws_kernel<T, G, false>), grid, dim3(256), 0, stream, a);                       \
         }                                                                                                             \
     } while (0)
-    if (t == 8 && wide) DG_WS(8, 8);
+    if (t == 16) {
+        if (strided)
+            hipLaunchKernelGGL((smfmac_ws_kernel<16, 4, false, true>), grid, dim3(256), 0, stream, a);
+        else
+            hipLaunchKernelGGL((smfmac_ws_kernel<16, 4, false>), grid, dim3(256), 0, stream, a);
+    } else if (t == 8 && wide) DG_WS(8, 8);
     else if (t == 8) DG_WS(8, 4);
     else if (t == 4 && wide) DG_WS(4, 8);
     else if (t == 4) DG_WS(4, 4);

@@ -932,9 +932,10 @@ def test_four_bit_auto_takes_the_sparse_kernel_on_large_layers():
 
 
 @pytest.mark.parametrize("waves", [0, 3, 7, 100000, -3])
-@pytest.mark.parametrize("K", [64, 128, 256])
+@pytest.mark.parametrize("K", [64, 128, 256, 512])
 def test_stationary_weight_kernel(K, waves, monkeypatch):
-    """The sparse-instruction kernel with stationary weight operands (K = 64, 128, 256, no filter window), forced on
+    """The sparse-instruction kernel with stationary weight operands (K = 64, 128, 256, and 512 on packed activations; no
+    filter window), forced on
     shapes with ragged M and N: runs of one, of an even and of an odd number of pixel blocks per wavefront (`waves`: 0 =
     the default count, 3 and 7 = long runs, 100000 = one block per wavefront); GEMM with column-major output (run as it
     is) and row-major output (run transposed), 1x1 convolution -- also with strides, equal and unequal, on odd image
@@ -974,6 +975,11 @@ def test_stationary_weight_kernel(K, waves, monkeypatch):
     # a filter window, padding or another K is not its case: the tiled sparse-instruction kernel takes over
     c = wl.small_conv(1, 8, 8, 64, 32, 3, 3, (1, 1), (1, 1), seed=1)
     assert GpuCase(c, levels=(lw, la), entry=entry).kernel_name("onehot_smfmac") != "onehot_smfmac_ws_32xK"
+    if K == 512:        # (on codes one per byte: the packing kernel first)
+        c = wl.small_conv(1, 31, 33, K, 64, 1, 1, (1, 1), (0, 0), seed=3)
+        case = GpuCase(c, levels=(lw, la), entry=entry)
+        assert not dg.dg_conv_codes_kernel_name(case.lut, case.desc, "onehot_smfmac").startswith("codes_onehot_smfmac_ws")
+        return
     # on codes one per byte it packs them itself (no work buffer needed): convolutions, and GEMMs whose output has the
     # weight rows' axis contiguous (the other layout runs transposed, with the packing kernel first)
     for (B, H, W, Cout) in [(3, 9, 7, 36), (1, 31, 33, 64), (2, 16, 16, 100), (1, 1, 5, 8)]:
