@@ -131,3 +131,36 @@ def test_sampled_output_two_plane_table(name):
     for variant in ("auto", "onehot_mfma"):
         flat = case.run(variant).cpu().numpy().reshape(-1)[pos]
         assert np.array_equal(flat, want), f"{name} {variant}: {np.count_nonzero(flat != want)} sampled outputs differ"
+
+
+NETWORK_LAYERS = [
+    # (B, H, Cin, Cout, filter, stride), AUTO's kernel on packed codes, the one-call step's kernel
+    ((32, 28, 320, 320, 3, 1), "onehot_smfmac_staged_32x128", "onehot_smfmac_staged_32x128"),       # taps of 2.5 runs
+    ((32, 56, 256, 256, 3, 1), "onehot_smfmac_staged_32x224", "onehot_smfmac_staged_32x224"),
+    ((32, 56, 256, 512, 1, 2), "onehot_smfmac_ws_32xK", "onehot_smfmac_ws_32xK"),                   # strided; the step packs the pixels read
+    ((32, 28, 512, 512, 1, 1), "onehot_smfmac_ws_32xK", "onehot_smfmac_ws_32xK"),                   # K = 512
+    ((8, 14, 1024, 256, 1, 1), "onehot_smfmac_staged_32x64_k4", "codes_onehot_smfmac_64x32_k4"),    # the tiled kernel packs
+    ((1, 56, 256, 64, 1, 1), "onehot_mfma_splitk_s4", "codes_onehot_mfma_splitk_s4"),               # 64-position chunks
+    ((8, 7, 512, 512, 3, 1), "onehot_mfma_splitk_s12", "onehot_mfma_splitk_s12"),
+]
+
+
+@pytest.mark.parametrize("shape,kernel,step_kernel", NETWORK_LAYERS)
+def test_sampled_output_network_layers(shape, kernel, step_kernel):
+    """Full-size layers of the networks bench.py --layers times, one per kernel and rule that the small parity cases
+    reach only through forced plans: AUTO's kernel on packed codes and the one-call step on unpacked codes, against
+    sampled oracle outputs (borders included)."""
+    from paper_2304_09049_amd import binding as dg
+    B, H, Cin, Cout, k, s = shape
+    w = wl._conv("layer", B, H, H, Cin, Cout, k, k, (s, s), (k // 2, k // 2))
+    inp = wl.make_inputs(w)
+    case = GpuCase(inp)
+    assert case.kernel_name("auto") == kernel
+    assert dg.dg_conv_codes_kernel_name(case.lut, case.desc, "auto") == step_kernel
+    rng = np.random.default_rng(B + H + Cin + Cout)
+    pos = _border_heavy_positions(w, rng, int(min(60000, 2e8 // w.K)))
+    want = oracle.conv2d_sampled(inp.Wc, inp.Ac, inp.levels_w, inp.levels_a, pos, stride=w.stride, pad=w.pad)
+    got = case.run("auto").cpu().numpy().reshape(-1)[pos]
+    assert np.array_equal(got, want), f"{shape} {kernel}: {np.count_nonzero(got != want)} sampled outputs differ"
+    got = _one_call(case, inp).reshape(-1)[pos]
+    assert np.array_equal(got, want), f"{shape} {step_kernel}: {np.count_nonzero(got != want)} sampled outputs differ (one call)"
